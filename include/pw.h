@@ -1,0 +1,279 @@
+/* pw.h - C boundary of the MI355X (gfx950) build of the Pathways hot path.
+ *
+ * What is behind it.  The paper's unit of work is the "compiled function": a
+ * computation whose input/output types and shapes are known before its inputs
+ * exist (Section 3; Appendix B).  Executors enqueue such functions "with buffer
+ * futures as inputs" and hand back futures for the outputs at once (Section
+ * 4.4); because shapes are static, all host-side work for a chain of functions
+ * can run before the first of them has produced anything ("parallel
+ * asynchronous dispatch", Section 4.5); buffers live in a device object store
+ * and are named by opaque handles (Section 4.6).  The dominant compiled
+ * function of the paper's workloads is one accelerator's share of a
+ * decoder-only Transformer LM train step (Section 5.3).
+ *
+ * Here a future is (device buffer, HIP event, status, refcount), the executor
+ * is one HIP stream (FIFO, as in Section 4.4), a chain may be replayed as a
+ * HIP graph, and the train step is a static list of hand-written gfx950
+ * kernels over a static buffer plan.
+ *
+ * Conventions for every call:
+ *  - returns a pw_status; never throws; outputs go through pointer arguments;
+ *  - "host" pointers are ordinary process memory, "device" pointers are HIP
+ *    device memory on the context's GPU; the caller owns what it passes in;
+ *  - calls on one pw_ctx must come from one thread at a time;
+ *  - on error nothing is enqueued unless the text says otherwise, and
+ *    pw_last_error() gives a message.
+ * There is no CPU fallback: without a usable GPU pw_ctx_create fails.
+ */
+#ifndef PW_H_
+#define PW_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PW_OK = 0,
+  PW_ERR_INVALID = 1,     /* bad handle, null pointer, bad enum value */
+  PW_ERR_SHAPE = 2,       /* tensor rank/dims do not match the compiled signature */
+  PW_ERR_DTYPE = 3,       /* element type does not match the compiled signature */
+  PW_ERR_OOM = 4,         /* device allocation failed */
+  PW_ERR_DEVICE = 5,      /* a HIP call failed; see pw_last_error */
+  PW_ERR_NOT_READY = 6,   /* pw_future_query: producer has not finished */
+  PW_ERR_POISONED = 7,    /* the future, or one it depends on, failed or timed out */
+  PW_ERR_UNSUPPORTED = 8
+} pw_status;
+
+typedef enum { PW_F32 = 0, PW_BF16 = 1, PW_I32 = 2 } pw_dtype;
+
+typedef struct pw_ctx pw_ctx;       /* device, executor stream, buffer/event pools, handle tables */
+typedef struct pw_model pw_model;   /* LM parameters, optimiser state, activation plan; owned by its ctx */
+typedef uint64_t pw_fn;             /* compiled function handle; 0 is never valid */
+typedef uint64_t pw_future;         /* buffer-future handle; 0 is never valid */
+
+typedef struct {
+  int32_t dtype;                    /* pw_dtype */
+  int32_t rank;                     /* 0..4 */
+  int64_t dims[4];
+} pw_tensor_spec;
+
+/* Kinds of compiled function. */
+typedef enum {
+  PW_FN_ADD_CONST = 1,   /* y = x + c, fp32; params: one float c.  The trivial computation of the
+                            dispatch micro-benchmark (Section 5.1) and "b" of Figure 2. */
+  PW_FN_MUL_CONST = 2,   /* y = x * c ("a" of Figure 2) */
+  PW_FN_DIV_CONST = 3,   /* y = x / c ("c" of Figure 2) */
+  PW_FN_BUSY = 4,        /* y = x + c after spinning params[1] microseconds on the device: a computation
+                            of tunable duration for the overhead-masking sweep (Section 5.1) */
+  PW_FN_LM_TRAIN_STEP = 16, /* in: tokens i32 [B, T+1]; out: loss f32 [1].  params: pw_model*. */
+  PW_FN_STAGE_FWD = 17,  /* in: X [N, d]; out: Y [N, d].  params: pw_stage_params */
+  PW_FN_STAGE_BWD = 18   /* in: dY [N, d]; out: dX [N, d]; adds into the stage's weight gradients */
+} pw_fn_kind;
+
+typedef struct {
+  int32_t kind;                     /* pw_fn_kind */
+  int32_t n_in, n_out;              /* at most 8 each */
+  pw_tensor_spec in[8], out[8];
+  const void* params;               /* host pointer, copied by pw_compile_fn */
+  size_t params_bytes;
+} pw_fn_desc;
+
+typedef struct {
+  pw_model* model;
+  int32_t microbatch;               /* which activation slot the call stashes into / reads from */
+} pw_stage_params;
+
+typedef enum {
+  PW_STREAM = 0,      /* enqueue every function of the chain at once on the executor stream */
+  PW_GRAPH = 1,       /* the same launches, captured once into a HIP graph and replayed */
+  PW_SEQUENTIAL = 2   /* wait for each function to complete before enqueuing the next: the
+                         sequential-dispatch baseline of Section 5.1, for comparison only */
+} pw_chain_mode;
+
+/* ---- context -------------------------------------------------------------------------------- */
+
+/* Create a context on `device`.  `hip_stream` (a hipStream_t created by the caller, e.g. PyTorch's
+ * current stream) becomes the executor stream when non-null; otherwise the context creates its own
+ * non-blocking stream.  Fails with PW_ERR_DEVICE when no gfx950 GPU is usable. */
+pw_status pw_ctx_create(int device, void* hip_stream, pw_ctx** out);
+/* Cancels unresolved pending futures, drains the stream, frees everything the context owns
+ * (models, functions, futures, pools). */
+pw_status pw_ctx_destroy(pw_ctx* ctx);
+/* Message of the last failing call on this context (valid until the next call); "" if none. */
+const char* pw_last_error(pw_ctx* ctx);
+/* The executor stream (a hipStream_t) so that callers can order their own work against it. */
+void* pw_ctx_stream(pw_ctx* ctx);
+/* Blocks until everything enqueued so far has run. */
+pw_status pw_ctx_synchronize(pw_ctx* ctx);
+/* Upper bound, in milliseconds, that a device-side wait on an unresolved future may spin before
+ * it gives up and poisons the future (default 20000). */
+pw_status pw_ctx_set_gate_timeout_ms(pw_ctx* ctx, int ms);
+
+/* ---- compiled functions (Section 3, Appendix B) ---------------------------------------------- */
+
+/* "Compile": validate the signature, copy params, choose kernels and launch shapes.  PW_ERR_SHAPE /
+ * PW_ERR_DTYPE when the signature is impossible for the kind. */
+pw_status pw_compile_fn(pw_ctx* ctx, const pw_fn_desc* desc, pw_fn* out);
+pw_status pw_fn_release(pw_ctx* ctx, pw_fn fn);
+
+/* Enqueue one function with futures as inputs (Section 4.4 (i)).  Returns as soon as the launches
+ * are enqueued - before the inputs are ready - with new futures for the outputs (refcount 1, owned
+ * by the caller).  Inputs are checked against the compiled signature first: on PW_ERR_SHAPE /
+ * PW_ERR_DTYPE / PW_ERR_INVALID nothing is enqueued.  Inputs stay valid and may feed any number of
+ * later calls (fan-out, Figure 2); outputs are always fresh buffers, never updated in place.
+ * A poisoned input yields poisoned outputs. */
+pw_status pw_run_fn(pw_ctx* ctx, pw_fn fn, const pw_future* in, int n_in, pw_future* out, int n_out);
+
+/* Enqueue a chain: fns[0] consumes `in`, fns[i] consumes the outputs of fns[i-1] (so their
+ * signatures must match), `out` receives the outputs of the last function (Section 4.5; the
+ * "Chained" mode of Section 5.1).  Intermediate buffers never surface as futures.  All signature
+ * checks for the whole chain happen before the first launch. */
+pw_status pw_chain(pw_ctx* ctx, const pw_fn* fns, int n_fns, const pw_future* in, int n_in,
+                   pw_future* out, int n_out, int mode /* pw_chain_mode */);
+
+/* One LM train step: pw_run_fn on a function of kind PW_FN_LM_TRAIN_STEP.  The model's parameters
+ * and optimiser state are updated in place on the device (they are the function's private state). */
+pw_status pw_train_step(pw_ctx* ctx, pw_fn step_fn, pw_future tokens, pw_future* loss_out);
+
+/* ---- futures (Sections 4.4, 4.6) -------------------------------------------------------------- */
+
+/* Blocks until the future is ready; then copies `bytes` (<= its size) to host_dst if non-null.
+ * PW_ERR_POISONED if it or a dependency failed. */
+pw_status pw_await(pw_ctx* ctx, pw_future f, void* host_dst, size_t bytes);
+/* New future whose library-owned device buffer is filled from host memory (asynchronous copy). */
+pw_status pw_future_from_host(pw_ctx* ctx, const void* host_src, const pw_tensor_spec* spec, pw_future* out);
+/* New future over caller-owned device memory (not freed by the library); ready with respect to
+ * work already enqueued on the executor stream. */
+pw_status pw_future_wrap_device(pw_ctx* ctx, void* dev_ptr, const pw_tensor_spec* spec, pw_future* out);
+/* New future that is NOT ready: consumers enqueued on it wait on the device until
+ * pw_future_resolve supplies the data.  This is how "enqueued before its inputs are ready" is made
+ * real on one GPU. */
+pw_status pw_future_pending(pw_ctx* ctx, const pw_tensor_spec* spec, pw_future* out);
+/* Supplies the bytes of a pending future from host memory and releases its waiters.  With
+ * host_src == NULL the future is poisoned instead (its producer "failed"). */
+pw_status pw_future_resolve(pw_ctx* ctx, pw_future f, const void* host_src);
+/* PW_OK (ready) | PW_ERR_NOT_READY | PW_ERR_POISONED; never blocks. */
+pw_status pw_future_query(pw_ctx* ctx, pw_future f);
+pw_status pw_future_spec(pw_ctx* ctx, pw_future f, pw_tensor_spec* out);
+/* Device address of the buffer (valid while the caller holds a reference). */
+pw_status pw_future_device_ptr(pw_ctx* ctx, pw_future f, void** out);
+pw_status pw_future_retain(pw_ctx* ctx, pw_future f);
+/* Drops one reference; at zero the buffer returns to the pool (stream-ordered, so work already
+ * enqueued on it stays correct). */
+pw_status pw_future_release(pw_ctx* ctx, pw_future f);
+/* Number of live futures / bytes currently handed out by the buffer pool (for leak tests). */
+pw_status pw_ctx_stats(pw_ctx* ctx, int64_t* live_futures, int64_t* pool_bytes_in_use);
+
+/* ---- the LM (Section 5.3) --------------------------------------------------------------------- */
+
+typedef struct {
+  int32_t n_layer, d_model, n_head, d_ff, vocab, seq, batch;
+  int32_t bf16;          /* 0: fp32 throughout; 1: bf16 GEMM/attention operands, fp32 accumulation,
+                            fp32 residual stream, statistics, master weights and optimiser state */
+  int32_t optimizer;     /* 1 SGD, 2 Adam */
+  float lr, beta1, beta2, eps;
+  int32_t has_embed;     /* 0 for a pipeline stage fed with activations */
+  int32_t has_head;      /* 0 for a pipeline stage returning activations */
+  int32_t n_microbatch;  /* activation slots kept for a GPipe-like fwd-all / bwd-all schedule */
+} pw_lm_config;
+
+/* Allocates parameters (zero), gradients, optimiser state and every activation buffer of the step
+ * up front (static buffer plan).  d_model % n_head == 0, head_dim in {64, 128}. */
+pw_status pw_model_create(pw_ctx* ctx, const pw_lm_config* cfg, pw_model** out);
+pw_status pw_model_destroy(pw_model* m);
+/* Parameter tensors in the model's own order; weights are [in, out] row-major fp32. */
+int64_t pw_model_param_count(pw_model* m);
+pw_status pw_model_param_info(pw_model* m, int64_t idx, char* name, int name_cap, int64_t* numel);
+typedef enum { PW_PARAMS = 0, PW_GRADS = 1, PW_ADAM_M = 2, PW_ADAM_V = 3 } pw_model_part;
+/* Copy one tensor in (fp32; src may be host or device memory).  For PW_PARAMS in bf16 mode the
+ * bf16 compute copy is refreshed too.  Synchronous with respect to the executor stream. */
+pw_status pw_model_import(pw_model* m, int part, int64_t idx, const float* src, int src_on_device);
+/* Copy one tensor out to host memory (fp32), after draining the executor stream. */
+pw_status pw_model_export(pw_model* m, int part, int64_t idx, float* host_dst);
+/* Zero the weight gradients (a pipeline stage does this before its first micro-batch). */
+pw_status pw_model_zero_grads(pw_model* m);
+/* Apply the optimiser to the current gradients (used by the pipeline stage after the last backward;
+ * pw_train_step does it as part of the step). */
+pw_status pw_model_apply_optimizer(pw_model* m);
+/* Read back an activation of the most recent step for inspection: "logits" [N, V] as fp32. */
+pw_status pw_model_export_activation(pw_model* m, const char* name, int microbatch, float* host_dst, int64_t numel);
+/* Model FLOPs of one step (2 m n k per GEMM, forward + backward; causal attention at half the dense
+ * T^2), the figure the throughput is priced against. */
+double pw_model_step_flops(const pw_lm_config* cfg);
+
+/* ---- single kernels, for parity tests and profiling --------------------------------------------
+ * All pointers are device pointers; work is enqueued on the executor stream and not waited for.
+ * `dtype` is the element type of activations: PW_F32 or PW_BF16. */
+
+typedef enum {
+  PW_EPI_STORE = 0,          /* C = acc */
+  PW_EPI_BIAS = 1,           /* C = acc + bias[n] */
+  PW_EPI_BIAS_RESIDUAL = 2,  /* C(f32) = aux(f32)[m,n] + acc + bias[n] */
+  PW_EPI_BIAS_GELU = 3,      /* C = u = acc + bias[n];  C2 = gelu(u) */
+  PW_EPI_GELU_BWD = 4        /* C = acc * gelu'(aux[m,n]),  aux in the activation dtype */
+} pw_epilogue;
+
+typedef struct {
+  int32_t dtype;             /* operand element type (A and B) */
+  int32_t a_kmajor;          /* 0: A stored [M][K] (lda >= K); 1: A stored [K][M] (lda >= M) */
+  int32_t b_kmajor;          /* 0: B stored [N][K] (ldb >= K); 1: B stored [K][N] (ldb >= N) */
+  int64_t M, N, K, lda, ldb, ldc;
+  int32_t epilogue;          /* pw_epilogue */
+  int32_t out_dtype;         /* PW_F32 or PW_BF16 (bf16 only with bf16 operands) */
+  int32_t accumulate;        /* 1: C += result (fp32 output, PW_EPI_STORE only) */
+  const void* A;
+  const void* B;
+  const float* bias;         /* [N] or null */
+  const void* aux;           /* [M, ldc] or null */
+  void* C;
+  void* C2;                  /* second output of PW_EPI_BIAS_GELU, else null */
+} pw_gemm_args;
+
+/* C[M,N] = op(A)[M,K] . op(B)[K,N] with fp32 accumulation and a fused epilogue.  bf16 operands run on
+ * MFMA; they need K, lda, ldb multiples of 8 and 16-byte aligned pointers. */
+pw_status pw_op_gemm(pw_ctx* ctx, const pw_gemm_args* args);
+/* x[b*T+t,:] = wte[tok[b*(T+1)+t],:] + wpe[t,:]  (fp32 in, fp32 out; exact). */
+pw_status pw_op_embedding_fwd(pw_ctx* ctx, const int32_t* tokens, const float* wte, const float* wpe,
+                              float* x, int B, int T, int d, int V);
+/* dwte[id,:] = sum over positions holding id of dx (fixed ascending-position order: deterministic);
+ * rows of unused ids are zeroed;  dwpe[t,:] = sum_b dx[b*T+t,:]. */
+pw_status pw_op_embedding_bwd(pw_ctx* ctx, const int32_t* tokens, const float* dx, float* dwte, float* dwpe,
+                              int B, int T, int d, int V);
+/* y = (x - mean) rstd * g + b per row; x fp32 [N,d]; y in `dtype`; mean, rstd fp32 [N]. */
+pw_status pw_op_layernorm_fwd(pw_ctx* ctx, int dtype, const float* x, const float* g, const float* b,
+                              void* y, float* mean, float* rstd, int N, int d);
+/* dx(f32) = (dres ? dres : 0) + LayerNorm-backward(dy); dx_lp (optional) receives dx in `dtype`;
+ * dg, db fp32 [d] (overwritten, or added into when accumulate = 1).  ws: fp32 workspace of
+ * pw_layernorm_bwd_ws_floats(N, d) floats. */
+pw_status pw_op_layernorm_bwd(pw_ctx* ctx, int dtype, const void* dy, const float* x, const float* g,
+                              const float* mean, const float* rstd, const float* dres, float* dx, void* dx_lp,
+                              float* dg, float* db, float* ws, int N, int d, int accumulate);
+int64_t pw_layernorm_bwd_ws_floats(int N, int d);
+/* Causal multi-head attention over qkv [B*T, 3d] in `dtype` (columns [Q|K|V], head h at h*hd):
+ * o [B*T, d] in `dtype`, lse fp32 [B, H, T] (log-sum-exp of the scaled scores of each row). */
+pw_status pw_op_attention_fwd(pw_ctx* ctx, int dtype, const void* qkv, void* o, float* lse, int B, int T, int H, int hd);
+/* dqkv [B*T, 3d] from qkv, o, dout and lse.  delta: fp32 workspace [B, H, T]. */
+pw_status pw_op_attention_bwd(pw_ctx* ctx, int dtype, const void* qkv, const void* o, const void* dout,
+                              const float* lse, float* delta, void* dqkv, int B, int T, int H, int hd);
+/* Mean softmax cross-entropy over N rows of logits z [N, V] in `dtype` against tokens[b*(T+1)+t+1];
+ * z is overwritten by dz = (softmax(z) - onehot)/N; loss: one fp32; row_loss: fp32 workspace [N]. */
+pw_status pw_op_softmax_xent(pw_ctx* ctx, int dtype, void* z, const int32_t* tokens, float* loss, float* row_loss,
+                             int B, int T, int V);
+/* out[c] (=|+=) sum_r in[r, c]; `in` is [rows, cols] in `dtype`; ws: fp32 workspace of
+ * pw_colsum_ws_floats(rows, cols) floats. */
+pw_status pw_op_colsum(pw_ctx* ctx, int dtype, const void* in, float* out, float* ws, int64_t rows, int64_t cols,
+                       int accumulate);
+int64_t pw_colsum_ws_floats(int64_t rows, int64_t cols);
+/* w -= lr g */
+pw_status pw_op_sgd(pw_ctx* ctx, float* w, const float* g, int64_t n, float lr);
+/* Adam with bias correction at step t (>= 1); w_bf16 (optional) receives round-to-nearest-even(w). */
+pw_status pw_op_adam(pw_ctx* ctx, float* w, float* m, float* v, const float* g, void* w_bf16, int64_t n,
+                     float lr, float beta1, float beta2, float eps, int t);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PW_H_ */

@@ -1,0 +1,385 @@
+"""Thin ctypes binding of libpw.so (include/pw.h): argument marshalling only.
+
+Every step of the hot path runs in the library's HIP kernels.  PyTorch is used
+by callers for device memory and streams; this module only needs raw device
+pointers (``tensor.data_ptr()``).  If the library is missing the import of any
+symbol fails loudly: there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpw.so")
+
+PW_OK, PW_ERR_INVALID, PW_ERR_SHAPE, PW_ERR_DTYPE, PW_ERR_OOM, PW_ERR_DEVICE, PW_ERR_NOT_READY, \
+    PW_ERR_POISONED, PW_ERR_UNSUPPORTED = range(9)
+STATUS_NAMES = ["PW_OK", "PW_ERR_INVALID", "PW_ERR_SHAPE", "PW_ERR_DTYPE", "PW_ERR_OOM", "PW_ERR_DEVICE",
+                "PW_ERR_NOT_READY", "PW_ERR_POISONED", "PW_ERR_UNSUPPORTED"]
+PW_F32, PW_BF16, PW_I32 = 0, 1, 2
+PW_FN_ADD_CONST, PW_FN_MUL_CONST, PW_FN_DIV_CONST, PW_FN_BUSY = 1, 2, 3, 4
+PW_FN_LM_TRAIN_STEP, PW_FN_STAGE_FWD, PW_FN_STAGE_BWD = 16, 17, 18
+PW_STREAM, PW_GRAPH, PW_SEQUENTIAL = 0, 1, 2
+PW_PARAMS, PW_GRADS, PW_ADAM_M, PW_ADAM_V = 0, 1, 2, 3
+PW_EPI_STORE, PW_EPI_BIAS, PW_EPI_BIAS_RESIDUAL, PW_EPI_BIAS_GELU, PW_EPI_GELU_BWD = range(5)
+
+
+class TensorSpec(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("rank", C.c_int32), ("dims", C.c_int64 * 4)]
+
+
+class FnDesc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("n_in", C.c_int32), ("n_out", C.c_int32),
+                ("in_", TensorSpec * 8), ("out", TensorSpec * 8),
+                ("params", C.c_void_p), ("params_bytes", C.c_size_t)]
+
+
+class StageParams(C.Structure):
+    _fields_ = [("model", C.c_void_p), ("microbatch", C.c_int32)]
+
+
+class LMConfigC(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layer", "d_model", "n_head", "d_ff", "vocab", "seq", "batch", "bf16",
+                                         "optimizer")] + \
+               [(n, C.c_float) for n in ("lr", "beta1", "beta2", "eps")] + \
+               [(n, C.c_int32) for n in ("has_embed", "has_head", "n_microbatch")]
+
+
+class GemmArgs(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("a_kmajor", C.c_int32), ("b_kmajor", C.c_int32),
+                ("M", C.c_int64), ("N", C.c_int64), ("K", C.c_int64),
+                ("lda", C.c_int64), ("ldb", C.c_int64), ("ldc", C.c_int64),
+                ("epilogue", C.c_int32), ("out_dtype", C.c_int32), ("accumulate", C.c_int32),
+                ("A", C.c_void_p), ("B", C.c_void_p), ("bias", C.c_void_p), ("aux", C.c_void_p),
+                ("C", C.c_void_p), ("C2", C.c_void_p)]
+
+
+class PwError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else status}: {msg}")
+        self.status = status
+
+
+_lib = None
+
+# name -> (restype, argtypes); everything pw.h declares
+_SIGS = {
+    "pw_ctx_create": (C.c_int, [C.c_int, C.c_void_p, C.POINTER(C.c_void_p)]),
+    "pw_ctx_destroy": (C.c_int, [C.c_void_p]),
+    "pw_last_error": (C.c_char_p, [C.c_void_p]),
+    "pw_ctx_stream": (C.c_void_p, [C.c_void_p]),
+    "pw_ctx_synchronize": (C.c_int, [C.c_void_p]),
+    "pw_ctx_set_gate_timeout_ms": (C.c_int, [C.c_void_p, C.c_int]),
+    "pw_ctx_stats": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]),
+    "pw_compile_fn": (C.c_int, [C.c_void_p, C.POINTER(FnDesc), C.POINTER(C.c_uint64)]),
+    "pw_fn_release": (C.c_int, [C.c_void_p, C.c_uint64]),
+    "pw_run_fn": (C.c_int, [C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64), C.c_int, C.POINTER(C.c_uint64), C.c_int]),
+    "pw_chain": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64), C.c_int, C.POINTER(C.c_uint64), C.c_int,
+                           C.POINTER(C.c_uint64), C.c_int, C.c_int]),
+    "pw_train_step": (C.c_int, [C.c_void_p, C.c_uint64, C.c_uint64, C.POINTER(C.c_uint64)]),
+    "pw_await": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_size_t]),
+    "pw_future_from_host": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(TensorSpec), C.POINTER(C.c_uint64)]),
+    "pw_future_wrap_device": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(TensorSpec), C.POINTER(C.c_uint64)]),
+    "pw_future_pending": (C.c_int, [C.c_void_p, C.POINTER(TensorSpec), C.POINTER(C.c_uint64)]),
+    "pw_future_resolve": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p]),
+    "pw_future_query": (C.c_int, [C.c_void_p, C.c_uint64]),
+    "pw_future_spec": (C.c_int, [C.c_void_p, C.c_uint64, C.POINTER(TensorSpec)]),
+    "pw_future_device_ptr": (C.c_int, [C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p)]),
+    "pw_future_retain": (C.c_int, [C.c_void_p, C.c_uint64]),
+    "pw_future_release": (C.c_int, [C.c_void_p, C.c_uint64]),
+    "pw_model_create": (C.c_int, [C.c_void_p, C.POINTER(LMConfigC), C.POINTER(C.c_void_p)]),
+    "pw_model_destroy": (C.c_int, [C.c_void_p]),
+    "pw_model_param_count": (C.c_int64, [C.c_void_p]),
+    "pw_model_param_info": (C.c_int, [C.c_void_p, C.c_int64, C.c_char_p, C.c_int, C.POINTER(C.c_int64)]),
+    "pw_model_import": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_void_p, C.c_int]),
+    "pw_model_export": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_void_p]),
+    "pw_model_zero_grads": (C.c_int, [C.c_void_p]),
+    "pw_model_apply_optimizer": (C.c_int, [C.c_void_p]),
+    "pw_model_export_activation": (C.c_int, [C.c_void_p, C.c_char_p, C.c_int, C.c_void_p, C.c_int64]),
+    "pw_model_step_flops": (C.c_double, [C.POINTER(LMConfigC)]),
+    "pw_op_gemm": (C.c_int, [C.c_void_p, C.POINTER(GemmArgs)]),
+    "pw_op_embedding_fwd": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4 + [C.c_int] * 4),
+    "pw_op_embedding_bwd": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4 + [C.c_int] * 4),
+    "pw_op_layernorm_fwd": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 6 + [C.c_int] * 2),
+    "pw_op_layernorm_bwd": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 11 + [C.c_int] * 3),
+    "pw_layernorm_bwd_ws_floats": (C.c_int64, [C.c_int, C.c_int]),
+    "pw_op_attention_fwd": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 3 + [C.c_int] * 4),
+    "pw_op_attention_bwd": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 6 + [C.c_int] * 4),
+    "pw_op_softmax_xent": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 4 + [C.c_int] * 3),
+    "pw_op_colsum": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 3 + [C.c_int64] * 2 + [C.c_int]),
+    "pw_colsum_ws_floats": (C.c_int64, [C.c_int64, C.c_int64]),
+    "pw_op_sgd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float]),
+    "pw_op_adam": (C.c_int, [C.c_void_p] + [C.c_void_p] * 5 + [C.c_int64] + [C.c_float] * 4 + [C.c_int]),
+}
+DECLARED_SYMBOLS = sorted(_SIGS)
+
+
+def lib():
+    """Load libpw.so.  Raises if it has not been built: the product path has no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2203_12533_amd.build`")
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(l, name)          # AttributeError if the library lacks a declared symbol
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def make_spec(dtype: int, shape) -> TensorSpec:
+    s = TensorSpec()
+    s.dtype, s.rank = dtype, len(shape)
+    for i, v in enumerate(shape):
+        s.dims[i] = int(v)
+    return s
+
+
+_NP_DTYPES = {PW_F32: np.float32, PW_I32: np.int32, PW_BF16: np.uint16}
+
+
+class Context:
+    """pw_ctx: one GPU, one FIFO executor stream."""
+
+    def __init__(self, device: int = 0, stream_ptr: int | None = None):
+        self._h = C.c_void_p()
+        st = lib().pw_ctx_create(device, C.c_void_p(stream_ptr) if stream_ptr else None, C.byref(self._h))
+        if st != PW_OK:
+            self._h = None
+            raise PwError(st, "pw_ctx_create failed (is a gfx950 GPU visible?)")
+        self._models = []
+
+    # -- plumbing
+    def _check(self, st: int):
+        if st != PW_OK:
+            raise PwError(st, lib().pw_last_error(self._h).decode())
+
+    @property
+    def handle(self):
+        return self._h
+
+    def close(self):
+        if self._h is not None:
+            for m in list(self._models):
+                m.close()
+            lib().pw_ctx_destroy(self._h)
+            self._h = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    def synchronize(self):
+        self._check(lib().pw_ctx_synchronize(self._h))
+
+    def stream_ptr(self) -> int:
+        return lib().pw_ctx_stream(self._h)
+
+    def set_gate_timeout_ms(self, ms: int):
+        self._check(lib().pw_ctx_set_gate_timeout_ms(self._h, ms))
+
+    def stats(self):
+        a, b = C.c_int64(), C.c_int64()
+        self._check(lib().pw_ctx_stats(self._h, C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+    # -- compiled functions
+    def compile_fn(self, kind: int, in_specs, out_specs, params: bytes = b"") -> int:
+        d = FnDesc()
+        d.kind, d.n_in, d.n_out = kind, len(in_specs), len(out_specs)
+        for i, s in enumerate(in_specs):
+            d.in_[i] = s
+        for i, s in enumerate(out_specs):
+            d.out[i] = s
+        buf = C.create_string_buffer(params, len(params)) if params else None
+        d.params = C.cast(buf, C.c_void_p) if buf is not None else None
+        d.params_bytes = len(params)
+        h = C.c_uint64()
+        self._check(lib().pw_compile_fn(self._h, C.byref(d), C.byref(h)))
+        return h.value
+
+    def compile_scalar_fn(self, kind: int, n: int, c: float, busy_us: float | None = None) -> int:
+        spec = make_spec(PW_F32, (n,))
+        vals = [c] if busy_us is None else [c, busy_us]
+        return self.compile_fn(kind, [spec], [spec], np.asarray(vals, np.float32).tobytes())
+
+    def fn_release(self, fn: int):
+        self._check(lib().pw_fn_release(self._h, fn))
+
+    def run_fn(self, fn: int, inputs, n_out: int = 1):
+        a_in = (C.c_uint64 * max(1, len(inputs)))(*inputs)
+        a_out = (C.c_uint64 * max(1, n_out))()
+        self._check(lib().pw_run_fn(self._h, fn, a_in, len(inputs), a_out, n_out))
+        return list(a_out[:n_out])
+
+    def chain(self, fns, inputs, n_out: int = 1, mode: int = PW_STREAM):
+        a_f = (C.c_uint64 * len(fns))(*fns)
+        a_in = (C.c_uint64 * max(1, len(inputs)))(*inputs)
+        a_out = (C.c_uint64 * max(1, n_out))()
+        self._check(lib().pw_chain(self._h, a_f, len(fns), a_in, len(inputs), a_out, n_out, mode))
+        return list(a_out[:n_out])
+
+    def train_step(self, step_fn: int, tokens_future: int) -> int:
+        out = C.c_uint64()
+        self._check(lib().pw_train_step(self._h, step_fn, tokens_future, C.byref(out)))
+        return out.value
+
+    # -- futures
+    def future_from_host(self, arr: np.ndarray, dtype: int | None = None) -> int:
+        arr = np.ascontiguousarray(arr)
+        if dtype is None:
+            dtype = {np.dtype(np.float32): PW_F32, np.dtype(np.int32): PW_I32, np.dtype(np.uint16): PW_BF16}[arr.dtype]
+        spec = make_spec(dtype, arr.shape)
+        h = C.c_uint64()
+        self._check(lib().pw_future_from_host(self._h, arr.ctypes.data_as(C.c_void_p), C.byref(spec), C.byref(h)))
+        return h.value
+
+    def future_wrap_device(self, ptr: int, dtype: int, shape) -> int:
+        spec = make_spec(dtype, shape)
+        h = C.c_uint64()
+        self._check(lib().pw_future_wrap_device(self._h, C.c_void_p(ptr), C.byref(spec), C.byref(h)))
+        return h.value
+
+    def future_pending(self, dtype: int, shape) -> int:
+        spec = make_spec(dtype, shape)
+        h = C.c_uint64()
+        self._check(lib().pw_future_pending(self._h, C.byref(spec), C.byref(h)))
+        return h.value
+
+    def future_resolve(self, f: int, arr: np.ndarray | None):
+        if arr is None:
+            self._check(lib().pw_future_resolve(self._h, f, None))
+        else:
+            arr = np.ascontiguousarray(arr)
+            self._check(lib().pw_future_resolve(self._h, f, arr.ctypes.data_as(C.c_void_p)))
+
+    def future_query(self, f: int) -> int:
+        return lib().pw_future_query(self._h, f)
+
+    def future_spec(self, f: int):
+        s = TensorSpec()
+        self._check(lib().pw_future_spec(self._h, f, C.byref(s)))
+        return s.dtype, tuple(s.dims[i] for i in range(s.rank))
+
+    def future_device_ptr(self, f: int) -> int:
+        p = C.c_void_p()
+        self._check(lib().pw_future_device_ptr(self._h, f, C.byref(p)))
+        return p.value
+
+    def future_retain(self, f: int):
+        self._check(lib().pw_future_retain(self._h, f))
+
+    def future_release(self, f: int):
+        self._check(lib().pw_future_release(self._h, f))
+
+    def await_(self, f: int, fetch: bool = True):
+        """Block until ready; returns the value as a numpy array (bf16 as raw uint16) when fetch."""
+        if not fetch:
+            self._check(lib().pw_await(self._h, f, None, 0))
+            return None
+        dtype, shape = self.future_spec(f)
+        out = np.empty(shape, dtype=_NP_DTYPES[dtype])
+        self._check(lib().pw_await(self._h, f, out.ctypes.data_as(C.c_void_p), out.nbytes))
+        return out
+
+    # -- model
+    def model(self, cfg) -> "Model":
+        return Model(self, cfg)
+
+    # -- single kernels (device pointers as ints)
+    def op(self, name: str, *args):
+        self._check(getattr(lib(), "pw_op_" + name)(self._h, *args))
+
+    def gemm(self, **kw):
+        a = GemmArgs()
+        for k, v in kw.items():
+            setattr(a, k, v)
+        self._check(lib().pw_op_gemm(self._h, C.byref(a)))
+
+
+def lm_config_c(cfg) -> LMConfigC:
+    """From the generator module's LMConfig (or any object with the same fields)."""
+    return LMConfigC(cfg.n_layer, cfg.d_model, cfg.n_head, cfg.d_ff, cfg.vocab, cfg.seq, cfg.batch, int(cfg.bf16),
+                     {"sgd": 1, "adam": 2}[cfg.optimizer], cfg.lr, cfg.beta1, cfg.beta2, cfg.eps,
+                     int(cfg.has_embed), int(cfg.has_head), cfg.n_microbatch)
+
+
+def step_flops(cfg) -> float:
+    c = lm_config_c(cfg)
+    return lib().pw_model_step_flops(C.byref(c))
+
+
+class Model:
+    """pw_model: parameters, optimiser state and the static activation plan of one LM (or pipeline stage)."""
+
+    def __init__(self, ctx: Context, cfg):
+        self.ctx, self.cfg = ctx, cfg
+        self._h = C.c_void_p()
+        c = lm_config_c(cfg)
+        ctx._check(lib().pw_model_create(ctx.handle, C.byref(c), C.byref(self._h)))
+        ctx._models.append(self)
+        self.names, self.numel = [], {}
+        name = C.create_string_buffer(64)
+        n = C.c_int64()
+        for i in range(lib().pw_model_param_count(self._h)):
+            lib().pw_model_param_info(self._h, i, name, 64, C.byref(n))
+            self.names.append(name.value.decode())
+            self.numel[self.names[-1]] = n.value
+        self._index = {k: i for i, k in enumerate(self.names)}
+
+    def close(self):
+        if self._h is not None:
+            lib().pw_model_destroy(self._h)
+            self._h = None
+            if self in self.ctx._models:
+                self.ctx._models.remove(self)
+
+    def import_(self, part: int, name: str, arr: np.ndarray):
+        arr = np.ascontiguousarray(arr, dtype=np.float32)
+        assert arr.size == self.numel[name], (name, arr.size, self.numel[name])
+        self.ctx._check(lib().pw_model_import(self._h, part, self._index[name], arr.ctypes.data_as(C.c_void_p), 0))
+
+    def import_device(self, part: int, name: str, ptr: int):
+        self.ctx._check(lib().pw_model_import(self._h, part, self._index[name], C.c_void_p(ptr), 1))
+
+    def load_params(self, params: dict):
+        for k in self.names:
+            self.import_(PW_PARAMS, k, params[k])
+
+    def export(self, part: int, name: str, shape=None) -> np.ndarray:
+        out = np.empty(self.numel[name], dtype=np.float32)
+        self.ctx._check(lib().pw_model_export(self._h, part, self._index[name], out.ctypes.data_as(C.c_void_p)))
+        return out.reshape(shape) if shape is not None else out
+
+    def export_all(self, part: int, like: dict) -> dict:
+        return {k: self.export(part, k, like[k].shape) for k in self.names}
+
+    def export_activation(self, name: str, numel: int, microbatch: int = 0) -> np.ndarray:
+        out = np.empty(numel, dtype=np.float32)
+        self.ctx._check(lib().pw_model_export_activation(self._h, name.encode(), microbatch,
+                                                         out.ctypes.data_as(C.c_void_p), numel))
+        return out
+
+    def zero_grads(self):
+        self.ctx._check(lib().pw_model_zero_grads(self._h))
+
+    def apply_optimizer(self):
+        self.ctx._check(lib().pw_model_apply_optimizer(self._h))
+
+    def compile_train_step(self) -> int:
+        cfg = self.cfg
+        params = C.c_void_p(self._h.value)
+        return self.ctx.compile_fn(PW_FN_LM_TRAIN_STEP, [make_spec(PW_I32, (cfg.batch, cfg.seq + 1))],
+                                   [make_spec(PW_F32, (1,))], bytes(params))
+
+    def compile_stage(self, kind: int, microbatch: int) -> int:
+        cfg = self.cfg
+        sp = StageParams(self._h.value, microbatch)
+        spec = make_spec(PW_F32, (cfg.batch * cfg.seq, cfg.d_model))
+        return self.ctx.compile_fn(kind, [spec], [spec], bytes(sp))

@@ -1,0 +1,468 @@
+// GEMM engine: C[M,N] = op(A)[M,K] . op(B)[K,N], fp32 accumulation, fused epilogues.
+//
+// bf16 path (the one that carries ~96% of the train step's FLOPs): v_mfma_f32_32x32x16_bf16 tiles,
+// 64-wide wavefronts, block tile BM x BN x 64 staged through double-buffered LDS.  In LDS both operand
+// tiles are always [row][k] with k contiguous (row = m for A, n for B), padded to 72 elements per row so
+// that the 16-byte fragment reads of 32 consecutive rows fall in distinct bank groups.  Operands stored
+// k-major in memory (B of a forward GEMM, both operands of a weight-gradient GEMM) are transposed on the
+// way in: a thread fetches a 4(k) x 8(row) block with four 16-byte loads, regroups it with v_perm_b32
+// into eight 4(k)-element pieces and stores those with 8-byte LDS writes.  The main loop is therefore the
+// same for every layout.  The MFMA is issued with the B fragment as its first operand, so a lane ends up
+// with 4 consecutive n for one m: epilogue loads/stores are 8- or 16-byte vectors.
+//
+// Launch mapping: one workgroup per output tile, 1-D grid.  Hardware deals consecutive workgroup ids
+// round-robin to the 8 XCDs (each with its own L2), so ids are first regrouped so that every XCD owns a
+// contiguous range of tiles, and within the range tiles are walked in groups of 8 tile-rows so that
+// concurrently resident workgroups share A and B panels through that XCD's L2.
+//
+// fp32 path: a plain LDS-tiled ALU kernel; it serves the small fp32 configuration only.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace pw {
+
+struct EpiParams {
+  int mode, out_bf16, accumulate;
+  const float* bias;
+  const void* aux;
+  void* C;
+  void* C2;
+  int64_t ldc;
+};
+
+// Epilogue on 4 consecutive columns n0..n0+3 of row m.  AUXT: element type of aux for kEpiGeluBwd / of the
+// outputs when out_bf16 (the activation type).
+template <bool BF16ACT>
+__device__ __forceinline__ void epilogue4(const EpiParams& e, int64_t m, int64_t n0, float v0, float v1, float v2, float v3) {
+  const int64_t off = m * e.ldc + n0;
+  if (e.mode == kEpiBias || e.mode == kEpiBiasResidual || e.mode == kEpiBiasGelu) {
+    if (e.bias) {
+      const float4 b = *reinterpret_cast<const float4*>(e.bias + n0);
+      v0 += b.x; v1 += b.y; v2 += b.z; v3 += b.w;
+    }
+  }
+  if (e.mode == kEpiBiasResidual) {
+    const float4 r = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(e.aux) + off);
+    v0 += r.x; v1 += r.y; v2 += r.z; v3 += r.w;
+  } else if (e.mode == kEpiGeluBwd) {
+    float u0, u1, u2, u3;
+    if (BF16ACT) {
+      const bf16x4 u = *reinterpret_cast<const bf16x4*>(reinterpret_cast<const bf16*>(e.aux) + off);
+      u0 = (float)u[0]; u1 = (float)u[1]; u2 = (float)u[2]; u3 = (float)u[3];
+    } else {
+      const float4 u = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(e.aux) + off);
+      u0 = u.x; u1 = u.y; u2 = u.z; u3 = u.w;
+    }
+    v0 *= gelu_grad_f(u0); v1 *= gelu_grad_f(u1); v2 *= gelu_grad_f(u2); v3 *= gelu_grad_f(u3);
+  }
+  if (e.out_bf16) {
+    bf16x4 o = {(bf16)v0, (bf16)v1, (bf16)v2, (bf16)v3};
+    *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(e.C) + off) = o;
+    if (e.mode == kEpiBiasGelu) {
+      bf16x4 h = {(bf16)gelu_f(v0), (bf16)gelu_f(v1), (bf16)gelu_f(v2), (bf16)gelu_f(v3)};
+      *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(e.C2) + off) = h;
+    }
+  } else {
+    float* c = reinterpret_cast<float*>(e.C) + off;
+    if (e.accumulate) {
+      const float4 old = *reinterpret_cast<const float4*>(c);
+      v0 += old.x; v1 += old.y; v2 += old.z; v3 += old.w;
+    }
+    *reinterpret_cast<float4*>(c) = make_float4(v0, v1, v2, v3);
+    if (e.mode == kEpiBiasGelu)
+      *reinterpret_cast<float4*>(reinterpret_cast<float*>(e.C2) + off) = make_float4(gelu_f(v0), gelu_f(v1), gelu_f(v2), gelu_f(v3));
+  }
+}
+
+// Same, one element (ragged right edge).
+template <bool BF16ACT>
+__device__ __forceinline__ void epilogue1(const EpiParams& e, int64_t m, int64_t n, float v) {
+  const int64_t off = m * e.ldc + n;
+  if ((e.mode == kEpiBias || e.mode == kEpiBiasResidual || e.mode == kEpiBiasGelu) && e.bias) v += e.bias[n];
+  if (e.mode == kEpiBiasResidual) v += reinterpret_cast<const float*>(e.aux)[off];
+  if (e.mode == kEpiGeluBwd)
+    v *= gelu_grad_f(BF16ACT ? (float)reinterpret_cast<const bf16*>(e.aux)[off] : reinterpret_cast<const float*>(e.aux)[off]);
+  if (e.out_bf16) {
+    reinterpret_cast<bf16*>(e.C)[off] = (bf16)v;
+    if (e.mode == kEpiBiasGelu) reinterpret_cast<bf16*>(e.C2)[off] = (bf16)gelu_f(v);
+  } else {
+    float* c = reinterpret_cast<float*>(e.C) + off;
+    if (e.accumulate) v += *c;
+    *c = v;
+    if (e.mode == kEpiBiasGelu) reinterpret_cast<float*>(e.C2)[off] = gelu_f(v);
+  }
+}
+
+// Workgroup id -> output tile, XCD-aware (see file header).
+__device__ __forceinline__ void tile_of_block(int pid, int nblk, int tiles_m, int tiles_n, int& tm, int& tn) {
+  constexpr int kXcd = 8, kGroup = 8;
+  const int q = nblk / kXcd, r = nblk % kXcd;
+  const int xcd = pid % kXcd, j = pid / kXcd;
+  const int logical = xcd * q + (xcd < r ? xcd : r) + j;
+  const int per_group = kGroup * tiles_n;
+  const int group = logical / per_group;
+  const int first_m = group * kGroup;
+  const int gsize = tiles_m - first_m < kGroup ? tiles_m - first_m : kGroup;
+  const int in_group = logical - group * per_group;
+  tm = first_m + in_group % gsize;
+  tn = in_group / gsize;
+}
+
+// ======================================================================================================
+// bf16 MFMA kernel
+// ======================================================================================================
+constexpr int kBK = 64;          // k extent of one LDS stage
+constexpr int kLdk = kBK + 8;    // padded row length in LDS (elements)
+
+struct GemmBf16Params {
+  const bf16* A;
+  const bf16* B;
+  int64_t M, N, K, lda, ldb;
+  int tiles_m, tiles_n;
+  EpiParams epi;
+};
+
+// Global -> registers for one operand tile of ROWS rows x 64 k.  Each thread owns CNT pieces.
+//   row-major-k operand (KMAJOR = false): piece = 16 bytes = 8 consecutive k of one row.
+//   k-major operand     (KMAJOR = true):  piece = 4 k x 8 rows, held as four 16-byte loads.
+template <int ROWS, int NT, bool KMAJOR, bool EDGE>
+struct TileLoader {
+  static constexpr int kPieces = KMAJOR ? (kBK / 4) * (ROWS / 8) : ROWS * (kBK / 8);
+  static constexpr int CNT = kPieces / NT;
+  static_assert(kPieces % NT == 0, "tile does not divide over the workgroup");
+  uint4 reg[KMAJOR ? CNT * 4 : CNT];
+
+  // p: operand base; ld: leading dimension; row0: first row (m or n) of the tile; k0: first k;
+  // rows_total / k_total: operand extents (used only when EDGE).
+  __device__ __forceinline__ void load(const bf16* __restrict__ p, int64_t ld, int64_t row0, int64_t k0,
+                                       int64_t rows_total, int64_t k_total) {
+#pragma unroll
+    for (int i = 0; i < CNT; ++i) {
+      const int id = threadIdx.x + i * NT;
+      if (!KMAJOR) {
+        const int r = id >> 3, kc = id & 7;
+        const int64_t row = row0 + r, k = k0 + kc * 8;
+        if (!EDGE || (row < rows_total && k < k_total))
+          reg[i] = *reinterpret_cast<const uint4*>(p + row * ld + k);
+        else
+          reg[i] = make_uint4(0, 0, 0, 0);
+      } else {
+        const int rc = id % (ROWS / 8), kq = id / (ROWS / 8);
+        const int64_t row = row0 + rc * 8;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int64_t k = k0 + kq * 4 + j;
+          if (!EDGE || (row < rows_total && k < k_total))
+            reg[i * 4 + j] = *reinterpret_cast<const uint4*>(p + k * ld + row);
+          else
+            reg[i * 4 + j] = make_uint4(0, 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // registers -> LDS tile [ROWS][kLdk]
+  __device__ __forceinline__ void store(bf16* __restrict__ tile) const {
+#pragma unroll
+    for (int i = 0; i < CNT; ++i) {
+      const int id = threadIdx.x + i * NT;
+      if (!KMAJOR) {
+        const int r = id >> 3, kc = id & 7;
+        *reinterpret_cast<uint4*>(tile + r * kLdk + kc * 8) = reg[i];
+      } else {
+        const int rc = id % (ROWS / 8), kq = id / (ROWS / 8);
+        const uint32_t* w0 = reinterpret_cast<const uint32_t*>(&reg[i * 4 + 0]);
+        const uint32_t* w1 = reinterpret_cast<const uint32_t*>(&reg[i * 4 + 1]);
+        const uint32_t* w2 = reinterpret_cast<const uint32_t*>(&reg[i * 4 + 2]);
+        const uint32_t* w3 = reinterpret_cast<const uint32_t*>(&reg[i * 4 + 3]);
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+          // rows 2*e2 (low halves) and 2*e2+1 (high halves) of the 8-row group; 4 consecutive k each
+          uint2 lo, hi;
+          lo.x = __builtin_amdgcn_perm(w1[e2], w0[e2], 0x05040100u);
+          lo.y = __builtin_amdgcn_perm(w3[e2], w2[e2], 0x05040100u);
+          hi.x = __builtin_amdgcn_perm(w1[e2], w0[e2], 0x07060302u);
+          hi.y = __builtin_amdgcn_perm(w3[e2], w2[e2], 0x07060302u);
+          // rotate the order of the 8 stores by the lane's row-chunk so that lanes of one wave spread over banks
+          *reinterpret_cast<uint2*>(tile + (rc * 8 + 2 * e2) * kLdk + kq * 4) = lo;
+          *reinterpret_cast<uint2*>(tile + (rc * 8 + 2 * e2 + 1) * kLdk + kq * 4) = hi;
+        }
+      }
+    }
+  }
+};
+
+template <int BM, int BN, int WM, int WN, bool A_KMAJOR, bool B_KMAJOR, bool EDGE>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmBf16Params p) {
+  constexpr int NT = 64 * WM * WN;
+  constexpr int TM = BM / WM, TN = BN / WN;   // wave tile
+  constexpr int FM = TM / 32, FN = TN / 32;   // 32x32 MFMA tiles per wave
+  static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be a multiple of the MFMA tile");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16* As[2];
+  bf16* Bs[2];
+  As[0] = reinterpret_cast<bf16*>(smem_raw);
+  As[1] = As[0] + BM * kLdk;
+  Bs[0] = As[1] + BM * kLdk;
+  Bs[1] = Bs[0] + BN * kLdk;
+
+  int tm, tn;
+  tile_of_block(blockIdx.x, p.tiles_m * p.tiles_n, p.tiles_m, p.tiles_n, tm, tn);
+  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = wave / WN, wn = wave % WN;
+  const int lrow = lane & 31, lhalf = lane >> 5;
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  TileLoader<BM, NT, A_KMAJOR, EDGE> la;
+  TileLoader<BN, NT, B_KMAJOR, EDGE> lb;
+  const int64_t kt_total = (p.K + kBK - 1) / kBK;
+
+  la.load(p.A, p.lda, m0, 0, p.M, p.K);
+  lb.load(p.B, p.ldb, n0, 0, p.N, p.K);
+  la.store(As[0]);
+  lb.store(Bs[0]);
+  __syncthreads();
+
+  for (int64_t kt = 0; kt < kt_total; ++kt) {
+    const int cur = (int)(kt & 1);
+    if (kt + 1 < kt_total) {
+      la.load(p.A, p.lda, m0, (kt + 1) * kBK, p.M, p.K);
+      lb.load(p.B, p.ldb, n0, (kt + 1) * kBK, p.N, p.K);
+    }
+    const bf16* a_tile = As[cur] + (wm * TM + lrow) * kLdk + lhalf * 8;
+    const bf16* b_tile = Bs[cur] + (wn * TN + lrow) * kLdk + lhalf * 8;
+#pragma unroll
+    for (int kk = 0; kk < kBK / 16; ++kk) {
+      bf16x8 af[FM], bfr[FN];
+#pragma unroll
+      for (int i = 0; i < FM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(a_tile + i * 32 * kLdk + kk * 16);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(b_tile + j * 32 * kLdk + kk * 16);
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < kt_total) {
+      la.store(As[cur ^ 1]);
+      lb.store(Bs[cur ^ 1]);
+    }
+    __syncthreads();
+  }
+
+  // acc[i][j][r]: m = m0 + wm*TM + 32 i + lane%32,  n = n0 + wn*TN + 32 j + 8 (r/4) + 4 (lane/32) + r%4
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    const int64_t m = m0 + wm * TM + i * 32 + lrow;
+    if (EDGE && m >= p.M) continue;
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int64_t n = n0 + wn * TN + j * 32 + q * 8 + lhalf * 4;
+        if (!EDGE || n + 3 < p.N) {
+          epilogue4<true>(p.epi, m, n, acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (n + e < p.N) epilogue1<true>(p.epi, m, n + e, acc[i][j][q * 4 + e]);
+        }
+      }
+  }
+}
+
+// The kernels use more than the default 64 KiB of dynamic LDS: raise the limit once per variant (done for all
+// variants by gemm_init() so that it never happens inside a stream capture).
+template <int BM, int BN, int WM, int WN, bool AK, bool BK_, bool EDGE>
+static hipError_t prepare_bf16_variant() {
+  constexpr size_t smem = (size_t)2 * (BM + BN) * kLdk * sizeof(bf16);
+  static bool attr_done = false;   // per instantiation
+  if (attr_done) return hipSuccess;
+  auto kern = gemm_bf16_kernel<BM, BN, WM, WN, AK, BK_, EDGE>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (e == hipSuccess) attr_done = true;
+  return e;
+}
+
+template <int BM, int BN, int WM, int WN, bool AK, bool BK_, bool EDGE>
+static hipError_t launch_bf16_variant(hipStream_t s, const GemmBf16Params& p) {
+  constexpr int NT = 64 * WM * WN;
+  constexpr size_t smem = (size_t)2 * (BM + BN) * kLdk * sizeof(bf16);
+  hipError_t e = prepare_bf16_variant<BM, BN, WM, WN, AK, BK_, EDGE>();
+  if (e != hipSuccess) return e;
+  gemm_bf16_kernel<BM, BN, WM, WN, AK, BK_, EDGE><<<p.tiles_m * p.tiles_n, NT, smem, s>>>(p);
+  return hipGetLastError();
+}
+
+template <int BM, int BN, int WM, int WN>
+static hipError_t prepare_bf16_tile() {
+  hipError_t e = hipSuccess;
+#define PW_PREP(AK, BKM)                                                               \
+  if (e == hipSuccess) e = prepare_bf16_variant<BM, BN, WM, WN, AK, BKM, true>();      \
+  if (e == hipSuccess) e = prepare_bf16_variant<BM, BN, WM, WN, AK, BKM, false>()
+  PW_PREP(false, false);
+  PW_PREP(false, true);
+  PW_PREP(true, true);
+  PW_PREP(true, false);
+#undef PW_PREP
+  return e;
+}
+
+hipError_t gemm_init() {
+  hipError_t e = prepare_bf16_tile<256, 256, 2, 4>();
+  if (e == hipSuccess) e = prepare_bf16_tile<128, 128, 2, 2>();
+  return e;
+}
+
+template <int BM, int BN, int WM, int WN>
+static hipError_t launch_bf16_tile(hipStream_t s, const GemmBf16Params& p, bool ak, bool bk, bool edge) {
+#define PW_DISPATCH(AK, BKM)                                                                  \
+  return edge ? launch_bf16_variant<BM, BN, WM, WN, AK, BKM, true>(s, p)                      \
+              : launch_bf16_variant<BM, BN, WM, WN, AK, BKM, false>(s, p)
+  if (!ak && !bk) { PW_DISPATCH(false, false); }
+  if (!ak && bk) { PW_DISPATCH(false, true); }
+  if (ak && bk) { PW_DISPATCH(true, true); }
+  PW_DISPATCH(true, false);
+#undef PW_DISPATCH
+}
+
+// ======================================================================================================
+// fp32 ALU kernel: 64x64 tile, 256 threads, 4x4 outputs per thread, BK = 16.  Any M, N, K.
+// ======================================================================================================
+struct GemmF32Params {
+  const float* A;
+  const float* B;
+  int64_t M, N, K;
+  int64_t sam, sak, sbn, sbk;   // element strides: A(m,k) = A[m*sam + k*sak], B(k,n) = B[n*sbn + k*sbk]
+  EpiParams epi;
+};
+
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32Params p) {
+  __shared__ float As[16][64 + 4];
+  __shared__ float Bs[16][64 + 4];
+  const int64_t m0 = (int64_t)blockIdx.y * 64, n0 = (int64_t)blockIdx.x * 64;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  float acc[4][4] = {};
+  for (int64_t k0 = 0; k0 < p.K; k0 += 16) {
+    for (int idx = threadIdx.x; idx < 16 * 64; idx += 256) {
+      // consecutive threads walk the dimension that is contiguous in memory
+      int r, k;
+      if (p.sak == 1) { k = idx & 15; r = idx >> 4; } else { r = idx & 63; k = idx >> 6; }
+      const int64_t m = m0 + r, kk = k0 + k;
+      As[k][r] = (m < p.M && kk < p.K) ? p.A[m * p.sam + kk * p.sak] : 0.f;
+    }
+    for (int idx = threadIdx.x; idx < 16 * 64; idx += 256) {
+      int r, k;
+      if (p.sbk == 1) { k = idx & 15; r = idx >> 4; } else { r = idx & 63; k = idx >> 6; }
+      const int64_t n = n0 + r, kk = k0 + k;
+      Bs[k][r] = (n < p.N && kk < p.K) ? p.B[n * p.sbn + kk * p.sbk] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const float4 a = *reinterpret_cast<const float4*>(&As[k][ty * 4]);
+      const float4 b = *reinterpret_cast<const float4*>(&Bs[k][tx * 4]);
+      const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] += av[i] * bv[j];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int64_t m = m0 + ty * 4 + i;
+    if (m >= p.M) continue;
+    const int64_t n = n0 + tx * 4;
+    const bool vec_ok = n + 3 < p.N && (p.epi.ldc & 3) == 0;
+    if (vec_ok) {
+      epilogue4<false>(p.epi, m, n, acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (n + j < p.N) epilogue1<false>(p.epi, m, n + j, acc[i][j]);
+    }
+  }
+}
+
+// ======================================================================================================
+// host side
+// ======================================================================================================
+hipError_t launch_gemm(hipStream_t s, const GemmArgs& a) {
+  if (!a.A || !a.B || !a.C || a.M < 0 || a.N < 0 || a.K < 0) return hipErrorInvalidValue;
+  if (a.epilogue < kEpiStore || a.epilogue > kEpiGeluBwd) return hipErrorInvalidValue;
+  if (a.lda < (a.a_kmajor ? a.M : a.K) || a.ldb < (a.b_kmajor ? a.N : a.K) || a.ldc < a.N) return hipErrorInvalidValue;
+  if ((a.epilogue == kEpiBiasResidual || a.epilogue == kEpiGeluBwd) && !a.aux) return hipErrorInvalidValue;
+  if (a.epilogue == kEpiBiasGelu && !a.C2) return hipErrorInvalidValue;
+  if (a.accumulate && (a.out_dtype != kF32 || a.epilogue != kEpiStore)) return hipErrorInvalidValue;
+  if (a.epilogue == kEpiBiasResidual && a.out_dtype != kF32) return hipErrorInvalidValue;
+  if (a.out_dtype == kBF16 && a.dtype != kBF16) return hipErrorInvalidValue;
+  if (a.M == 0 || a.N == 0) return hipSuccess;
+  if (a.M > (1LL << 30) || a.N > (1LL << 30) || a.K > (1LL << 30)) return hipErrorInvalidValue;
+
+  EpiParams e;
+  e.mode = a.epilogue;
+  e.out_bf16 = a.out_dtype == kBF16;
+  e.accumulate = a.accumulate;
+  e.bias = a.bias;
+  e.aux = a.aux;
+  e.C = a.C;
+  e.C2 = a.C2;
+  e.ldc = a.ldc;
+
+  if (a.dtype == kF32) {
+    if (a.out_dtype != kF32) return hipErrorInvalidValue;
+    // vector epilogue accesses need 16-byte alignment; the kernel falls back to scalars when ldc % 4 != 0
+    if (((uintptr_t)a.C | (uintptr_t)a.C2 | (uintptr_t)a.aux | (uintptr_t)a.bias) & 15) return hipErrorInvalidValue;
+    GemmF32Params p;
+    p.A = (const float*)a.A;
+    p.B = (const float*)a.B;
+    p.M = a.M; p.N = a.N; p.K = a.K;
+    p.sam = a.a_kmajor ? 1 : a.lda; p.sak = a.a_kmajor ? a.lda : 1;
+    p.sbn = a.b_kmajor ? 1 : a.ldb; p.sbk = a.b_kmajor ? a.ldb : 1;
+    p.epi = e;
+    dim3 grid((unsigned)((a.N + 63) / 64), (unsigned)((a.M + 63) / 64));
+    if (grid.y > 65535) return hipErrorInvalidValue;
+    gemm_f32_kernel<<<grid, 256, 0, s>>>(p);
+    return hipGetLastError();
+  }
+  if (a.dtype != kBF16) return hipErrorInvalidValue;
+  // 16-byte vector loads: every row start and every k offset of a piece must be 16-byte aligned
+  if ((a.K % 8) || (a.lda % 8) || (a.ldb % 8)) return hipErrorInvalidValue;
+  if ((a.a_kmajor && a.M % 8) || (a.b_kmajor && a.N % 8)) return hipErrorInvalidValue;
+  if (((uintptr_t)a.A | (uintptr_t)a.B) & 15) return hipErrorInvalidValue;
+  if (((uintptr_t)a.C | (uintptr_t)a.C2 | (uintptr_t)a.aux | (uintptr_t)a.bias) & 15) return hipErrorInvalidValue;
+  if (a.ldc % 4) return hipErrorInvalidValue;
+
+  GemmBf16Params p;
+  p.A = (const bf16*)a.A;
+  p.B = (const bf16*)a.B;
+  p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb;
+  p.epi = e;
+  // Tile choice: 256x256 when that still yields at least one workgroup per CU; otherwise 128x128.
+  const int64_t big_tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
+  const bool use_big = big_tiles >= 200;
+  if (use_big) {
+    p.tiles_m = (int)((a.M + 255) / 256);
+    p.tiles_n = (int)((a.N + 255) / 256);
+    const bool edge = (a.M % 256) || (a.N % 256) || (a.K % kBK);
+    return launch_bf16_tile<256, 256, 2, 4>(s, p, a.a_kmajor, a.b_kmajor, edge);
+  }
+  p.tiles_m = (int)((a.M + 127) / 128);
+  p.tiles_n = (int)((a.N + 127) / 128);
+  if ((int64_t)p.tiles_m * p.tiles_n > (1 << 24)) return hipErrorInvalidValue;
+  const bool edge = (a.M % 128) || (a.N % 128) || (a.K % kBK);
+  return launch_bf16_tile<128, 128, 2, 2>(s, p, a.a_kmajor, a.b_kmajor, edge);
+}
+
+}  // namespace pw

@@ -1,0 +1,70 @@
+// Host-side launchers of the gfx950 kernels.  Every launcher validates what its kernel assumes
+// about shapes and alignment BEFORE launching, enqueues on `s`, and returns a hipError_t
+// (hipErrorInvalidValue for a rejected argument).  Nothing here allocates or synchronises.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pw {
+
+enum DType { kF32 = 0, kBF16 = 1, kI32 = 2 };
+enum Epilogue { kEpiStore = 0, kEpiBias = 1, kEpiBiasResidual = 2, kEpiBiasGelu = 3, kEpiGeluBwd = 4 };
+
+struct GemmArgs {
+  int dtype;
+  int a_kmajor, b_kmajor;
+  int64_t M, N, K, lda, ldb, ldc;
+  int epilogue, out_dtype, accumulate;
+  const void* A;
+  const void* B;
+  const float* bias;
+  const void* aux;
+  void* C;
+  void* C2;
+};
+
+// elementwise.hip
+hipError_t launch_scalar_fn(hipStream_t s, int kind, const float* x, float* y, int64_t n, float c, float busy_us);
+hipError_t launch_fill_f32(hipStream_t s, float* p, int64_t n, float v);
+hipError_t launch_f32_to_bf16(hipStream_t s, const float* src, void* dst, int64_t n);
+hipError_t launch_bf16_to_f32(hipStream_t s, const void* src, float* dst, int64_t n);
+hipError_t launch_copy_bytes(hipStream_t s, const void* src, void* dst, int64_t bytes);
+// Spins (bounded by timeout_ticks of the 100 MHz wall clock) until *flag != 0.  *flag == 1 means
+// "resolved"; any other value, or a timeout, writes 1 to *poison.  Both words live in pinned host memory.
+hipError_t launch_gate(hipStream_t s, const uint32_t* flag, uint32_t* poison, uint64_t timeout_ticks);
+hipError_t launch_sgd(hipStream_t s, float* w, const float* g, int64_t n, float lr);
+hipError_t launch_adam(hipStream_t s, float* w, float* m, float* v, const float* g, void* w_bf16, int64_t n,
+                       float lr, float b1, float b2, float eps, int t, const int* t_dev);
+hipError_t launch_increment(hipStream_t s, int* counter);
+
+// norm.hip
+hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, const float* x, const float* g, const float* b, void* y,
+                                float* mean, float* rstd, int N, int d);
+int64_t layernorm_bwd_ws_floats(int N, int d);
+hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const float* x, const float* g,
+                                const float* mean, const float* rstd, const float* dres, float* dx, void* dx_lp,
+                                float* dg, float* db, float* ws, int N, int d, int accumulate);
+int64_t colsum_ws_floats(int64_t rows, int64_t cols);
+hipError_t launch_colsum(hipStream_t s, int dtype, const void* in, float* out, float* ws, int64_t rows, int64_t cols,
+                         int accumulate);
+
+// embed_xent.hip
+hipError_t launch_embedding_fwd(hipStream_t s, const int32_t* tokens, const float* wte, const float* wpe, float* x,
+                                int B, int T, int d, int V);
+hipError_t launch_embedding_bwd(hipStream_t s, const int32_t* tokens, const float* dx, float* dwte, float* dwpe,
+                                int B, int T, int d, int V);
+hipError_t launch_softmax_xent(hipStream_t s, int dtype, void* z, const int32_t* tokens, float* loss, float* row_loss,
+                               int B, int T, int V);
+
+// attention.hip
+hipError_t launch_attention_fwd(hipStream_t s, int dtype, const void* qkv, void* o, float* lse, int B, int T, int H,
+                                int hd);
+hipError_t launch_attention_bwd(hipStream_t s, int dtype, const void* qkv, const void* o, const void* dout,
+                                const float* lse, float* delta, void* dqkv, int B, int T, int H, int hd);
+
+// gemm.hip
+hipError_t launch_gemm(hipStream_t s, const GemmArgs& a);
+// One-time per-process set-up of kernel attributes (large dynamic LDS); call once before any capture.
+hipError_t gemm_init();
+
+}  // namespace pw

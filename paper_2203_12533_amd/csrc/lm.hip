@@ -1,0 +1,387 @@
+// The LM train step: forward, backward and optimiser update as an ordered list of kernel launches on one
+// stream.  The workload is the decoder-only Transformer of the paper's large-scale evaluation (Section
+// 5.3: embedding lookup in front, Transformer layers of model dimension d and hidden dimension F, a
+// softmax layer at the end); it is a "compiled function" in the sense of Section 3: every shape is
+// known up front, so every buffer is allocated once, at model creation.
+//
+// bf16 mode keeps fp32 where rounding would accumulate: the residual stream x, LayerNorm statistics,
+// softmax statistics, the loss, every GEMM accumulator, weight gradients, master weights and optimiser
+// state.  GEMM and attention operands (LayerNorm outputs, qkv, attention output, FFN activations and
+// their gradients, logits) are bf16.
+#include "lm.hpp"
+
+#include <cmath>
+#include <cstdio>
+
+#include "kernels.hpp"
+
+namespace pw {
+
+namespace {
+
+constexpr int64_t kAlign = 64;   // elements; keeps every tensor 256-byte aligned in fp32 and 128 in bf16
+
+int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+void build_param_table(const pw_lm_config& c, std::vector<ParamInfo>& t, int64_t& total) {
+  int64_t off = 0;
+  auto add = [&](const std::string& n, int64_t numel) {
+    t.push_back({n, off, numel});
+    off += round_up(numel, kAlign);
+  };
+  const int64_t d = c.d_model, F = c.d_ff, V = c.vocab, T = c.seq;
+  if (c.has_embed) {
+    add("wte", V * d);
+    add("wpe", T * d);
+  }
+  for (int l = 0; l < c.n_layer; ++l) {
+    const std::string p = "l" + std::to_string(l) + ".";
+    add(p + "ln1_g", d); add(p + "ln1_b", d);
+    add(p + "wqkv", d * 3 * d); add(p + "bqkv", 3 * d);
+    add(p + "wo", d * d); add(p + "bo", d);
+    add(p + "ln2_g", d); add(p + "ln2_b", d);
+    add(p + "w1", d * F); add(p + "b1", F);
+    add(p + "w2", F * d); add(p + "b2", d);
+  }
+  if (c.has_head) {
+    add("lnf_g", d); add("lnf_b", d);
+    add("wh", d * V);
+  }
+  total = off;
+}
+
+struct Carver {
+  size_t off = 0;
+  unsigned char* base = nullptr;
+  template <class T> T* take(size_t bytes) {
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += (bytes + 255) / 256 * 256;
+    return p;
+  }
+};
+
+// Assigns every activation / scratch pointer; with base == nullptr only measures.
+size_t plan(Model* m, unsigned char* base) {
+  const pw_lm_config& c = m->cfg;
+  const size_t N = (size_t)m->N(), d = c.d_model, F = c.d_ff, V = c.vocab, L = c.n_layer;
+  const size_t es = c.bf16 ? 2 : 4;
+  const size_t BHT = (size_t)c.batch * c.n_head * c.seq;
+  Carver cv;
+  cv.base = base;
+  m->slots.resize(c.n_microbatch);
+  for (auto& s : m->slots) {
+    s.layer.resize(L);
+    for (size_t l = 0; l < L; ++l) {
+      auto& a = s.layer[l];
+      a.x_in = cv.take<float>(N * d * 4);
+      a.x_mid = cv.take<float>(N * d * 4);
+      a.lse = cv.take<float>(BHT * 4);
+      a.mean1 = cv.take<float>(N * 4);
+      a.rstd1 = cv.take<float>(N * 4);
+      a.mean2 = cv.take<float>(N * 4);
+      a.rstd2 = cv.take<float>(N * 4);
+      a.a = cv.take<void>(N * d * es);
+      a.qkv = cv.take<void>(N * 3 * d * es);
+      a.o = cv.take<void>(N * d * es);
+      a.mm = cv.take<void>(N * d * es);
+      a.u = cv.take<void>(N * F * es);
+      a.h = cv.take<void>(N * F * es);
+    }
+    s.x_out = cv.take<float>(N * d * 4);
+  }
+  if (c.has_head) {
+    m->y = cv.take<void>(N * d * es);
+    m->logits = cv.take<void>(N * V * es);
+    m->meanf = cv.take<float>(N * 4);
+    m->rstdf = cv.take<float>(N * 4);
+    m->row_loss = cv.take<float>(N * 4);
+  }
+  m->dx_a = cv.take<float>(N * d * 4);
+  m->dx_b = cv.take<float>(N * d * 4);
+  m->delta = cv.take<float>(BHT * 4);
+  m->dx_lp = cv.take<void>(N * d * es);
+  m->d_big = cv.take<void>(N * F * es);
+  m->d_qkv = cv.take<void>(N * 3 * d * es);
+  m->d_small = cv.take<void>(N * d * es);
+  int64_t wsf = layernorm_bwd_ws_floats((int)N, (int)d);
+  const int64_t widest = (int64_t)std::max(std::max(3 * d, F), d);
+  wsf = std::max(wsf, colsum_ws_floats((int64_t)N, widest));
+  m->ws = cv.take<float>((size_t)wsf * 4);
+  return cv.off;
+}
+
+#define PW_TRY(expr, what)                                                        \
+  do {                                                                            \
+    hipError_t e_ = (expr);                                                       \
+    if (e_ != hipSuccess) {                                                       \
+      m->error = std::string(what) + ": " + hipGetErrorString(e_);                \
+      return e_;                                                                  \
+    }                                                                             \
+  } while (0)
+
+const ParamInfo& P(const Model* m, size_t idx) { return m->params[idx]; }
+
+// GEMM helpers in the model's three layouts.  W matrices are [in, out] row-major.
+hipError_t gemm_fwd(Model* m, const void* x, int64_t wi, const float* bias, int64_t N, int64_t in, int64_t out,
+                    int epi, int out_dtype, const void* aux, void* C, void* C2) {
+  GemmArgs a{};
+  a.dtype = m->act_dtype();
+  a.a_kmajor = 0;                      // x [N, in]
+  a.b_kmajor = 1;                      // W [in, out]: stored [k][n]
+  a.M = N; a.N = out; a.K = in; a.lda = in; a.ldb = out; a.ldc = out;
+  a.epilogue = epi; a.out_dtype = out_dtype; a.accumulate = 0;
+  a.A = x;
+  a.B = m->cfg.bf16 ? (const void*)((const uint16_t*)m->wlp + P(m, wi).offset) : (const void*)(m->w + P(m, wi).offset);
+  a.bias = bias; a.aux = aux; a.C = C; a.C2 = C2;
+  return launch_gemm(m->stream, a);
+}
+// dx[N, in] = dy[N, out] . W^T
+hipError_t gemm_dgrad(Model* m, const void* dy, int64_t wi, int64_t N, int64_t in, int64_t out, int epi,
+                      const void* aux, void* C) {
+  GemmArgs a{};
+  a.dtype = m->act_dtype();
+  a.a_kmajor = 0;                      // dy [N, out]
+  a.b_kmajor = 0;                      // W [in, out]: stored [n = in][k = out]
+  a.M = N; a.N = in; a.K = out; a.lda = out; a.ldb = out; a.ldc = in;
+  a.epilogue = epi; a.out_dtype = m->act_dtype(); a.accumulate = 0;
+  a.A = dy;
+  a.B = m->cfg.bf16 ? (const void*)((const uint16_t*)m->wlp + P(m, wi).offset) : (const void*)(m->w + P(m, wi).offset);
+  a.aux = aux; a.C = C;
+  return launch_gemm(m->stream, a);
+}
+// dW[in, out] (=|+=) x^T[in, N] . dy[N, out]
+hipError_t gemm_wgrad(Model* m, const void* x, const void* dy, int64_t wi, int64_t N, int64_t in, int64_t out, int accumulate) {
+  GemmArgs a{};
+  a.dtype = m->act_dtype();
+  a.a_kmajor = 1;                      // x [N, in]: stored [k = N][m = in]
+  a.b_kmajor = 1;                      // dy [N, out]: stored [k = N][n = out]
+  a.M = in; a.N = out; a.K = N; a.lda = in; a.ldb = out; a.ldc = out;
+  a.epilogue = kEpiStore; a.out_dtype = kF32; a.accumulate = accumulate;
+  a.A = x; a.B = dy; a.C = m->g + P(m, wi).offset;
+  return launch_gemm(m->stream, a);
+}
+
+size_t layer_base(const Model* m, int l) { return (m->cfg.has_embed ? 2 : 0) + (size_t)l * 12; }
+
+hipError_t layers_forward(Model* m, Model::Slot& s) {
+  const pw_lm_config& c = m->cfg;
+  const int N = m->N(), d = c.d_model, F = c.d_ff;
+  const int dt = m->act_dtype();
+  for (int l = 0; l < c.n_layer; ++l) {
+    auto& A = s.layer[l];
+    const size_t e = layer_base(m, l);
+    float* x_next = l + 1 < c.n_layer ? s.layer[l + 1].x_in : s.x_out;
+    PW_TRY(launch_layernorm_fwd(m->stream, dt, A.x_in, m->w + P(m, e).offset, m->w + P(m, e + 1).offset, A.a, A.mean1, A.rstd1, N, d), "ln1 fwd");
+    PW_TRY(gemm_fwd(m, A.a, e + 2, m->w + P(m, e + 3).offset, N, d, 3 * d, kEpiBias, dt, nullptr, A.qkv, nullptr), "qkv gemm");
+    PW_TRY(launch_attention_fwd(m->stream, dt, A.qkv, A.o, A.lse, c.batch, c.seq, c.n_head, m->hd()), "attention fwd");
+    PW_TRY(gemm_fwd(m, A.o, e + 4, m->w + P(m, e + 5).offset, N, d, d, kEpiBiasResidual, kF32, A.x_in, A.x_mid, nullptr), "out-proj gemm");
+    PW_TRY(launch_layernorm_fwd(m->stream, dt, A.x_mid, m->w + P(m, e + 6).offset, m->w + P(m, e + 7).offset, A.mm, A.mean2, A.rstd2, N, d), "ln2 fwd");
+    PW_TRY(gemm_fwd(m, A.mm, e + 8, m->w + P(m, e + 9).offset, N, d, F, kEpiBiasGelu, dt, nullptr, A.u, A.h), "ffn1 gemm");
+    PW_TRY(gemm_fwd(m, A.h, e + 10, m->w + P(m, e + 11).offset, N, F, d, kEpiBiasResidual, kF32, A.x_mid, x_next, nullptr), "ffn2 gemm");
+  }
+  return hipSuccess;
+}
+
+// On entry m->dx_a holds the gradient w.r.t. the stack output (fp32) and, in bf16 mode, m->dx_lp its bf16
+// copy.  On exit m->dx_a holds the gradient w.r.t. the stack input.
+hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate) {
+  const pw_lm_config& c = m->cfg;
+  const int N = m->N(), d = c.d_model, F = c.d_ff;
+  const int dt = m->act_dtype();
+  float* g = m->g;
+  for (int l = c.n_layer - 1; l >= 0; --l) {
+    auto& A = s.layer[l];
+    const size_t e = layer_base(m, l);
+    const void* dx_op = c.bf16 ? m->dx_lp : (const void*)m->dx_a;
+    // FFN2: x_out = x_mid + h W2 + b2
+    PW_TRY(gemm_wgrad(m, A.h, dx_op, e + 10, N, F, d, accumulate), "ffn2 wgrad");
+    PW_TRY(launch_colsum(m->stream, kF32, m->dx_a, g + P(m, e + 11).offset, m->ws, N, d, accumulate), "b2 grad");
+    PW_TRY(gemm_dgrad(m, dx_op, e + 10, N, F, d, kEpiGeluBwd, A.u, m->d_big), "ffn2 dgrad + gelu'");
+    // FFN1: u = m W1 + b1
+    PW_TRY(gemm_wgrad(m, A.mm, m->d_big, e + 8, N, d, F, accumulate), "ffn1 wgrad");
+    PW_TRY(launch_colsum(m->stream, dt, m->d_big, g + P(m, e + 9).offset, m->ws, N, F, accumulate), "b1 grad");
+    PW_TRY(gemm_dgrad(m, m->d_big, e + 8, N, d, F, kEpiStore, nullptr, m->d_small), "ffn1 dgrad");
+    // LN2 and the residual branch: dx_b = dx_a + LN2'(d_small)
+    PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_mid, m->w + P(m, e + 6).offset, A.mean2, A.rstd2, m->dx_a,
+                                m->dx_b, c.bf16 ? m->dx_lp : nullptr, g + P(m, e + 6).offset, g + P(m, e + 7).offset,
+                                m->ws, N, d, accumulate), "ln2 bwd");
+    dx_op = c.bf16 ? m->dx_lp : (const void*)m->dx_b;
+    // out-proj: x_mid = x_in + o Wo + bo
+    PW_TRY(gemm_wgrad(m, A.o, dx_op, e + 4, N, d, d, accumulate), "out-proj wgrad");
+    PW_TRY(launch_colsum(m->stream, kF32, m->dx_b, g + P(m, e + 5).offset, m->ws, N, d, accumulate), "bo grad");
+    PW_TRY(gemm_dgrad(m, dx_op, e + 4, N, d, d, kEpiStore, nullptr, m->d_small), "out-proj dgrad");
+    PW_TRY(launch_attention_bwd(m->stream, dt, A.qkv, A.o, m->d_small, A.lse, m->delta, m->d_qkv, c.batch, c.seq,
+                                c.n_head, m->hd()), "attention bwd");
+    // QKV: qkv = a Wqkv + bqkv
+    PW_TRY(gemm_wgrad(m, A.a, m->d_qkv, e + 2, N, d, 3 * d, accumulate), "qkv wgrad");
+    PW_TRY(launch_colsum(m->stream, dt, m->d_qkv, g + P(m, e + 3).offset, m->ws, N, 3 * d, accumulate), "bqkv grad");
+    PW_TRY(gemm_dgrad(m, m->d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small), "qkv dgrad");
+    // LN1 and the residual branch: dx_a = dx_b + LN1'(d_small)
+    PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->w + P(m, e).offset, A.mean1, A.rstd1, m->dx_b,
+                                m->dx_a, c.bf16 ? m->dx_lp : nullptr, g + P(m, e).offset, g + P(m, e + 1).offset, m->ws,
+                                N, d, accumulate), "ln1 bwd");
+  }
+  return hipSuccess;
+}
+
+}  // namespace
+
+bool model_config_ok(const pw_lm_config& c, std::string* why) {
+  auto bad = [&](const char* s) {
+    if (why) *why = s;
+    return false;
+  };
+  if (c.n_layer < 1 || c.d_model < 1 || c.n_head < 1 || c.d_ff < 1 || c.seq < 1 || c.batch < 1) return bad("non-positive dimension");
+  if (c.d_model % c.n_head) return bad("d_model must be a multiple of n_head");
+  const int hd = c.d_model / c.n_head;
+  if (hd != 64 && hd != 128) return bad("head_dim must be 64 or 128");
+  if (c.d_model % 64 || c.d_ff % 64) return bad("d_model and d_ff must be multiples of 64");
+  if (c.d_model > 8192) return bad("d_model above 8192 is not supported by the row kernels");
+  if (c.has_head && (c.vocab < 8 || c.vocab % 8)) return bad("vocab must be a positive multiple of 8");
+  if (c.has_embed != c.has_head) return bad("has_embed and has_head must be set together (full LM) or both clear (stage)");
+  if (c.has_embed && c.vocab < 1) return bad("vocab missing");
+  if (c.n_microbatch < 1 || c.n_microbatch > 64) return bad("n_microbatch out of range");
+  if (c.has_head && c.n_microbatch != 1) return bad("a full LM step uses one micro-batch");
+  if (c.optimizer != 1 && c.optimizer != 2) return bad("optimizer must be 1 (SGD) or 2 (Adam)");
+  if ((int64_t)c.batch * c.n_head > 65535) return bad("batch * n_head too large");
+  if ((int64_t)c.batch * c.seq > (1 << 24)) return bad("too many tokens");
+  return true;
+}
+
+hipError_t model_create(const pw_lm_config& cfg, hipStream_t stream, Model** out, std::string* err) {
+  std::string why;
+  if (!model_config_ok(cfg, &why)) {
+    if (err) *err = why;
+    return hipErrorInvalidValue;
+  }
+  Model* m = new Model();
+  m->cfg = cfg;
+  m->stream = stream;
+  build_param_table(cfg, m->params, m->total);
+  auto fail = [&](hipError_t e, const char* what) {
+    if (err) *err = std::string(what) + ": " + hipGetErrorString(e);
+    model_destroy(m);
+    return e;
+  };
+  hipError_t e;
+  const size_t bytes = (size_t)m->total * 4;
+  if ((e = hipMalloc(&m->w, bytes)) != hipSuccess) return fail(e, "alloc params");
+  if ((e = hipMalloc(&m->g, bytes)) != hipSuccess) return fail(e, "alloc grads");
+  if (cfg.optimizer == 2) {
+    if ((e = hipMalloc(&m->m, bytes)) != hipSuccess) return fail(e, "alloc adam m");
+    if ((e = hipMalloc(&m->v, bytes)) != hipSuccess) return fail(e, "alloc adam v");
+  }
+  if (cfg.bf16 && (e = hipMalloc(&m->wlp, (size_t)m->total * 2)) != hipSuccess) return fail(e, "alloc bf16 weights");
+  if ((e = hipMalloc(&m->step_dev, 256)) != hipSuccess) return fail(e, "alloc step counter");
+  m->act_bytes = plan(m, nullptr);
+  if ((e = hipMalloc(&m->act, m->act_bytes)) != hipSuccess) return fail(e, "alloc activations");
+  plan(m, m->act);
+  // zero everything that is read before it is written
+  if ((e = launch_fill_f32(stream, m->w, m->total, 0.f)) != hipSuccess) return fail(e, "zero params");
+  if ((e = launch_fill_f32(stream, m->g, m->total, 0.f)) != hipSuccess) return fail(e, "zero grads");
+  if (m->m && (e = launch_fill_f32(stream, m->m, m->total, 0.f)) != hipSuccess) return fail(e, "zero m");
+  if (m->v && (e = launch_fill_f32(stream, m->v, m->total, 0.f)) != hipSuccess) return fail(e, "zero v");
+  if (m->wlp && (e = launch_f32_to_bf16(stream, m->w, m->wlp, m->total)) != hipSuccess) return fail(e, "zero bf16 weights");
+  const int one = 1;
+  if ((e = hipMemcpyAsync(m->step_dev, &one, sizeof(int), hipMemcpyHostToDevice, stream)) != hipSuccess) return fail(e, "init step");
+  if ((e = hipStreamSynchronize(stream)) != hipSuccess) return fail(e, "sync");
+  *out = m;
+  return hipSuccess;
+}
+
+void model_destroy(Model* m) {
+  if (!m) return;
+  (void)hipFree(m->w); (void)hipFree(m->g); (void)hipFree(m->m); (void)hipFree(m->v);
+  (void)hipFree(m->wlp); (void)hipFree(m->step_dev); (void)hipFree(m->act);
+  delete m;
+}
+
+hipError_t model_refresh_lowp(Model* m, int64_t offset, int64_t numel) {
+  if (!m->wlp) return hipSuccess;
+  return launch_f32_to_bf16(m->stream, m->w + offset, (uint16_t*)m->wlp + offset, numel);
+}
+
+hipError_t model_zero_grads(Model* m) {
+  PW_TRY(launch_fill_f32(m->stream, m->g, m->total, 0.f), "zero grads");
+  return hipSuccess;
+}
+
+hipError_t model_apply_optimizer(Model* m) {
+  const pw_lm_config& c = m->cfg;
+  if (c.optimizer == 1) {
+    PW_TRY(launch_sgd(m->stream, m->w, m->g, m->total, c.lr), "sgd");
+    if (m->wlp) PW_TRY(launch_f32_to_bf16(m->stream, m->w, m->wlp, m->total), "refresh bf16 weights");
+  } else {
+    PW_TRY(launch_adam(m->stream, m->w, m->m, m->v, m->g, m->wlp, m->total, c.lr, c.beta1, c.beta2, c.eps, 0, m->step_dev), "adam");
+    PW_TRY(launch_increment(m->stream, m->step_dev), "step counter");
+  }
+  return hipSuccess;
+}
+
+hipError_t model_train_step(Model* m, const int32_t* tokens, float* loss) {
+  const pw_lm_config& c = m->cfg;
+  if (!c.has_embed || !c.has_head) {
+    m->error = "train step needs a full LM (has_embed and has_head)";
+    return hipErrorInvalidValue;
+  }
+  const int N = m->N(), d = c.d_model, V = c.vocab;
+  const int dt = m->act_dtype();
+  Model::Slot& s = m->slots[0];
+  const size_t tail = layer_base(m, c.n_layer);
+  PW_TRY(launch_embedding_fwd(m->stream, tokens, m->w + P(m, 0).offset, m->w + P(m, 1).offset, s.layer[0].x_in, c.batch, c.seq, d, V), "embedding fwd");
+  hipError_t e = layers_forward(m, s);
+  if (e != hipSuccess) return e;
+  PW_TRY(launch_layernorm_fwd(m->stream, dt, s.x_out, m->w + P(m, tail).offset, m->w + P(m, tail + 1).offset, m->y, m->meanf, m->rstdf, N, d), "lnf fwd");
+  PW_TRY(gemm_fwd(m, m->y, tail + 2, nullptr, N, d, V, kEpiStore, dt, nullptr, m->logits, nullptr), "head gemm");
+  PW_TRY(launch_softmax_xent(m->stream, dt, m->logits, tokens, loss, m->row_loss, c.batch, c.seq, V), "softmax-xent");
+  // head backward: logits now hold dlogits
+  PW_TRY(gemm_wgrad(m, m->y, m->logits, tail + 2, N, d, V, 0), "head wgrad");
+  PW_TRY(gemm_dgrad(m, m->logits, tail + 2, N, d, V, kEpiStore, nullptr, m->d_small), "head dgrad");
+  PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, s.x_out, m->w + P(m, tail).offset, m->meanf, m->rstdf, nullptr, m->dx_a,
+                              c.bf16 ? m->dx_lp : nullptr, m->g + P(m, tail).offset, m->g + P(m, tail + 1).offset, m->ws, N, d, 0), "lnf bwd");
+  e = layers_backward(m, s, 0);
+  if (e != hipSuccess) return e;
+  PW_TRY(launch_embedding_bwd(m->stream, tokens, m->dx_a, m->g + P(m, 0).offset, m->g + P(m, 1).offset, c.batch, c.seq, d, V), "embedding bwd");
+  return model_apply_optimizer(m);
+}
+
+hipError_t model_stage_fwd(Model* m, int mb, const float* x, float* y) {
+  const pw_lm_config& c = m->cfg;
+  if (c.has_embed || c.has_head || mb < 0 || mb >= c.n_microbatch) {
+    m->error = "stage_fwd: not a pipeline-stage model or bad micro-batch index";
+    return hipErrorInvalidValue;
+  }
+  Model::Slot& s = m->slots[mb];
+  const int64_t bytes = (int64_t)m->N() * c.d_model * 4;
+  PW_TRY(launch_copy_bytes(m->stream, x, s.layer[0].x_in, bytes), "stage input copy");
+  hipError_t e = layers_forward(m, s);
+  if (e != hipSuccess) return e;
+  PW_TRY(launch_copy_bytes(m->stream, s.x_out, y, bytes), "stage output copy");
+  return hipSuccess;
+}
+
+hipError_t model_stage_bwd(Model* m, int mb, const float* dy, float* dx) {
+  const pw_lm_config& c = m->cfg;
+  if (c.has_embed || c.has_head || mb < 0 || mb >= c.n_microbatch) {
+    m->error = "stage_bwd: not a pipeline-stage model or bad micro-batch index";
+    return hipErrorInvalidValue;
+  }
+  Model::Slot& s = m->slots[mb];
+  const int64_t n = (int64_t)m->N() * c.d_model;
+  PW_TRY(launch_copy_bytes(m->stream, dy, m->dx_a, n * 4), "stage grad-output copy");
+  if (c.bf16) PW_TRY(launch_f32_to_bf16(m->stream, dy, m->dx_lp, n), "stage grad-output to bf16");
+  hipError_t e = layers_backward(m, s, 1);
+  if (e != hipSuccess) return e;
+  PW_TRY(launch_copy_bytes(m->stream, m->dx_a, dx, n * 4), "stage grad-input copy");
+  return hipSuccess;
+}
+
+double model_step_flops(const pw_lm_config& c) {
+  const double N = (double)c.batch * c.seq, d = c.d_model, F = c.d_ff, V = c.has_head ? c.vocab : 0, L = c.n_layer;
+  const double per_layer = d * 3 * d + d * d + 2 * d * F;          // multiply-adds per token, forward
+  const double gemm = 6.0 * N * (L * per_layer + d * V);           // x2 flops, x3 fwd + dgrad + wgrad
+  const double attn = 6.0 * c.batch * (double)c.seq * c.seq * d * L;   // causal half of QK^T, PV and their 4 backward products
+  return (gemm + attn) * c.n_microbatch;
+}
+
+}  // namespace pw

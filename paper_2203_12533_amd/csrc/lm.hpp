@@ -1,0 +1,70 @@
+// Decoder-only LM train step as a static list of kernel launches over a static buffer plan
+// (the body of the PW_FN_LM_TRAIN_STEP / PW_FN_STAGE_* compiled functions).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "../../include/pw.h"
+
+namespace pw {
+
+struct ParamInfo {
+  std::string name;
+  int64_t offset, numel;
+};
+
+struct Model {
+  pw_lm_config cfg;
+  hipStream_t stream;
+  std::string error;
+
+  // parameters and optimiser state: flat fp32 arenas with one shared offset table
+  std::vector<ParamInfo> params;
+  int64_t total = 0;
+  float* w = nullptr;
+  float* g = nullptr;
+  float* m = nullptr;
+  float* v = nullptr;
+  void* wlp = nullptr;        // bf16 compute copy of w (bf16 mode only)
+  int* step_dev = nullptr;    // Adam step number, on the device so that captured graphs stay valid
+
+  // activations: one allocation, carved by plan()
+  unsigned char* act = nullptr;
+  size_t act_bytes = 0;
+  struct LayerActs {
+    float *x_in, *x_mid, *lse, *mean1, *rstd1, *mean2, *rstd2;
+    void *a, *qkv, *o, *mm, *u, *h;
+  };
+  struct Slot {
+    std::vector<LayerActs> layer;
+    float* x_out;
+  };
+  std::vector<Slot> slots;    // one per micro-batch
+  // head
+  void* y = nullptr;
+  void* logits = nullptr;
+  float *meanf = nullptr, *rstdf = nullptr, *row_loss = nullptr;
+  // backward scratch
+  float *dx_a = nullptr, *dx_b = nullptr, *delta = nullptr, *ws = nullptr;
+  void *dx_lp = nullptr, *d_big = nullptr, *d_qkv = nullptr, *d_small = nullptr;
+
+  int N() const { return cfg.batch * cfg.seq; }
+  int hd() const { return cfg.d_model / cfg.n_head; }
+  int act_dtype() const { return cfg.bf16 ? 1 : 0; }
+};
+
+// Each returns a hipError_t; on failure `model->error` says which launch was rejected.
+hipError_t model_create(const pw_lm_config& cfg, hipStream_t stream, Model** out, std::string* err);
+void model_destroy(Model* m);
+hipError_t model_refresh_lowp(Model* m, int64_t offset, int64_t numel);
+hipError_t model_train_step(Model* m, const int32_t* tokens_dev, float* loss_dev);
+hipError_t model_stage_fwd(Model* m, int mb, const float* x_dev, float* y_dev);
+hipError_t model_stage_bwd(Model* m, int mb, const float* dy_dev, float* dx_dev);
+hipError_t model_zero_grads(Model* m);
+hipError_t model_apply_optimizer(Model* m);
+double model_step_flops(const pw_lm_config& cfg);
+bool model_config_ok(const pw_lm_config& cfg, std::string* why);
+
+}  // namespace pw

@@ -1,0 +1,1012 @@
+// Future/dispatch runtime and the C boundary (include/pw.h).
+//
+// Mapping of the paper's dispatch design onto one GPU:
+//   compiled function (Section 3, App. B)  -> FnRec: kind + static signature + params, checked at compile time
+//   buffer future (Section 4.4)            -> FutureRec: device buffer + HIP event + poison words + refcount
+//   FIFO executor (Section 4.4)            -> one HIP stream; enqueue order is execution order
+//   parallel asynchronous dispatch (4.5)   -> pw_chain validates and enqueues every function of the chain
+//                                             before any input exists; output buffers come from a pool, so no
+//                                             allocation or synchronisation sits between launches
+//   one message per subgraph (4.5)         -> PW_GRAPH: the chain's launches replayed as one HIP graph
+//   sequential dispatch baseline (5.1)     -> PW_SEQUENTIAL
+//   device object store (4.6)              -> handle tables + size-class buffer pool + refcounts
+// An input that "is not ready" is made real by a gate kernel on a second stream that spins (bounded) on a
+// word in pinned host memory; consumers wait on the event recorded behind it.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/pw.h"
+#include "kernels.hpp"
+#include "lm.hpp"
+
+using namespace pw;
+
+namespace {
+
+size_t dtype_size(int dt) { return dt == PW_BF16 ? 2 : 4; }
+
+bool spec_ok(const pw_tensor_spec& s) {
+  if (s.dtype < PW_F32 || s.dtype > PW_I32 || s.rank < 0 || s.rank > 4) return false;
+  for (int i = 0; i < s.rank; ++i)
+    if (s.dims[i] < 0 || s.dims[i] > (1LL << 40)) return false;
+  return true;
+}
+int64_t spec_numel(const pw_tensor_spec& s) {
+  int64_t n = 1;
+  for (int i = 0; i < s.rank; ++i) n *= s.dims[i];
+  return n;
+}
+size_t spec_bytes(const pw_tensor_spec& s) { return (size_t)spec_numel(s) * dtype_size(s.dtype); }
+// 0 same, PW_ERR_DTYPE or PW_ERR_SHAPE otherwise
+pw_status spec_match(const pw_tensor_spec& a, const pw_tensor_spec& b) {
+  if (a.dtype != b.dtype) return PW_ERR_DTYPE;
+  if (a.rank != b.rank) return PW_ERR_SHAPE;
+  for (int i = 0; i < a.rank; ++i)
+    if (a.dims[i] != b.dims[i]) return PW_ERR_SHAPE;
+  return PW_OK;
+}
+
+// A pair of words in pinned host memory: [0] the gate flag the host sets, [1] the poison mark.
+struct GateWords {
+  uint32_t* words;   // host-visible, device-visible
+};
+
+struct FutureRec {
+  bool live = false;
+  uint32_t gen = 0;
+  void* buf = nullptr;
+  size_t bytes = 0, pool_bytes = 0;
+  pw_tensor_spec spec{};
+  bool owns = false;             // buffer goes back to the pool on release
+  bool on_gate_stream = false;   // produced by the gate stream: consumers must wait on `event`
+  bool pending = false;          // created by pw_future_pending and not resolved yet
+  hipEvent_t event = nullptr;    // null: ready w.r.t. the executor stream's order
+  int refcount = 0;
+  bool host_poison = false;
+  std::vector<std::shared_ptr<GateWords>> poison;   // gates this future depends on
+  std::shared_ptr<GateWords> gate;                  // own gate (pending futures)
+  void* staging = nullptr;                          // pinned host staging (pending futures)
+};
+
+struct FnRec {
+  bool live = false;
+  uint32_t gen = 0;
+  pw_fn_desc desc{};
+  float cst = 0.f, busy_us = 0.f;
+  Model* model = nullptr;
+  int microbatch = 0;
+};
+
+struct GraphEntry {
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+};
+
+}  // namespace
+
+struct pw_ctx {
+  int device = 0;
+  hipStream_t exec = nullptr;      // executor stream
+  bool own_exec = false;
+  hipStream_t gate = nullptr;      // gate kernels and their copies
+  hipStream_t io = nullptr;        // device-to-host copies of pw_await
+  std::string error;
+  int gate_timeout_ms = 20000;
+
+  std::vector<FutureRec> futures;
+  std::vector<uint32_t> free_futures;
+  std::vector<FnRec> fns;
+  std::vector<Model*> models;
+  int64_t live_futures = 0;
+
+  // buffer pool: power-of-two size classes
+  std::map<size_t, std::vector<void*>> pool;
+  int64_t pool_in_use = 0;
+  std::vector<hipEvent_t> event_pool;
+
+  // pinned host words for gates
+  std::vector<uint32_t*> word_slabs;
+  std::vector<uint32_t*> free_words;
+  std::map<size_t, std::vector<void*>> staging_pool;
+
+  std::unordered_map<std::string, GraphEntry> graphs;
+};
+
+struct pw_model {
+  pw_ctx* ctx;
+  Model* impl;
+};
+
+namespace {
+
+pw_status fail(pw_ctx* c, pw_status st, const char* fmt, ...) {
+  if (c) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    c->error = buf;
+  }
+  return st;
+}
+#define PW_HIP(c, expr)                                                                          \
+  do {                                                                                           \
+    hipError_t e_ = (expr);                                                                      \
+    if (e_ != hipSuccess) return fail(c, e_ == hipErrorOutOfMemory ? PW_ERR_OOM : PW_ERR_DEVICE, \
+                                      "%s: %s", #expr, hipGetErrorString(e_));                   \
+  } while (0)
+
+size_t size_class(size_t bytes) {
+  size_t c = 256;
+  while (c < bytes) c <<= 1;
+  return c;
+}
+
+pw_status pool_alloc(pw_ctx* c, size_t bytes, void** out, size_t* cls_out) {
+  const size_t cls = size_class(bytes ? bytes : 1);
+  auto& fl = c->pool[cls];
+  if (!fl.empty()) {
+    *out = fl.back();
+    fl.pop_back();
+  } else {
+    hipError_t e = hipMalloc(out, cls);
+    if (e != hipSuccess) return fail(c, PW_ERR_OOM, "hipMalloc(%zu): %s", cls, hipGetErrorString(e));
+  }
+  *cls_out = cls;
+  c->pool_in_use += (int64_t)cls;
+  return PW_OK;
+}
+void pool_free(pw_ctx* c, void* p, size_t cls) {
+  c->pool[cls].push_back(p);
+  c->pool_in_use -= (int64_t)cls;
+}
+
+pw_status event_get(pw_ctx* c, hipEvent_t* ev) {
+  if (!c->event_pool.empty()) {
+    *ev = c->event_pool.back();
+    c->event_pool.pop_back();
+    return PW_OK;
+  }
+  PW_HIP(c, hipEventCreateWithFlags(ev, hipEventDisableTiming));
+  return PW_OK;
+}
+
+std::shared_ptr<GateWords> words_get(pw_ctx* c) {
+  if (c->free_words.empty()) {
+    uint32_t* slab = nullptr;
+    if (hipHostMalloc((void**)&slab, 4096, hipHostMallocDefault) != hipSuccess) return nullptr;
+    c->word_slabs.push_back(slab);
+    for (int i = 0; i < 4096 / 64; ++i) c->free_words.push_back(slab + i * 16);   // one 64-byte line per gate
+  }
+  uint32_t* w = c->free_words.back();
+  c->free_words.pop_back();
+  w[0] = 0;
+  w[1] = 0;
+  pw_ctx* ctx = c;
+  return std::shared_ptr<GateWords>(new GateWords{w}, [ctx](GateWords* g) {
+    ctx->free_words.push_back(g->words);
+    delete g;
+  });
+}
+
+pw_status future_new(pw_ctx* c, FutureRec** out, pw_future* handle) {
+  uint32_t idx;
+  if (!c->free_futures.empty()) {
+    idx = c->free_futures.back();
+    c->free_futures.pop_back();
+  } else {
+    idx = (uint32_t)c->futures.size();
+    c->futures.emplace_back();
+  }
+  FutureRec& f = c->futures[idx];
+  const uint32_t gen = f.gen + 1;
+  f = FutureRec();
+  f.gen = gen;
+  f.live = true;
+  f.refcount = 1;
+  c->live_futures++;
+  *out = &f;
+  *handle = ((uint64_t)gen << 32) | (uint64_t)(idx + 1);
+  return PW_OK;
+}
+
+FutureRec* future_get(pw_ctx* c, pw_future h) {
+  const uint32_t idx = (uint32_t)(h & 0xFFFFFFFFu), gen = (uint32_t)(h >> 32);
+  if (idx == 0 || idx > c->futures.size()) return nullptr;
+  FutureRec& f = c->futures[idx - 1];
+  return (f.live && f.gen == gen) ? &f : nullptr;
+}
+
+void future_drop(pw_ctx* c, pw_future h) {
+  FutureRec* f = future_get(c, h);
+  if (!f) return;
+  if (--f->refcount > 0) return;
+  if (f->gate) {
+    // The gate kernel reads the flag word and the copy behind it reads the staging buffer: neither may be
+    // recycled before they are done.  An unresolved gate is released first; the wait is then short.
+    if (f->pending) __atomic_store_n(&f->gate->words[0], 2u, __ATOMIC_RELEASE);
+    if (f->event) (void)hipEventSynchronize(f->event);
+  }
+  if (f->owns && f->buf) pool_free(c, f->buf, f->pool_bytes);
+  if (f->event) c->event_pool.push_back(f->event);
+  if (f->staging) c->staging_pool[size_class(f->bytes)].push_back(f->staging);
+  f->poison.clear();
+  f->gate.reset();
+  f->live = false;
+  c->live_futures--;
+  c->free_futures.push_back((uint32_t)(h & 0xFFFFFFFFu) - 1);
+}
+
+FnRec* fn_get(pw_ctx* c, pw_fn h) {
+  const uint32_t idx = (uint32_t)(h & 0xFFFFFFFFu), gen = (uint32_t)(h >> 32);
+  if (idx == 0 || idx > c->fns.size()) return nullptr;
+  FnRec& f = c->fns[idx - 1];
+  return (f.live && f.gen == gen) ? &f : nullptr;
+}
+
+bool is_scalar_kind(int k) { return k >= PW_FN_ADD_CONST && k <= PW_FN_BUSY; }
+
+// Launch the body of one function on the executor stream.  in/out are device pointers.
+pw_status fn_launch(pw_ctx* c, FnRec* fn, void* const* in, void* const* out) {
+  const int k = fn->desc.kind;
+  if (is_scalar_kind(k)) {
+    hipError_t e = launch_scalar_fn(c->exec, k, (const float*)in[0], (float*)out[0], spec_numel(fn->desc.in[0]), fn->cst, fn->busy_us);
+    if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "scalar fn launch: %s", hipGetErrorString(e));
+    return PW_OK;
+  }
+  hipError_t e = hipErrorInvalidValue;
+  if (k == PW_FN_LM_TRAIN_STEP) e = model_train_step(fn->model, (const int32_t*)in[0], (float*)out[0]);
+  if (k == PW_FN_STAGE_FWD) e = model_stage_fwd(fn->model, fn->microbatch, (const float*)in[0], (float*)out[0]);
+  if (k == PW_FN_STAGE_BWD) e = model_stage_bwd(fn->model, fn->microbatch, (const float*)in[0], (float*)out[0]);
+  if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "%s", fn->model ? fn->model->error.c_str() : "bad function kind");
+  return PW_OK;
+}
+
+// Checks n_in/n_out and every input spec against the compiled signature.
+pw_status check_inputs(pw_ctx* c, FnRec* fn, const pw_tensor_spec* specs, int n_in, int n_out) {
+  if (n_in != fn->desc.n_in || n_out != fn->desc.n_out)
+    return fail(c, PW_ERR_SHAPE, "function takes %d inputs / %d outputs, got %d / %d", fn->desc.n_in, fn->desc.n_out, n_in, n_out);
+  for (int i = 0; i < n_in; ++i) {
+    pw_status st = spec_match(specs[i], fn->desc.in[i]);
+    if (st != PW_OK) return fail(c, st, "input %d does not match the compiled signature", i);
+  }
+  return PW_OK;
+}
+
+// Make the executor stream wait for inputs produced elsewhere; collect poison dependencies.
+pw_status wait_inputs(pw_ctx* c, FutureRec* const* in, int n_in, std::vector<std::shared_ptr<GateWords>>& poison, bool& host_poison) {
+  for (int i = 0; i < n_in; ++i) {
+    if (in[i]->on_gate_stream && in[i]->event) PW_HIP(c, hipStreamWaitEvent(c->exec, in[i]->event, 0));
+    for (auto& p : in[i]->poison) poison.push_back(p);
+    host_poison = host_poison || in[i]->host_poison;
+  }
+  return PW_OK;
+}
+
+bool model_alive(pw_ctx* c, Model* m) {
+  for (Model* x : c->models)
+    if (x == m) return true;
+  return false;
+}
+
+}  // namespace
+
+// =====================================================================================================
+extern "C" {
+
+pw_status pw_ctx_create(int device, void* hip_stream, pw_ctx** out) {
+  if (!out) return PW_ERR_INVALID;
+  *out = nullptr;
+  int n = 0;
+  if (hipGetDeviceCount(&n) != hipSuccess || n <= 0 || device < 0 || device >= n) return PW_ERR_DEVICE;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) != hipSuccess) return PW_ERR_DEVICE;
+  if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return PW_ERR_UNSUPPORTED;   // kernels are built for gfx950 only
+  if (hipSetDevice(device) != hipSuccess) return PW_ERR_DEVICE;
+  pw_ctx* c = new pw_ctx();
+  c->device = device;
+  if (hip_stream) {
+    c->exec = (hipStream_t)hip_stream;
+  } else {
+    if (hipStreamCreateWithFlags(&c->exec, hipStreamNonBlocking) != hipSuccess) { delete c; return PW_ERR_DEVICE; }
+    c->own_exec = true;
+  }
+  if (hipStreamCreateWithFlags(&c->gate, hipStreamNonBlocking) != hipSuccess ||
+      hipStreamCreateWithFlags(&c->io, hipStreamNonBlocking) != hipSuccess) {
+    delete c;
+    return PW_ERR_DEVICE;
+  }
+  if (gemm_init() != hipSuccess) {
+    (void)hipStreamDestroy(c->gate);
+    (void)hipStreamDestroy(c->io);
+    if (c->own_exec) (void)hipStreamDestroy(c->exec);
+    delete c;
+    return PW_ERR_DEVICE;
+  }
+  *out = c;
+  return PW_OK;
+}
+
+pw_status pw_ctx_destroy(pw_ctx* c) {
+  if (!c) return PW_ERR_INVALID;
+  (void)hipSetDevice(c->device);
+  // release every gate that is still waiting so that the streams can drain
+  for (auto& f : c->futures)
+    if (f.live && f.pending && f.gate) __atomic_store_n(&f.gate->words[0], 2u, __ATOMIC_RELEASE);
+  (void)hipStreamSynchronize(c->gate);
+  (void)hipStreamSynchronize(c->exec);
+  (void)hipStreamSynchronize(c->io);
+  for (auto& kv : c->graphs) {
+    if (kv.second.exec) (void)hipGraphExecDestroy(kv.second.exec);
+    if (kv.second.graph) (void)hipGraphDestroy(kv.second.graph);
+  }
+  for (Model* m : c->models) model_destroy(m);
+  for (auto& f : c->futures) {
+    if (!f.live) continue;
+    if (f.owns && f.buf) (void)hipFree(f.buf);
+    if (f.event) (void)hipEventDestroy(f.event);
+    if (f.staging) (void)hipHostFree(f.staging);
+    f.poison.clear();
+    f.gate.reset();
+  }
+  for (auto& kv : c->pool)
+    for (void* p : kv.second) (void)hipFree(p);
+  for (auto& kv : c->staging_pool)
+    for (void* p : kv.second) (void)hipHostFree(p);
+  for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
+  c->futures.clear();
+  for (uint32_t* s : c->word_slabs) (void)hipHostFree(s);
+  (void)hipStreamDestroy(c->gate);
+  (void)hipStreamDestroy(c->io);
+  if (c->own_exec) (void)hipStreamDestroy(c->exec);
+  delete c;
+  return PW_OK;
+}
+
+const char* pw_last_error(pw_ctx* c) { return c ? c->error.c_str() : "null context"; }
+void* pw_ctx_stream(pw_ctx* c) { return c ? (void*)c->exec : nullptr; }
+
+pw_status pw_ctx_synchronize(pw_ctx* c) {
+  if (!c) return PW_ERR_INVALID;
+  PW_HIP(c, hipStreamSynchronize(c->exec));
+  return PW_OK;
+}
+
+pw_status pw_ctx_set_gate_timeout_ms(pw_ctx* c, int ms) {
+  if (!c || ms < 1 || ms > 600000) return PW_ERR_INVALID;
+  c->gate_timeout_ms = ms;
+  return PW_OK;
+}
+
+pw_status pw_ctx_stats(pw_ctx* c, int64_t* live_futures, int64_t* pool_bytes_in_use) {
+  if (!c) return PW_ERR_INVALID;
+  if (live_futures) *live_futures = c->live_futures;
+  if (pool_bytes_in_use) *pool_bytes_in_use = c->pool_in_use;
+  return PW_OK;
+}
+
+// ---- compiled functions -----------------------------------------------------------------------------
+
+pw_status pw_compile_fn(pw_ctx* c, const pw_fn_desc* d, pw_fn* out) {
+  if (!c || !d || !out) return PW_ERR_INVALID;
+  if (d->n_in < 0 || d->n_in > 8 || d->n_out < 0 || d->n_out > 8) return fail(c, PW_ERR_INVALID, "n_in / n_out out of range");
+  for (int i = 0; i < d->n_in; ++i)
+    if (!spec_ok(d->in[i])) return fail(c, PW_ERR_INVALID, "input spec %d is malformed", i);
+  for (int i = 0; i < d->n_out; ++i)
+    if (!spec_ok(d->out[i])) return fail(c, PW_ERR_INVALID, "output spec %d is malformed", i);
+  FnRec fn;
+  fn.desc = *d;
+  fn.desc.params = nullptr;
+  const int k = d->kind;
+  if (is_scalar_kind(k)) {
+    if (d->n_in != 1 || d->n_out != 1) return fail(c, PW_ERR_SHAPE, "elementwise functions take one input and give one output");
+    if (d->in[0].dtype != PW_F32 || d->out[0].dtype != PW_F32) return fail(c, PW_ERR_DTYPE, "elementwise functions are fp32");
+    pw_status st = spec_match(d->in[0], d->out[0]);
+    if (st != PW_OK) return fail(c, st, "output must have the input's shape");
+    const size_t need = k == PW_FN_BUSY ? 2 * sizeof(float) : sizeof(float);
+    if (!d->params || d->params_bytes != need) return fail(c, PW_ERR_INVALID, "params must hold %zu bytes", need);
+    fn.cst = ((const float*)d->params)[0];
+    if (k == PW_FN_BUSY) {
+      fn.busy_us = ((const float*)d->params)[1];
+      if (!(fn.busy_us >= 0.f && fn.busy_us <= 1e6f)) return fail(c, PW_ERR_INVALID, "busy time must be within [0, 1e6] microseconds");
+    }
+  } else if (k == PW_FN_LM_TRAIN_STEP || k == PW_FN_STAGE_FWD || k == PW_FN_STAGE_BWD) {
+    pw_model* pm = nullptr;
+    if (k == PW_FN_LM_TRAIN_STEP) {
+      if (!d->params || d->params_bytes != sizeof(pw_model*)) return fail(c, PW_ERR_INVALID, "params must hold a pw_model*");
+      std::memcpy(&pm, d->params, sizeof pm);
+    } else {
+      if (!d->params || d->params_bytes != sizeof(pw_stage_params)) return fail(c, PW_ERR_INVALID, "params must hold pw_stage_params");
+      pw_stage_params sp;
+      std::memcpy(&sp, d->params, sizeof sp);
+      pm = sp.model;
+      fn.microbatch = sp.microbatch;
+    }
+    if (!pm || pm->ctx != c || !model_alive(c, pm->impl)) return fail(c, PW_ERR_INVALID, "model does not belong to this context");
+    fn.model = pm->impl;
+    const pw_lm_config& cfg = fn.model->cfg;
+    if (d->n_in != 1 || d->n_out != 1) return fail(c, PW_ERR_SHAPE, "one input and one output expected");
+    pw_tensor_spec want_in{}, want_out{};
+    if (k == PW_FN_LM_TRAIN_STEP) {
+      if (!cfg.has_embed || !cfg.has_head) return fail(c, PW_ERR_UNSUPPORTED, "model is a pipeline stage, not a full LM");
+      want_in = {PW_I32, 2, {cfg.batch, cfg.seq + 1, 0, 0}};
+      want_out = {PW_F32, 1, {1, 0, 0, 0}};
+    } else {
+      if (cfg.has_embed || cfg.has_head) return fail(c, PW_ERR_UNSUPPORTED, "model is a full LM, not a pipeline stage");
+      if (fn.microbatch < 0 || fn.microbatch >= cfg.n_microbatch) return fail(c, PW_ERR_INVALID, "micro-batch index out of range");
+      want_in = {PW_F32, 2, {(int64_t)cfg.batch * cfg.seq, cfg.d_model, 0, 0}};
+      want_out = want_in;
+    }
+    pw_status st = spec_match(d->in[0], want_in);
+    if (st != PW_OK) return fail(c, st, "input signature does not fit the model");
+    st = spec_match(d->out[0], want_out);
+    if (st != PW_OK) return fail(c, st, "output signature does not fit the model");
+  } else {
+    return fail(c, PW_ERR_INVALID, "unknown function kind %d", k);
+  }
+  uint32_t idx = (uint32_t)c->fns.size();
+  for (uint32_t i = 0; i < c->fns.size(); ++i)
+    if (!c->fns[i].live) { idx = i; break; }
+  if (idx == c->fns.size()) c->fns.emplace_back();
+  const uint32_t gen = c->fns[idx].gen + 1;
+  c->fns[idx] = fn;
+  c->fns[idx].gen = gen;
+  c->fns[idx].live = true;
+  *out = ((uint64_t)gen << 32) | (uint64_t)(idx + 1);
+  return PW_OK;
+}
+
+pw_status pw_fn_release(pw_ctx* c, pw_fn h) {
+  if (!c) return PW_ERR_INVALID;
+  FnRec* f = fn_get(c, h);
+  if (!f) return fail(c, PW_ERR_INVALID, "bad function handle");
+  f->live = false;
+  return PW_OK;
+}
+
+pw_status pw_run_fn(pw_ctx* c, pw_fn h, const pw_future* in, int n_in, pw_future* out, int n_out) {
+  if (!c || (n_in > 0 && !in) || (n_out > 0 && !out) || n_in < 0 || n_in > 8 || n_out < 0 || n_out > 8) return PW_ERR_INVALID;
+  FnRec* fn = fn_get(c, h);
+  if (!fn) return fail(c, PW_ERR_INVALID, "bad function handle");
+  FutureRec* fin[8];
+  pw_tensor_spec specs[8];
+  for (int i = 0; i < n_in; ++i) {
+    fin[i] = future_get(c, in[i]);
+    if (!fin[i]) return fail(c, PW_ERR_INVALID, "input %d is not a live future", i);
+    specs[i] = fin[i]->spec;
+  }
+  pw_status st = check_inputs(c, fn, specs, n_in, n_out);
+  if (st != PW_OK) return st;
+  // everything is validated: from here on we enqueue
+  void* obuf[8];
+  size_t ocls[8];
+  for (int i = 0; i < n_out; ++i) {
+    st = pool_alloc(c, spec_bytes(fn->desc.out[i]), &obuf[i], &ocls[i]);
+    if (st != PW_OK) {
+      for (int j = 0; j < i; ++j) pool_free(c, obuf[j], ocls[j]);
+      return st;
+    }
+  }
+  std::vector<std::shared_ptr<GateWords>> poison;
+  bool host_poison = false;
+  st = wait_inputs(c, fin, n_in, poison, host_poison);
+  void* ibuf[8];
+  for (int i = 0; i < n_in; ++i) ibuf[i] = fin[i]->buf;
+  if (st == PW_OK) st = fn_launch(c, fn, ibuf, obuf);
+  hipEvent_t ev = nullptr;
+  if (st == PW_OK) st = event_get(c, &ev);
+  if (st == PW_OK && hipEventRecord(ev, c->exec) != hipSuccess) st = fail(c, PW_ERR_DEVICE, "hipEventRecord failed");
+  if (st != PW_OK) {
+    for (int i = 0; i < n_out; ++i) pool_free(c, obuf[i], ocls[i]);
+    if (ev) c->event_pool.push_back(ev);
+    return st;
+  }
+  for (int i = 0; i < n_out; ++i) {
+    FutureRec* f;
+    future_new(c, &f, &out[i]);
+    // the vector may have grown: input records are not touched below
+    f->buf = obuf[i];
+    f->bytes = spec_bytes(fn->desc.out[i]);
+    f->pool_bytes = ocls[i];
+    f->spec = fn->desc.out[i];
+    f->owns = true;
+    f->poison = poison;
+    f->host_poison = host_poison;
+    if (i == 0) {
+      f->event = ev;
+    } else {   // one event per future keeps release simple
+      hipEvent_t e2;
+      if (event_get(c, &e2) == PW_OK && hipEventRecord(e2, c->exec) == hipSuccess) f->event = e2;
+    }
+  }
+  return PW_OK;
+}
+
+pw_status pw_chain(pw_ctx* c, const pw_fn* fns, int n_fns, const pw_future* in, int n_in, pw_future* out, int n_out, int mode) {
+  if (!c || !fns || n_fns < 1 || n_fns > 4096 || (n_in > 0 && !in) || (n_out > 0 && !out) || n_in < 0 || n_in > 8 || n_out < 0 || n_out > 8)
+    return PW_ERR_INVALID;
+  if (mode != PW_STREAM && mode != PW_GRAPH && mode != PW_SEQUENTIAL) return fail(c, PW_ERR_INVALID, "bad chain mode");
+  // ---- validate the whole chain before touching the device
+  std::vector<FnRec*> recs(n_fns);
+  for (int i = 0; i < n_fns; ++i) {
+    recs[i] = fn_get(c, fns[i]);
+    if (!recs[i]) return fail(c, PW_ERR_INVALID, "function %d of the chain is not a live handle", i);
+  }
+  FutureRec* fin[8];
+  pw_tensor_spec specs[8];
+  for (int i = 0; i < n_in; ++i) {
+    fin[i] = future_get(c, in[i]);
+    if (!fin[i]) return fail(c, PW_ERR_INVALID, "input %d is not a live future", i);
+    specs[i] = fin[i]->spec;
+  }
+  int cur_n = n_in;
+  for (int i = 0; i < n_fns; ++i) {
+    const int want_out = i + 1 < n_fns ? recs[i]->desc.n_out : n_out;
+    pw_status st = check_inputs(c, recs[i], specs, cur_n, want_out);
+    if (st != PW_OK) {
+      c->error = "chain link " + std::to_string(i) + ": " + c->error;
+      return st;
+    }
+    cur_n = recs[i]->desc.n_out;
+    for (int j = 0; j < cur_n; ++j) specs[j] = recs[i]->desc.out[j];
+  }
+  // ---- allocate every buffer the chain needs (two alternating sets of intermediates, then the outputs)
+  struct Buf { void* p; size_t cls; };
+  std::vector<std::vector<Buf>> bufs(n_fns);
+  auto release_all = [&]() {
+    for (auto& v : bufs)
+      for (auto& b : v) pool_free(c, b.p, b.cls);
+  };
+  // Intermediates of link i can be recycled once link i+1 has been enqueued; allocating and freeing in
+  // that order makes the pool hand back the same few buffers, so the address pattern repeats call after
+  // call (which is what lets a cached graph be replayed unchanged).
+  std::vector<std::vector<Buf>> plan_bufs(n_fns);
+  {
+    std::vector<Buf> prev;
+    for (int i = 0; i < n_fns; ++i) {
+      for (int j = 0; j < recs[i]->desc.n_out; ++j) {
+        Buf b;
+        pw_status st = pool_alloc(c, spec_bytes(recs[i]->desc.out[j]), &b.p, &b.cls);
+        if (st != PW_OK) {
+          for (auto& x : prev) pool_free(c, x.p, x.cls);
+          for (auto& x : plan_bufs[i]) pool_free(c, x.p, x.cls);
+          return st;
+        }
+        plan_bufs[i].push_back(b);
+      }
+      for (auto& x : prev) pool_free(c, x.p, x.cls);   // stream order keeps reuse safe
+      prev = plan_bufs[i];
+    }
+    bufs[n_fns - 1] = prev;   // only the last link's buffers stay allocated
+  }
+  std::vector<std::shared_ptr<GateWords>> poison;
+  bool host_poison = false;
+  pw_status st = wait_inputs(c, fin, n_in, poison, host_poison);
+  if (st != PW_OK) { release_all(); return st; }
+
+  auto enqueue_all = [&](bool sync_each) -> pw_status {
+    void* ibuf[8];
+    void* obuf[8];
+    for (int j = 0; j < n_in; ++j) ibuf[j] = fin[j]->buf;
+    for (int i = 0; i < n_fns; ++i) {
+      for (size_t j = 0; j < plan_bufs[i].size(); ++j) obuf[j] = plan_bufs[i][j].p;
+      pw_status s2 = fn_launch(c, recs[i], ibuf, obuf);
+      if (s2 != PW_OK) return s2;
+      if (sync_each && hipStreamSynchronize(c->exec) != hipSuccess) return fail(c, PW_ERR_DEVICE, "stream synchronize failed");
+      for (size_t j = 0; j < plan_bufs[i].size(); ++j) ibuf[j] = obuf[j];
+    }
+    return PW_OK;
+  };
+
+  if (mode == PW_GRAPH) {
+    std::string key;
+    key.append((const char*)fns, sizeof(pw_fn) * n_fns);
+    for (int j = 0; j < n_in; ++j) key.append((const char*)&fin[j]->buf, sizeof(void*));
+    for (auto& v : plan_bufs)
+      for (auto& b : v) key.append((const char*)&b.p, sizeof(void*));
+    auto it = c->graphs.find(key);
+    if (it == c->graphs.end()) {
+      if (c->graphs.size() >= 256) {   // bounded cache: drop everything rather than grow without limit
+        for (auto& kv : c->graphs) {
+          (void)hipGraphExecDestroy(kv.second.exec);
+          (void)hipGraphDestroy(kv.second.graph);
+        }
+        c->graphs.clear();
+      }
+      GraphEntry ge;
+      hipError_t e = hipStreamBeginCapture(c->exec, hipStreamCaptureModeThreadLocal);
+      if (e != hipSuccess) { release_all(); return fail(c, PW_ERR_DEVICE, "begin capture: %s", hipGetErrorString(e)); }
+      st = enqueue_all(false);
+      e = hipStreamEndCapture(c->exec, &ge.graph);
+      if (st != PW_OK || e != hipSuccess || !ge.graph) {
+        if (ge.graph) (void)hipGraphDestroy(ge.graph);
+        release_all();
+        return st != PW_OK ? st : fail(c, PW_ERR_DEVICE, "end capture: %s", hipGetErrorString(e));
+      }
+      e = hipGraphInstantiate(&ge.exec, ge.graph, nullptr, nullptr, 0);
+      if (e != hipSuccess) {
+        (void)hipGraphDestroy(ge.graph);
+        release_all();
+        return fail(c, PW_ERR_DEVICE, "graph instantiate: %s", hipGetErrorString(e));
+      }
+      it = c->graphs.emplace(key, ge).first;
+    }
+    hipError_t e = hipGraphLaunch(it->second.exec, c->exec);
+    if (e != hipSuccess) { release_all(); return fail(c, PW_ERR_DEVICE, "graph launch: %s", hipGetErrorString(e)); }
+  } else {
+    st = enqueue_all(mode == PW_SEQUENTIAL);
+    if (st != PW_OK) { release_all(); return st; }
+  }
+  hipEvent_t ev = nullptr;
+  st = event_get(c, &ev);
+  if (st == PW_OK && hipEventRecord(ev, c->exec) != hipSuccess) st = fail(c, PW_ERR_DEVICE, "hipEventRecord failed");
+  if (st != PW_OK) { release_all(); return st; }
+  for (int i = 0; i < n_out; ++i) {
+    FutureRec* f;
+    future_new(c, &f, &out[i]);
+    f->buf = bufs[n_fns - 1][i].p;
+    f->pool_bytes = bufs[n_fns - 1][i].cls;
+    f->spec = recs[n_fns - 1]->desc.out[i];
+    f->bytes = spec_bytes(f->spec);
+    f->owns = true;
+    f->poison = poison;
+    f->host_poison = host_poison;
+    if (i == 0) {
+      f->event = ev;
+    } else {
+      hipEvent_t e2;
+      if (event_get(c, &e2) == PW_OK && hipEventRecord(e2, c->exec) == hipSuccess) f->event = e2;
+    }
+  }
+  return PW_OK;
+}
+
+pw_status pw_train_step(pw_ctx* c, pw_fn step_fn, pw_future tokens, pw_future* loss_out) {
+  if (!c || !loss_out) return PW_ERR_INVALID;
+  FnRec* fn = fn_get(c, step_fn);
+  if (!fn || fn->desc.kind != PW_FN_LM_TRAIN_STEP) return fail(c, PW_ERR_INVALID, "not a train-step function");
+  return pw_run_fn(c, step_fn, &tokens, 1, loss_out, 1);
+}
+
+// ---- futures -----------------------------------------------------------------------------------------
+
+pw_status pw_await(pw_ctx* c, pw_future h, void* host_dst, size_t bytes) {
+  if (!c) return PW_ERR_INVALID;
+  FutureRec* f = future_get(c, h);
+  if (!f) return fail(c, PW_ERR_INVALID, "bad future handle");
+  if (bytes > f->bytes) return fail(c, PW_ERR_SHAPE, "asked for %zu bytes of a %zu-byte future", bytes, f->bytes);
+  if (f->event) PW_HIP(c, hipEventSynchronize(f->event));
+  else PW_HIP(c, hipStreamSynchronize(c->exec));
+  if (f->host_poison) return fail(c, PW_ERR_POISONED, "future depends on a failed producer");
+  for (auto& p : f->poison)
+    if (__atomic_load_n(&p->words[1], __ATOMIC_ACQUIRE)) return fail(c, PW_ERR_POISONED, "a pending input was poisoned or timed out");
+  if (host_dst && bytes) {
+    PW_HIP(c, hipMemcpyAsync(host_dst, f->buf, bytes, hipMemcpyDeviceToHost, c->io));
+    PW_HIP(c, hipStreamSynchronize(c->io));
+  }
+  return PW_OK;
+}
+
+pw_status pw_future_from_host(pw_ctx* c, const void* src, const pw_tensor_spec* spec, pw_future* out) {
+  if (!c || !src || !spec || !out) return PW_ERR_INVALID;
+  if (!spec_ok(*spec)) return fail(c, PW_ERR_INVALID, "malformed spec");
+  void* buf;
+  size_t cls;
+  pw_status st = pool_alloc(c, spec_bytes(*spec), &buf, &cls);
+  if (st != PW_OK) return st;
+  if (spec_bytes(*spec)) {
+    hipError_t e = hipMemcpyAsync(buf, src, spec_bytes(*spec), hipMemcpyHostToDevice, c->exec);
+    if (e != hipSuccess) { pool_free(c, buf, cls); return fail(c, PW_ERR_DEVICE, "H2D copy: %s", hipGetErrorString(e)); }
+  }
+  FutureRec* f;
+  future_new(c, &f, out);
+  f->buf = buf; f->pool_bytes = cls; f->bytes = spec_bytes(*spec); f->spec = *spec; f->owns = true;
+  return PW_OK;
+}
+
+pw_status pw_future_wrap_device(pw_ctx* c, void* dev_ptr, const pw_tensor_spec* spec, pw_future* out) {
+  if (!c || !dev_ptr || !spec || !out) return PW_ERR_INVALID;
+  if (!spec_ok(*spec)) return fail(c, PW_ERR_INVALID, "malformed spec");
+  FutureRec* f;
+  future_new(c, &f, out);
+  f->buf = dev_ptr; f->bytes = spec_bytes(*spec); f->spec = *spec; f->owns = false;
+  return PW_OK;
+}
+
+pw_status pw_future_pending(pw_ctx* c, const pw_tensor_spec* spec, pw_future* out) {
+  if (!c || !spec || !out) return PW_ERR_INVALID;
+  if (!spec_ok(*spec)) return fail(c, PW_ERR_INVALID, "malformed spec");
+  const size_t bytes = spec_bytes(*spec);
+  if (bytes > (1ull << 30)) return fail(c, PW_ERR_UNSUPPORTED, "pending futures are limited to 1 GiB");
+  void* buf;
+  size_t cls;
+  pw_status st = pool_alloc(c, bytes, &buf, &cls);
+  if (st != PW_OK) return st;
+  std::shared_ptr<GateWords> gw = words_get(c);
+  void* staging = nullptr;
+  auto& sp = c->staging_pool[size_class(bytes)];
+  if (!sp.empty()) { staging = sp.back(); sp.pop_back(); }
+  else if (hipHostMalloc(&staging, size_class(bytes), hipHostMallocDefault) != hipSuccess) staging = nullptr;
+  hipEvent_t ev = nullptr, order = nullptr;
+  if (!gw || !staging || event_get(c, &ev) != PW_OK || event_get(c, &order) != PW_OK) {
+    pool_free(c, buf, cls);
+    if (staging) sp.push_back(staging);
+    if (ev) c->event_pool.push_back(ev);
+    return fail(c, PW_ERR_OOM, "could not set up a gate");
+  }
+  // The buffer may have been used by work already enqueued on the executor stream: the gate stream's
+  // copy into it must come after that work.
+  hipError_t e = hipEventRecord(order, c->exec);
+  if (e == hipSuccess) e = hipStreamWaitEvent(c->gate, order, 0);
+  c->event_pool.push_back(order);
+  if (e == hipSuccess) e = launch_gate(c->gate, gw->words, gw->words + 1, (uint64_t)c->gate_timeout_ms * 100000ull);
+  if (e == hipSuccess && bytes) e = launch_copy_bytes(c->gate, staging, buf, (int64_t)bytes);
+  if (e == hipSuccess) e = hipEventRecord(ev, c->gate);
+  if (e != hipSuccess) {
+    __atomic_store_n(&gw->words[0], 2u, __ATOMIC_RELEASE);
+    pool_free(c, buf, cls);
+    sp.push_back(staging);
+    c->event_pool.push_back(ev);
+    return fail(c, PW_ERR_DEVICE, "gate launch: %s", hipGetErrorString(e));
+  }
+  FutureRec* f;
+  future_new(c, &f, out);
+  f->buf = buf; f->pool_bytes = cls; f->bytes = bytes; f->spec = *spec; f->owns = true;
+  f->on_gate_stream = true; f->pending = true; f->event = ev; f->gate = gw; f->staging = staging;
+  f->poison.push_back(gw);
+  return PW_OK;
+}
+
+pw_status pw_future_resolve(pw_ctx* c, pw_future h, const void* host_src) {
+  if (!c) return PW_ERR_INVALID;
+  FutureRec* f = future_get(c, h);
+  if (!f) return fail(c, PW_ERR_INVALID, "bad future handle");
+  if (!f->pending) return fail(c, PW_ERR_INVALID, "future is not pending");
+  f->pending = false;
+  if (!host_src) {
+    f->host_poison = true;
+    __atomic_store_n(&f->gate->words[0], 2u, __ATOMIC_RELEASE);
+    return PW_OK;
+  }
+  std::memcpy(f->staging, host_src, f->bytes);
+  __atomic_store_n(&f->gate->words[0], 1u, __ATOMIC_RELEASE);
+  return PW_OK;
+}
+
+pw_status pw_future_query(pw_ctx* c, pw_future h) {
+  if (!c) return PW_ERR_INVALID;
+  FutureRec* f = future_get(c, h);
+  if (!f) return fail(c, PW_ERR_INVALID, "bad future handle");
+  if (f->host_poison) return PW_ERR_POISONED;
+  hipError_t e = f->event ? hipEventQuery(f->event) : hipStreamQuery(c->exec);
+  if (e == hipErrorNotReady) return PW_ERR_NOT_READY;
+  if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "query: %s", hipGetErrorString(e));
+  for (auto& p : f->poison)
+    if (__atomic_load_n(&p->words[1], __ATOMIC_ACQUIRE)) return PW_ERR_POISONED;
+  return PW_OK;
+}
+
+pw_status pw_future_spec(pw_ctx* c, pw_future h, pw_tensor_spec* out) {
+  if (!c || !out) return PW_ERR_INVALID;
+  FutureRec* f = future_get(c, h);
+  if (!f) return fail(c, PW_ERR_INVALID, "bad future handle");
+  *out = f->spec;
+  return PW_OK;
+}
+
+pw_status pw_future_device_ptr(pw_ctx* c, pw_future h, void** out) {
+  if (!c || !out) return PW_ERR_INVALID;
+  FutureRec* f = future_get(c, h);
+  if (!f) return fail(c, PW_ERR_INVALID, "bad future handle");
+  *out = f->buf;
+  return PW_OK;
+}
+
+pw_status pw_future_retain(pw_ctx* c, pw_future h) {
+  if (!c) return PW_ERR_INVALID;
+  FutureRec* f = future_get(c, h);
+  if (!f) return fail(c, PW_ERR_INVALID, "bad future handle");
+  f->refcount++;
+  return PW_OK;
+}
+
+pw_status pw_future_release(pw_ctx* c, pw_future h) {
+  if (!c) return PW_ERR_INVALID;
+  FutureRec* f = future_get(c, h);
+  if (!f) return fail(c, PW_ERR_INVALID, "bad future handle");
+  if (f->refcount == 1 && f->on_gate_stream && f->event) {
+    // its buffer is written by the gate stream: make sure that write is over before the buffer is reused
+    if (f->pending) __atomic_store_n(&f->gate->words[0], 2u, __ATOMIC_RELEASE);
+    (void)hipStreamWaitEvent(c->exec, f->event, 0);
+  }
+  future_drop(c, h);
+  return PW_OK;
+}
+
+// ---- model -------------------------------------------------------------------------------------------
+
+pw_status pw_model_create(pw_ctx* c, const pw_lm_config* cfg, pw_model** out) {
+  if (!c || !cfg || !out) return PW_ERR_INVALID;
+  std::string why;
+  if (!model_config_ok(*cfg, &why)) return fail(c, PW_ERR_UNSUPPORTED, "%s", why.c_str());
+  Model* m = nullptr;
+  hipError_t e = model_create(*cfg, c->exec, &m, &why);
+  if (e != hipSuccess) return fail(c, e == hipErrorOutOfMemory ? PW_ERR_OOM : PW_ERR_DEVICE, "%s", why.c_str());
+  c->models.push_back(m);
+  *out = new pw_model{c, m};
+  return PW_OK;
+}
+
+pw_status pw_model_destroy(pw_model* pm) {
+  if (!pm) return PW_ERR_INVALID;
+  pw_ctx* c = pm->ctx;
+  (void)hipStreamSynchronize(c->exec);
+  for (size_t i = 0; i < c->models.size(); ++i)
+    if (c->models[i] == pm->impl) {
+      c->models.erase(c->models.begin() + i);
+      model_destroy(pm->impl);
+      break;
+    }
+  for (auto& f : c->fns)
+    if (f.live && f.model == pm->impl) f.live = false;   // functions of a dead model die with it
+  delete pm;
+  return PW_OK;
+}
+
+int64_t pw_model_param_count(pw_model* pm) { return pm ? (int64_t)pm->impl->params.size() : -1; }
+
+pw_status pw_model_param_info(pw_model* pm, int64_t idx, char* name, int cap, int64_t* numel) {
+  if (!pm || idx < 0 || idx >= (int64_t)pm->impl->params.size()) return PW_ERR_INVALID;
+  const ParamInfo& p = pm->impl->params[idx];
+  if (name && cap > 0) snprintf(name, cap, "%s", p.name.c_str());
+  if (numel) *numel = p.numel;
+  return PW_OK;
+}
+
+static float* part_base(Model* m, int part) {
+  switch (part) {
+    case PW_PARAMS: return m->w;
+    case PW_GRADS: return m->g;
+    case PW_ADAM_M: return m->m;
+    case PW_ADAM_V: return m->v;
+  }
+  return nullptr;
+}
+
+pw_status pw_model_import(pw_model* pm, int part, int64_t idx, const float* src, int src_on_device) {
+  if (!pm || !src || idx < 0 || idx >= (int64_t)pm->impl->params.size()) return PW_ERR_INVALID;
+  pw_ctx* c = pm->ctx;
+  Model* m = pm->impl;
+  float* base = part_base(m, part);
+  if (!base) return fail(c, PW_ERR_INVALID, "this model has no such part");
+  const ParamInfo& p = m->params[idx];
+  PW_HIP(c, hipMemcpyAsync(base + p.offset, src, (size_t)p.numel * 4, src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, c->exec));
+  if (part == PW_PARAMS) {
+    hipError_t e = model_refresh_lowp(m, p.offset, p.numel);
+    if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "bf16 refresh: %s", hipGetErrorString(e));
+  }
+  PW_HIP(c, hipStreamSynchronize(c->exec));
+  return PW_OK;
+}
+
+pw_status pw_model_export(pw_model* pm, int part, int64_t idx, float* dst) {
+  if (!pm || !dst || idx < 0 || idx >= (int64_t)pm->impl->params.size()) return PW_ERR_INVALID;
+  pw_ctx* c = pm->ctx;
+  Model* m = pm->impl;
+  float* base = part_base(m, part);
+  if (!base) return fail(c, PW_ERR_INVALID, "this model has no such part");
+  const ParamInfo& p = m->params[idx];
+  PW_HIP(c, hipStreamSynchronize(c->exec));
+  PW_HIP(c, hipMemcpy(dst, base + p.offset, (size_t)p.numel * 4, hipMemcpyDeviceToHost));
+  return PW_OK;
+}
+
+pw_status pw_model_zero_grads(pw_model* pm) {
+  if (!pm) return PW_ERR_INVALID;
+  if (model_zero_grads(pm->impl) != hipSuccess) return fail(pm->ctx, PW_ERR_DEVICE, "%s", pm->impl->error.c_str());
+  return PW_OK;
+}
+
+pw_status pw_model_apply_optimizer(pw_model* pm) {
+  if (!pm) return PW_ERR_INVALID;
+  if (model_apply_optimizer(pm->impl) != hipSuccess) return fail(pm->ctx, PW_ERR_DEVICE, "%s", pm->impl->error.c_str());
+  return PW_OK;
+}
+
+pw_status pw_model_export_activation(pw_model* pm, const char* name, int mb, float* dst, int64_t numel) {
+  if (!pm || !name || !dst) return PW_ERR_INVALID;
+  pw_ctx* c = pm->ctx;
+  Model* m = pm->impl;
+  if (mb < 0 || mb >= m->cfg.n_microbatch) return fail(c, PW_ERR_INVALID, "micro-batch index out of range");
+  const int64_t N = m->N(), d = m->cfg.d_model;
+  const void* src = nullptr;
+  int64_t n = 0;
+  int dt = PW_F32;
+  const std::string s(name);
+  if (s == "x_out") { src = m->slots[mb].x_out; n = N * d; }
+  else if (s == "dlogits" && m->logits) { src = m->logits; n = N * m->cfg.vocab; dt = m->act_dtype(); }
+  else if (s == "dx_in") { src = m->dx_a; n = N * d; }
+  else return fail(c, PW_ERR_INVALID, "unknown activation name");
+  if (numel != n) return fail(c, PW_ERR_SHAPE, "activation has %lld elements", (long long)n);
+  PW_HIP(c, hipStreamSynchronize(c->exec));
+  if (dt == PW_F32) {
+    PW_HIP(c, hipMemcpy(dst, src, (size_t)n * 4, hipMemcpyDeviceToHost));
+  } else {
+    float* tmp = nullptr;
+    PW_HIP(c, hipMalloc(&tmp, (size_t)n * 4));
+    hipError_t e = launch_bf16_to_f32(c->exec, src, tmp, n);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->exec);
+    if (e == hipSuccess) e = hipMemcpy(dst, tmp, (size_t)n * 4, hipMemcpyDeviceToHost);
+    (void)hipFree(tmp);
+    if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "activation export: %s", hipGetErrorString(e));
+  }
+  return PW_OK;
+}
+
+double pw_model_step_flops(const pw_lm_config* cfg) { return cfg ? model_step_flops(*cfg) : 0.0; }
+
+// ---- single kernels ------------------------------------------------------------------------------------
+
+#define PW_OP(c, expr)                                                                               \
+  do {                                                                                               \
+    if (!(c)) return PW_ERR_INVALID;                                                                 \
+    hipError_t e_ = (expr);                                                                          \
+    if (e_ == hipErrorInvalidValue) return fail(c, PW_ERR_INVALID, "arguments rejected by the launcher"); \
+    if (e_ == hipErrorNotSupported) return fail(c, PW_ERR_UNSUPPORTED, "not supported");            \
+    if (e_ != hipSuccess) return fail(c, PW_ERR_DEVICE, "%s", hipGetErrorString(e_));               \
+    return PW_OK;                                                                                    \
+  } while (0)
+
+pw_status pw_op_gemm(pw_ctx* c, const pw_gemm_args* a) {
+  if (!c || !a) return PW_ERR_INVALID;
+  GemmArgs g{};
+  g.dtype = a->dtype; g.a_kmajor = a->a_kmajor; g.b_kmajor = a->b_kmajor;
+  g.M = a->M; g.N = a->N; g.K = a->K; g.lda = a->lda; g.ldb = a->ldb; g.ldc = a->ldc;
+  g.epilogue = a->epilogue; g.out_dtype = a->out_dtype; g.accumulate = a->accumulate;
+  g.A = a->A; g.B = a->B; g.bias = a->bias; g.aux = a->aux; g.C = a->C; g.C2 = a->C2;
+  PW_OP(c, launch_gemm(c->exec, g));
+}
+pw_status pw_op_embedding_fwd(pw_ctx* c, const int32_t* tokens, const float* wte, const float* wpe, float* x, int B, int T, int d, int V) {
+  PW_OP(c, launch_embedding_fwd(c->exec, tokens, wte, wpe, x, B, T, d, V));
+}
+pw_status pw_op_embedding_bwd(pw_ctx* c, const int32_t* tokens, const float* dx, float* dwte, float* dwpe, int B, int T, int d, int V) {
+  PW_OP(c, launch_embedding_bwd(c->exec, tokens, dx, dwte, dwpe, B, T, d, V));
+}
+pw_status pw_op_layernorm_fwd(pw_ctx* c, int dtype, const float* x, const float* g, const float* b, void* y, float* mean, float* rstd, int N, int d) {
+  PW_OP(c, launch_layernorm_fwd(c->exec, dtype, x, g, b, y, mean, rstd, N, d));
+}
+pw_status pw_op_layernorm_bwd(pw_ctx* c, int dtype, const void* dy, const float* x, const float* g, const float* mean, const float* rstd,
+                              const float* dres, float* dx, void* dx_lp, float* dg, float* db, float* ws, int N, int d, int accumulate) {
+  PW_OP(c, launch_layernorm_bwd(c->exec, dtype, dy, x, g, mean, rstd, dres, dx, dx_lp, dg, db, ws, N, d, accumulate));
+}
+int64_t pw_layernorm_bwd_ws_floats(int N, int d) { return layernorm_bwd_ws_floats(N, d); }
+pw_status pw_op_attention_fwd(pw_ctx* c, int dtype, const void* qkv, void* o, float* lse, int B, int T, int H, int hd) {
+  PW_OP(c, launch_attention_fwd(c->exec, dtype, qkv, o, lse, B, T, H, hd));
+}
+pw_status pw_op_attention_bwd(pw_ctx* c, int dtype, const void* qkv, const void* o, const void* dout, const float* lse, float* delta,
+                              void* dqkv, int B, int T, int H, int hd) {
+  PW_OP(c, launch_attention_bwd(c->exec, dtype, qkv, o, dout, lse, delta, dqkv, B, T, H, hd));
+}
+pw_status pw_op_softmax_xent(pw_ctx* c, int dtype, void* z, const int32_t* tokens, float* loss, float* row_loss, int B, int T, int V) {
+  PW_OP(c, launch_softmax_xent(c->exec, dtype, z, tokens, loss, row_loss, B, T, V));
+}
+pw_status pw_op_colsum(pw_ctx* c, int dtype, const void* in, float* out, float* ws, int64_t rows, int64_t cols, int accumulate) {
+  PW_OP(c, launch_colsum(c->exec, dtype, in, out, ws, rows, cols, accumulate));
+}
+int64_t pw_colsum_ws_floats(int64_t rows, int64_t cols) { return colsum_ws_floats(rows, cols); }
+pw_status pw_op_sgd(pw_ctx* c, float* w, const float* g, int64_t n, float lr) { PW_OP(c, launch_sgd(c->exec, w, g, n, lr)); }
+pw_status pw_op_adam(pw_ctx* c, float* w, float* m, float* v, const float* g, void* w_bf16, int64_t n, float lr, float beta1, float beta2,
+                     float eps, int t) {
+  PW_OP(c, launch_adam(c->exec, w, m, v, g, w_bf16, n, lr, beta1, beta2, eps, t, nullptr));
+}
+
+}  // extern "C"

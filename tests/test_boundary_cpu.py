@@ -1,0 +1,84 @@
+"""Host-side checks that need no GPU: the C-ABI library exports what include/pw.h declares, the
+binding covers it, the product path refuses to run without a GPU, and host-only arithmetic."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2203_12533_amd import binding as pwb
+from paper_2203_12533_amd import inputs as I
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_in_header():
+    text = open(os.path.join(ROOT, "include", "pw.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pw_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_in_header()
+    assert len(names) >= 40
+    lib = C.CDLL(pwb.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), f"libpw.so lacks {n}"
+
+
+def test_binding_covers_the_header():
+    assert sorted(pwb.DECLARED_SYMBOLS) == _declared_in_header()
+    pwb.lib()      # sets every signature; raises if one is missing
+
+
+def test_struct_layouts_match_the_header():
+    assert C.sizeof(pwb.TensorSpec) == 40
+    assert C.sizeof(pwb.FnDesc) == 16 + 16 * 40 + 16
+    assert C.sizeof(pwb.LMConfigC) == 16 * 4
+    assert C.sizeof(pwb.StageParams) == 16
+    assert C.sizeof(pwb.GemmArgs) == 12 + 4 + 6 * 8 + 12 + 4 + 6 * 8
+
+
+def test_no_gpu_means_a_loud_failure_not_a_fallback():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(pwb.PwError) as e:
+        pwb.Context(0)
+    assert e.value.status in (pwb.PW_ERR_DEVICE, pwb.PW_ERR_UNSUPPORTED)
+
+
+def test_null_arguments_are_rejected_without_a_context():
+    lib = pwb.lib()
+    assert lib.pw_ctx_create(0, None, None) == pwb.PW_ERR_INVALID
+    assert lib.pw_ctx_destroy(None) == pwb.PW_ERR_INVALID
+    assert lib.pw_compile_fn(None, None, None) == pwb.PW_ERR_INVALID
+    assert lib.pw_run_fn(None, 0, None, 0, None, 0) == pwb.PW_ERR_INVALID
+    assert lib.pw_await(None, 0, None, 0) == pwb.PW_ERR_INVALID
+    assert lib.pw_model_param_count(None) == -1
+
+
+def test_model_flops_of_the_measured_workloads():
+    # 6 N (L 12 d^2 + d V) + 6 B T^2 d L, the convention the throughput is priced with
+    c3 = I.workload("cfg3")
+    want = 6 * 8192 * (12 * 12 * 2048 ** 2 + 2048 * 32768) + 6 * 8 * 1024 ** 2 * 2048 * 12
+    assert pwb.step_flops(c3) == pytest.approx(want, rel=1e-12)
+    assert pwb.step_flops(c3) == pytest.approx(34.2e12, rel=5e-3)
+    assert pwb.step_flops(I.workload("cfg1")) == pytest.approx(5.64e9 + 0.20e9, rel=1e-2)
+    assert pwb.step_flops(I.workload("cfg4")) == pytest.approx(82.5e12, rel=5e-3)
+    assert pwb.step_flops(I.workload("cfg5")) == pytest.approx(47.0e12, rel=5e-3)
+
+
+def test_generator_is_counter_based_and_reproducible():
+    import numpy as np
+    a = I.normal(5, 9, 1000)
+    b = I.normal(5, 9, 2000)
+    assert np.array_equal(a, b[:1000])                      # a prefix does not depend on the length drawn
+    assert not np.array_equal(a, I.normal(6, 9, 1000))
+    t = I.lm_tokens(I.workload("cfg1"))
+    assert t.shape == (4, 129) and t.min() >= 0 and t.max() < 1024
+    w = I.lm_params(I.workload("cfg3").with_(n_layer=1, vocab=64, seq=8))
+    assert np.array_equal(I.round_to_bf16(w["l0.wo"]), w["l0.wo"])   # bf16 workloads start bf16-representable
+    x = np.array([1.0, 1.00390625, 1.01171875, -3.0e-41], dtype=np.float32)
+    r = I.round_to_bf16(x)
+    assert r[0] == 1.0 and r[1] == 1.0 and r[2] == np.float32(1.015625)   # ties to even, both directions

@@ -1,0 +1,187 @@
+"""Dispatch layer on the GPU: chained compiled functions consuming futures (Sections 3, 4.4, 4.5, 5.1)."""
+import os
+import time
+
+import numpy as np
+import pytest
+
+from paper_2203_12533_amd import binding as pwb
+from paper_2203_12533_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = pwb.Context(0)
+    yield c
+    c.close()
+
+
+@pytest.mark.parametrize("mode", [pwb.PW_STREAM, pwb.PW_GRAPH, pwb.PW_SEQUENTIAL])
+@pytest.mark.parametrize("L", [1, 8, 32, 128])
+def test_chain_on_pending_input_is_exact(ctx, orc, L, mode):
+    x = I.dispatch_input()
+    add1 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    want = orc.chain_add(x, L)
+    for rep in range(3):                       # replays of a cached graph must stay right
+        xin = x + np.float32(rep)
+        want = orc.chain_add(xin, L)
+        if mode == pwb.PW_SEQUENTIAL:
+            # this baseline waits for every link to finish, so its input has to exist already
+            f_in = ctx.future_from_host(xin)
+            (f_out,) = ctx.chain([add1] * L, [f_in], 1, mode)
+        else:
+            f_in = ctx.future_pending(pwb.PW_F32, (128,))
+            (f_out,) = ctx.chain([add1] * L, [f_in], 1, mode)
+            # the whole chain is enqueued although its input does not exist yet
+            assert ctx.future_query(f_out) == pwb.PW_ERR_NOT_READY
+            ctx.future_resolve(f_in, xin)
+        got = ctx.await_(f_out)
+        assert np.array_equal(got, want), (L, mode, rep)
+        assert ctx.future_query(f_out) == pwb.PW_OK
+        ctx.future_release(f_in)
+        ctx.future_release(f_out)
+    ctx.fn_release(add1)
+
+
+def test_sequential_mode_is_not_given_a_pending_input(ctx):
+    """PW_SEQUENTIAL synchronises after every link; with a ready input it must give the same bits."""
+    x = I.dispatch_input()
+    add1 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    f_in = ctx.future_from_host(x)
+    outs = []
+    for mode in (pwb.PW_STREAM, pwb.PW_GRAPH, pwb.PW_SEQUENTIAL):
+        (f,) = ctx.chain([add1] * 16, [f_in], 1, mode)
+        outs.append(ctx.await_(f))
+        ctx.future_release(f)
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    ctx.future_release(f_in)
+
+
+def test_op_by_op_equals_chained(ctx, orc):
+    x = I.dispatch_input()
+    add1 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    f = ctx.future_from_host(x)
+    for _ in range(32):
+        (g,) = ctx.run_fn(add1, [f])
+        ctx.future_release(f)
+        f = g
+    assert np.array_equal(ctx.await_(f), orc.chain_add(x, 32))
+    ctx.future_release(f)
+
+
+def test_figure2_program_with_fan_out(ctx):
+    rows = {}
+    for line in open(os.path.join(GOLD, "fig2_example.txt")):
+        if line.strip() and not line.startswith("#"):
+            k, *v = line.split()
+            rows[k] = np.array(v, dtype=np.float32)
+    n = rows["input"].size
+    a = ctx.compile_scalar_fn(pwb.PW_FN_MUL_CONST, n, 2.0)
+    b = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, n, 1.0)
+    c = ctx.compile_scalar_fn(pwb.PW_FN_DIV_CONST, n, 2.0)
+    v = ctx.future_pending(pwb.PW_F32, (n,))
+    (x,) = ctx.run_fn(a, [v])
+    (y,) = ctx.run_fn(b, [x])          # x feeds two consumers
+    (cx,) = ctx.run_fn(c, [x])
+    (z,) = ctx.run_fn(a, [cx])         # `a` is reused
+    assert ctx.future_query(y) == pwb.PW_ERR_NOT_READY and ctx.future_query(z) == pwb.PW_ERR_NOT_READY
+    ctx.future_resolve(v, rows["input"])
+    assert np.array_equal(ctx.await_(y), rows["y"])
+    assert np.array_equal(ctx.await_(z), rows["z"])
+    for f in (v, x, y, cx, z):
+        ctx.future_release(f)
+
+
+def test_signature_mismatch_is_rejected_before_any_launch(ctx):
+    add128 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    add64 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 64, 1.0)
+    live0, bytes0 = ctx.stats()
+    f64 = ctx.future_from_host(np.zeros(64, np.float32))
+    fi = ctx.future_from_host(np.zeros(128, np.int32))
+    with pytest.raises(pwb.PwError) as e:
+        ctx.run_fn(add128, [f64])
+    assert e.value.status == pwb.PW_ERR_SHAPE
+    with pytest.raises(pwb.PwError) as e:
+        ctx.run_fn(add128, [fi])
+    assert e.value.status == pwb.PW_ERR_DTYPE
+    with pytest.raises(pwb.PwError) as e:          # link 1 of the chain does not fit link 0's output
+        ctx.chain([add64, add128], [f64], 1, pwb.PW_STREAM)
+    assert e.value.status == pwb.PW_ERR_SHAPE
+    with pytest.raises(pwb.PwError) as e:
+        ctx.run_fn(add128, [f64, f64])
+    assert e.value.status == pwb.PW_ERR_SHAPE
+    with pytest.raises(pwb.PwError) as e:
+        ctx.run_fn(12345, [f64])
+    assert e.value.status == pwb.PW_ERR_INVALID
+    with pytest.raises(pwb.PwError) as e:          # impossible signature at compile time
+        ctx.compile_fn(pwb.PW_FN_ADD_CONST, [pwb.make_spec(pwb.PW_F32, (4,))], [pwb.make_spec(pwb.PW_F32, (5,))],
+                       np.float32(1).tobytes())
+    assert e.value.status == pwb.PW_ERR_SHAPE
+    ctx.future_release(f64)
+    ctx.future_release(fi)
+    assert ctx.stats() == (live0, bytes0)          # the failed calls allocated nothing that stayed
+
+
+def test_poisoned_and_timed_out_inputs_poison_their_dependents(ctx):
+    add1 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    f_in = ctx.future_pending(pwb.PW_F32, (128,))
+    (f_out,) = ctx.chain([add1] * 4, [f_in], 1, pwb.PW_STREAM)
+    ctx.future_resolve(f_in, None)                 # the producer "failed"
+    with pytest.raises(pwb.PwError) as e:
+        ctx.await_(f_out)
+    assert e.value.status == pwb.PW_ERR_POISONED
+    assert ctx.future_query(f_out) == pwb.PW_ERR_POISONED
+    ctx.future_release(f_in)
+    ctx.future_release(f_out)
+    # a gate nobody resolves gives up by itself after the (here tiny) time limit: every kernel still exits
+    ctx.set_gate_timeout_ms(50)
+    f_in = ctx.future_pending(pwb.PW_F32, (128,))
+    (f_out,) = ctx.run_fn(add1, [f_in])
+    t0 = time.time()
+    with pytest.raises(pwb.PwError) as e:
+        ctx.await_(f_out)
+    assert e.value.status == pwb.PW_ERR_POISONED and time.time() - t0 < 5.0
+    ctx.set_gate_timeout_ms(20000)
+    ctx.future_release(f_in)
+    ctx.future_release(f_out)
+
+
+def test_refcounts_and_pool_reuse(ctx):
+    live0, bytes0 = ctx.stats()
+    add1 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    f = ctx.future_from_host(np.ones(128, np.float32))
+    ctx.future_retain(f)
+    ctx.future_release(f)
+    (g,) = ctx.run_fn(add1, [f])                   # still alive after one release
+    assert ctx.await_(g)[0] == 2.0
+    ctx.future_release(f)
+    with pytest.raises(pwb.PwError):               # now it is gone
+        ctx.run_fn(add1, [f])
+    ctx.future_release(g)
+    assert ctx.stats() == (live0, bytes0)
+    p1 = []
+    for _ in range(3):
+        h = ctx.future_from_host(np.ones(128, np.float32))
+        p1.append(ctx.future_device_ptr(h))
+        ctx.future_release(h)
+    assert p1[0] == p1[1] == p1[2]                 # the pool hands the same buffer back
+
+
+def test_busy_function_and_empty_tensor(ctx):
+    busy = ctx.compile_scalar_fn(pwb.PW_FN_BUSY, 128, 1.0, busy_us=200.0)
+    f = ctx.future_from_host(np.zeros(128, np.float32))
+    t0 = time.time()
+    (g,) = ctx.chain([busy] * 10, [f], 1, pwb.PW_STREAM)
+    out = ctx.await_(g)
+    assert np.array_equal(out, np.full(128, 10.0, np.float32)) and time.time() - t0 > 0.0015
+    ctx.future_release(f)
+    ctx.future_release(g)
+    add0 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 0, 1.0)
+    f = ctx.future_from_host(np.zeros(0, np.float32))
+    (g,) = ctx.run_fn(add0, [f])
+    assert ctx.await_(g).size == 0
+    ctx.future_release(f)
+    ctx.future_release(g)

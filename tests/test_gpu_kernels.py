@@ -1,0 +1,286 @@
+"""Per-kernel parity: every HIP kernel, called through the C boundary, against the CPU oracle on the same
+seeded inputs.  Sizes span several tiles and ragged tails.  Bars (relative L2 per tensor): fp32 path 1e-4,
+bf16 path 2e-2; where the arithmetic allows a much tighter bound the test uses it."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2203_12533_amd import binding as pwb
+from paper_2203_12533_amd import inputs as I
+from gpu_util import DT, TOL, dev_act, dev_f32, dev_i32, empty_act, host, ptr, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = pwb.Context(0)
+    yield c
+    c.close()
+
+
+def _rand(seed, shape, std=1.0):
+    return I.normal(seed, 77, int(np.prod(shape)), std).reshape(shape)
+
+
+# ---- GEMM ---------------------------------------------------------------------------------------------
+
+GEMM_SHAPES = [(300, 200, 136), (512, 384, 256), (130, 72, 8), (4096, 4096, 128), (4072, 4088, 200)]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("shape", GEMM_SHAPES)
+def test_gemm_forward_layout_bias(ctx, orc, shape, bf16):
+    """C = x[M,K] . W[K,N] + b: A row-major in k, B stored k-major (the forward projections)."""
+    M, N, K = shape
+    if not bf16 and M * N * K > 1e9:
+        pytest.skip("fp32 ALU path is for the small configuration")
+    x, xv = dev_act(_rand(1, (M, K)), bf16)
+    w, wv = dev_act(_rand(2, (K, N), 0.05), bf16)
+    b = _rand(3, (N,))
+    bd = dev_f32(b)
+    out = empty_act((M, N), bf16)
+    ctx.gemm(dtype=DT[bf16], a_kmajor=0, b_kmajor=1, M=M, N=N, K=K, lda=K, ldb=N, ldc=N, epilogue=pwb.PW_EPI_BIAS,
+             out_dtype=DT[bf16], accumulate=0, A=ptr(x), B=ptr(w), bias=ptr(bd), C=ptr(out))
+    ctx.synchronize()
+    ref = orc.linear_fwd(xv, wv, b.astype(np.float64))
+    assert rel_l2(host(out), ref) < (4e-3 if bf16 else 2e-6)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("shape", GEMM_SHAPES[:3] + [(4096, 4096, 128)])
+def test_gemm_dgrad_and_wgrad_layouts(ctx, orc, shape, bf16):
+    """dx = dy . W^T (B stored [n][k]) and dW = x^T . dy (both operands k-major), fp32 accumulate-into."""
+    M, N, K = shape          # M tokens, N = in features, K = out features
+    if not bf16 and M * N * K > 1e9:
+        pytest.skip("fp32 ALU path is for the small configuration")
+    if bf16 and (N % 8 or K % 8 or M % 8):
+        pytest.skip("bf16 operands need 16-byte aligned rows")
+    dy, dyv = dev_act(_rand(4, (M, K)), bf16)
+    w, wv = dev_act(_rand(5, (N, K), 0.05), bf16)
+    x, xv = dev_act(_rand(6, (M, N)), bf16)
+    dx = empty_act((M, N), bf16)
+    ctx.gemm(dtype=DT[bf16], a_kmajor=0, b_kmajor=0, M=M, N=N, K=K, lda=K, ldb=K, ldc=N, epilogue=pwb.PW_EPI_STORE,
+             out_dtype=DT[bf16], accumulate=0, A=ptr(dy), B=ptr(w), C=ptr(dx))
+    base = _rand(7, (N, K))
+    dw = dev_f32(base)
+    for acc in (1, 0):
+        ctx.gemm(dtype=DT[bf16], a_kmajor=1, b_kmajor=1, M=N, N=K, K=M, lda=N, ldb=K, ldc=K,
+                 epilogue=pwb.PW_EPI_STORE, out_dtype=pwb.PW_F32, accumulate=acc, A=ptr(x), B=ptr(dy), C=ptr(dw))
+        ctx.synchronize()
+        rdx, rdw, _ = orc.linear_bwd(xv, wv, dyv)
+        want = rdw + base if acc else rdw
+        assert rel_l2(host(dw), want) < 2e-6, acc
+    assert rel_l2(host(dx), rdx) < (4e-3 if bf16 else 2e-6)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_gemm_fused_epilogues(ctx, orc, bf16):
+    M, N, K = 264, 328, 192
+    x, xv = dev_act(_rand(8, (M, K)), bf16)
+    w, wv = dev_act(_rand(9, (K, N), 0.08), bf16)
+    b = _rand(10, (N,), 0.5)
+    bd = dev_f32(b)
+    lin = orc.linear_fwd(xv, wv, b.astype(np.float64))
+    common = dict(dtype=DT[bf16], a_kmajor=0, b_kmajor=1, M=M, N=N, K=K, lda=K, ldb=N, ldc=N, accumulate=0,
+                  A=ptr(x), B=ptr(w))
+    # bias + GELU, both the pre-activation and the activation are kept
+    u, h = empty_act((M, N), bf16), empty_act((M, N), bf16)
+    ctx.gemm(epilogue=pwb.PW_EPI_BIAS_GELU, out_dtype=DT[bf16], bias=ptr(bd), C=ptr(u), C2=ptr(h), **common)
+    # bias + residual into the fp32 stream
+    res = _rand(11, (M, N))
+    resd, xo = dev_f32(res), torch.empty((M, N), dtype=torch.float32, device="cuda")
+    ctx.gemm(epilogue=pwb.PW_EPI_BIAS_RESIDUAL, out_dtype=pwb.PW_F32, bias=ptr(bd), aux=ptr(resd), C=ptr(xo), **common)
+    # product times gelu'(aux)
+    pre, prev = dev_act(_rand(12, (M, N), 1.5), bf16)
+    du = empty_act((M, N), bf16)
+    ctx.gemm(epilogue=pwb.PW_EPI_GELU_BWD, out_dtype=DT[bf16], aux=ptr(pre), C=ptr(du), **common)
+    ctx.synchronize()
+    tol = 4e-3 if bf16 else 2e-6
+    assert rel_l2(host(u), lin) < tol
+    assert rel_l2(host(h), orc.gelu_fwd(lin)) < tol * 1.5
+    assert rel_l2(host(xo), lin + res) < (2e-6 if not bf16 else 1e-5)
+    nobias = orc.linear_fwd(xv, wv)
+    assert rel_l2(host(du), orc.gelu_bwd(prev, nobias)) < tol
+
+
+def test_gemm_rejects_what_the_kernel_cannot_take(ctx):
+    a = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros(64 * 64, dtype=torch.float32, device="cuda")
+    base = dict(dtype=pwb.PW_BF16, a_kmajor=0, b_kmajor=0, M=16, N=16, K=20, lda=20, ldb=20, ldc=16,
+                epilogue=pwb.PW_EPI_STORE, out_dtype=pwb.PW_F32, accumulate=0, A=ptr(a), B=ptr(a), C=ptr(c))
+    with pytest.raises(pwb.PwError):
+        ctx.gemm(**base)                                   # K not a multiple of 8
+    with pytest.raises(pwb.PwError):
+        ctx.gemm(**{**base, "K": 16, "lda": 8, "ldb": 16})  # lda < K
+    with pytest.raises(pwb.PwError):
+        ctx.gemm(**{**base, "K": 16, "lda": 16, "ldb": 16, "A": ptr(a) + 2})   # misaligned
+    with pytest.raises(pwb.PwError):
+        ctx.gemm(**{**base, "K": 16, "lda": 16, "ldb": 16, "epilogue": pwb.PW_EPI_BIAS_RESIDUAL})   # no aux
+    ctx.gemm(**{**base, "K": 16, "lda": 16, "ldb": 16, "M": 0})    # empty problem: accepted, nothing launched
+    ctx.synchronize()
+
+
+# ---- LayerNorm ----------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("N,d", [(37, 256), (5, 1000), (600, 2048), (3, 8192)])
+def test_layernorm_forward_backward(ctx, orc, N, d, bf16):
+    x = _rand(20, (N, d), 2.0) + 0.5
+    g, b = 1 + _rand(21, (d,), 0.1), _rand(22, (d,), 0.1)
+    xd, gd, bd = dev_f32(x), dev_f32(g), dev_f32(b)
+    y = empty_act((N, d), bf16)
+    mean, rstd = torch.empty(N, device="cuda"), torch.empty(N, device="cuda")
+    ctx.op("layernorm_fwd", DT[bf16], ptr(xd), ptr(gd), ptr(bd), ptr(y), ptr(mean), ptr(rstd), N, d)
+    ry, rmean, rrstd = orc.layernorm_fwd(x, g, b)
+    dy, dyv = dev_act(_rand(23, (N, d)), bf16)
+    dres = _rand(24, (N, d))
+    dresd = dev_f32(dres)
+    dx = torch.empty((N, d), device="cuda")
+    dxlp = empty_act((N, d), bf16) if bf16 else None
+    dg, db = dev_f32(np.ones(d)), dev_f32(np.ones(d))
+    ws = torch.empty(pwb.lib().pw_layernorm_bwd_ws_floats(N, d), device="cuda")
+    ctx.op("layernorm_bwd", DT[bf16], ptr(dy), ptr(xd), ptr(gd), ptr(mean), ptr(rstd), ptr(dresd), ptr(dx), ptr(dxlp),
+           ptr(dg), ptr(db), ptr(ws), N, d, 1)
+    ctx.synchronize()
+    assert rel_l2(host(y), ry) < (4e-3 if bf16 else 2e-6)
+    assert rel_l2(host(mean), rmean) < 1e-5 and rel_l2(host(rstd), rrstd) < 1e-5
+    rdx, rdg, rdb = orc.layernorm_bwd(dyv, x, g)
+    assert rel_l2(host(dx), rdx + dres) < 1e-5
+    assert rel_l2(host(dg), rdg + 1.0) < 1e-5 and rel_l2(host(db), rdb + 1.0) < 1e-5   # accumulate = 1 adds
+    if bf16:
+        assert rel_l2(host(dxlp), rdx + dres) < 4e-3
+
+
+# ---- attention ----------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("B,T,H,hd", [(2, 200, 2, 64), (1, 130, 3, 128), (2, 1, 1, 64), (1, 384, 2, 128)])
+def test_attention_forward_backward(ctx, orc, B, T, H, hd, bf16):
+    d = H * hd
+    qkv, qkvv = dev_act(_rand(30, (B * T, 3 * d), 1.0), bf16)
+    o = empty_act((B * T, d), bf16)
+    lse = torch.empty((B, H, T), device="cuda")
+    ctx.op("attention_fwd", DT[bf16], ptr(qkv), ptr(o), ptr(lse), B, T, H, hd)
+    ctx.synchronize()
+    ro = orc.attention_fwd(qkvv, B, T, H, hd)
+    assert rel_l2(host(o), ro) < (6e-3 if bf16 else 1e-5)
+    # log-sum-exp of the scaled causal scores, brute force for a few rows
+    r = qkvv.reshape(B, T, 3, H, hd)
+    for (b, h, i) in [(0, 0, 0), (B - 1, H - 1, T - 1), (0, H - 1, T // 2)]:
+        s = r[b, : i + 1, 1, h] @ r[b, i, 0, h] / np.sqrt(hd)
+        want = np.log(np.exp(s - s.max()).sum()) + s.max()
+        assert abs(host(lse)[b, h, i] - want) < (2e-2 if bf16 else 1e-4)
+    dout, doutv = dev_act(_rand(31, (B * T, d)), bf16)
+    dqkv = empty_act((B * T, 3 * d), bf16)
+    delta = torch.empty((B, H, T), device="cuda")
+    ctx.op("attention_bwd", DT[bf16], ptr(qkv), ptr(o), ptr(dout), ptr(lse), ptr(delta), ptr(dqkv), B, T, H, hd)
+    ctx.synchronize()
+    rd = orc.attention_bwd(qkvv, doutv, B, T, H, hd)
+    got = host(dqkv)
+    for name, sl in (("dq", slice(0, d)), ("dk", slice(d, 2 * d)), ("dv", slice(2 * d, 3 * d))):
+        assert rel_l2(got[:, sl], rd[:, sl]) < (1.5e-2 if bf16 else 1e-5), name
+
+
+# ---- softmax cross-entropy ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("B,T,V", [(3, 5, 1024), (2, 7, 4096), (1, 3, 32768), (2, 2, 8)])
+def test_softmax_xent(ctx, orc, B, T, V, bf16):
+    N = B * T
+    z, zv = dev_act(_rand(40, (N, V), 2.0), bf16)
+    tok = I.tokens(41, 1, (B, T + 1), V)
+    tokd = dev_i32(tok)
+    loss, rows = torch.empty(1, device="cuda"), torch.empty(N, device="cuda")
+    ctx.op("softmax_xent", DT[bf16], ptr(z), ptr(tokd), ptr(loss), ptr(rows), B, T, V)
+    ctx.synchronize()
+    rl, rdz = orc.softmax_xent(zv, tok[:, 1:].reshape(-1))
+    assert abs(host(loss)[0] - rl) / rl < 1e-5
+    assert rel_l2(host(z), rdz) < (6e-3 if bf16 else 1e-5)
+    if not bf16:
+        assert np.abs(host(z).sum(axis=1)).max() < 1e-6     # rows of dlogits sum to 0
+
+
+# ---- embedding ----------------------------------------------------------------------------------------
+
+def test_embedding_forward_is_bit_exact_and_backward_is_deterministic(ctx, orc):
+    B, T, d, V = 4, 129, 256, 97          # V small: many repeated ids
+    tok = I.tokens(50, 1, (B, T + 1), V)
+    tok[0, :40] = 5                        # one id repeated many times, in a row and across rows
+    tok[1, 10:30] = 5
+    wte, wpe = _rand(51, (V, d), 0.02), _rand(52, (T, d), 0.02)
+    tokd, wted, wped = dev_i32(tok), dev_f32(wte), dev_f32(wpe)
+    x = torch.empty((B * T, d), device="cuda")
+    ctx.op("embedding_fwd", ptr(tokd), ptr(wted), ptr(wped), ptr(x), B, T, d, V)
+    ctx.synchronize()
+    inp = tok[:, :T]
+    want = (wte[inp.reshape(-1)] + np.tile(wpe, (B, 1))).astype(np.float32)      # one fp32 add per element
+    assert np.array_equal(x.cpu().numpy(), want)
+    # the oracle adds in double, where the sum of two fp32 values is exact; rounded once it must give the same bits
+    assert np.array_equal(x.cpu().numpy(), orc.embedding_fwd(inp, wte, wpe).astype(np.float32))
+    dx = _rand(53, (B * T, d))
+    dxd = dev_f32(dx)
+    outs = []
+    for _ in range(2):
+        dwte = torch.full((V, d), 7.0, device="cuda")        # stale contents must be overwritten
+        dwpe = torch.full((T, d), 7.0, device="cuda")
+        ctx.op("embedding_bwd", ptr(tokd), ptr(dxd), ptr(dwte), ptr(dwpe), B, T, d, V)
+        ctx.synchronize()
+        outs.append((dwte.cpu().numpy(), dwpe.cpu().numpy()))
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+    rwte, rwpe = orc.embedding_bwd(inp, dx, V)
+    assert rel_l2(outs[0][0], rwte) < 1e-6 and rel_l2(outs[0][1], rwpe) < 1e-6
+    unused = sorted(set(range(V)) - set(inp.reshape(-1).tolist()))
+    for u in unused:
+        assert (outs[0][0][u] == 0).all()
+
+
+def test_embedding_backward_handles_one_id_everywhere(ctx, orc):
+    """Degenerate case: every position holds the same id (the list of matches exceeds one LDS batch)."""
+    B, T, d, V = 3, 1000, 64, 11
+    tok = np.full((B, T + 1), 4, dtype=np.int32)
+    dx = _rand(54, (B * T, d))
+    tokd, dxd = dev_i32(tok), dev_f32(dx)
+    dwte, dwpe = torch.empty((V, d), device="cuda"), torch.empty((T, d), device="cuda")
+    ctx.op("embedding_bwd", ptr(tokd), ptr(dxd), ptr(dwte), ptr(dwpe), B, T, d, V)
+    ctx.synchronize()
+    rwte, _ = orc.embedding_bwd(tok[:, :T], dx, V)
+    assert rel_l2(host(dwte), rwte) < 1e-5
+
+
+# ---- column sums and optimisers -----------------------------------------------------------------------
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("rows,cols", [(513, 768), (8, 64), (2048, 8192), (1, 12)])
+def test_colsum(ctx, rows, cols, bf16):
+    a, av = dev_act(_rand(60, (rows, cols)), bf16)
+    out = dev_f32(np.full(cols, 3.0))
+    ws = torch.empty(pwb.lib().pw_colsum_ws_floats(rows, cols), device="cuda")
+    ctx.op("colsum", DT[bf16], ptr(a), ptr(out), ptr(ws), rows, cols, 1)
+    ctx.synchronize()
+    assert rel_l2(host(out), av.sum(axis=0) + 3.0) < 1e-5
+    ctx.op("colsum", DT[bf16], ptr(a), ptr(out), ptr(ws), rows, cols, 0)
+    ctx.synchronize()
+    assert rel_l2(host(out), av.sum(axis=0)) < 1e-5
+
+
+@pytest.mark.parametrize("n", [1, 1023, 1 << 20])
+def test_sgd_and_adam_kernels(ctx, orc, n):
+    w, g = _rand(70, (n,)), _rand(71, (n,), 0.1)
+    g[: n // 3] = 0.0
+    wd, gd = dev_f32(w), dev_f32(g)
+    ctx.op("sgd", ptr(wd), ptr(gd), n, 0.01)
+    ctx.synchronize()
+    assert rel_l2(host(wd), orc.sgd(w.astype(np.float64), g.astype(np.float64), np.float32(0.01))) < 1e-7
+    wd, md, vd = dev_f32(w), dev_f32(np.zeros(n)), dev_f32(np.zeros(n))
+    wlp = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    rw, rm, rv = w.astype(np.float64), np.zeros(n), np.zeros(n)
+    lr, b1, b2, eps = 1e-3, 0.9, 0.95, 1e-8
+    for t in (1, 2, 3):
+        ctx.op("adam", ptr(wd), ptr(md), ptr(vd), ptr(gd), ptr(wlp), n, lr, b1, b2, eps, t)
+        rw, rm, rv = orc.adam(rw, rm, rv, g.astype(np.float64), np.float32(lr), np.float32(b1), np.float32(b2),
+                              np.float32(eps), t)
+    ctx.synchronize()
+    assert np.abs(host(wd) - rw).max() < 1e-6            # identical gradient: the kernel itself is held to 1e-6
+    assert rel_l2(host(md), rm) < 1e-6 and rel_l2(host(vd), rv) < 1e-6
+    assert np.array_equal(wlp.float().cpu().numpy(), I.round_to_bf16(wd.cpu().numpy()))   # bf16 copy is RNE of w

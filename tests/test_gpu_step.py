@@ -1,0 +1,179 @@
+"""Whole train step on the GPU against the CPU oracle: fp32 configuration 1 in full, a reduced bf16
+configuration, the pipeline-stage schedule, and run-to-run / dispatch-mode determinism."""
+import numpy as np
+import pytest
+
+from paper_2203_12533_amd import binding as pwb
+from paper_2203_12533_amd import inputs as I
+from gpu_util import TOL, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = pwb.Context(0)
+    yield c
+    c.close()
+
+
+def run_steps(ctx, cfg, params, tok, n_steps=1, mode=None):
+    """Runs n_steps train steps; returns (losses, model) - caller closes the model."""
+    model = ctx.model(cfg)
+    model.load_params(params)
+    step = model.compile_train_step()
+    losses = []
+    for _ in range(n_steps):
+        ft = ctx.future_from_host(tok)
+        if mode is None:
+            fl = ctx.train_step(step, ft)
+        else:
+            (fl,) = ctx.chain([step], [ft], 1, mode)
+        losses.append(float(ctx.await_(fl)[0]))
+        ctx.future_release(ft)
+        ctx.future_release(fl)
+    return losses, model
+
+
+def check_against_oracle(cfg, params, ref, loss, model, tol, check_update=True):
+    assert abs(loss - ref["loss"]) / abs(ref["loss"]) < tol, (loss, ref["loss"])
+    grads = model.export_all(pwb.PW_GRADS, params)
+    worst = ("", 0.0)
+    for k, g in grads.items():
+        err = rel_l2(g, ref["grads"][k])
+        if err > worst[1]:
+            worst = (k, err)
+        assert err < tol, (k, err)
+    if check_update:
+        new = model.export_all(pwb.PW_PARAMS, params)
+        for k in new:
+            got_delta = new[k].astype(np.float64) - params[k].astype(np.float64)
+            ref_delta = ref["params"][k] - params[k].astype(np.float64)
+            # fp32 storage of w limits how well a tiny delta can be read back: allow w's rounding on top
+            slack = np.linalg.norm(params[k]) * 6e-8 / max(np.linalg.norm(ref_delta), 1e-30)
+            assert rel_l2(got_delta, ref_delta) < tol + slack, (k, rel_l2(got_delta, ref_delta))
+    return worst
+
+
+@pytest.mark.parametrize("perturb", [False, True])
+def test_cfg1_fp32_step_matches_oracle(ctx, orc, perturb):
+    cfg = I.workload("cfg1")
+    params, tok = I.lm_params(cfg, perturb=perturb), I.lm_tokens(cfg)
+    ref = orc.lm_train_step(cfg, params, tok)
+    (loss,), model = run_steps(ctx, cfg, params, tok)
+    worst = check_against_oracle(cfg, params, ref, loss, model, TOL[False])
+    print("cfg1 fp32 worst gradient error", worst)
+    model.close()
+
+
+def test_fp32_ragged_sequence_and_adam(ctx, orc):
+    """Sequence length that is not a multiple of any tile, Adam update, three steps."""
+    cfg = I.LMConfig(2, 128, 2, 256, 264, 75, 3, bf16=False, optimizer="adam", lr=1e-3)
+    params, tok = I.lm_params(cfg, perturb=True), I.lm_tokens(cfg)
+    losses, model = run_steps(ctx, cfg, params, tok, n_steps=3)
+    p, st, ref_losses = params, None, []
+    for t in (1, 2, 3):
+        ref = orc.lm_train_step(cfg, p, tok, state=st, t=t)
+        ref_losses.append(ref["loss"])
+        p, st = ref["params"], {"m": ref["m"], "v": ref["v"]}
+    for a, b in zip(losses, ref_losses):
+        assert abs(a - b) / b < 1e-4
+    assert ref_losses[2] < ref_losses[0]          # it does train
+    model.close()
+
+
+BF16_SMALL = I.LMConfig(2, 256, 2, 1024, 2048, 256, 2, bf16=True, optimizer="adam", lr=1e-4)
+
+
+def test_bf16_step_matches_oracle(ctx, orc):
+    cfg = BF16_SMALL
+    params, tok = I.lm_params(cfg, perturb=True), I.lm_tokens(cfg)
+    ref = orc.lm_train_step(cfg, params, tok)
+    (loss,), model = run_steps(ctx, cfg, params, tok)
+    # Adam's first update is -lr*sign(g) wherever |g| >> eps: sign-sensitive for tiny g, so the update is held
+    # to the kernel-level test; here loss and every gradient are compared
+    worst = check_against_oracle(cfg, params, ref, loss, model, TOL[True], check_update=False)
+    print("bf16 worst gradient error", worst)
+    model.close()
+
+
+def test_bf16_three_steps_track_the_oracle(ctx, orc):
+    cfg = BF16_SMALL.with_(lr=1e-3)
+    params, tok = I.lm_params(cfg), I.lm_tokens(cfg)
+    losses, model = run_steps(ctx, cfg, params, tok, n_steps=3)
+    p, st = params, None
+    for t in (1, 2, 3):
+        ref = orc.lm_train_step(cfg, p, tok, state=st, t=t)
+        assert abs(losses[t - 1] - ref["loss"]) / ref["loss"] < TOL[True], (t, losses, ref["loss"])
+        p, st = ref["params"], {"m": ref["m"], "v": ref["v"]}
+    model.close()
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_step_is_deterministic_and_dispatch_modes_agree(ctx, bf16):
+    """Same inputs, same bits: twice directly, once as a one-link chain, once as a replayed HIP graph."""
+    cfg = BF16_SMALL.with_(bf16=bf16)
+    params, tok = I.lm_params(cfg, perturb=True), I.lm_tokens(cfg)
+    results = []
+    for mode in (None, None, pwb.PW_STREAM, pwb.PW_GRAPH):
+        losses, model = run_steps(ctx, cfg, params, tok, n_steps=2, mode=mode)
+        results.append((losses, model.export_all(pwb.PW_GRADS, params), model.export_all(pwb.PW_PARAMS, params)))
+        model.close()
+    for losses, grads, new in results[1:]:
+        assert losses == results[0][0]
+        for k in grads:
+            assert np.array_equal(grads[k], results[0][1][k]), k
+            assert np.array_equal(new[k], results[0][2][k]), k
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_pipeline_stage_schedule_matches_oracle(ctx, orc, bf16):
+    """GPipe-like schedule on one stage: forward for every micro-batch, backward in reverse, gradients summed."""
+    cfg = I.LMConfig(2, 256, 2, 512, 0, 136, 1, bf16=bf16, optimizer="adam", has_embed=False, has_head=False,
+                     n_microbatch=3)
+    params = I.lm_params(cfg, perturb=True)
+    xs, dys = I.stage_io(cfg)
+    model = ctx.model(cfg)
+    model.load_params(params)
+    model.zero_grads()
+    fwd = [model.compile_stage(pwb.PW_FN_STAGE_FWD, mb) for mb in range(3)]
+    bwd = [model.compile_stage(pwb.PW_FN_STAGE_BWD, mb) for mb in range(3)]
+    ys, dxs = [None] * 3, [None] * 3
+    futs = []
+    for mb in range(3):
+        fx = ctx.future_from_host(xs[mb])
+        (fy,) = ctx.run_fn(fwd[mb], [fx])
+        futs += [fx, fy]
+        ys[mb] = fy
+    for mb in (2, 1, 0):
+        fd = ctx.future_from_host(dys[mb])
+        (fdx,) = ctx.run_fn(bwd[mb], [fd])
+        futs += [fd, fdx]
+        dxs[mb] = fdx
+    Y = [ctx.await_(f) for f in ys]
+    dX = [ctx.await_(f) for f in dxs]
+    rY, rdX, rG = orc.stage_fwd_bwd(cfg, params, xs, dys)
+    tol = TOL[bf16]
+    for mb in range(3):
+        assert rel_l2(Y[mb], rY[mb]) < tol and rel_l2(dX[mb], rdX[mb]) < tol, mb
+    grads = model.export_all(pwb.PW_GRADS, params)
+    for k in grads:
+        assert rel_l2(grads[k], rG[k]) < tol, k
+    for f in futs:
+        ctx.future_release(f)
+    model.close()
+
+
+def test_wrong_token_shape_is_rejected(ctx):
+    cfg = I.LMConfig(1, 128, 2, 256, 64, 16, 2)
+    model = ctx.model(cfg)
+    step = model.compile_train_step()
+    bad = ctx.future_from_host(np.zeros((2, 16), np.int32))       # needs [B, T+1]
+    with pytest.raises(pwb.PwError) as e:
+        ctx.train_step(step, bad)
+    assert e.value.status == pwb.PW_ERR_SHAPE
+    ctx.future_release(bad)
+    with pytest.raises(pwb.PwError) as e:
+        ctx.model(cfg.with_(n_head=3))
+    assert e.value.status == pwb.PW_ERR_UNSUPPORTED
+    model.close()
