@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+A step is one full LM train step (embedding .. loss, backward, Adam) on the 12-layer bf16 workload
+("cfg3": d_model 2048, 16 heads, FFN 8192, vocab 32768, seq 1024, batch 8) with synthetic seeded
+inputs already resident in HBM.  Prints ONE JSON line: whole-step tokens/s, the MFMA roofline of
+the GEMM kernel (HIP-event timing of every GEMM launch inside the timed steps), the chained-dispatch
+cost per function, and the CPU oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg5|cfg1] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
+
+
+def fill_model_on_device(model, cfg, torch, seed: int):
+    """Random-init weights drawn on the GPU (N(0, init_std), bf16-representable), biases 0, gains 1."""
+    from paper_2203_12533_amd import binding as pwb
+    from paper_2203_12533_amd import inputs as I
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    for name, shape, kind in I.param_shapes(cfg):
+        n = int(np.prod(shape))
+        if kind == "matrix":
+            t = torch.randn(n, device="cuda", generator=gen, dtype=torch.float32) * cfg.init_std
+            if cfg.bf16:
+                t = t.to(torch.bfloat16).float()
+        elif kind == "gain":
+            t = torch.ones(n, device="cuda", dtype=torch.float32)
+        else:
+            t = torch.zeros(n, device="cuda", dtype=torch.float32)
+        torch.cuda.synchronize()      # torch filled t on its own stream; the import runs on the executor stream
+        model.import_device(pwb.PW_PARAMS, name, t.data_ptr())
+        del t
+
+
+def dispatch_bench(ctx, pwb, I, reps: int = 200):
+    """Chained dispatch cost (Section 5.1 analogue on one GPU): chains of L trivial functions on a
+    128-float buffer.  host = time for the enqueue call to return; wall = until the result is ready."""
+    add1 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    x = I.dispatch_input()
+    out = {}
+    for L in (1, 8, 32, 128):
+        for mode, mname in ((pwb.PW_STREAM, "stream"), (pwb.PW_GRAPH, "graph")):
+            f_in = ctx.future_from_host(x)
+            host_t, wall_t = [], []
+            for r in range(reps + 20):
+                ctx.synchronize()
+                t0 = time.perf_counter()
+                (f,) = ctx.chain([add1] * L, [f_in], 1, mode)
+                t1 = time.perf_counter()
+                ctx.await_(f, fetch=False)
+                t2 = time.perf_counter()
+                ctx.future_release(f)
+                if r >= 20:
+                    host_t.append(t1 - t0)
+                    wall_t.append(t2 - t0)
+            ctx.future_release(f_in)
+            out[f"L{L}_{mname}"] = {"host_us_per_fn": round(float(np.median(host_t)) * 1e6 / L, 3),
+                                    "wall_us_per_fn": round(float(np.median(wall_t)) * 1e6 / L, 3)}
+    # op-by-op: one client call per function, each awaited (the stress case of Section 5.1)
+    f = ctx.future_from_host(x)
+    ctx.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(128):
+        (g,) = ctx.run_fn(add1, [f])
+        ctx.await_(g, fetch=False)
+        ctx.future_release(f)
+        f = g
+    out["L128_opbyop"] = {"wall_us_per_fn": round((time.perf_counter() - t0) * 1e6 / 128, 3)}
+    ctx.future_release(f)
+    return out
+
+
+def cpu_baseline(cfg, pwb, budget_tokens: int = 128):
+    """The CPU oracle, as it stands, on a bounded sample: same layer / head shapes, one layer, one
+    sequence of `budget_tokens` tokens.  Extrapolated to the full workload by model-FLOP ratio."""
+    from oracle import oracle
+    sample = cfg.with_(n_layer=1, batch=1, seq=min(cfg.seq, budget_tokens))
+    secs = oracle.time_train_step(sample)
+    flops_sample = pwb.step_flops(sample)
+    flops_full_per_token = pwb.step_flops(cfg) / cfg.n_tokens
+    tokens_per_s = (flops_sample / secs) / flops_full_per_token
+    return {"value": tokens_per_s, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"one full oracle train step (fp64, plain loops) on n_layer=1, batch=1, seq={sample.seq} with the "
+                      f"workload's d_model/d_ff/vocab took {secs:.2f} s = {flops_sample / secs / 1e9:.2f} GFLOP/s; "
+                      f"tokens/s extrapolated to the full workload by model-FLOP ratio"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dispatch", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2203_12533_amd import binding as pwb
+    from paper_2203_12533_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    cfg = I.workload(args.workload)
+    ctx = pwb.Context(0)
+    model = ctx.model(cfg)
+    fill_model_on_device(model, cfg, torch, seed=1234)
+    tok = torch.from_numpy(I.lm_tokens(cfg, seed=1234)).cuda()
+    f_tok = ctx.future_wrap_device(tok.data_ptr(), pwb.PW_I32, tuple(tok.shape))
+    step = model.compile_train_step()
+
+    def one_step():
+        f = ctx.train_step(step, f_tok)
+        return f
+
+    losses = []
+    for _ in range(args.warmup):
+        f = one_step()
+        losses.append(float(ctx.await_(f)[0]))
+        ctx.future_release(f)
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    ctx.profile_begin()
+    t0 = time.perf_counter()
+    pending = [one_step() for _ in range(args.steps)]
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    n_gemm, gemm_ms, gemm_flops = ctx.profile_end()
+    for f in pending:
+        losses.append(float(ctx.await_(f)[0]))
+        ctx.future_release(f)
+    if not all(math.isfinite(l) for l in losses):
+        print(f"bench.py: non-finite loss {losses}", file=sys.stderr)
+        sys.exit(1)
+
+    ms_per_step = dt * 1e3 / args.steps
+    tokens_per_s = cfg.n_tokens * args.steps / dt
+    flops = pwb.step_flops(cfg)
+    achieved = flops / (dt / args.steps) / 1e12
+    gemm_tflops = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    result = {
+        "metric": "train tokens/sec/GPU", "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {cfg.n_layer}-layer decoder-only LM train step, d_model {cfg.d_model}, "
+                               f"{cfg.n_head} heads, FFN {cfg.d_ff}, vocab {cfg.vocab}, seq {cfg.seq}, batch {cfg.batch}, "
+                               f"{'bf16 compute / fp32 master' if cfg.bf16 else 'fp32'} + {cfg.optimizer}",
+                   "tokens_per_step": cfg.n_tokens, "model_tflop_per_step": round(flops / 1e12, 3)},
+        "pct_peak_bf16_mfma": round(100.0 * achieved / PEAK_BF16_TFLOPS, 2),
+        "step_tflops": round(achieved, 1),
+        "loss_first_last": [round(losses[0], 4), round(losses[-1], 4)],
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel (all layouts)", "achieved": round(gemm_tflops, 1),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None, "launches_per_step": n_gemm // max(1, args.steps),
+                     "avg_launch_ms": round(gemm_ms / max(1, n_gemm), 4),
+                     "avg_launch_gflop": round(gemm_flops / max(1, n_gemm) / 1e9, 2),
+                     "gemm_ms_per_step": round(gemm_ms / args.steps, 3)},
+    }
+    if not args.no_dispatch:
+        result["dispatch_us_per_fn"] = dispatch_bench(ctx, pwb, I)
+    model.close()
+    ctx.close()
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, pwb)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

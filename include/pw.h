@@ -273,6 +273,14 @@ pw_status pw_op_sgd(pw_ctx* ctx, float* w, const float* g, int64_t n, float lr);
 pw_status pw_op_adam(pw_ctx* ctx, float* w, float* m, float* v, const float* g, void* w_bf16, int64_t n,
                      float lr, float beta1, float beta2, float eps, int t);
 
+/* ---- measurement aid ----------------------------------------------------------------------------
+ * Between pw_profile_begin and pw_profile_end every MFMA GEMM launched on the executor stream (by a train
+ * step or by pw_op_gemm) is bracketed by a pair of timing HIP events on that stream.  pw_profile_end
+ * drains the stream and returns the number of such launches, the sum of their durations in
+ * milliseconds and the sum of their algorithmic FLOPs (2 M N K each).  Not for use inside PW_GRAPH. */
+pw_status pw_profile_begin(pw_ctx* ctx);
+pw_status pw_profile_end(pw_ctx* ctx, int64_t* launches, double* total_ms, double* total_flops);
+
 #ifdef __cplusplus
 }
 #endif

@@ -10,6 +10,7 @@ import ctypes as C
 import os
 import subprocess
 import sys
+import time
 
 import numpy as np
 
@@ -226,17 +227,39 @@ def lm_train_step(cfg, params: dict, tokens, state=None, t: int = 1, update: boo
     loss = ty()
     o = _opt(cfg, t, update and backward)
     fn = lib().orc_lm_train_step if dtype == np.float64 else lib().orc_lm_train_step_f32
+    t0 = time.perf_counter()
     rc = fn(C.byref(s), _p(P, ty), _p(M, ty), _p(V, ty), _p(tok, C.c_int32), C.byref(o), C.byref(loss),
             _p(G, ty), _p(logits, ty), int(backward))
+    seconds = time.perf_counter() - t0
     if rc:
         raise RuntimeError("oracle lm_train_step rejected the configuration")
-    out = {"loss": float(loss.value)}
+    out = {"loss": float(loss.value), "seconds": seconds}   # time inside the C++ step only
     if backward:
         out.update(grads=unpack(cfg, G, params), params=unpack(cfg, P, params),
                    m=unpack(cfg, M, params), v=unpack(cfg, V, params))
     if want_logits:
         out["logits"] = logits
     return out
+
+
+def time_train_step(cfg, seed: int = 0) -> float:
+    """Seconds the C++ oracle takes for one full train step of `cfg` on freshly drawn weights
+    (numpy's own generator: the values only have to be ordinary numbers, nothing is compared)."""
+    s = _shape(cfg)
+    total = lib().orc_lm_param_total(C.byref(s))
+    rng = np.random.default_rng(seed)
+    P = rng.standard_normal(total) * cfg.init_std
+    M, V, G = np.zeros(total), np.zeros(total), np.zeros(total)
+    tok = rng.integers(0, cfg.vocab, size=(cfg.batch, cfg.seq + 1)).astype(np.int32)
+    loss = C.c_double()
+    o = _opt(cfg, 1, True)
+    t0 = time.perf_counter()
+    rc = lib().orc_lm_train_step(C.byref(s), _p(P), _p(M), _p(V), _p(tok, C.c_int32), C.byref(o), C.byref(loss),
+                                 _p(G), None, 1)
+    dt = time.perf_counter() - t0
+    if rc or not np.isfinite(loss.value):
+        raise RuntimeError("oracle step failed")
+    return dt
 
 
 def stage_fwd_bwd(cfg, params: dict, xs, dys):

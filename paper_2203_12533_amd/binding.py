@@ -100,6 +100,8 @@ _SIGS = {
     "pw_model_apply_optimizer": (C.c_int, [C.c_void_p]),
     "pw_model_export_activation": (C.c_int, [C.c_void_p, C.c_char_p, C.c_int, C.c_void_p, C.c_int64]),
     "pw_model_step_flops": (C.c_double, [C.POINTER(LMConfigC)]),
+    "pw_profile_begin": (C.c_int, [C.c_void_p]),
+    "pw_profile_end": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "pw_op_gemm": (C.c_int, [C.c_void_p, C.POINTER(GemmArgs)]),
     "pw_op_embedding_fwd": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4 + [C.c_int] * 4),
     "pw_op_embedding_bwd": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4 + [C.c_int] * 4),
@@ -287,6 +289,15 @@ class Context:
         out = np.empty(shape, dtype=_NP_DTYPES[dtype])
         self._check(lib().pw_await(self._h, f, out.ctypes.data_as(C.c_void_p), out.nbytes))
         return out
+
+    # -- measurement aid
+    def profile_begin(self):
+        self._check(lib().pw_profile_begin(self._h))
+
+    def profile_end(self):
+        n, ms, fl = C.c_int64(), C.c_double(), C.c_double()
+        self._check(lib().pw_profile_end(self._h, C.byref(n), C.byref(ms), C.byref(fl)))
+        return n.value, ms.value, fl.value
 
     # -- model
     def model(self, cfg) -> "Model":

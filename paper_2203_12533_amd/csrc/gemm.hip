@@ -19,6 +19,8 @@
 #include "common.hpp"
 #include "kernels.hpp"
 
+#include <vector>
+
 namespace pw {
 
 struct EpiParams {
@@ -125,12 +127,15 @@ struct GemmBf16Params {
 // Global -> registers for one operand tile of ROWS rows x 64 k.  Each thread owns CNT pieces.
 //   row-major-k operand (KMAJOR = false): piece = 16 bytes = 8 consecutive k of one row.
 //   k-major operand     (KMAJOR = true):  piece = 4 k x 8 rows, held as four 16-byte loads.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
 template <int ROWS, int NT, bool KMAJOR, bool EDGE>
 struct TileLoader {
   static constexpr int kPieces = KMAJOR ? (kBK / 4) * (ROWS / 8) : ROWS * (kBK / 8);
   static constexpr int CNT = kPieces / NT;
   static_assert(kPieces % NT == 0, "tile does not divide over the workgroup");
-  uint4 reg[KMAJOR ? CNT * 4 : CNT];
+  u32x4 reg[KMAJOR ? CNT * 4 : CNT];
 
   // p: operand base; ld: leading dimension; row0: first row (m or n) of the tile; k0: first k;
   // rows_total / k_total: operand extents (used only when EDGE).
@@ -143,9 +148,9 @@ struct TileLoader {
         const int r = id >> 3, kc = id & 7;
         const int64_t row = row0 + r, k = k0 + kc * 8;
         if (!EDGE || (row < rows_total && k < k_total))
-          reg[i] = *reinterpret_cast<const uint4*>(p + row * ld + k);
+          reg[i] = *reinterpret_cast<const u32x4*>(p + row * ld + k);
         else
-          reg[i] = make_uint4(0, 0, 0, 0);
+          reg[i] = u32x4{0, 0, 0, 0};
       } else {
         const int rc = id % (ROWS / 8), kq = id / (ROWS / 8);
         const int64_t row = row0 + rc * 8;
@@ -153,9 +158,9 @@ struct TileLoader {
         for (int j = 0; j < 4; ++j) {
           const int64_t k = k0 + kq * 4 + j;
           if (!EDGE || (row < rows_total && k < k_total))
-            reg[i * 4 + j] = *reinterpret_cast<const uint4*>(p + k * ld + row);
+            reg[i * 4 + j] = *reinterpret_cast<const u32x4*>(p + k * ld + row);
           else
-            reg[i * 4 + j] = make_uint4(0, 0, 0, 0);
+            reg[i * 4 + j] = u32x4{0, 0, 0, 0};
         }
       }
     }
@@ -168,24 +173,20 @@ struct TileLoader {
       const int id = threadIdx.x + i * NT;
       if (!KMAJOR) {
         const int r = id >> 3, kc = id & 7;
-        *reinterpret_cast<uint4*>(tile + r * kLdk + kc * 8) = reg[i];
+        *reinterpret_cast<u32x4*>(tile + r * kLdk + kc * 8) = reg[i];
       } else {
         const int rc = id % (ROWS / 8), kq = id / (ROWS / 8);
-        const uint32_t* w0 = reinterpret_cast<const uint32_t*>(&reg[i * 4 + 0]);
-        const uint32_t* w1 = reinterpret_cast<const uint32_t*>(&reg[i * 4 + 1]);
-        const uint32_t* w2 = reinterpret_cast<const uint32_t*>(&reg[i * 4 + 2]);
-        const uint32_t* w3 = reinterpret_cast<const uint32_t*>(&reg[i * 4 + 3]);
+        const u32x4 w0 = reg[i * 4 + 0], w1 = reg[i * 4 + 1], w2 = reg[i * 4 + 2], w3 = reg[i * 4 + 3];
 #pragma unroll
         for (int e2 = 0; e2 < 4; ++e2) {
           // rows 2*e2 (low halves) and 2*e2+1 (high halves) of the 8-row group; 4 consecutive k each
-          uint2 lo, hi;
+          u32x2 lo, hi;
           lo.x = __builtin_amdgcn_perm(w1[e2], w0[e2], 0x05040100u);
           lo.y = __builtin_amdgcn_perm(w3[e2], w2[e2], 0x05040100u);
           hi.x = __builtin_amdgcn_perm(w1[e2], w0[e2], 0x07060302u);
           hi.y = __builtin_amdgcn_perm(w3[e2], w2[e2], 0x07060302u);
-          // rotate the order of the 8 stores by the lane's row-chunk so that lanes of one wave spread over banks
-          *reinterpret_cast<uint2*>(tile + (rc * 8 + 2 * e2) * kLdk + kq * 4) = lo;
-          *reinterpret_cast<uint2*>(tile + (rc * 8 + 2 * e2 + 1) * kLdk + kq * 4) = hi;
+          *reinterpret_cast<u32x2*>(tile + (rc * 8 + 2 * e2) * kLdk + kq * 4) = lo;
+          *reinterpret_cast<u32x2*>(tile + (rc * 8 + 2 * e2 + 1) * kLdk + kq * 4) = hi;
         }
       }
     }
@@ -198,13 +199,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmBf16Params 
   constexpr int TM = BM / WM, TN = BN / WN;   // wave tile
   constexpr int FM = TM / 32, FN = TN / 32;   // 32x32 MFMA tiles per wave
   static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be a multiple of the MFMA tile");
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16* As[2];
-  bf16* Bs[2];
-  As[0] = reinterpret_cast<bf16*>(smem_raw);
-  As[1] = As[0] + BM * kLdk;
-  Bs[0] = As[1] + BM * kLdk;
-  Bs[1] = Bs[0] + BN * kLdk;
+  // One LDS allocation: [stage 0: A tile, B tile][stage 1: A tile, B tile].  Addresses are formed from the
+  // __shared__ symbol directly so that every access stays an LDS (ds_*) instruction.
+  extern __shared__ __attribute__((aligned(16))) bf16 smem[];
+  constexpr int kStage = (BM + BN) * kLdk;   // elements per stage
+  constexpr int kBoff = BM * kLdk;           // B tile offset inside a stage
 
   int tm, tn;
   tile_of_block(blockIdx.x, p.tiles_m * p.tiles_n, p.tiles_m, p.tiles_n, tm, tn);
@@ -227,18 +226,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmBf16Params 
 
   la.load(p.A, p.lda, m0, 0, p.M, p.K);
   lb.load(p.B, p.ldb, n0, 0, p.N, p.K);
-  la.store(As[0]);
-  lb.store(Bs[0]);
+  la.store(smem);
+  lb.store(smem + kBoff);
   __syncthreads();
 
-  for (int64_t kt = 0; kt < kt_total; ++kt) {
-    const int cur = (int)(kt & 1);
-    if (kt + 1 < kt_total) {
-      la.load(p.A, p.lda, m0, (kt + 1) * kBK, p.M, p.K);
-      lb.load(p.B, p.ldb, n0, (kt + 1) * kBK, p.N, p.K);
-    }
-    const bf16* a_tile = As[cur] + (wm * TM + lrow) * kLdk + lhalf * 8;
-    const bf16* b_tile = Bs[cur] + (wn * TN + lrow) * kLdk + lhalf * 8;
+  auto compute = [&](int cur) {
+    const bf16* a_tile = smem + cur * kStage + (wm * TM + lrow) * kLdk + lhalf * 8;
+    const bf16* b_tile = smem + cur * kStage + kBoff + (wn * TN + lrow) * kLdk + lhalf * 8;
 #pragma unroll
     for (int kk = 0; kk < kBK / 16; ++kk) {
       bf16x8 af[FM], bfr[FN];
@@ -252,12 +246,19 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmBf16Params 
         for (int j = 0; j < FN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < kt_total) {
-      la.store(As[cur ^ 1]);
-      lb.store(Bs[cur ^ 1]);
-    }
+  };
+  // Steady state: fetch tile kt+1 into registers, multiply tile kt out of LDS, park tile kt+1 in the other
+  // LDS stage, one barrier.  The last tile has nothing to fetch and is peeled off.
+  for (int64_t kt = 0; kt + 1 < kt_total; ++kt) {
+    const int cur = (int)(kt & 1);
+    la.load(p.A, p.lda, m0, (kt + 1) * kBK, p.M, p.K);
+    lb.load(p.B, p.ldb, n0, (kt + 1) * kBK, p.N, p.K);
+    compute(cur);
+    la.store(smem + (cur ^ 1) * kStage);
+    lb.store(smem + (cur ^ 1) * kStage + kBoff);
     __syncthreads();
   }
+  compute((int)((kt_total - 1) & 1));
 
   // acc[i][j][r]: m = m0 + wm*TM + 32 i + lane%32,  n = n0 + wn*TN + 32 j + 8 (r/4) + 4 (lane/32) + r%4
 #pragma unroll
@@ -398,7 +399,72 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32Params p) {
 // ======================================================================================================
 // host side
 // ======================================================================================================
+namespace {
+struct ProfiledLaunch {
+  hipEvent_t start, stop;
+  double flops;
+};
+bool g_profile_on = false;
+std::vector<ProfiledLaunch> g_profile;
+std::vector<hipEvent_t> g_profile_free;
+
+hipEvent_t profile_event() {
+  if (!g_profile_free.empty()) {
+    hipEvent_t e = g_profile_free.back();
+    g_profile_free.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  (void)hipEventCreate(&e);
+  return e;
+}
+}  // namespace
+
+void gemm_profile_begin() {
+  for (auto& p : g_profile) {
+    g_profile_free.push_back(p.start);
+    g_profile_free.push_back(p.stop);
+  }
+  g_profile.clear();
+  g_profile_on = true;
+}
+
+hipError_t gemm_profile_end(int64_t* launches, double* total_ms, double* total_flops) {
+  g_profile_on = false;
+  double ms = 0.0, fl = 0.0;
+  hipError_t err = hipSuccess;
+  for (auto& p : g_profile) {
+    hipError_t e = hipEventSynchronize(p.stop);
+    float t = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, p.start, p.stop);
+    if (e != hipSuccess) err = e;
+    ms += t;
+    fl += p.flops;
+    g_profile_free.push_back(p.start);
+    g_profile_free.push_back(p.stop);
+  }
+  if (launches) *launches = (int64_t)g_profile.size();
+  if (total_ms) *total_ms = ms;
+  if (total_flops) *total_flops = fl;
+  g_profile.clear();
+  return err;
+}
+
+static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a);
+
 hipError_t launch_gemm(hipStream_t s, const GemmArgs& a) {
+  const bool timed = g_profile_on && a.dtype == kBF16 && a.M > 0 && a.N > 0;
+  if (!timed) return launch_gemm_impl(s, a);
+  ProfiledLaunch p{profile_event(), profile_event(), 2.0 * (double)a.M * (double)a.N * (double)a.K};
+  if (!p.start || !p.stop) return hipErrorOutOfMemory;
+  hipError_t e = hipEventRecord(p.start, s);
+  if (e == hipSuccess) e = launch_gemm_impl(s, a);
+  if (e == hipSuccess) e = hipEventRecord(p.stop, s);
+  if (e == hipSuccess) g_profile.push_back(p);
+  return e;
+}
+
+static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a) {
   if (!a.A || !a.B || !a.C || a.M < 0 || a.N < 0 || a.K < 0) return hipErrorInvalidValue;
   if (a.epilogue < kEpiStore || a.epilogue > kEpiGeluBwd) return hipErrorInvalidValue;
   if (a.lda < (a.a_kmajor ? a.M : a.K) || a.ldb < (a.b_kmajor ? a.N : a.K) || a.ldc < a.N) return hipErrorInvalidValue;

@@ -64,6 +64,9 @@ hipError_t launch_attention_bwd(hipStream_t s, int dtype, const void* qkv, const
 
 // gemm.hip
 hipError_t launch_gemm(hipStream_t s, const GemmArgs& a);
+// Timing of MFMA GEMM launches with HIP events on the launch stream (measurement aid).
+void gemm_profile_begin();
+hipError_t gemm_profile_end(int64_t* launches, double* total_ms, double* total_flops);
 // One-time per-process set-up of kernel attributes (large dynamic LDS); call once before any capture.
 hipError_t gemm_init();
 

@@ -163,14 +163,30 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_bwd_kernel(const T* __re
   }
 }
 
-// out[c] (=|+=) sum_{p < parts} ws[p*stride + c], parts added in index order.
-__global__ void reduce_parts_kernel(const float* __restrict__ ws, float* __restrict__ out, int parts, int64_t stride,
-                                    int64_t cols, int accumulate) {
-  const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= cols) return;
+// out[c] (=|+=) sum_{p < parts} ws[p*stride + c].  Block = 32 columns x 32 part-groups: group j adds parts
+// j, j+32, ... in order, then the 32 group sums are added in group order: a fixed tree, same bits every run.
+constexpr int kRpCols = 32, kRpGroups = 32;
+__global__ __launch_bounds__(kRpCols * kRpGroups) void reduce_parts_kernel(const float* __restrict__ ws,
+                                                                           float* __restrict__ out, int parts,
+                                                                           int64_t stride, int64_t cols, int accumulate) {
+  __shared__ float part[kRpGroups][kRpCols + 1];
+  const int tx = threadIdx.x % kRpCols, ty = threadIdx.x / kRpCols;
+  const int64_t c = (int64_t)blockIdx.x * kRpCols + tx;
   float s = 0.f;
-  for (int p = 0; p < parts; ++p) s += ws[(size_t)p * stride + c];
-  out[c] = accumulate ? out[c] + s : s;
+  if (c < cols)
+    for (int p = ty; p < parts; p += kRpGroups) s += ws[(size_t)p * stride + c];
+  part[ty][tx] = s;
+  __syncthreads();
+  if (ty == 0 && c < cols) {
+    float t = 0.f;
+#pragma unroll
+    for (int j = 0; j < kRpGroups; ++j) t += part[j][tx];
+    out[c] = accumulate ? out[c] + t : t;
+  }
+}
+static inline void launch_reduce_parts(hipStream_t s, const float* ws, float* out, int parts, int64_t stride, int64_t cols,
+                                       int accumulate) {
+  reduce_parts_kernel<<<(unsigned)((cols + kRpCols - 1) / kRpCols), kRpCols * kRpGroups, 0, s>>>(ws, out, parts, stride, cols, accumulate);
 }
 
 hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const float* x, const float* g,
@@ -194,8 +210,8 @@ hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const 
     if (e != hipSuccess) return e;
   }
   const int parts = N > 0 ? G : 0;
-  reduce_parts_kernel<<<(d + 255) / 256, 256, 0, s>>>(ws, dg, parts, d, d, accumulate);
-  reduce_parts_kernel<<<(d + 255) / 256, 256, 0, s>>>(ws + (size_t)G * d, db, parts, d, d, accumulate);
+  launch_reduce_parts(s, ws, dg, parts, d, d, accumulate);
+  launch_reduce_parts(s, ws + (size_t)G * d, db, parts, d, d, accumulate);
   return hipGetLastError();
 }
 
@@ -244,7 +260,7 @@ hipError_t launch_colsum(hipStream_t s, int dtype, const void* in, float* out, f
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  reduce_parts_kernel<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(ws, out, rows > 0 ? slabs : 0, cols, cols, accumulate);
+  launch_reduce_parts(s, ws, out, rows > 0 ? slabs : 0, cols, cols, accumulate);
   return hipGetLastError();
 }
 

@@ -1009,4 +1009,16 @@ pw_status pw_op_adam(pw_ctx* c, float* w, float* m, float* v, const float* g, vo
   PW_OP(c, launch_adam(c->exec, w, m, v, g, w_bf16, n, lr, beta1, beta2, eps, t, nullptr));
 }
 
+pw_status pw_profile_begin(pw_ctx* c) {
+  if (!c) return PW_ERR_INVALID;
+  gemm_profile_begin();
+  return PW_OK;
+}
+pw_status pw_profile_end(pw_ctx* c, int64_t* launches, double* total_ms, double* total_flops) {
+  if (!c) return PW_ERR_INVALID;
+  hipError_t e = gemm_profile_end(launches, total_ms, total_flops);
+  if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "profile read: %s", hipGetErrorString(e));
+  return PW_OK;
+}
+
 }  // extern "C"

@@ -38,6 +38,9 @@ def rel_l2(got, ref):
 
 
 def ptr(t):
+    """Device address of a torch tensor.  torch fills tensors on its own stream and the library runs on the
+    context's executor stream, so wait for torch first."""
+    torch.cuda.synchronize()
     return 0 if t is None else t.data_ptr()
 
 
