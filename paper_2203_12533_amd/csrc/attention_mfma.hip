@@ -1,17 +1,493 @@
-// bf16 MFMA attention kernels (forward and backward).
+// bf16 MFMA attention: forward, dQ, and dK/dV kernels (v_mfma_f32_32x32x16_bf16, wave64).
+//
+// Register-layout facts everything below rests on (D = A.B, 32x32 output, k = 16 per instruction):
+//   A operand: lane l supplies row l%32, k-slots 8*(l/32) .. +7        (8 bf16)
+//   B operand: lane l supplies column l%32, the same k-slots
+//   D:         lane l holds column l%32; register r holds row 8*(r/4) + 4*(l/32) + r%4
+// The contraction only needs A and B to agree on what k-slot (half h, element e) means.
+//
+// All three kernels put the softmax row index on the D *column*, i.e. on the lane, so that row
+// statistics (max, sum, log-sum-exp, delta) are one value per lane and never need a transpose:
+//   forward / dQ :  S^T[key][query] = K . Q^T      (A = K tile from LDS, B = Q fragments in registers)
+//   dK/dV        :  S[query][key]   = Q . K^T      (A = Q tile from LDS, B = K fragments in registers)
+// The second product consumes P (or dS) straight from the D registers as its B operand.  For that the 16
+// rows a lane holds in registers 0..7 / 8..15 must be the 8 k-slots of its half for the first / second
+// k=16 step.  That is arranged by reading the A tile of the FIRST product with permuted rows: MFMA row i
+// is fed tile row perm(i), perm = [0-3, 8-11, 4-7, 12-15] within every 16, so that register r of half h
+// corresponds to tile row 16*(r/8) + 8*h + r%8.  LDS reads are lane-addressed, so this costs nothing.
+// The second product's A operand needs the tile transposed ([feature][row], rows contiguous); tiles are
+// written to LDS in both forms from one set of global loads (4 rows x 8 features per thread, regrouped
+// with v_perm_b32).
+//
+// Determinism: no atomics.  dQ is accumulated by the block that owns the queries, dK/dV by the block that
+// owns the keys, each over its tiles in ascending order (two kernels, S recomputed in both).
 #include "common.hpp"
 #include "kernels.hpp"
 
 namespace pw {
 
-bool attention_mfma_supported(int T, int hd) {
-  (void)T; (void)hd;
-  return false;
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kNT = 256;           // threads per block: 4 waves
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ int perm_row(int i) {   // [0-3, 8-11, 4-7, 12-15] within each 16
+  const int j = i & 15;
+  const int p = (j & 3) | ((j & 4) << 1) | ((j & 8) >> 1);
+  return (i & ~15) | p;
 }
-hipError_t launch_attention_fwd_mfma(hipStream_t, const void*, void*, float*, int, int, int, int) { return hipErrorNotSupported; }
-hipError_t launch_attention_bwd_mfma(hipStream_t, const void*, const void*, const void*, const float*, float*, void*, int,
-                                     int, int, int) {
-  return hipErrorNotSupported;
+
+// One tile of ROWS rows x HD features, fetched as 4-row x 8-feature pieces.
+template <int ROWS, int HD>
+struct Tile {
+  static constexpr int kPieces = (ROWS / 4) * (HD / 8);
+  static constexpr int CNT = (kPieces + kNT - 1) / kNT;
+  static constexpr int kLdNat = HD + 8;     // [row][feature] layout
+  static constexpr int kLdTr = ROWS + 8;    // [feature][row] layout
+  u32x4 reg[CNT][4];
+
+  // src: element (row 0, feature 0); ld: row stride in elements; rows at or past `limit` read as zero.
+  __device__ __forceinline__ void load(const bf16* __restrict__ src, int64_t ld, int row0, int limit) {
+#pragma unroll
+    for (int i = 0; i < CNT; ++i) {
+      const int p = threadIdx.x + i * kNT;
+      const int fc = p % (HD / 8), rq = p / (HD / 8);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int row = row0 + rq * 4 + j;
+        if ((kPieces % kNT == 0 || p < kPieces) && row < limit)
+          reg[i][j] = *reinterpret_cast<const u32x4*>(src + (int64_t)row * ld + fc * 8);
+        else
+          reg[i][j] = u32x4{0, 0, 0, 0};
+      }
+    }
+  }
+  __device__ __forceinline__ void store_nat(bf16* __restrict__ lds) const {
+#pragma unroll
+    for (int i = 0; i < CNT; ++i) {
+      const int p = threadIdx.x + i * kNT;
+      if (kPieces % kNT != 0 && p >= kPieces) continue;
+      const int fc = p % (HD / 8), rq = p / (HD / 8);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4*>(lds + (rq * 4 + j) * kLdNat + fc * 8) = reg[i][j];
+    }
+  }
+  __device__ __forceinline__ void store_tr(bf16* __restrict__ lds) const {
+#pragma unroll
+    for (int i = 0; i < CNT; ++i) {
+      const int p = threadIdx.x + i * kNT;
+      if (kPieces % kNT != 0 && p >= kPieces) continue;
+      const int fc = p % (HD / 8), rq = p / (HD / 8);
+      const u32x4 w0 = reg[i][0], w1 = reg[i][1], w2 = reg[i][2], w3 = reg[i][3];
+#pragma unroll
+      for (int e2 = 0; e2 < 4; ++e2) {
+        u32x2 lo, hi;   // features 2*e2 and 2*e2+1 of the piece, 4 consecutive rows each
+        lo.x = __builtin_amdgcn_perm(w1[e2], w0[e2], 0x05040100u);
+        lo.y = __builtin_amdgcn_perm(w3[e2], w2[e2], 0x05040100u);
+        hi.x = __builtin_amdgcn_perm(w1[e2], w0[e2], 0x07060302u);
+        hi.y = __builtin_amdgcn_perm(w3[e2], w2[e2], 0x07060302u);
+        *reinterpret_cast<u32x2*>(lds + (fc * 8 + 2 * e2) * kLdTr + rq * 4) = lo;
+        *reinterpret_cast<u32x2*>(lds + (fc * 8 + 2 * e2 + 1) * kLdTr + rq * 4) = hi;
+      }
+    }
+  }
+};
+
+// Fragments of 32 rows x HD features held in registers as the B operand of a first product:
+// lane l holds row (row0 + l%32), features kk*16 + 8*(l/32) .. +7 for every kk.  Rows >= limit read as zero.
+template <int HD>
+__device__ __forceinline__ void load_row_frags(const bf16* __restrict__ src, int64_t ld, int row0, int limit, bf16x8* frag) {
+  const int lane = threadIdx.x & 63;
+  const int row = row0 + (lane & 31);
+  const bf16* p = src + (int64_t)row * ld + (lane >> 5) * 8;
+#pragma unroll
+  for (int kk = 0; kk < HD / 16; ++kk) {
+    if (row < limit) {
+      frag[kk] = *reinterpret_cast<const bf16x8*>(p + kk * 16);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) frag[kk][e] = (bf16)0.f;
+    }
+  }
+}
+
+// 32x32 block of a first product: A rows from a natural-layout LDS tile (permuted), B from register fragments.
+template <int HD, int LDN>
+__device__ __forceinline__ f32x16 first_product(const bf16* __restrict__ tile, int row_base, const bf16x8* bfrag) {
+  const int lane = threadIdx.x & 63;
+  const bf16* a = tile + (row_base + perm_row(lane & 31)) * LDN + (lane >> 5) * 8;
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < HD / 16; ++kk)
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(a + kk * 16), bfrag[kk], acc, 0, 0, 0);
+  return acc;
+}
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16& v, int first) {
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (bf16)v[first + e];
+  return o;
+}
+
+// acc[cb] += T^T[feature block cb][rows kb*32 + 16 b ..] . frag   for a transposed LDS tile (ld = LDT)
+template <int HD, int LDT>
+__device__ __forceinline__ void second_product(const bf16* __restrict__ tile_tr, int row_base, const bf16x8& frag, f32x16* acc) {
+  const int lane = threadIdx.x & 63;
+  const bf16* a = tile_tr + (lane & 31) * LDT + row_base + (lane >> 5) * 8;
+#pragma unroll
+  for (int cb = 0; cb < HD / 32; ++cb)
+    acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(a + cb * 32 * LDT), frag, acc[cb], 0, 0, 0);
+}
+
+// Tile-local row index that register r of this lane's D column stands for (see file header).
+__device__ __forceinline__ int reg_row(int r, int half) { return 16 * (r >> 3) + 8 * half + (r & 7); }
+
+// Writes acc (feature-major: register r of block cb = feature cb*32 + 8*(r/4) + 4*half + r%4) for this lane's
+// row to dst (row pointer, feature 0), scaled.
+template <int HD>
+__device__ __forceinline__ void store_row(bf16* __restrict__ dst, const f32x16* acc, float scale) {
+  const int half = (threadIdx.x & 63) >> 5;
+#pragma unroll
+  for (int cb = 0; cb < HD / 32; ++cb)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      bf16x4 o = {(bf16)(acc[cb][q * 4] * scale), (bf16)(acc[cb][q * 4 + 1] * scale), (bf16)(acc[cb][q * 4 + 2] * scale),
+                  (bf16)(acc[cb][q * 4 + 3] * scale)};
+      *reinterpret_cast<bf16x4*>(dst + cb * 32 + q * 8 + half * 4) = o;
+    }
+}
+
+// ===================================================================================================
+// forward: block = 128 queries of one (batch, head); wave = 32 queries; key/value tiles of 64
+// ===================================================================================================
+template <int HD>
+__global__ __launch_bounds__(kNT) void attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o,
+                                                       float* __restrict__ lse, int T, int H) {
+  constexpr int BKV = 64;
+  using KT = Tile<BKV, HD>;
+  __shared__ __attribute__((aligned(16))) bf16 Ks[BKV * KT::kLdNat];
+  __shared__ __attribute__((aligned(16))) bf16 Vt[HD * KT::kLdTr];
+  const int d = H * HD;
+  const int64_t ld = 3 * (int64_t)d;
+  const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
+  const int qblk = gridDim.x - 1 - blockIdx.x;          // longest blocks first
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
+  const int q0 = qblk * 128 + wave * 32;
+  const int query = q0 + (lane & 31);
+  const bf16* qbase = qkv + (int64_t)b * T * ld + h * HD;
+  const bf16* kbase = qbase + d;
+  const bf16* vbase = qbase + 2 * d;
+  const float c2 = kLog2e / sqrtf((float)HD);
+
+  bf16x8 qf[HD / 16];
+  load_row_frags<HD>(qbase, ld, q0, T, qf);
+  f32x16 acc[HD / 32];
+#pragma unroll
+  for (int cb = 0; cb < HD / 32; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  const int last_q = min(T, (qblk + 1) * 128) - 1;
+  const int n_tiles = last_q / BKV + 1;
+  KT kt, vt;
+  kt.load(kbase, ld, 0, T);
+  vt.load(vbase, ld, 0, T);
+  for (int t = 0; t < n_tiles; ++t) {
+    const int j0 = t * BKV;
+    __syncthreads();            // everyone is done with the previous tile
+    kt.store_nat(Ks);
+    vt.store_tr(Vt);
+    __syncthreads();
+    if (t + 1 < n_tiles) {
+      kt.load(kbase, ld, j0 + BKV, T);
+      vt.load(vbase, ld, j0 + BKV, T);
+    }
+    if (j0 > q0 + 31) continue;   // every key of the tile lies in this wave's future
+    f32x16 s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) s[kb] = first_product<HD, KT::kLdNat>(Ks, kb * 32, qf);
+    const bool diag = j0 + BKV - 1 > q0;
+    float mx = m;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v = s[kb][r] * c2;
+        if (diag && j0 + kb * 32 + reg_row(r, half) > query) v = -INFINITY;
+        s[kb][r] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float alpha = exp2f(m - mx);      // m = -inf on the first tile: exp2(-inf) = 0
+    m = mx;
+    float sum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = exp2f(s[kb][r] - mx);
+        s[kb][r] = p;
+        sum += p;
+      }
+    l = l * alpha + sum;
+#pragma unroll
+    for (int cb = 0; cb < HD / 32; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[cb][r] *= alpha;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) second_product<HD, KT::kLdTr>(Vt, kb * 32 + b2 * 16, pack8(s[kb], b2 * 8), acc);
+  }
+  l += __shfl_xor(l, 32, 64);
+  if (query < T) {
+    store_row<HD>(o + ((int64_t)b * T + query) * d + h * HD, acc, 1.f / l);
+    if (half == 0) lse[(int64_t)bh * T + query] = (m + log2f(l)) * kLn2;
+  }
+}
+
+// ===================================================================================================
+// dQ: same tiling as the forward.  dQ_i = scale * sum_j dS_ij K_j, dS = P (dP - delta)
+// ===================================================================================================
+template <int HD>
+__global__ __launch_bounds__(kNT) void attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
+                                                      const float* __restrict__ lse, const float* __restrict__ delta,
+                                                      bf16* __restrict__ dqkv, int T, int H) {
+  constexpr int BKV = 64;
+  using KT = Tile<BKV, HD>;
+  __shared__ __attribute__((aligned(16))) bf16 Ks[BKV * KT::kLdNat];
+  __shared__ __attribute__((aligned(16))) bf16 Vs[BKV * KT::kLdNat];
+  __shared__ __attribute__((aligned(16))) bf16 Kt[HD * KT::kLdTr];
+  const int d = H * HD;
+  const int64_t ld = 3 * (int64_t)d;
+  const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
+  const int qblk = gridDim.x - 1 - blockIdx.x;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
+  const int q0 = qblk * 128 + wave * 32;
+  const int query = q0 + (lane & 31);
+  const bf16* qbase = qkv + (int64_t)b * T * ld + h * HD;
+  const bf16* kbase = qbase + d;
+  const bf16* vbase = qbase + 2 * d;
+  const float scale = 1.f / sqrtf((float)HD);
+  const float c2 = kLog2e * scale;
+
+  bf16x8 qf[HD / 16], gf[HD / 16];
+  load_row_frags<HD>(qbase, ld, q0, T, qf);
+  load_row_frags<HD>(dout + (int64_t)b * T * d + h * HD, d, q0, T, gf);
+  const float lse2 = query < T ? lse[(int64_t)bh * T + query] * kLog2e : INFINITY;   // +inf: P = 0 for rows past the end
+  const float dl = query < T ? delta[(int64_t)bh * T + query] : 0.f;
+  f32x16 acc[HD / 32];
+#pragma unroll
+  for (int cb = 0; cb < HD / 32; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+
+  const int last_q = min(T, (qblk + 1) * 128) - 1;
+  const int n_tiles = last_q / BKV + 1;
+  KT kt, vt;
+  kt.load(kbase, ld, 0, T);
+  vt.load(vbase, ld, 0, T);
+  for (int t = 0; t < n_tiles; ++t) {
+    const int j0 = t * BKV;
+    __syncthreads();
+    kt.store_nat(Ks);
+    kt.store_tr(Kt);
+    vt.store_nat(Vs);
+    __syncthreads();
+    if (t + 1 < n_tiles) {
+      kt.load(kbase, ld, j0 + BKV, T);
+      vt.load(vbase, ld, j0 + BKV, T);
+    }
+    if (j0 > q0 + 31) continue;
+    const bool diag = j0 + BKV - 1 > q0;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      f32x16 s = first_product<HD, KT::kLdNat>(Ks, kb * 32, qf);      // S^T
+      f32x16 dp = first_product<HD, KT::kLdNat>(Vs, kb * 32, gf);     // dP^T = V . dO^T
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float p = exp2f(s[r] * c2 - lse2);
+        if (diag && j0 + kb * 32 + reg_row(r, half) > query) p = 0.f;
+        s[r] = p * (dp[r] - dl);
+      }
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) second_product<HD, KT::kLdTr>(Kt, kb * 32 + b2 * 16, pack8(s, b2 * 8), acc);
+    }
+  }
+  if (query < T) store_row<HD>(dqkv + ((int64_t)b * T + query) * ld + h * HD, acc, scale);
+}
+
+// ===================================================================================================
+// dK, dV: block = 128 keys of one (batch, head); wave = 32 keys; query tiles of 32
+// ===================================================================================================
+template <int HD>
+__global__ __launch_bounds__(kNT) void attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
+                                                       const float* __restrict__ lse, const float* __restrict__ delta,
+                                                       bf16* __restrict__ dqkv, int T, int H) {
+  constexpr int BQ = 32;
+  using QT = Tile<BQ, HD>;
+  __shared__ __attribute__((aligned(16))) bf16 Qs[BQ * QT::kLdNat];
+  __shared__ __attribute__((aligned(16))) bf16 Gs[BQ * QT::kLdNat];
+  __shared__ __attribute__((aligned(16))) bf16 Qt[HD * QT::kLdTr];
+  __shared__ __attribute__((aligned(16))) bf16 Gt[HD * QT::kLdTr];
+  __shared__ __attribute__((aligned(16))) float Ls[BQ];
+  __shared__ __attribute__((aligned(16))) float Ds[BQ];
+  const int d = H * HD;
+  const int64_t ld = 3 * (int64_t)d;
+  const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
+  const int kblk = blockIdx.x;                          // first key blocks see the most queries: they come first
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
+  const int k0 = kblk * 128 + wave * 32;
+  const int key = k0 + (lane & 31);
+  const bf16* qbase = qkv + (int64_t)b * T * ld + h * HD;
+  const bf16* gbase = dout + (int64_t)b * T * d + h * HD;
+  const float scale = 1.f / sqrtf((float)HD);
+  const float c2 = kLog2e * scale;
+
+  bf16x8 kf[HD / 16], vf[HD / 16];
+  load_row_frags<HD>(qbase + d, ld, k0, T, kf);
+  load_row_frags<HD>(qbase + 2 * d, ld, k0, T, vf);
+  f32x16 dk[HD / 32], dv[HD / 32];
+#pragma unroll
+  for (int cb = 0; cb < HD / 32; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      dk[cb][r] = 0.f;
+      dv[cb][r] = 0.f;
+    }
+
+  const int first_tile = (kblk * 128) / BQ;
+  const int n_tiles = (T + BQ - 1) / BQ;
+  QT qt, gt;
+  float l_next = 0.f, d_next = 0.f;
+  auto fetch = [&](int i0) {
+    qt.load(qbase, ld, i0, T);
+    gt.load(gbase, d, i0, T);
+    if (threadIdx.x < BQ) {
+      const int i = i0 + threadIdx.x;
+      l_next = i < T ? lse[(int64_t)bh * T + i] * kLog2e : INFINITY;
+      d_next = i < T ? delta[(int64_t)bh * T + i] : 0.f;
+    }
+  };
+  fetch(first_tile * BQ);
+  for (int t = first_tile; t < n_tiles; ++t) {
+    const int i0 = t * BQ;
+    __syncthreads();
+    qt.store_nat(Qs);
+    qt.store_tr(Qt);
+    gt.store_nat(Gs);
+    gt.store_tr(Gt);
+    if (threadIdx.x < BQ) {
+      Ls[threadIdx.x] = l_next;
+      Ds[threadIdx.x] = d_next;
+    }
+    __syncthreads();
+    if (t + 1 < n_tiles) fetch(i0 + BQ);
+    if (i0 + BQ - 1 < k0) continue;        // every query of the tile precedes this wave's keys
+    f32x16 s = first_product<HD, QT::kLdNat>(Qs, 0, kf);       // S[query][key]
+    f32x16 dp = first_product<HD, QT::kLdNat>(Gs, 0, vf);      // dP = dO . V^T
+    // statistics of the 16 queries this lane's registers stand for: rows 8h..8h+7 and 16+8h..16+8h+7
+    float lq[16], dq[16];
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+      for (int v4 = 0; v4 < 2; ++v4) {
+        const float4 a = *reinterpret_cast<const float4*>(&Ls[16 * g + 8 * half + 4 * v4]);
+        const float4 c = *reinterpret_cast<const float4*>(&Ds[16 * g + 8 * half + 4 * v4]);
+        lq[8 * g + 4 * v4] = a.x; lq[8 * g + 4 * v4 + 1] = a.y; lq[8 * g + 4 * v4 + 2] = a.z; lq[8 * g + 4 * v4 + 3] = a.w;
+        dq[8 * g + 4 * v4] = c.x; dq[8 * g + 4 * v4 + 1] = c.y; dq[8 * g + 4 * v4 + 2] = c.z; dq[8 * g + 4 * v4 + 3] = c.w;
+      }
+    const bool diag = i0 < k0 + 31;
+    f32x16 ds;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float p = exp2f(s[r] * c2 - lq[r]);
+      if (diag && key > i0 + reg_row(r, half)) p = 0.f;
+      s[r] = p;
+      ds[r] = p * (dp[r] - dq[r]);
+    }
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2) {
+      second_product<HD, QT::kLdTr>(Gt, b2 * 16, pack8(s, b2 * 8), dv);    // dV^T += dO^T . P
+      second_product<HD, QT::kLdTr>(Qt, b2 * 16, pack8(ds, b2 * 8), dk);   // dK^T += Q^T . dS
+    }
+  }
+  if (key < T) {
+    bf16* row = dqkv + ((int64_t)b * T + key) * ld + h * HD;
+    store_row<HD>(row + d, dk, scale);
+    store_row<HD>(row + 2 * d, dv, 1.f);
+  }
+}
+
+// delta[b,h,i] = sum_c dO[i,c] O[i,c].  16 lanes share one (token, head) row of 128 (8 lanes for 64).
+template <int HD>
+__global__ void attn_delta_kernel(const bf16* __restrict__ o, const bf16* __restrict__ dout, float* __restrict__ delta,
+                                  int T, int H, int64_t rows) {
+  constexpr int LPR = HD / 8;                       // lanes per row
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t row = gid / LPR;                    // (token n, head h) flattened: n*H + h
+  const int part = (int)(gid % LPR);
+  float s = 0.f;
+  if (row < rows) {
+    const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + row * HD + part * 8);
+    const bf16x8 g = *reinterpret_cast<const bf16x8*>(dout + row * HD + part * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += (float)a[e] * (float)g[e];
+  }
+#pragma unroll
+  for (int off = LPR / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+  if (row < rows && part == 0) {
+    const int64_t n = row / H;
+    const int hh = (int)(row - n * H);
+    const int64_t bb = n / T, t = n - bb * T;
+    delta[(bb * H + hh) * T + t] = s;
+  }
+}
+
+}  // namespace
+
+bool attention_mfma_supported(int T, int hd) { return T >= 1 && (hd == 64 || hd == 128); }
+
+hipError_t launch_attention_fwd_mfma(hipStream_t s, const void* qkv, void* o, float* lse, int B, int T, int H, int hd) {
+  if (!qkv || !o || !lse || B <= 0 || T <= 0 || H <= 0 || (int64_t)B * H > 65535) return hipErrorInvalidValue;
+  if (((uintptr_t)qkv | (uintptr_t)o) & 15) return hipErrorInvalidValue;
+  dim3 grid((T + 127) / 128, B * H);
+  if (hd == 128)
+    attn_fwd_kernel<128><<<grid, kNT, 0, s>>>((const bf16*)qkv, (bf16*)o, lse, T, H);
+  else if (hd == 64)
+    attn_fwd_kernel<64><<<grid, kNT, 0, s>>>((const bf16*)qkv, (bf16*)o, lse, T, H);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_bwd_mfma(hipStream_t s, const void* qkv, const void* o, const void* dout, const float* lse,
+                                     float* delta, void* dqkv, int B, int T, int H, int hd) {
+  if (!qkv || !o || !dout || !lse || !delta || !dqkv || B <= 0 || T <= 0 || H <= 0 || (int64_t)B * H > 65535)
+    return hipErrorInvalidValue;
+  if (((uintptr_t)qkv | (uintptr_t)o | (uintptr_t)dout | (uintptr_t)dqkv) & 15) return hipErrorInvalidValue;
+  if (hd != 64 && hd != 128) return hipErrorInvalidValue;
+  const int64_t rows = (int64_t)B * T * H;
+  const int64_t threads = rows * (hd / 8);
+  dim3 grid((T + 127) / 128, B * H);
+  if (hd == 128) {
+    attn_delta_kernel<128><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>((const bf16*)o, (const bf16*)dout, delta, T, H, rows);
+    attn_dq_kernel<128><<<grid, kNT, 0, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
+    attn_dkv_kernel<128><<<grid, kNT, 0, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
+  } else {
+    attn_delta_kernel<64><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>((const bf16*)o, (const bf16*)dout, delta, T, H, rows);
+    attn_dq_kernel<64><<<grid, kNT, 0, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
+    attn_dkv_kernel<64><<<grid, kNT, 0, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
+  }
+  return hipGetLastError();
 }
 
 }  // namespace pw
