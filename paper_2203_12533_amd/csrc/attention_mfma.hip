@@ -50,12 +50,20 @@ struct Tile {
   static constexpr int kLdTr = ROWS + 8;    // [feature][row] layout
   u32x4 reg[CNT][4];
 
+  // Which 8-feature chunk (fc) and which 4-row group (rq) piece p covers.  A 32-lane half-wave gets two
+  // adjacent feature chunks x the row groups: its 8-byte transposed LDS stores then fall on distinct banks
+  // (the bank depends on fc only through its parity).
+  static constexpr int kRqBits = ROWS == 64 ? 4 : 3;
+  static_assert(ROWS == 64 || ROWS == 32, "tile heights used by the kernels");
+  static __device__ __forceinline__ int piece_fc(int p) { return (p & 1) | ((p >> (1 + kRqBits)) << 1); }
+  static __device__ __forceinline__ int piece_rq(int p) { return (p >> 1) & (ROWS / 4 - 1); }
+
   // src: element (row 0, feature 0); ld: row stride in elements; rows at or past `limit` read as zero.
   __device__ __forceinline__ void load(const bf16* __restrict__ src, int64_t ld, int row0, int limit) {
 #pragma unroll
     for (int i = 0; i < CNT; ++i) {
       const int p = threadIdx.x + i * kNT;
-      const int fc = p % (HD / 8), rq = p / (HD / 8);
+      const int fc = piece_fc(p), rq = piece_rq(p);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int row = row0 + rq * 4 + j;
@@ -71,7 +79,7 @@ struct Tile {
     for (int i = 0; i < CNT; ++i) {
       const int p = threadIdx.x + i * kNT;
       if (kPieces % kNT != 0 && p >= kPieces) continue;
-      const int fc = p % (HD / 8), rq = p / (HD / 8);
+      const int fc = piece_fc(p), rq = piece_rq(p);
 #pragma unroll
       for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4*>(lds + (rq * 4 + j) * kLdNat + fc * 8) = reg[i][j];
     }
@@ -81,7 +89,7 @@ struct Tile {
     for (int i = 0; i < CNT; ++i) {
       const int p = threadIdx.x + i * kNT;
       if (kPieces % kNT != 0 && p >= kPieces) continue;
-      const int fc = p % (HD / 8), rq = p / (HD / 8);
+      const int fc = piece_fc(p), rq = piece_rq(p);
       const u32x4 w0 = reg[i][0], w1 = reg[i][1], w2 = reg[i][2], w3 = reg[i][3];
 #pragma unroll
       for (int e2 = 0; e2 < 4; ++e2) {

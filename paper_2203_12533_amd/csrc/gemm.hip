@@ -137,6 +137,13 @@ struct TileLoader {
   static_assert(kPieces % NT == 0, "tile does not divide over the workgroup");
   u32x4 reg[KMAJOR ? CNT * 4 : CNT];
 
+  // k-major pieces: which 8-row chunk (rc) and which 4-k group (kq) piece `id` covers.  The 8-byte LDS
+  // stores of one 32-lane half-wave land on bank (32*(rc&1) + 2*kq + const) mod 64, so a half-wave is given
+  // 2 adjacent row chunks x all 16 k-groups: 32 distinct 8-byte slots, no bank conflict.  (The price is
+  // that a half-wave's global loads cover 32 bytes x 16 rows instead of whole 128-byte lines.)
+  static __device__ __forceinline__ int piece_rc(int id) { return (id & 1) | ((id >> 5) << 1); }
+  static __device__ __forceinline__ int piece_kq(int id) { return (id >> 1) & 15; }
+
   // p: operand base; ld: leading dimension; row0: first row (m or n) of the tile; k0: first k;
   // rows_total / k_total: operand extents (used only when EDGE).
   __device__ __forceinline__ void load(const bf16* __restrict__ p, int64_t ld, int64_t row0, int64_t k0,
@@ -152,7 +159,7 @@ struct TileLoader {
         else
           reg[i] = u32x4{0, 0, 0, 0};
       } else {
-        const int rc = id % (ROWS / 8), kq = id / (ROWS / 8);
+        const int rc = piece_rc(id), kq = piece_kq(id);
         const int64_t row = row0 + rc * 8;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -175,7 +182,7 @@ struct TileLoader {
         const int r = id >> 3, kc = id & 7;
         *reinterpret_cast<u32x4*>(tile + r * kLdk + kc * 8) = reg[i];
       } else {
-        const int rc = id % (ROWS / 8), kq = id / (ROWS / 8);
+        const int rc = piece_rc(id), kq = piece_kq(id);
         const u32x4 w0 = reg[i * 4 + 0], w1 = reg[i * 4 + 1], w2 = reg[i * 4 + 2], w3 = reg[i * 4 + 3];
 #pragma unroll
         for (int e2 = 0; e2 < 4; ++e2) {
