@@ -55,14 +55,20 @@ __device__ __forceinline__ float block_max(float v, float* red) {
   return t;
 }
 
+// tanh(x) = 1 - 2 / (exp(2x) + 1) with the hardware exp2 and reciprocal: a handful of instructions, relative
+// error ~1e-6, exact limits at +-inf.
+__device__ __forceinline__ float fast_tanh(float x) {
+  const float e = __builtin_amdgcn_exp2f(x * 2.8853900817779268f);   // exp(2x)
+  return 1.f - 2.f * __builtin_amdgcn_rcpf(e + 1.f);
+}
 // tanh-form GELU and its derivative, fp32.
 __device__ __forceinline__ float gelu_f(float u) {
   const float c = 0.7978845608028654f;   // sqrt(2/pi)
-  return 0.5f * u * (1.f + tanhf(c * (u + 0.044715f * u * u * u)));
+  return 0.5f * u * (1.f + fast_tanh(c * (u + 0.044715f * u * u * u)));
 }
 __device__ __forceinline__ float gelu_grad_f(float u) {
   const float c = 0.7978845608028654f;
-  const float t = tanhf(c * (u + 0.044715f * u * u * u));
+  const float t = fast_tanh(c * (u + 0.044715f * u * u * u));
   return 0.5f * (1.f + t) + 0.5f * u * (1.f - t * t) * c * (1.f + 3.f * 0.044715f * u * u);
 }
 

@@ -95,6 +95,49 @@ __device__ __forceinline__ void epilogue1(const EpiParams& e, int64_t m, int64_t
   }
 }
 
+// Epilogue on 8 consecutive columns n0..n0+7 of row m (bf16-activation kernels; all accesses 16-byte vectors).
+__device__ __forceinline__ void epilogue8(const EpiParams& e, int64_t m, int64_t n0, float* v) {
+  const int64_t off = m * e.ldc + n0;
+  if ((e.mode == kEpiBias || e.mode == kEpiBiasResidual || e.mode == kEpiBiasGelu) && e.bias) {
+    const float4 b0 = *reinterpret_cast<const float4*>(e.bias + n0), b1 = *reinterpret_cast<const float4*>(e.bias + n0 + 4);
+    v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w; v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
+  }
+  if (e.mode == kEpiBiasResidual) {
+    const float* r = reinterpret_cast<const float*>(e.aux) + off;
+    const float4 r0 = *reinterpret_cast<const float4*>(r), r1 = *reinterpret_cast<const float4*>(r + 4);
+    v[0] += r0.x; v[1] += r0.y; v[2] += r0.z; v[3] += r0.w; v[4] += r1.x; v[5] += r1.y; v[6] += r1.z; v[7] += r1.w;
+  } else if (e.mode == kEpiGeluBwd) {
+    const bf16x8 u = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16*>(e.aux) + off);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] *= gelu_grad_f((float)u[i]);
+  }
+  if (e.out_bf16) {
+    bf16x8 o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (bf16)v[i];
+    *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(e.C) + off) = o;
+    if (e.mode == kEpiBiasGelu) {
+      bf16x8 h;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) h[i] = (bf16)gelu_f(v[i]);
+      *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(e.C2) + off) = h;
+    }
+  } else {
+    float* c = reinterpret_cast<float*>(e.C) + off;
+    if (e.accumulate) {
+      const float4 o0 = *reinterpret_cast<const float4*>(c), o1 = *reinterpret_cast<const float4*>(c + 4);
+      v[0] += o0.x; v[1] += o0.y; v[2] += o0.z; v[3] += o0.w; v[4] += o1.x; v[5] += o1.y; v[6] += o1.z; v[7] += o1.w;
+    }
+    *reinterpret_cast<float4*>(c) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(c + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    if (e.mode == kEpiBiasGelu) {
+      float* c2 = reinterpret_cast<float*>(e.C2) + off;
+      *reinterpret_cast<float4*>(c2) = make_float4(gelu_f(v[0]), gelu_f(v[1]), gelu_f(v[2]), gelu_f(v[3]));
+      *reinterpret_cast<float4*>(c2 + 4) = make_float4(gelu_f(v[4]), gelu_f(v[5]), gelu_f(v[6]), gelu_f(v[7]));
+    }
+  }
+}
+
 // Workgroup id -> output tile, XCD-aware (see file header).
 __device__ __forceinline__ void tile_of_block(int pid, int nblk, int tiles_m, int tiles_n, int& tm, int& tn) {
   constexpr int kXcd = 8, kGroup = 8;
@@ -267,24 +310,41 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmBf16Params 
   }
   compute((int)((kt_total - 1) & 1));
 
-  // acc[i][j][r]: m = m0 + wm*TM + 32 i + lane%32,  n = n0 + wn*TN + 32 j + 8 (r/4) + 4 (lane/32) + r%4
+  // Epilogue.  acc[i][j][r] is element m = 32 i + lane%32, n = 32 j + 8 (r/4) + 4 (lane/32) + r%4 of the wave
+  // tile: a lane owns one row fragment of 4 columns, so storing straight from here would scatter 8-byte
+  // pieces over 32 rows per instruction.  Instead each wave parks one 32 x 64 block at a time in its own
+  // slice of LDS (the operand tiles are dead by now) and reads it back row-wise: 8 lanes cover the 64
+  // columns of a row with 8 consecutive values each, so every global access of the epilogue (output,
+  // residual, saved pre-activation) is a 16-byte vector and every row segment a full 128-byte line or more.
+  static_assert(TN == 64, "epilogue staging assumes a 64-column wave tile");
+  constexpr int kLdS = 64 + 4;   // floats; 272-byte rows keep the 16-byte LDS accesses conflict-free
+  __syncthreads();
+  float* stage = reinterpret_cast<float*>(smem) + wave * (32 * kLdS);
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
-    const int64_t m = m0 + wm * TM + i * 32 + lrow;
-    if (EDGE && m >= p.M) continue;
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int64_t n = n0 + wn * TN + j * 32 + q * 8 + lhalf * 4;
-        if (!EDGE || n + 3 < p.N) {
-          epilogue4<true>(p.epi, m, n, acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
-        } else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (n + e < p.N) epilogue1<true>(p.epi, m, n + e, acc[i][j][q * 4 + e]);
-        }
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4*>(stage + lrow * kLdS + j * 32 + q * 8 + lhalf * 4) =
+            make_float4(acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+    __syncthreads();
+#pragma unroll 1
+    for (int it = 0; it < 4; ++it) {
+      const int row = it * 8 + (lane >> 3), c8 = lane & 7;
+      const float4 v0 = *reinterpret_cast<const float4*>(stage + row * kLdS + c8 * 8);
+      const float4 v1 = *reinterpret_cast<const float4*>(stage + row * kLdS + c8 * 8 + 4);
+      float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+      const int64_t m = m0 + wm * TM + i * 32 + row;
+      const int64_t n = n0 + wn * TN + c8 * 8;
+      if (!EDGE || (m < p.M && n + 7 < p.N)) {
+        epilogue8(p.epi, m, n, v);
+      } else if (m < p.M) {
+        for (int e = 0; e < 8; ++e)
+          if (n + e < p.N) epilogue1<true>(p.epi, m, n + e, v[e]);
       }
+    }
+    __syncthreads();
   }
 }
 
@@ -515,7 +575,7 @@ static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a) {
   if ((a.a_kmajor && a.M % 8) || (a.b_kmajor && a.N % 8)) return hipErrorInvalidValue;
   if (((uintptr_t)a.A | (uintptr_t)a.B) & 15) return hipErrorInvalidValue;
   if (((uintptr_t)a.C | (uintptr_t)a.C2 | (uintptr_t)a.aux | (uintptr_t)a.bias) & 15) return hipErrorInvalidValue;
-  if (a.ldc % 4) return hipErrorInvalidValue;
+  if (a.ldc % 8) return hipErrorInvalidValue;
 
   GemmBf16Params p;
   p.A = (const bf16*)a.A;
