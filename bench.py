@@ -86,6 +86,8 @@ def dispatch_bench(ctx, pwb, I, reps: int = 200):
 
 
 def cpu_baseline(cfg, pwb, budget_tokens: int = 128):
+    if not cfg.has_head:
+        return None
     """The CPU oracle, as it stands, on a bounded sample: same layer / head shapes, one layer, one
     sequence of `budget_tokens` tokens.  Extrapolated to the full workload by model-FLOP ratio."""
     from oracle import oracle
@@ -125,18 +127,47 @@ def main():
     ctx = pwb.Context(0)
     model = ctx.model(cfg)
     fill_model_on_device(model, cfg, torch, seed=1234)
-    tok = torch.from_numpy(I.lm_tokens(cfg, seed=1234)).cuda()
-    f_tok = ctx.future_wrap_device(tok.data_ptr(), pwb.PW_I32, tuple(tok.shape))
-    step = model.compile_train_step()
+    if cfg.has_head:
+        tok = torch.from_numpy(I.lm_tokens(cfg, seed=1234)).cuda()
+        torch.cuda.synchronize()
+        f_tok = ctx.future_wrap_device(tok.data_ptr(), pwb.PW_I32, tuple(tok.shape))
+        step = model.compile_train_step()
 
-    def one_step():
-        f = ctx.train_step(step, f_tok)
-        return f
+        def one_step():
+            return ctx.train_step(step, f_tok)
+    else:
+        # One pipeline stage under the GPipe-like schedule: forward for every micro-batch, then backward in
+        # reverse order with weight gradients summed, then Adam.  The 2 x n_microbatch calls are one chain of
+        # compiled functions consuming futures; a step returns the future of the last input gradient.
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(4321)
+        nmb, shape = cfg.n_microbatch, (cfg.n_tokens, cfg.d_model)
+        xs = [torch.randn(shape, device="cuda", generator=gen).to(torch.bfloat16).float() for _ in range(nmb)]
+        dys = [torch.randn(shape, device="cuda", generator=gen).to(torch.bfloat16).float() for _ in range(nmb)]
+        torch.cuda.synchronize()
+        fx = [ctx.future_wrap_device(t.data_ptr(), pwb.PW_F32, shape) for t in xs]
+        fdy = [ctx.future_wrap_device(t.data_ptr(), pwb.PW_F32, shape) for t in dys]
+        fwd = [model.compile_stage(pwb.PW_FN_STAGE_FWD, mb) for mb in range(nmb)]
+        bwd = [model.compile_stage(pwb.PW_FN_STAGE_BWD, mb) for mb in range(nmb)]
+
+        def one_step():
+            model.zero_grads()
+            last = None
+            for mb in range(nmb):
+                (fy,) = ctx.run_fn(fwd[mb], [fx[mb]])
+                ctx.future_release(fy)
+            for mb in reversed(range(nmb)):
+                (fdx,) = ctx.run_fn(bwd[mb], [fdy[mb]])
+                if last is not None:
+                    ctx.future_release(last)
+                last = fdx
+            model.apply_optimizer()
+            return last
 
     losses = []
     for _ in range(args.warmup):
         f = one_step()
-        losses.append(float(ctx.await_(f)[0]))
+        losses.append(float(ctx.await_(f).reshape(-1)[0]))
         ctx.future_release(f)
     ctx.synchronize()
     torch.cuda.synchronize()
@@ -148,14 +179,15 @@ def main():
     dt = time.perf_counter() - t0
     n_gemm, gemm_ms, gemm_flops = ctx.profile_end()
     for f in pending:
-        losses.append(float(ctx.await_(f)[0]))
+        losses.append(float(ctx.await_(f).reshape(-1)[0]))
         ctx.future_release(f)
     if not all(math.isfinite(l) for l in losses):
         print(f"bench.py: non-finite loss {losses}", file=sys.stderr)
         sys.exit(1)
 
     ms_per_step = dt * 1e3 / args.steps
-    tokens_per_s = cfg.n_tokens * args.steps / dt
+    tokens_per_step = cfg.n_tokens * cfg.n_microbatch
+    tokens_per_s = tokens_per_step * args.steps / dt
     flops = pwb.step_flops(cfg)
     achieved = flops / (dt / args.steps) / 1e12
     gemm_tflops = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
@@ -163,13 +195,14 @@ def main():
         "metric": "train tokens/sec/GPU", "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.bf16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {cfg.n_layer}-layer decoder-only LM train step, d_model {cfg.d_model}, "
-                               f"{cfg.n_head} heads, FFN {cfg.d_ff}, vocab {cfg.vocab}, seq {cfg.seq}, batch {cfg.batch}, "
-                               f"{'bf16 compute / fp32 master' if cfg.bf16 else 'fp32'} + {cfg.optimizer}",
-                   "tokens_per_step": cfg.n_tokens, "model_tflop_per_step": round(flops / 1e12, 3)},
+        "config": {"workload": f"{args.workload}: {cfg.n_layer}-layer decoder-only LM "
+                               f"{'train step' if cfg.has_head else f'pipeline stage, {cfg.n_microbatch} micro-batches fwd-all/bwd-all'}, "
+                               f"d_model {cfg.d_model}, {cfg.n_head} heads, FFN {cfg.d_ff}, vocab {cfg.vocab}, seq {cfg.seq}, "
+                               f"batch {cfg.batch}, {'bf16 compute / fp32 master' if cfg.bf16 else 'fp32'} + {cfg.optimizer}",
+                   "tokens_per_step": tokens_per_step, "model_tflop_per_step": round(flops / 1e12, 3)},
         "pct_peak_bf16_mfma": round(100.0 * achieved / PEAK_BF16_TFLOPS, 2),
         "step_tflops": round(achieved, 1),
-        "loss_first_last": [round(losses[0], 4), round(losses[-1], 4)],
+        ("loss_first_last" if cfg.has_head else "dx0_first_last"): [round(losses[0], 4), round(losses[-1], 4)],
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel (all layouts)", "achieved": round(gemm_tflops, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": None, "launches_per_step": n_gemm // max(1, args.steps),
@@ -182,7 +215,9 @@ def main():
     model.close()
     ctx.close()
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, pwb)
+        cb = cpu_baseline(cfg, pwb)
+        if cb is not None:
+            result["cpu_baseline"] = cb
     print(json.dumps(result))
 
 

@@ -21,6 +21,11 @@
 
 #include <vector>
 
+#ifndef PW_WM
+#define PW_WM 2
+#define PW_WN 4
+#endif
+
 namespace pw {
 
 struct EpiParams {
@@ -176,8 +181,8 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 template <int ROWS, int NT, bool KMAJOR, bool EDGE>
 struct TileLoader {
   static constexpr int kPieces = KMAJOR ? (kBK / 4) * (ROWS / 8) : ROWS * (kBK / 8);
-  static constexpr int CNT = kPieces / NT;
-  static_assert(kPieces % NT == 0, "tile does not divide over the workgroup");
+  static constexpr int CNT = (kPieces + NT - 1) / NT;
+  static constexpr bool kPartial = kPieces % NT != 0;   // some threads own no piece in the last round
   u32x4 reg[KMAJOR ? CNT * 4 : CNT];
 
   // k-major pieces: which 8-row chunk (rc) and which 4-k group (kq) piece `id` covers.  The 8-byte LDS
@@ -194,6 +199,7 @@ struct TileLoader {
 #pragma unroll
     for (int i = 0; i < CNT; ++i) {
       const int id = threadIdx.x + i * NT;
+      if (kPartial && id >= kPieces) continue;
       if (!KMAJOR) {
         const int r = id >> 3, kc = id & 7;
         const int64_t row = row0 + r, k = k0 + kc * 8;
@@ -221,6 +227,7 @@ struct TileLoader {
 #pragma unroll
     for (int i = 0; i < CNT; ++i) {
       const int id = threadIdx.x + i * NT;
+      if (kPartial && id >= kPieces) continue;
       if (!KMAJOR) {
         const int r = id >> 3, kc = id & 7;
         *reinterpret_cast<u32x4*>(tile + r * kLdk + kc * 8) = reg[i];
@@ -386,7 +393,7 @@ static hipError_t prepare_bf16_tile() {
 }
 
 hipError_t gemm_init() {
-  hipError_t e = prepare_bf16_tile<256, 256, 2, 4>();
+  hipError_t e = prepare_bf16_tile<256, 256, PW_WM, PW_WN>();
   if (e == hipSuccess) e = prepare_bf16_tile<128, 128, 2, 2>();
   return e;
 }
@@ -584,12 +591,12 @@ static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a) {
   p.epi = e;
   // Tile choice: 256x256 when that still yields at least one workgroup per CU; otherwise 128x128.
   const int64_t big_tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-  const bool use_big = big_tiles >= 200;
+  const bool use_big = big_tiles >= 150;
   if (use_big) {
     p.tiles_m = (int)((a.M + 255) / 256);
     p.tiles_n = (int)((a.N + 255) / 256);
     const bool edge = (a.M % 256) || (a.N % 256) || (a.K % kBK);
-    return launch_bf16_tile<256, 256, 2, 4>(s, p, a.a_kmajor, a.b_kmajor, edge);
+    return launch_bf16_tile<256, 256, PW_WM, PW_WN>(s, p, a.a_kmajor, a.b_kmajor, edge);
   }
   p.tiles_m = (int)((a.M + 127) / 128);
   p.tiles_n = (int)((a.N + 127) / 128);
