@@ -47,6 +47,20 @@ def fill_model_on_device(model, cfg, torch, seed: int):
         del t
 
 
+def recorded_gemm_traffic(workload: str):
+    """HBM-side bytes per GEMM launch as measured with rocprofv3 counters (two --pmc runs, scaled by a plain
+    copy kernel; see the summary under profiles/).  Counters cannot be collected from inside this process, so
+    the recorded figure is reported; None for workloads that were not profiled."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_train_step_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("# all gemm_bf16_kernel launches:"):
+                return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
 def dispatch_bench(ctx, pwb, I, reps: int = 200):
     """Chained dispatch cost (Section 5.1 analogue on one GPU): chains of L trivial functions on a
     128-float buffer.  host = time for the enqueue call to return; wall = until the result is ready."""
@@ -110,6 +124,8 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dispatch", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy three times (reference for HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
@@ -185,6 +201,14 @@ def main():
         print(f"bench.py: non-finite loss {losses}", file=sys.stderr)
         sys.exit(1)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     ms_per_step = dt * 1e3 / args.steps
     tokens_per_step = cfg.n_tokens * cfg.n_microbatch
     tokens_per_s = tokens_per_step * args.steps / dt
@@ -205,7 +229,7 @@ def main():
         ("loss_first_last" if cfg.has_head else "dx0_first_last"): [round(losses[0], 4), round(losses[-1], 4)],
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel (all layouts)", "achieved": round(gemm_tflops, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None, "launches_per_step": n_gemm // max(1, args.steps),
+                     "traffic": recorded_gemm_traffic(args.workload), "launches_per_step": n_gemm // max(1, args.steps),
                      "avg_launch_ms": round(gemm_ms / max(1, n_gemm), 4),
                      "avg_launch_gflop": round(gemm_flops / max(1, n_gemm) / 1e9, 2),
                      "gemm_ms_per_step": round(gemm_ms / args.steps, 3)},
