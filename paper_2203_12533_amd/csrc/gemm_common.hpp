@@ -1,0 +1,194 @@
+// Pieces shared by the GEMM kernels: epilogue parameters and functions, tile mapping.
+#pragma once
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace pw {
+
+struct EpiParams {
+  int mode, out_bf16, accumulate;
+  const float* bias;
+  const void* aux;
+  void* C;
+  void* C2;
+  int64_t ldc;
+};
+
+// Epilogue on 4 consecutive columns n0..n0+3 of row m.  AUXT: element type of aux for kEpiGeluBwd / of the
+// outputs when out_bf16 (the activation type).
+template <bool BF16ACT>
+__device__ __forceinline__ void epilogue4(const EpiParams& e, int64_t m, int64_t n0, float v0, float v1, float v2, float v3) {
+  const int64_t off = m * e.ldc + n0;
+  if (e.mode == kEpiBias || e.mode == kEpiBiasResidual || e.mode == kEpiBiasGelu) {
+    if (e.bias) {
+      const float4 b = *reinterpret_cast<const float4*>(e.bias + n0);
+      v0 += b.x; v1 += b.y; v2 += b.z; v3 += b.w;
+    }
+  }
+  if (e.mode == kEpiBiasResidual) {
+    const float4 r = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(e.aux) + off);
+    v0 += r.x; v1 += r.y; v2 += r.z; v3 += r.w;
+  } else if (e.mode == kEpiGeluBwd) {
+    float u0, u1, u2, u3;
+    if (BF16ACT) {
+      const bf16x4 u = *reinterpret_cast<const bf16x4*>(reinterpret_cast<const bf16*>(e.aux) + off);
+      u0 = (float)u[0]; u1 = (float)u[1]; u2 = (float)u[2]; u3 = (float)u[3];
+    } else {
+      const float4 u = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(e.aux) + off);
+      u0 = u.x; u1 = u.y; u2 = u.z; u3 = u.w;
+    }
+    v0 *= gelu_grad_f(u0); v1 *= gelu_grad_f(u1); v2 *= gelu_grad_f(u2); v3 *= gelu_grad_f(u3);
+  }
+  if (e.out_bf16) {
+    bf16x4 o = {(bf16)v0, (bf16)v1, (bf16)v2, (bf16)v3};
+    *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(e.C) + off) = o;
+    if (e.mode == kEpiBiasGelu) {
+      bf16x4 h = {(bf16)gelu_f(v0), (bf16)gelu_f(v1), (bf16)gelu_f(v2), (bf16)gelu_f(v3)};
+      *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(e.C2) + off) = h;
+    }
+  } else {
+    float* c = reinterpret_cast<float*>(e.C) + off;
+    if (e.accumulate) {
+      const float4 old = *reinterpret_cast<const float4*>(c);
+      v0 += old.x; v1 += old.y; v2 += old.z; v3 += old.w;
+    }
+    *reinterpret_cast<float4*>(c) = make_float4(v0, v1, v2, v3);
+    if (e.mode == kEpiBiasGelu)
+      *reinterpret_cast<float4*>(reinterpret_cast<float*>(e.C2) + off) = make_float4(gelu_f(v0), gelu_f(v1), gelu_f(v2), gelu_f(v3));
+  }
+}
+
+// Same, one element (ragged right edge).
+template <bool BF16ACT>
+__device__ __forceinline__ void epilogue1(const EpiParams& e, int64_t m, int64_t n, float v) {
+  const int64_t off = m * e.ldc + n;
+  if ((e.mode == kEpiBias || e.mode == kEpiBiasResidual || e.mode == kEpiBiasGelu) && e.bias) v += e.bias[n];
+  if (e.mode == kEpiBiasResidual) v += reinterpret_cast<const float*>(e.aux)[off];
+  if (e.mode == kEpiGeluBwd)
+    v *= gelu_grad_f(BF16ACT ? (float)reinterpret_cast<const bf16*>(e.aux)[off] : reinterpret_cast<const float*>(e.aux)[off]);
+  if (e.out_bf16) {
+    reinterpret_cast<bf16*>(e.C)[off] = (bf16)v;
+    if (e.mode == kEpiBiasGelu) reinterpret_cast<bf16*>(e.C2)[off] = (bf16)gelu_f(v);
+  } else {
+    float* c = reinterpret_cast<float*>(e.C) + off;
+    if (e.accumulate) v += *c;
+    *c = v;
+    if (e.mode == kEpiBiasGelu) reinterpret_cast<float*>(e.C2)[off] = gelu_f(v);
+  }
+}
+
+// Epilogue on 8 consecutive columns n0..n0+7 of row m (bf16-activation kernels; all accesses 16-byte vectors).
+__device__ __forceinline__ void epilogue8(const EpiParams& e, int64_t m, int64_t n0, float* v) {
+  const int64_t off = m * e.ldc + n0;
+  if ((e.mode == kEpiBias || e.mode == kEpiBiasResidual || e.mode == kEpiBiasGelu) && e.bias) {
+    const float4 b0 = *reinterpret_cast<const float4*>(e.bias + n0), b1 = *reinterpret_cast<const float4*>(e.bias + n0 + 4);
+    v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w; v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
+  }
+  if (e.mode == kEpiBiasResidual) {
+    const float* r = reinterpret_cast<const float*>(e.aux) + off;
+    const float4 r0 = *reinterpret_cast<const float4*>(r), r1 = *reinterpret_cast<const float4*>(r + 4);
+    v[0] += r0.x; v[1] += r0.y; v[2] += r0.z; v[3] += r0.w; v[4] += r1.x; v[5] += r1.y; v[6] += r1.z; v[7] += r1.w;
+  } else if (e.mode == kEpiGeluBwd) {
+    const bf16x8 u = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16*>(e.aux) + off);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] *= gelu_grad_f((float)u[i]);
+  }
+  if (e.out_bf16) {
+    bf16x8 o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (bf16)v[i];
+    *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(e.C) + off) = o;
+    if (e.mode == kEpiBiasGelu) {
+      bf16x8 h;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) h[i] = (bf16)gelu_f(v[i]);
+      *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(e.C2) + off) = h;
+    }
+  } else {
+    float* c = reinterpret_cast<float*>(e.C) + off;
+    if (e.accumulate) {
+      const float4 o0 = *reinterpret_cast<const float4*>(c), o1 = *reinterpret_cast<const float4*>(c + 4);
+      v[0] += o0.x; v[1] += o0.y; v[2] += o0.z; v[3] += o0.w; v[4] += o1.x; v[5] += o1.y; v[6] += o1.z; v[7] += o1.w;
+    }
+    *reinterpret_cast<float4*>(c) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(c + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    if (e.mode == kEpiBiasGelu) {
+      float* c2 = reinterpret_cast<float*>(e.C2) + off;
+      *reinterpret_cast<float4*>(c2) = make_float4(gelu_f(v[0]), gelu_f(v[1]), gelu_f(v[2]), gelu_f(v[3]));
+      *reinterpret_cast<float4*>(c2 + 4) = make_float4(gelu_f(v[4]), gelu_f(v[5]), gelu_f(v[6]), gelu_f(v[7]));
+    }
+  }
+}
+
+// Workgroup id -> output tile, XCD-aware (see file header).
+__device__ __forceinline__ void tile_of_block(int pid, int nblk, int tiles_m, int tiles_n, int& tm, int& tn) {
+  constexpr int kXcd = 8, kGroup = 8;
+  const int q = nblk / kXcd, r = nblk % kXcd;
+  const int xcd = pid % kXcd, j = pid / kXcd;
+  const int logical = xcd * q + (xcd < r ? xcd : r) + j;
+  const int per_group = kGroup * tiles_n;
+  const int group = logical / per_group;
+  const int first_m = group * kGroup;
+  const int gsize = tiles_m - first_m < kGroup ? tiles_m - first_m : kGroup;
+  const int in_group = logical - group * per_group;
+  tm = first_m + in_group % gsize;
+  tn = in_group / gsize;
+}
+
+struct GemmBf16Params {
+  const bf16* A;
+  const bf16* B;
+  int64_t M, N, K, lda, ldb;
+  int tiles_m, tiles_n;
+  EpiParams epi;
+};
+
+// Epilogue of the MFMA kernels.  acc[i][j][r] is element m = 32 i + lane%32, n = 32 j + 8 (r/4) + 4 (lane/32) + r%4
+// of the wave tile (rows mw0.., columns nw0..): a lane owns one row fragment of 4 columns, so storing straight
+// from the accumulators would scatter 8-byte pieces over 32 rows per instruction.  Instead each wave parks one
+// 32 x 64 block at a time in its own slice of LDS (the operand tiles are dead by now) and reads it back
+// row-wise: 8 lanes cover the 64 columns of a row with 8 consecutive values each, so every global access of
+// the epilogue (output, residual, saved pre-activation) is a 16-byte vector and every row segment a full
+// 128-byte line or more.  All waves of the block must call (it synchronises the block).
+template <int FM, int FN, bool EDGE>
+__device__ __forceinline__ void gemm_epilogue_staged(bf16* smem, f32x16 (&acc)[FM][FN], const GemmBf16Params& p,
+                                                     int64_t mw0, int64_t nw0, int wave, int lane) {
+  static_assert(FN == 2, "epilogue staging assumes a 64-column wave tile");
+  constexpr int kLdS = 64 + 4;   // floats; 272-byte rows keep the 16-byte LDS accesses conflict-free
+  const int lrow = lane & 31, lhalf = lane >> 5;
+  __syncthreads();
+  float* stage = reinterpret_cast<float*>(smem) + wave * (32 * kLdS);
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4*>(stage + lrow * kLdS + j * 32 + q * 8 + lhalf * 4) =
+            make_float4(acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+    __syncthreads();
+#pragma unroll 1
+    for (int it = 0; it < 4; ++it) {
+      const int row = it * 8 + (lane >> 3), c8 = lane & 7;
+      const float4 v0 = *reinterpret_cast<const float4*>(stage + row * kLdS + c8 * 8);
+      const float4 v1 = *reinterpret_cast<const float4*>(stage + row * kLdS + c8 * 8 + 4);
+      float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+      const int64_t m = mw0 + i * 32 + row;
+      const int64_t n = nw0 + c8 * 8;
+      if (!EDGE || (m < p.M && n + 7 < p.N)) {
+        epilogue8(p.epi, m, n, v);
+      } else if (m < p.M) {
+        for (int e = 0; e < 8; ++e)
+          if (n + e < p.N) epilogue1<true>(p.epi, m, n + e, v[e]);
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// Ring-buffered variant for full tiles (gemm_ring.hip).
+bool gemm_ring_supported(int64_t M, int64_t N, int64_t K);
+hipError_t launch_gemm_ring(hipStream_t s, const GemmBf16Params& p, bool a_kmajor, bool b_kmajor);
+hipError_t gemm_ring_init();
+
+}  // namespace pw

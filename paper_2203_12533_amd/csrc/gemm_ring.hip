@@ -1,0 +1,195 @@
+// bf16 MFMA GEMM, ring-buffered variant for full tiles: global memory -> LDS directly
+// (global_load_lds_dwordx4, no staging registers, no LDS store instructions) into a two-stage ring of
+// 64-deep k tiles - the next tile is in flight while one is multiplied - and transposing LDS reads
+// (ds_read_b64_tr_b16) for operands stored k-major, so no data is ever regrouped in registers.
+//
+// Facts about the two gfx950 instructions, checked on the device with in-bounds probes:
+//  * global_load_lds_dwordx4: the wave's 64 lanes deposit their 16 bytes at LDS base + 16*lane, in lane
+//    order, whatever global address each lane supplied.  A swizzled LDS layout is therefore obtained by
+//    choosing which global chunk each lane fetches.
+//  * ds_read_b64_tr_b16: within each group of 16 lanes, lane i receives element i%4 of the four 8-byte
+//    pieces addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12 of the group.  If lane L of the group
+//    points at [k0 + L/4][r0 + 4*(L%4)] of a k-major tile, lane i ends up with k0..k0+3 of row r0 + i:
+//    half of an MFMA operand fragment.
+//
+// LDS layouts (one stage = A tile then B tile, 32 KiB each, no padding):
+//  * operand stored [row][k] in memory: LDS [256 rows][8 chunks of 8 k]; chunk c of row r sits at
+//    position c ^ ((r >> 1) & 7): the 16-byte fragment reads of 16 consecutive rows hit 16 distinct
+//    bank groups.
+//  * operand stored [k][row] in memory: LDS [64 k][32 chunks of 8 rows]; chunk c of k-row k sits at
+//    position c ^ (4 * (k & 3)): the four k-rows touched by one transposing read fall into four
+//    different 64-byte bank windows.
+#include "common.hpp"
+#include "gemm_common.hpp"
+#include "kernels.hpp"
+
+namespace pw {
+
+namespace {
+
+constexpr int kRT = 256;            // tile is kRT x kRT
+constexpr int kRBK = 64;            // k per stage
+constexpr int kRStages = 2;
+constexpr int kROperand = kRT * kRBK;            // elements per operand tile (32 KiB)
+constexpr int kRStage = 2 * kROperand;           // elements per stage
+constexpr int kRThreads = 512;
+
+typedef __attribute__((address_space(3))) void* lds_ptr;
+typedef const __attribute__((address_space(1))) void* gbl_ptr;
+typedef short short4v __attribute__((ext_vector_type(4)));
+
+// Issue this wave's share (4 x 1 KiB) of one operand tile's direct loads (32 instructions of 1 KiB per tile).
+//   base: operand; ld: leading dimension; row0: first tile row (m or n); k0: first k of the stage.
+// 16 bytes per lane from global memory straight into LDS at lds_off + 16*lane (lds_off: wave-uniform byte
+// offset).  Issued through inline assembly on purpose: the compiler then keeps no record of an LDS write in
+// flight, and so neither drains the vector-memory counter before unrelated LDS reads nor at barriers.  The
+// kernel waits for exactly the tile it needs with explicit s_waitcnt vmcnt(n) (see the main loop).
+__device__ __forceinline__ void dma16(const bf16* g, uint32_t lds_off) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_off) : "memory", "m0");
+}
+
+template <bool KMAJOR>
+__device__ __forceinline__ void issue_operand(const bf16* __restrict__ base, int64_t ld, int64_t row0, int64_t k0,
+                                              uint32_t lds_tile_off, int wave, int lane) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int instr = wave * 4 + j;
+    const bf16* g;
+    if (!KMAJOR) {
+      const int r = instr * 8 + (lane >> 3);        // 8 rows x 128 bytes per instruction
+      const int c = (lane & 7) ^ ((r >> 1) & 7);
+      g = base + (row0 + r) * ld + k0 + c * 8;
+    } else {
+      const int k = instr * 2 + (lane >> 5);        // 2 k-rows x 512 bytes per instruction
+      const int c = (lane & 31) ^ (4 * (k & 3));
+      g = base + (k0 + k) * ld + row0 + c * 8;
+    }
+    dma16(g, lds_tile_off + instr * 1024);
+  }
+}
+
+// One MFMA operand fragment (rows frag_row0 .. +31 of the tile, k16 step kk) for this lane.
+template <bool KMAJOR>
+__device__ __forceinline__ bf16x8 read_fragment(const bf16* lds_tile, int frag_row0, int kk, int lane) {
+  if (!KMAJOR) {
+    const int r = frag_row0 + (lane & 31);
+    const int c = (2 * kk + (lane >> 5)) ^ ((r >> 1) & 7);
+    return *reinterpret_cast<const bf16x8*>(lds_tile + r * kRBK + c * 8);
+  } else {
+    const int grp = lane >> 4, L = lane & 15;
+    const int row = frag_row0 + 16 * (grp & 1) + 4 * (L & 3);     // first of the 4 rows this lane points at
+    const int kbase = kk * 16 + 8 * (grp >> 1) + (L >> 2);
+    union { bf16x8 v; short4v h[2]; } u;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int k = kbase + 4 * t;
+      const int c = (row >> 3) ^ (4 * (k & 3));
+      const bf16* p = lds_tile + k * kRT + c * 8 + (row & 7);
+      u.h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)p);
+    }
+    return u.v;
+  }
+}
+
+template <bool A_KMAJOR, bool B_KMAJOR>
+__global__ __launch_bounds__(kRThreads) void gemm_ring_kernel(GemmBf16Params p) {
+  extern __shared__ __attribute__((aligned(16))) bf16 smem[];
+  int tm, tn;
+  tile_of_block(blockIdx.x, p.tiles_m * p.tiles_n, p.tiles_m, p.tiles_n, tm, tn);
+  const int64_t m0 = (int64_t)tm * kRT, n0 = (int64_t)tn * kRT;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = wave >> 2, wn = wave & 3;            // 2 x 4 waves, wave tile 128 x 64
+  constexpr int FM = 4, FN = 2;
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int64_t kt_total = p.K / kRBK;
+  const uint32_t smem_off = (uint32_t)(uintptr_t)(lds_ptr)smem;   // byte offset of the ring inside LDS
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  auto issue = [&](int64_t kt) {
+    const uint32_t stage = smem_off + (uint32_t)(kt % kRStages) * (kRStage * 2);
+    issue_operand<A_KMAJOR>(p.A, p.lda, m0, kt * kRBK, stage, wave_s, lane);
+    issue_operand<B_KMAJOR>(p.B, p.ldb, n0, kt * kRBK, stage + kROperand * 2, wave_s, lane);
+  };
+  auto load_frags = [&](const bf16* a_tile, const bf16* b_tile, int kk, bf16x8* af, bf16x8* bfr) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i) af[i] = read_fragment<A_KMAJOR>(a_tile, wm * 128 + i * 32, kk, lane);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) bfr[j] = read_fragment<B_KMAJOR>(b_tile, wn * 64 + j * 32, kk, lane);
+  };
+  issue(0);
+  for (int64_t kt = 0; kt < kt_total; ++kt) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's share of tile kt has landed
+    // Bare barrier (no fence): tile kt is now visible to all waves, and every wave has consumed tile kt-1 (its
+    // MFMAs were issued, hence its LDS reads had returned), so that stage may be overwritten.
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (kt + 1 < kt_total) issue(kt + 1);
+    const bf16* a_tile = smem + (kt % kRStages) * kRStage;
+    const bf16* b_tile = a_tile + kROperand;
+    // Fragments are double-buffered in registers: the LDS reads of k-step kk+1 are issued before the MFMAs
+    // of k-step kk, so their latency hides behind 8 MFMAs instead of stalling every second one.
+    bf16x8 af[2][FM], bfr[2][FN];
+    load_frags(a_tile, b_tile, 0, af[0], bfr[0]);
+#pragma unroll
+    for (int kk = 0; kk < kRBK / 16; ++kk) {
+      if (kk + 1 < kRBK / 16) load_frags(a_tile, b_tile, kk + 1, af[(kk + 1) & 1], bfr[(kk + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  gemm_epilogue_staged<FM, FN, false>(smem, acc, p, m0 + wm * 128, n0 + wn * 64, wave, lane);
+}
+
+constexpr size_t kRSmemBytes = (size_t)kRStages * kRStage * sizeof(bf16);   // 128 KiB
+static_assert(kRSmemBytes >= 8 * 32 * 68 * 4, "epilogue staging must fit");
+
+template <bool AK, bool BK_>
+hipError_t prepare_ring_variant() {
+  static bool attr_done = false;
+  if (attr_done) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_kernel<AK, BK_>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRSmemBytes);
+  if (e == hipSuccess) attr_done = true;
+  return e;
+}
+
+template <bool AK, bool BK_>
+hipError_t launch_ring_variant(hipStream_t s, const GemmBf16Params& p) {
+  hipError_t e = prepare_ring_variant<AK, BK_>();
+  if (e != hipSuccess) return e;
+  gemm_ring_kernel<AK, BK_><<<p.tiles_m * p.tiles_n, kRThreads, kRSmemBytes, s>>>(p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool gemm_ring_supported(int64_t M, int64_t N, int64_t K) { return M % kRT == 0 && N % kRT == 0 && K % kRBK == 0 && K >= kRBK; }
+
+hipError_t launch_gemm_ring(hipStream_t s, const GemmBf16Params& p, bool ak, bool bk) {
+  if (!ak && !bk) return launch_ring_variant<false, false>(s, p);
+  if (!ak && bk) return launch_ring_variant<false, true>(s, p);
+  if (ak && bk) return launch_ring_variant<true, true>(s, p);
+  return launch_ring_variant<true, false>(s, p);
+}
+
+hipError_t gemm_ring_init() {
+  hipError_t e = prepare_ring_variant<false, false>();
+  if (e == hipSuccess) e = prepare_ring_variant<false, true>();
+  if (e == hipSuccess) e = prepare_ring_variant<true, true>();
+  if (e == hipSuccess) e = prepare_ring_variant<true, false>();
+  return e;
+}
+
+}  // namespace pw
