@@ -227,7 +227,7 @@ def main():
         "pct_peak_bf16_mfma": round(100.0 * achieved / PEAK_BF16_TFLOPS, 2),
         "step_tflops": round(achieved, 1),
         ("loss_first_last" if cfg.has_head else "dx0_first_last"): [round(losses[0], 4), round(losses[-1], 4)],
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel (all layouts)", "achieved": round(gemm_tflops, 1),
+        "roofline": {"bound": "mfma", "kernel": "bf16 MFMA GEMM (gemm_ring_kernel + gemm_bf16_kernel, all layouts)", "achieved": round(gemm_tflops, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": recorded_gemm_traffic(args.workload), "launches_per_step": n_gemm // max(1, args.steps),
                      "avg_launch_ms": round(gemm_ms / max(1, n_gemm), 4),

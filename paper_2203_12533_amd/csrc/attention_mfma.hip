@@ -176,7 +176,7 @@ __device__ __forceinline__ void store_row(bf16* __restrict__ dst, const f32x16* 
 // forward: block = 128 queries of one (batch, head); wave = 32 queries; key/value tiles of 64
 // ===================================================================================================
 template <int HD>
-__global__ __launch_bounds__(kNT) void attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o,
+__global__ __launch_bounds__(kNT, 2) void attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o,
                                                        float* __restrict__ lse, int T, int H) {
   constexpr int BKV = 64;
   using KT = Tile<BKV, HD>;
@@ -222,34 +222,41 @@ __global__ __launch_bounds__(kNT) void attn_fwd_kernel(const bf16* __restrict__ 
     f32x16 s[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) s[kb] = first_product<HD, KT::kLdNat>(Ks, kb * 32, qf);
-    const bool diag = j0 + BKV - 1 > q0;
-    float mx = m;
+    if (j0 + BKV - 1 > q0) {        // the tile straddles the diagonal for this wave: mask key > query
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float v = s[kb][r] * c2;
-        if (diag && j0 + kb * 32 + reg_row(r, half) > query) v = -INFINITY;
-        s[kb][r] = v;
-        mx = fmaxf(mx, v);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float alpha = exp2f(m - mx);      // m = -inf on the first tile: exp2(-inf) = 0
-    m = mx;
+        for (int r = 0; r < 16; ++r)
+          if (j0 + kb * 32 + reg_row(r, half) > query) s[kb][r] = -INFINITY;
+    }
+    // row maximum of the raw scores (the scale is positive, so it commutes with max)
+    float mx = fmaxf(s[0][0], s[1][0]);
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s[0][r], s[1][r]));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c2;
+    // Lazy rescaling: the running reference m only has to bound the exponents, not equal the maximum.  It is
+    // moved (and the accumulators rescaled) only when some row's maximum grew by more than 2^8; otherwise
+    // exp2(s - m) <= 256 and nothing can overflow.  Same mathematics, far fewer multiplies.
+    if (__builtin_amdgcn_ballot_w64(mx > m + 8.f) != 0) {
+      const float m_new = fmaxf(m, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m - m_new);      // m = -inf on the first tile: exp2(-inf) = 0
+      m = m_new;
+      l *= alpha;
+#pragma unroll
+      for (int cb = 0; cb < HD / 32; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[cb][r] *= alpha;
+    }
     float sum = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = exp2f(s[kb][r] - mx);
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[kb][r], c2, -m));
         s[kb][r] = p;
         sum += p;
       }
-    l = l * alpha + sum;
-#pragma unroll
-    for (int cb = 0; cb < HD / 32; ++cb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[cb][r] *= alpha;
+    l += sum;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -258,7 +265,7 @@ __global__ __launch_bounds__(kNT) void attn_fwd_kernel(const bf16* __restrict__ 
   l += __shfl_xor(l, 32, 64);
   if (query < T) {
     store_row<HD>(o + ((int64_t)b * T + query) * d + h * HD, acc, 1.f / l);
-    if (half == 0) lse[(int64_t)bh * T + query] = (m + log2f(l)) * kLn2;
+    if (half == 0) lse[(int64_t)bh * T + query] = (m + __builtin_amdgcn_logf(l)) * kLn2;   // v_log_f32 is log2
   }
 }
 
@@ -266,7 +273,7 @@ __global__ __launch_bounds__(kNT) void attn_fwd_kernel(const bf16* __restrict__ 
 // dQ: same tiling as the forward.  dQ_i = scale * sum_j dS_ij K_j, dS = P (dP - delta)
 // ===================================================================================================
 template <int HD>
-__global__ __launch_bounds__(kNT) void attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
+__global__ __launch_bounds__(kNT, 2) void attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
                                                       const float* __restrict__ lse, const float* __restrict__ delta,
                                                       bf16* __restrict__ dqkv, int T, int H) {
   constexpr int BKV = 64;
@@ -320,12 +327,13 @@ __global__ __launch_bounds__(kNT) void attn_dq_kernel(const bf16* __restrict__ q
     for (int kb = 0; kb < 2; ++kb) {
       f32x16 s = first_product<HD, KT::kLdNat>(Ks, kb * 32, qf);      // S^T
       f32x16 dp = first_product<HD, KT::kLdNat>(Vs, kb * 32, gf);     // dP^T = V . dO^T
+      if (diag) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float p = exp2f(s[r] * c2 - lse2);
-        if (diag && j0 + kb * 32 + reg_row(r, half) > query) p = 0.f;
-        s[r] = p * (dp[r] - dl);
+        for (int r = 0; r < 16; ++r)
+          if (j0 + kb * 32 + reg_row(r, half) > query) s[r] = -INFINITY;      // exp2(-inf) = 0
       }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse2)) * (dp[r] - dl);
 #pragma unroll
       for (int b2 = 0; b2 < 2; ++b2) second_product<HD, KT::kLdTr>(Kt, kb * 32 + b2 * 16, pack8(s, b2 * 8), acc);
     }
@@ -337,7 +345,7 @@ __global__ __launch_bounds__(kNT) void attn_dq_kernel(const bf16* __restrict__ q
 // dK, dV: block = 128 keys of one (batch, head); wave = 32 keys; query tiles of 32
 // ===================================================================================================
 template <int HD>
-__global__ __launch_bounds__(kNT) void attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
+__global__ __launch_bounds__(kNT, HD == 64 ? 2 : 1) void attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
                                                        const float* __restrict__ lse, const float* __restrict__ delta,
                                                        bf16* __restrict__ dqkv, int T, int H) {
   constexpr int BQ = 32;
@@ -413,12 +421,15 @@ __global__ __launch_bounds__(kNT) void attn_dkv_kernel(const bf16* __restrict__ 
         lq[8 * g + 4 * v4] = a.x; lq[8 * g + 4 * v4 + 1] = a.y; lq[8 * g + 4 * v4 + 2] = a.z; lq[8 * g + 4 * v4 + 3] = a.w;
         dq[8 * g + 4 * v4] = c.x; dq[8 * g + 4 * v4 + 1] = c.y; dq[8 * g + 4 * v4 + 2] = c.z; dq[8 * g + 4 * v4 + 3] = c.w;
       }
-    const bool diag = i0 < k0 + 31;
+    if (i0 < k0 + 31) {              // diagonal tile: a key may not see an earlier query
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (key > i0 + reg_row(r, half)) s[r] = -INFINITY;
+    }
     f32x16 ds;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      float p = exp2f(s[r] * c2 - lq[r]);
-      if (diag && key > i0 + reg_row(r, half)) p = 0.f;
+      const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lq[r]));
       s[r] = p;
       ds[r] = p * (dp[r] - dq[r]);
     }
