@@ -1,0 +1,63 @@
+// Helpers shared by the MFMA attention kernels (register-layout bookkeeping; see attention_mfma.hip).
+#pragma once
+#include "common.hpp"
+
+namespace pw {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ int perm_row(int i) {   // [0-3, 8-11, 4-7, 12-15] within each 16
+  const int j = i & 15;
+  const int p = (j & 3) | ((j & 4) << 1) | ((j & 8) >> 1);
+  return (i & ~15) | p;
+}
+
+
+// Fragments of 32 rows x HD features held in registers as the B operand of a first product:
+// lane l holds row (row0 + l%32), features kk*16 + 8*(l/32) .. +7 for every kk.  Rows >= limit read as zero.
+template <int HD>
+__device__ __forceinline__ void load_row_frags(const bf16* __restrict__ src, int64_t ld, int row0, int limit, bf16x8* frag) {
+  const int lane = threadIdx.x & 63;
+  const int row = row0 + (lane & 31);
+  const bf16* p = src + (int64_t)row * ld + (lane >> 5) * 8;
+#pragma unroll
+  for (int kk = 0; kk < HD / 16; ++kk) {
+    if (row < limit) {
+      frag[kk] = *reinterpret_cast<const bf16x8*>(p + kk * 16);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) frag[kk][e] = (bf16)0.f;
+    }
+  }
+}
+
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16& v, int first) {
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (bf16)v[first + e];
+  return o;
+}
+
+
+// Tile-local row index that register r of this lane's D column stands for (see file header).
+__device__ __forceinline__ int reg_row(int r, int half) { return 16 * (r >> 3) + 8 * half + (r & 7); }
+
+// Writes acc (feature-major: register r of block cb = feature cb*32 + 8*(r/4) + 4*half + r%4) for this lane's
+// row to dst (row pointer, feature 0), scaled.
+template <int HD>
+__device__ __forceinline__ void store_row(bf16* __restrict__ dst, const f32x16* acc, float scale) {
+  const int half = (threadIdx.x & 63) >> 5;
+#pragma unroll
+  for (int cb = 0; cb < HD / 32; ++cb)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      bf16x4 o = {(bf16)(acc[cb][q * 4] * scale), (bf16)(acc[cb][q * 4 + 1] * scale), (bf16)(acc[cb][q * 4 + 2] * scale),
+                  (bf16)(acc[cb][q * 4 + 3] * scale)};
+      *reinterpret_cast<bf16x4*>(dst + cb * 32 + q * 8 + half * 4) = o;
+    }
+}
+
+
+}  // namespace pw

@@ -1,0 +1,399 @@
+// bf16 MFMA attention for head_dim 128 with direct global->LDS loads and transposing LDS reads.
+//
+// Same register-layout scheme as attention_mfma.hip (softmax row on the lane; first product's A rows read
+// permuted so that P / dS feed the second product from the accumulator registers).  What changes is how
+// operands travel:
+//  * every tile (K, V, or Q, dO) is brought into LDS once, in its natural [row][128] layout, by
+//    global_load_lds_dwordx4 (each wave instruction deposits 4 rows = 1 KiB; no staging registers, no LDS
+//    store instructions), double-buffered so the next tile is in flight while one is consumed;
+//  * the second product needs the tile as [feature][row]; instead of keeping a transposed copy it is read
+//    with ds_read_b64_tr_b16 (lane L of each 16-lane group points at [k0 + L/4][c0 + 4*(L%4)], lane i
+//    receives rows k0..k0+3 of feature c0 + i).
+// LDS swizzle, one rule for both access patterns: chunk c (8 features = 16 bytes) of row r sits at
+// position c ^ (((r & 3) << 2) | ((r >> 2) & 3)).  16 consecutive (or permuted-within-16) rows of one chunk
+// then hit 16 distinct 16-byte bank groups, and the 4 rows touched by one transposing read fall into 4
+// different 64-byte windows.
+// Rows past the end of the sequence are fetched from the last valid row (always in bounds); every use of
+// such a row is masked (causality) or multiplied by an exact zero (P = exp2(-inf)).
+#include "attention_common.hpp"
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace pw {
+
+namespace {
+
+constexpr int HD = 128;
+constexpr int kNT = 256;                 // 4 waves
+constexpr int kRowBytes = HD * 2;        // 256
+typedef __attribute__((address_space(3))) void* lds_ptr;
+typedef short short4v __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+
+__device__ __forceinline__ void dma16(const bf16* g, uint32_t lds_off) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_off) : "memory", "m0");
+}
+
+// This wave's share of the direct loads of a ROWS x 128 tile (ROWS/4 instructions of 1 KiB over 4 waves).
+// src: element (row 0 of the sequence, feature 0); tile rows row0 .. row0+ROWS-1, clamped to `last`.
+template <int ROWS>
+__device__ __forceinline__ void issue_tile(const bf16* __restrict__ src, int64_t ld, int row0, int last, uint32_t lds_off,
+                                           int wave, int lane) {
+  constexpr int kPerWave = ROWS / 4 / 4;
+#pragma unroll
+  for (int j = 0; j < kPerWave; ++j) {
+    const int instr = wave * kPerWave + j;
+    const int r = instr * 4 + (lane >> 4);
+    const int c = (lane & 15) ^ swz(r);
+    const int row = min(row0 + r, last);
+    dma16(src + (int64_t)row * ld + c * 8, lds_off + instr * 1024);
+  }
+}
+
+// 32x32 block of a first product: A rows (permuted) from a swizzled natural LDS tile, B from register fragments.
+__device__ __forceinline__ f32x16 first_product(const bf16* __restrict__ tile, int row_base, const bf16x8* bfrag) {
+  const int lane = threadIdx.x & 63;
+  const int row = row_base + perm_row(lane & 31);
+  const int t = (lane >> 5) ^ swz(row);                 // chunk (2 kk + half) ^ swz = (2 kk) ^ t
+  const bf16* a = tile + row * HD;
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < HD / 16; ++kk)
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(a + ((2 * kk) ^ t) * 8), bfrag[kk], acc, 0, 0, 0);
+  return acc;
+}
+
+// acc[cb] += Tile^T[features cb*32 ..][rows row_base .. row_base+15] . frag, the tile read transposed.
+__device__ __forceinline__ void second_product(const bf16* __restrict__ tile, int row_base, const bf16x8& frag, f32x16* acc) {
+  const int lane = threadIdx.x & 63;
+  const int grp = lane >> 4, L = lane & 15;
+  const int row0 = row_base + 8 * (grp >> 1) + (L >> 2);          // tile row this lane points at for t = 0
+  const int f0 = 16 * (grp & 1) + 4 * (L & 3);                    // first of its 4 features inside a 32-feature block
+#pragma unroll
+  for (int cb = 0; cb < HD / 32; ++cb) {
+    union { bf16x8 v; short4v h[2]; } u;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int row = row0 + 4 * t;
+      const int chunk = (cb * 32 + f0) >> 3;
+      const bf16* p = tile + row * HD + ((chunk ^ swz(row)) << 3) + (f0 & 7);
+      u.h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)p);
+    }
+    acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, frag, acc[cb], 0, 0, 0);
+  }
+}
+
+__device__ __forceinline__ void wait_and_sync() {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's share of the tile in flight has landed
+  __builtin_amdgcn_s_barrier();                      // ... and so has everyone else's; the other stage is free again
+  asm volatile("" ::: "memory");
+}
+
+// ===================================================================================================
+// forward: block = 128 queries of one (batch, head); wave = 32 queries; key/value tiles of 64
+// ===================================================================================================
+__global__ __launch_bounds__(kNT, 2) void attn_fwd_dma_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o,
+                                                              float* __restrict__ lse, int T, int H) {
+  constexpr int BKV = 64;
+  constexpr int kTile = BKV * HD;                       // elements per K (or V) tile
+  extern __shared__ __attribute__((aligned(1024))) bf16 smem[];         // [stage][K | V], 64 KiB
+  const int d = H * HD;
+  const int64_t ld = 3 * (int64_t)d;
+  const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
+  const int qblk = gridDim.x - 1 - blockIdx.x;          // longest blocks first
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5;
+  const int q0 = qblk * 128 + wave * 32;
+  const int query = q0 + (lane & 31);
+  const bf16* qbase = qkv + (int64_t)b * T * ld + h * HD;
+  const bf16* kbase = qbase + d;
+  const bf16* vbase = qbase + 2 * d;
+  const float c2 = kLog2e / sqrtf((float)HD);
+  const uint32_t smem_off = (uint32_t)(uintptr_t)(lds_ptr)smem;
+
+  bf16x8 qf[HD / 16];
+  load_row_frags<HD>(qbase, ld, q0, T, qf);
+  f32x16 acc[HD / 32];
+#pragma unroll
+  for (int cb = 0; cb < HD / 32; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  const int last_q = min(T, (qblk + 1) * 128) - 1;
+  const int n_tiles = last_q / BKV + 1;
+  auto issue = [&](int t) {
+    const uint32_t st = smem_off + (uint32_t)(t & 1) * (2 * kTile * 2);
+    issue_tile<BKV>(kbase, ld, t * BKV, T - 1, st, wave, lane);
+    issue_tile<BKV>(vbase, ld, t * BKV, T - 1, st + kTile * 2, wave, lane);
+  };
+  issue(0);
+  for (int t = 0; t < n_tiles; ++t) {
+    const int j0 = t * BKV;
+    wait_and_sync();
+    if (t + 1 < n_tiles) issue(t + 1);
+    if (j0 > q0 + 31) continue;   // every key of the tile lies in this wave's future
+    const bf16* Ks = smem + (t & 1) * (2 * kTile);
+    const bf16* Vs = Ks + kTile;
+    f32x16 s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) s[kb] = first_product(Ks, kb * 32, qf);
+    if (j0 + BKV - 1 > q0) {        // the tile straddles the diagonal for this wave: mask key > query
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (j0 + kb * 32 + reg_row(r, half) > query) s[kb][r] = -INFINITY;
+    }
+    float mx = fmaxf(s[0][0], s[1][0]);
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s[0][r], s[1][r]));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c2;
+    // lazy rescaling: the reference m only has to bound the exponents (see attention_mfma.hip)
+    if (__builtin_amdgcn_ballot_w64(mx > m + 8.f) != 0) {
+      const float m_new = fmaxf(m, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+      m = m_new;
+      l *= alpha;
+#pragma unroll
+      for (int cb = 0; cb < HD / 32; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[cb][r] *= alpha;
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[kb][r], c2, -m));
+        s[kb][r] = p;
+        sum += p;
+      }
+    l += sum;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) second_product(Vs, kb * 32 + b2 * 16, pack8(s[kb], b2 * 8), acc);
+  }
+  l += __shfl_xor(l, 32, 64);
+  if (query < T) {
+    store_row<HD>(o + ((int64_t)b * T + query) * d + h * HD, acc, 1.f / l);
+    if (half == 0) lse[(int64_t)bh * T + query] = (m + __builtin_amdgcn_logf(l)) * kLn2;
+  }
+}
+
+// ===================================================================================================
+// dQ: same tiling as the forward.  dQ_i = scale * sum_j dS_ij K_j, dS = P (dP - delta)
+// ===================================================================================================
+__global__ __launch_bounds__(kNT, 2) void attn_dq_dma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
+                                                             const float* __restrict__ lse, const float* __restrict__ delta,
+                                                             bf16* __restrict__ dqkv, int T, int H) {
+  constexpr int BKV = 64;
+  constexpr int kTile = BKV * HD;
+  extern __shared__ __attribute__((aligned(1024))) bf16 smem[];
+  const int d = H * HD;
+  const int64_t ld = 3 * (int64_t)d;
+  const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
+  const int qblk = gridDim.x - 1 - blockIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5;
+  const int q0 = qblk * 128 + wave * 32;
+  const int query = q0 + (lane & 31);
+  const bf16* qbase = qkv + (int64_t)b * T * ld + h * HD;
+  const bf16* kbase = qbase + d;
+  const bf16* vbase = qbase + 2 * d;
+  const float scale = 1.f / sqrtf((float)HD);
+  const float c2 = kLog2e * scale;
+  const uint32_t smem_off = (uint32_t)(uintptr_t)(lds_ptr)smem;
+
+  bf16x8 qf[HD / 16], gf[HD / 16];
+  load_row_frags<HD>(qbase, ld, q0, T, qf);
+  load_row_frags<HD>(dout + (int64_t)b * T * d + h * HD, d, q0, T, gf);
+  const float lse2 = query < T ? lse[(int64_t)bh * T + query] * kLog2e : INFINITY;   // +inf: P = 0 for rows past the end
+  const float dl = query < T ? delta[(int64_t)bh * T + query] : 0.f;
+  f32x16 acc[HD / 32];
+#pragma unroll
+  for (int cb = 0; cb < HD / 32; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+
+  const int last_q = min(T, (qblk + 1) * 128) - 1;
+  const int n_tiles = last_q / BKV + 1;
+  auto issue = [&](int t) {
+    const uint32_t st = smem_off + (uint32_t)(t & 1) * (2 * kTile * 2);
+    issue_tile<BKV>(kbase, ld, t * BKV, T - 1, st, wave, lane);
+    issue_tile<BKV>(vbase, ld, t * BKV, T - 1, st + kTile * 2, wave, lane);
+  };
+  issue(0);
+  for (int t = 0; t < n_tiles; ++t) {
+    const int j0 = t * BKV;
+    wait_and_sync();
+    if (t + 1 < n_tiles) issue(t + 1);
+    if (j0 > q0 + 31) continue;
+    const bf16* Ks = smem + (t & 1) * (2 * kTile);
+    const bf16* Vs = Ks + kTile;
+    const bool diag = j0 + BKV - 1 > q0;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      f32x16 s = first_product(Ks, kb * 32, qf);      // S^T
+      f32x16 dp = first_product(Vs, kb * 32, gf);     // dP^T = V . dO^T
+      if (diag) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (j0 + kb * 32 + reg_row(r, half) > query) s[r] = -INFINITY;
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse2)) * (dp[r] - dl);
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) second_product(Ks, kb * 32 + b2 * 16, pack8(s, b2 * 8), acc);   // dQ^T += K^T . dS^T
+    }
+  }
+  if (query < T) store_row<HD>(dqkv + ((int64_t)b * T + query) * ld + h * HD, acc, scale);
+}
+
+// ===================================================================================================
+// dK, dV: block = 128 keys of one (batch, head); wave = 32 keys; query tiles of 64 (two 32-row halves)
+// ===================================================================================================
+__global__ __launch_bounds__(kNT) void attn_dkv_dma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
+                                                           const float* __restrict__ lse, const float* __restrict__ delta,
+                                                           bf16* __restrict__ dqkv, int T, int H) {
+  constexpr int BQ = 64;
+  constexpr int kTile = BQ * HD;
+  extern __shared__ __attribute__((aligned(1024))) bf16 smem[];          // [stage][Q | dO], then the statistics
+  float (*Ls)[BQ] = reinterpret_cast<float (*)[BQ]>(smem + 2 * 2 * kTile);
+  float (*Ds)[BQ] = Ls + 2;
+  const int d = H * HD;
+  const int64_t ld = 3 * (int64_t)d;
+  const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
+  const int kblk = blockIdx.x;                          // first key blocks see the most queries: they come first
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5;
+  const int k0 = kblk * 128 + wave * 32;
+  const int key = k0 + (lane & 31);
+  const bf16* qbase = qkv + (int64_t)b * T * ld + h * HD;
+  const bf16* gbase = dout + (int64_t)b * T * d + h * HD;
+  const float scale = 1.f / sqrtf((float)HD);
+  const float c2 = kLog2e * scale;
+  const uint32_t smem_off = (uint32_t)(uintptr_t)(lds_ptr)smem;
+
+  bf16x8 kf[HD / 16], vf[HD / 16];
+  load_row_frags<HD>(qbase + d, ld, k0, T, kf);
+  load_row_frags<HD>(qbase + 2 * d, ld, k0, T, vf);
+  f32x16 dk[HD / 32], dv[HD / 32];
+#pragma unroll
+  for (int cb = 0; cb < HD / 32; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      dk[cb][r] = 0.f;
+      dv[cb][r] = 0.f;
+    }
+
+  const int first_tile = (kblk * 128) / BQ;
+  const int n_tiles = (T + BQ - 1) / BQ;
+  auto issue = [&](int t) {
+    const uint32_t st = smem_off + (uint32_t)(t & 1) * (2 * kTile * 2);
+    issue_tile<BQ>(qbase, ld, t * BQ, T - 1, st, wave, lane);
+    issue_tile<BQ>(gbase, d, t * BQ, T - 1, st + kTile * 2, wave, lane);
+  };
+  // per-query statistics of a tile: fetched one tile ahead into registers by the first 64 threads
+  float l_next = 0.f, d_next = 0.f;
+  auto fetch_stats = [&](int t) {
+    if (threadIdx.x < BQ) {
+      const int i = t * BQ + threadIdx.x;
+      l_next = i < T ? lse[(int64_t)bh * T + i] * kLog2e : INFINITY;   // +inf: P = 0 for queries past the end
+      d_next = i < T ? delta[(int64_t)bh * T + i] : 0.f;
+    }
+  };
+  fetch_stats(first_tile);
+  issue(first_tile);
+  for (int t = first_tile; t < n_tiles; ++t) {
+    const int i0 = t * BQ;
+    if (threadIdx.x < BQ) {          // stage t&1 of the statistics was last read two tiles ago
+      Ls[t & 1][threadIdx.x] = l_next;
+      Ds[t & 1][threadIdx.x] = d_next;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the two LDS stores above are done before the barrier
+    wait_and_sync();
+    if (t + 1 < n_tiles) {
+      issue(t + 1);
+      fetch_stats(t + 1);
+    }
+    const bf16* Qs = smem + (t & 1) * (2 * kTile);
+    const bf16* Gs = Qs + kTile;
+#pragma unroll
+    for (int hb = 0; hb < 2; ++hb) {                     // the two 32-query halves of the tile
+      const int ib = i0 + hb * 32;
+      if (ib + 31 < k0) continue;                        // every query of this half precedes this wave's keys
+      f32x16 s = first_product(Qs, hb * 32, kf);         // S[query][key]
+      f32x16 dp = first_product(Gs, hb * 32, vf);        // dP = dO . V^T
+      if (ib < k0 + 31) {                                // diagonal: a key may not see an earlier query
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (key > ib + reg_row(r, half)) s[r] = -INFINITY;
+      }
+      f32x16 ds;
+#pragma unroll
+      for (int g = 0; g < 2; ++g)
+#pragma unroll
+        for (int v4 = 0; v4 < 2; ++v4) {
+          const int base = hb * 32 + 16 * g + 8 * half + 4 * v4;
+          const float4 lq = *reinterpret_cast<const float4*>(&Ls[t & 1][base]);
+          const float4 dq = *reinterpret_cast<const float4*>(&Ds[t & 1][base]);
+          const float lqa[4] = {lq.x, lq.y, lq.z, lq.w}, dqa[4] = {dq.x, dq.y, dq.z, dq.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = 8 * g + 4 * v4 + e;
+            const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lqa[e]));
+            s[r] = p;
+            ds[r] = p * (dp[r] - dqa[e]);
+          }
+        }
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) {
+        second_product(Gs, hb * 32 + b2 * 16, pack8(s, b2 * 8), dv);    // dV^T += dO^T . P
+        second_product(Qs, hb * 32 + b2 * 16, pack8(ds, b2 * 8), dk);   // dK^T += Q^T . dS
+      }
+    }
+  }
+  if (key < T) {
+    bf16* row = dqkv + ((int64_t)b * T + key) * ld + h * HD;
+    store_row<HD>(row + d, dk, scale);
+    store_row<HD>(row + 2 * d, dv, 1.f);
+  }
+}
+
+}  // namespace
+
+constexpr int kSmemTiles = 2 * 2 * 64 * HD * 2;          // two stages of two 64 x 128 bf16 tiles: 64 KiB
+constexpr int kSmemDkv = kSmemTiles + 4 * 64 * 4;        // + log-sum-exp and delta of two query tiles
+
+// Raises the dynamic-LDS limit of the three kernels (once; called at context creation, never inside a capture).
+hipError_t attention_dma_init() {
+  static bool done = false;
+  if (done) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd_dma_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kSmemTiles);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_dq_dma_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kSmemTiles);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_dkv_dma_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kSmemDkv);
+  if (e == hipSuccess) done = true;
+  return e;
+}
+
+hipError_t launch_attention_fwd_dma(hipStream_t s, const void* qkv, void* o, float* lse, int B, int T, int H) {
+  hipError_t e = attention_dma_init();
+  if (e != hipSuccess) return e;
+  dim3 grid((T + 127) / 128, B * H);
+  attn_fwd_dma_kernel<<<grid, kNT, kSmemTiles, s>>>((const bf16*)qkv, (bf16*)o, lse, T, H);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_dq_dkv_dma(hipStream_t s, const void* qkv, const void* dout, const float* lse,
+                                       const float* delta, void* dqkv, int B, int T, int H) {
+  hipError_t e = attention_dma_init();
+  if (e != hipSuccess) return e;
+  dim3 grid((T + 127) / 128, B * H);
+  attn_dq_dma_kernel<<<grid, kNT, kSmemTiles, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
+  attn_dkv_dma_kernel<<<grid, kNT, kSmemDkv, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
+  return hipGetLastError();
+}
+
+}  // namespace pw

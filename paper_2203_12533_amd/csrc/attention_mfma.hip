@@ -21,8 +21,11 @@
 //
 // Determinism: no atomics.  dQ is accumulated by the block that owns the queries, dK/dV by the block that
 // owns the keys, each over its tiles in ascending order (two kernels, S recomputed in both).
+#include "attention_common.hpp"
 #include "common.hpp"
 #include "kernels.hpp"
+
+#include <cstdlib>
 
 namespace pw {
 
@@ -32,14 +35,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kNT = 256;           // threads per block: 4 waves
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
-
-__device__ __forceinline__ int perm_row(int i) {   // [0-3, 8-11, 4-7, 12-15] within each 16
-  const int j = i & 15;
-  const int p = (j & 3) | ((j & 4) << 1) | ((j & 8) >> 1);
-  return (i & ~15) | p;
-}
 
 // One tile of ROWS rows x HD features, fetched as 4-row x 8-feature pieces.
 template <int ROWS, int HD>
@@ -105,24 +100,6 @@ struct Tile {
   }
 };
 
-// Fragments of 32 rows x HD features held in registers as the B operand of a first product:
-// lane l holds row (row0 + l%32), features kk*16 + 8*(l/32) .. +7 for every kk.  Rows >= limit read as zero.
-template <int HD>
-__device__ __forceinline__ void load_row_frags(const bf16* __restrict__ src, int64_t ld, int row0, int limit, bf16x8* frag) {
-  const int lane = threadIdx.x & 63;
-  const int row = row0 + (lane & 31);
-  const bf16* p = src + (int64_t)row * ld + (lane >> 5) * 8;
-#pragma unroll
-  for (int kk = 0; kk < HD / 16; ++kk) {
-    if (row < limit) {
-      frag[kk] = *reinterpret_cast<const bf16x8*>(p + kk * 16);
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) frag[kk][e] = (bf16)0.f;
-    }
-  }
-}
-
 // 32x32 block of a first product: A rows from a natural-layout LDS tile (permuted), B from register fragments.
 template <int HD, int LDN>
 __device__ __forceinline__ f32x16 first_product(const bf16* __restrict__ tile, int row_base, const bf16x8* bfrag) {
@@ -137,13 +114,6 @@ __device__ __forceinline__ f32x16 first_product(const bf16* __restrict__ tile, i
   return acc;
 }
 
-__device__ __forceinline__ bf16x8 pack8(const f32x16& v, int first) {
-  bf16x8 o;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) o[e] = (bf16)v[first + e];
-  return o;
-}
-
 // acc[cb] += T^T[feature block cb][rows kb*32 + 16 b ..] . frag   for a transposed LDS tile (ld = LDT)
 template <int HD, int LDT>
 __device__ __forceinline__ void second_product(const bf16* __restrict__ tile_tr, int row_base, const bf16x8& frag, f32x16* acc) {
@@ -152,24 +122,6 @@ __device__ __forceinline__ void second_product(const bf16* __restrict__ tile_tr,
 #pragma unroll
   for (int cb = 0; cb < HD / 32; ++cb)
     acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(a + cb * 32 * LDT), frag, acc[cb], 0, 0, 0);
-}
-
-// Tile-local row index that register r of this lane's D column stands for (see file header).
-__device__ __forceinline__ int reg_row(int r, int half) { return 16 * (r >> 3) + 8 * half + (r & 7); }
-
-// Writes acc (feature-major: register r of block cb = feature cb*32 + 8*(r/4) + 4*half + r%4) for this lane's
-// row to dst (row pointer, feature 0), scaled.
-template <int HD>
-__device__ __forceinline__ void store_row(bf16* __restrict__ dst, const f32x16* acc, float scale) {
-  const int half = (threadIdx.x & 63) >> 5;
-#pragma unroll
-  for (int cb = 0; cb < HD / 32; ++cb)
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      bf16x4 o = {(bf16)(acc[cb][q * 4] * scale), (bf16)(acc[cb][q * 4 + 1] * scale), (bf16)(acc[cb][q * 4 + 2] * scale),
-                  (bf16)(acc[cb][q * 4 + 3] * scale)};
-      *reinterpret_cast<bf16x4*>(dst + cb * 32 + q * 8 + half * 4) = o;
-    }
 }
 
 // ===================================================================================================
@@ -473,11 +425,27 @@ __global__ void attn_delta_kernel(const bf16* __restrict__ o, const bf16* __rest
 
 }  // namespace
 
+hipError_t attention_dma_init();
+hipError_t launch_attention_fwd_dma(hipStream_t s, const void* qkv, void* o, float* lse, int B, int T, int H);
+hipError_t launch_attention_dq_dkv_dma(hipStream_t s, const void* qkv, const void* dout, const float* lse, const float* delta,
+                                       void* dqkv, int B, int T, int H);
+
+// head_dim 128 runs the kernels of attention_dma.hip unless PW_ATTN_DMA=0 (A/B switch for measurements).
+static bool use_dma_kernels() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("PW_ATTN_DMA");
+    v = !(e && e[0] == '0');
+  }
+  return v != 0;
+}
+
 bool attention_mfma_supported(int T, int hd) { return T >= 1 && (hd == 64 || hd == 128); }
 
 hipError_t launch_attention_fwd_mfma(hipStream_t s, const void* qkv, void* o, float* lse, int B, int T, int H, int hd) {
   if (!qkv || !o || !lse || B <= 0 || T <= 0 || H <= 0 || (int64_t)B * H > 65535) return hipErrorInvalidValue;
   if (((uintptr_t)qkv | (uintptr_t)o) & 15) return hipErrorInvalidValue;
+  if (hd == 128 && use_dma_kernels()) return launch_attention_fwd_dma(s, qkv, o, lse, B, T, H);
   dim3 grid((T + 127) / 128, B * H);
   if (hd == 128)
     attn_fwd_kernel<128><<<grid, kNT, 0, s>>>((const bf16*)qkv, (bf16*)o, lse, T, H);
@@ -497,6 +465,12 @@ hipError_t launch_attention_bwd_mfma(hipStream_t s, const void* qkv, const void*
   const int64_t rows = (int64_t)B * T * H;
   const int64_t threads = rows * (hd / 8);
   dim3 grid((T + 127) / 128, B * H);
+  if (hd == 128 && use_dma_kernels()) {
+    attn_delta_kernel<128><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>((const bf16*)o, (const bf16*)dout, delta, T, H, rows);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_attention_dq_dkv_dma(s, qkv, dout, lse, delta, dqkv, B, T, H);
+  }
   if (hd == 128) {
     attn_delta_kernel<128><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>((const bf16*)o, (const bf16*)dout, delta, T, H, rows);
     attn_dq_kernel<128><<<grid, kNT, 0, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);

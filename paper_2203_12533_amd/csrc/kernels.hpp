@@ -62,6 +62,9 @@ hipError_t launch_attention_fwd(hipStream_t s, int dtype, const void* qkv, void*
 hipError_t launch_attention_bwd(hipStream_t s, int dtype, const void* qkv, const void* o, const void* dout,
                                 const float* lse, float* delta, void* dqkv, int B, int T, int H, int hd);
 
+// One-time set-up of the head_dim-128 attention kernels' dynamic-LDS limits; call once before any capture.
+hipError_t attention_dma_init();
+
 // gemm.hip
 hipError_t launch_gemm(hipStream_t s, const GemmArgs& a);
 // Timing of MFMA GEMM launches with HIP events on the launch stream (measurement aid).
