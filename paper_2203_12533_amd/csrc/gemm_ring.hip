@@ -22,6 +22,7 @@
 #include "common.hpp"
 #include "gemm_common.hpp"
 #include "kernels.hpp"
+#include <type_traits>
 
 namespace pw {
 
@@ -38,34 +39,31 @@ typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef const __attribute__((address_space(1))) void* gbl_ptr;
 typedef short short4v __attribute__((ext_vector_type(4)));
 
-// Issue this wave's share (4 x 1 KiB) of one operand tile's direct loads (32 instructions of 1 KiB per tile).
-//   base: operand; ld: leading dimension; row0: first tile row (m or n); k0: first k of the stage.
 // 16 bytes per lane from global memory straight into LDS at lds_off + 16*lane (lds_off: wave-uniform byte
 // offset).  Issued through inline assembly on purpose: the compiler then keeps no record of an LDS write in
 // flight, and so neither drains the vector-memory counter before unrelated LDS reads nor at barriers.  The
-// kernel waits for exactly the tile it needs with explicit s_waitcnt vmcnt(n) (see the main loop).
+// kernel waits for the tile it needs with an explicit s_waitcnt (see the main loop).
 __device__ __forceinline__ void dma16(const bf16* g, uint32_t lds_off) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_off) : "memory", "m0");
 }
 
+// One of this wave's four direct-load instructions (1 KiB each; 32 per operand tile, 4 per wave) of an operand tile.
+//   base: operand; ld: leading dimension; row0: first tile row (m or n); k0: first k of the stage; j: 0..3.
 template <bool KMAJOR>
-__device__ __forceinline__ void issue_operand(const bf16* __restrict__ base, int64_t ld, int64_t row0, int64_t k0,
-                                              uint32_t lds_tile_off, int wave, int lane) {
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int instr = wave * 4 + j;
-    const bf16* g;
-    if (!KMAJOR) {
-      const int r = instr * 8 + (lane >> 3);        // 8 rows x 128 bytes per instruction
-      const int c = (lane & 7) ^ ((r >> 1) & 7);
-      g = base + (row0 + r) * ld + k0 + c * 8;
-    } else {
-      const int k = instr * 2 + (lane >> 5);        // 2 k-rows x 512 bytes per instruction
-      const int c = (lane & 31) ^ (4 * (k & 3));
-      g = base + (k0 + k) * ld + row0 + c * 8;
-    }
-    dma16(g, lds_tile_off + instr * 1024);
+__device__ __forceinline__ void issue_one(const bf16* __restrict__ base, int64_t ld, int64_t row0, int64_t k0,
+                                          uint32_t lds_tile_off, int wave, int lane, int j) {
+  const int instr = wave * 4 + j;
+  const bf16* g;
+  if (!KMAJOR) {
+    const int r = instr * 8 + (lane >> 3);        // 8 rows x 128 bytes per instruction
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    g = base + (row0 + r) * ld + k0 + c * 8;
+  } else {
+    const int k = instr * 2 + (lane >> 5);        // 2 k-rows x 512 bytes per instruction
+    const int c = (lane & 31) ^ (4 * (k & 3));
+    g = base + (k0 + k) * ld + row0 + c * 8;
   }
+  dma16(g, lds_tile_off + instr * 1024);
 }
 
 // One MFMA operand fragment (rows frag_row0 .. +31 of the tile, k16 step kk) for this lane.
@@ -109,46 +107,88 @@ __global__ __launch_bounds__(kRThreads) void gemm_ring_kernel(GemmBf16Params p) 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int64_t kt_total = p.K / kRBK;
+  const int kt_total = (int)(p.K / kRBK);
   const uint32_t smem_off = (uint32_t)(uintptr_t)(lds_ptr)smem;   // byte offset of the ring inside LDS
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-  auto issue = [&](int64_t kt) {
+  // idx 0..3: A tile instructions, 4..7: B tile instructions of k-tile kt
+  auto issue_idx = [&](int kt, int idx) {
     const uint32_t stage = smem_off + (uint32_t)(kt % kRStages) * (kRStage * 2);
-    issue_operand<A_KMAJOR>(p.A, p.lda, m0, kt * kRBK, stage, wave_s, lane);
-    issue_operand<B_KMAJOR>(p.B, p.ldb, n0, kt * kRBK, stage + kROperand * 2, wave_s, lane);
+    if (idx < 4) issue_one<A_KMAJOR>(p.A, p.lda, m0, (int64_t)kt * kRBK, stage, wave_s, lane, idx);
+    else issue_one<B_KMAJOR>(p.B, p.ldb, n0, (int64_t)kt * kRBK, stage + kROperand * 2, wave_s, lane, idx - 4);
   };
-  auto load_frags = [&](const bf16* a_tile, const bf16* b_tile, int kk, bf16x8* af, bf16x8* bfr) {
+  auto load_frags = [&](int stage, int kk, bf16x8* af, bf16x8* bfr) {
+    const bf16* a_tile = smem + stage * kRStage;
+    const bf16* b_tile = a_tile + kROperand;
 #pragma unroll
     for (int i = 0; i < FM; ++i) af[i] = read_fragment<A_KMAJOR>(a_tile, wm * 128 + i * 32, kk, lane);
 #pragma unroll
     for (int j = 0; j < FN; ++j) bfr[j] = read_fragment<B_KMAJOR>(b_tile, wn * 64 + j * 32, kk, lane);
   };
-  issue(0);
-  for (int64_t kt = 0; kt < kt_total; ++kt) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's share of tile kt has landed
-    // Bare barrier (no fence): tile kt is now visible to all waves, and every wave has consumed tile kt-1 (its
-    // MFMAs were issued, hence its LDS reads had returned), so that stage may be overwritten.
+  auto wait_and_sync = [&]() {
+    // all of this wave's LDS reads and its share of the tile in flight are complete ...
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    // ... and after the (bare, fence-less) barrier so are everyone else's: the tile in flight is visible and
+    // the stage just consumed may be overwritten.
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (kt + 1 < kt_total) issue(kt + 1);
-    const bf16* a_tile = smem + (kt % kRStages) * kRStage;
-    const bf16* b_tile = a_tile + kROperand;
-    // Fragments are double-buffered in registers: the LDS reads of k-step kk+1 are issued before the MFMAs
-    // of k-step kk, so their latency hides behind 8 MFMAs instead of stalling every second one.
-    bf16x8 af[2][FM], bfr[2][FN];
-    load_frags(a_tile, b_tile, 0, af[0], bfr[0]);
+  };
+
+  // The MFMA stream runs across k-tiles without a gap.  Fragments are double-buffered in registers (the LDS
+  // reads of k-step kk+1 are issued before the MFMAs of k-step kk).  The one barrier per k-tile sits in front
+  // of the MFMAs of the LAST k-step: by then every wave has finished reading the current stage, so behind the
+  // barrier the first fragments of the next tile are fetched and the direct loads of the tile after next are
+  // issued between those last MFMAs.
 #pragma unroll
-    for (int kk = 0; kk < kRBK / 16; ++kk) {
-      if (kk + 1 < kRBK / 16) load_frags(a_tile, b_tile, kk + 1, af[(kk + 1) & 1], bfr[(kk + 1) & 1]);
+  for (int idx = 0; idx < 8; ++idx) issue_idx(0, idx);
+  wait_and_sync();
+  if (kt_total > 1) {
+#pragma unroll
+    for (int idx = 0; idx < 8; ++idx) issue_idx(1, idx);
+  }
+  bf16x8 af[2][FM], bfr[2][FN];
+  load_frags(0, 0, af[0], bfr[0]);
+  constexpr int KS = kRBK / 16;   // 4 k-steps per tile
+  // One k-tile.  MORE: another tile follows (already in flight); MORE2: the one after that exists and is issued here.
+  auto k_tile = [&](int kt, auto more, auto more2) {
+    const int stage = kt & 1;
+#pragma unroll
+    for (int kk = 0; kk < KS - 1; ++kk) {
+      // k-step 0 starts with one MFMA on fragments fetched during the previous tile, so that the wait for
+      // those does not also cover the reads issued here.
+      if (kk == 0) {
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[0][0], af[0][0], acc[0][0], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      load_frags(stage, kk + 1, af[(kk + 1) & 1], bfr[(kk + 1) & 1]);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+          if (kk != 0 || i != 0 || j != 0)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
-  }
+    if constexpr (decltype(more)::value) {
+      wait_and_sync();
+      load_frags(stage ^ 1, 0, af[0], bfr[0]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[(KS - 1) & 1][j], af[(KS - 1) & 1][i], acc[i][j], 0, 0, 0);
+        if constexpr (decltype(more2)::value) issue_idx(kt + 2, i * FN + j);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+  };
+  using yes = std::integral_constant<bool, true>;
+  using no = std::integral_constant<bool, false>;
+  int kt = 0;
+  for (; kt + 2 < kt_total; ++kt) k_tile(kt, yes{}, yes{});
+  if (kt + 1 < kt_total) { k_tile(kt, yes{}, no{}); ++kt; }
+  k_tile(kt, no{}, no{});
   gemm_epilogue_staged<FM, FN, false>(smem, acc, p, m0 + wm * 128, n0 + wn * 64, wave, lane);
 }
 
