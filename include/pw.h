@@ -235,6 +235,11 @@ typedef struct {
 /* C[M,N] = op(A)[M,K] . op(B)[K,N] with fp32 accumulation and a fused epilogue.  bf16 operands run on
  * MFMA; they need K, lda, ldb multiples of 8 and 16-byte aligned pointers. */
 pw_status pw_op_gemm(pw_ctx* ctx, const pw_gemm_args* args);
+/* Two independent GEMMs (their outputs must not overlap each other or any operand).  Same results as two
+ * pw_op_gemm calls; when both are full-tile bf16 problems of one operand layout that would each leave
+ * compute units idle - the attention weight gradients of one layer, section 5.3's Transformer layers - their
+ * tiles run side by side in one launch.  Nothing is enqueued if either argument set is invalid. */
+pw_status pw_op_gemm_pair(pw_ctx* ctx, const pw_gemm_args* args0, const pw_gemm_args* args1);
 /* x[b*T+t,:] = wte[tok[b*(T+1)+t],:] + wpe[t,:]  (fp32 in, fp32 out; exact). */
 pw_status pw_op_embedding_fwd(pw_ctx* ctx, const int32_t* tokens, const float* wte, const float* wpe,
                               float* x, int B, int T, int d, int V);

@@ -103,6 +103,7 @@ _SIGS = {
     "pw_profile_begin": (C.c_int, [C.c_void_p]),
     "pw_profile_end": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "pw_op_gemm": (C.c_int, [C.c_void_p, C.POINTER(GemmArgs)]),
+    "pw_op_gemm_pair": (C.c_int, [C.c_void_p, C.POINTER(GemmArgs), C.POINTER(GemmArgs)]),
     "pw_op_embedding_fwd": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4 + [C.c_int] * 4),
     "pw_op_embedding_bwd": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4 + [C.c_int] * 4),
     "pw_op_layernorm_fwd": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 6 + [C.c_int] * 2),
@@ -312,6 +313,13 @@ class Context:
         for k, v in kw.items():
             setattr(a, k, v)
         self._check(lib().pw_op_gemm(self._h, C.byref(a)))
+
+    def gemm_pair(self, kw0: dict, kw1: dict):
+        a0, a1 = GemmArgs(), GemmArgs()
+        for a, kw in ((a0, kw0), (a1, kw1)):
+            for k, v in kw.items():
+                setattr(a, k, v)
+        self._check(lib().pw_op_gemm_pair(self._h, C.byref(a0), C.byref(a1)))
 
 
 def lm_config_c(cfg) -> LMConfigC:

@@ -373,7 +373,9 @@ hipError_t launch_gemm(hipStream_t s, const GemmArgs& a) {
   return e;
 }
 
-static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a) {
+// Argument checks shared by every path; *empty is set when there is nothing to compute.
+static hipError_t check_gemm_args(const GemmArgs& a, bool* empty) {
+  *empty = false;
   if (!a.A || !a.B || !a.C || a.M < 0 || a.N < 0 || a.K < 0) return hipErrorInvalidValue;
   if (a.epilogue < kEpiStore || a.epilogue > kEpiGeluBwd) return hipErrorInvalidValue;
   if (a.lda < (a.a_kmajor ? a.M : a.K) || a.ldb < (a.b_kmajor ? a.N : a.K) || a.ldc < a.N) return hipErrorInvalidValue;
@@ -382,9 +384,25 @@ static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a) {
   if (a.accumulate && (a.out_dtype != kF32 || a.epilogue != kEpiStore)) return hipErrorInvalidValue;
   if (a.epilogue == kEpiBiasResidual && a.out_dtype != kF32) return hipErrorInvalidValue;
   if (a.out_dtype == kBF16 && a.dtype != kBF16) return hipErrorInvalidValue;
-  if (a.M == 0 || a.N == 0) return hipSuccess;
+  if (a.M == 0 || a.N == 0) { *empty = true; return hipSuccess; }
   if (a.M > (1LL << 30) || a.N > (1LL << 30) || a.K > (1LL << 30)) return hipErrorInvalidValue;
+  if (a.dtype == kF32) {
+    if (a.out_dtype != kF32) return hipErrorInvalidValue;
+    // vector epilogue accesses need 16-byte alignment; the kernel falls back to scalars when ldc % 4 != 0
+    if (((uintptr_t)a.C | (uintptr_t)a.C2 | (uintptr_t)a.aux | (uintptr_t)a.bias) & 15) return hipErrorInvalidValue;
+    return hipSuccess;
+  }
+  if (a.dtype != kBF16) return hipErrorInvalidValue;
+  // 16-byte vector loads: every row start and every k offset of a piece must be 16-byte aligned
+  if ((a.K % 8) || (a.lda % 8) || (a.ldb % 8)) return hipErrorInvalidValue;
+  if ((a.a_kmajor && a.M % 8) || (a.b_kmajor && a.N % 8)) return hipErrorInvalidValue;
+  if (((uintptr_t)a.A | (uintptr_t)a.B) & 15) return hipErrorInvalidValue;
+  if (((uintptr_t)a.C | (uintptr_t)a.C2 | (uintptr_t)a.aux | (uintptr_t)a.bias) & 15) return hipErrorInvalidValue;
+  if (a.ldc % 8) return hipErrorInvalidValue;
+  return hipSuccess;
+}
 
+static EpiParams epi_of(const GemmArgs& a) {
   EpiParams e;
   e.mode = a.epilogue;
   e.out_bf16 = a.out_dtype == kBF16;
@@ -394,56 +412,90 @@ static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a) {
   e.C = a.C;
   e.C2 = a.C2;
   e.ldc = a.ldc;
+  return e;
+}
+
+static GemmBf16Params bf16_params_of(const GemmArgs& a, int tile) {
+  GemmBf16Params p;
+  p.A = (const bf16*)a.A;
+  p.B = (const bf16*)a.B;
+  p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb;
+  p.tiles_m = (int)((a.M + tile - 1) / tile);
+  p.tiles_n = (int)((a.N + tile - 1) / tile);
+  p.epi = epi_of(a);
+  return p;
+}
+
+// The ring-buffered kernel takes full 256 x 256 tiles only.
+static bool ring_eligible(const GemmArgs& a) {
+  return g_use_ring && a.dtype == kBF16 && gemm_ring_supported(a.M, a.N, a.K);
+}
+
+static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a) {
+  bool empty;
+  hipError_t err = check_gemm_args(a, &empty);
+  if (err != hipSuccess || empty) return err;
 
   if (a.dtype == kF32) {
-    if (a.out_dtype != kF32) return hipErrorInvalidValue;
-    // vector epilogue accesses need 16-byte alignment; the kernel falls back to scalars when ldc % 4 != 0
-    if (((uintptr_t)a.C | (uintptr_t)a.C2 | (uintptr_t)a.aux | (uintptr_t)a.bias) & 15) return hipErrorInvalidValue;
     GemmF32Params p;
     p.A = (const float*)a.A;
     p.B = (const float*)a.B;
     p.M = a.M; p.N = a.N; p.K = a.K;
     p.sam = a.a_kmajor ? 1 : a.lda; p.sak = a.a_kmajor ? a.lda : 1;
     p.sbn = a.b_kmajor ? 1 : a.ldb; p.sbk = a.b_kmajor ? a.ldb : 1;
-    p.epi = e;
+    p.epi = epi_of(a);
     dim3 grid((unsigned)((a.N + 63) / 64), (unsigned)((a.M + 63) / 64));
     if (grid.y > 65535) return hipErrorInvalidValue;
     gemm_f32_kernel<<<grid, 256, 0, s>>>(p);
     return hipGetLastError();
   }
-  if (a.dtype != kBF16) return hipErrorInvalidValue;
-  // 16-byte vector loads: every row start and every k offset of a piece must be 16-byte aligned
-  if ((a.K % 8) || (a.lda % 8) || (a.ldb % 8)) return hipErrorInvalidValue;
-  if ((a.a_kmajor && a.M % 8) || (a.b_kmajor && a.N % 8)) return hipErrorInvalidValue;
-  if (((uintptr_t)a.A | (uintptr_t)a.B) & 15) return hipErrorInvalidValue;
-  if (((uintptr_t)a.C | (uintptr_t)a.C2 | (uintptr_t)a.aux | (uintptr_t)a.bias) & 15) return hipErrorInvalidValue;
-  if (a.ldc % 8) return hipErrorInvalidValue;
-
-  GemmBf16Params p;
-  p.A = (const bf16*)a.A;
-  p.B = (const bf16*)a.B;
-  p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb;
-  p.epi = e;
   // Full 256x256 tiles with enough of them to fill the chip: the ring-buffered kernel.
-  if (g_use_ring && gemm_ring_supported(a.M, a.N, a.K) && (a.M / 256) * (a.N / 256) >= 150) {
-    p.tiles_m = (int)(a.M / 256);
-    p.tiles_n = (int)(a.N / 256);
-    return launch_gemm_ring(s, p, a.a_kmajor, a.b_kmajor);
-  }
+  if (ring_eligible(a) && (a.M / 256) * (a.N / 256) >= 150)
+    return launch_gemm_ring(s, bf16_params_of(a, 256), a.a_kmajor, a.b_kmajor);
   // Tile choice: 256x256 when that still yields at least one workgroup per CU; otherwise 128x128.
   const int64_t big_tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-  const bool use_big = big_tiles >= 150;
-  if (use_big) {
-    p.tiles_m = (int)((a.M + 255) / 256);
-    p.tiles_n = (int)((a.N + 255) / 256);
+  if (big_tiles >= 150) {
     const bool edge = (a.M % 256) || (a.N % 256) || (a.K % kBK);
-    return launch_bf16_tile<256, 256, PW_WM, PW_WN>(s, p, a.a_kmajor, a.b_kmajor, edge);
+    return launch_bf16_tile<256, 256, PW_WM, PW_WN>(s, bf16_params_of(a, 256), a.a_kmajor, a.b_kmajor, edge);
   }
-  p.tiles_m = (int)((a.M + 127) / 128);
-  p.tiles_n = (int)((a.N + 127) / 128);
+  const GemmBf16Params p = bf16_params_of(a, 128);
   if ((int64_t)p.tiles_m * p.tiles_n > (1 << 24)) return hipErrorInvalidValue;
   const bool edge = (a.M % 128) || (a.N % 128) || (a.K % kBK);
   return launch_bf16_tile<128, 128, 2, 2>(s, p, a.a_kmajor, a.b_kmajor, edge);
+}
+
+// Two independent GEMMs.  When both are ring-kernel problems of one operand layout and together fill at least
+// most of the chip, they share a single launch (their tiles run side by side); otherwise one launch each.
+hipError_t launch_gemm_pair(hipStream_t s, const GemmArgs& a0, const GemmArgs& a1) {
+  bool e0, e1;
+  hipError_t err = check_gemm_args(a0, &e0);
+  if (err == hipSuccess) err = check_gemm_args(a1, &e1);
+  if (err != hipSuccess) return err;
+  const bool pairable = !e0 && !e1 && ring_eligible(a0) && ring_eligible(a1) && a0.a_kmajor == a1.a_kmajor &&
+                        a0.b_kmajor == a1.b_kmajor;
+  const int64_t t0 = (a0.M / 256) * (a0.N / 256), t1 = (a1.M / 256) * (a1.N / 256);
+  // worth it only if at least one of the two would leave part of the chip idle (or miss the ring kernel) alone
+  if (!pairable || t0 + t1 < 150 || t0 + t1 > (1 << 20) || (t0 % 256 == 0 && t1 % 256 == 0)) {
+    err = launch_gemm(s, a0);
+    return err == hipSuccess ? launch_gemm(s, a1) : err;
+  }
+  const bool timed = g_profile_on;
+  ProfiledLaunch pl{nullptr, nullptr, 2.0 * ((double)a0.M * (double)a0.N * (double)a0.K + (double)a1.M * (double)a1.N * (double)a1.K)};
+  if (timed) {
+    pl.start = profile_event();
+    pl.stop = profile_event();
+    if (!pl.start || !pl.stop) return hipErrorOutOfMemory;
+    err = hipEventRecord(pl.start, s);
+    if (err != hipSuccess) return err;
+  }
+  // the larger problem's workgroups first
+  const bool swap = t1 > t0;
+  err = launch_gemm_ring_pair(s, bf16_params_of(swap ? a1 : a0, 256), bf16_params_of(swap ? a0 : a1, 256), a0.a_kmajor, a0.b_kmajor);
+  if (timed && err == hipSuccess) {
+    err = hipEventRecord(pl.stop, s);
+    if (err == hipSuccess) g_profile.push_back(pl);
+  }
+  return err;
 }
 
 }  // namespace pw

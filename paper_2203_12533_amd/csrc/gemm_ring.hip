@@ -89,11 +89,11 @@ __device__ __forceinline__ bf16x8 read_fragment(const bf16* lds_tile, int frag_r
   }
 }
 
+// One 256 x 256 output tile of problem p; pid: index of the tile's workgroup among the problem's own.
 template <bool A_KMAJOR, bool B_KMAJOR>
-__global__ __launch_bounds__(kRThreads) void gemm_ring_kernel(GemmBf16Params p) {
-  extern __shared__ __attribute__((aligned(16))) bf16 smem[];
+__device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16* smem) {
   int tm, tn;
-  tile_of_block(blockIdx.x, p.tiles_m * p.tiles_n, p.tiles_m, p.tiles_n, tm, tn);
+  tile_of_block(pid, p.tiles_m * p.tiles_n, p.tiles_m, p.tiles_n, tm, tn);
   const int64_t m0 = (int64_t)tm * kRT, n0 = (int64_t)tn * kRT;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 2, wn = wave & 3;            // 2 x 4 waves, wave tile 128 x 64
@@ -192,6 +192,23 @@ __global__ __launch_bounds__(kRThreads) void gemm_ring_kernel(GemmBf16Params p) 
   gemm_epilogue_staged<FM, FN, false>(smem, acc, p, m0 + wm * 128, n0 + wn * 64, wave, lane);
 }
 
+template <bool A_KMAJOR, bool B_KMAJOR>
+__global__ __launch_bounds__(kRThreads) void gemm_ring_kernel(GemmBf16Params p) {
+  extern __shared__ __attribute__((aligned(16))) bf16 smem[];
+  ring_tile<A_KMAJOR, B_KMAJOR>(p, blockIdx.x, smem);
+}
+
+// Two independent problems of the same operand layout in one launch: workgroups [0, tiles of p0) work on p0,
+// the rest on p1.  Lets two GEMMs that each fill only part of the chip share one round of workgroups.
+template <bool A_KMAJOR, bool B_KMAJOR>
+__global__ __launch_bounds__(kRThreads) void gemm_ring_pair_kernel(GemmBf16Params p0, GemmBf16Params p1) {
+  extern __shared__ __attribute__((aligned(16))) bf16 smem[];
+  const int t0 = p0.tiles_m * p0.tiles_n;
+  const bool first = (int)blockIdx.x < t0;
+  const GemmBf16Params p = first ? p0 : p1;
+  ring_tile<A_KMAJOR, B_KMAJOR>(p, first ? (int)blockIdx.x : (int)blockIdx.x - t0, smem);
+}
+
 constexpr size_t kRSmemBytes = (size_t)kRStages * kRStage * sizeof(bf16);   // 128 KiB
 static_assert(kRSmemBytes >= 8 * 32 * 68 * 4, "epilogue staging must fit");
 
@@ -213,7 +230,27 @@ hipError_t launch_ring_variant(hipStream_t s, const GemmBf16Params& p) {
   return hipGetLastError();
 }
 
+template <bool AK, bool BK_>
+hipError_t launch_ring_pair_variant(hipStream_t s, const GemmBf16Params& p0, const GemmBf16Params& p1) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_pair_kernel<AK, BK_>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRSmemBytes);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  gemm_ring_pair_kernel<AK, BK_><<<p0.tiles_m * p0.tiles_n + p1.tiles_m * p1.tiles_n, kRThreads, kRSmemBytes, s>>>(p0, p1);
+  return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_gemm_ring_pair(hipStream_t s, const GemmBf16Params& p0, const GemmBf16Params& p1, bool ak, bool bk) {
+  if (!ak && !bk) return launch_ring_pair_variant<false, false>(s, p0, p1);
+  if (!ak && bk) return launch_ring_pair_variant<false, true>(s, p0, p1);
+  if (ak && bk) return launch_ring_pair_variant<true, true>(s, p0, p1);
+  return launch_ring_pair_variant<true, false>(s, p0, p1);
+}
 
 bool gemm_ring_supported(int64_t M, int64_t N, int64_t K) { return M % kRT == 0 && N % kRT == 0 && K % kRBK == 0 && K >= kRBK; }
 
@@ -229,7 +266,7 @@ hipError_t gemm_ring_init() {
   if (e == hipSuccess) e = prepare_ring_variant<false, true>();
   if (e == hipSuccess) e = prepare_ring_variant<true, true>();
   if (e == hipSuccess) e = prepare_ring_variant<true, false>();
-  return e;
+  return e;   // the pair kernels set their attribute on first use
 }
 
 }  // namespace pw

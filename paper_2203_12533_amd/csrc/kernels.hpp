@@ -67,6 +67,8 @@ hipError_t attention_dma_init();
 
 // gemm.hip
 hipError_t launch_gemm(hipStream_t s, const GemmArgs& a);
+// Two independent GEMMs; shares one launch between them when that fills the chip better (same results either way).
+hipError_t launch_gemm_pair(hipStream_t s, const GemmArgs& a0, const GemmArgs& a1);
 // Timing of MFMA GEMM launches with HIP events on the launch stream (measurement aid).
 void gemm_profile_begin();
 hipError_t gemm_profile_end(int64_t* launches, double* total_ms, double* total_flops);

@@ -150,7 +150,7 @@ hipError_t gemm_dgrad(Model* m, const void* dy, int64_t wi, int64_t N, int64_t i
   return launch_gemm(m->stream, a);
 }
 // dW[in, out] (=|+=) x^T[in, N] . dy[N, out]
-hipError_t gemm_wgrad(Model* m, const void* x, const void* dy, int64_t wi, int64_t N, int64_t in, int64_t out, int accumulate) {
+GemmArgs wgrad_args(Model* m, const void* x, const void* dy, int64_t wi, int64_t N, int64_t in, int64_t out, int accumulate) {
   GemmArgs a{};
   a.dtype = m->act_dtype();
   a.a_kmajor = 1;                      // x [N, in]: stored [k = N][m = in]
@@ -158,7 +158,10 @@ hipError_t gemm_wgrad(Model* m, const void* x, const void* dy, int64_t wi, int64
   a.M = in; a.N = out; a.K = N; a.lda = in; a.ldb = out; a.ldc = out;
   a.epilogue = kEpiStore; a.out_dtype = kF32; a.accumulate = accumulate;
   a.A = x; a.B = dy; a.C = m->g + P(m, wi).offset;
-  return launch_gemm(m->stream, a);
+  return a;
+}
+hipError_t gemm_wgrad(Model* m, const void* x, const void* dy, int64_t wi, int64_t N, int64_t in, int64_t out, int accumulate) {
+  return launch_gemm(m->stream, wgrad_args(m, x, dy, wi, N, in, out, accumulate));
 }
 
 size_t layer_base(const Model* m, int l) { return (m->cfg.has_embed ? 2 : 0) + (size_t)l * 12; }
@@ -207,13 +210,16 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate) {
                                 m->ws, N, d, accumulate), "ln2 bwd");
     dx_op = c.bf16 ? m->dx_lp : (const void*)m->dx_b;
     // out-proj: x_mid = x_in + o Wo + bo
-    PW_TRY(gemm_wgrad(m, A.o, dx_op, e + 4, N, d, d, accumulate), "out-proj wgrad");
+    // (its weight gradient is computed together with the QKV one below: neither fills the chip alone)
+    const void* dy_out = dx_op;
     PW_TRY(launch_colsum(m->stream, kF32, m->dx_b, g + P(m, e + 5).offset, m->ws, N, d, accumulate), "bo grad");
     PW_TRY(gemm_dgrad(m, dx_op, e + 4, N, d, d, kEpiStore, nullptr, m->d_small), "out-proj dgrad");
     PW_TRY(launch_attention_bwd(m->stream, dt, A.qkv, A.o, m->d_small, A.lse, m->delta, m->d_qkv, c.batch, c.seq,
                                 c.n_head, m->hd()), "attention bwd");
     // QKV: qkv = a Wqkv + bqkv
-    PW_TRY(gemm_wgrad(m, A.a, m->d_qkv, e + 2, N, d, 3 * d, accumulate), "qkv wgrad");
+    // (dy_out, the bf16 residual gradient, stays intact until the LN1 backward below rewrites it)
+    PW_TRY(launch_gemm_pair(m->stream, wgrad_args(m, A.a, m->d_qkv, e + 2, N, d, 3 * d, accumulate),
+                            wgrad_args(m, A.o, dy_out, e + 4, N, d, d, accumulate)), "qkv + out-proj wgrad");
     PW_TRY(launch_colsum(m->stream, dt, m->d_qkv, g + P(m, e + 3).offset, m->ws, N, 3 * d, accumulate), "bqkv grad");
     PW_TRY(gemm_dgrad(m, m->d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small), "qkv dgrad");
     // LN1 and the residual branch: dx_a = dx_b + LN1'(d_small)

@@ -975,6 +975,18 @@ pw_status pw_op_gemm(pw_ctx* c, const pw_gemm_args* a) {
   g.A = a->A; g.B = a->B; g.bias = a->bias; g.aux = a->aux; g.C = a->C; g.C2 = a->C2;
   PW_OP(c, launch_gemm(c->exec, g));
 }
+static GemmArgs gemm_args_of(const pw_gemm_args* a) {
+  GemmArgs g{};
+  g.dtype = a->dtype; g.a_kmajor = a->a_kmajor; g.b_kmajor = a->b_kmajor;
+  g.M = a->M; g.N = a->N; g.K = a->K; g.lda = a->lda; g.ldb = a->ldb; g.ldc = a->ldc;
+  g.epilogue = a->epilogue; g.out_dtype = a->out_dtype; g.accumulate = a->accumulate;
+  g.A = a->A; g.B = a->B; g.bias = a->bias; g.aux = a->aux; g.C = a->C; g.C2 = a->C2;
+  return g;
+}
+pw_status pw_op_gemm_pair(pw_ctx* c, const pw_gemm_args* a0, const pw_gemm_args* a1) {
+  if (!c || !a0 || !a1) return PW_ERR_INVALID;
+  PW_OP(c, launch_gemm_pair(c->exec, gemm_args_of(a0), gemm_args_of(a1)));
+}
 pw_status pw_op_embedding_fwd(pw_ctx* c, const int32_t* tokens, const float* wte, const float* wpe, float* x, int B, int T, int d, int V) {
   PW_OP(c, launch_embedding_fwd(c->exec, tokens, wte, wpe, x, B, T, d, V));
 }

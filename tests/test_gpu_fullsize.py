@@ -62,6 +62,32 @@ def test_dgrad_and_wgrad_gemms_at_cfg3_shape(ctx, orc, name, n_in, k_out):
     assert rel_l2(host(dw[cols]), rdw) < 1e-5
 
 
+def test_paired_attention_weight_gradients_at_cfg3_shape(ctx, orc):
+    """dWqkv = a^T . dqkv and dWo = o^T . dy in one launch (192 + 64 tiles = one workgroup per compute unit),
+    against the oracle on sampled rows, and in agreement with the two single launches everywhere (the single
+    out-projection launch takes another tile shape, so its summation order differs)."""
+    a, dqkv = _bf16_randn((N, D), 11), _bf16_randn((N, 3 * D), 12)
+    o, dy = _bf16_randn((N, D), 13), _bf16_randn((N, D), 14)
+    def args(x, g, out, n_out):
+        return dict(dtype=pwb.PW_BF16, a_kmajor=1, b_kmajor=1, M=D, N=n_out, K=N, lda=D, ldb=n_out, ldc=n_out,
+                    epilogue=pwb.PW_EPI_STORE, out_dtype=pwb.PW_F32, accumulate=0, A=ptr(x), B=ptr(g), C=ptr(out))
+    dwqkv = torch.full((D, 3 * D), float("nan"), device="cuda")
+    dwo = torch.full((D, D), float("nan"), device="cuda")
+    ctx.gemm_pair(args(a, dqkv, dwqkv, 3 * D), args(o, dy, dwo, D))
+    one_qkv, one_o = torch.empty_like(dwqkv), torch.empty_like(dwo)
+    ctx.gemm(**args(a, dqkv, one_qkv, 3 * D))
+    ctx.gemm(**args(o, dy, one_o, D))
+    ctx.synchronize()
+    cols = np.array([0, 9, 255, 256, 1031, D - 1])
+    _, want, _ = orc.linear_bwd(host(a[:, cols]), np.zeros((len(cols), 3 * D)), host(dqkv))
+    assert rel_l2(host(dwqkv[cols]), want) < 1e-5
+    _, want, _ = orc.linear_bwd(host(o[:, cols]), np.zeros((len(cols), D)), host(dy))
+    assert rel_l2(host(dwo[cols]), want) < 1e-5
+    assert rel_l2(host(one_o[cols]), want) < 1e-5
+    assert torch.isfinite(dwqkv).all() and torch.isfinite(dwo).all()
+    assert rel_l2(host(dwqkv), host(one_qkv)) < 1e-6 and rel_l2(host(dwo), host(one_o)) < 1e-6
+
+
 def test_attention_at_cfg3_shape(ctx, orc):
     B, hd = CFG3.batch, CFG3.head_dim
     qkv = _bf16_randn((N, 3 * D), 6)

@@ -104,6 +104,30 @@ def test_gemm_fused_epilogues(ctx, orc, bf16):
     assert rel_l2(host(du), orc.gelu_bwd(prev, nobias)) < tol
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_gemm_pair_small_problems_and_rejection(ctx, orc, bf16):
+    """Two problems that do not qualify for a shared launch still give both results; one bad argument set
+    means neither runs."""
+    (M0, N0, K0), (M1, N1, K1) = (136, 72, 64), (40, 264, 200)
+    x0, x0v = dev_act(_rand(20, (M0, K0)), bf16)
+    w0, w0v = dev_act(_rand(21, (K0, N0), 0.1), bf16)
+    x1, x1v = dev_act(_rand(22, (M1, K1)), bf16)
+    w1, w1v = dev_act(_rand(23, (K1, N1), 0.1), bf16)
+    c0 = torch.full((M0, N0), 7.0, device="cuda")
+    c1 = torch.full((M1, N1), 7.0, device="cuda")
+    def args(x, w, c, M, N, K):
+        return dict(dtype=DT[bf16], a_kmajor=0, b_kmajor=1, M=M, N=N, K=K, lda=K, ldb=N, ldc=N,
+                    epilogue=pwb.PW_EPI_STORE, out_dtype=pwb.PW_F32, accumulate=0, A=ptr(x), B=ptr(w), C=ptr(c))
+    with pytest.raises(pwb.PwError):
+        ctx.gemm_pair(args(x0, w0, c0, M0, N0, K0), {**args(x1, w1, c1, M1, N1, K1), "ldb": 8})
+    ctx.synchronize()
+    assert (host(c0) == 7.0).all() and (host(c1) == 7.0).all()
+    ctx.gemm_pair(args(x0, w0, c0, M0, N0, K0), args(x1, w1, c1, M1, N1, K1))
+    ctx.synchronize()
+    assert rel_l2(host(c0), orc.linear_fwd(x0v, w0v)) < 2e-6
+    assert rel_l2(host(c1), orc.linear_fwd(x1v, w1v)) < 2e-6
+
+
 def test_gemm_rejects_what_the_kernel_cannot_take(ctx):
     a = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
     c = torch.zeros(64 * 64, dtype=torch.float32, device="cuda")
