@@ -251,11 +251,13 @@ pw_status pw_op_embedding_bwd(pw_ctx* ctx, const int32_t* tokens, const float* d
 pw_status pw_op_layernorm_fwd(pw_ctx* ctx, int dtype, const float* x, const float* g, const float* b,
                               void* y, float* mean, float* rstd, int N, int d);
 /* dx(f32) = (dres ? dres : 0) + LayerNorm-backward(dy); dx_lp (optional) receives dx in `dtype`;
- * dg, db fp32 [d] (overwritten, or added into when accumulate = 1).  ws: fp32 workspace of
+ * dg, db fp32 [d] (overwritten, or added into when accumulate = 1); dxsum (optional, fp32 [d], same
+ * accumulate rule) receives the column sums of dx: dx is the output gradient of the linear layer that feeds
+ * the residual stream here, so this is that layer's bias gradient.  ws: fp32 workspace of
  * pw_layernorm_bwd_ws_floats(N, d) floats. */
 pw_status pw_op_layernorm_bwd(pw_ctx* ctx, int dtype, const void* dy, const float* x, const float* g,
                               const float* mean, const float* rstd, const float* dres, float* dx, void* dx_lp,
-                              float* dg, float* db, float* ws, int N, int d, int accumulate);
+                              float* dg, float* db, float* dxsum, float* ws, int N, int d, int accumulate);
 int64_t pw_layernorm_bwd_ws_floats(int N, int d);
 /* Causal multi-head attention over qkv [B*T, 3d] in `dtype` (columns [Q|K|V], head h at h*hd):
  * o [B*T, d] in `dtype`, lse fp32 [B, H, T] (log-sum-exp of the scaled scores of each row). */

@@ -43,7 +43,7 @@ hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, const float* x, const 
 int64_t layernorm_bwd_ws_floats(int N, int d);
 hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const float* x, const float* g,
                                 const float* mean, const float* rstd, const float* dres, float* dx, void* dx_lp,
-                                float* dg, float* db, float* ws, int N, int d, int accumulate);
+                                float* dg, float* db, float* dsum, float* ws, int N, int d, int accumulate);
 int64_t colsum_ws_floats(int64_t rows, int64_t cols);
 hipError_t launch_colsum(hipStream_t s, int dtype, const void* in, float* out, float* ws, int64_t rows, int64_t cols,
                          int accumulate);

@@ -187,7 +187,10 @@ hipError_t layers_forward(Model* m, Model::Slot& s) {
 
 // On entry m->dx_a holds the gradient w.r.t. the stack output (fp32) and, in bf16 mode, m->dx_lp its bf16
 // copy.  On exit m->dx_a holds the gradient w.r.t. the stack input.
-hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate) {
+// The bias gradients of the two projections that write the residual stream (b2, bo) are column sums of the
+// stream's gradient; the LayerNorm backward that produces that gradient delivers them.  top_b2_done says
+// whether the caller's producer of dx_a already did so for the last layer's b2.
+hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2_done) {
   const pw_lm_config& c = m->cfg;
   const int N = m->N(), d = c.d_model, F = c.d_ff;
   const int dt = m->act_dtype();
@@ -198,7 +201,8 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate) {
     const void* dx_op = c.bf16 ? m->dx_lp : (const void*)m->dx_a;
     // FFN2: x_out = x_mid + h W2 + b2
     PW_TRY(gemm_wgrad(m, A.h, dx_op, e + 10, N, F, d, accumulate), "ffn2 wgrad");
-    PW_TRY(launch_colsum(m->stream, kF32, m->dx_a, g + P(m, e + 11).offset, m->ws, N, d, accumulate), "b2 grad");
+    if (l == c.n_layer - 1 && !top_b2_done)
+      PW_TRY(launch_colsum(m->stream, kF32, m->dx_a, g + P(m, e + 11).offset, m->ws, N, d, accumulate), "b2 grad");
     PW_TRY(gemm_dgrad(m, dx_op, e + 10, N, F, d, kEpiGeluBwd, A.u, m->d_big), "ffn2 dgrad + gelu'");
     // FFN1: u = m W1 + b1
     PW_TRY(gemm_wgrad(m, A.mm, m->d_big, e + 8, N, d, F, accumulate), "ffn1 wgrad");
@@ -207,12 +211,11 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate) {
     // LN2 and the residual branch: dx_b = dx_a + LN2'(d_small)
     PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_mid, m->w + P(m, e + 6).offset, A.mean2, A.rstd2, m->dx_a,
                                 m->dx_b, c.bf16 ? m->dx_lp : nullptr, g + P(m, e + 6).offset, g + P(m, e + 7).offset,
-                                m->ws, N, d, accumulate), "ln2 bwd");
+                                g + P(m, e + 5).offset /* bo */, m->ws, N, d, accumulate), "ln2 bwd");
     dx_op = c.bf16 ? m->dx_lp : (const void*)m->dx_b;
     // out-proj: x_mid = x_in + o Wo + bo
     // (its weight gradient is computed together with the QKV one below: neither fills the chip alone)
     const void* dy_out = dx_op;
-    PW_TRY(launch_colsum(m->stream, kF32, m->dx_b, g + P(m, e + 5).offset, m->ws, N, d, accumulate), "bo grad");
     PW_TRY(gemm_dgrad(m, dx_op, e + 4, N, d, d, kEpiStore, nullptr, m->d_small), "out-proj dgrad");
     PW_TRY(launch_attention_bwd(m->stream, dt, A.qkv, A.o, m->d_small, A.lse, m->delta, m->d_qkv, c.batch, c.seq,
                                 c.n_head, m->hd()), "attention bwd");
@@ -224,8 +227,9 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate) {
     PW_TRY(gemm_dgrad(m, m->d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small), "qkv dgrad");
     // LN1 and the residual branch: dx_a = dx_b + LN1'(d_small)
     PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->w + P(m, e).offset, A.mean1, A.rstd1, m->dx_b,
-                                m->dx_a, c.bf16 ? m->dx_lp : nullptr, g + P(m, e).offset, g + P(m, e + 1).offset, m->ws,
-                                N, d, accumulate), "ln1 bwd");
+                                m->dx_a, c.bf16 ? m->dx_lp : nullptr, g + P(m, e).offset, g + P(m, e + 1).offset,
+                                l > 0 ? g + P(m, layer_base(m, l - 1) + 11).offset /* b2 of the layer below */ : nullptr,
+                                m->ws, N, d, accumulate), "ln1 bwd");
   }
   return hipSuccess;
 }
@@ -344,8 +348,9 @@ hipError_t model_train_step(Model* m, const int32_t* tokens, float* loss) {
   PW_TRY(gemm_wgrad(m, m->y, m->logits, tail + 2, N, d, V, 0), "head wgrad");
   PW_TRY(gemm_dgrad(m, m->logits, tail + 2, N, d, V, kEpiStore, nullptr, m->d_small), "head dgrad");
   PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, s.x_out, m->w + P(m, tail).offset, m->meanf, m->rstdf, nullptr, m->dx_a,
-                              c.bf16 ? m->dx_lp : nullptr, m->g + P(m, tail).offset, m->g + P(m, tail + 1).offset, m->ws, N, d, 0), "lnf bwd");
-  e = layers_backward(m, s, 0);
+                              c.bf16 ? m->dx_lp : nullptr, m->g + P(m, tail).offset, m->g + P(m, tail + 1).offset,
+                              c.n_layer > 0 ? m->g + P(m, layer_base(m, c.n_layer - 1) + 11).offset : nullptr, m->ws, N, d, 0), "lnf bwd");
+  e = layers_backward(m, s, 0, true);
   if (e != hipSuccess) return e;
   PW_TRY(launch_embedding_bwd(m->stream, tokens, m->dx_a, m->g + P(m, 0).offset, m->g + P(m, 1).offset, c.batch, c.seq, d, V), "embedding bwd");
   return model_apply_optimizer(m);
@@ -376,7 +381,7 @@ hipError_t model_stage_bwd(Model* m, int mb, const float* dy, float* dx) {
   const int64_t n = (int64_t)m->N() * c.d_model;
   PW_TRY(launch_copy_bytes(m->stream, dy, m->dx_a, n * 4), "stage grad-output copy");
   if (c.bf16) PW_TRY(launch_f32_to_bf16(m->stream, dy, m->dx_lp, n), "stage grad-output to bf16");
-  hipError_t e = layers_backward(m, s, 1);
+  hipError_t e = layers_backward(m, s, 1, false);
   if (e != hipSuccess) return e;
   PW_TRY(launch_copy_bytes(m->stream, m->dx_a, dx, n * 4), "stage grad-input copy");
   return hipSuccess;

@@ -997,8 +997,8 @@ pw_status pw_op_layernorm_fwd(pw_ctx* c, int dtype, const float* x, const float*
   PW_OP(c, launch_layernorm_fwd(c->exec, dtype, x, g, b, y, mean, rstd, N, d));
 }
 pw_status pw_op_layernorm_bwd(pw_ctx* c, int dtype, const void* dy, const float* x, const float* g, const float* mean, const float* rstd,
-                              const float* dres, float* dx, void* dx_lp, float* dg, float* db, float* ws, int N, int d, int accumulate) {
-  PW_OP(c, launch_layernorm_bwd(c->exec, dtype, dy, x, g, mean, rstd, dres, dx, dx_lp, dg, db, ws, N, d, accumulate));
+                              const float* dres, float* dx, void* dx_lp, float* dg, float* db, float* dxsum, float* ws, int N, int d, int accumulate) {
+  PW_OP(c, launch_layernorm_bwd(c->exec, dtype, dy, x, g, mean, rstd, dres, dx, dx_lp, dg, db, dxsum, ws, N, d, accumulate));
 }
 int64_t pw_layernorm_bwd_ws_floats(int N, int d) { return layernorm_bwd_ws_floats(N, d); }
 pw_status pw_op_attention_fwd(pw_ctx* c, int dtype, const void* qkv, void* o, float* lse, int B, int T, int H, int hd) {

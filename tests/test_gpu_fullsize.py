@@ -118,8 +118,22 @@ def test_layernorm_and_xent_at_cfg3_shape(ctx, orc):
     mean, rstd = torch.empty(N, device="cuda"), torch.empty(N, device="cuda")
     ctx.op("layernorm_fwd", pwb.PW_BF16, ptr(x), ptr(g), ptr(b), ptr(y), ptr(mean), ptr(rstd), N, D)
     ctx.synchronize()
-    ry, _, _ = orc.layernorm_fwd(host(x[ROWS]), host(g), host(b))
+    ry, rmean, rrstd = orc.layernorm_fwd(host(x[ROWS]), host(g), host(b))
     assert rel_l2(host(y[ROWS]), ry) < 4e-3
+    assert rel_l2(host(mean[ROWS]), rmean) < 1e-5 and rel_l2(host(rstd[ROWS]), rrstd) < 1e-5
+    # backward in the step's configuration: bf16 dy, fp32 residual gradient in, fp32 + bf16 dx out, column sums
+    dy, dres = _bf16_randn((N, D), 21), torch.randn((N, D), device="cuda")
+    dx, dxlp = torch.empty((N, D), device="cuda"), torch.empty((N, D), dtype=torch.bfloat16, device="cuda")
+    dg, db, dsum = (torch.empty(D, device="cuda") for _ in range(3))
+    ws = torch.empty(pwb.lib().pw_layernorm_bwd_ws_floats(N, D), device="cuda")
+    ctx.op("layernorm_bwd", pwb.PW_BF16, ptr(dy), ptr(x), ptr(g), ptr(mean), ptr(rstd), ptr(dres), ptr(dx), ptr(dxlp),
+           ptr(dg), ptr(db), ptr(dsum), ptr(ws), N, D, 0)
+    ctx.synchronize()
+    rdx, rdg, rdb = orc.layernorm_bwd(host(dy), host(x), host(g))        # the whole tensor: 16.8 M elements
+    want = rdx + host(dres)
+    assert rel_l2(host(dx), want) < 1e-5 and rel_l2(host(dxlp), want) < 4e-3
+    assert rel_l2(host(dg), rdg) < 1e-5 and rel_l2(host(db), rdb) < 1e-5
+    assert rel_l2(host(dsum), want.sum(axis=0)) < 1e-5
     z = _bf16_randn((N, V), 8, 1.5)
     tok = I.lm_tokens(CFG3)
     tokd = dev_i32(tok)

@@ -148,7 +148,7 @@ def test_gemm_rejects_what_the_kernel_cannot_take(ctx):
 # ---- LayerNorm ----------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("bf16", [False, True])
-@pytest.mark.parametrize("N,d", [(37, 256), (5, 1000), (600, 2048), (3, 8192)])
+@pytest.mark.parametrize("N,d", [(37, 256), (5, 1000), (600, 2048), (3, 8192), (2100, 2048), (1030, 512), (70, 4096)])
 def test_layernorm_forward_backward(ctx, orc, N, d, bf16):
     x = _rand(20, (N, d), 2.0) + 0.5
     g, b = 1 + _rand(21, (d,), 0.1), _rand(22, (d,), 0.1)
@@ -162,16 +162,22 @@ def test_layernorm_forward_backward(ctx, orc, N, d, bf16):
     dresd = dev_f32(dres)
     dx = torch.empty((N, d), device="cuda")
     dxlp = empty_act((N, d), bf16) if bf16 else None
-    dg, db = dev_f32(np.ones(d)), dev_f32(np.ones(d))
+    dg, db, dsum = dev_f32(np.ones(d)), dev_f32(np.ones(d)), dev_f32(np.ones(d))
     ws = torch.empty(pwb.lib().pw_layernorm_bwd_ws_floats(N, d), device="cuda")
     ctx.op("layernorm_bwd", DT[bf16], ptr(dy), ptr(xd), ptr(gd), ptr(mean), ptr(rstd), ptr(dresd), ptr(dx), ptr(dxlp),
-           ptr(dg), ptr(db), ptr(ws), N, d, 1)
+           ptr(dg), ptr(db), ptr(dsum), ptr(ws), N, d, 1)
+    # without the residual input and the optional outputs, overwrite mode
+    dx0, dg0, db0 = torch.empty((N, d), device="cuda"), dev_f32(np.ones(d)), dev_f32(np.ones(d))
+    ctx.op("layernorm_bwd", DT[bf16], ptr(dy), ptr(xd), ptr(gd), ptr(mean), ptr(rstd), None, ptr(dx0), None,
+           ptr(dg0), ptr(db0), None, ptr(ws), N, d, 0)
     ctx.synchronize()
     assert rel_l2(host(y), ry) < (4e-3 if bf16 else 2e-6)
     assert rel_l2(host(mean), rmean) < 1e-5 and rel_l2(host(rstd), rrstd) < 1e-5
     rdx, rdg, rdb = orc.layernorm_bwd(dyv, x, g)
     assert rel_l2(host(dx), rdx + dres) < 1e-5
     assert rel_l2(host(dg), rdg + 1.0) < 1e-5 and rel_l2(host(db), rdb + 1.0) < 1e-5   # accumulate = 1 adds
+    assert rel_l2(host(dsum), (rdx + dres).sum(axis=0) + 1.0) < 1e-5                   # column sums of dx
+    assert rel_l2(host(dx0), rdx) < 1e-5 and rel_l2(host(dg0), rdg) < 1e-5 and rel_l2(host(db0), rdb) < 1e-5
     if bf16:
         assert rel_l2(host(dxlp), rdx + dres) < 4e-3
 
