@@ -7,6 +7,19 @@ namespace pw {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
+// Linear workgroup id -> (problem = batch*H + head, block index inside the problem).  The hardware deals
+// consecutive workgroup ids round-robin over the 8 XCDs, each with an L2 of its own; the n_inner blocks of one
+// problem all stream the same K/V (or Q/dO) rows, so they are given ids that land on ONE XCD, back to back:
+// XCD x owns a contiguous range of (problem, block) pairs.  A bijection for any grid size.
+__device__ __forceinline__ void xcd_block_map(int pid, int nblk, int n_inner, int& problem, int& inner) {
+  constexpr int kXcd = 8;
+  const int q = nblk / kXcd, r = nblk % kXcd;
+  const int xcd = pid % kXcd, j = pid / kXcd;
+  const int logical = xcd * q + (xcd < r ? xcd : r) + j;
+  problem = logical / n_inner;
+  inner = logical - problem * n_inner;
+}
+
 __device__ __forceinline__ int perm_row(int i) {   // [0-3, 8-11, 4-7, 12-15] within each 16
   const int j = i & 15;
   const int p = (j & 3) | ((j & 4) << 1) | ((j & 8) >> 1);

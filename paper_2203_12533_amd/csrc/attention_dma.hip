@@ -102,8 +102,11 @@ __global__ __launch_bounds__(kNT, 2) void attn_fwd_dma_kernel(const bf16* __rest
   extern __shared__ __attribute__((aligned(1024))) bf16 smem[];         // [stage][K | V], 64 KiB
   const int d = H * HD;
   const int64_t ld = 3 * (int64_t)d;
-  const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
-  const int qblk = gridDim.x - 1 - blockIdx.x;          // longest blocks first
+  const int nq = (T + 127) / 128;
+  int bh, qi;
+  xcd_block_map(blockIdx.x, gridDim.x, nq, bh, qi);
+  const int b = bh / H, h = bh - b * H;
+  const int qblk = nq - 1 - qi;                         // longest blocks of a problem first
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5;
   const int q0 = qblk * 128 + wave * 32;
   const int query = q0 + (lane & 31);
@@ -195,8 +198,11 @@ __global__ __launch_bounds__(kNT, 2) void attn_dq_dma_kernel(const bf16* __restr
   extern __shared__ __attribute__((aligned(1024))) bf16 smem[];
   const int d = H * HD;
   const int64_t ld = 3 * (int64_t)d;
-  const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
-  const int qblk = gridDim.x - 1 - blockIdx.x;
+  const int nq = (T + 127) / 128;
+  int bh, qi;
+  xcd_block_map(blockIdx.x, gridDim.x, nq, bh, qi);
+  const int b = bh / H, h = bh - b * H;
+  const int qblk = nq - 1 - qi;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5;
   const int q0 = qblk * 128 + wave * 32;
   const int query = q0 + (lane & 31);
@@ -265,8 +271,9 @@ __global__ __launch_bounds__(kNT) void attn_dkv_dma_kernel(const bf16* __restric
   float (*Ds)[BQ] = Ls + 2;
   const int d = H * HD;
   const int64_t ld = 3 * (int64_t)d;
-  const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
-  const int kblk = blockIdx.x;                          // first key blocks see the most queries: they come first
+  int bh, kblk;                                         // first key blocks see the most queries: they come first
+  xcd_block_map(blockIdx.x, gridDim.x, (T + 127) / 128, bh, kblk);
+  const int b = bh / H, h = bh - b * H;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5;
   const int k0 = kblk * 128 + wave * 32;
   const int key = k0 + (lane & 31);
@@ -381,7 +388,7 @@ hipError_t attention_dma_init() {
 hipError_t launch_attention_fwd_dma(hipStream_t s, const void* qkv, void* o, float* lse, int B, int T, int H) {
   hipError_t e = attention_dma_init();
   if (e != hipSuccess) return e;
-  dim3 grid((T + 127) / 128, B * H);
+  const int grid = ((T + 127) / 128) * B * H;          // (problem, block) pairs, see xcd_block_map
   attn_fwd_dma_kernel<<<grid, kNT, kSmemTiles, s>>>((const bf16*)qkv, (bf16*)o, lse, T, H);
   return hipGetLastError();
 }
@@ -390,7 +397,7 @@ hipError_t launch_attention_dq_dkv_dma(hipStream_t s, const void* qkv, const voi
                                        const float* delta, void* dqkv, int B, int T, int H) {
   hipError_t e = attention_dma_init();
   if (e != hipSuccess) return e;
-  dim3 grid((T + 127) / 128, B * H);
+  const int grid = ((T + 127) / 128) * B * H;
   attn_dq_dma_kernel<<<grid, kNT, kSmemTiles, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
   attn_dkv_dma_kernel<<<grid, kNT, kSmemDkv, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
   return hipGetLastError();
