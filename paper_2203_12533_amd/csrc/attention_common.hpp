@@ -20,6 +20,14 @@ __device__ __forceinline__ void xcd_block_map(int pid, int nblk, int n_inner, in
   inner = logical - problem * n_inner;
 }
 
+// max of three in one instruction.  (Scores are never signalling NaNs, so the quieting pass the compiler puts
+// in front of every fmaxf on values it cannot trace is not needed.)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float d;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
+
 __device__ __forceinline__ int perm_row(int i) {   // [0-3, 8-11, 4-7, 12-15] within each 16
   const int j = i & 15;
   const int p = (j & 3) | ((j & 4) << 1) | ((j & 8) >> 1);

@@ -35,19 +35,46 @@ __device__ __forceinline__ void dma16(const bf16* g, uint32_t lds_off) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_off) : "memory", "m0");
 }
 
-// This wave's share of the direct loads of a ROWS x 128 tile (ROWS/4 instructions of 1 KiB over 4 waves).
-// src: element (row 0 of the sequence, feature 0); tile rows row0 .. row0+ROWS-1, clamped to `last`.
+// Same with a wave-uniform base pointer in scalar registers and a 32-bit per-lane byte offset.
+__device__ __forceinline__ void dma16_s(const bf16* base, uint32_t voff, uint32_t lds_off) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(lds_off) : "memory", "m0");
+}
+
+// Direct loads of a ROWS x 128 tile, ROWS/16 instructions of 1 KiB per wave (4 waves).  Instruction j of wave w
+// covers tile rows 4 (w ROWS/16 + j) .. +3; lane l fetches chunk (l%16) ^ swz(row) of row l/16 of those.
+// TileOffsets holds this lane's byte offsets inside a tile whose first row is row 0 (they do not depend on the
+// tile), so a tile that lies fully inside the sequence costs no vector arithmetic: base + rows*ld is scalar.
 template <int ROWS>
-__device__ __forceinline__ void issue_tile(const bf16* __restrict__ src, int64_t ld, int row0, int last, uint32_t lds_off,
-                                           int wave, int lane) {
-  constexpr int kPerWave = ROWS / 4 / 4;
+struct TileOffsets {
+  static constexpr int kPerWave = ROWS / 16;
+  uint32_t off[kPerWave];
+  __device__ __forceinline__ void init(int64_t ld, int wave, int lane) {
 #pragma unroll
-  for (int j = 0; j < kPerWave; ++j) {
-    const int instr = wave * kPerWave + j;
-    const int r = instr * 4 + (lane >> 4);
-    const int c = (lane & 15) ^ swz(r);
-    const int row = min(row0 + r, last);
-    dma16(src + (int64_t)row * ld + c * 8, lds_off + instr * 1024);
+    for (int j = 0; j < kPerWave; ++j) {
+      const int r = (wave * kPerWave + j) * 4 + (lane >> 4);
+      off[j] = (uint32_t)((r * ld + (((lane & 15) ^ swz(r)) << 3)) * 2);
+    }
+  }
+};
+// src: element (row 0 of the sequence, feature 0); tile rows row0 .. row0+ROWS-1; rows past `last` are fetched
+// from row `last` (the slow path, only for the one tile that straddles the end of the sequence).
+template <int ROWS>
+__device__ __forceinline__ void issue_tile(const bf16* __restrict__ src, int64_t ld, int row0, int last,
+                                           const TileOffsets<ROWS>& to, uint32_t lds_off, int wave, int lane) {
+  constexpr int kPerWave = ROWS / 16;
+  if (row0 + ROWS - 1 <= last) {
+    const bf16* base = src + (int64_t)row0 * ld;
+#pragma unroll
+    for (int j = 0; j < kPerWave; ++j) dma16_s(base, to.off[j], lds_off + (wave * kPerWave + j) * 1024);
+  } else {
+#pragma unroll
+    for (int j = 0; j < kPerWave; ++j) {
+      const int instr = wave * kPerWave + j;
+      const int r = instr * 4 + (lane >> 4);
+      const int c = (lane & 15) ^ swz(r);
+      const int row = min(row0 + r, last);
+      dma16(src + (int64_t)row * ld + c * 8, lds_off + instr * 1024);
+    }
   }
 }
 
@@ -127,10 +154,12 @@ __global__ __launch_bounds__(kNT, 2) void attn_fwd_dma_kernel(const bf16* __rest
 
   const int last_q = min(T, (qblk + 1) * 128) - 1;
   const int n_tiles = last_q / BKV + 1;
+  TileOffsets<BKV> to;
+  to.init(ld, wave, lane);
   auto issue = [&](int t) {
     const uint32_t st = smem_off + (uint32_t)(t & 1) * (2 * kTile * 2);
-    issue_tile<BKV>(kbase, ld, t * BKV, T - 1, st, wave, lane);
-    issue_tile<BKV>(vbase, ld, t * BKV, T - 1, st + kTile * 2, wave, lane);
+    issue_tile<BKV>(kbase, ld, t * BKV, T - 1, to, st, wave, lane);
+    issue_tile<BKV>(vbase, ld, t * BKV, T - 1, to, st + kTile * 2, wave, lane);
   };
   issue(0);
   for (int t = 0; t < n_tiles; ++t) {
@@ -150,10 +179,12 @@ __global__ __launch_bounds__(kNT, 2) void attn_fwd_dma_kernel(const bf16* __rest
         for (int r = 0; r < 16; ++r)
           if (j0 + kb * 32 + reg_row(r, half) > query) s[kb][r] = -INFINITY;
     }
-    float mx = fmaxf(s[0][0], s[1][0]);
+    float mx = max3(s[0][0], s[1][0], s[0][1]);
 #pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s[0][r], s[1][r]));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c2;
+    for (int r = 1; r < 15; ++r) mx = max3(mx, s[1][r], s[0][r + 1]);
+    mx = max3(mx, s[1][15], s[1][15]);
+    const float other = __shfl_xor(mx, 32, 64);
+    mx = max3(mx, other, other) * c2;
     // lazy rescaling: the reference m only has to bound the exponents (see attention_mfma.hip)
     if (__builtin_amdgcn_ballot_w64(mx > m + 8.f) != 0) {
       const float m_new = fmaxf(m, mx);
@@ -226,10 +257,12 @@ __global__ __launch_bounds__(kNT, 2) void attn_dq_dma_kernel(const bf16* __restr
 
   const int last_q = min(T, (qblk + 1) * 128) - 1;
   const int n_tiles = last_q / BKV + 1;
+  TileOffsets<BKV> to;
+  to.init(ld, wave, lane);
   auto issue = [&](int t) {
     const uint32_t st = smem_off + (uint32_t)(t & 1) * (2 * kTile * 2);
-    issue_tile<BKV>(kbase, ld, t * BKV, T - 1, st, wave, lane);
-    issue_tile<BKV>(vbase, ld, t * BKV, T - 1, st + kTile * 2, wave, lane);
+    issue_tile<BKV>(kbase, ld, t * BKV, T - 1, to, st, wave, lane);
+    issue_tile<BKV>(vbase, ld, t * BKV, T - 1, to, st + kTile * 2, wave, lane);
   };
   issue(0);
   for (int t = 0; t < n_tiles; ++t) {
@@ -297,10 +330,13 @@ __global__ __launch_bounds__(kNT) void attn_dkv_dma_kernel(const bf16* __restric
 
   const int first_tile = (kblk * 128) / BQ;
   const int n_tiles = (T + BQ - 1) / BQ;
+  TileOffsets<BQ> to_q, to_g;
+  to_q.init(ld, wave, lane);
+  to_g.init(d, wave, lane);
   auto issue = [&](int t) {
     const uint32_t st = smem_off + (uint32_t)(t & 1) * (2 * kTile * 2);
-    issue_tile<BQ>(qbase, ld, t * BQ, T - 1, st, wave, lane);
-    issue_tile<BQ>(gbase, d, t * BQ, T - 1, st + kTile * 2, wave, lane);
+    issue_tile<BQ>(qbase, ld, t * BQ, T - 1, to_q, st, wave, lane);
+    issue_tile<BQ>(gbase, d, t * BQ, T - 1, to_g, st + kTile * 2, wave, lane);
   };
   // per-query statistics of a tile: fetched one tile ahead into registers by the first 64 threads
   float l_next = 0.f, d_next = 0.f;
