@@ -54,7 +54,7 @@ def recorded_gemm_traffic(workload: str):
     path = os.path.join(ROOT, "profiles", f"{workload}_train_step_hbm_traffic.txt")
     try:
         for line in open(path):
-            if line.startswith("# all gemm_bf16_kernel launches:"):
+            if line.startswith("# all MFMA GEMM launches"):
                 return float(line.split("=")[1].split()[0])
     except OSError:
         pass
