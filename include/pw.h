@@ -68,6 +68,9 @@ typedef enum {
   PW_FN_DIV_CONST = 3,   /* y = x / c ("c" of Figure 2) */
   PW_FN_BUSY = 4,        /* y = x + c after spinning params[1] microseconds on the device: a computation
                             of tunable duration for the overhead-masking sweep (Section 5.1) */
+  PW_FN_BUSY_CHAIN = 5,  /* params {c, microseconds, count}: PW_FN_BUSY applied count times in a row inside ONE
+                            launch - a chain of computations fused into a single node (the "Fused" case of
+                            Section 5.1); the result equals count separate PW_FN_BUSY functions bit for bit */
   PW_FN_LM_TRAIN_STEP = 16, /* in: tokens i32 [B, T+1]; out: loss f32 [1].  params: pw_model*. */
   PW_FN_STAGE_FWD = 17,  /* in: X [N, d]; out: Y [N, d].  params: pw_stage_params */
   PW_FN_STAGE_BWD = 18   /* in: dY [N, d]; out: dX [N, d]; adds into the stage's weight gradients */
@@ -92,6 +95,13 @@ typedef enum {
   PW_SEQUENTIAL = 2   /* wait for each function to complete before enqueuing the next: the
                          sequential-dispatch baseline of Section 5.1, for comparison only */
 } pw_chain_mode;
+
+typedef enum {
+  PW_DISPATCH_PARALLEL = 0,   /* every node is handed to its executor at once (parallel asynchronous dispatch,
+                                 Section 4.5, Figure 4b) */
+  PW_DISPATCH_SEQUENTIAL = 1  /* node i+1 is handed out only after node i's executor has reported it enqueued
+                                 (Figure 4a; the comparison of Section 5.1, Figure 7) */
+} pw_dispatch_mode;
 
 /* ---- context -------------------------------------------------------------------------------- */
 
@@ -133,6 +143,20 @@ pw_status pw_run_fn(pw_ctx* ctx, pw_fn fn, const pw_future* in, int n_in, pw_fut
  * checks for the whole chain happen before the first launch. */
 pw_status pw_chain(pw_ctx* ctx, const pw_fn* fns, int n_fns, const pw_future* in, int n_in,
                    pw_future* out, int n_out, int mode /* pw_chain_mode */);
+
+/* Executors (Section 4.4: one FIFO per set of devices).  Sets up n of them: executor 0 is the context's own
+ * stream; each further one is a HIP stream of its own served by a host thread of its own - on one GPU the
+ * stand-in for "a different set of cores attached to a different host".  n in [1, 64]; once per context. */
+pw_status pw_ctx_set_executors(pw_ctx* ctx, int n);
+/* A chain whose node i runs on executor executor_of[i] (host array of n_fns ids): fns[0] consumes `in`, node i+1
+ * consumes node i's output.  Only elementwise kinds (one fp32 input, one output of the same shape).  Where
+ * consecutive nodes sit on different executors the consumer's input buffer is allocated up front and the
+ * producer's stream copies its output into it (Section 4.5: shapes are static, so every buffer is planned
+ * before anything runs); the dependency is a HIP event.  Everything is validated first: on any error nothing
+ * is enqueued.  Returns when every node has been enqueued (not run); `out` receives the last node's output
+ * (refcount 1).  dispatch: a pw_dispatch_mode.  Not thread-safe, like every call on a context. */
+pw_status pw_pipeline(pw_ctx* ctx, const pw_fn* fns, const int32_t* executor_of, int n_fns, pw_future in,
+                      pw_future* out, int dispatch);
 
 /* One LM train step: pw_run_fn on a function of kind PW_FN_LM_TRAIN_STEP.  The model's parameters
  * and optimiser state are updated in place on the device (they are the function's private state). */

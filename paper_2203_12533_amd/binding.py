@@ -20,7 +20,8 @@ PW_OK, PW_ERR_INVALID, PW_ERR_SHAPE, PW_ERR_DTYPE, PW_ERR_OOM, PW_ERR_DEVICE, PW
 STATUS_NAMES = ["PW_OK", "PW_ERR_INVALID", "PW_ERR_SHAPE", "PW_ERR_DTYPE", "PW_ERR_OOM", "PW_ERR_DEVICE",
                 "PW_ERR_NOT_READY", "PW_ERR_POISONED", "PW_ERR_UNSUPPORTED"]
 PW_F32, PW_BF16, PW_I32 = 0, 1, 2
-PW_FN_ADD_CONST, PW_FN_MUL_CONST, PW_FN_DIV_CONST, PW_FN_BUSY = 1, 2, 3, 4
+PW_FN_ADD_CONST, PW_FN_MUL_CONST, PW_FN_DIV_CONST, PW_FN_BUSY, PW_FN_BUSY_CHAIN = 1, 2, 3, 4, 5
+PW_DISPATCH_PARALLEL, PW_DISPATCH_SEQUENTIAL = 0, 1
 PW_FN_LM_TRAIN_STEP, PW_FN_STAGE_FWD, PW_FN_STAGE_BWD = 16, 17, 18
 PW_STREAM, PW_GRAPH, PW_SEQUENTIAL = 0, 1, 2
 PW_PARAMS, PW_GRADS, PW_ADAM_M, PW_ADAM_V = 0, 1, 2, 3
@@ -80,6 +81,9 @@ _SIGS = {
     "pw_chain": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64), C.c_int, C.POINTER(C.c_uint64), C.c_int,
                            C.POINTER(C.c_uint64), C.c_int, C.c_int]),
     "pw_train_step": (C.c_int, [C.c_void_p, C.c_uint64, C.c_uint64, C.POINTER(C.c_uint64)]),
+    "pw_ctx_set_executors": (C.c_int, [C.c_void_p, C.c_int]),
+    "pw_pipeline": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.c_int, C.c_uint64,
+                              C.POINTER(C.c_uint64), C.c_int]),
     "pw_await": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_size_t]),
     "pw_future_from_host": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(TensorSpec), C.POINTER(C.c_uint64)]),
     "pw_future_wrap_device": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(TensorSpec), C.POINTER(C.c_uint64)]),
@@ -207,9 +211,10 @@ class Context:
         self._check(lib().pw_compile_fn(self._h, C.byref(d), C.byref(h)))
         return h.value
 
-    def compile_scalar_fn(self, kind: int, n: int, c: float, busy_us: float | None = None) -> int:
+    def compile_scalar_fn(self, kind: int, n: int, c: float, busy_us: float | None = None,
+                          reps: int | None = None) -> int:
         spec = make_spec(PW_F32, (n,))
-        vals = [c] if busy_us is None else [c, busy_us]
+        vals = [c] if busy_us is None else [c, busy_us] if reps is None else [c, busy_us, reps]
         return self.compile_fn(kind, [spec], [spec], np.asarray(vals, np.float32).tobytes())
 
     def fn_release(self, fn: int):
@@ -227,6 +232,16 @@ class Context:
         a_out = (C.c_uint64 * max(1, n_out))()
         self._check(lib().pw_chain(self._h, a_f, len(fns), a_in, len(inputs), a_out, n_out, mode))
         return list(a_out[:n_out])
+
+    def set_executors(self, n: int):
+        self._check(lib().pw_ctx_set_executors(self._h, n))
+
+    def pipeline(self, fns, executor_of, f_in: int, dispatch: int = PW_DISPATCH_PARALLEL) -> int:
+        a_f = (C.c_uint64 * len(fns))(*fns)
+        a_e = (C.c_int32 * len(fns))(*executor_of)
+        out = C.c_uint64()
+        self._check(lib().pw_pipeline(self._h, a_f, a_e, len(fns), f_in, C.byref(out), dispatch))
+        return out.value
 
     def train_step(self, step_fn: int, tokens_future: int) -> int:
         out = C.c_uint64()

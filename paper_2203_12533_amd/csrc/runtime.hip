@@ -9,15 +9,24 @@
 //                                             allocation or synchronisation sits between launches
 //   one message per subgraph (4.5)         -> PW_GRAPH: the chain's launches replayed as one HIP graph
 //   sequential dispatch baseline (5.1)     -> PW_SEQUENTIAL
+//   nodes on different executors (4.5, Fig. 4; measured in 5.1, Fig. 7) -> pw_pipeline: one HIP stream and one
+//                                             host thread per executor, dependencies carried by HIP events,
+//                                             a copy into the consumer's pre-allocated buffer as the transfer
 //   device object store (4.6)              -> handle tables + size-class buffer pool + refcounts
 // An input that "is not ready" is made real by a gate kernel on a second stream that spins (bounded) on a
 // word in pinned host memory; consumers wait on the event recorded behind it.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+#include <chrono>
+#include <condition_variable>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <deque>
 #include <map>
+#include <mutex>
+#include <thread>
 #include <memory>
 #include <string>
 #include <unordered_map>
@@ -81,6 +90,7 @@ struct FnRec {
   uint32_t gen = 0;
   pw_fn_desc desc{};
   float cst = 0.f, busy_us = 0.f;
+  int reps = 1;
   Model* model = nullptr;
   int microbatch = 0;
 };
@@ -88,6 +98,34 @@ struct FnRec {
 struct GraphEntry {
   hipGraph_t graph = nullptr;
   hipGraphExec_t exec = nullptr;
+};
+
+// One node of a pipeline as handed to an executor's host thread.  Everything the thread needs is in here (the
+// controller planned every buffer beforehand: shapes are static), so the thread touches no context tables.
+struct NodeMsg {
+  int kind = 0;
+  float cst = 0.f, busy_us = 0.f;
+  int reps = 1;
+  int64_t numel = 0;
+  const float* in = nullptr;
+  float* out = nullptr;
+  void* xfer_dst = nullptr;          // consumer-side buffer on another executor (null: consumer shares this stream)
+  size_t xfer_bytes = 0;
+  hipEvent_t wait_event = nullptr;   // producer's event on another stream (null: none, or same stream)
+  std::atomic<int>* wait_flag = nullptr;   // set by the producer's thread once wait_event has been recorded (1) or it failed (2)
+  hipEvent_t done_event = nullptr;   // recorded behind this node (and its transfer)
+  std::atomic<int>* done_flag = nullptr;
+  std::atomic<int>* ack = nullptr;   // 1: enqueued, 2: failed
+};
+
+struct Executor {
+  hipStream_t stream = nullptr;
+  bool own_stream = false;
+  std::thread thread;
+  std::mutex mu;
+  std::condition_variable cv;
+  std::deque<NodeMsg> queue;
+  bool stop = false;
 };
 
 }  // namespace
@@ -118,6 +156,8 @@ struct pw_ctx {
   std::map<size_t, std::vector<void*>> staging_pool;
 
   std::unordered_map<std::string, GraphEntry> graphs;
+
+  std::vector<std::unique_ptr<Executor>> executors;   // pw_ctx_set_executors; [0] wraps the executor stream
 };
 
 struct pw_model {
@@ -253,13 +293,13 @@ FnRec* fn_get(pw_ctx* c, pw_fn h) {
   return (f.live && f.gen == gen) ? &f : nullptr;
 }
 
-bool is_scalar_kind(int k) { return k >= PW_FN_ADD_CONST && k <= PW_FN_BUSY; }
+bool is_scalar_kind(int k) { return k >= PW_FN_ADD_CONST && k <= PW_FN_BUSY_CHAIN; }
 
 // Launch the body of one function on the executor stream.  in/out are device pointers.
 pw_status fn_launch(pw_ctx* c, FnRec* fn, void* const* in, void* const* out) {
   const int k = fn->desc.kind;
   if (is_scalar_kind(k)) {
-    hipError_t e = launch_scalar_fn(c->exec, k, (const float*)in[0], (float*)out[0], spec_numel(fn->desc.in[0]), fn->cst, fn->busy_us);
+    hipError_t e = launch_scalar_fn(c->exec, k, (const float*)in[0], (float*)out[0], spec_numel(fn->desc.in[0]), fn->cst, fn->busy_us, fn->reps);
     if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "scalar fn launch: %s", hipGetErrorString(e));
     return PW_OK;
   }
@@ -296,6 +336,62 @@ bool model_alive(pw_ctx* c, Model* m) {
   for (Model* x : c->models)
     if (x == m) return true;
   return false;
+}
+
+// ---- executors of pw_pipeline -------------------------------------------------------------------------
+// HIP only orders a stream behind an event that has ALREADY been recorded, so a node's thread may not
+// enqueue its wait before the producer's thread has recorded; that much of the order is kept on the host
+// (wait_flag), everything else a thread does for its node runs concurrently with the other threads.
+void executor_handle(int device, Executor* ex, NodeMsg& m) {
+  bool ok = true;
+  if (m.wait_flag) {
+    const auto t0 = std::chrono::steady_clock::now();
+    int v;
+    while ((v = m.wait_flag->load(std::memory_order_acquire)) == 0) {
+      if (std::chrono::steady_clock::now() - t0 > std::chrono::seconds(30)) { v = 2; break; }   // a thread that never reports: give up
+      std::this_thread::yield();
+    }
+    ok = v == 1;
+    if (ok && m.wait_event) ok = hipStreamWaitEvent(ex->stream, m.wait_event, 0) == hipSuccess;
+  }
+  if (ok) ok = launch_scalar_fn(ex->stream, m.kind, m.in, m.out, m.numel, m.cst, m.busy_us, m.reps) == hipSuccess;
+  // "the source writes directly into the buffer the destination allocated" (Section 4.5)
+  if (ok && m.xfer_dst && m.xfer_bytes) ok = launch_copy_bytes(ex->stream, m.out, m.xfer_dst, (int64_t)m.xfer_bytes) == hipSuccess;
+  if (ok && m.done_event) ok = hipEventRecord(m.done_event, ex->stream) == hipSuccess;
+  if (m.done_flag) m.done_flag->store(ok ? 1 : 2, std::memory_order_release);   // always: a consumer may be waiting
+  m.ack->store(ok ? 1 : 2, std::memory_order_release);
+  (void)device;
+}
+
+void executor_loop(int device, Executor* ex) {
+  (void)hipSetDevice(device);
+  for (;;) {
+    NodeMsg m;
+    {
+      std::unique_lock<std::mutex> lk(ex->mu);
+      ex->cv.wait(lk, [&] { return ex->stop || !ex->queue.empty(); });
+      if (ex->queue.empty()) return;   // stop requested and nothing left
+      m = ex->queue.front();
+      ex->queue.pop_front();
+    }
+    executor_handle(device, ex, m);
+  }
+}
+
+void stop_executors(pw_ctx* c) {
+  for (auto& ex : c->executors) {
+    {
+      std::lock_guard<std::mutex> lk(ex->mu);
+      ex->stop = true;
+    }
+    ex->cv.notify_all();
+  }
+  for (auto& ex : c->executors) {
+    if (ex->thread.joinable()) ex->thread.join();
+    if (ex->stream) (void)hipStreamSynchronize(ex->stream);
+    if (ex->own_stream && ex->stream) (void)hipStreamDestroy(ex->stream);
+  }
+  c->executors.clear();
 }
 
 }  // namespace
@@ -339,6 +435,7 @@ pw_status pw_ctx_create(int device, void* hip_stream, pw_ctx** out) {
 pw_status pw_ctx_destroy(pw_ctx* c) {
   if (!c) return PW_ERR_INVALID;
   (void)hipSetDevice(c->device);
+  stop_executors(c);
   // release every gate that is still waiting so that the streams can drain
   for (auto& f : c->futures)
     if (f.live && f.pending && f.gate) __atomic_store_n(&f.gate->words[0], 2u, __ATOMIC_RELEASE);
@@ -412,12 +509,18 @@ pw_status pw_compile_fn(pw_ctx* c, const pw_fn_desc* d, pw_fn* out) {
     if (d->in[0].dtype != PW_F32 || d->out[0].dtype != PW_F32) return fail(c, PW_ERR_DTYPE, "elementwise functions are fp32");
     pw_status st = spec_match(d->in[0], d->out[0]);
     if (st != PW_OK) return fail(c, st, "output must have the input's shape");
-    const size_t need = k == PW_FN_BUSY ? 2 * sizeof(float) : sizeof(float);
+    const size_t need = (k == PW_FN_BUSY ? 2 : k == PW_FN_BUSY_CHAIN ? 3 : 1) * sizeof(float);
     if (!d->params || d->params_bytes != need) return fail(c, PW_ERR_INVALID, "params must hold %zu bytes", need);
     fn.cst = ((const float*)d->params)[0];
-    if (k == PW_FN_BUSY) {
+    if (k == PW_FN_BUSY || k == PW_FN_BUSY_CHAIN) {
       fn.busy_us = ((const float*)d->params)[1];
       if (!(fn.busy_us >= 0.f && fn.busy_us <= 1e6f)) return fail(c, PW_ERR_INVALID, "busy time must be within [0, 1e6] microseconds");
+    }
+    if (k == PW_FN_BUSY_CHAIN) {
+      const float r = ((const float*)d->params)[2];
+      if (!(r >= 1.f && r <= 65536.f) || r != (float)(int)r) return fail(c, PW_ERR_INVALID, "repetition count must be an integer within [1, 65536]");
+      fn.reps = (int)r;
+      if ((double)fn.busy_us * fn.reps > 1e7) return fail(c, PW_ERR_INVALID, "busy time times repetitions must stay within 1e7 microseconds");
     }
   } else if (k == PW_FN_LM_TRAIN_STEP || k == PW_FN_STAGE_FWD || k == PW_FN_STAGE_BWD) {
     pw_model* pm = nullptr;
@@ -667,6 +770,140 @@ pw_status pw_chain(pw_ctx* c, const pw_fn* fns, int n_fns, const pw_future* in, 
       if (event_get(c, &e2) == PW_OK && hipEventRecord(e2, c->exec) == hipSuccess) f->event = e2;
     }
   }
+  return PW_OK;
+}
+
+pw_status pw_ctx_set_executors(pw_ctx* c, int n) {
+  if (!c) return PW_ERR_INVALID;
+  if (n < 1 || n > 64) return fail(c, PW_ERR_INVALID, "executor count must be within [1, 64]");
+  if (!c->executors.empty()) return fail(c, PW_ERR_INVALID, "executors are already set up");
+  (void)hipSetDevice(c->device);
+  for (int i = 0; i < n; ++i) {
+    std::unique_ptr<Executor> ex(new Executor());
+    if (i == 0) {
+      ex->stream = c->exec;
+    } else {
+      if (hipStreamCreateWithFlags(&ex->stream, hipStreamNonBlocking) != hipSuccess) {
+        stop_executors(c);
+        return fail(c, PW_ERR_DEVICE, "could not create the stream of executor %d", i);
+      }
+      ex->own_stream = true;
+    }
+    c->executors.push_back(std::move(ex));
+  }
+  for (auto& ex : c->executors) ex->thread = std::thread(executor_loop, c->device, ex.get());
+  return PW_OK;
+}
+
+pw_status pw_pipeline(pw_ctx* c, const pw_fn* fns, const int32_t* executor_of, int n_fns, pw_future in, pw_future* out, int dispatch) {
+  if (!c || !fns || !executor_of || !out || n_fns < 1 || n_fns > 4096) return PW_ERR_INVALID;
+  if (dispatch != PW_DISPATCH_PARALLEL && dispatch != PW_DISPATCH_SEQUENTIAL) return fail(c, PW_ERR_INVALID, "bad dispatch mode");
+  if (c->executors.empty()) return fail(c, PW_ERR_INVALID, "call pw_ctx_set_executors first");
+  // ---- validate everything before touching the device
+  std::vector<FnRec*> recs(n_fns);
+  FutureRec* fin = future_get(c, in);
+  if (!fin) return fail(c, PW_ERR_INVALID, "input is not a live future");
+  pw_tensor_spec spec = fin->spec;
+  for (int i = 0; i < n_fns; ++i) {
+    recs[i] = fn_get(c, fns[i]);
+    if (!recs[i]) return fail(c, PW_ERR_INVALID, "function %d of the pipeline is not a live handle", i);
+    if (!is_scalar_kind(recs[i]->desc.kind)) return fail(c, PW_ERR_UNSUPPORTED, "node %d: only elementwise functions can be placed on an executor", i);
+    if (executor_of[i] < 0 || executor_of[i] >= (int)c->executors.size()) return fail(c, PW_ERR_INVALID, "node %d: no executor %d", i, executor_of[i]);
+    pw_status st = check_inputs(c, recs[i], &spec, 1, 1);
+    if (st != PW_OK) {
+      c->error = "pipeline node " + std::to_string(i) + ": " + c->error;
+      return st;
+    }
+    spec = recs[i]->desc.out[0];
+  }
+  const size_t bytes = spec_bytes(spec);   // elementwise: every node has the input's shape
+  // ---- plan: per node an output buffer, and where it crosses executors a consumer-side input buffer + event
+  struct Plan { void* out = nullptr; size_t out_cls = 0; void* xfer = nullptr; size_t xfer_cls = 0; hipEvent_t ev = nullptr; };
+  std::vector<Plan> plan(n_fns);
+  auto release_plan = [&](bool keep_last) {
+    for (int i = 0; i < n_fns; ++i) {
+      if (plan[i].out && !(keep_last && i == n_fns - 1)) pool_free(c, plan[i].out, plan[i].out_cls);
+      if (plan[i].xfer) pool_free(c, plan[i].xfer, plan[i].xfer_cls);
+      if (plan[i].ev && !(keep_last && i == n_fns - 1)) c->event_pool.push_back(plan[i].ev);
+    }
+  };
+  for (int i = 0; i < n_fns; ++i) {
+    pw_status st = pool_alloc(c, bytes, &plan[i].out, &plan[i].out_cls);
+    const bool crosses = i + 1 < n_fns && executor_of[i + 1] != executor_of[i];
+    if (st == PW_OK && crosses) st = pool_alloc(c, bytes, &plan[i].xfer, &plan[i].xfer_cls);
+    if (st == PW_OK && (crosses || i == n_fns - 1)) st = event_get(c, &plan[i].ev);
+    if (st != PW_OK) { release_plan(false); return st; }
+  }
+  // the first node's stream must be ordered behind the producer of `in` (and behind earlier users of the pool's
+  // buffers, which all ran on streams this context has since been synchronised with or on the executor stream)
+  std::vector<std::shared_ptr<GateWords>> poison = fin->poison;
+  bool host_poison = fin->host_poison;
+  hipEvent_t order = nullptr;
+  pw_status st = event_get(c, &order);
+  if (st != PW_OK) { release_plan(false); return st; }
+  hipError_t e = hipSuccess;
+  if (fin->on_gate_stream && fin->event) e = hipStreamWaitEvent(c->exec, fin->event, 0);
+  if (e == hipSuccess) e = hipEventRecord(order, c->exec);
+  std::vector<char> used(c->executors.size(), 0);
+  for (int i = 0; i < n_fns; ++i) used[executor_of[i]] = 1;
+  for (size_t x = 1; x < c->executors.size() && e == hipSuccess; ++x)
+    if (used[x]) e = hipStreamWaitEvent(c->executors[x]->stream, order, 0);
+  c->event_pool.push_back(order);
+  if (e != hipSuccess) { release_plan(false); return fail(c, PW_ERR_DEVICE, "ordering the executors: %s", hipGetErrorString(e)); }
+
+  // ---- dispatch
+  std::vector<std::atomic<int>> acks(n_fns), flags(n_fns);
+  for (int i = 0; i < n_fns; ++i) { acks[i].store(0); flags[i].store(0); }
+  auto post = [&](int i) {
+    NodeMsg m;
+    m.kind = recs[i]->desc.kind; m.cst = recs[i]->cst; m.busy_us = recs[i]->busy_us; m.reps = recs[i]->reps;
+    m.numel = spec_numel(spec);
+    const bool from_other = i > 0 && executor_of[i - 1] != executor_of[i];
+    m.in = (const float*)(i == 0 ? fin->buf : from_other ? plan[i - 1].xfer : plan[i - 1].out);
+    m.out = (float*)plan[i].out;
+    m.xfer_dst = plan[i].xfer; m.xfer_bytes = plan[i].xfer ? bytes : 0;
+    if (from_other) { m.wait_event = plan[i - 1].ev; m.wait_flag = &flags[i - 1]; }
+    else if (i > 0) { m.wait_flag = &flags[i - 1]; }   // same stream: only the host-side order of the two enqueues matters
+    m.done_event = plan[i].ev; m.done_flag = &flags[i]; m.ack = &acks[i];
+    Executor* ex = c->executors[executor_of[i]].get();
+    {
+      std::lock_guard<std::mutex> lk(ex->mu);
+      ex->queue.push_back(m);
+    }
+    ex->cv.notify_one();
+  };
+  auto wait_ack = [&](int i) {
+    while (acks[i].load(std::memory_order_acquire) == 0) std::this_thread::yield();
+    return acks[i].load(std::memory_order_acquire) == 1;
+  };
+  bool all_ok = true;
+  if (dispatch == PW_DISPATCH_PARALLEL) {
+    for (int i = 0; i < n_fns; ++i) post(i);                      // every node's host-side work starts now
+    for (int i = 0; i < n_fns; ++i) all_ok = wait_ack(i) && all_ok;
+  } else {
+    for (int i = 0; i < n_fns; ++i) {                             // node i+1 is handed out once node i reports "enqueued"
+      post(i);
+      all_ok = wait_ack(i) && all_ok;
+    }
+  }
+  // Intermediates go back to the pool: their last use is already enqueued; later users are ordered behind the
+  // executor stream, which is made to wait for the last node below.
+  FutureRec* f;
+  future_new(c, &f, out);
+  f->buf = plan[n_fns - 1].out; f->pool_bytes = plan[n_fns - 1].out_cls; f->spec = spec; f->bytes = bytes; f->owns = true;
+  f->poison = poison;
+  f->host_poison = host_poison || !all_ok;
+  f->event = plan[n_fns - 1].ev;
+  // join: everything enqueued on the executor stream from now on runs after the whole pipeline
+  for (size_t x = 1; x < c->executors.size(); ++x) {
+    hipEvent_t j = nullptr;
+    if (used[x] && event_get(c, &j) == PW_OK) {
+      if (hipEventRecord(j, c->executors[x]->stream) == hipSuccess) (void)hipStreamWaitEvent(c->exec, j, 0);
+      c->event_pool.push_back(j);
+    }
+  }
+  release_plan(true);
+  if (!all_ok) return fail(c, PW_ERR_DEVICE, "a pipeline node could not be enqueued; the output future is poisoned");
   return PW_OK;
 }
 

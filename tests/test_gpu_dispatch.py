@@ -185,3 +185,95 @@ def test_busy_function_and_empty_tensor(ctx):
     assert ctx.await_(g).size == 0
     ctx.future_release(f)
     ctx.future_release(g)
+
+
+# ---- a chain fused into one node, and chains spread over several executors (Section 5.1) ----------------
+
+@pytest.mark.parametrize("L", [1, 7, 128])
+def test_fused_chain_equals_the_chain_of_separate_functions(ctx, orc, L):
+    """The "Fused" case: L computations inside one node.  Same L sequential fp32 additions, so same bits."""
+    x = I.dispatch_input() * np.float32(3.0)
+    fused = ctx.compile_scalar_fn(pwb.PW_FN_BUSY_CHAIN, 128, 1.0, busy_us=2.0, reps=L)
+    f_in = ctx.future_pending(pwb.PW_F32, (128,))
+    (f_out,) = ctx.run_fn(fused, [f_in])
+    ctx.future_resolve(f_in, x)
+    assert np.array_equal(ctx.await_(f_out), orc.chain_add(x, L))
+    for h in (f_in, f_out):
+        ctx.future_release(h)
+    ctx.fn_release(fused)
+    with pytest.raises(pwb.PwError):
+        ctx.compile_scalar_fn(pwb.PW_FN_BUSY_CHAIN, 128, 1.0, busy_us=2.0, reps=0)
+    with pytest.raises(pwb.PwError):
+        ctx.compile_scalar_fn(pwb.PW_FN_BUSY_CHAIN, 128, 1.0, busy_us=1e6, reps=100)     # more than ten seconds
+
+
+@pytest.fixture(scope="module")
+def pctx():
+    c = pwb.Context(0)
+    c.set_executors(8)
+    yield c
+    c.close()
+
+
+@pytest.mark.parametrize("dispatch", [pwb.PW_DISPATCH_PARALLEL, pwb.PW_DISPATCH_SEQUENTIAL])
+@pytest.mark.parametrize("placement", ["round_robin", "one_executor", "blocks_of_3", "back_and_forth"])
+def test_pipeline_over_executors_is_exact(pctx, orc, placement, dispatch):
+    """Every node on its own executor (or not): the result is the chain's, whatever the placement and the way the
+    nodes were handed out; nothing is left allocated afterwards."""
+    L, S = 37, 8
+    where = {"round_robin": [i % S for i in range(L)], "one_executor": [5] * L,
+             "blocks_of_3": [(i // 3) % S for i in range(L)], "back_and_forth": [0 if i % 2 else 7 for i in range(L)]}[placement]
+    add1 = pctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    mul = pctx.compile_scalar_fn(pwb.PW_FN_MUL_CONST, 128, 1.0009765625)
+    fns = [add1 if i % 5 else mul for i in range(L)]
+    live0, bytes0 = pctx.stats()
+    for rep in range(3):
+        x = I.dispatch_input() + np.float32(rep)
+        want = x.copy()
+        for i in range(L):
+            want = orc.scalar_fn("add" if i % 5 else "mul", want, 1.0 if i % 5 else 1.0009765625)
+        f_in = pctx.future_pending(pwb.PW_F32, (128,))
+        f_out = pctx.pipeline(fns, where, f_in, dispatch)
+        assert pctx.future_query(f_out) == pwb.PW_ERR_NOT_READY       # enqueued before its input exists
+        pctx.future_resolve(f_in, x)
+        assert np.array_equal(pctx.await_(f_out), want), (placement, dispatch, rep)
+        # the result feeds ordinary functions on the context's own executor afterwards
+        (g,) = pctx.run_fn(add1, [f_out])
+        assert np.array_equal(pctx.await_(g), orc.scalar_fn("add", want, 1.0))
+        for h in (f_in, f_out, g):
+            pctx.future_release(h)
+    assert pctx.stats() == (live0, bytes0)
+    pctx.fn_release(add1)
+    pctx.fn_release(mul)
+
+
+def test_pipeline_rejects_bad_programs_before_enqueuing_and_propagates_poison(pctx):
+    add1 = pctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    add_other = pctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 64, 1.0)
+    f_in = pctx.future_from_host(np.zeros(128, np.float32))
+    live0, bytes0 = pctx.stats()
+    with pytest.raises(pwb.PwError) as e:
+        pctx.pipeline([add1, add1], [0, 8], f_in)                  # there is no executor 8
+    assert e.value.status == pwb.PW_ERR_INVALID
+    with pytest.raises(pwb.PwError) as e:
+        pctx.pipeline([add1, add_other, add1], [0, 1, 2], f_in)    # shapes do not chain
+    assert e.value.status == pwb.PW_ERR_SHAPE
+    with pytest.raises(pwb.PwError):
+        pctx.set_executors(4)                                      # once per context
+    assert pctx.stats() == (live0, bytes0)
+    pctx.future_release(f_in)
+    # a failed producer poisons what the pipeline computes from it
+    f_bad = pctx.future_pending(pwb.PW_F32, (128,))
+    f_out = pctx.pipeline([add1] * 4, [1, 2, 3, 4], f_bad)
+    pctx.future_resolve(f_bad, None)
+    with pytest.raises(pwb.PwError) as e:
+        pctx.await_(f_out)
+    assert e.value.status == pwb.PW_ERR_POISONED
+    for h in (f_bad, f_out):
+        pctx.future_release(h)
+    c2 = pwb.Context(0)
+    f = c2.future_from_host(np.zeros(128, np.float32))
+    a = c2.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    with pytest.raises(pwb.PwError):
+        c2.pipeline([a], [0], f)                                   # executors were never set up
+    c2.close()
