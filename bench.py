@@ -99,6 +99,32 @@ def dispatch_bench(ctx, pwb, I, reps: int = 200):
     return out
 
 
+def dispatch_bench_c_abi():
+    """The pure C++ run of the two dispatch experiments of Section 5.1 (tools/dispatch_bench, built by build()),
+    as a child process in its quick mode; returns its summary figures or None if the binary is not there."""
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2203_12533_amd", "tools", "dispatch_bench")
+    if not os.path.exists(exe):
+        return None
+    try:
+        r = subprocess.run([exe, "--quick"], capture_output=True, text=True, timeout=120)
+    except (OSError, subprocess.TimeoutExpired):
+        return None
+    if r.returncode != 0:
+        return {"error": r.stderr.strip()[-200:]}
+    rows = [json.loads(l) for l in r.stdout.splitlines() if l.startswith("{")]
+    out = {}
+    for row in rows:
+        if row["bench"] == "overhead_masking" and row["computation_us"] == 0:
+            out["us_per_computation_at_0us"] = {k: round(1e6 / v, 3) for k, v in row["computations_per_s"].items()}
+        if row["bench"] == "overhead_masking_summary":
+            out["smallest_computation_us_masking_dispatch"] = row["smallest_computation_us_for_chained_to_reach"]
+        if row["bench"] == "parallel_vs_sequential" and row["stages"] == 64:
+            out[f"parallel_over_sequential_64_stages_comp{row['computation_us']:g}us_prep{row['host_prep_us']}us"] = \
+                row["parallel_over_sequential"]
+    return out
+
+
 def cpu_baseline(cfg, pwb, budget_tokens: int = 128):
     if not cfg.has_head:
         return None
@@ -238,6 +264,10 @@ def main():
         result["dispatch_us_per_fn"] = dispatch_bench(ctx, pwb, I)
     model.close()
     ctx.close()
+    if not args.no_dispatch:
+        cabi = dispatch_bench_c_abi()
+        if cabi is not None:
+            result["dispatch_c_abi"] = cabi
     if not args.no_cpu_baseline:
         cb = cpu_baseline(cfg, pwb)
         if cb is not None:

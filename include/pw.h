@@ -148,6 +148,11 @@ pw_status pw_chain(pw_ctx* ctx, const pw_fn* fns, int n_fns, const pw_future* in
  * stream; each further one is a HIP stream of its own served by a host thread of its own - on one GPU the
  * stand-in for "a different set of cores attached to a different host".  n in [1, 64]; once per context. */
 pw_status pw_ctx_set_executors(pw_ctx* ctx, int n);
+/* Measurement aid: every node handed to an executor first costs its host thread `us` microseconds of busy work
+ * (0 by default, at most 100000) - a stand-in for the buffer allocation, scheduling and coordination that a
+ * node's host performs in a multi-host deployment and that does not depend on the node's predecessor.  With
+ * parallel dispatch these overlap across executors; with sequential dispatch they add up (Section 4.5). */
+pw_status pw_ctx_set_executor_prep_us(pw_ctx* ctx, int us);
 /* A chain whose node i runs on executor executor_of[i] (host array of n_fns ids): fns[0] consumes `in`, node i+1
  * consumes node i's output.  Only elementwise kinds (one fp32 input, one output of the same shape).  Where
  * consecutive nodes sit on different executors the consumer's input buffer is allocated up front and the

@@ -82,6 +82,7 @@ _SIGS = {
                            C.POINTER(C.c_uint64), C.c_int, C.c_int]),
     "pw_train_step": (C.c_int, [C.c_void_p, C.c_uint64, C.c_uint64, C.POINTER(C.c_uint64)]),
     "pw_ctx_set_executors": (C.c_int, [C.c_void_p, C.c_int]),
+    "pw_ctx_set_executor_prep_us": (C.c_int, [C.c_void_p, C.c_int]),
     "pw_pipeline": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.c_int, C.c_uint64,
                               C.POINTER(C.c_uint64), C.c_int]),
     "pw_await": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_size_t]),
@@ -235,6 +236,9 @@ class Context:
 
     def set_executors(self, n: int):
         self._check(lib().pw_ctx_set_executors(self._h, n))
+
+    def set_executor_prep_us(self, us: int):
+        self._check(lib().pw_ctx_set_executor_prep_us(self._h, us))
 
     def pipeline(self, fns, executor_of, f_in: int, dispatch: int = PW_DISPATCH_PARALLEL) -> int:
         a_f = (C.c_uint64 * len(fns))(*fns)

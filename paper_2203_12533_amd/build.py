@@ -35,11 +35,23 @@ def _compile(src: str, force: bool) -> str:
     return obj
 
 
+DISPATCH_BENCH = os.path.join(HERE, "tools", "dispatch_bench")
+
+
+def build_tools() -> str:
+    """The pure-C++ dispatch benchmark: host code only, talks to libpw.so through include/pw.h."""
+    subprocess.check_call(["g++", "-O2", "-std=c++17", "-I", os.path.join(HERE, "..", "include"),
+                           os.path.join(HERE, "tools", "dispatch_bench.cpp"), "-L", HERE, "-lpw",
+                           "-Wl,-rpath,$ORIGIN/..", "-Wl,-rpath,/opt/rocm/lib", "-o", DISPATCH_BENCH])
+    return DISPATCH_BENCH
+
+
 def build(force: bool = True, jobs: int = 8) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda s: _compile(s, force), SOURCES))
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
+    build_tools()
     return LIB
 
 

@@ -116,6 +116,7 @@ struct NodeMsg {
   hipEvent_t done_event = nullptr;   // recorded behind this node (and its transfer)
   std::atomic<int>* done_flag = nullptr;
   std::atomic<int>* ack = nullptr;   // 1: enqueued, 2: failed
+  int prep_us = 0;                   // emulated host-side preparation (see pw_ctx_set_executor_prep_us)
 };
 
 struct Executor {
@@ -158,6 +159,7 @@ struct pw_ctx {
   std::unordered_map<std::string, GraphEntry> graphs;
 
   std::vector<std::unique_ptr<Executor>> executors;   // pw_ctx_set_executors; [0] wraps the executor stream
+  int executor_prep_us = 0;
 };
 
 struct pw_model {
@@ -344,6 +346,10 @@ bool model_alive(pw_ctx* c, Model* m) {
 // (wait_flag), everything else a thread does for its node runs concurrently with the other threads.
 void executor_handle(int device, Executor* ex, NodeMsg& m) {
   bool ok = true;
+  if (m.prep_us > 0) {   // host-side work for this node that needs nothing from its predecessor
+    const auto t0 = std::chrono::steady_clock::now();
+    while (std::chrono::steady_clock::now() - t0 < std::chrono::microseconds(m.prep_us)) {}
+  }
   if (m.wait_flag) {
     const auto t0 = std::chrono::steady_clock::now();
     int v;
@@ -795,6 +801,12 @@ pw_status pw_ctx_set_executors(pw_ctx* c, int n) {
   return PW_OK;
 }
 
+pw_status pw_ctx_set_executor_prep_us(pw_ctx* c, int us) {
+  if (!c || us < 0 || us > 100000) return PW_ERR_INVALID;
+  c->executor_prep_us = us;
+  return PW_OK;
+}
+
 pw_status pw_pipeline(pw_ctx* c, const pw_fn* fns, const int32_t* executor_of, int n_fns, pw_future in, pw_future* out, int dispatch) {
   if (!c || !fns || !executor_of || !out || n_fns < 1 || n_fns > 4096) return PW_ERR_INVALID;
   if (dispatch != PW_DISPATCH_PARALLEL && dispatch != PW_DISPATCH_SEQUENTIAL) return fail(c, PW_ERR_INVALID, "bad dispatch mode");
@@ -865,6 +877,7 @@ pw_status pw_pipeline(pw_ctx* c, const pw_fn* fns, const int32_t* executor_of, i
     if (from_other) { m.wait_event = plan[i - 1].ev; m.wait_flag = &flags[i - 1]; }
     else if (i > 0) { m.wait_flag = &flags[i - 1]; }   // same stream: only the host-side order of the two enqueues matters
     m.done_event = plan[i].ev; m.done_flag = &flags[i]; m.ack = &acks[i];
+    m.prep_us = c->executor_prep_us;
     Executor* ex = c->executors[executor_of[i]].get();
     {
       std::lock_guard<std::mutex> lk(ex->mu);
