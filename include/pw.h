@@ -103,6 +103,19 @@ typedef enum {
                                  (Figure 4a; the comparison of Section 5.1, Figure 7) */
 } pw_dispatch_mode;
 
+typedef enum {
+  PW_SCHED_FIFO = 0,          /* programs reach the executor in arrival order (the paper's current policy) */
+  PW_SCHED_PROPORTIONAL = 1   /* among clients with work queued, the one with the least weighted device time goes
+                                 next (the proportional-share multi-tenancy of Section 5.2) */
+} pw_sched_policy;
+
+typedef struct pw_sched pw_sched;   /* owned by its context; destroyed with it at the latest */
+typedef struct {
+  int32_t client;
+  int32_t computations;     /* computations the program contained */
+  float start_ms, end_ms;   /* on the device, relative to the scheduler's creation */
+} pw_sched_slice;
+
 /* ---- context -------------------------------------------------------------------------------- */
 
 /* Create a context on `device`.  `hip_stream` (a hipStream_t created by the caller, e.g. PyTorch's
@@ -162,6 +175,33 @@ pw_status pw_ctx_set_executor_prep_us(pw_ctx* ctx, int us);
  * (refcount 1).  dispatch: a pw_dispatch_mode.  Not thread-safe, like every call on a context. */
 pw_status pw_pipeline(pw_ctx* ctx, const pw_fn* fns, const int32_t* executor_of, int n_fns, pw_future in,
                       pw_future* out, int dispatch);
+
+/* ---- several clients, one executor: the centralized scheduler (Section 4.4 "gang-scheduled dynamic dispatch",
+ * measured in Section 5.2).  pw_sched_submit / _wait / _client_stats / _drain / _trace may be called from any
+ * thread at any time; so may the function / future / chain / await calls of the context while a scheduler exists
+ * (they are serialised inside).  Model and pw_op_* calls stay single-threaded. */
+/* max_in_flight: programs the scheduler keeps enqueued on the device at once (1..1024); the rest wait in the
+ * clients' queues, where the policy still has a say. */
+pw_status pw_sched_create(pw_ctx* ctx, int policy, int max_in_flight, pw_sched** out);
+/* Stops the scheduler thread after the queued programs have been enqueued and have run; results that were never
+ * collected are released. */
+pw_status pw_sched_destroy(pw_sched* sched);
+/* weight > 0: share of device time under PW_SCHED_PROPORTIONAL (ignored by FIFO).  *client: id for the calls below. */
+pw_status pw_sched_add_client(pw_sched* sched, double weight, int* client);
+/* Queue a program: the chain fns[0..n_fns) applied to `in` (one input, one output; validated when it is enqueued).
+ * Returns at once with a ticket.  `in` must stay alive until the ticket has been waited for. */
+pw_status pw_sched_submit(pw_sched* sched, int client, const pw_fn* fns, int n_fns, pw_future in, uint64_t* ticket);
+/* Blocks until the program has run; copies `bytes` of its output to host_dst (may be null / 0); the output
+ * future is released.  A ticket can be waited for once.  Returns the program's status. */
+pw_status pw_sched_wait(pw_sched* sched, uint64_t ticket, void* host_dst, size_t bytes);
+/* Blocks until every queued program has been enqueued, has run and has been accounted for. */
+pw_status pw_sched_drain(pw_sched* sched);
+/* Programs and computations enqueued for the client so far, and the device time (HIP events around each program)
+ * of those that have been retired. */
+pw_status pw_sched_client_stats(pw_sched* sched, int client, int64_t* programs, int64_t* computations, double* device_ms);
+/* Device-time slices of retired programs in execution order (at most the first 65536): copies min(capacity, n)
+ * of them, *n = how many there are. */
+pw_status pw_sched_trace(pw_sched* sched, pw_sched_slice* out, int capacity, int* n);
 
 /* One LM train step: pw_run_fn on a function of kind PW_FN_LM_TRAIN_STEP.  The model's parameters
  * and optimiser state are updated in place on the device (they are the function's private state). */

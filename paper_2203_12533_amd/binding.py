@@ -22,6 +22,7 @@ STATUS_NAMES = ["PW_OK", "PW_ERR_INVALID", "PW_ERR_SHAPE", "PW_ERR_DTYPE", "PW_E
 PW_F32, PW_BF16, PW_I32 = 0, 1, 2
 PW_FN_ADD_CONST, PW_FN_MUL_CONST, PW_FN_DIV_CONST, PW_FN_BUSY, PW_FN_BUSY_CHAIN = 1, 2, 3, 4, 5
 PW_DISPATCH_PARALLEL, PW_DISPATCH_SEQUENTIAL = 0, 1
+PW_SCHED_FIFO, PW_SCHED_PROPORTIONAL = 0, 1
 PW_FN_LM_TRAIN_STEP, PW_FN_STAGE_FWD, PW_FN_STAGE_BWD = 16, 17, 18
 PW_STREAM, PW_GRAPH, PW_SEQUENTIAL = 0, 1, 2
 PW_PARAMS, PW_GRADS, PW_ADAM_M, PW_ADAM_V = 0, 1, 2, 3
@@ -81,6 +82,14 @@ _SIGS = {
     "pw_chain": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64), C.c_int, C.POINTER(C.c_uint64), C.c_int,
                            C.POINTER(C.c_uint64), C.c_int, C.c_int]),
     "pw_train_step": (C.c_int, [C.c_void_p, C.c_uint64, C.c_uint64, C.POINTER(C.c_uint64)]),
+    "pw_sched_create": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_void_p)]),
+    "pw_sched_destroy": (C.c_int, [C.c_void_p]),
+    "pw_sched_add_client": (C.c_int, [C.c_void_p, C.c_double, C.POINTER(C.c_int)]),
+    "pw_sched_submit": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_uint64), C.c_int, C.c_uint64, C.POINTER(C.c_uint64)]),
+    "pw_sched_wait": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_size_t]),
+    "pw_sched_drain": (C.c_int, [C.c_void_p]),
+    "pw_sched_client_stats": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
+    "pw_sched_trace": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int)]),
     "pw_ctx_set_executors": (C.c_int, [C.c_void_p, C.c_int]),
     "pw_ctx_set_executor_prep_us": (C.c_int, [C.c_void_p, C.c_int]),
     "pw_pipeline": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.c_int, C.c_uint64,
@@ -339,6 +348,59 @@ class Context:
             for k, v in kw.items():
                 setattr(a, k, v)
         self._check(lib().pw_op_gemm_pair(self._h, C.byref(a0), C.byref(a1)))
+
+
+class SchedSlice(C.Structure):
+    _fields_ = [("client", C.c_int32), ("computations", C.c_int32), ("start_ms", C.c_float), ("end_ms", C.c_float)]
+
+
+class Scheduler:
+    """pw_sched: several clients, one executor.  submit / wait / stats may be called from any thread."""
+
+    def __init__(self, ctx: Context, policy: int = PW_SCHED_FIFO, max_in_flight: int = 4):
+        self._ctx = ctx
+        self._h = C.c_void_p()
+        ctx._check(lib().pw_sched_create(ctx.handle, policy, max_in_flight, C.byref(self._h)))
+
+    def _check(self, st: int):
+        if st != PW_OK:
+            raise PwError(st, lib().pw_last_error(self._ctx.handle).decode())
+
+    def add_client(self, weight: float = 1.0) -> int:
+        cid = C.c_int()
+        self._check(lib().pw_sched_add_client(self._h, weight, C.byref(cid)))
+        return cid.value
+
+    def submit(self, client: int, fns, f_in: int) -> int:
+        a_f = (C.c_uint64 * len(fns))(*fns)
+        t = C.c_uint64()
+        self._check(lib().pw_sched_submit(self._h, client, a_f, len(fns), f_in, C.byref(t)))
+        return t.value
+
+    def wait(self, ticket: int, n_floats: int = 0):
+        out = np.empty(n_floats, np.float32)
+        self._check(lib().pw_sched_wait(self._h, ticket, out.ctypes.data_as(C.c_void_p) if n_floats else None, n_floats * 4))
+        return out
+
+    def drain(self):
+        self._check(lib().pw_sched_drain(self._h))
+
+    def client_stats(self, client: int):
+        p, n, ms = C.c_int64(), C.c_int64(), C.c_double()
+        self._check(lib().pw_sched_client_stats(self._h, client, C.byref(p), C.byref(n), C.byref(ms)))
+        return p.value, n.value, ms.value
+
+    def trace(self):
+        n = C.c_int()
+        self._check(lib().pw_sched_trace(self._h, None, 0, C.byref(n)))
+        arr = (SchedSlice * max(1, n.value))()
+        self._check(lib().pw_sched_trace(self._h, arr, n.value, C.byref(n)))
+        return [(a.client, a.computations, a.start_ms, a.end_ms) for a in arr[:n.value]]
+
+    def close(self):
+        if self._h:
+            lib().pw_sched_destroy(self._h)
+            self._h = None
 
 
 def lm_config_c(cfg) -> LMConfigC:

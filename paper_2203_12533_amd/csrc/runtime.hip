@@ -17,6 +17,7 @@
 // word in pinned host memory; consumers wait on the event recorded behind it.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <chrono>
 #include <condition_variable>
@@ -131,6 +132,8 @@ struct Executor {
 
 }  // namespace
 
+struct pw_sched;
+
 struct pw_ctx {
   int device = 0;
   hipStream_t exec = nullptr;      // executor stream
@@ -160,11 +163,71 @@ struct pw_ctx {
 
   std::vector<std::unique_ptr<Executor>> executors;   // pw_ctx_set_executors; [0] wraps the executor stream
   int executor_prep_us = 0;
+
+  // Serialises the dispatch calls (functions, futures, chains, pipelines, await) so that client threads and the
+  // scheduler thread of pw_sched may share a context.  Recursive: some calls are built from others.
+  std::recursive_mutex api_mu;
+  std::vector<pw_sched*> scheds;
 };
+
+#define PW_API_LOCK(c)                                  \
+  std::unique_lock<std::recursive_mutex> api_lk_;       \
+  if (c) api_lk_ = std::unique_lock<std::recursive_mutex>((c)->api_mu)
 
 struct pw_model {
   pw_ctx* ctx;
   Model* impl;
+};
+
+// ---- multi-tenant scheduler (Section 4.4 "centralized scheduler", Section 5.2) -----------------------------
+// Clients (any threads) put programs - chains of compiled functions - into per-client queues; ONE scheduler
+// thread decides the order in which programs reach the executor stream, so that order is consistent whatever
+// the clients do.  FIFO takes programs in arrival order; proportional share takes, among the clients that have
+// work queued, the one whose weighted device time consumed so far (estimated at enqueue) is smallest (stride
+// scheduling).  Only a bounded number of programs is kept in flight on the device, so a client that arrives
+// late is not stuck behind an arbitrarily long backlog of others.
+namespace {
+struct SchedProgram {
+  std::vector<pw_fn> fns;
+  pw_future in = 0;
+  uint64_t ticket = 0, arrival = 0;
+  double est_us = 0;
+  int n_computations = 0;
+};
+struct SchedClient {
+  double weight = 1, vtime = 0;
+  std::deque<SchedProgram> queue;
+  int64_t programs = 0, computations = 0;
+  double device_ms = 0;
+};
+struct SchedResult {
+  pw_status status = PW_OK;
+  pw_future out = 0;
+};
+struct SchedInFlight {
+  int client = 0;
+  int n_computations = 0;
+  hipEvent_t start = nullptr, stop = nullptr;
+};
+}  // namespace
+
+struct pw_sched {
+  pw_ctx* ctx = nullptr;
+  int policy = PW_SCHED_FIFO;
+  int window = 4;                       // programs in flight on the device at most
+  std::mutex mu;
+  std::condition_variable cv_work, cv_done;
+  std::vector<SchedClient> clients;
+  std::unordered_map<uint64_t, SchedResult> results;
+  std::unordered_map<uint64_t, bool> outstanding;   // tickets handed out and not yet collected (value: someone is waiting)
+  uint64_t next_ticket = 1, next_arrival = 1;
+  int64_t queued = 0;
+  std::deque<SchedInFlight> inflight;   // scheduler thread only
+  std::vector<hipEvent_t> timing_events;
+  hipEvent_t epoch = nullptr;           // recorded at creation: slices are reported relative to it
+  std::vector<pw_sched_slice> trace;
+  bool stop = false, idle = true;
+  std::thread thread;
 };
 
 namespace {
@@ -441,6 +504,7 @@ pw_status pw_ctx_create(int device, void* hip_stream, pw_ctx** out) {
 pw_status pw_ctx_destroy(pw_ctx* c) {
   if (!c) return PW_ERR_INVALID;
   (void)hipSetDevice(c->device);
+  while (!c->scheds.empty()) (void)pw_sched_destroy(c->scheds.back());
   stop_executors(c);
   // release every gate that is still waiting so that the streams can drain
   for (auto& f : c->futures)
@@ -479,18 +543,21 @@ const char* pw_last_error(pw_ctx* c) { return c ? c->error.c_str() : "null conte
 void* pw_ctx_stream(pw_ctx* c) { return c ? (void*)c->exec : nullptr; }
 
 pw_status pw_ctx_synchronize(pw_ctx* c) {
+  PW_API_LOCK(c);
   if (!c) return PW_ERR_INVALID;
   PW_HIP(c, hipStreamSynchronize(c->exec));
   return PW_OK;
 }
 
 pw_status pw_ctx_set_gate_timeout_ms(pw_ctx* c, int ms) {
+  PW_API_LOCK(c);
   if (!c || ms < 1 || ms > 600000) return PW_ERR_INVALID;
   c->gate_timeout_ms = ms;
   return PW_OK;
 }
 
 pw_status pw_ctx_stats(pw_ctx* c, int64_t* live_futures, int64_t* pool_bytes_in_use) {
+  PW_API_LOCK(c);
   if (!c) return PW_ERR_INVALID;
   if (live_futures) *live_futures = c->live_futures;
   if (pool_bytes_in_use) *pool_bytes_in_use = c->pool_in_use;
@@ -500,6 +567,7 @@ pw_status pw_ctx_stats(pw_ctx* c, int64_t* live_futures, int64_t* pool_bytes_in_
 // ---- compiled functions -----------------------------------------------------------------------------
 
 pw_status pw_compile_fn(pw_ctx* c, const pw_fn_desc* d, pw_fn* out) {
+  PW_API_LOCK(c);
   if (!c || !d || !out) return PW_ERR_INVALID;
   if (d->n_in < 0 || d->n_in > 8 || d->n_out < 0 || d->n_out > 8) return fail(c, PW_ERR_INVALID, "n_in / n_out out of range");
   for (int i = 0; i < d->n_in; ++i)
@@ -575,6 +643,7 @@ pw_status pw_compile_fn(pw_ctx* c, const pw_fn_desc* d, pw_fn* out) {
 }
 
 pw_status pw_fn_release(pw_ctx* c, pw_fn h) {
+  PW_API_LOCK(c);
   if (!c) return PW_ERR_INVALID;
   FnRec* f = fn_get(c, h);
   if (!f) return fail(c, PW_ERR_INVALID, "bad function handle");
@@ -583,6 +652,7 @@ pw_status pw_fn_release(pw_ctx* c, pw_fn h) {
 }
 
 pw_status pw_run_fn(pw_ctx* c, pw_fn h, const pw_future* in, int n_in, pw_future* out, int n_out) {
+  PW_API_LOCK(c);
   if (!c || (n_in > 0 && !in) || (n_out > 0 && !out) || n_in < 0 || n_in > 8 || n_out < 0 || n_out > 8) return PW_ERR_INVALID;
   FnRec* fn = fn_get(c, h);
   if (!fn) return fail(c, PW_ERR_INVALID, "bad function handle");
@@ -641,6 +711,7 @@ pw_status pw_run_fn(pw_ctx* c, pw_fn h, const pw_future* in, int n_in, pw_future
 }
 
 pw_status pw_chain(pw_ctx* c, const pw_fn* fns, int n_fns, const pw_future* in, int n_in, pw_future* out, int n_out, int mode) {
+  PW_API_LOCK(c);
   if (!c || !fns || n_fns < 1 || n_fns > 4096 || (n_in > 0 && !in) || (n_out > 0 && !out) || n_in < 0 || n_in > 8 || n_out < 0 || n_out > 8)
     return PW_ERR_INVALID;
   if (mode != PW_STREAM && mode != PW_GRAPH && mode != PW_SEQUENTIAL) return fail(c, PW_ERR_INVALID, "bad chain mode");
@@ -780,6 +851,7 @@ pw_status pw_chain(pw_ctx* c, const pw_fn* fns, int n_fns, const pw_future* in, 
 }
 
 pw_status pw_ctx_set_executors(pw_ctx* c, int n) {
+  PW_API_LOCK(c);
   if (!c) return PW_ERR_INVALID;
   if (n < 1 || n > 64) return fail(c, PW_ERR_INVALID, "executor count must be within [1, 64]");
   if (!c->executors.empty()) return fail(c, PW_ERR_INVALID, "executors are already set up");
@@ -802,12 +874,14 @@ pw_status pw_ctx_set_executors(pw_ctx* c, int n) {
 }
 
 pw_status pw_ctx_set_executor_prep_us(pw_ctx* c, int us) {
+  PW_API_LOCK(c);
   if (!c || us < 0 || us > 100000) return PW_ERR_INVALID;
   c->executor_prep_us = us;
   return PW_OK;
 }
 
 pw_status pw_pipeline(pw_ctx* c, const pw_fn* fns, const int32_t* executor_of, int n_fns, pw_future in, pw_future* out, int dispatch) {
+  PW_API_LOCK(c);
   if (!c || !fns || !executor_of || !out || n_fns < 1 || n_fns > 4096) return PW_ERR_INVALID;
   if (dispatch != PW_DISPATCH_PARALLEL && dispatch != PW_DISPATCH_SEQUENTIAL) return fail(c, PW_ERR_INVALID, "bad dispatch mode");
   if (c->executors.empty()) return fail(c, PW_ERR_INVALID, "call pw_ctx_set_executors first");
@@ -920,7 +994,254 @@ pw_status pw_pipeline(pw_ctx* c, const pw_fn* fns, const int32_t* executor_of, i
   return PW_OK;
 }
 
+// ---- scheduler ---------------------------------------------------------------------------------------------
+namespace {
+
+hipEvent_t sched_event(pw_sched* s) {
+  if (!s->timing_events.empty()) {
+    hipEvent_t e = s->timing_events.back();
+    s->timing_events.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+// Retire the oldest program in flight: wait for it, charge its device time to its client.
+void sched_retire(pw_sched* s) {
+  SchedInFlight f = s->inflight.front();
+  s->inflight.pop_front();
+  float ms = 0.f, t0 = 0.f;
+  const bool ok = f.start && f.stop && hipEventSynchronize(f.stop) == hipSuccess &&
+                  hipEventElapsedTime(&ms, f.start, f.stop) == hipSuccess &&
+                  hipEventElapsedTime(&t0, s->epoch, f.start) == hipSuccess;
+  std::lock_guard<std::mutex> lk(s->mu);
+  if (ok) {
+    SchedClient& c = s->clients[f.client];
+    c.device_ms += ms;
+    if (s->trace.size() < 65536) s->trace.push_back(pw_sched_slice{f.client, f.n_computations, t0, t0 + ms});
+  }
+  if (f.start) s->timing_events.push_back(f.start);
+  if (f.stop) s->timing_events.push_back(f.stop);
+}
+
+void sched_loop(pw_sched* s) {
+  (void)hipSetDevice(s->ctx->device);
+  for (;;) {
+    SchedProgram prog;
+    int client = -1;
+    {
+      std::unique_lock<std::mutex> lk(s->mu);
+      while (!s->stop && s->queued == 0) {
+        if (!s->inflight.empty()) {          // nothing to hand out: use the time to retire finished programs
+          lk.unlock();
+          sched_retire(s);
+          lk.lock();
+          continue;
+        }
+        s->idle = true;
+        s->cv_done.notify_all();
+        s->cv_work.wait(lk);
+      }
+      if (s->stop && s->queued == 0) break;
+      s->idle = false;
+      // ---- the policy
+      double best = 0;
+      for (int i = 0; i < (int)s->clients.size(); ++i) {
+        SchedClient& c = s->clients[i];
+        if (c.queue.empty()) continue;
+        const double key = s->policy == PW_SCHED_FIFO ? (double)c.queue.front().arrival : c.vtime;
+        if (client < 0 || key < best) { client = i; best = key; }
+      }
+      SchedClient& c = s->clients[client];
+      prog = std::move(c.queue.front());
+      c.queue.pop_front();
+      s->queued--;
+      c.vtime += prog.est_us / c.weight;
+    }
+    while ((int)s->inflight.size() >= s->window) sched_retire(s);
+    // ---- enqueue on the executor stream, bracketed by timing events
+    SchedInFlight fl;
+    fl.client = client;
+    fl.n_computations = prog.n_computations;
+    SchedResult res;
+    {
+      std::unique_lock<std::recursive_mutex> api(s->ctx->api_mu);
+      fl.start = sched_event(s);
+      fl.stop = sched_event(s);
+      if (fl.start) (void)hipEventRecord(fl.start, s->ctx->exec);
+      res.status = pw_chain(s->ctx, prog.fns.data(), (int)prog.fns.size(), &prog.in, 1, &res.out, 1, PW_STREAM);
+      if (fl.stop) (void)hipEventRecord(fl.stop, s->ctx->exec);
+    }
+    s->inflight.push_back(fl);
+    {
+      std::lock_guard<std::mutex> lk(s->mu);
+      s->results[prog.ticket] = res;
+      SchedClient& c = s->clients[client];
+      c.programs++;
+      if (res.status == PW_OK) c.computations += prog.n_computations;
+    }
+    s->cv_done.notify_all();
+  }
+  while (!s->inflight.empty()) sched_retire(s);
+  std::lock_guard<std::mutex> lk(s->mu);
+  s->idle = true;
+  s->cv_done.notify_all();
+}
+
+void sched_shutdown(pw_sched* s) {
+  {
+    std::lock_guard<std::mutex> lk(s->mu);
+    s->stop = true;
+  }
+  s->cv_work.notify_all();
+  if (s->thread.joinable()) s->thread.join();
+  // results nobody collected: give their futures back
+  for (auto& kv : s->results)
+    if (kv.second.status == PW_OK && kv.second.out) (void)pw_future_release(s->ctx, kv.second.out);
+  s->results.clear();
+  for (hipEvent_t e : s->timing_events) (void)hipEventDestroy(e);
+  if (s->epoch) (void)hipEventDestroy(s->epoch);
+}
+
+}  // namespace
+
+pw_status pw_sched_create(pw_ctx* c, int policy, int max_in_flight, pw_sched** out) {
+  if (!c || !out) return PW_ERR_INVALID;
+  PW_API_LOCK(c);
+  if (policy != PW_SCHED_FIFO && policy != PW_SCHED_PROPORTIONAL) return fail(c, PW_ERR_INVALID, "unknown scheduling policy");
+  if (max_in_flight < 1 || max_in_flight > 1024) return fail(c, PW_ERR_INVALID, "programs in flight must be within [1, 1024]");
+  pw_sched* s = new pw_sched();
+  s->ctx = c;
+  s->policy = policy;
+  s->window = max_in_flight;
+  if (hipEventCreate(&s->epoch) != hipSuccess || hipEventRecord(s->epoch, c->exec) != hipSuccess) {
+    if (s->epoch) (void)hipEventDestroy(s->epoch);
+    delete s;
+    return fail(c, PW_ERR_DEVICE, "could not create the scheduler's timing events");
+  }
+  s->thread = std::thread(sched_loop, s);
+  c->scheds.push_back(s);
+  *out = s;
+  return PW_OK;
+}
+
+pw_status pw_sched_destroy(pw_sched* s) {
+  if (!s) return PW_ERR_INVALID;
+  pw_ctx* c = s->ctx;
+  sched_shutdown(s);
+  {
+    PW_API_LOCK(c);
+    for (size_t i = 0; i < c->scheds.size(); ++i)
+      if (c->scheds[i] == s) { c->scheds.erase(c->scheds.begin() + i); break; }
+  }
+  delete s;
+  return PW_OK;
+}
+
+pw_status pw_sched_add_client(pw_sched* s, double weight, int* client) {
+  if (!s || !client || !(weight > 0.0) || weight > 1e6) return PW_ERR_INVALID;
+  std::lock_guard<std::mutex> lk(s->mu);
+  if (s->clients.size() >= 1024) return PW_ERR_INVALID;
+  SchedClient c;
+  c.weight = weight;
+  // a newcomer starts level with the least-served client, not with a credit for the past
+  bool any = false;
+  for (auto& o : s->clients)
+    if (!any || o.vtime < c.vtime) { c.vtime = o.vtime; any = true; }
+  s->clients.push_back(c);
+  *client = (int)s->clients.size() - 1;
+  return PW_OK;
+}
+
+pw_status pw_sched_submit(pw_sched* s, int client, const pw_fn* fns, int n_fns, pw_future in, uint64_t* ticket) {
+  if (!s || !fns || !ticket || n_fns < 1 || n_fns > 4096) return PW_ERR_INVALID;
+  SchedProgram p;
+  p.fns.assign(fns, fns + n_fns);
+  p.in = in;
+  {
+    // cost estimate from the compiled functions (busy time where known, a launch's worth otherwise)
+    PW_API_LOCK(s->ctx);
+    for (int i = 0; i < n_fns; ++i) {
+      FnRec* f = fn_get(s->ctx, fns[i]);
+      if (!f) return fail(s->ctx, PW_ERR_INVALID, "function %d of the program is not a live handle", i);
+      p.est_us += 3.0 + (double)f->busy_us * f->reps;
+      p.n_computations += f->reps;
+    }
+    if (!future_get(s->ctx, in)) return fail(s->ctx, PW_ERR_INVALID, "input is not a live future");
+  }
+  std::lock_guard<std::mutex> lk(s->mu);
+  if (client < 0 || client >= (int)s->clients.size()) return PW_ERR_INVALID;
+  if (s->stop) return PW_ERR_INVALID;
+  SchedClient& c = s->clients[client];
+  if (c.queue.empty() && s->policy == PW_SCHED_PROPORTIONAL) {
+    // back from idle: no credit for time not used
+    bool any = false;
+    double floor_v = 0;
+    for (auto& o : s->clients)
+      if (!o.queue.empty() && (!any || o.vtime < floor_v)) { floor_v = o.vtime; any = true; }
+    if (any && c.vtime < floor_v) c.vtime = floor_v;
+  }
+  p.ticket = s->next_ticket++;
+  p.arrival = s->next_arrival++;
+  *ticket = p.ticket;
+  s->outstanding[p.ticket] = false;
+  c.queue.push_back(std::move(p));
+  s->queued++;
+  s->cv_work.notify_one();
+  return PW_OK;
+}
+
+pw_status pw_sched_wait(pw_sched* s, uint64_t ticket, void* host_dst, size_t bytes) {
+  if (!s) return PW_ERR_INVALID;
+  SchedResult r;
+  {
+    std::unique_lock<std::mutex> lk(s->mu);
+    auto o = s->outstanding.find(ticket);
+    if (o == s->outstanding.end() || o->second) return PW_ERR_INVALID;   // unknown, collected already, or being waited for
+    o->second = true;
+    s->cv_done.wait(lk, [&] { return s->results.count(ticket) != 0 || s->stop; });
+    s->outstanding.erase(ticket);
+    auto it = s->results.find(ticket);
+    if (it == s->results.end()) return PW_ERR_INVALID;   // the scheduler was shut down first
+    r = it->second;
+    s->results.erase(it);
+  }
+  if (r.status != PW_OK) return r.status;
+  pw_status st = pw_await(s->ctx, r.out, host_dst, bytes);
+  (void)pw_future_release(s->ctx, r.out);
+  return st;
+}
+
+pw_status pw_sched_drain(pw_sched* s) {
+  if (!s) return PW_ERR_INVALID;
+  std::unique_lock<std::mutex> lk(s->mu);
+  s->cv_done.wait(lk, [&] { return (s->queued == 0 && s->idle) || s->stop; });
+  return PW_OK;
+}
+
+pw_status pw_sched_client_stats(pw_sched* s, int client, int64_t* programs, int64_t* computations, double* device_ms) {
+  if (!s) return PW_ERR_INVALID;
+  std::lock_guard<std::mutex> lk(s->mu);
+  if (client < 0 || client >= (int)s->clients.size()) return PW_ERR_INVALID;
+  if (programs) *programs = s->clients[client].programs;
+  if (computations) *computations = s->clients[client].computations;
+  if (device_ms) *device_ms = s->clients[client].device_ms;
+  return PW_OK;
+}
+
+pw_status pw_sched_trace(pw_sched* s, pw_sched_slice* out, int capacity, int* n) {
+  if (!s || !n || capacity < 0 || (capacity > 0 && !out)) return PW_ERR_INVALID;
+  std::lock_guard<std::mutex> lk(s->mu);
+  const int k = std::min<int>(capacity, (int)s->trace.size());
+  for (int i = 0; i < k; ++i) out[i] = s->trace[i];
+  *n = (int)s->trace.size();
+  return PW_OK;
+}
+
 pw_status pw_train_step(pw_ctx* c, pw_fn step_fn, pw_future tokens, pw_future* loss_out) {
+  PW_API_LOCK(c);
   if (!c || !loss_out) return PW_ERR_INVALID;
   FnRec* fn = fn_get(c, step_fn);
   if (!fn || fn->desc.kind != PW_FN_LM_TRAIN_STEP) return fail(c, PW_ERR_INVALID, "not a train-step function");
@@ -931,22 +1252,35 @@ pw_status pw_train_step(pw_ctx* c, pw_fn step_fn, pw_future tokens, pw_future* l
 
 pw_status pw_await(pw_ctx* c, pw_future h, void* host_dst, size_t bytes) {
   if (!c) return PW_ERR_INVALID;
+  PW_API_LOCK(c);
   FutureRec* f = future_get(c, h);
   if (!f) return fail(c, PW_ERR_INVALID, "bad future handle");
   if (bytes > f->bytes) return fail(c, PW_ERR_SHAPE, "asked for %zu bytes of a %zu-byte future", bytes, f->bytes);
-  if (f->event) PW_HIP(c, hipEventSynchronize(f->event));
-  else PW_HIP(c, hipStreamSynchronize(c->exec));
-  if (f->host_poison) return fail(c, PW_ERR_POISONED, "future depends on a failed producer");
-  for (auto& p : f->poison)
-    if (__atomic_load_n(&p->words[1], __ATOMIC_ACQUIRE)) return fail(c, PW_ERR_POISONED, "a pending input was poisoned or timed out");
-  if (host_dst && bytes) {
-    PW_HIP(c, hipMemcpyAsync(host_dst, f->buf, bytes, hipMemcpyDeviceToHost, c->io));
-    PW_HIP(c, hipStreamSynchronize(c->io));
+  // Block without holding the lock (other threads keep dispatching); the extra reference keeps the record and
+  // its event alive meanwhile.
+  f->refcount++;
+  hipEvent_t ev = f->event;
+  hipStream_t exec = c->exec;
+  api_lk_.unlock();
+  hipError_t e = ev ? hipEventSynchronize(ev) : hipStreamSynchronize(exec);
+  api_lk_.lock();
+  f = future_get(c, h);   // the table may have been reallocated
+  pw_status st = PW_OK;
+  if (e != hipSuccess) st = fail(c, PW_ERR_DEVICE, "waiting for the future: %s", hipGetErrorString(e));
+  if (st == PW_OK && f->host_poison) st = fail(c, PW_ERR_POISONED, "future depends on a failed producer");
+  if (st == PW_OK)
+    for (auto& p : f->poison)
+      if (__atomic_load_n(&p->words[1], __ATOMIC_ACQUIRE)) { st = fail(c, PW_ERR_POISONED, "a pending input was poisoned or timed out"); break; }
+  if (st == PW_OK && host_dst && bytes) {
+    if (hipMemcpyAsync(host_dst, f->buf, bytes, hipMemcpyDeviceToHost, c->io) != hipSuccess || hipStreamSynchronize(c->io) != hipSuccess)
+      st = fail(c, PW_ERR_DEVICE, "copy to the host failed");
   }
-  return PW_OK;
+  future_drop(c, h);
+  return st;
 }
 
 pw_status pw_future_from_host(pw_ctx* c, const void* src, const pw_tensor_spec* spec, pw_future* out) {
+  PW_API_LOCK(c);
   if (!c || !src || !spec || !out) return PW_ERR_INVALID;
   if (!spec_ok(*spec)) return fail(c, PW_ERR_INVALID, "malformed spec");
   void* buf;
@@ -964,6 +1298,7 @@ pw_status pw_future_from_host(pw_ctx* c, const void* src, const pw_tensor_spec* 
 }
 
 pw_status pw_future_wrap_device(pw_ctx* c, void* dev_ptr, const pw_tensor_spec* spec, pw_future* out) {
+  PW_API_LOCK(c);
   if (!c || !dev_ptr || !spec || !out) return PW_ERR_INVALID;
   if (!spec_ok(*spec)) return fail(c, PW_ERR_INVALID, "malformed spec");
   FutureRec* f;
@@ -973,6 +1308,7 @@ pw_status pw_future_wrap_device(pw_ctx* c, void* dev_ptr, const pw_tensor_spec* 
 }
 
 pw_status pw_future_pending(pw_ctx* c, const pw_tensor_spec* spec, pw_future* out) {
+  PW_API_LOCK(c);
   if (!c || !spec || !out) return PW_ERR_INVALID;
   if (!spec_ok(*spec)) return fail(c, PW_ERR_INVALID, "malformed spec");
   const size_t bytes = spec_bytes(*spec);
@@ -1017,6 +1353,7 @@ pw_status pw_future_pending(pw_ctx* c, const pw_tensor_spec* spec, pw_future* ou
 }
 
 pw_status pw_future_resolve(pw_ctx* c, pw_future h, const void* host_src) {
+  PW_API_LOCK(c);
   if (!c) return PW_ERR_INVALID;
   FutureRec* f = future_get(c, h);
   if (!f) return fail(c, PW_ERR_INVALID, "bad future handle");
@@ -1033,6 +1370,7 @@ pw_status pw_future_resolve(pw_ctx* c, pw_future h, const void* host_src) {
 }
 
 pw_status pw_future_query(pw_ctx* c, pw_future h) {
+  PW_API_LOCK(c);
   if (!c) return PW_ERR_INVALID;
   FutureRec* f = future_get(c, h);
   if (!f) return fail(c, PW_ERR_INVALID, "bad future handle");
@@ -1046,6 +1384,7 @@ pw_status pw_future_query(pw_ctx* c, pw_future h) {
 }
 
 pw_status pw_future_spec(pw_ctx* c, pw_future h, pw_tensor_spec* out) {
+  PW_API_LOCK(c);
   if (!c || !out) return PW_ERR_INVALID;
   FutureRec* f = future_get(c, h);
   if (!f) return fail(c, PW_ERR_INVALID, "bad future handle");
@@ -1054,6 +1393,7 @@ pw_status pw_future_spec(pw_ctx* c, pw_future h, pw_tensor_spec* out) {
 }
 
 pw_status pw_future_device_ptr(pw_ctx* c, pw_future h, void** out) {
+  PW_API_LOCK(c);
   if (!c || !out) return PW_ERR_INVALID;
   FutureRec* f = future_get(c, h);
   if (!f) return fail(c, PW_ERR_INVALID, "bad future handle");
@@ -1062,6 +1402,7 @@ pw_status pw_future_device_ptr(pw_ctx* c, pw_future h, void** out) {
 }
 
 pw_status pw_future_retain(pw_ctx* c, pw_future h) {
+  PW_API_LOCK(c);
   if (!c) return PW_ERR_INVALID;
   FutureRec* f = future_get(c, h);
   if (!f) return fail(c, PW_ERR_INVALID, "bad future handle");
@@ -1070,6 +1411,7 @@ pw_status pw_future_retain(pw_ctx* c, pw_future h) {
 }
 
 pw_status pw_future_release(pw_ctx* c, pw_future h) {
+  PW_API_LOCK(c);
   if (!c) return PW_ERR_INVALID;
   FutureRec* f = future_get(c, h);
   if (!f) return fail(c, PW_ERR_INVALID, "bad future handle");

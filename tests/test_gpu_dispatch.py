@@ -277,3 +277,92 @@ def test_pipeline_rejects_bad_programs_before_enqueuing_and_propagates_poison(pc
     with pytest.raises(pwb.PwError):
         c2.pipeline([a], [0], f)                                   # executors were never set up
     c2.close()
+
+
+# ---- several clients, one executor (Sections 4.4 and 5.2) ------------------------------------------------
+
+def test_scheduler_runs_programs_of_concurrent_clients_exactly(orc):
+    """Four client threads submit chains of different lengths at once; every program's result is exact, every
+    ticket can be waited for from its own thread, nothing stays allocated."""
+    import threading
+    ctx = pwb.Context(0)
+    sched = pwb.Scheduler(ctx, pwb.PW_SCHED_FIFO, max_in_flight=3)
+    add1 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    x = I.dispatch_input()
+    f_in = ctx.future_from_host(x)
+    live0, bytes0 = ctx.stats()
+    errors = []
+
+    def client(cid, length, reps):
+        try:
+            for r in range(reps):
+                t = sched.submit(cid, [add1] * length, f_in)
+                got = sched.wait(t, 128)
+                if not np.array_equal(got, orc.chain_add(x, length)):
+                    errors.append((cid, r))
+        except Exception as e:                                # noqa: BLE001 - reported below
+            errors.append((cid, repr(e)))
+
+    ids = [sched.add_client(1.0) for _ in range(4)]
+    threads = [threading.Thread(target=client, args=(ids[i], 3 + 5 * i, 25)) for i in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    sched.drain()
+    assert not errors, errors
+    for i, cid in enumerate(ids):
+        programs, comps, ms = sched.client_stats(cid)
+        assert programs == 25 and comps == 25 * (3 + 5 * i) and ms > 0
+    assert ctx.stats() == (live0, bytes0)
+    # a program that cannot be enqueued reports its error through its ticket; the scheduler keeps going
+    add_other = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 64, 1.0)
+    bad = sched.submit(ids[0], [add1, add_other], f_in)
+    good = sched.submit(ids[1], [add1], f_in)
+    with pytest.raises(pwb.PwError) as e:
+        sched.wait(bad)
+    assert e.value.status == pwb.PW_ERR_SHAPE
+    assert np.array_equal(sched.wait(good, 128), orc.chain_add(x, 1))
+    with pytest.raises(pwb.PwError):
+        sched.wait(good)                                       # a ticket can be waited for once
+    sched.close()
+    ctx.close()
+
+
+@pytest.mark.parametrize("weights", [(1, 1, 1, 1), (1, 2, 4, 8)])
+def test_proportional_share_of_device_time(weights):
+    """All clients keep work queued; device time (HIP events around every program) splits like the weights.
+    FIFO with the same submissions splits evenly whatever the weights."""
+    for policy in (pwb.PW_SCHED_PROPORTIONAL, pwb.PW_SCHED_FIFO):
+        ctx = pwb.Context(0)
+        sched = pwb.Scheduler(ctx, policy, max_in_flight=2)
+        busy = ctx.compile_scalar_fn(pwb.PW_FN_BUSY, 128, 1.0, busy_us=100.0)
+        f_in = ctx.future_from_host(np.zeros(128, np.float32))
+        ids = [sched.add_client(float(w)) for w in weights]
+        per_client = 120
+        # everything is queued up front, round-robin, so every client stays backlogged while the others are served
+        tickets = [sched.submit(ids[i % 4], [busy] * 4, f_in) for i in range(4 * per_client)]
+        # look at the schedule once the heaviest client has been served completely
+        sched.drain()
+        trace = sched.trace()
+        assert len(trace) == 4 * per_client
+        total = sum(weights)
+        if policy == pwb.PW_SCHED_PROPORTIONAL:
+            # while all four are backlogged (until the best-served one runs out) time splits like the weights
+            n_window = int(per_client * total / max(weights) * 0.9)
+            window = trace[:n_window]
+            share = [sum(e - s for c, _, s, e in window if c == ids[i]) for i in range(4)]
+            for i in range(4):
+                want = weights[i] / total
+                assert abs(share[i] / sum(share) - want) < 0.25 * want + 0.02, (weights, share)
+        else:
+            window = trace[:200]
+            count = [sum(1 for c, _, _, _ in window if c == ids[i]) for i in range(4)]
+            assert max(count) - min(count) <= 2, count                  # arrival order was round-robin
+        # slices do not overlap: one program at a time owns the device
+        for a, b in zip(trace, trace[1:]):
+            assert b[2] >= a[3] - 0.02
+        for t in tickets:
+            sched.wait(t)
+        sched.close()
+        ctx.close()
