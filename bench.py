@@ -122,6 +122,11 @@ def dispatch_bench_c_abi():
         if row["bench"] == "parallel_vs_sequential" and row["stages"] == 64:
             out[f"parallel_over_sequential_64_stages_comp{row['computation_us']:g}us_prep{row['host_prep_us']}us"] = \
                 row["parallel_over_sequential"]
+        if row["bench"] == "proportional_share":
+            out["device_time_share_weights_" + "_".join(f"{w:g}" for w in row["weights"])] = row["device_time_share"]
+        if row["bench"] == "multi_tenancy" and row["clients"] == 16 and row["computation_us"] > 0:
+            out[f"aggregate_over_single_client_16_clients_comp{row['computation_us']:g}us"] = \
+                round(row["aggregate_computations_per_s"] / row["one_client_without_scheduler"], 4)
     return out
 
 

@@ -9,6 +9,9 @@
 //    analogue of the "smallest computation that masks the single-controller overhead".
 //  * "parallel_vs_sequential": one trivial computation per pipeline stage, every stage on an executor of its own,
 //    handed out all at once or one after the other (the second micro-benchmark of the section).
+//  * "multi_tenancy": several client threads submit programs (chains of 16 computations) to the central scheduler
+//    (Section 5.2): aggregate throughput against the number of clients and the computation size, and the split
+//    of device time between four clients under proportional-share weights 1:1:1:1 and 1:2:4:8.
 //
 // Build: g++ -O2 -std=c++17 -I include dispatch_bench.cpp -L <dir of libpw.so> -lpw -Wl,-rpath,<dir> -o dispatch_bench
 #include <algorithm>
@@ -16,7 +19,9 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <atomic>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "pw.h"
@@ -186,6 +191,88 @@ int main(int argc, char** argv) {
     CHECK(pw_fn_release(ctx, one));
   }
   CHECK(pw_ctx_set_executor_prep_us(ctx, 0));
+  // ---- multi-tenancy ----------------------------------------------------------------------------------
+  {
+    constexpr int kProg = 16;   // computations per program
+    const double run_s = quick ? 0.1 : 0.3;
+    auto run_clients = [&](pw_sched* sched, const std::vector<int>& ids, pw_fn fn, int outstanding, std::vector<long>& done) {
+      std::vector<pw_fn> prog(kProg, fn);
+      std::atomic<bool> stop{false};
+      std::vector<std::thread> th;
+      done.assign(ids.size(), 0);
+      for (size_t k = 0; k < ids.size(); ++k)
+        th.emplace_back([&, k] {
+          std::vector<uint64_t> tickets;
+          while (!stop.load(std::memory_order_relaxed)) {
+            while ((int)tickets.size() < outstanding) {
+              uint64_t t;
+              if (pw_sched_submit(sched, ids[k], prog.data(), kProg, x, &t) != PW_OK) return;
+              tickets.push_back(t);
+            }
+            if (pw_sched_wait(sched, tickets.front(), nullptr, 0) != PW_OK) return;
+            tickets.erase(tickets.begin());
+            done[k] += kProg;
+          }
+          for (uint64_t t : tickets) (void)pw_sched_wait(sched, t, nullptr, 0);
+        });
+      std::this_thread::sleep_for(std::chrono::duration<double>(run_s));
+      stop.store(true);
+      for (auto& t : th) t.join();
+    };
+    for (float us : quick ? std::vector<float>{0.f, 330.f} : std::vector<float>{0.f, 10.f, 100.f, 330.f}) {
+      pw_fn fn = compile(PW_FN_BUSY, 1.f, us, 1);
+      // one client alone, straight on the context (no scheduler): the yardstick
+      std::vector<pw_fn> prog(kProg, fn);
+      const double alone = throughput(kProg, budget, [&] {
+        pw_future out;
+        CHECK(pw_chain(ctx, prog.data(), kProg, &x, 1, &out, 1, PW_STREAM));
+        CHECK(pw_await(ctx, out, nullptr, 0));
+        CHECK(pw_future_release(ctx, out));
+      });
+      for (int n_clients : {1, 2, 4, 8, 16}) {
+        pw_sched* sched;
+        CHECK(pw_sched_create(ctx, PW_SCHED_FIFO, 8, &sched));
+        std::vector<int> ids(n_clients);
+        for (int& id : ids) CHECK(pw_sched_add_client(sched, 1.0, &id));
+        std::vector<long> done;
+        const double t0 = now_s();
+        run_clients(sched, ids, fn, 1, done);
+        const double dt = now_s() - t0;
+        long total = 0;
+        for (long d : done) total += d;
+        CHECK(pw_sched_destroy(sched));
+        std::printf("{\"bench\": \"multi_tenancy\", \"computation_us\": %g, \"clients\": %d, \"programs_of\": %d, "
+                    "\"aggregate_computations_per_s\": %.0f, \"one_client_without_scheduler\": %.0f, \"device_limit\": %.0f}\n",
+                    us, n_clients, kProg, total / dt, alone, us > 0 ? 1e6 / us : 0.0);
+        std::fflush(stdout);
+      }
+      CHECK(pw_fn_release(ctx, fn));
+    }
+    pw_fn fn = compile(PW_FN_BUSY, 1.f, 330.f / kProg, 1);   // programs of 0.33 ms
+    for (int set = 0; set < 2; ++set) {
+      const double w[2][4] = {{1, 1, 1, 1}, {1, 2, 4, 8}};
+      pw_sched* sched;
+      CHECK(pw_sched_create(ctx, PW_SCHED_PROPORTIONAL, 2, &sched));
+      std::vector<int> ids(4);
+      for (int k = 0; k < 4; ++k) CHECK(pw_sched_add_client(sched, w[set][k], &ids[k]));
+      std::vector<long> done;
+      run_clients(sched, ids, fn, 4, done);
+      CHECK(pw_sched_drain(sched));
+      double ms[4], total = 0;
+      for (int k = 0; k < 4; ++k) {
+        int64_t p, c;
+        CHECK(pw_sched_client_stats(sched, ids[k], &p, &c, &ms[k]));
+        total += ms[k];
+      }
+      CHECK(pw_sched_destroy(sched));
+      std::printf("{\"bench\": \"proportional_share\", \"program_ms\": 0.33, \"weights\": [%g, %g, %g, %g], "
+                  "\"device_time_share\": [%.3f, %.3f, %.3f, %.3f], \"device_busy_fraction\": %.3f}\n",
+                  w[set][0], w[set][1], w[set][2], w[set][3], ms[0] / total, ms[1] / total, ms[2] / total, ms[3] / total,
+                  total / 1e3 / run_s);
+      std::fflush(stdout);
+    }
+    CHECK(pw_fn_release(ctx, fn));
+  }
   CHECK(pw_future_release(ctx, x));
   CHECK(pw_ctx_destroy(ctx));
   return 0;
