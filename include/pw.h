@@ -71,6 +71,7 @@ typedef enum {
   PW_FN_BUSY_CHAIN = 5,  /* params {c, microseconds, count}: PW_FN_BUSY applied count times in a row inside ONE
                             launch - a chain of computations fused into a single node (the "Fused" case of
                             Section 5.1); the result equals count separate PW_FN_BUSY functions bit for bit */
+  PW_FN_ADD2 = 6,        /* two inputs of one shape: y = a + b (no params): the fan-in node of dataflow programs */
   PW_FN_LM_TRAIN_STEP = 16, /* in: tokens i32 [B, T+1]; out: loss f32 [1].  params: pw_model*. */
   PW_FN_STAGE_FWD = 17,  /* in: X [N, d]; out: Y [N, d].  params: pw_stage_params */
   PW_FN_STAGE_BWD = 18   /* in: dY [N, d]; out: dX [N, d]; adds into the stage's weight gradients */
@@ -108,6 +109,15 @@ typedef enum {
   PW_SCHED_PROPORTIONAL = 1   /* among clients with work queued, the one with the least weighted device time goes
                                  next (the proportional-share multi-tenancy of Section 5.2) */
 } pw_sched_policy;
+
+/* A traced dataflow program (Section 3: the program tracer, Figure 2): a DAG of compiled functions.  Values are
+ * numbered: the program's inputs are values 0 .. n_inputs-1, then every node's outputs in node order. */
+typedef struct pw_program pw_program;   /* owned by its context; destroyed with it at the latest */
+typedef struct {
+  pw_fn fn;
+  int32_t n_in;      /* must equal the function's input count */
+  int32_t in[8];     /* value ids consumed; each must be defined before this node (nodes come in tracing order) */
+} pw_node;
 
 typedef struct pw_sched pw_sched;   /* owned by its context; destroyed with it at the latest */
 typedef struct {
@@ -175,6 +185,19 @@ pw_status pw_ctx_set_executor_prep_us(pw_ctx* ctx, int us);
  * (refcount 1).  dispatch: a pw_dispatch_mode.  Not thread-safe, like every call on a context. */
 pw_status pw_pipeline(pw_ctx* ctx, const pw_fn* fns, const int32_t* executor_of, int n_fns, pw_future in,
                       pw_future* out, int dispatch);
+
+/* ---- dataflow programs (Section 3, Figure 2; "a single message describing the entire subgraph", Section 4.5) */
+/* Trace -> program: checks every edge against the compiled signatures (PW_ERR_SHAPE / PW_ERR_DTYPE name the node in
+ * pw_last_error), computes each value's last use so that intermediates are recycled as soon as their last consumer
+ * has been enqueued, and snapshots the functions (they may be released afterwards).  outputs: value ids returned. */
+pw_status pw_program_create(pw_ctx* ctx, const pw_tensor_spec* input_specs, int n_inputs, const pw_node* nodes,
+                            int n_nodes, const int32_t* outputs, int n_outputs, pw_program** out);
+/* One client call runs the whole DAG: inputs are checked against the traced specs first (nothing is enqueued on a
+ * mismatch), then every node is enqueued in tracing order before any input needs to exist.  mode: PW_STREAM, or
+ * PW_GRAPH (captured once per buffer pattern, then replayed).  A value may feed any number of nodes (fan-out) and
+ * may be returned as well; outputs are fresh futures (refcount 1); a poisoned input poisons all outputs. */
+pw_status pw_program_run(pw_ctx* ctx, pw_program* program, const pw_future* in, int n_in, pw_future* out, int n_out, int mode);
+pw_status pw_program_destroy(pw_program* program);
 
 /* ---- several clients, one executor: the centralized scheduler (Section 4.4 "gang-scheduled dynamic dispatch",
  * measured in Section 5.2).  pw_sched_submit / _wait / _client_stats / _drain / _trace may be called from any

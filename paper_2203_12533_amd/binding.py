@@ -20,7 +20,7 @@ PW_OK, PW_ERR_INVALID, PW_ERR_SHAPE, PW_ERR_DTYPE, PW_ERR_OOM, PW_ERR_DEVICE, PW
 STATUS_NAMES = ["PW_OK", "PW_ERR_INVALID", "PW_ERR_SHAPE", "PW_ERR_DTYPE", "PW_ERR_OOM", "PW_ERR_DEVICE",
                 "PW_ERR_NOT_READY", "PW_ERR_POISONED", "PW_ERR_UNSUPPORTED"]
 PW_F32, PW_BF16, PW_I32 = 0, 1, 2
-PW_FN_ADD_CONST, PW_FN_MUL_CONST, PW_FN_DIV_CONST, PW_FN_BUSY, PW_FN_BUSY_CHAIN = 1, 2, 3, 4, 5
+PW_FN_ADD_CONST, PW_FN_MUL_CONST, PW_FN_DIV_CONST, PW_FN_BUSY, PW_FN_BUSY_CHAIN, PW_FN_ADD2 = 1, 2, 3, 4, 5, 6
 PW_DISPATCH_PARALLEL, PW_DISPATCH_SEQUENTIAL = 0, 1
 PW_SCHED_FIFO, PW_SCHED_PROPORTIONAL = 0, 1
 PW_FN_LM_TRAIN_STEP, PW_FN_STAGE_FWD, PW_FN_STAGE_BWD = 16, 17, 18
@@ -82,6 +82,10 @@ _SIGS = {
     "pw_chain": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64), C.c_int, C.POINTER(C.c_uint64), C.c_int,
                            C.POINTER(C.c_uint64), C.c_int, C.c_int]),
     "pw_train_step": (C.c_int, [C.c_void_p, C.c_uint64, C.c_uint64, C.POINTER(C.c_uint64)]),
+    "pw_program_create": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.POINTER(C.c_int32), C.c_int,
+                                    C.POINTER(C.c_void_p)]),
+    "pw_program_run": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64), C.c_int, C.POINTER(C.c_uint64), C.c_int, C.c_int]),
+    "pw_program_destroy": (C.c_int, [C.c_void_p]),
     "pw_sched_create": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_void_p)]),
     "pw_sched_destroy": (C.c_int, [C.c_void_p]),
     "pw_sched_add_client": (C.c_int, [C.c_void_p, C.c_double, C.POINTER(C.c_int)]),
@@ -348,6 +352,41 @@ class Context:
             for k, v in kw.items():
                 setattr(a, k, v)
         self._check(lib().pw_op_gemm_pair(self._h, C.byref(a0), C.byref(a1)))
+
+
+class Node(C.Structure):
+    _fields_ = [("fn", C.c_uint64), ("n_in", C.c_int32), ("inputs", C.c_int32 * 8)]
+
+
+class Program:
+    """pw_program: a traced DAG of compiled functions.  Values: inputs 0..n_inputs-1, then node outputs in order."""
+
+    def __init__(self, ctx: Context, input_specs, nodes, outputs):
+        """nodes: list of (fn handle, [value ids]); outputs: value ids."""
+        self._ctx = ctx
+        specs = (TensorSpec * max(1, len(input_specs)))(*input_specs)
+        arr = (Node * len(nodes))()
+        for k, (fn, ins) in enumerate(nodes):
+            arr[k].fn = fn
+            arr[k].n_in = len(ins)
+            for j, v in enumerate(ins):
+                arr[k].inputs[j] = v
+        outs = (C.c_int32 * len(outputs))(*outputs)
+        self._n_out = len(outputs)
+        self._h = C.c_void_p()
+        ctx._check(lib().pw_program_create(ctx.handle, specs, len(input_specs), arr, len(nodes), outs, len(outputs),
+                                           C.byref(self._h)))
+
+    def run(self, inputs, mode: int = PW_STREAM):
+        a_in = (C.c_uint64 * max(1, len(inputs)))(*inputs)
+        a_out = (C.c_uint64 * self._n_out)()
+        self._ctx._check(lib().pw_program_run(self._ctx.handle, self._h, a_in, len(inputs), a_out, self._n_out, mode))
+        return list(a_out)
+
+    def close(self):
+        if self._h:
+            lib().pw_program_destroy(self._h)
+            self._h = None
 
 
 class SchedSlice(C.Structure):

@@ -51,6 +51,19 @@ hipError_t launch_scalar_fn(hipStream_t s, int kind, const float* x, float* y, i
   return hipGetLastError();
 }
 
+// y = a + b, the two-input node of dataflow programs with fan-in.
+__global__ void add2_kernel(const float* __restrict__ a, const float* __restrict__ b, float* __restrict__ y, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+    y[i] = __fadd_rn(a[i], b[i]);
+}
+hipError_t launch_add2(hipStream_t s, const float* a, const float* b, float* y, int64_t n) {
+  if (!a || !b || !y || n < 0) return hipErrorInvalidValue;
+  if (n == 0) return hipSuccess;
+  const int block = n <= 128 ? 128 : 256;
+  add2_kernel<<<grid_for(n, block), block, 0, s>>>(a, b, y, n);
+  return hipGetLastError();
+}
+
 // ---- fills, conversions, copies -----------------------------------------------------------------------
 __global__ void fill_f32_kernel(float* __restrict__ p, int64_t n, float v) {
   const int64_t n4 = n >> 2;

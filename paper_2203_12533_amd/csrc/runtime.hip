@@ -168,6 +168,7 @@ struct pw_ctx {
   // scheduler thread of pw_sched may share a context.  Recursive: some calls are built from others.
   std::recursive_mutex api_mu;
   std::vector<pw_sched*> scheds;
+  std::vector<pw_program*> programs;
 };
 
 #define PW_API_LOCK(c)                                  \
@@ -177,6 +178,25 @@ struct pw_ctx {
 struct pw_model {
   pw_ctx* ctx;
   Model* impl;
+};
+
+// ---- traced dataflow programs (Section 3) ---------------------------------------------------------------
+namespace {
+struct ProgNode {
+  FnRec fn;            // snapshot: the handle may be released after tracing
+  pw_fn handle = 0;    // only part of the graph-cache key
+  int n_in = 0, in[8] = {0};
+  int first_out = 0;
+};
+}  // namespace
+struct pw_program {
+  pw_ctx* ctx = nullptr;
+  int n_inputs = 0;
+  std::vector<pw_tensor_spec> specs;   // per value
+  std::vector<ProgNode> nodes;
+  std::vector<int> outputs;
+  std::vector<int> last_use;           // per value: last node that reads it; n_nodes if it is a program output; -1 if unused
+  std::unordered_map<std::string, GraphEntry> graphs;
 };
 
 // ---- multi-tenant scheduler (Section 4.4 "centralized scheduler", Section 5.2) -----------------------------
@@ -358,7 +378,7 @@ FnRec* fn_get(pw_ctx* c, pw_fn h) {
   return (f.live && f.gen == gen) ? &f : nullptr;
 }
 
-bool is_scalar_kind(int k) { return k >= PW_FN_ADD_CONST && k <= PW_FN_BUSY_CHAIN; }
+bool is_scalar_kind(int k) { return k >= PW_FN_ADD_CONST && k <= PW_FN_BUSY_CHAIN; }   // one fp32 input, one output
 
 // Launch the body of one function on the executor stream.  in/out are device pointers.
 pw_status fn_launch(pw_ctx* c, FnRec* fn, void* const* in, void* const* out) {
@@ -366,6 +386,11 @@ pw_status fn_launch(pw_ctx* c, FnRec* fn, void* const* in, void* const* out) {
   if (is_scalar_kind(k)) {
     hipError_t e = launch_scalar_fn(c->exec, k, (const float*)in[0], (float*)out[0], spec_numel(fn->desc.in[0]), fn->cst, fn->busy_us, fn->reps);
     if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "scalar fn launch: %s", hipGetErrorString(e));
+    return PW_OK;
+  }
+  if (k == PW_FN_ADD2) {
+    hipError_t e = launch_add2(c->exec, (const float*)in[0], (const float*)in[1], (float*)out[0], spec_numel(fn->desc.in[0]));
+    if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "add2 launch: %s", hipGetErrorString(e));
     return PW_OK;
   }
   hipError_t e = hipErrorInvalidValue;
@@ -505,6 +530,7 @@ pw_status pw_ctx_destroy(pw_ctx* c) {
   if (!c) return PW_ERR_INVALID;
   (void)hipSetDevice(c->device);
   while (!c->scheds.empty()) (void)pw_sched_destroy(c->scheds.back());
+  while (!c->programs.empty()) (void)pw_program_destroy(c->programs.back());
   stop_executors(c);
   // release every gate that is still waiting so that the streams can drain
   for (auto& f : c->futures)
@@ -596,6 +622,13 @@ pw_status pw_compile_fn(pw_ctx* c, const pw_fn_desc* d, pw_fn* out) {
       fn.reps = (int)r;
       if ((double)fn.busy_us * fn.reps > 1e7) return fail(c, PW_ERR_INVALID, "busy time times repetitions must stay within 1e7 microseconds");
     }
+  } else if (k == PW_FN_ADD2) {
+    if (d->n_in != 2 || d->n_out != 1) return fail(c, PW_ERR_SHAPE, "add2 takes two inputs and gives one output");
+    if (d->in[0].dtype != PW_F32 || d->in[1].dtype != PW_F32 || d->out[0].dtype != PW_F32) return fail(c, PW_ERR_DTYPE, "add2 is fp32");
+    pw_status st = spec_match(d->in[0], d->in[1]);
+    if (st == PW_OK) st = spec_match(d->in[0], d->out[0]);
+    if (st != PW_OK) return fail(c, st, "add2: inputs and output must have one shape");
+    if (d->params_bytes != 0) return fail(c, PW_ERR_INVALID, "add2 takes no params");
   } else if (k == PW_FN_LM_TRAIN_STEP || k == PW_FN_STAGE_FWD || k == PW_FN_STAGE_BWD) {
     pw_model* pm = nullptr;
     if (k == PW_FN_LM_TRAIN_STEP) {
@@ -991,6 +1024,182 @@ pw_status pw_pipeline(pw_ctx* c, const pw_fn* fns, const int32_t* executor_of, i
   }
   release_plan(true);
   if (!all_ok) return fail(c, PW_ERR_DEVICE, "a pipeline node could not be enqueued; the output future is poisoned");
+  return PW_OK;
+}
+
+// ---- dataflow programs ---------------------------------------------------------------------------------------
+pw_status pw_program_create(pw_ctx* c, const pw_tensor_spec* input_specs, int n_inputs, const pw_node* nodes, int n_nodes,
+                            const int32_t* outputs, int n_outputs, pw_program** out) {
+  if (!c || !out || !nodes || !outputs || (n_inputs > 0 && !input_specs)) return PW_ERR_INVALID;
+  PW_API_LOCK(c);
+  if (n_inputs < 0 || n_inputs > 8 || n_nodes < 1 || n_nodes > 4096 || n_outputs < 1 || n_outputs > 8)
+    return fail(c, PW_ERR_INVALID, "a program has 0..8 inputs, 1..4096 nodes and 1..8 outputs");
+  std::unique_ptr<pw_program> p(new pw_program());
+  p->ctx = c;
+  p->n_inputs = n_inputs;
+  for (int i = 0; i < n_inputs; ++i) {
+    if (!spec_ok(input_specs[i])) return fail(c, PW_ERR_INVALID, "input spec %d is malformed", i);
+    p->specs.push_back(input_specs[i]);
+  }
+  for (int i = 0; i < n_nodes; ++i) {
+    FnRec* fn = fn_get(c, nodes[i].fn);
+    if (!fn) return fail(c, PW_ERR_INVALID, "node %d: not a live function handle", i);
+    if (nodes[i].n_in != fn->desc.n_in) return fail(c, PW_ERR_SHAPE, "node %d: function takes %d inputs, the trace gives %d", i, fn->desc.n_in, nodes[i].n_in);
+    ProgNode n;
+    n.fn = *fn;
+    n.handle = nodes[i].fn;
+    n.n_in = nodes[i].n_in;
+    for (int j = 0; j < n.n_in; ++j) {
+      const int v = nodes[i].in[j];
+      if (v < 0 || v >= (int)p->specs.size()) return fail(c, PW_ERR_INVALID, "node %d: input %d names value %d, which is not defined before it", i, j, v);
+      pw_status st = spec_match(p->specs[v], fn->desc.in[j]);
+      if (st != PW_OK) return fail(c, st, "node %d: value %d does not match input %d of the compiled signature", i, v, j);
+      n.in[j] = v;
+    }
+    n.first_out = (int)p->specs.size();
+    for (int j = 0; j < fn->desc.n_out; ++j) p->specs.push_back(fn->desc.out[j]);
+    p->nodes.push_back(n);
+  }
+  p->last_use.assign(p->specs.size(), -1);
+  for (int i = 0; i < n_nodes; ++i)
+    for (int j = 0; j < p->nodes[i].n_in; ++j) p->last_use[p->nodes[i].in[j]] = i;
+  for (int i = 0; i < n_outputs; ++i) {
+    const int v = outputs[i];
+    if (v < 0 || v >= (int)p->specs.size()) return fail(c, PW_ERR_INVALID, "output %d names value %d, which does not exist", i, v);
+    if (v < n_inputs) return fail(c, PW_ERR_UNSUPPORTED, "output %d is a program input; return it from the caller instead", i);
+    for (int k = 0; k < i; ++k)
+      if (outputs[k] == v) return fail(c, PW_ERR_UNSUPPORTED, "value %d is returned twice", v);
+    p->last_use[v] = n_nodes;
+    p->outputs.push_back(v);
+  }
+  c->programs.push_back(p.get());
+  *out = p.release();
+  return PW_OK;
+}
+
+pw_status pw_program_destroy(pw_program* p) {
+  if (!p) return PW_ERR_INVALID;
+  pw_ctx* c = p->ctx;
+  PW_API_LOCK(c);
+  (void)hipStreamSynchronize(c->exec);   // a replay may still be running
+  for (auto& kv : p->graphs) {
+    if (kv.second.exec) (void)hipGraphExecDestroy(kv.second.exec);
+    if (kv.second.graph) (void)hipGraphDestroy(kv.second.graph);
+  }
+  for (size_t i = 0; i < c->programs.size(); ++i)
+    if (c->programs[i] == p) { c->programs.erase(c->programs.begin() + i); break; }
+  delete p;
+  return PW_OK;
+}
+
+pw_status pw_program_run(pw_ctx* c, pw_program* p, const pw_future* in, int n_in, pw_future* out, int n_out, int mode) {
+  if (!c || !p || p->ctx != c || (n_in > 0 && !in) || !out) return PW_ERR_INVALID;
+  PW_API_LOCK(c);
+  if (mode != PW_STREAM && mode != PW_GRAPH) return fail(c, PW_ERR_INVALID, "programs run in PW_STREAM or PW_GRAPH mode");
+  if (n_in != p->n_inputs || n_out != (int)p->outputs.size())
+    return fail(c, PW_ERR_SHAPE, "program takes %d inputs / gives %zu outputs, got %d / %d", p->n_inputs, p->outputs.size(), n_in, n_out);
+  FutureRec* fin[8];
+  for (int i = 0; i < n_in; ++i) {
+    fin[i] = future_get(c, in[i]);
+    if (!fin[i]) return fail(c, PW_ERR_INVALID, "input %d is not a live future", i);
+    pw_status st = spec_match(fin[i]->spec, p->specs[i]);
+    if (st != PW_OK) return fail(c, st, "input %d does not match the traced signature", i);
+  }
+  // ---- buffer plan: allocate each value when its producer is reached, give it back when its last consumer has
+  // been passed (stream order keeps the reuse safe; the pool then repeats the same addresses call after call)
+  const int n_nodes = (int)p->nodes.size();
+  struct Buf { void* p = nullptr; size_t cls = 0; };
+  std::vector<Buf> val(p->specs.size());
+  for (int i = 0; i < n_in; ++i) val[i].p = fin[i]->buf;
+  std::vector<char> held(p->specs.size(), 0);
+  for (int i = 0; i < n_nodes; ++i) {
+    const ProgNode& n = p->nodes[i];
+    for (int j = 0; j < n.fn.desc.n_out; ++j) {
+      const int v = n.first_out + j;
+      pw_status st = pool_alloc(c, spec_bytes(p->specs[v]), &val[v].p, &val[v].cls);
+      if (st != PW_OK) {
+        for (size_t w = p->n_inputs; w < val.size(); ++w)
+          if (held[w]) pool_free(c, val[w].p, val[w].cls);
+        return st;
+      }
+      held[v] = 1;
+    }
+    for (int j = 0; j < n.n_in; ++j) {
+      const int v = n.in[j];
+      if (v >= p->n_inputs && held[v] && p->last_use[v] == i) { pool_free(c, val[v].p, val[v].cls); held[v] = 0; }
+    }
+    for (int j = 0; j < n.fn.desc.n_out; ++j) {   // produced but never read nor returned
+      const int v = n.first_out + j;
+      if (p->last_use[v] < 0) { pool_free(c, val[v].p, val[v].cls); held[v] = 0; }
+    }
+  }
+  auto release_outputs = [&]() {
+    for (int v : p->outputs)
+      if (held[v]) { pool_free(c, val[v].p, val[v].cls); held[v] = 0; }
+  };
+  std::vector<std::shared_ptr<GateWords>> poison;
+  bool host_poison = false;
+  pw_status st = wait_inputs(c, fin, n_in, poison, host_poison);
+  if (st != PW_OK) { release_outputs(); return st; }
+
+  auto enqueue_all = [&]() -> pw_status {
+    for (int i = 0; i < n_nodes; ++i) {
+      ProgNode& n = p->nodes[i];
+      void* ibuf[8];
+      void* obuf[8];
+      for (int j = 0; j < n.n_in; ++j) ibuf[j] = val[n.in[j]].p;
+      for (int j = 0; j < n.fn.desc.n_out; ++j) obuf[j] = val[n.first_out + j].p;
+      pw_status s2 = fn_launch(c, &n.fn, ibuf, obuf);
+      if (s2 != PW_OK) return s2;
+    }
+    return PW_OK;
+  };
+  if (mode == PW_GRAPH) {
+    std::string key;
+    for (auto& b : val) key.append((const char*)&b.p, sizeof(void*));
+    auto it = p->graphs.find(key);
+    if (it == p->graphs.end()) {
+      if (p->graphs.size() >= 64) {
+        (void)hipStreamSynchronize(c->exec);
+        for (auto& kv : p->graphs) {
+          (void)hipGraphExecDestroy(kv.second.exec);
+          (void)hipGraphDestroy(kv.second.graph);
+        }
+        p->graphs.clear();
+      }
+      GraphEntry ge;
+      hipError_t e = hipStreamBeginCapture(c->exec, hipStreamCaptureModeThreadLocal);
+      if (e != hipSuccess) { release_outputs(); return fail(c, PW_ERR_DEVICE, "begin capture: %s", hipGetErrorString(e)); }
+      st = enqueue_all();
+      e = hipStreamEndCapture(c->exec, &ge.graph);
+      if (st != PW_OK || e != hipSuccess || !ge.graph) {
+        if (ge.graph) (void)hipGraphDestroy(ge.graph);
+        release_outputs();
+        return st != PW_OK ? st : fail(c, PW_ERR_DEVICE, "end capture: %s", hipGetErrorString(e));
+      }
+      e = hipGraphInstantiate(&ge.exec, ge.graph, nullptr, nullptr, 0);
+      if (e != hipSuccess) {
+        (void)hipGraphDestroy(ge.graph);
+        release_outputs();
+        return fail(c, PW_ERR_DEVICE, "graph instantiate: %s", hipGetErrorString(e));
+      }
+      it = p->graphs.emplace(key, ge).first;
+    }
+    hipError_t e = hipGraphLaunch(it->second.exec, c->exec);
+    if (e != hipSuccess) { release_outputs(); return fail(c, PW_ERR_DEVICE, "graph launch: %s", hipGetErrorString(e)); }
+  } else {
+    st = enqueue_all();
+    if (st != PW_OK) { release_outputs(); return st; }
+  }
+  for (int i = 0; i < n_out; ++i) {
+    const int v = p->outputs[i];
+    hipEvent_t ev = nullptr;
+    if (event_get(c, &ev) == PW_OK && hipEventRecord(ev, c->exec) != hipSuccess) { c->event_pool.push_back(ev); ev = nullptr; }
+    FutureRec* f;
+    future_new(c, &f, &out[i]);
+    f->buf = val[v].p; f->pool_bytes = val[v].cls; f->spec = p->specs[v]; f->bytes = spec_bytes(f->spec); f->owns = true;
+    f->poison = poison; f->host_poison = host_poison; f->event = ev;
+  }
   return PW_OK;
 }
 

@@ -366,3 +366,115 @@ def test_proportional_share_of_device_time(weights):
             sched.wait(t)
         sched.close()
         ctx.close()
+
+
+# ---- traced dataflow programs (Section 3, Figure 2) -----------------------------------------------------
+
+def _golden_fig2():
+    rows = {}
+    for line in open(os.path.join(GOLD, "fig2_example.txt")):
+        if line.strip() and not line.startswith("#"):
+            k, *v = line.split()
+            rows[k] = np.array(v, dtype=np.float32)
+    return rows
+
+
+@pytest.mark.parametrize("mode", [pwb.PW_STREAM, pwb.PW_GRAPH])
+def test_traced_figure2_program_runs_from_one_call(ctx, mode):
+    """f(v): x = a(v); y = b(x); z = a(c(x)); return (y, z) with a = *2, b = +1, c = /2 - traced once, then each
+    run is one client call; the values the paper prints for v = [1, 2] come back, also on graph replays."""
+    rows = _golden_fig2()
+    n = rows["input"].size
+    a = ctx.compile_scalar_fn(pwb.PW_FN_MUL_CONST, n, 2.0)
+    b = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, n, 1.0)
+    c = ctx.compile_scalar_fn(pwb.PW_FN_DIV_CONST, n, 2.0)
+    spec = pwb.make_spec(pwb.PW_F32, (n,))
+    # values: 0 = v, 1 = x, 2 = y, 3 = c(x), 4 = z
+    prog = pwb.Program(ctx, [spec], [(a, [0]), (b, [1]), (c, [1]), (a, [3])], [2, 4])
+    for fn in (a, b, c):
+        ctx.fn_release(fn)                      # the trace keeps what it needs
+    live0, bytes0 = ctx.stats()
+    for rep in range(4):
+        scale = np.float32(1 + rep)
+        v = ctx.future_pending(pwb.PW_F32, (n,))
+        y, z = prog.run([v], mode)
+        assert ctx.future_query(y) == pwb.PW_ERR_NOT_READY and ctx.future_query(z) == pwb.PW_ERR_NOT_READY
+        ctx.future_resolve(v, rows["input"] * scale)
+        assert np.array_equal(ctx.await_(y), rows["input"] * scale * 2 + 1)
+        assert np.array_equal(ctx.await_(z), rows["input"] * scale * 2 / 2 * 2)
+        if rep == 0:
+            assert np.array_equal(ctx.await_(y), rows["y"]) and np.array_equal(ctx.await_(z), rows["z"])
+        for f in (v, y, z):
+            ctx.future_release(f)
+    assert ctx.stats() == (live0, bytes0)
+    prog.close()
+
+
+@pytest.mark.parametrize("mode", [pwb.PW_STREAM, pwb.PW_GRAPH])
+def test_program_with_fan_in_and_two_inputs(ctx, orc, mode):
+    """A diamond and a second input: s = (u + 1) + (u * 3); t = s + w; r = t / 2; returns (s, r).  s is both returned
+    and consumed; intermediates are recycled inside the run."""
+    n = 1000
+    add1 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, n, 1.0)
+    mul3 = ctx.compile_scalar_fn(pwb.PW_FN_MUL_CONST, n, 3.0)
+    half = ctx.compile_scalar_fn(pwb.PW_FN_DIV_CONST, n, 2.0)
+    spec = pwb.make_spec(pwb.PW_F32, (n,))
+    add2 = ctx.compile_fn(pwb.PW_FN_ADD2, [spec, spec], [spec])
+    # values: 0 = u, 1 = w, 2 = u+1, 3 = u*3, 4 = s, 5 = t, 6 = r
+    prog = pwb.Program(ctx, [spec, spec], [(add1, [0]), (mul3, [0]), (add2, [2, 3]), (add2, [4, 1]), (half, [5])], [4, 6])
+    live0, bytes0 = ctx.stats()
+    for rep in range(3):
+        u = I.normal(5 + rep, 1, n, 1.0).astype(np.float32)
+        w = I.normal(5 + rep, 2, n, 1.0).astype(np.float32)
+        fu, fw = ctx.future_from_host(u), ctx.future_pending(pwb.PW_F32, (n,))
+        s, r = prog.run([fu, fw], mode)
+        ctx.future_resolve(fw, w)
+        want_s = orc.scalar_fn("add", u, 1.0) + orc.scalar_fn("mul", u, 3.0)          # fp32 adds, rounded once each
+        want_r = orc.scalar_fn("div", want_s + w, 2.0)
+        assert np.array_equal(ctx.await_(s), want_s) and np.array_equal(ctx.await_(r), want_r)
+        for f in (fu, fw, s, r):
+            ctx.future_release(f)
+    assert ctx.stats() == (live0, bytes0)
+    prog.close()
+    # a poisoned input poisons every output
+    prog = pwb.Program(ctx, [spec, spec], [(add2, [0, 1]), (half, [2])], [3])
+    fu, fw = ctx.future_from_host(np.zeros(n, np.float32)), ctx.future_pending(pwb.PW_F32, (n,))
+    (r,) = prog.run([fu, fw], mode)
+    ctx.future_resolve(fw, None)
+    with pytest.raises(pwb.PwError) as e:
+        ctx.await_(r)
+    assert e.value.status == pwb.PW_ERR_POISONED
+    for f in (fu, fw, r):
+        ctx.future_release(f)
+    prog.close()
+
+
+def test_program_tracing_rejects_what_cannot_run(ctx):
+    spec128, spec64 = pwb.make_spec(pwb.PW_F32, (128,)), pwb.make_spec(pwb.PW_F32, (64,))
+    add128 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    add64 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 64, 1.0)
+    add2 = ctx.compile_fn(pwb.PW_FN_ADD2, [spec128, spec128], [spec128])
+    with pytest.raises(pwb.PwError) as e:
+        ctx.compile_fn(pwb.PW_FN_ADD2, [spec128, spec64], [spec128])
+    assert e.value.status == pwb.PW_ERR_SHAPE
+    for nodes, outs, status in [
+        ([(add128, [0]), (add64, [1])], [2], pwb.PW_ERR_SHAPE),          # edge with the wrong shape
+        ([(add128, [1])], [1], pwb.PW_ERR_INVALID),                      # reads a value defined later (itself)
+        ([(add2, [0])], [1], pwb.PW_ERR_SHAPE),                          # wrong number of inputs
+        ([(add128, [0])], [5], pwb.PW_ERR_INVALID),                      # returns a value that does not exist
+        ([(add128, [0])], [0], pwb.PW_ERR_UNSUPPORTED),                  # returns its own input
+    ]:
+        with pytest.raises(pwb.PwError) as e:
+            pwb.Program(ctx, [spec128], nodes, outs)
+        assert e.value.status == status, (nodes, outs)
+    prog = pwb.Program(ctx, [spec128], [(add128, [0])], [1])
+    live0, bytes0 = ctx.stats()
+    f64 = ctx.future_from_host(np.zeros(64, np.float32))
+    with pytest.raises(pwb.PwError) as e:
+        prog.run([f64])
+    assert e.value.status == pwb.PW_ERR_SHAPE
+    with pytest.raises(pwb.PwError):
+        prog.run([f64, f64])
+    ctx.future_release(f64)
+    assert ctx.stats() == (live0, bytes0)
+    prog.close()
