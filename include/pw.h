@@ -211,6 +211,11 @@ pw_status pw_sched_create(pw_ctx* ctx, int policy, int max_in_flight, pw_sched**
 pw_status pw_sched_destroy(pw_sched* sched);
 /* weight > 0: share of device time under PW_SCHED_PROPORTIONAL (ignored by FIFO).  *client: id for the calls below. */
 pw_status pw_sched_add_client(pw_sched* sched, double weight, int* client);
+/* The client has failed: its queued programs are dropped (their tickets report PW_ERR_POISONED), every object it
+ * owns - results it has not collected included - is garbage-collected, further submissions are refused. */
+pw_status pw_sched_client_fail(pw_sched* sched, int client, int64_t* objects_released);
+/* How many programs had to wait for memory (see pw_ctx_set_memory_limit) and for how long altogether. */
+pw_status pw_sched_stalls(pw_sched* sched, int64_t* programs_stalled, double* stalled_ms);
 /* Queue a program: the chain fns[0..n_fns) applied to `in` (one input, one output; validated when it is enqueued).
  * Returns at once with a ticket.  `in` must stay alive until the ticket has been waited for. */
 pw_status pw_sched_submit(pw_sched* sched, int client, const pw_fn* fns, int n_fns, pw_future in, uint64_t* ticket);
@@ -256,6 +261,17 @@ pw_status pw_future_retain(pw_ctx* ctx, pw_future f);
 /* Drops one reference; at zero the buffer returns to the pool (stream-ordered, so work already
  * enqueued on it stays correct). */
 pw_status pw_future_release(pw_ctx* ctx, pw_future f);
+/* ---- object store: ownership labels and back-pressure (Section 4.6) ----
+ * Every future carries the label that was current when it was created (0 until set).  pw_owner_collect drops
+ * every live future with that label whatever its reference count - the garbage collection after a client or a
+ * program has failed; their buffers return to the pool, unresolved pending futures are cancelled, the handles
+ * become invalid.  *released: how many there were (may be null). */
+pw_status pw_ctx_set_owner(pw_ctx* ctx, uint64_t owner);
+pw_status pw_owner_collect(pw_ctx* ctx, uint64_t owner, int64_t* released);
+/* Budget, in bytes, for what the buffer pool may have handed out at one time (0: none).  A call that would exceed
+ * it enqueues nothing and returns PW_ERR_OOM; the scheduler (pw_sched) stalls such a program instead until
+ * memory has come back. */
+pw_status pw_ctx_set_memory_limit(pw_ctx* ctx, int64_t bytes);
 /* Number of live futures / bytes currently handed out by the buffer pool (for leak tests). */
 pw_status pw_ctx_stats(pw_ctx* ctx, int64_t* live_futures, int64_t* pool_bytes_in_use);
 

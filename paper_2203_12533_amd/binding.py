@@ -82,6 +82,11 @@ _SIGS = {
     "pw_chain": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64), C.c_int, C.POINTER(C.c_uint64), C.c_int,
                            C.POINTER(C.c_uint64), C.c_int, C.c_int]),
     "pw_train_step": (C.c_int, [C.c_void_p, C.c_uint64, C.c_uint64, C.POINTER(C.c_uint64)]),
+    "pw_ctx_set_owner": (C.c_int, [C.c_void_p, C.c_uint64]),
+    "pw_owner_collect": (C.c_int, [C.c_void_p, C.c_uint64, C.POINTER(C.c_int64)]),
+    "pw_ctx_set_memory_limit": (C.c_int, [C.c_void_p, C.c_int64]),
+    "pw_sched_client_fail": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_int64)]),
+    "pw_sched_stalls": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
     "pw_program_create": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.POINTER(C.c_int32), C.c_int,
                                     C.POINTER(C.c_void_p)]),
     "pw_program_run": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64), C.c_int, C.POINTER(C.c_uint64), C.c_int, C.c_int]),
@@ -246,6 +251,17 @@ class Context:
         a_out = (C.c_uint64 * max(1, n_out))()
         self._check(lib().pw_chain(self._h, a_f, len(fns), a_in, len(inputs), a_out, n_out, mode))
         return list(a_out[:n_out])
+
+    def set_owner(self, owner: int):
+        self._check(lib().pw_ctx_set_owner(self._h, owner))
+
+    def owner_collect(self, owner: int) -> int:
+        n = C.c_int64()
+        self._check(lib().pw_owner_collect(self._h, owner, C.byref(n)))
+        return n.value
+
+    def set_memory_limit(self, nbytes: int):
+        self._check(lib().pw_ctx_set_memory_limit(self._h, nbytes))
 
     def set_executors(self, n: int):
         self._check(lib().pw_ctx_set_executors(self._h, n))
@@ -420,6 +436,16 @@ class Scheduler:
         out = np.empty(n_floats, np.float32)
         self._check(lib().pw_sched_wait(self._h, ticket, out.ctypes.data_as(C.c_void_p) if n_floats else None, n_floats * 4))
         return out
+
+    def client_fail(self, client: int) -> int:
+        n = C.c_int64()
+        self._check(lib().pw_sched_client_fail(self._h, client, C.byref(n)))
+        return n.value
+
+    def stalls(self):
+        n, ms = C.c_int64(), C.c_double()
+        self._check(lib().pw_sched_stalls(self._h, C.byref(n), C.byref(ms)))
+        return n.value, ms.value
 
     def drain(self):
         self._check(lib().pw_sched_drain(self._h))

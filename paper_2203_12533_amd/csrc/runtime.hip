@@ -80,6 +80,7 @@ struct FutureRec {
   bool pending = false;          // created by pw_future_pending and not resolved yet
   hipEvent_t event = nullptr;    // null: ready w.r.t. the executor stream's order
   int refcount = 0;
+  uint64_t owner = 0;            // ownership label (Section 4.6): who this object dies with
   bool host_poison = false;
   std::vector<std::shared_ptr<GateWords>> poison;   // gates this future depends on
   std::shared_ptr<GateWords> gate;                  // own gate (pending futures)
@@ -148,6 +149,8 @@ struct pw_ctx {
   std::vector<FnRec> fns;
   std::vector<Model*> models;
   int64_t live_futures = 0;
+  uint64_t current_owner = 0;    // label given to futures created from now on
+  int64_t memory_limit = 0;      // bytes the pool may have handed out at once; 0: no limit
 
   // buffer pool: power-of-two size classes
   std::map<size_t, std::vector<void*>> pool;
@@ -216,6 +219,8 @@ struct SchedProgram {
 };
 struct SchedClient {
   double weight = 1, vtime = 0;
+  uint64_t owner = 0;
+  bool failed = false;
   std::deque<SchedProgram> queue;
   int64_t programs = 0, computations = 0;
   double device_ms = 0;
@@ -246,6 +251,10 @@ struct pw_sched {
   std::vector<hipEvent_t> timing_events;
   hipEvent_t epoch = nullptr;           // recorded at creation: slices are reported relative to it
   std::vector<pw_sched_slice> trace;
+  int collecting = 0;                   // results taken by pw_sched_wait whose futures are not released yet
+  int64_t stalls = 0;                   // programs that had to wait for memory
+  double stalled_ms = 0;
+  uint64_t id = 0;
   bool stop = false, idle = true;
   std::thread thread;
 };
@@ -278,6 +287,9 @@ size_t size_class(size_t bytes) {
 
 pw_status pool_alloc(pw_ctx* c, size_t bytes, void** out, size_t* cls_out) {
   const size_t cls = size_class(bytes ? bytes : 1);
+  if (c->memory_limit > 0 && c->pool_in_use + (int64_t)cls > c->memory_limit)
+    return fail(c, PW_ERR_OOM, "memory budget: %lld bytes in use, %zu more asked for, limit %lld", (long long)c->pool_in_use, cls,
+                (long long)c->memory_limit);
   auto& fl = c->pool[cls];
   if (!fl.empty()) {
     *out = fl.back();
@@ -338,6 +350,7 @@ pw_status future_new(pw_ctx* c, FutureRec** out, pw_future* handle) {
   f.gen = gen;
   f.live = true;
   f.refcount = 1;
+  f.owner = c->current_owner;
   c->live_futures++;
   *out = &f;
   *handle = ((uint64_t)gen << 32) | (uint64_t)(idx + 1);
@@ -579,6 +592,40 @@ pw_status pw_ctx_set_gate_timeout_ms(pw_ctx* c, int ms) {
   PW_API_LOCK(c);
   if (!c || ms < 1 || ms > 600000) return PW_ERR_INVALID;
   c->gate_timeout_ms = ms;
+  return PW_OK;
+}
+
+pw_status pw_ctx_set_owner(pw_ctx* c, uint64_t owner) {
+  PW_API_LOCK(c);
+  if (!c) return PW_ERR_INVALID;
+  c->current_owner = owner;
+  return PW_OK;
+}
+
+pw_status pw_owner_collect(pw_ctx* c, uint64_t owner, int64_t* released) {
+  PW_API_LOCK(c);
+  if (!c) return PW_ERR_INVALID;
+  int64_t n = 0;
+  for (size_t i = 0; i < c->futures.size(); ++i) {
+    FutureRec& f = c->futures[i];
+    if (!f.live || f.owner != owner) continue;
+    const pw_future h = ((uint64_t)f.gen << 32) | (uint64_t)(i + 1);
+    if (f.on_gate_stream && f.event) {   // as in pw_future_release: the gate stream may still write the buffer
+      if (f.pending) __atomic_store_n(&f.gate->words[0], 2u, __ATOMIC_RELEASE);
+      (void)hipStreamWaitEvent(c->exec, f.event, 0);
+    }
+    f.refcount = 1;                      // every reference dies with the owner
+    future_drop(c, h);
+    ++n;
+  }
+  if (released) *released = n;
+  return PW_OK;
+}
+
+pw_status pw_ctx_set_memory_limit(pw_ctx* c, int64_t bytes) {
+  PW_API_LOCK(c);
+  if (!c || bytes < 0) return PW_ERR_INVALID;
+  c->memory_limit = bytes;
   return PW_OK;
 }
 
@@ -1275,13 +1322,37 @@ void sched_loop(pw_sched* s) {
     fl.client = client;
     fl.n_computations = prog.n_computations;
     SchedResult res;
-    {
-      std::unique_lock<std::recursive_mutex> api(s->ctx->api_mu);
-      fl.start = sched_event(s);
-      fl.stop = sched_event(s);
-      if (fl.start) (void)hipEventRecord(fl.start, s->ctx->exec);
-      res.status = pw_chain(s->ctx, prog.fns.data(), (int)prog.fns.size(), &prog.in, 1, &res.out, 1, PW_STREAM);
-      if (fl.stop) (void)hipEventRecord(fl.stop, s->ctx->exec);
+    const auto t_stall = std::chrono::steady_clock::now();
+    bool stalled = false;
+    for (;;) {
+      {
+        std::unique_lock<std::recursive_mutex> api(s->ctx->api_mu);
+        const uint64_t saved_owner = s->ctx->current_owner;
+        s->ctx->current_owner = s->clients[client].owner;   // what the program produces belongs to its client
+        if (!fl.start) fl.start = sched_event(s);
+        if (!fl.stop) fl.stop = sched_event(s);
+        if (fl.start) (void)hipEventRecord(fl.start, s->ctx->exec);
+        res.status = pw_chain(s->ctx, prog.fns.data(), (int)prog.fns.size(), &prog.in, 1, &res.out, 1, PW_STREAM);
+        if (fl.stop) (void)hipEventRecord(fl.stop, s->ctx->exec);
+        s->ctx->current_owner = saved_owner;
+      }
+      if (res.status != PW_ERR_OOM) break;
+      // Back-pressure (Section 4.6): other programs' buffers occupy the memory budget.  Stall this one: finish
+      // what is in flight, then wait for clients to collect results; give up when nothing can change any more.
+      stalled = true;
+      if (!s->inflight.empty()) { sched_retire(s); continue; }
+      bool hopeless;
+      {
+        std::lock_guard<std::mutex> lk(s->mu);
+        hopeless = (s->results.empty() && s->collecting == 0) || s->stop || s->clients[client].failed;   // nothing left to wait for
+      }
+      if (hopeless || std::chrono::steady_clock::now() - t_stall > std::chrono::seconds(20)) break;
+      std::this_thread::sleep_for(std::chrono::microseconds(50));
+    }
+    if (stalled) {
+      std::lock_guard<std::mutex> lk(s->mu);
+      s->stalls++;
+      s->stalled_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_stall).count();
     }
     s->inflight.push_back(fl);
     {
@@ -1330,6 +1401,8 @@ pw_status pw_sched_create(pw_ctx* c, int policy, int max_in_flight, pw_sched** o
     delete s;
     return fail(c, PW_ERR_DEVICE, "could not create the scheduler's timing events");
   }
+  static std::atomic<uint64_t> next_id{1};
+  s->id = next_id.fetch_add(1) & 0x7FFFFFFFu;
   s->thread = std::thread(sched_loop, s);
   c->scheds.push_back(s);
   *out = s;
@@ -1359,8 +1432,49 @@ pw_status pw_sched_add_client(pw_sched* s, double weight, int* client) {
   bool any = false;
   for (auto& o : s->clients)
     if (!any || o.vtime < c.vtime) { c.vtime = o.vtime; any = true; }
+  c.owner = (1ull << 63) | (s->id << 32) | (uint64_t)s->clients.size();
   s->clients.push_back(c);
   *client = (int)s->clients.size() - 1;
+  return PW_OK;
+}
+
+pw_status pw_sched_client_fail(pw_sched* s, int client, int64_t* objects_released) {
+  if (!s) return PW_ERR_INVALID;
+  uint64_t owner;
+  {
+    std::lock_guard<std::mutex> lk(s->mu);
+    if (client < 0 || client >= (int)s->clients.size()) return PW_ERR_INVALID;
+    SchedClient& c = s->clients[client];
+    c.failed = true;
+    owner = c.owner;
+    // programs that never reached the device are dropped; whoever waits for them learns why
+    for (auto& p : c.queue) {
+      SchedResult r;
+      r.status = PW_ERR_POISONED;
+      s->results[p.ticket] = r;
+      s->queued--;
+    }
+    c.queue.clear();
+    // results of this client that nobody collected are collected with its other objects below
+    for (auto& kv : s->results)
+      if (kv.second.status == PW_OK && kv.second.out) {
+        FutureRec* f = nullptr;
+        {
+          std::unique_lock<std::recursive_mutex> api(s->ctx->api_mu);
+          f = future_get(s->ctx, kv.second.out);
+          if (f && f->owner == owner) { kv.second.status = PW_ERR_POISONED; kv.second.out = 0; }
+        }
+      }
+  }
+  s->cv_done.notify_all();
+  return pw_owner_collect(s->ctx, owner, objects_released);
+}
+
+pw_status pw_sched_stalls(pw_sched* s, int64_t* programs_stalled, double* stalled_ms) {
+  if (!s) return PW_ERR_INVALID;
+  std::lock_guard<std::mutex> lk(s->mu);
+  if (programs_stalled) *programs_stalled = s->stalls;
+  if (stalled_ms) *stalled_ms = s->stalled_ms;
   return PW_OK;
 }
 
@@ -1384,6 +1498,7 @@ pw_status pw_sched_submit(pw_sched* s, int client, const pw_fn* fns, int n_fns, 
   if (client < 0 || client >= (int)s->clients.size()) return PW_ERR_INVALID;
   if (s->stop) return PW_ERR_INVALID;
   SchedClient& c = s->clients[client];
+  if (c.failed) return PW_ERR_INVALID;
   if (c.queue.empty() && s->policy == PW_SCHED_PROPORTIONAL) {
     // back from idle: no credit for time not used
     bool any = false;
@@ -1416,10 +1531,15 @@ pw_status pw_sched_wait(pw_sched* s, uint64_t ticket, void* host_dst, size_t byt
     if (it == s->results.end()) return PW_ERR_INVALID;   // the scheduler was shut down first
     r = it->second;
     s->results.erase(it);
+    if (r.status == PW_OK) s->collecting++;
   }
   if (r.status != PW_OK) return r.status;
   pw_status st = pw_await(s->ctx, r.out, host_dst, bytes);
   (void)pw_future_release(s->ctx, r.out);
+  {
+    std::lock_guard<std::mutex> lk(s->mu);
+    s->collecting--;
+  }
   return st;
 }
 
@@ -1474,6 +1594,7 @@ pw_status pw_await(pw_ctx* c, pw_future h, void* host_dst, size_t bytes) {
   hipError_t e = ev ? hipEventSynchronize(ev) : hipStreamSynchronize(exec);
   api_lk_.lock();
   f = future_get(c, h);   // the table may have been reallocated
+  if (!f) return fail(c, PW_ERR_POISONED, "the future was garbage-collected with its owner while being waited for");
   pw_status st = PW_OK;
   if (e != hipSuccess) st = fail(c, PW_ERR_DEVICE, "waiting for the future: %s", hipGetErrorString(e));
   if (st == PW_OK && f->host_poison) st = fail(c, PW_ERR_POISONED, "future depends on a failed producer");

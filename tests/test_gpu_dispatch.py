@@ -478,3 +478,95 @@ def test_program_tracing_rejects_what_cannot_run(ctx):
     ctx.future_release(f64)
     assert ctx.stats() == (live0, bytes0)
     prog.close()
+
+
+# ---- object store: ownership labels, garbage collection, back-pressure (Section 4.6) ---------------------
+
+def test_owner_labels_and_garbage_collection():
+    ctx = pwb.Context(0)
+    add1 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    keep = ctx.future_from_host(np.zeros(128, np.float32))          # label 0
+    live0, bytes0 = ctx.stats()
+    ctx.set_owner(7)
+    mine = [ctx.future_from_host(np.full(128, float(i), np.float32)) for i in range(3)]
+    (derived,) = ctx.chain([add1] * 5, [mine[0]], 1, pwb.PW_STREAM)
+    ctx.future_retain(derived)                                      # a second reference does not save it
+    pending = ctx.future_pending(pwb.PW_F32, (128,))                # never resolved: its gate is cancelled
+    ctx.set_owner(8)
+    other = ctx.future_from_host(np.ones(128, np.float32))
+    ctx.set_owner(0)
+    assert ctx.stats()[0] == live0 + 6
+    assert ctx.owner_collect(7) == 5
+    assert ctx.stats()[0] == live0 + 1
+    for h in mine + [derived, pending]:
+        with pytest.raises(pwb.PwError):
+            ctx.await_(h)                                           # the handles are dead
+    assert np.array_equal(ctx.await_(other), np.ones(128, np.float32))   # other owners are untouched
+    assert np.array_equal(ctx.await_(keep), np.zeros(128, np.float32))
+    assert ctx.owner_collect(7) == 0
+    assert ctx.owner_collect(8) == 1
+    assert ctx.stats() == (live0, bytes0)
+    ctx.close()
+
+
+def test_memory_budget_refuses_direct_calls_and_stalls_scheduled_programs(orc):
+    """Budget for three 1 MiB objects.  A direct call beyond it is refused with nothing enqueued; the scheduler
+    stalls the programs instead and lets them through as the client collects earlier results."""
+    n = 1 << 18                                                       # 1 MiB of fp32
+    ctx = pwb.Context(0)
+    add1 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, n, 1.0)
+    x = I.normal(9, 1, n, 1.0).astype(np.float32)
+    f_in = ctx.future_from_host(x)
+    base = ctx.stats()[1]
+    ctx.set_memory_limit(base + 3 * (1 << 20) + 4096)
+    held = [ctx.run_fn(add1, [f_in])[0] for _ in range(3)]
+    live, used = ctx.stats()
+    with pytest.raises(pwb.PwError) as e:
+        ctx.run_fn(add1, [f_in])
+    assert e.value.status == pwb.PW_ERR_OOM and ctx.stats() == (live, used)
+    for h in held:
+        ctx.future_release(h)
+    # chains recycle their intermediates, so a long chain still fits
+    (f,) = ctx.chain([add1] * 6, [f_in], 1, pwb.PW_STREAM)
+    assert np.array_equal(ctx.await_(f), orc.chain_add(x, 6))
+    ctx.future_release(f)
+    sched = pwb.Scheduler(ctx, pwb.PW_SCHED_FIFO, max_in_flight=8)
+    cid = sched.add_client(1.0)
+    tickets = [sched.submit(cid, [add1] * (k + 1), f_in) for k in range(10)]   # ten results of 1 MiB: seven must wait
+    time.sleep(0.05)
+    programs, _, _ = sched.client_stats(cid)
+    assert programs <= 4                                                # the rest is stalled, not failed
+    for k, t in enumerate(tickets):
+        assert np.array_equal(sched.wait(t, n), orc.chain_add(x, k + 1)), k
+    stalled, ms = sched.stalls()
+    assert stalled >= 1 and ms > 0
+    sched.close()
+    ctx.set_memory_limit(0)
+    ctx.close()
+
+
+def test_failed_client_is_garbage_collected_and_the_others_carry_on(orc):
+    ctx = pwb.Context(0)
+    sched = pwb.Scheduler(ctx, pwb.PW_SCHED_FIFO, max_in_flight=2)
+    busy = ctx.compile_scalar_fn(pwb.PW_FN_BUSY, 128, 1.0, busy_us=300.0)
+    add1 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    x = I.dispatch_input()
+    f_in = ctx.future_from_host(x)
+    live0, bytes0 = ctx.stats()
+    good, bad = sched.add_client(1.0), sched.add_client(1.0)
+    done_bad = [sched.submit(bad, [add1], f_in) for _ in range(3)]
+    sched.drain()                                                       # three results sit uncollected
+    queued_bad = [sched.submit(bad, [busy] * 8, f_in) for _ in range(6)]
+    t_good = sched.submit(good, [add1] * 4, f_in)
+    released = sched.client_fail(bad)
+    assert released >= 3
+    for t in done_bad + queued_bad[3:]:                                 # (the first ones may already have been handed out)
+        with pytest.raises(pwb.PwError) as e:
+            sched.wait(t)
+        assert e.value.status == pwb.PW_ERR_POISONED
+    with pytest.raises(pwb.PwError):
+        sched.submit(bad, [add1], f_in)
+    assert np.array_equal(sched.wait(t_good, 128), orc.chain_add(x, 4))
+    sched.close()
+    assert ctx.stats() == (live0, bytes0)
+    ctx.close()
