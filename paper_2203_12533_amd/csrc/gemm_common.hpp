@@ -153,36 +153,40 @@ struct GemmBf16Params {
 template <int FM, int FN, bool EDGE>
 __device__ __forceinline__ void gemm_epilogue_staged(bf16* smem, f32x16 (&acc)[FM][FN], const GemmBf16Params& p,
                                                      int64_t mw0, int64_t nw0, int wave, int lane) {
-  static_assert(FN == 2, "epilogue staging assumes a 64-column wave tile");
+  static_assert(FN % 2 == 0, "epilogue staging works on 64-column halves of the wave tile");
   constexpr int kLdS = 64 + 4;   // floats; 272-byte rows keep the 16-byte LDS accesses conflict-free
   const int lrow = lane & 31, lhalf = lane >> 5;
   __syncthreads();
   float* stage = reinterpret_cast<float*>(smem) + wave * (32 * kLdS);
 #pragma unroll
-  for (int i = 0; i < FM; ++i) {
+  for (int h = 0; h < FN / 2; ++h) {
 #pragma unroll
-    for (int j = 0; j < FN; ++j)
+    for (int i = 0; i < FM; ++i) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        *reinterpret_cast<float4*>(stage + lrow * kLdS + j * 32 + q * 8 + lhalf * 4) =
-            make_float4(acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
-    __syncthreads();
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          *reinterpret_cast<float4*>(stage + lrow * kLdS + j * 32 + q * 8 + lhalf * 4) =
+              make_float4(acc[i][2 * h + j][q * 4], acc[i][2 * h + j][q * 4 + 1], acc[i][2 * h + j][q * 4 + 2],
+                          acc[i][2 * h + j][q * 4 + 3]);
+      __syncthreads();
 #pragma unroll 1
-    for (int it = 0; it < 4; ++it) {
-      const int row = it * 8 + (lane >> 3), c8 = lane & 7;
-      const float4 v0 = *reinterpret_cast<const float4*>(stage + row * kLdS + c8 * 8);
-      const float4 v1 = *reinterpret_cast<const float4*>(stage + row * kLdS + c8 * 8 + 4);
-      float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-      const int64_t m = mw0 + i * 32 + row;
-      const int64_t n = nw0 + c8 * 8;
-      if (!EDGE || (m < p.M && n + 7 < p.N)) {
-        epilogue8(p.epi, m, n, v);
-      } else if (m < p.M) {
-        for (int e = 0; e < 8; ++e)
-          if (n + e < p.N) epilogue1<true>(p.epi, m, n + e, v[e]);
+      for (int it = 0; it < 4; ++it) {
+        const int row = it * 8 + (lane >> 3), c8 = lane & 7;
+        const float4 v0 = *reinterpret_cast<const float4*>(stage + row * kLdS + c8 * 8);
+        const float4 v1 = *reinterpret_cast<const float4*>(stage + row * kLdS + c8 * 8 + 4);
+        float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+        const int64_t m = mw0 + i * 32 + row;
+        const int64_t n = nw0 + h * 64 + c8 * 8;
+        if (!EDGE || (m < p.M && n + 7 < p.N)) {
+          epilogue8(p.epi, m, n, v);
+        } else if (m < p.M) {
+          for (int e = 0; e < 8; ++e)
+            if (n + e < p.N) epilogue1<true>(p.epi, m, n + e, v[e]);
+        }
       }
+      __syncthreads();
     }
-    __syncthreads();
   }
 }
 

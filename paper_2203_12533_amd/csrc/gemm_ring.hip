@@ -33,7 +33,6 @@ constexpr int kRBK = 64;            // k per stage
 constexpr int kRStages = 2;
 constexpr int kROperand = kRT * kRBK;            // elements per operand tile (32 KiB)
 constexpr int kRStage = 2 * kROperand;           // elements per stage
-constexpr int kRThreads = 512;
 
 typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef const __attribute__((address_space(1))) void* gbl_ptr;
@@ -47,12 +46,13 @@ __device__ __forceinline__ void dma16(const bf16* g, uint32_t lds_off) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_off) : "memory", "m0");
 }
 
-// One of this wave's four direct-load instructions (1 KiB each; 32 per operand tile, 4 per wave) of an operand tile.
-//   base: operand; ld: leading dimension; row0: first tile row (m or n); k0: first k of the stage; j: 0..3.
-template <bool KMAJOR>
+// One of this wave's PER direct-load instructions (1 KiB each; 32 per operand tile, shared evenly by the waves)
+// of an operand tile.  base: operand; ld: leading dimension; row0: first tile row (m or n); k0: first k of the
+// stage; j: 0..PER-1.
+template <bool KMAJOR, int PER>
 __device__ __forceinline__ void issue_one(const bf16* __restrict__ base, int64_t ld, int64_t row0, int64_t k0,
                                           uint32_t lds_tile_off, int wave, int lane, int j) {
-  const int instr = wave * 4 + j;
+  const int instr = wave * PER + j;
   const bf16* g;
   if (!KMAJOR) {
     const int r = instr * 8 + (lane >> 3);        // 8 rows x 128 bytes per instruction
@@ -90,14 +90,19 @@ __device__ __forceinline__ bf16x8 read_fragment(const bf16* lds_tile, int frag_r
 }
 
 // One 256 x 256 output tile of problem p; pid: index of the tile's workgroup among the problem's own.
-template <bool A_KMAJOR, bool B_KMAJOR>
+// Waves form a 2 x NW grid: NW = 4 -> 8 waves with 128 x 64 wave tiles, NW = 2 -> 4 waves with 128 x 128 wave
+// tiles (a third fewer LDS fragment reads per MFMA; the 256 accumulator registers then live in AGPRs).
+template <bool A_KMAJOR, bool B_KMAJOR, int NW>
 __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16* smem) {
   int tm, tn;
   tile_of_block(pid, p.tiles_m * p.tiles_n, p.tiles_m, p.tiles_n, tm, tn);
   const int64_t m0 = (int64_t)tm * kRT, n0 = (int64_t)tn * kRT;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wm = wave >> 2, wn = wave & 3;            // 2 x 4 waves, wave tile 128 x 64
-  constexpr int FM = 4, FN = 2;
+  const int wm = wave / NW, wn = wave % NW;
+  constexpr int FM = 4, FN = kRT / NW / 32;
+  constexpr int kWaveN = kRT / NW;                    // columns of a wave tile
+  constexpr int PER = 32 / (2 * NW);                  // direct-load instructions per operand tile and wave
+  static_assert(FM * FN == 2 * PER, "one direct load is issued behind each MFMA of the last k-step");
 
   f32x16 acc[FM][FN];
 #pragma unroll
@@ -110,11 +115,11 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
   const int kt_total = (int)(p.K / kRBK);
   const uint32_t smem_off = (uint32_t)(uintptr_t)(lds_ptr)smem;   // byte offset of the ring inside LDS
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-  // idx 0..3: A tile instructions, 4..7: B tile instructions of k-tile kt
+  // idx 0..PER-1: A tile instructions, PER..2 PER-1: B tile instructions of k-tile kt
   auto issue_idx = [&](int kt, int idx) {
     const uint32_t stage = smem_off + (uint32_t)(kt % kRStages) * (kRStage * 2);
-    if (idx < 4) issue_one<A_KMAJOR>(p.A, p.lda, m0, (int64_t)kt * kRBK, stage, wave_s, lane, idx);
-    else issue_one<B_KMAJOR>(p.B, p.ldb, n0, (int64_t)kt * kRBK, stage + kROperand * 2, wave_s, lane, idx - 4);
+    if (idx < PER) issue_one<A_KMAJOR, PER>(p.A, p.lda, m0, (int64_t)kt * kRBK, stage, wave_s, lane, idx);
+    else issue_one<B_KMAJOR, PER>(p.B, p.ldb, n0, (int64_t)kt * kRBK, stage + kROperand * 2, wave_s, lane, idx - PER);
   };
   auto load_frags = [&](int stage, int kk, bf16x8* af, bf16x8* bfr) {
     const bf16* a_tile = smem + stage * kRStage;
@@ -122,7 +127,7 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
 #pragma unroll
     for (int i = 0; i < FM; ++i) af[i] = read_fragment<A_KMAJOR>(a_tile, wm * 128 + i * 32, kk, lane);
 #pragma unroll
-    for (int j = 0; j < FN; ++j) bfr[j] = read_fragment<B_KMAJOR>(b_tile, wn * 64 + j * 32, kk, lane);
+    for (int j = 0; j < FN; ++j) bfr[j] = read_fragment<B_KMAJOR>(b_tile, wn * kWaveN + j * 32, kk, lane);
   };
   auto wait_and_sync = [&]() {
     // all of this wave's LDS reads and its share of the tile in flight are complete ...
@@ -139,11 +144,11 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
   // barrier the first fragments of the next tile are fetched and the direct loads of the tile after next are
   // issued between those last MFMAs.
 #pragma unroll
-  for (int idx = 0; idx < 8; ++idx) issue_idx(0, idx);
+  for (int idx = 0; idx < 2 * PER; ++idx) issue_idx(0, idx);
   wait_and_sync();
   if (kt_total > 1) {
 #pragma unroll
-    for (int idx = 0; idx < 8; ++idx) issue_idx(1, idx);
+    for (int idx = 0; idx < 2 * PER; ++idx) issue_idx(1, idx);
   }
   bf16x8 af[2][FM], bfr[2][FN];
   load_frags(0, 0, af[0], bfr[0]);
@@ -189,84 +194,85 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
   for (; kt + 2 < kt_total; ++kt) k_tile(kt, yes{}, yes{});
   if (kt + 1 < kt_total) { k_tile(kt, yes{}, no{}); ++kt; }
   k_tile(kt, no{}, no{});
-  gemm_epilogue_staged<FM, FN, false>(smem, acc, p, m0 + wm * 128, n0 + wn * 64, wave, lane);
+  gemm_epilogue_staged<FM, FN, false>(smem, acc, p, m0 + wm * 128, n0 + wn * kWaveN, wave, lane);
 }
 
-template <bool A_KMAJOR, bool B_KMAJOR>
-__global__ __launch_bounds__(kRThreads) void gemm_ring_kernel(GemmBf16Params p) {
+template <bool A_KMAJOR, bool B_KMAJOR, int NW>
+__global__ __launch_bounds__(2 * NW * 64) void gemm_ring_kernel(GemmBf16Params p) {
   extern __shared__ __attribute__((aligned(16))) bf16 smem[];
-  ring_tile<A_KMAJOR, B_KMAJOR>(p, blockIdx.x, smem);
+  ring_tile<A_KMAJOR, B_KMAJOR, NW>(p, blockIdx.x, smem);
 }
 
 // Two independent problems of the same operand layout in one launch: workgroups [0, tiles of p0) work on p0,
 // the rest on p1.  Lets two GEMMs that each fill only part of the chip share one round of workgroups.
-template <bool A_KMAJOR, bool B_KMAJOR>
-__global__ __launch_bounds__(kRThreads) void gemm_ring_pair_kernel(GemmBf16Params p0, GemmBf16Params p1) {
+template <bool A_KMAJOR, bool B_KMAJOR, int NW>
+__global__ __launch_bounds__(2 * NW * 64) void gemm_ring_pair_kernel(GemmBf16Params p0, GemmBf16Params p1) {
   extern __shared__ __attribute__((aligned(16))) bf16 smem[];
   const int t0 = p0.tiles_m * p0.tiles_n;
   const bool first = (int)blockIdx.x < t0;
   const GemmBf16Params p = first ? p0 : p1;
-  ring_tile<A_KMAJOR, B_KMAJOR>(p, first ? (int)blockIdx.x : (int)blockIdx.x - t0, smem);
+  ring_tile<A_KMAJOR, B_KMAJOR, NW>(p, first ? (int)blockIdx.x : (int)blockIdx.x - t0, smem);
 }
 
 constexpr size_t kRSmemBytes = (size_t)kRStages * kRStage * sizeof(bf16);   // 128 KiB
 static_assert(kRSmemBytes >= 8 * 32 * 68 * 4, "epilogue staging must fit");
 
-template <bool AK, bool BK_>
+// Waves along n.  4 (8 waves, 128 x 64 wave tiles) is what runs; 2 (4 waves, 128 x 128 wave tiles, accumulators in
+// AGPRs, a third fewer LDS fragment reads per MFMA) compiles to a clean loop as well and measured the same
+// within noise on every shape of the step, so it is not instantiated.
+constexpr int kRingNW = 4;
+
+template <bool AK, bool BK_, int NW>
 hipError_t prepare_ring_variant() {
   static bool attr_done = false;
   if (attr_done) return hipSuccess;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_kernel<AK, BK_>),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_kernel<AK, BK_, NW>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRSmemBytes);
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_pair_kernel<AK, BK_, NW>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRSmemBytes);
   if (e == hipSuccess) attr_done = true;
   return e;
 }
 
-template <bool AK, bool BK_>
-hipError_t launch_ring_variant(hipStream_t s, const GemmBf16Params& p) {
-  hipError_t e = prepare_ring_variant<AK, BK_>();
+template <bool AK, bool BK_, int NW>
+hipError_t launch_ring_variant(hipStream_t s, const GemmBf16Params& p, const GemmBf16Params* p1) {
+  hipError_t e = prepare_ring_variant<AK, BK_, NW>();
   if (e != hipSuccess) return e;
-  gemm_ring_kernel<AK, BK_><<<p.tiles_m * p.tiles_n, kRThreads, kRSmemBytes, s>>>(p);
+  if (!p1) {
+    gemm_ring_kernel<AK, BK_, NW><<<p.tiles_m * p.tiles_n, 2 * NW * 64, kRSmemBytes, s>>>(p);
+  } else {
+    gemm_ring_pair_kernel<AK, BK_, NW><<<p.tiles_m * p.tiles_n + p1->tiles_m * p1->tiles_n, 2 * NW * 64, kRSmemBytes, s>>>(p, *p1);
+  }
   return hipGetLastError();
 }
 
-template <bool AK, bool BK_>
-hipError_t launch_ring_pair_variant(hipStream_t s, const GemmBf16Params& p0, const GemmBf16Params& p1) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_pair_kernel<AK, BK_>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRSmemBytes);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
-  gemm_ring_pair_kernel<AK, BK_><<<p0.tiles_m * p0.tiles_n + p1.tiles_m * p1.tiles_n, kRThreads, kRSmemBytes, s>>>(p0, p1);
-  return hipGetLastError();
+template <int NW>
+hipError_t launch_ring_nw(hipStream_t s, const GemmBf16Params& p, const GemmBf16Params* p1, bool ak, bool bk) {
+  if (!ak && !bk) return launch_ring_variant<false, false, NW>(s, p, p1);
+  if (!ak && bk) return launch_ring_variant<false, true, NW>(s, p, p1);
+  if (ak && bk) return launch_ring_variant<true, true, NW>(s, p, p1);
+  return launch_ring_variant<true, false, NW>(s, p, p1);
 }
 
 }  // namespace
 
+hipError_t launch_gemm_ring(hipStream_t s, const GemmBf16Params& p, bool ak, bool bk) {
+  return launch_ring_nw<kRingNW>(s, p, nullptr, ak, bk);
+}
 hipError_t launch_gemm_ring_pair(hipStream_t s, const GemmBf16Params& p0, const GemmBf16Params& p1, bool ak, bool bk) {
-  if (!ak && !bk) return launch_ring_pair_variant<false, false>(s, p0, p1);
-  if (!ak && bk) return launch_ring_pair_variant<false, true>(s, p0, p1);
-  if (ak && bk) return launch_ring_pair_variant<true, true>(s, p0, p1);
-  return launch_ring_pair_variant<true, false>(s, p0, p1);
+  return launch_ring_nw<kRingNW>(s, p0, &p1, ak, bk);
 }
 
 bool gemm_ring_supported(int64_t M, int64_t N, int64_t K) { return M % kRT == 0 && N % kRT == 0 && K % kRBK == 0 && K >= kRBK; }
 
-hipError_t launch_gemm_ring(hipStream_t s, const GemmBf16Params& p, bool ak, bool bk) {
-  if (!ak && !bk) return launch_ring_variant<false, false>(s, p);
-  if (!ak && bk) return launch_ring_variant<false, true>(s, p);
-  if (ak && bk) return launch_ring_variant<true, true>(s, p);
-  return launch_ring_variant<true, false>(s, p);
-}
-
+// Sets the dynamic-LDS attribute of every variant up front (never inside a stream capture).
 hipError_t gemm_ring_init() {
-  hipError_t e = prepare_ring_variant<false, false>();
-  if (e == hipSuccess) e = prepare_ring_variant<false, true>();
-  if (e == hipSuccess) e = prepare_ring_variant<true, true>();
-  if (e == hipSuccess) e = prepare_ring_variant<true, false>();
-  return e;   // the pair kernels set their attribute on first use
+  hipError_t e = prepare_ring_variant<false, false, kRingNW>();
+  if (e == hipSuccess) e = prepare_ring_variant<false, true, kRingNW>();
+  if (e == hipSuccess) e = prepare_ring_variant<true, true, kRingNW>();
+  if (e == hipSuccess) e = prepare_ring_variant<true, false, kRingNW>();
+  return e;
 }
 
 }  // namespace pw
