@@ -338,6 +338,11 @@ typedef struct {
   const void* aux;           /* [M, ldc] or null */
   void* C;
   void* C2;                  /* second output of PW_EPI_BIAS_GELU, else null */
+  float* b_colsum;           /* optional, fp32 [N]: sum over k of op(B)[k, n] (overwritten, or added into when
+                                accumulate = 1) - the bias gradient that goes with a weight gradient dW = x^T . dy.
+                                Served only where it is free: bf16, both operands k-major, M, N multiples of 256, K of
+                                64, fp32 PW_EPI_STORE output and at least 150 tiles of 256 x 256 (alone or as a pair);
+                                PW_ERR_DEVICE otherwise.  Null: not wanted. */
 } pw_gemm_args;
 
 /* C[M,N] = op(A)[M,K] . op(B)[K,N] with fp32 accumulation and a fused epilogue.  bf16 operands run on

@@ -56,7 +56,7 @@ class GemmArgs(C.Structure):
                 ("lda", C.c_int64), ("ldb", C.c_int64), ("ldc", C.c_int64),
                 ("epilogue", C.c_int32), ("out_dtype", C.c_int32), ("accumulate", C.c_int32),
                 ("A", C.c_void_p), ("B", C.c_void_p), ("bias", C.c_void_p), ("aux", C.c_void_p),
-                ("C", C.c_void_p), ("C2", C.c_void_p)]
+                ("C", C.c_void_p), ("C2", C.c_void_p), ("b_colsum", C.c_void_p)]
 
 
 class PwError(RuntimeError):

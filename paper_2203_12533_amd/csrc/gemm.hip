@@ -422,6 +422,8 @@ static GemmBf16Params bf16_params_of(const GemmArgs& a, int tile) {
   p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb;
   p.tiles_m = (int)((a.M + tile - 1) / tile);
   p.tiles_n = (int)((a.N + tile - 1) / tile);
+  p.b_colsum = a.b_colsum;
+  p.colsum_accumulate = a.accumulate;
   p.epi = epi_of(a);
   return p;
 }
@@ -431,10 +433,16 @@ static bool ring_eligible(const GemmArgs& a) {
   return g_use_ring && a.dtype == kBF16 && gemm_ring_supported(a.M, a.N, a.K);
 }
 
+bool gemm_colsum_fusable(const GemmArgs& a, bool paired) {
+  return ring_eligible(a) && a.a_kmajor && a.b_kmajor && a.out_dtype == kF32 && a.epilogue == kEpiStore &&
+         (paired || (a.M / 256) * (a.N / 256) >= 150);
+}
+
 static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a) {
   bool empty;
   hipError_t err = check_gemm_args(a, &empty);
   if (err != hipSuccess || empty) return err;
+  if (a.b_colsum && (!gemm_colsum_fusable(a, false) || ((uintptr_t)a.b_colsum & 3))) return hipErrorInvalidValue;
 
   if (a.dtype == kF32) {
     GemmF32Params p;
@@ -466,16 +474,25 @@ static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a) {
 
 // Two independent GEMMs.  When both are ring-kernel problems of one operand layout and together fill at least
 // most of the chip, they share a single launch (their tiles run side by side); otherwise one launch each.
+// Whether launch_gemm_pair runs the two problems in one launch: both ring-kernel problems of one operand layout,
+// enough tiles together, and at least one of them would leave part of the chip idle (or miss the ring kernel) alone.
+bool gemm_pair_shares_launch(const GemmArgs& a0, const GemmArgs& a1) {
+  if (a0.M <= 0 || a0.N <= 0 || a1.M <= 0 || a1.N <= 0) return false;
+  if (!ring_eligible(a0) || !ring_eligible(a1) || a0.a_kmajor != a1.a_kmajor || a0.b_kmajor != a1.b_kmajor) return false;
+  const int64_t t0 = (a0.M / 256) * (a0.N / 256), t1 = (a1.M / 256) * (a1.N / 256);
+  return t0 + t1 >= 150 && t0 + t1 <= (1 << 20) && !(t0 % 256 == 0 && t1 % 256 == 0);
+}
+
 hipError_t launch_gemm_pair(hipStream_t s, const GemmArgs& a0, const GemmArgs& a1) {
   bool e0, e1;
   hipError_t err = check_gemm_args(a0, &e0);
   if (err == hipSuccess) err = check_gemm_args(a1, &e1);
   if (err != hipSuccess) return err;
-  const bool pairable = !e0 && !e1 && ring_eligible(a0) && ring_eligible(a1) && a0.a_kmajor == a1.a_kmajor &&
-                        a0.b_kmajor == a1.b_kmajor;
+  const bool shared = !e0 && !e1 && gemm_pair_shares_launch(a0, a1);
   const int64_t t0 = (a0.M / 256) * (a0.N / 256), t1 = (a1.M / 256) * (a1.N / 256);
-  // worth it only if at least one of the two would leave part of the chip idle (or miss the ring kernel) alone
-  if (!pairable || t0 + t1 < 150 || t0 + t1 > (1 << 20) || (t0 % 256 == 0 && t1 % 256 == 0)) {
+  if ((a0.b_colsum && !gemm_colsum_fusable(a0, shared)) || (a1.b_colsum && !gemm_colsum_fusable(a1, shared)))
+    return hipErrorInvalidValue;   // checked before anything is launched
+  if (!shared) {
     err = launch_gemm(s, a0);
     return err == hipSuccess ? launch_gemm(s, a1) : err;
   }

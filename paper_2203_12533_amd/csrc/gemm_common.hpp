@@ -140,6 +140,8 @@ struct GemmBf16Params {
   const bf16* B;
   int64_t M, N, K, lda, ldb;
   int tiles_m, tiles_n;
+  float* b_colsum;          // ring kernel, k-major B only: out[n] (=|+=) sum_k B[k][n]; null: not wanted
+  int colsum_accumulate;
   EpiParams epi;
 };
 

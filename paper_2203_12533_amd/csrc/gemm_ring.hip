@@ -112,6 +112,24 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // Column sums of a k-major B (the bias gradient that goes with a weight gradient): the waves of the first tile
+  // row that own the B columns (wm == 0) add up the fragments they read anyway.
+  const bool do_colsum = B_KMAJOR && p.b_colsum != nullptr && tm == 0 && wm == 0;
+  float cs[FN];
+#pragma unroll
+  for (int j = 0; j < FN; ++j) cs[j] = 0.f;
+  auto add_colsum = [&](const bf16x8* bfr) {
+    if (do_colsum) {
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        float t = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t += (float)bfr[j][e];
+        cs[j] += t;
+      }
+    }
+  };
+
   const int kt_total = (int)(p.K / kRBK);
   const uint32_t smem_off = (uint32_t)(uintptr_t)(lds_ptr)smem;   // byte offset of the ring inside LDS
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
@@ -172,6 +190,7 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
         for (int j = 0; j < FN; ++j)
           if (kk != 0 || i != 0 || j != 0)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+      add_colsum(bfr[kk & 1]);
       __builtin_amdgcn_sched_barrier(0);
     }
     if constexpr (decltype(more)::value) {
@@ -187,6 +206,8 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
         if constexpr (decltype(more2)::value) issue_idx(kt + 2, i * FN + j);
         __builtin_amdgcn_sched_barrier(0);
       }
+    add_colsum(bfr[(KS - 1) & 1]);
+    __builtin_amdgcn_sched_barrier(0);
   };
   using yes = std::integral_constant<bool, true>;
   using no = std::integral_constant<bool, false>;
@@ -194,6 +215,16 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
   for (; kt + 2 < kt_total; ++kt) k_tile(kt, yes{}, yes{});
   if (kt + 1 < kt_total) { k_tile(kt, yes{}, no{}); ++kt; }
   k_tile(kt, no{}, no{});
+  if (do_colsum) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const float t = cs[j] + __shfl_xor(cs[j], 32, 64);   // the two k-halves of the fragment
+      if (lane < 32) {
+        float* o = p.b_colsum + n0 + wn * kWaveN + j * 32 + lane;
+        *o = p.colsum_accumulate ? *o + t : t;
+      }
+    }
+  }
   gemm_epilogue_staged<FM, FN, false>(smem, acc, p, m0 + wm * 128, n0 + wn * kWaveN, wave, lane);
 }
 

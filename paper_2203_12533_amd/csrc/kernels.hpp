@@ -21,6 +21,7 @@ struct GemmArgs {
   const void* aux;
   void* C;
   void* C2;
+  float* b_colsum;   // optional: column sums of op(B) over k (= or +=, following `accumulate`); see gemm_colsum_fusable
 };
 
 // elementwise.hip
@@ -68,6 +69,10 @@ hipError_t attention_dma_init();
 
 // gemm.hip
 hipError_t launch_gemm(hipStream_t s, const GemmArgs& a);
+// Whether launch_gemm / launch_gemm_pair can deliver a.b_colsum for this problem (k-major bf16 operands on full
+// 256 x 256 tiles: the weight-gradient GEMMs); callers fall back to launch_colsum otherwise.
+bool gemm_colsum_fusable(const GemmArgs& a, bool paired);
+bool gemm_pair_shares_launch(const GemmArgs& a0, const GemmArgs& a1);
 // Two independent GEMMs; shares one launch between them when that fills the chip better (same results either way).
 hipError_t launch_gemm_pair(hipStream_t s, const GemmArgs& a0, const GemmArgs& a1);
 // Timing of MFMA GEMM launches with HIP events on the launch stream (measurement aid).

@@ -205,8 +205,18 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
       PW_TRY(launch_colsum(m->stream, kF32, m->dx_a, g + P(m, e + 11).offset, m->ws, N, d, accumulate), "b2 grad");
     PW_TRY(gemm_dgrad(m, dx_op, e + 10, N, F, d, kEpiGeluBwd, A.u, m->d_big), "ffn2 dgrad + gelu'");
     // FFN1: u = m W1 + b1
-    PW_TRY(gemm_wgrad(m, A.mm, m->d_big, e + 8, N, d, F, accumulate), "ffn1 wgrad");
-    PW_TRY(launch_colsum(m->stream, dt, m->d_big, g + P(m, e + 9).offset, m->ws, N, F, accumulate), "b1 grad");
+    {
+      // b1 gradient = column sums of d_big: delivered by the weight-gradient GEMM where that is free
+      GemmArgs wa = wgrad_args(m, A.mm, m->d_big, e + 8, N, d, F, accumulate);
+      wa.b_colsum = g + P(m, e + 9).offset;
+      if (gemm_colsum_fusable(wa, false)) {
+        PW_TRY(launch_gemm(m->stream, wa), "ffn1 wgrad + b1 grad");
+      } else {
+        wa.b_colsum = nullptr;
+        PW_TRY(launch_gemm(m->stream, wa), "ffn1 wgrad");
+        PW_TRY(launch_colsum(m->stream, dt, m->d_big, g + P(m, e + 9).offset, m->ws, N, F, accumulate), "b1 grad");
+      }
+    }
     PW_TRY(gemm_dgrad(m, m->d_big, e + 8, N, d, F, kEpiStore, nullptr, m->d_small), "ffn1 dgrad");
     // LN2 and the residual branch: dx_b = dx_a + LN2'(d_small)
     PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_mid, m->w + P(m, e + 6).offset, A.mean2, A.rstd2, m->dx_a,
@@ -221,9 +231,18 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
                                 c.n_head, m->hd()), "attention bwd");
     // QKV: qkv = a Wqkv + bqkv
     // (dy_out, the bf16 residual gradient, stays intact until the LN1 backward below rewrites it)
-    PW_TRY(launch_gemm_pair(m->stream, wgrad_args(m, A.a, m->d_qkv, e + 2, N, d, 3 * d, accumulate),
-                            wgrad_args(m, A.o, dy_out, e + 4, N, d, d, accumulate)), "qkv + out-proj wgrad");
-    PW_TRY(launch_colsum(m->stream, dt, m->d_qkv, g + P(m, e + 3).offset, m->ws, N, 3 * d, accumulate), "bqkv grad");
+    {
+      GemmArgs wq = wgrad_args(m, A.a, m->d_qkv, e + 2, N, d, 3 * d, accumulate);
+      const GemmArgs wo = wgrad_args(m, A.o, dy_out, e + 4, N, d, d, accumulate);
+      wq.b_colsum = g + P(m, e + 3).offset;   // bqkv gradient = column sums of d_qkv
+      if (gemm_colsum_fusable(wq, gemm_pair_shares_launch(wq, wo))) {
+        PW_TRY(launch_gemm_pair(m->stream, wq, wo), "qkv + out-proj wgrad + bqkv grad");
+      } else {
+        wq.b_colsum = nullptr;
+        PW_TRY(launch_gemm_pair(m->stream, wq, wo), "qkv + out-proj wgrad");
+        PW_TRY(launch_colsum(m->stream, dt, m->d_qkv, g + P(m, e + 3).offset, m->ws, N, 3 * d, accumulate), "bqkv grad");
+      }
+    }
     PW_TRY(gemm_dgrad(m, m->d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small), "qkv dgrad");
     // LN1 and the residual branch: dx_a = dx_b + LN1'(d_small)
     PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->w + P(m, e).offset, A.mean1, A.rstd1, m->dx_b,

@@ -1888,22 +1888,18 @@ double pw_model_step_flops(const pw_lm_config* cfg) { return cfg ? model_step_fl
     return PW_OK;                                                                                    \
   } while (0)
 
-pw_status pw_op_gemm(pw_ctx* c, const pw_gemm_args* a) {
-  if (!c || !a) return PW_ERR_INVALID;
-  GemmArgs g{};
-  g.dtype = a->dtype; g.a_kmajor = a->a_kmajor; g.b_kmajor = a->b_kmajor;
-  g.M = a->M; g.N = a->N; g.K = a->K; g.lda = a->lda; g.ldb = a->ldb; g.ldc = a->ldc;
-  g.epilogue = a->epilogue; g.out_dtype = a->out_dtype; g.accumulate = a->accumulate;
-  g.A = a->A; g.B = a->B; g.bias = a->bias; g.aux = a->aux; g.C = a->C; g.C2 = a->C2;
-  PW_OP(c, launch_gemm(c->exec, g));
-}
 static GemmArgs gemm_args_of(const pw_gemm_args* a) {
   GemmArgs g{};
   g.dtype = a->dtype; g.a_kmajor = a->a_kmajor; g.b_kmajor = a->b_kmajor;
   g.M = a->M; g.N = a->N; g.K = a->K; g.lda = a->lda; g.ldb = a->ldb; g.ldc = a->ldc;
   g.epilogue = a->epilogue; g.out_dtype = a->out_dtype; g.accumulate = a->accumulate;
   g.A = a->A; g.B = a->B; g.bias = a->bias; g.aux = a->aux; g.C = a->C; g.C2 = a->C2;
+  g.b_colsum = a->b_colsum;
   return g;
+}
+pw_status pw_op_gemm(pw_ctx* c, const pw_gemm_args* a) {
+  if (!c || !a) return PW_ERR_INVALID;
+  PW_OP(c, launch_gemm(c->exec, gemm_args_of(a)));
 }
 pw_status pw_op_gemm_pair(pw_ctx* c, const pw_gemm_args* a0, const pw_gemm_args* a1) {
   if (!c || !a0 || !a1) return PW_ERR_INVALID;

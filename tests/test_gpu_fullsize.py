@@ -73,7 +73,8 @@ def test_paired_attention_weight_gradients_at_cfg3_shape(ctx, orc):
                     epilogue=pwb.PW_EPI_STORE, out_dtype=pwb.PW_F32, accumulate=0, A=ptr(x), B=ptr(g), C=ptr(out))
     dwqkv = torch.full((D, 3 * D), float("nan"), device="cuda")
     dwo = torch.full((D, D), float("nan"), device="cuda")
-    ctx.gemm_pair(args(a, dqkv, dwqkv, 3 * D), args(o, dy, dwo, D))
+    dbqkv = torch.full((3 * D,), float("nan"), device="cuda")      # the bias gradient rides along: column sums of dqkv
+    ctx.gemm_pair({**args(a, dqkv, dwqkv, 3 * D), "b_colsum": ptr(dbqkv)}, args(o, dy, dwo, D))
     one_qkv, one_o = torch.empty_like(dwqkv), torch.empty_like(dwo)
     ctx.gemm(**args(a, dqkv, one_qkv, 3 * D))
     ctx.gemm(**args(o, dy, one_o, D))
@@ -84,6 +85,15 @@ def test_paired_attention_weight_gradients_at_cfg3_shape(ctx, orc):
     _, want, _ = orc.linear_bwd(host(o[:, cols]), np.zeros((len(cols), D)), host(dy))
     assert rel_l2(host(dwo[cols]), want) < 1e-5
     assert rel_l2(host(one_o[cols]), want) < 1e-5
+    assert rel_l2(host(dbqkv), host(dqkv).astype(np.float64).sum(axis=0)) < 1e-5
+    # alone (192 tiles: the ring kernel) and accumulating into what is there
+    acc_w, acc_b = torch.ones_like(dwqkv), torch.ones_like(dbqkv)
+    ctx.gemm(**{**args(a, dqkv, acc_w, 3 * D), "accumulate": 1, "b_colsum": ptr(acc_b)})
+    ctx.synchronize()
+    assert rel_l2(host(acc_b), host(dqkv).astype(np.float64).sum(axis=0) + 1.0) < 1e-5
+    assert rel_l2(host(acc_w), host(one_qkv) + 1.0) < 1e-6
+    with pytest.raises(pwb.PwError):                               # 64 tiles alone: not served, nothing launched
+        ctx.gemm(**{**args(o, dy, dwo, D), "b_colsum": ptr(acc_b)})
     assert torch.isfinite(dwqkv).all() and torch.isfinite(dwo).all()
     assert rel_l2(host(dwqkv), host(one_qkv)) < 1e-6 and rel_l2(host(dwo), host(one_o)) < 1e-6
 
