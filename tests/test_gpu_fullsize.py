@@ -196,3 +196,37 @@ def test_full_cfg3_step_properties():
     used = np.unique(I.lm_tokens(CFG3)[:, :-1])
     unused = np.setdiff1d(np.arange(V), used)[:50]
     assert (e1.reshape(V, D)[unused] == 0).all() and np.abs(e1.reshape(V, D)[used[:50]]).max() > 0
+
+
+def test_one_layer_step_at_cfg3_layer_shapes_matches_oracle(orc):
+    """The production kernels end to end against the oracle: one layer with cfg3's d_model / heads / FFN width and
+    full sequence length, 2048 tokens, so that the forward, data-gradient and weight-gradient GEMMs all run on the
+    ring-buffered kernel (192-1024 tiles), the weight-gradient pair and the fused bias-gradient sums included, the
+    head_dim-128 attention kernels see 1024-token sequences and LayerNorm its one-wave-per-row path.  Loss and
+    every gradient tensor are compared (the vocabulary is cut to 8192 to keep the oracle's run near 20 s)."""
+    cfg = CFG3.with_(n_layer=1, batch=2, vocab=8192)
+    tok = I.lm_tokens(cfg)
+    rng = np.random.default_rng(20)            # 84 M parameters: numpy's generator draws them in a second
+    params = {}
+    for name, shape, kind in I.param_shapes(cfg):
+        a = rng.standard_normal(int(np.prod(shape)), dtype=np.float32) * np.float32(cfg.init_std)
+        if kind == "gain":
+            a += np.float32(1.0)
+        params[name] = I.round_to_bf16(a).reshape(shape)       # biases and gains perturbed too
+    ref = orc.lm_train_step(cfg, params, tok)
+    with pwb.Context(0) as ctx:
+        model = ctx.model(cfg)
+        model.load_params(params)
+        step = model.compile_train_step()
+        ft = ctx.future_from_host(tok)
+        fl = ctx.train_step(step, ft)
+        loss = float(ctx.await_(fl)[0])
+        assert abs(loss - ref["loss"]) / abs(ref["loss"]) < 2e-2, (loss, ref["loss"])
+        grads = model.export_all(pwb.PW_GRADS, params)
+        worst = ("", 0.0)
+        for k, g in grads.items():
+            err = rel_l2(g, ref["grads"][k])
+            worst = max(worst, (k, err), key=lambda t: t[1])
+            assert err < 2e-2, (k, err)
+        print("worst gradient error", worst)
+        model.close()
