@@ -31,12 +31,28 @@ def test_binding_covers_the_header():
     pwb.lib()      # sets every signature; raises if one is missing
 
 
-def test_struct_layouts_match_the_header():
-    assert C.sizeof(pwb.TensorSpec) == 40
-    assert C.sizeof(pwb.FnDesc) == 16 + 16 * 40 + 16
-    assert C.sizeof(pwb.LMConfigC) == 16 * 4
-    assert C.sizeof(pwb.StageParams) == 16
-    assert C.sizeof(pwb.GemmArgs) == 12 + 4 + 6 * 8 + 12 + 4 + 6 * 8
+def test_struct_layouts_match_the_header(tmp_path):
+    """The ctypes mirrors against the C compiler's view of include/pw.h: size of every struct that crosses the
+    boundary, and the offset of each struct's last field."""
+    structs = [("pw_tensor_spec", pwb.TensorSpec, "dims"), ("pw_fn_desc", pwb.FnDesc, "params_bytes"),
+               ("pw_lm_config", pwb.LMConfigC, "n_microbatch"), ("pw_stage_params", pwb.StageParams, "microbatch"),
+               ("pw_gemm_args", pwb.GemmArgs, "b_colsum"), ("pw_node", pwb.Node, "in"),
+               ("pw_sched_slice", pwb.SchedSlice, "end_ms")]
+    src = tmp_path / "sizes.c"
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "pw.h"', 'int main(void) {']
+    for cname, _, last in structs:
+        lines.append(f'  printf("%zu %zu\\n", sizeof({cname}), offsetof({cname}, {last}));')
+    lines += ['  return 0;', '}']
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "sizes"
+    import subprocess
+    subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    out = subprocess.check_output([str(exe)], text=True).split()
+    for k, (cname, ct, last) in enumerate(structs):
+        size, off = int(out[2 * k]), int(out[2 * k + 1])
+        assert C.sizeof(ct) == size, cname
+        py_last = ct._fields_[-1][0]
+        assert getattr(ct, py_last).offset == off, (cname, last)
 
 
 def test_no_gpu_means_a_loud_failure_not_a_fallback():
