@@ -219,11 +219,19 @@ def main():
     ctx.synchronize()
     torch.cuda.synchronize()
     ctx.profile_begin()
+    # per-step durations as well: HIP events on the executor stream between the steps (no synchronisation)
+    ext = torch.cuda.ExternalStream(ctx.stream_ptr())
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    pending = [one_step() for _ in range(args.steps)]
+    pending = []
+    marks[0].record(ext)
+    for i in range(args.steps):
+        pending.append(one_step())
+        marks[i + 1].record(ext)
     ctx.synchronize()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     n_gemm, gemm_ms, gemm_flops = ctx.profile_end()
     for f in pending:
         losses.append(float(ctx.await_(f).reshape(-1)[0]))
@@ -257,6 +265,8 @@ def main():
                    "tokens_per_step": tokens_per_step, "model_tflop_per_step": round(flops / 1e12, 3)},
         "pct_peak_bf16_mfma": round(100.0 * achieved / PEAK_BF16_TFLOPS, 2),
         "step_tflops": round(achieved, 1),
+        "ms_per_step_device": {"median": round(per_step[len(per_step) // 2], 3), "min": round(per_step[0], 3),
+                               "max": round(per_step[-1], 3)},
         ("loss_first_last" if cfg.has_head else "dx0_first_last"): [round(losses[0], 4), round(losses[-1], 4)],
         "roofline": {"bound": "mfma", "kernel": "bf16 MFMA GEMM (gemm_ring_kernel + gemm_bf16_kernel, all layouts)", "achieved": round(gemm_tflops, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
