@@ -396,6 +396,13 @@ __global__ __launch_bounds__(kNT) void attn_dkv_dma_kernel(const bf16* __restric
         second_product(Gs, hb * 32 + b2 * 16, pack8(s, b2 * 8), dv);    // dV^T += dO^T . P
         second_product(Qs, hb * 32 + b2 * 16, pack8(ds, b2 * 8), dk);   // dK^T += Q^T . dS
       }
+      // Register classes: the two output accumulators are only ever touched by MFMAs, so they belong in the
+      // accumulation registers; the K/V fragments feed MFMAs as ordinary operands.  Without the hint the
+      // allocator parks the fragments and the score accumulators there and copies them back and forth.
+#pragma unroll
+      for (int cb = 0; cb < HD / 32; ++cb) asm volatile("" : "+a"(dk[cb]), "+a"(dv[cb]));
+#pragma unroll
+      for (int kk = 0; kk < HD / 16; ++kk) asm volatile("" : "+v"(kf[kk]), "+v"(vf[kk]));
     }
   }
   if (key < T) {
