@@ -399,6 +399,10 @@ pw_status pw_op_adam(pw_ctx* ctx, float* w, float* m, float* v, const float* g, 
  * drains the stream and returns the number of such launches, the sum of their durations in
  * milliseconds and the sum of their algorithmic FLOPs (2 M N K each).  Not for use inside PW_GRAPH. */
 pw_status pw_profile_begin(pw_ctx* ctx);
+/* Stops bracketing further launches without waiting for anything (each pair of events costs a few microseconds of
+ * stream time: a caller that times many steps brackets only the first few); the launches recorded so far are
+ * still returned by pw_profile_end. */
+pw_status pw_profile_pause(pw_ctx* ctx);
 pw_status pw_profile_end(pw_ctx* ctx, int64_t* launches, double* total_ms, double* total_flops);
 
 #ifdef __cplusplus

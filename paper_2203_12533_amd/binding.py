@@ -124,6 +124,7 @@ _SIGS = {
     "pw_model_export_activation": (C.c_int, [C.c_void_p, C.c_char_p, C.c_int, C.c_void_p, C.c_int64]),
     "pw_model_step_flops": (C.c_double, [C.POINTER(LMConfigC)]),
     "pw_profile_begin": (C.c_int, [C.c_void_p]),
+    "pw_profile_pause": (C.c_int, [C.c_void_p]),
     "pw_profile_end": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "pw_op_gemm": (C.c_int, [C.c_void_p, C.POINTER(GemmArgs)]),
     "pw_op_gemm_pair": (C.c_int, [C.c_void_p, C.POINTER(GemmArgs), C.POINTER(GemmArgs)]),
@@ -342,6 +343,9 @@ class Context:
     # -- measurement aid
     def profile_begin(self):
         self._check(lib().pw_profile_begin(self._h))
+
+    def profile_pause(self):
+        self._check(lib().pw_profile_pause(self._h))
 
     def profile_end(self):
         n, ms, fl = C.c_int64(), C.c_double(), C.c_double()

@@ -338,6 +338,8 @@ void gemm_profile_begin() {
   g_profile_on = true;
 }
 
+void gemm_profile_pause() { g_profile_on = false; }
+
 hipError_t gemm_profile_end(int64_t* launches, double* total_ms, double* total_flops) {
   g_profile_on = false;
   double ms = 0.0, fl = 0.0;

@@ -77,6 +77,7 @@ bool gemm_pair_shares_launch(const GemmArgs& a0, const GemmArgs& a1);
 hipError_t launch_gemm_pair(hipStream_t s, const GemmArgs& a0, const GemmArgs& a1);
 // Timing of MFMA GEMM launches with HIP events on the launch stream (measurement aid).
 void gemm_profile_begin();
+void gemm_profile_pause();   // stop bracketing launches; what was recorded so far stays for gemm_profile_end
 hipError_t gemm_profile_end(int64_t* launches, double* total_ms, double* total_flops);
 // One-time per-process set-up of kernel attributes (large dynamic LDS); call once before any capture.
 hipError_t gemm_init();

@@ -1944,6 +1944,11 @@ pw_status pw_profile_begin(pw_ctx* c) {
   gemm_profile_begin();
   return PW_OK;
 }
+pw_status pw_profile_pause(pw_ctx* c) {
+  if (!c) return PW_ERR_INVALID;
+  gemm_profile_pause();
+  return PW_OK;
+}
 pw_status pw_profile_end(pw_ctx* c, int64_t* launches, double* total_ms, double* total_flops) {
   if (!c) return PW_ERR_INVALID;
   hipError_t e = gemm_profile_end(launches, total_ms, total_flops);
