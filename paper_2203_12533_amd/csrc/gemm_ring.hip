@@ -161,12 +161,17 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
   // of the MFMAs of the LAST k-step: by then every wave has finished reading the current stage, so behind the
   // barrier the first fragments of the next tile are fetched and the direct loads of the tile after next are
   // issued between those last MFMAs.
+  // Prologue: both stages are free, so the first two k-tiles go out back to back; only the first is waited for.
 #pragma unroll
   for (int idx = 0; idx < 2 * PER; ++idx) issue_idx(0, idx);
-  wait_and_sync();
   if (kt_total > 1) {
 #pragma unroll
     for (int idx = 0; idx < 2 * PER; ++idx) issue_idx(1, idx);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * PER) : "memory");   // all but the second tile's loads have landed
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  } else {
+    wait_and_sync();
   }
   bf16x8 af[2][FM], bfr[2][FN];
   load_frags(0, 0, af[0], bfr[0]);
