@@ -55,21 +55,23 @@ __device__ __forceinline__ float block_max(float v, float* red) {
   return t;
 }
 
-// tanh(x) = 1 - 2 / (exp(2x) + 1) with the hardware exp2 and reciprocal: a handful of instructions, relative
-// error ~1e-6, exact limits at +-inf.
-__device__ __forceinline__ float fast_tanh(float x) {
-  const float e = __builtin_amdgcn_exp2f(x * 2.8853900817779268f);   // exp(2x)
-  return 1.f - 2.f * __builtin_amdgcn_rcpf(e + 1.f);
+// tanh-form GELU and its derivative, fp32, written through the logistic function: with z = c (u + 0.044715 u^3),
+// 0.5 (1 + tanh z) = s = 1 / (1 + exp(-2z)), so gelu(u) = u s and gelu'(u) = s + u s (1 - s) 2 dz/du.  Six plain
+// operations and two transcendentals for gelu, three more operations for the derivative on top.
+struct GeluSig { float s, dz2; };   // s as above; dz2 = 2 dz/du = 2c (1 + 3 * 0.044715 u^2)
+__device__ __forceinline__ GeluSig gelu_sigmoid(float u) {
+  constexpr float c2 = 2.f * 0.7978845608028654f;            // 2 sqrt(2/pi)
+  constexpr float ka = -c2 * 1.4426950408889634f;            // exp(-2z) = exp2(u (ka + kb u^2))
+  constexpr float kb = ka * 0.044715f;
+  const float u2 = u * u;
+  const float e = __builtin_amdgcn_exp2f(u * __builtin_fmaf(kb, u2, ka));
+  return {__builtin_amdgcn_rcpf(1.f + e), __builtin_fmaf(c2 * 3.f * 0.044715f, u2, c2)};
 }
-// tanh-form GELU and its derivative, fp32.
-__device__ __forceinline__ float gelu_f(float u) {
-  const float c = 0.7978845608028654f;   // sqrt(2/pi)
-  return 0.5f * u * (1.f + fast_tanh(c * (u + 0.044715f * u * u * u)));
-}
+__device__ __forceinline__ float gelu_f(float u) { return u * gelu_sigmoid(u).s; }
 __device__ __forceinline__ float gelu_grad_f(float u) {
-  const float c = 0.7978845608028654f;
-  const float t = fast_tanh(c * (u + 0.044715f * u * u * u));
-  return 0.5f * (1.f + t) + 0.5f * u * (1.f - t * t) * c * (1.f + 3.f * 0.044715f * u * u);
+  const GeluSig g = gelu_sigmoid(u);
+  const float h = u * g.s;
+  return __builtin_fmaf(__builtin_fmaf(-h, g.s, h), g.dz2, g.s);
 }
 
 }  // namespace pw

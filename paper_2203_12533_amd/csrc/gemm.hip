@@ -1,7 +1,10 @@
-// GEMM engine: C[M,N] = op(A)[M,K] . op(B)[K,N], fp32 accumulation, fused epilogues.
+// GEMM engine: C[M,N] = op(A)[M,K] . op(B)[K,N], fp32 accumulation, fused epilogues; argument checks and the
+// choice of kernel for every problem (launch_gemm, launch_gemm_pair).
 //
-// bf16 path (the one that carries ~96% of the train step's FLOPs): v_mfma_f32_32x32x16_bf16 tiles,
-// 64-wide wavefronts, block tile BM x BN x 64 staged through double-buffered LDS.  In LDS both operand
+// bf16 problems made of full 256 x 256 tiles that fill the chip go to the ring-buffered kernel of gemm_ring.hip
+// (direct global->LDS loads): that is every GEMM of the large workloads.  The kernel in this file takes the rest
+// - any shape, ragged edges, few tiles: v_mfma_f32_32x32x16_bf16 tiles, 64-wide wavefronts, block tile
+// BM x BN x 64 staged through registers into double-buffered LDS.  In LDS both operand
 // tiles are always [row][k] with k contiguous (row = m for A, n for B), padded to 72 elements per row so
 // that the 16-byte fragment reads of 32 consecutive rows fall in distinct bank groups.  Operands stored
 // k-major in memory (B of a forward GEMM, both operands of a weight-gradient GEMM) are transposed on the

@@ -14,16 +14,23 @@ struct EpiParams {
   int64_t ldc;
 };
 
+__device__ __forceinline__ bool epi_has_bias(int mode) {
+  return mode == kEpiBias || mode == kEpiBiasResidual || mode == kEpiBiasGelu;
+}
+
 // Epilogue on 4 consecutive columns n0..n0+3 of row m.  AUXT: element type of aux for kEpiGeluBwd / of the
 // outputs when out_bf16 (the activation type).
 template <bool BF16ACT>
 __device__ __forceinline__ void epilogue4(const EpiParams& e, int64_t m, int64_t n0, float v0, float v1, float v2, float v3) {
   const int64_t off = m * e.ldc + n0;
-  if (e.mode == kEpiBias || e.mode == kEpiBiasResidual || e.mode == kEpiBiasGelu) {
-    if (e.bias) {
-      const float4 b = *reinterpret_cast<const float4*>(e.bias + n0);
-      v0 += b.x; v1 += b.y; v2 += b.z; v3 += b.w;
-    }
+  if (epi_has_bias(e.mode) && e.bias) {
+    const float4 b = *reinterpret_cast<const float4*>(e.bias + n0);
+    v0 += b.x; v1 += b.y; v2 += b.z; v3 += b.w;
+  }
+  float h0 = 0.f, h1 = 0.f, h2 = 0.f, h3 = 0.f;
+  const bool two = e.mode == kEpiBiasGelu;
+  if (two) {
+    h0 = gelu_f(v0); h1 = gelu_f(v1); h2 = gelu_f(v2); h3 = gelu_f(v3);
   }
   if (e.mode == kEpiBiasResidual) {
     const float4 r = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(e.aux) + off);
@@ -42,8 +49,8 @@ __device__ __forceinline__ void epilogue4(const EpiParams& e, int64_t m, int64_t
   if (e.out_bf16) {
     bf16x4 o = {(bf16)v0, (bf16)v1, (bf16)v2, (bf16)v3};
     *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(e.C) + off) = o;
-    if (e.mode == kEpiBiasGelu) {
-      bf16x4 h = {(bf16)gelu_f(v0), (bf16)gelu_f(v1), (bf16)gelu_f(v2), (bf16)gelu_f(v3)};
+    if (two) {
+      bf16x4 h = {(bf16)h0, (bf16)h1, (bf16)h2, (bf16)h3};
       *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(e.C2) + off) = h;
     }
   } else {
@@ -53,8 +60,7 @@ __device__ __forceinline__ void epilogue4(const EpiParams& e, int64_t m, int64_t
       v0 += old.x; v1 += old.y; v2 += old.z; v3 += old.w;
     }
     *reinterpret_cast<float4*>(c) = make_float4(v0, v1, v2, v3);
-    if (e.mode == kEpiBiasGelu)
-      *reinterpret_cast<float4*>(reinterpret_cast<float*>(e.C2) + off) = make_float4(gelu_f(v0), gelu_f(v1), gelu_f(v2), gelu_f(v3));
+    if (two) *reinterpret_cast<float4*>(reinterpret_cast<float*>(e.C2) + off) = make_float4(h0, h1, h2, h3);
   }
 }
 
@@ -62,60 +68,100 @@ __device__ __forceinline__ void epilogue4(const EpiParams& e, int64_t m, int64_t
 template <bool BF16ACT>
 __device__ __forceinline__ void epilogue1(const EpiParams& e, int64_t m, int64_t n, float v) {
   const int64_t off = m * e.ldc + n;
-  if ((e.mode == kEpiBias || e.mode == kEpiBiasResidual || e.mode == kEpiBiasGelu) && e.bias) v += e.bias[n];
+  if (epi_has_bias(e.mode) && e.bias) v += e.bias[n];
   if (e.mode == kEpiBiasResidual) v += reinterpret_cast<const float*>(e.aux)[off];
-  if (e.mode == kEpiGeluBwd)
-    v *= gelu_grad_f(BF16ACT ? (float)reinterpret_cast<const bf16*>(e.aux)[off] : reinterpret_cast<const float*>(e.aux)[off]);
+  if (e.mode == kEpiGeluBwd) {
+    const float u = BF16ACT ? (float)reinterpret_cast<const bf16*>(e.aux)[off] : reinterpret_cast<const float*>(e.aux)[off];
+    v *= gelu_grad_f(u);
+  }
+  float h = 0.f;
+  const bool two = e.mode == kEpiBiasGelu;
+  if (two) h = gelu_f(v);
   if (e.out_bf16) {
     reinterpret_cast<bf16*>(e.C)[off] = (bf16)v;
-    if (e.mode == kEpiBiasGelu) reinterpret_cast<bf16*>(e.C2)[off] = (bf16)gelu_f(v);
+    if (two) reinterpret_cast<bf16*>(e.C2)[off] = (bf16)h;
   } else {
     float* c = reinterpret_cast<float*>(e.C) + off;
     if (e.accumulate) v += *c;
     *c = v;
-    if (e.mode == kEpiBiasGelu) reinterpret_cast<float*>(e.C2)[off] = gelu_f(v);
+    if (two) reinterpret_cast<float*>(e.C2)[off] = h;
   }
 }
 
+// What epilogue8 reads from global memory besides the bias: 16 bytes of bf16 aux, 32 bytes of fp32 residual, or the
+// 32 bytes of fp32 output it accumulates into.  The staged epilogue fetches these a few row segments ahead of their
+// use, so that a wave has several such loads in flight instead of one round trip per row segment.
+struct EpiExtra { uint4 lo, hi; };
+enum { kExtraNone = 0, kExtraAuxBf16, kExtraAuxF32, kExtraOldC };
+__device__ __forceinline__ int epi_extra_kind(const EpiParams& e) {
+  if (e.mode == kEpiBiasResidual) return kExtraAuxF32;
+  if (e.mode == kEpiGeluBwd) return kExtraAuxBf16;
+  return (!e.out_bf16 && e.accumulate) ? kExtraOldC : kExtraNone;
+}
+// src: e.aux for the two aux kinds, e.C for kExtraOldC.
+__device__ __forceinline__ const void* epi_extra_src(const EpiParams& e, int kind) {
+  return kind == kExtraOldC ? e.C : e.aux;
+}
+__device__ __forceinline__ void epi_extra_load(int kind, const void* src, int64_t off, EpiExtra& x) {
+  if (kind == kExtraAuxBf16) {
+    x.lo = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16*>(src) + off);
+  } else if (kind != kExtraNone) {
+    const uint4* s4 = reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(src) + off);
+    x.lo = s4[0];
+    x.hi = s4[1];
+  }
+}
+__device__ __forceinline__ void add8(float* v, const uint4& lo, const uint4& hi) {
+  v[0] += __uint_as_float(lo.x); v[1] += __uint_as_float(lo.y); v[2] += __uint_as_float(lo.z); v[3] += __uint_as_float(lo.w);
+  v[4] += __uint_as_float(hi.x); v[5] += __uint_as_float(hi.y); v[6] += __uint_as_float(hi.z); v[7] += __uint_as_float(hi.w);
+}
+
 // Epilogue on 8 consecutive columns n0..n0+7 of row m (bf16-activation kernels; all accesses 16-byte vectors).
-__device__ __forceinline__ void epilogue8(const EpiParams& e, int64_t m, int64_t n0, float* v) {
+// x holds what epi_extra_load(kind, epi_extra_src(e, kind), m * ldc + n0, x) fetched, kind = epi_extra_kind(e).
+__device__ __forceinline__ void epilogue8(const EpiParams& e, int64_t m, int64_t n0, float* v, int kind, const EpiExtra& x) {
   const int64_t off = m * e.ldc + n0;
-  if ((e.mode == kEpiBias || e.mode == kEpiBiasResidual || e.mode == kEpiBiasGelu) && e.bias) {
+  if (epi_has_bias(e.mode) && e.bias) {
     const float4 b0 = *reinterpret_cast<const float4*>(e.bias + n0), b1 = *reinterpret_cast<const float4*>(e.bias + n0 + 4);
     v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w; v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
   }
-  if (e.mode == kEpiBiasResidual) {
-    const float* r = reinterpret_cast<const float*>(e.aux) + off;
-    const float4 r0 = *reinterpret_cast<const float4*>(r), r1 = *reinterpret_cast<const float4*>(r + 4);
-    v[0] += r0.x; v[1] += r0.y; v[2] += r0.z; v[3] += r0.w; v[4] += r1.x; v[5] += r1.y; v[6] += r1.z; v[7] += r1.w;
-  } else if (e.mode == kEpiGeluBwd) {
-    const bf16x8 u = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16*>(e.aux) + off);
+  if (kind == kExtraAuxF32) {
+    add8(v, x.lo, x.hi);
+  } else if (kind == kExtraAuxBf16) {
+    const bf16x8 u = __builtin_bit_cast(bf16x8, x.lo);
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] *= gelu_grad_f((float)u[i]);
+  }
+  const bool two = e.mode == kEpiBiasGelu;
+  float hh[8];
+  if (two) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) hh[i] = gelu_f(v[i]);
   }
   if (e.out_bf16) {
     bf16x8 o;
 #pragma unroll
     for (int i = 0; i < 8; ++i) o[i] = (bf16)v[i];
     *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(e.C) + off) = o;
-    if (e.mode == kEpiBiasGelu) {
+    if (two) {
       bf16x8 h;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) h[i] = (bf16)gelu_f(v[i]);
+      for (int i = 0; i < 8; ++i) h[i] = (bf16)hh[i];
       *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(e.C2) + off) = h;
     }
   } else {
     float* c = reinterpret_cast<float*>(e.C) + off;
-    if (e.accumulate) {
-      const float4 o0 = *reinterpret_cast<const float4*>(c), o1 = *reinterpret_cast<const float4*>(c + 4);
-      v[0] += o0.x; v[1] += o0.y; v[2] += o0.z; v[3] += o0.w; v[4] += o1.x; v[5] += o1.y; v[6] += o1.z; v[7] += o1.w;
+    if (kind == kExtraOldC) {
+      add8(v, x.lo, x.hi);
+    } else if (e.accumulate) {   // accumulating into the output of a residual epilogue: no slot left to fetch ahead
+      const uint4 o0 = *reinterpret_cast<const uint4*>(c), o1 = *reinterpret_cast<const uint4*>(c + 4);
+      add8(v, o0, o1);
     }
     *reinterpret_cast<float4*>(c) = make_float4(v[0], v[1], v[2], v[3]);
     *reinterpret_cast<float4*>(c + 4) = make_float4(v[4], v[5], v[6], v[7]);
-    if (e.mode == kEpiBiasGelu) {
+    if (two) {
       float* c2 = reinterpret_cast<float*>(e.C2) + off;
-      *reinterpret_cast<float4*>(c2) = make_float4(gelu_f(v[0]), gelu_f(v[1]), gelu_f(v[2]), gelu_f(v[3]));
-      *reinterpret_cast<float4*>(c2 + 4) = make_float4(gelu_f(v[4]), gelu_f(v[5]), gelu_f(v[6]), gelu_f(v[7]));
+      *reinterpret_cast<float4*>(c2) = make_float4(hh[0], hh[1], hh[2], hh[3]);
+      *reinterpret_cast<float4*>(c2 + 4) = make_float4(hh[4], hh[5], hh[6], hh[7]);
     }
   }
 }
@@ -151,15 +197,42 @@ struct GemmBf16Params {
 // 32 x 64 block at a time in its own slice of LDS (the operand tiles are dead by now) and reads it back
 // row-wise: 8 lanes cover the 64 columns of a row with 8 consecutive values each, so every global access of
 // the epilogue (output, residual, saved pre-activation) is a 16-byte vector and every row segment a full
-// 128-byte line or more.  All waves of the block must call (it synchronises the block).
-template <int FM, int FN, bool EDGE>
-__device__ __forceinline__ void gemm_epilogue_staged(bf16* smem, f32x16 (&acc)[FM][FN], const GemmBf16Params& p,
-                                                     int64_t mw0, int64_t nw0, int wave, int lane) {
+// 128-byte line or more.  What a segment needs from memory besides the accumulators is fetched one 32-row block
+// ahead.  All waves of the block must call (it synchronises the block).
+template <int FM, int FN, bool EDGE, int KIND>
+__device__ __forceinline__ void gemm_epilogue_staged_kind(bf16* smem, f32x16 (&acc)[FM][FN], const GemmBf16Params& p,
+                                                          int64_t mw0, int64_t nw0, int wave, int lane) {
   static_assert(FN % 2 == 0, "epilogue staging works on 64-column halves of the wave tile");
   constexpr int kLdS = 64 + 4;   // floats; 272-byte rows keep the 16-byte LDS accesses conflict-free
+  constexpr bool kAhead = KIND != kExtraNone;
   const int lrow = lane & 31, lhalf = lane >> 5;
-  __syncthreads();
+  const int r8 = lane >> 3, c8 = lane & 7;
+  const void* const extra_src = epi_extra_src(p.epi, KIND);
+  const int64_t M = p.M, N = p.N, ldc = p.epi.ldc;
+  // Row segment `it` of 32-row block i, column half h: the fetch of what this lane needs there.
+  auto fetch = [=](int h, int i, int it, EpiExtra& x) {
+    const int64_t m = mw0 + i * 32 + it * 8 + r8, n = nw0 + h * 64 + c8 * 8;
+    if (!EDGE || (m < M && n + 7 < N)) epi_extra_load(KIND, extra_src, m * ldc + n, x);
+  };
+  // Between the staging writes and the row-wise reads of a wave's private slice.  With extras in flight a block
+  // barrier would wait for them (and for the stores); a wave's LDS accesses execute in issue order, so keeping
+  // the compiler from reordering them is enough.  Without extras the plain barrier measured faster.
+  auto sync = [] {
+    if (kAhead) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    } else {
+      __syncthreads();
+    }
+  };
+  __syncthreads();   // every wave is done with the operand tiles
   float* stage = reinterpret_cast<float*>(smem) + wave * (32 * kLdS);
+  EpiExtra q[4] = {};   // extras of the four row segments of a 32-row block, fetched one block ahead
+  if (kAhead) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) fetch(0, 0, it, q[it]);
+  }
 #pragma unroll
   for (int h = 0; h < FN / 2; ++h) {
 #pragma unroll
@@ -167,28 +240,49 @@ __device__ __forceinline__ void gemm_epilogue_staged(bf16* smem, f32x16 (&acc)[F
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-          *reinterpret_cast<float4*>(stage + lrow * kLdS + j * 32 + q * 8 + lhalf * 4) =
-              make_float4(acc[i][2 * h + j][q * 4], acc[i][2 * h + j][q * 4 + 1], acc[i][2 * h + j][q * 4 + 2],
-                          acc[i][2 * h + j][q * 4 + 3]);
-      __syncthreads();
-#pragma unroll 1
-      for (int it = 0; it < 4; ++it) {
-        const int row = it * 8 + (lane >> 3), c8 = lane & 7;
+        for (int qq = 0; qq < 4; ++qq)
+          *reinterpret_cast<float4*>(stage + lrow * kLdS + j * 32 + qq * 8 + lhalf * 4) =
+              make_float4(acc[i][2 * h + j][qq * 4], acc[i][2 * h + j][qq * 4 + 1], acc[i][2 * h + j][qq * 4 + 2],
+                          acc[i][2 * h + j][qq * 4 + 3]);
+      sync();
+      const bool wrap = i + 1 == FM;
+      const int ni = wrap ? 0 : i + 1, nh = wrap ? h + 1 : h;
+      auto segment = [&](int it, EpiExtra& slot) {
+        const int row = it * 8 + r8;
         const float4 v0 = *reinterpret_cast<const float4*>(stage + row * kLdS + c8 * 8);
         const float4 v1 = *reinterpret_cast<const float4*>(stage + row * kLdS + c8 * 8 + 4);
         float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+        const EpiExtra x = slot;
+        if (kAhead && nh < FN / 2) fetch(nh, ni, it, slot);
         const int64_t m = mw0 + i * 32 + row;
         const int64_t n = nw0 + h * 64 + c8 * 8;
-        if (!EDGE || (m < p.M && n + 7 < p.N)) {
-          epilogue8(p.epi, m, n, v);
-        } else if (m < p.M) {
+        if (!EDGE || (m < M && n + 7 < N)) {
+          epilogue8(p.epi, m, n, v, KIND, x);
+        } else if (m < M) {
           for (int e = 0; e < 8; ++e)
-            if (n + e < p.N) epilogue1<true>(p.epi, m, n + e, v[e]);
+            if (n + e < N) epilogue1<true>(p.epi, m, n + e, v[e]);
         }
+      };
+      if (kAhead) {   // unrolled: each segment has its own registers for what was fetched ahead
+#pragma unroll
+        for (int it = 0; it < 4; ++it) segment(it, q[it]);
+      } else {
+#pragma unroll 1
+        for (int it = 0; it < 4; ++it) segment(it, q[0]);
       }
-      __syncthreads();
+      sync();
     }
+  }
+}
+
+template <int FM, int FN, bool EDGE>
+__device__ __forceinline__ void gemm_epilogue_staged(bf16* smem, f32x16 (&acc)[FM][FN], const GemmBf16Params& p,
+                                                     int64_t mw0, int64_t nw0, int wave, int lane) {
+  switch (epi_extra_kind(p.epi)) {   // uniform over the launch
+    case kExtraAuxBf16: gemm_epilogue_staged_kind<FM, FN, EDGE, kExtraAuxBf16>(smem, acc, p, mw0, nw0, wave, lane); break;
+    case kExtraAuxF32: gemm_epilogue_staged_kind<FM, FN, EDGE, kExtraAuxF32>(smem, acc, p, mw0, nw0, wave, lane); break;
+    case kExtraOldC: gemm_epilogue_staged_kind<FM, FN, EDGE, kExtraOldC>(smem, acc, p, mw0, nw0, wave, lane); break;
+    default: gemm_epilogue_staged_kind<FM, FN, EDGE, kExtraNone>(smem, acc, p, mw0, nw0, wave, lane); break;
   }
 }
 
