@@ -22,7 +22,8 @@ _lib = None
 def build(force: bool = True) -> str:
     """Compile the oracle with g++ (plain loops, OpenMP over independent iterations)."""
     srcs = [os.path.join(_HERE, "oracle_capi.cpp")]
-    if not force and os.path.exists(_SO):
+    deps = srcs + [os.path.join(_HERE, h) for h in ("lm_oracle.hpp", "encdec_oracle.hpp")]
+    if not force and os.path.exists(_SO) and all(os.path.getmtime(_SO) >= os.path.getmtime(f) for f in deps):
         return _SO
     cmd = ["g++", "-O3", "-march=x86-64-v3", "-fopenmp", "-fPIC", "-shared", "-std=c++17",
            "-fno-fast-math", "-o", _SO] + srcs
@@ -38,6 +39,8 @@ def lib():
         _lib = C.CDLL(_SO)
         _lib.orc_lm_param_count.restype = C.c_int64
         _lib.orc_lm_param_total.restype = C.c_int64
+        _lib.orc_encdec_param_count.restype = C.c_int64
+        _lib.orc_encdec_param_total.restype = C.c_int64
     return _lib
 
 
@@ -274,6 +277,108 @@ def stage_fwd_bwd(cfg, params: dict, xs, dys):
     if rc:
         raise RuntimeError("oracle stage_fwd_bwd rejected the configuration")
     return list(Y), list(dX), unpack(cfg, G, params)
+
+
+# ---- encoder-decoder workload -------------------------------------------------------------------
+
+def mha_fwd(q, k, v, B, Tq, Tk, H, hd, causal=False):
+    """Multi-head attention of Tq queries over Tk keys.  q [B*Tq, >= H*hd], k and v [B*Tk, >= H*hd] may be
+    column slices of wider arrays (k and v of the same one): rows are taken at their strides."""
+    q, k, v, ldq, ldkv = _strided(q, k, v)
+    o = np.empty((B * Tq, H * hd))
+    rc = lib().orc_mha_fwd(q, C.c_int64(ldq), k, v, C.c_int64(ldkv), _p(o), B, Tq, Tk, H, hd, int(causal))
+    if rc:
+        raise ValueError("causal attention needs Tq == Tk")
+    return o
+
+
+def mha_bwd(q, k, v, dout, B, Tq, Tk, H, hd, causal=False):
+    """Returns (dq [B*Tq, H*hd], dk [B*Tk, H*hd], dv [B*Tk, H*hd])."""
+    q, k, v, ldq, ldkv = _strided(q, k, v)
+    dout = _f64(dout)
+    d = H * hd
+    dq, dk, dv = np.empty((B * Tq, d)), np.empty((B * Tk, d)), np.empty((B * Tk, d))
+    rc = lib().orc_mha_bwd(q, C.c_int64(ldq), k, v, C.c_int64(ldkv), _p(dout), _p(dq), C.c_int64(d), _p(dk), _p(dv),
+                           C.c_int64(d), B, Tq, Tk, H, hd, int(causal))
+    if rc:
+        raise ValueError("causal attention needs Tq == Tk")
+    return dq, dk, dv
+
+
+_keep = []
+
+
+def _strided(q, k, v):
+    """Pointers and row strides of 2-D float64 arrays that may be column slices of C-contiguous parents."""
+    out = []
+    for a in (q, k, v):
+        a = np.asarray(a)
+        if a.dtype != np.float64 or a.ndim != 2 or a.strides[1] != 8:
+            a = _f64(a)
+        out.append(a)
+    q, k, v = out
+    if k.strides[0] != v.strides[0]:
+        k, v = _f64(k), _f64(v)
+    _keep[:] = [q, k, v]   # alive until the next call returns
+    cast = lambda a: C.cast(a.ctypes.data, C.POINTER(C.c_double))
+    return cast(q), cast(k), cast(v), q.strides[0] // 8, k.strides[0] // 8
+
+
+class EncDecShape(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("Le", "Ld", "d", "H", "F", "V", "Ts", "Tt", "B")]
+
+
+def _ed_shape(cfg) -> EncDecShape:
+    return EncDecShape(cfg.n_enc_layer, cfg.n_dec_layer, cfg.d_model, cfg.n_head, cfg.d_ff, cfg.vocab, cfg.src_len,
+                       cfg.tgt_len, cfg.batch)
+
+
+def encdec_param_table(cfg):
+    s = _ed_shape(cfg)
+    out = []
+    name = C.create_string_buffer(64)
+    off, num = C.c_int64(), C.c_int64()
+    for i in range(lib().orc_encdec_param_count(C.byref(s))):
+        lib().orc_encdec_param_info(C.byref(s), C.c_int64(i), name, 64, C.byref(off), C.byref(num))
+        out.append((name.value.decode(), off.value, num.value))
+    return out
+
+
+def encdec_train_step(cfg, params: dict, src, tgt, state=None, t: int = 1, update: bool = True,
+                      want_logits: bool = False, backward: bool = True):
+    """One encoder-decoder train step in double.  Returns dict(loss, grads, params, m, v[, logits])."""
+    s = _ed_shape(cfg)
+    tab = encdec_param_table(cfg)
+    total = lib().orc_encdec_param_total(C.byref(s))
+
+    def pk(dct):
+        flat = np.zeros(total)
+        for name, off, num in tab:
+            flat[off:off + num] = np.asarray(dct[name], dtype=np.float64).reshape(-1)
+        return flat
+
+    def unpk(flat):
+        return {name: flat[off:off + num].reshape(np.shape(params[name])).copy() for name, off, num in tab}
+
+    P = pk(params)
+    M, V = (np.zeros_like(P), np.zeros_like(P)) if state is None else (pk(state["m"]), pk(state["v"]))
+    G = np.zeros_like(P)
+    src, tgt = _i32(src), _i32(tgt)
+    logits = np.empty((cfg.batch * cfg.tgt_len, cfg.vocab)) if want_logits else None
+    loss = C.c_double()
+    o = _opt(cfg, t, update and backward)
+    t0 = time.perf_counter()
+    rc = lib().orc_encdec_train_step(C.byref(s), _p(P), _p(M), _p(V), _p(src, C.c_int32), _p(tgt, C.c_int32),
+                                     C.byref(o), C.byref(loss), _p(G), _p(logits), int(backward))
+    seconds = time.perf_counter() - t0
+    if rc:
+        raise RuntimeError("oracle encdec_train_step rejected the configuration")
+    out = {"loss": float(loss.value), "seconds": seconds}
+    if backward:
+        out.update(grads=unpk(G), params=unpk(P), m=unpk(M), v=unpk(V))
+    if want_logits:
+        out["logits"] = logits
+    return out
 
 
 # ---- dispatch micro-benchmark -------------------------------------------------------------------

@@ -1,5 +1,6 @@
 // C entry points of the CPU oracle (test infrastructure only; see lm_oracle.hpp).
 // Every array is a host pointer owned by the caller; functions return 0 on success.
+#include "encdec_oracle.hpp"
 #include "lm_oracle.hpp"
 
 #include <chrono>
@@ -119,6 +120,47 @@ int orc_stage_fwd_bwd(const orc_lm_shape* c, const double* P, int n_mb, const do
                       double* Y, double* dX, double* G) {
   if (c->has_embed || c->has_head) return 1;
   stage_fwd_bwd<double>(to_shape(c), P, n_mb, X, dY, Y, dX, G);
+  return 0;
+}
+
+// ---- encoder-decoder workload (encdec_oracle.hpp) ------------------------------------------------
+
+struct orc_encdec_shape {
+  int Le, Ld, d, H, F, V, Ts, Tt, B;
+};
+static EncDecShape to_ed_shape(const orc_encdec_shape* c) {
+  return EncDecShape{c->Le, c->Ld, c->d, c->H, c->F, c->V, c->Ts, c->Tt, c->B};
+}
+
+int orc_mha_fwd(const double* q, int64_t ldq, const double* k, const double* v, int64_t ldkv, double* o, int B, int Tq,
+                int Tk, int H, int hd, int causal) {
+  if (causal && Tq != Tk) return 1;
+  mha_fwd<double>(q, (size_t)ldq, k, v, (size_t)ldkv, o, B, Tq, Tk, H, hd, causal);
+  return 0;
+}
+int orc_mha_bwd(const double* q, int64_t ldq, const double* k, const double* v, int64_t ldkv, const double* dout,
+                double* dq, int64_t lddq, double* dk, double* dv, int64_t lddkv, int B, int Tq, int Tk, int H, int hd,
+                int causal) {
+  if (causal && Tq != Tk) return 1;
+  mha_bwd<double>(q, (size_t)ldq, k, v, (size_t)ldkv, dout, dq, (size_t)lddq, dk, dv, (size_t)lddkv, B, Tq, Tk, H, hd, causal);
+  return 0;
+}
+
+int64_t orc_encdec_param_count(const orc_encdec_shape* c) { return (int64_t)encdec_param_table(to_ed_shape(c)).size(); }
+int64_t orc_encdec_param_total(const orc_encdec_shape* c) { return (int64_t)encdec_param_total(to_ed_shape(c)); }
+int orc_encdec_param_info(const orc_encdec_shape* c, int64_t idx, char* name, int name_cap, int64_t* offset, int64_t* numel) {
+  const auto t = encdec_param_table(to_ed_shape(c));
+  if (idx < 0 || idx >= (int64_t)t.size()) return 1;
+  std::snprintf(name, name_cap, "%s", t[idx].name.c_str());
+  *offset = (int64_t)t[idx].offset;
+  *numel = (int64_t)t[idx].numel;
+  return 0;
+}
+int orc_encdec_train_step(const orc_encdec_shape* c, double* P, double* M, double* V, const int32_t* src,
+                          const int32_t* tgt, const orc_opt* o, double* loss, double* G, double* logits, int do_bwd) {
+  if (c->Le < 1 || c->Ld < 1 || c->d % c->H) return 1;
+  OptConfig oc{o->kind, o->lr, o->beta1, o->beta2, o->eps, o->t};
+  encdec_train_step<double>(to_ed_shape(c), P, M, V, src, tgt, oc, loss, G, logits, do_bwd);
   return 0;
 }
 

@@ -207,6 +207,106 @@ def stage_io(cfg: LMConfig, seed: int = 1234):
     return xs, dys
 
 
+@dataclass(frozen=True)
+class EncDecConfig:
+    """Shape of one accelerator's share of the encoder-decoder step (the text-to-text family of the paper's
+    Table 1, built from the decoder-only model's pieces)."""
+    n_enc_layer: int
+    n_dec_layer: int
+    d_model: int
+    n_head: int
+    d_ff: int
+    vocab: int
+    src_len: int
+    tgt_len: int
+    batch: int
+    bf16: bool = False
+    optimizer: str = "sgd"
+    lr: float = 1e-2
+    beta1: float = 0.9
+    beta2: float = 0.95
+    eps: float = 1e-8
+    init_std: float = 0.02
+
+    @property
+    def head_dim(self) -> int:
+        return self.d_model // self.n_head
+
+    @property
+    def n_tokens(self) -> int:
+        """Source plus target positions of one step."""
+        return self.batch * (self.src_len + self.tgt_len)
+
+    def with_(self, **kw) -> "EncDecConfig":
+        return replace(self, **kw)
+
+
+def encdec_workload(name: str) -> EncDecConfig:
+    if name == "ed1":    # small fp32 case the CPU oracle finishes in seconds; ragged lengths
+        return EncDecConfig(2, 2, 256, 4, 1024, 1024, 96, 80, 3, bf16=False, optimizer="sgd", lr=1e-2)
+    if name == "ed3":    # 6 + 6 layers of the cfg3 layer shape, 1024 source and 1024 target positions
+        return EncDecConfig(6, 6, 2048, 16, 8192, 32768, 1024, 1024, 8, bf16=True, optimizer="adam", lr=1e-4)
+    raise KeyError(name)
+
+
+def encdec_param_shapes(cfg: EncDecConfig):
+    """Ordered (name, shape, kind) list.  Linear weights are [in, out]; wqkv columns are [Q | K | V], wkv
+    columns [K | V]; head h owns columns h*head_dim .. (h+1)*head_dim of each part."""
+    d, F, V = cfg.d_model, cfg.d_ff, cfg.vocab
+
+    def attn(p):
+        return [(p + "ln1_g", (d,), "gain"), (p + "ln1_b", (d,), "bias"),
+                (p + "wqkv", (d, 3 * d), "matrix"), (p + "bqkv", (3 * d,), "bias"),
+                (p + "wo", (d, d), "matrix"), (p + "bo", (d,), "bias")]
+
+    def ffn(p):
+        return [(p + "ln2_g", (d,), "gain"), (p + "ln2_b", (d,), "bias"),
+                (p + "w1", (d, F), "matrix"), (p + "b1", (F,), "bias"),
+                (p + "w2", (F, d), "matrix"), (p + "b2", (d,), "bias")]
+
+    out = [("enc.wte", (V, d), "matrix"), ("enc.wpe", (cfg.src_len, d), "matrix")]
+    for l in range(cfg.n_enc_layer):
+        out += attn(f"e{l}.") + ffn(f"e{l}.")
+    out += [("enc.lnf_g", (d,), "gain"), ("enc.lnf_b", (d,), "bias"),
+            ("dec.wte", (V, d), "matrix"), ("dec.wpe", (cfg.tgt_len, d), "matrix")]
+    for l in range(cfg.n_dec_layer):
+        p = f"d{l}."
+        out += attn(p)
+        out += [(p + "lnx_g", (d,), "gain"), (p + "lnx_b", (d,), "bias"),
+                (p + "wq", (d, d), "matrix"), (p + "bq", (d,), "bias"),
+                (p + "wkv", (d, 2 * d), "matrix"), (p + "bkv", (2 * d,), "bias"),
+                (p + "wox", (d, d), "matrix"), (p + "box", (d,), "bias")]
+        out += ffn(p)
+    out += [("dec.lnf_g", (d,), "gain"), ("dec.lnf_b", (d,), "bias"), ("wh", (d, V), "matrix")]
+    return out
+
+
+def encdec_params(cfg: EncDecConfig, seed: int = 1234, perturb: bool = False) -> dict:
+    """Initial parameters, drawn like lm_params."""
+    out = {}
+    for name, shape, kind in encdec_param_shapes(cfg):
+        n = int(np.prod(shape))
+        if kind == "matrix":
+            a = normal(seed, _tid(name), n, cfg.init_std)
+        elif kind == "bias":
+            a = normal(seed, _tid(name), n, cfg.init_std) if perturb else np.zeros(n, np.float32)
+        else:
+            a = np.ones(n, np.float32)
+            if perturb:
+                a = a + normal(seed, _tid(name), n, cfg.init_std)
+        if cfg.bf16:
+            a = round_to_bf16(a)
+        out[name] = a.reshape(shape)
+    return out
+
+
+def encdec_tokens(cfg: EncDecConfig, seed: int = 1234):
+    """(src [batch, src_len], tgt [batch, tgt_len+1]): decoder inputs are tgt columns 0..tgt_len-1, targets
+    columns 1..tgt_len."""
+    return (tokens(seed, _tid("src_tokens"), (cfg.batch, cfg.src_len), cfg.vocab),
+            tokens(seed, _tid("tgt_tokens"), (cfg.batch, cfg.tgt_len + 1), cfg.vocab))
+
+
 def dispatch_input(seed: int = 1234, n: int = 128) -> np.ndarray:
     """x for the dispatch micro-benchmark: fp32 uniform [0, 1)."""
     r = raw_u64(seed, _tid("dispatch_x"), 0, n) >> np.uint64(40)      # 24 bits: exact in fp32, < 1
