@@ -378,6 +378,29 @@ pw_status pw_op_attention_fwd(pw_ctx* ctx, int dtype, const void* qkv, void* o, 
 /* dqkv [B*T, 3d] from qkv, o, dout and lse.  delta: fp32 workspace [B, H, T]. */
 pw_status pw_op_attention_bwd(pw_ctx* ctx, int dtype, const void* qkv, const void* o, const void* dout,
                               const float* lse, float* delta, void* dqkv, int B, int T, int H, int hd);
+/* Multi-head attention of Tq queries over Tk keys per (batch, head), scale 1/sqrt(hd): the encoder's unmasked
+ * self-attention and the decoder's attention over the encoder output of an encoder-decoder model (the
+ * text-to-text Transformers of the paper's Table 1), and - with causal = 1 and the packed layout - the call
+ * above.  q, k, v: device pointers to element (batch 0, row 0, feature 0) of arrays in `dtype`; rows are ldq
+ * (q) and ldkv (k and v) elements apart, batch b starts at row b*Tq (q) or b*Tk (k, v), head h owns features
+ * h*hd .. (h+1)*hd of a row; hd in {64, 128}.  causal = 1: query i sees keys j <= i and Tq must equal Tk.
+ * Nothing is owned or kept; PW_ERR_INVALID on a rejected shape or null pointer. */
+typedef struct {
+  int32_t dtype;
+  const void* q;
+  const void* k;
+  const void* v;
+  int64_t ldq, ldkv;
+  int32_t B, Tq, Tk, H, hd;
+  int32_t causal;
+} pw_mha_args;
+/* o: dense [B*Tq, H*hd] in `dtype`; lse: fp32 [B, H, Tq]. */
+pw_status pw_op_mha_fwd(pw_ctx* ctx, const pw_mha_args* args, void* o, float* lse);
+/* Gradients from o, dout [B*Tq, H*hd] and lse: dq rows lddq elements apart, dk and dv rows lddkv (the H*hd
+ * features of every row are overwritten; packed outputs are pointers into one array).  delta: fp32 workspace
+ * [B, H, Tq]. */
+pw_status pw_op_mha_bwd(pw_ctx* ctx, const pw_mha_args* args, const void* o, const void* dout, const float* lse,
+                        float* delta, void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv);
 /* Mean softmax cross-entropy over N rows of logits z [N, V] in `dtype` against tokens[b*(T+1)+t+1];
  * z is overwritten by dz = (softmax(z) - onehot)/N; loss: one fp32; row_loss: fp32 workspace [N]. */
 pw_status pw_op_softmax_xent(pw_ctx* ctx, int dtype, void* z, const int32_t* tokens, float* loss, float* row_loss,

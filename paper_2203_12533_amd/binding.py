@@ -59,6 +59,13 @@ class GemmArgs(C.Structure):
                 ("C", C.c_void_p), ("C2", C.c_void_p), ("b_colsum", C.c_void_p)]
 
 
+class MhaArgs(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p),
+                ("ldq", C.c_int64), ("ldkv", C.c_int64),
+                ("B", C.c_int32), ("Tq", C.c_int32), ("Tk", C.c_int32), ("H", C.c_int32), ("hd", C.c_int32),
+                ("causal", C.c_int32)]
+
+
 class PwError(RuntimeError):
     def __init__(self, status: int, msg: str):
         super().__init__(f"{STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else status}: {msg}")
@@ -135,6 +142,8 @@ _SIGS = {
     "pw_layernorm_bwd_ws_floats": (C.c_int64, [C.c_int, C.c_int]),
     "pw_op_attention_fwd": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 3 + [C.c_int] * 4),
     "pw_op_attention_bwd": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 6 + [C.c_int] * 4),
+    "pw_op_mha_fwd": (C.c_int, [C.c_void_p] * 4),
+    "pw_op_mha_bwd": (C.c_int, [C.c_void_p] * 7 + [C.c_int64, C.c_void_p, C.c_void_p, C.c_int64]),
     "pw_op_softmax_xent": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 4 + [C.c_int] * 3),
     "pw_op_colsum": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 3 + [C.c_int64] * 2 + [C.c_int]),
     "pw_colsum_ws_floats": (C.c_int64, [C.c_int64, C.c_int64]),
@@ -365,6 +374,13 @@ class Context:
         for k, v in kw.items():
             setattr(a, k, v)
         self._check(lib().pw_op_gemm(self._h, C.byref(a)))
+
+    def mha_fwd(self, args: "MhaArgs", o: int, lse: int):
+        self._check(lib().pw_op_mha_fwd(self._h, C.byref(args), o, lse))
+
+    def mha_bwd(self, args: "MhaArgs", o: int, dout: int, lse: int, delta: int, dq: int, lddq: int, dk: int, dv: int,
+                lddkv: int):
+        self._check(lib().pw_op_mha_bwd(self._h, C.byref(args), o, dout, lse, delta, dq, lddq, dk, dv, lddkv))
 
     def gemm_pair(self, kw0: dict, kw1: dict):
         a0, a1 = GemmArgs(), GemmArgs()

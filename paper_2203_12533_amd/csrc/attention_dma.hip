@@ -13,8 +13,12 @@
 // position c ^ (((r & 3) << 2) | ((r >> 2) & 3)).  16 consecutive (or permuted-within-16) rows of one chunk
 // then hit 16 distinct 16-byte bank groups, and the 4 rows touched by one transposing read fall into 4
 // different 64-byte windows.
-// Rows past the end of the sequence are fetched from the last valid row (always in bounds); every use of
-// such a row is masked (causality) or multiplied by an exact zero (P = exp2(-inf)).
+// Rows past the end of a sequence are fetched from its last valid row (always in bounds); every use of such
+// a row is masked (causality, or the explicit key-index mask of the unmasked variant) or multiplied by an exact
+// zero (P = exp2(-inf)).
+// Queries, keys and values come with their own pointers, row strides and lengths (MhaDev), so one set of kernels
+// serves the packed causal self-attention of a decoder, the unmasked self-attention of an encoder and attention
+// of decoder queries over encoder keys; CAUSAL is a template parameter (it decides which tiles are visited).
 #include "attention_common.hpp"
 #include "common.hpp"
 #include "kernels.hpp"
@@ -28,6 +32,13 @@ constexpr int kNT = 256;                 // 4 waves
 constexpr int kRowBytes = HD * 2;        // 256
 typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef short short4v __attribute__((ext_vector_type(4)));
+
+// q, k, v: element (batch 0, row 0, feature 0); rows ldq / ldkv elements apart; batch b starts at row b*Tq / b*Tk.
+struct MhaDev {
+  const bf16 *q, *k, *v;
+  int64_t ldq, ldkv;
+  int Tq, Tk, H;
+};
 
 __device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 
@@ -122,29 +133,30 @@ __device__ __forceinline__ void wait_and_sync() {
 // ===================================================================================================
 // forward: block = 128 queries of one (batch, head); wave = 32 queries; key/value tiles of 64
 // ===================================================================================================
-__global__ __launch_bounds__(kNT, 2) void attn_fwd_dma_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o,
-                                                              float* __restrict__ lse, int T, int H) {
+template <bool CAUSAL>
+__global__ __launch_bounds__(kNT, 2) void attn_fwd_dma_kernel(MhaDev a, bf16* __restrict__ o, float* __restrict__ lse) {
   constexpr int BKV = 64;
   constexpr int kTile = BKV * HD;                       // elements per K (or V) tile
   extern __shared__ __attribute__((aligned(1024))) bf16 smem[];         // [stage][K | V], 64 KiB
+  const int Tq = a.Tq, Tk = a.Tk, H = a.H;
   const int d = H * HD;
-  const int64_t ld = 3 * (int64_t)d;
-  const int nq = (T + 127) / 128;
+  const int64_t ld = a.ldkv;
+  const int nq = (Tq + 127) / 128;
   int bh, qi;
   xcd_block_map(blockIdx.x, gridDim.x, nq, bh, qi);
   const int b = bh / H, h = bh - b * H;
-  const int qblk = nq - 1 - qi;                         // longest blocks of a problem first
+  const int qblk = CAUSAL ? nq - 1 - qi : qi;           // causal: longest blocks of a problem first
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5;
   const int q0 = qblk * 128 + wave * 32;
   const int query = q0 + (lane & 31);
-  const bf16* qbase = qkv + (int64_t)b * T * ld + h * HD;
-  const bf16* kbase = qbase + d;
-  const bf16* vbase = qbase + 2 * d;
+  const bf16* qbase = a.q + (int64_t)b * Tq * a.ldq + h * HD;
+  const bf16* kbase = a.k + (int64_t)b * Tk * ld + h * HD;
+  const bf16* vbase = a.v + (int64_t)b * Tk * ld + h * HD;
   const float c2 = kLog2e / sqrtf((float)HD);
   const uint32_t smem_off = (uint32_t)(uintptr_t)(lds_ptr)smem;
 
   bf16x8 qf[HD / 16];
-  load_row_frags<HD>(qbase, ld, q0, T, qf);
+  load_row_frags<HD>(qbase, a.ldq, q0, Tq, qf);
   f32x16 acc[HD / 32];
 #pragma unroll
   for (int cb = 0; cb < HD / 32; ++cb)
@@ -152,32 +164,34 @@ __global__ __launch_bounds__(kNT, 2) void attn_fwd_dma_kernel(const bf16* __rest
     for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
   float m = -INFINITY, l = 0.f;
 
-  const int last_q = min(T, (qblk + 1) * 128) - 1;
-  const int n_tiles = last_q / BKV + 1;
+  const int last_q = min(Tq, (qblk + 1) * 128) - 1;
+  const int n_tiles = CAUSAL ? last_q / BKV + 1 : (Tk + BKV - 1) / BKV;
   TileOffsets<BKV> to;
   to.init(ld, wave, lane);
   auto issue = [&](int t) {
     const uint32_t st = smem_off + (uint32_t)(t & 1) * (2 * kTile * 2);
-    issue_tile<BKV>(kbase, ld, t * BKV, T - 1, to, st, wave, lane);
-    issue_tile<BKV>(vbase, ld, t * BKV, T - 1, to, st + kTile * 2, wave, lane);
+    issue_tile<BKV>(kbase, ld, t * BKV, Tk - 1, to, st, wave, lane);
+    issue_tile<BKV>(vbase, ld, t * BKV, Tk - 1, to, st + kTile * 2, wave, lane);
   };
   issue(0);
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = t * BKV;
     wait_and_sync();
     if (t + 1 < n_tiles) issue(t + 1);
-    if (j0 > q0 + 31) continue;   // every key of the tile lies in this wave's future
+    if (CAUSAL && j0 > q0 + 31) continue;   // every key of the tile lies in this wave's future
     const bf16* Ks = smem + (t & 1) * (2 * kTile);
     const bf16* Vs = Ks + kTile;
     f32x16 s[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) s[kb] = first_product(Ks, kb * 32, qf);
-    if (j0 + BKV - 1 > q0) {        // the tile straddles the diagonal for this wave: mask key > query
+    // last visible key of this lane's query: itself (causal), else the last key there is
+    const int last_key = CAUSAL ? query : Tk - 1;
+    if (CAUSAL ? j0 + BKV - 1 > q0 : j0 + BKV > Tk) {   // the tile straddles the diagonal / the end of the keys
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-          if (j0 + kb * 32 + reg_row(r, half) > query) s[kb][r] = -INFINITY;
+          if (j0 + kb * 32 + reg_row(r, half) > last_key) s[kb][r] = -INFINITY;
     }
     float mx = max3(s[0][0], s[1][0], s[0][1]);
 #pragma unroll
@@ -212,67 +226,70 @@ __global__ __launch_bounds__(kNT, 2) void attn_fwd_dma_kernel(const bf16* __rest
       for (int b2 = 0; b2 < 2; ++b2) second_product(Vs, kb * 32 + b2 * 16, pack8(s[kb], b2 * 8), acc);
   }
   l += __shfl_xor(l, 32, 64);
-  if (query < T) {
-    store_row<HD>(o + ((int64_t)b * T + query) * d + h * HD, acc, 1.f / l);
-    if (half == 0) lse[(int64_t)bh * T + query] = (m + __builtin_amdgcn_logf(l)) * kLn2;
+  if (query < Tq) {
+    store_row<HD>(o + ((int64_t)b * Tq + query) * d + h * HD, acc, 1.f / l);
+    if (half == 0) lse[(int64_t)bh * Tq + query] = (m + __builtin_amdgcn_logf(l)) * kLn2;
   }
 }
 
 // ===================================================================================================
 // dQ: same tiling as the forward.  dQ_i = scale * sum_j dS_ij K_j, dS = P (dP - delta)
 // ===================================================================================================
-__global__ __launch_bounds__(kNT, 2) void attn_dq_dma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
+template <bool CAUSAL>
+__global__ __launch_bounds__(kNT, 2) void attn_dq_dma_kernel(MhaDev a, const bf16* __restrict__ dout,
                                                              const float* __restrict__ lse, const float* __restrict__ delta,
-                                                             bf16* __restrict__ dqkv, int T, int H) {
+                                                             bf16* __restrict__ dq, int64_t lddq) {
   constexpr int BKV = 64;
   constexpr int kTile = BKV * HD;
   extern __shared__ __attribute__((aligned(1024))) bf16 smem[];
+  const int Tq = a.Tq, Tk = a.Tk, H = a.H;
   const int d = H * HD;
-  const int64_t ld = 3 * (int64_t)d;
-  const int nq = (T + 127) / 128;
+  const int64_t ld = a.ldkv;
+  const int nq = (Tq + 127) / 128;
   int bh, qi;
   xcd_block_map(blockIdx.x, gridDim.x, nq, bh, qi);
   const int b = bh / H, h = bh - b * H;
-  const int qblk = nq - 1 - qi;
+  const int qblk = CAUSAL ? nq - 1 - qi : qi;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5;
   const int q0 = qblk * 128 + wave * 32;
   const int query = q0 + (lane & 31);
-  const bf16* qbase = qkv + (int64_t)b * T * ld + h * HD;
-  const bf16* kbase = qbase + d;
-  const bf16* vbase = qbase + 2 * d;
+  const bf16* qbase = a.q + (int64_t)b * Tq * a.ldq + h * HD;
+  const bf16* kbase = a.k + (int64_t)b * Tk * ld + h * HD;
+  const bf16* vbase = a.v + (int64_t)b * Tk * ld + h * HD;
   const float scale = 1.f / sqrtf((float)HD);
   const float c2 = kLog2e * scale;
   const uint32_t smem_off = (uint32_t)(uintptr_t)(lds_ptr)smem;
 
   bf16x8 qf[HD / 16], gf[HD / 16];
-  load_row_frags<HD>(qbase, ld, q0, T, qf);
-  load_row_frags<HD>(dout + (int64_t)b * T * d + h * HD, d, q0, T, gf);
-  const float lse2 = query < T ? lse[(int64_t)bh * T + query] * kLog2e : INFINITY;   // +inf: P = 0 for rows past the end
-  const float dl = query < T ? delta[(int64_t)bh * T + query] : 0.f;
+  load_row_frags<HD>(qbase, a.ldq, q0, Tq, qf);
+  load_row_frags<HD>(dout + (int64_t)b * Tq * d + h * HD, d, q0, Tq, gf);
+  const float lse2 = query < Tq ? lse[(int64_t)bh * Tq + query] * kLog2e : INFINITY;   // +inf: P = 0 for rows past the end
+  const float dl = query < Tq ? delta[(int64_t)bh * Tq + query] : 0.f;
   f32x16 acc[HD / 32];
 #pragma unroll
   for (int cb = 0; cb < HD / 32; ++cb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
 
-  const int last_q = min(T, (qblk + 1) * 128) - 1;
-  const int n_tiles = last_q / BKV + 1;
+  const int last_q = min(Tq, (qblk + 1) * 128) - 1;
+  const int n_tiles = CAUSAL ? last_q / BKV + 1 : (Tk + BKV - 1) / BKV;
+  const int last_key = CAUSAL ? query : Tk - 1;
   TileOffsets<BKV> to;
   to.init(ld, wave, lane);
   auto issue = [&](int t) {
     const uint32_t st = smem_off + (uint32_t)(t & 1) * (2 * kTile * 2);
-    issue_tile<BKV>(kbase, ld, t * BKV, T - 1, to, st, wave, lane);
-    issue_tile<BKV>(vbase, ld, t * BKV, T - 1, to, st + kTile * 2, wave, lane);
+    issue_tile<BKV>(kbase, ld, t * BKV, Tk - 1, to, st, wave, lane);
+    issue_tile<BKV>(vbase, ld, t * BKV, Tk - 1, to, st + kTile * 2, wave, lane);
   };
   issue(0);
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = t * BKV;
     wait_and_sync();
     if (t + 1 < n_tiles) issue(t + 1);
-    if (j0 > q0 + 31) continue;
+    if (CAUSAL && j0 > q0 + 31) continue;
     const bf16* Ks = smem + (t & 1) * (2 * kTile);
     const bf16* Vs = Ks + kTile;
-    const bool diag = j0 + BKV - 1 > q0;
+    const bool diag = CAUSAL ? j0 + BKV - 1 > q0 : j0 + BKV > Tk;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       f32x16 s = first_product(Ks, kb * 32, qf);      // S^T
@@ -280,7 +297,7 @@ __global__ __launch_bounds__(kNT, 2) void attn_dq_dma_kernel(const bf16* __restr
       if (diag) {
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-          if (j0 + kb * 32 + reg_row(r, half) > query) s[r] = -INFINITY;
+          if (j0 + kb * 32 + reg_row(r, half) > last_key) s[r] = -INFINITY;
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse2)) * (dp[r] - dl);
@@ -288,37 +305,39 @@ __global__ __launch_bounds__(kNT, 2) void attn_dq_dma_kernel(const bf16* __restr
       for (int b2 = 0; b2 < 2; ++b2) second_product(Ks, kb * 32 + b2 * 16, pack8(s, b2 * 8), acc);   // dQ^T += K^T . dS^T
     }
   }
-  if (query < T) store_row<HD>(dqkv + ((int64_t)b * T + query) * ld + h * HD, acc, scale);
+  if (query < Tq) store_row<HD>(dq + ((int64_t)b * Tq + query) * lddq + h * HD, acc, scale);
 }
 
 // ===================================================================================================
 // dK, dV: block = 128 keys of one (batch, head); wave = 32 keys; query tiles of 64 (two 32-row halves)
 // ===================================================================================================
-__global__ __launch_bounds__(kNT) void attn_dkv_dma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
+template <bool CAUSAL>
+__global__ __launch_bounds__(kNT) void attn_dkv_dma_kernel(MhaDev a, const bf16* __restrict__ dout,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
-                                                           bf16* __restrict__ dqkv, int T, int H) {
+                                                           bf16* __restrict__ dk_out, bf16* __restrict__ dv_out, int64_t lddkv) {
   constexpr int BQ = 64;
   constexpr int kTile = BQ * HD;
   extern __shared__ __attribute__((aligned(1024))) bf16 smem[];          // [stage][Q | dO], then the statistics
   float (*Ls)[BQ] = reinterpret_cast<float (*)[BQ]>(smem + 2 * 2 * kTile);
   float (*Ds)[BQ] = Ls + 2;
+  const int T = a.Tq, Tk = a.Tk, H = a.H;               // T: number of queries (the streamed side)
   const int d = H * HD;
-  const int64_t ld = 3 * (int64_t)d;
-  int bh, kblk;                                         // first key blocks see the most queries: they come first
-  xcd_block_map(blockIdx.x, gridDim.x, (T + 127) / 128, bh, kblk);
+  const int64_t ld = a.ldq;
+  int bh, kblk;                                         // causal: first key blocks see the most queries, they come first
+  xcd_block_map(blockIdx.x, gridDim.x, (Tk + 127) / 128, bh, kblk);
   const int b = bh / H, h = bh - b * H;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5;
   const int k0 = kblk * 128 + wave * 32;
   const int key = k0 + (lane & 31);
-  const bf16* qbase = qkv + (int64_t)b * T * ld + h * HD;
+  const bf16* qbase = a.q + (int64_t)b * T * ld + h * HD;
   const bf16* gbase = dout + (int64_t)b * T * d + h * HD;
   const float scale = 1.f / sqrtf((float)HD);
   const float c2 = kLog2e * scale;
   const uint32_t smem_off = (uint32_t)(uintptr_t)(lds_ptr)smem;
 
   bf16x8 kf[HD / 16], vf[HD / 16];
-  load_row_frags<HD>(qbase + d, ld, k0, T, kf);
-  load_row_frags<HD>(qbase + 2 * d, ld, k0, T, vf);
+  load_row_frags<HD>(a.k + (int64_t)b * Tk * a.ldkv + h * HD, a.ldkv, k0, Tk, kf);
+  load_row_frags<HD>(a.v + (int64_t)b * Tk * a.ldkv + h * HD, a.ldkv, k0, Tk, vf);
   f32x16 dk[HD / 32], dv[HD / 32];
 #pragma unroll
   for (int cb = 0; cb < HD / 32; ++cb)
@@ -328,7 +347,7 @@ __global__ __launch_bounds__(kNT) void attn_dkv_dma_kernel(const bf16* __restric
       dv[cb][r] = 0.f;
     }
 
-  const int first_tile = (kblk * 128) / BQ;
+  const int first_tile = CAUSAL ? (kblk * 128) / BQ : 0;
   const int n_tiles = (T + BQ - 1) / BQ;
   TileOffsets<BQ> to_q, to_g;
   to_q.init(ld, wave, lane);
@@ -366,10 +385,10 @@ __global__ __launch_bounds__(kNT) void attn_dkv_dma_kernel(const bf16* __restric
 #pragma unroll
     for (int hb = 0; hb < 2; ++hb) {                     // the two 32-query halves of the tile
       const int ib = i0 + hb * 32;
-      if (ib + 31 < k0) continue;                        // every query of this half precedes this wave's keys
+      if (CAUSAL && ib + 31 < k0) continue;              // every query of this half precedes this wave's keys
       f32x16 s = first_product(Qs, hb * 32, kf);         // S[query][key]
       f32x16 dp = first_product(Gs, hb * 32, vf);        // dP = dO . V^T
-      if (ib < k0 + 31) {                                // diagonal: a key may not see an earlier query
+      if (CAUSAL && ib < k0 + 31) {                      // diagonal: a key may not see an earlier query
 #pragma unroll
         for (int r = 0; r < 16; ++r)
           if (key > ib + reg_row(r, half)) s[r] = -INFINITY;
@@ -405,10 +424,10 @@ __global__ __launch_bounds__(kNT) void attn_dkv_dma_kernel(const bf16* __restric
       for (int kk = 0; kk < HD / 16; ++kk) asm volatile("" : "+v"(kf[kk]), "+v"(vf[kk]));
     }
   }
-  if (key < T) {
-    bf16* row = dqkv + ((int64_t)b * T + key) * ld + h * HD;
-    store_row<HD>(row + d, dk, scale);
-    store_row<HD>(row + 2 * d, dv, 1.f);
+  if (key < Tk) {
+    const int64_t row = ((int64_t)b * Tk + key) * lddkv + h * HD;
+    store_row<HD>(dk_out + row, dk, scale);
+    store_row<HD>(dv_out + row, dv, 1.f);
   }
 }
 
@@ -417,32 +436,61 @@ __global__ __launch_bounds__(kNT) void attn_dkv_dma_kernel(const bf16* __restric
 constexpr int kSmemTiles = 2 * 2 * 64 * HD * 2;          // two stages of two 64 x 128 bf16 tiles: 64 KiB
 constexpr int kSmemDkv = kSmemTiles + 4 * 64 * 4;        // + log-sum-exp and delta of two query tiles
 
-// Raises the dynamic-LDS limit of the three kernels (once; called at context creation, never inside a capture).
+// Raises the dynamic-LDS limit of the kernels (once; called at context creation, never inside a capture).
 hipError_t attention_dma_init() {
   static bool done = false;
   if (done) return hipSuccess;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd_dma_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kSmemTiles);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_dq_dma_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kSmemTiles);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_dkv_dma_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kSmemDkv);
-  if (e == hipSuccess) done = true;
-  return e;
+  const struct { const void* fn; int bytes; } all[] = {
+      {reinterpret_cast<const void*>(attn_fwd_dma_kernel<true>), kSmemTiles},
+      {reinterpret_cast<const void*>(attn_fwd_dma_kernel<false>), kSmemTiles},
+      {reinterpret_cast<const void*>(attn_dq_dma_kernel<true>), kSmemTiles},
+      {reinterpret_cast<const void*>(attn_dq_dma_kernel<false>), kSmemTiles},
+      {reinterpret_cast<const void*>(attn_dkv_dma_kernel<true>), kSmemDkv},
+      {reinterpret_cast<const void*>(attn_dkv_dma_kernel<false>), kSmemDkv}};
+  for (const auto& k : all) {
+    const hipError_t e = hipFuncSetAttribute(k.fn, hipFuncAttributeMaxDynamicSharedMemorySize, k.bytes);
+    if (e != hipSuccess) return e;
+  }
+  done = true;
+  return hipSuccess;
 }
 
-hipError_t launch_attention_fwd_dma(hipStream_t s, const void* qkv, void* o, float* lse, int B, int T, int H) {
+static MhaDev dev_of(const MhaArgs& a) {
+  return MhaDev{(const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, a.ldq, a.ldkv, a.Tq, a.Tk, a.H};
+}
+
+// Whether the kernels of this file take the problem: bf16, head_dim 128, 16-byte aligned rows.
+bool mha_dma_supported(const MhaArgs& a) {
+  if (a.dtype != kBF16 || a.hd != HD) return false;
+  if (((uintptr_t)a.q | (uintptr_t)a.k | (uintptr_t)a.v) & 15) return false;
+  return a.ldq % 8 == 0 && a.ldkv % 8 == 0;
+}
+
+hipError_t launch_mha_fwd_dma(hipStream_t s, const MhaArgs& a, void* o, float* lse) {
   hipError_t e = attention_dma_init();
   if (e != hipSuccess) return e;
-  const int grid = ((T + 127) / 128) * B * H;          // (problem, block) pairs, see xcd_block_map
-  attn_fwd_dma_kernel<<<grid, kNT, kSmemTiles, s>>>((const bf16*)qkv, (bf16*)o, lse, T, H);
+  const int grid = ((a.Tq + 127) / 128) * a.B * a.H;          // (problem, block) pairs, see xcd_block_map
+  if (a.causal)
+    attn_fwd_dma_kernel<true><<<grid, kNT, kSmemTiles, s>>>(dev_of(a), (bf16*)o, lse);
+  else
+    attn_fwd_dma_kernel<false><<<grid, kNT, kSmemTiles, s>>>(dev_of(a), (bf16*)o, lse);
   return hipGetLastError();
 }
 
-hipError_t launch_attention_dq_dkv_dma(hipStream_t s, const void* qkv, const void* dout, const float* lse,
-                                       const float* delta, void* dqkv, int B, int T, int H) {
+hipError_t launch_mha_dq_dkv_dma(hipStream_t s, const MhaArgs& a, const void* dout, const float* lse, const float* delta,
+                                 void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv) {
   hipError_t e = attention_dma_init();
   if (e != hipSuccess) return e;
-  const int grid = ((T + 127) / 128) * B * H;
-  attn_dq_dma_kernel<<<grid, kNT, kSmemTiles, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
-  attn_dkv_dma_kernel<<<grid, kNT, kSmemDkv, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
+  if ((((uintptr_t)dq | (uintptr_t)dk | (uintptr_t)dv) & 7) || lddq % 4 || lddkv % 4) return hipErrorInvalidValue;
+  const int grid_q = ((a.Tq + 127) / 128) * a.B * a.H, grid_k = ((a.Tk + 127) / 128) * a.B * a.H;
+  const MhaDev dv_ = dev_of(a);
+  if (a.causal) {
+    attn_dq_dma_kernel<true><<<grid_q, kNT, kSmemTiles, s>>>(dv_, (const bf16*)dout, lse, delta, (bf16*)dq, lddq);
+    attn_dkv_dma_kernel<true><<<grid_k, kNT, kSmemDkv, s>>>(dv_, (const bf16*)dout, lse, delta, (bf16*)dk, (bf16*)dv, lddkv);
+  } else {
+    attn_dq_dma_kernel<false><<<grid_q, kNT, kSmemTiles, s>>>(dv_, (const bf16*)dout, lse, delta, (bf16*)dq, lddq);
+    attn_dkv_dma_kernel<false><<<grid_k, kNT, kSmemDkv, s>>>(dv_, (const bf16*)dout, lse, delta, (bf16*)dk, (bf16*)dv, lddkv);
+  }
   return hipGetLastError();
 }
 

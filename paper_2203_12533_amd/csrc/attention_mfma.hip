@@ -425,27 +425,11 @@ __global__ void attn_delta_kernel(const bf16* __restrict__ o, const bf16* __rest
 
 }  // namespace
 
-hipError_t attention_dma_init();
-hipError_t launch_attention_fwd_dma(hipStream_t s, const void* qkv, void* o, float* lse, int B, int T, int H);
-hipError_t launch_attention_dq_dkv_dma(hipStream_t s, const void* qkv, const void* dout, const float* lse, const float* delta,
-                                       void* dqkv, int B, int T, int H);
-
-// head_dim 128 runs the kernels of attention_dma.hip unless PW_ATTN_DMA=0 (A/B switch for measurements).
-static bool use_dma_kernels() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("PW_ATTN_DMA");
-    v = !(e && e[0] == '0');
-  }
-  return v != 0;
-}
-
 bool attention_mfma_supported(int T, int hd) { return T >= 1 && (hd == 64 || hd == 128); }
 
 hipError_t launch_attention_fwd_mfma(hipStream_t s, const void* qkv, void* o, float* lse, int B, int T, int H, int hd) {
   if (!qkv || !o || !lse || B <= 0 || T <= 0 || H <= 0 || (int64_t)B * H > 65535) return hipErrorInvalidValue;
   if (((uintptr_t)qkv | (uintptr_t)o) & 15) return hipErrorInvalidValue;
-  if (hd == 128 && use_dma_kernels()) return launch_attention_fwd_dma(s, qkv, o, lse, B, T, H);
   dim3 grid((T + 127) / 128, B * H);
   if (hd == 128)
     attn_fwd_kernel<128><<<grid, kNT, 0, s>>>((const bf16*)qkv, (bf16*)o, lse, T, H);
@@ -465,12 +449,6 @@ hipError_t launch_attention_bwd_mfma(hipStream_t s, const void* qkv, const void*
   const int64_t rows = (int64_t)B * T * H;
   const int64_t threads = rows * (hd / 8);
   dim3 grid((T + 127) / 128, B * H);
-  if (hd == 128 && use_dma_kernels()) {
-    attn_delta_kernel<128><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>((const bf16*)o, (const bf16*)dout, delta, T, H, rows);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    return launch_attention_dq_dkv_dma(s, qkv, dout, lse, delta, dqkv, B, T, H);
-  }
   if (hd == 128) {
     attn_delta_kernel<128><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>((const bf16*)o, (const bf16*)dout, delta, T, H, rows);
     attn_dq_kernel<128><<<grid, kNT, 0, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
@@ -480,6 +458,14 @@ hipError_t launch_attention_bwd_mfma(hipStream_t s, const void* qkv, const void*
     attn_dq_kernel<64><<<grid, kNT, 0, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
     attn_dkv_kernel<64><<<grid, kNT, 0, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
   }
+  return hipGetLastError();
+}
+
+// delta[b, h, t] = sum_c dO[b*T+t, h*128+c] O[b*T+t, h*128+c] for the head_dim-128 kernels of attention_dma.hip.
+hipError_t launch_attention_delta128(hipStream_t s, const void* o, const void* dout, float* delta, int B, int T, int H) {
+  const int64_t rows = (int64_t)B * T * H;
+  const int64_t threads = rows * (128 / 8);
+  attn_delta_kernel<128><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>((const bf16*)o, (const bf16*)dout, delta, T, H, rows);
   return hipGetLastError();
 }
 

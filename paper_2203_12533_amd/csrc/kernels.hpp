@@ -59,6 +59,24 @@ hipError_t launch_softmax_xent(hipStream_t s, int dtype, void* z, const int32_t*
                                int B, int T, int V);
 
 // attention.hip
+// Multi-head attention of Tq queries over Tk keys per (batch, head), scale 1/sqrt(hd).  q, k, v point at element
+// (batch 0, row 0, feature 0) of arrays in `dtype`; rows are ldq (q) and ldkv (k and v) elements apart, batch b
+// starts at row b*Tq (q) or b*Tk (k, v), head h owns features h*hd .. of a row.  causal: query i sees keys j <= i
+// (needs Tq == Tk).  Packed self-attention is q = qkv, k = qkv + d, v = qkv + 2d, ldq = ldkv = 3d.
+struct MhaArgs {
+  int dtype;
+  const void *q, *k, *v;
+  int64_t ldq, ldkv;
+  int B, Tq, Tk, H, hd;
+  int causal;
+};
+// o: dense [B*Tq, H*hd] in `dtype`; lse: [B, H, Tq] row log-sum-exp (kept for the backward pass).
+hipError_t launch_mha_fwd(hipStream_t s, const MhaArgs& a, void* o, float* lse);
+// dq rows lddq elements apart, dk and dv rows lddkv; delta: [B, H, Tq] scratch.  Every feature of every row of
+// dq, dk, dv is overwritten.
+hipError_t launch_mha_bwd(hipStream_t s, const MhaArgs& a, const void* o, const void* dout, const float* lse,
+                          float* delta, void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv);
+// Causal self-attention over packed qkv [B*T, 3d] (the two calls above with the packed layout).
 hipError_t launch_attention_fwd(hipStream_t s, int dtype, const void* qkv, void* o, float* lse, int B, int T, int H,
                                 int hd);
 hipError_t launch_attention_bwd(hipStream_t s, int dtype, const void* qkv, const void* o, const void* dout,

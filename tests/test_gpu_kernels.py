@@ -214,6 +214,67 @@ def test_attention_forward_backward(ctx, orc, B, T, H, hd, bf16):
         assert rel_l2(got[:, sl], rd[:, sl]) < (1.5e-2 if bf16 else 1e-5), name
 
 
+def _mha_case(ctx, orc, bf16, B, Tq, Tk, H, hd, causal, packed_kv):
+    """General attention against the oracle: q from its own array, k and v either packed [K|V] rows or separate."""
+    d = H * hd
+    es = 2 if bf16 else 4
+    q, qv = dev_act(_rand(32, (B * Tq, d), 1.0), bf16)
+    if packed_kv:
+        kv, kvv = dev_act(_rand(33, (B * Tk, 2 * d), 1.0), bf16)
+        kp, vp, ldkv, kh, vh = ptr(kv), ptr(kv) + d * es, 2 * d, kvv[:, :d], kvv[:, d:]
+    else:
+        k, kh = dev_act(_rand(33, (B * Tk, d), 1.0), bf16)
+        v, vh = dev_act(_rand(34, (B * Tk, d), 1.0), bf16)
+        kp, vp, ldkv = ptr(k), ptr(v), d
+    a = pwb.MhaArgs(DT[bf16], ptr(q), kp, vp, d, ldkv, B, Tq, Tk, H, hd, int(causal))
+    o = empty_act((B * Tq, d), bf16)
+    lse = torch.empty((B, H, Tq), device="cuda")
+    ctx.mha_fwd(a, ptr(o), ptr(lse))
+    ctx.synchronize()
+    ro = orc.mha_fwd(qv, kh, vh, B, Tq, Tk, H, hd, causal=causal)
+    assert rel_l2(host(o), ro) < (6e-3 if bf16 else 1e-5)
+    qr, kr = qv.reshape(B, Tq, H, hd), np.ascontiguousarray(kh).reshape(B, Tk, H, hd)
+    for (b, h, i) in [(0, 0, 0), (B - 1, H - 1, Tq - 1), (0, H - 1, Tq // 2)]:
+        s = kr[b, : (i + 1 if causal else Tk), h] @ qr[b, i, h] / np.sqrt(hd)
+        want = np.log(np.exp(s - s.max()).sum()) + s.max()
+        assert abs(host(lse)[b, h, i] - want) < (2e-2 if bf16 else 1e-4)
+    dout, doutv = dev_act(_rand(35, (B * Tq, d)), bf16)
+    dq = empty_act((B * Tq, d), bf16)
+    dkv = empty_act((B * Tk, 2 * d), bf16)             # gradients always packed [dK|dV] here
+    delta = torch.empty((B, H, Tq), device="cuda")
+    ctx.mha_bwd(a, ptr(o), ptr(dout), ptr(lse), ptr(delta), ptr(dq), d, ptr(dkv), ptr(dkv) + d * es, 2 * d)
+    ctx.synchronize()
+    rdq, rdk, rdv = orc.mha_bwd(qv, kh, vh, doutv, B, Tq, Tk, H, hd, causal=causal)
+    tol = 1.5e-2 if bf16 else 1e-5
+    assert rel_l2(host(dq), rdq) < tol
+    assert rel_l2(host(dkv)[:, :d], rdk) < tol and rel_l2(host(dkv)[:, d:], rdv) < tol
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("B,Tq,Tk,H,hd", [(2, 70, 200, 2, 64), (1, 130, 97, 3, 128), (2, 5, 1, 1, 64), (1, 300, 384, 2, 128),
+                                          (2, 129, 64, 2, 128)])
+def test_unmasked_attention_with_separate_lengths(ctx, orc, B, Tq, Tk, H, hd, bf16):
+    _mha_case(ctx, orc, bf16, B, Tq, Tk, H, hd, causal=False, packed_kv=True)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_general_attention_entry_point_other_layouts(ctx, orc, bf16):
+    _mha_case(ctx, orc, bf16, 2, 150, 150, 2, 128, causal=True, packed_kv=False)    # causal, k and v separate
+    _mha_case(ctx, orc, bf16, 1, 96, 96, 2, 64, causal=False, packed_kv=False)      # encoder self-attention shape
+
+
+def test_general_attention_rejects_bad_arguments(ctx):
+    q = torch.zeros((64, 128), device="cuda")
+    lse = torch.zeros((1, 1, 64), device="cuda")
+    ok = dict(dtype=pwb.PW_F32, q=ptr(q), k=ptr(q), v=ptr(q), ldq=128, ldkv=128, B=1, Tq=64, Tk=64, H=1, hd=128, causal=0)
+    for bad in (dict(hd=96), dict(Tk=0), dict(ldkv=64), dict(causal=1, Tk=32), dict(k=0), dict(dtype=7)):
+        a = pwb.MhaArgs(**{**ok, **bad})
+        with pytest.raises(pwb.PwError):
+            ctx.mha_fwd(a, ptr(q), ptr(lse))
+    ctx.mha_fwd(pwb.MhaArgs(**ok), ptr(q), ptr(lse))
+    ctx.synchronize()
+
+
 # ---- softmax cross-entropy ----------------------------------------------------------------------------
 
 @pytest.mark.parametrize("bf16", [False, True])
