@@ -51,6 +51,7 @@ typedef enum { PW_F32 = 0, PW_BF16 = 1, PW_I32 = 2 } pw_dtype;
 
 typedef struct pw_ctx pw_ctx;       /* device, executor stream, buffer/event pools, handle tables */
 typedef struct pw_model pw_model;   /* LM parameters, optimiser state, activation plan; owned by its ctx */
+typedef struct pw_encdec pw_encdec; /* the same for the encoder-decoder model */
 typedef uint64_t pw_fn;             /* compiled function handle; 0 is never valid */
 typedef uint64_t pw_future;         /* buffer-future handle; 0 is never valid */
 
@@ -74,7 +75,9 @@ typedef enum {
   PW_FN_ADD2 = 6,        /* two inputs of one shape: y = a + b (no params): the fan-in node of dataflow programs */
   PW_FN_LM_TRAIN_STEP = 16, /* in: tokens i32 [B, T+1]; out: loss f32 [1].  params: pw_model*. */
   PW_FN_STAGE_FWD = 17,  /* in: X [N, d]; out: Y [N, d].  params: pw_stage_params */
-  PW_FN_STAGE_BWD = 18   /* in: dY [N, d]; out: dX [N, d]; adds into the stage's weight gradients */
+  PW_FN_STAGE_BWD = 18,  /* in: dY [N, d]; out: dX [N, d]; adds into the stage's weight gradients */
+  PW_FN_ENCDEC_TRAIN_STEP = 19 /* in: source tokens i32 [B, Ts], target tokens i32 [B, Tt+1]; out: loss f32 [1].
+                            params: pw_encdec*. */
 } pw_fn_kind;
 
 typedef struct {
@@ -311,6 +314,36 @@ pw_status pw_model_export_activation(pw_model* m, const char* name, int microbat
 /* Model FLOPs of one step (2 m n k per GEMM, forward + backward; causal attention at half the dense
  * T^2), the figure the throughput is priced against. */
 double pw_model_step_flops(const pw_lm_config* cfg);
+
+/* ---- the encoder-decoder model (the text-to-text Transformers of Table 1) -----------------------
+ * The paper gives neither the layer recipe nor the sizes of these models; this one keeps what defines the
+ * family and builds it from the LM's pieces: encoder layers x += SelfAttn_unmasked(LN x), x += FFN(LN x);
+ * decoder layers y += SelfAttn_causal(LN y), y += Attn(LN y over mem), y += FFN(LN y); mem = LN(encoder
+ * output); logits = LN(decoder output) Wh; mean next-token cross-entropy over the B*Tt target positions.
+ * Encoder and decoder have their own token and position tables. */
+typedef struct {
+  int32_t n_enc_layer, n_dec_layer, d_model, n_head, d_ff, vocab, src_len, tgt_len, batch;
+  int32_t bf16;          /* as in pw_lm_config */
+  int32_t optimizer;     /* 1 SGD, 2 Adam */
+  float lr, beta1, beta2, eps;
+} pw_encdec_config;
+
+/* Allocates parameters (zero), gradients, optimiser state and every activation buffer of the step up front.
+ * d_model % n_head == 0, head_dim in {64, 128}; PW_ERR_UNSUPPORTED otherwise, PW_ERR_OOM if HBM runs out. */
+pw_status pw_encdec_create(pw_ctx* ctx, const pw_encdec_config* cfg, pw_encdec** out);
+pw_status pw_encdec_destroy(pw_encdec* m);
+/* Parameter tensors in the model's own order ("enc.wte", "e0.wqkv", ..., "d0.wkv", ..., "wh"); weights are
+ * [in, out] row-major fp32; wqkv columns are [Q|K|V], wkv columns [K|V]. */
+int64_t pw_encdec_param_count(pw_encdec* m);
+pw_status pw_encdec_param_info(pw_encdec* m, int64_t idx, char* name, int name_cap, int64_t* numel);
+/* As pw_model_import / pw_model_export (part: pw_model_part). */
+pw_status pw_encdec_import(pw_encdec* m, int part, int64_t idx, const float* src, int src_on_device);
+pw_status pw_encdec_export(pw_encdec* m, int part, int64_t idx, float* host_dst);
+/* "dlogits" [B*Tt, V] of the most recent step, as fp32. */
+pw_status pw_encdec_export_activation(pw_encdec* m, const char* name, float* host_dst, int64_t numel);
+/* Model FLOPs of one step (2 m n k per GEMM, forward + backward; attention at the visible part of Tq x Tk). */
+double pw_encdec_step_flops(const pw_encdec_config* cfg);
+/* One train step: pw_run_fn on a function of kind PW_FN_ENCDEC_TRAIN_STEP with the two token arrays. */
 
 /* ---- single kernels, for parity tests and profiling --------------------------------------------
  * All pointers are device pointers; work is enqueued on the executor stream and not waited for.

@@ -23,7 +23,7 @@ PW_F32, PW_BF16, PW_I32 = 0, 1, 2
 PW_FN_ADD_CONST, PW_FN_MUL_CONST, PW_FN_DIV_CONST, PW_FN_BUSY, PW_FN_BUSY_CHAIN, PW_FN_ADD2 = 1, 2, 3, 4, 5, 6
 PW_DISPATCH_PARALLEL, PW_DISPATCH_SEQUENTIAL = 0, 1
 PW_SCHED_FIFO, PW_SCHED_PROPORTIONAL = 0, 1
-PW_FN_LM_TRAIN_STEP, PW_FN_STAGE_FWD, PW_FN_STAGE_BWD = 16, 17, 18
+PW_FN_LM_TRAIN_STEP, PW_FN_STAGE_FWD, PW_FN_STAGE_BWD, PW_FN_ENCDEC_TRAIN_STEP = 16, 17, 18, 19
 PW_STREAM, PW_GRAPH, PW_SEQUENTIAL = 0, 1, 2
 PW_PARAMS, PW_GRADS, PW_ADAM_M, PW_ADAM_V = 0, 1, 2, 3
 PW_EPI_STORE, PW_EPI_BIAS, PW_EPI_BIAS_RESIDUAL, PW_EPI_BIAS_GELU, PW_EPI_GELU_BWD = range(5)
@@ -57,6 +57,12 @@ class GemmArgs(C.Structure):
                 ("epilogue", C.c_int32), ("out_dtype", C.c_int32), ("accumulate", C.c_int32),
                 ("A", C.c_void_p), ("B", C.c_void_p), ("bias", C.c_void_p), ("aux", C.c_void_p),
                 ("C", C.c_void_p), ("C2", C.c_void_p), ("b_colsum", C.c_void_p)]
+
+
+class EncDecConfigC(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_enc_layer", "n_dec_layer", "d_model", "n_head", "d_ff", "vocab", "src_len",
+                                         "tgt_len", "batch", "bf16", "optimizer")] + \
+               [(n, C.c_float) for n in ("lr", "beta1", "beta2", "eps")]
 
 
 class MhaArgs(C.Structure):
@@ -130,6 +136,14 @@ _SIGS = {
     "pw_model_apply_optimizer": (C.c_int, [C.c_void_p]),
     "pw_model_export_activation": (C.c_int, [C.c_void_p, C.c_char_p, C.c_int, C.c_void_p, C.c_int64]),
     "pw_model_step_flops": (C.c_double, [C.POINTER(LMConfigC)]),
+    "pw_encdec_create": (C.c_int, [C.c_void_p, C.POINTER(EncDecConfigC), C.POINTER(C.c_void_p)]),
+    "pw_encdec_destroy": (C.c_int, [C.c_void_p]),
+    "pw_encdec_param_count": (C.c_int64, [C.c_void_p]),
+    "pw_encdec_param_info": (C.c_int, [C.c_void_p, C.c_int64, C.c_char_p, C.c_int, C.POINTER(C.c_int64)]),
+    "pw_encdec_import": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_void_p, C.c_int]),
+    "pw_encdec_export": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_void_p]),
+    "pw_encdec_export_activation": (C.c_int, [C.c_void_p, C.c_char_p, C.c_void_p, C.c_int64]),
+    "pw_encdec_step_flops": (C.c_double, [C.POINTER(EncDecConfigC)]),
     "pw_profile_begin": (C.c_int, [C.c_void_p]),
     "pw_profile_pause": (C.c_int, [C.c_void_p]),
     "pw_profile_end": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
@@ -365,6 +379,9 @@ class Context:
     def model(self, cfg) -> "Model":
         return Model(self, cfg)
 
+    def encdec(self, cfg) -> "EncDec":
+        return EncDec(self, cfg)
+
     # -- single kernels (device pointers as ints)
     def op(self, name: str, *args):
         self._check(getattr(lib(), "pw_op_" + name)(self._h, *args))
@@ -498,6 +515,76 @@ def lm_config_c(cfg) -> LMConfigC:
 def step_flops(cfg) -> float:
     c = lm_config_c(cfg)
     return lib().pw_model_step_flops(C.byref(c))
+
+
+def encdec_config_c(cfg) -> EncDecConfigC:
+    """From the generator module's EncDecConfig (or any object with the same fields)."""
+    return EncDecConfigC(cfg.n_enc_layer, cfg.n_dec_layer, cfg.d_model, cfg.n_head, cfg.d_ff, cfg.vocab, cfg.src_len,
+                         cfg.tgt_len, cfg.batch, int(cfg.bf16), {"sgd": 1, "adam": 2}[cfg.optimizer], cfg.lr, cfg.beta1,
+                         cfg.beta2, cfg.eps)
+
+
+def encdec_step_flops(cfg) -> float:
+    c = encdec_config_c(cfg)
+    return lib().pw_encdec_step_flops(C.byref(c))
+
+
+class EncDec:
+    """pw_encdec: parameters, optimiser state and the static activation plan of one encoder-decoder model."""
+
+    def __init__(self, ctx: "Context", cfg):
+        self.ctx, self.cfg = ctx, cfg
+        self._h = C.c_void_p()
+        c = encdec_config_c(cfg)
+        ctx._check(lib().pw_encdec_create(ctx.handle, C.byref(c), C.byref(self._h)))
+        ctx._models.append(self)
+        self.names, self.numel = [], {}
+        name = C.create_string_buffer(64)
+        n = C.c_int64()
+        for i in range(lib().pw_encdec_param_count(self._h)):
+            lib().pw_encdec_param_info(self._h, i, name, 64, C.byref(n))
+            self.names.append(name.value.decode())
+            self.numel[self.names[-1]] = n.value
+        self._index = {k: i for i, k in enumerate(self.names)}
+
+    def close(self):
+        if self._h is not None:
+            lib().pw_encdec_destroy(self._h)
+            self._h = None
+            if self in self.ctx._models:
+                self.ctx._models.remove(self)
+
+    def import_(self, part: int, name: str, arr: np.ndarray):
+        arr = np.ascontiguousarray(arr, dtype=np.float32)
+        assert arr.size == self.numel[name], (name, arr.size, self.numel[name])
+        self.ctx._check(lib().pw_encdec_import(self._h, part, self._index[name], arr.ctypes.data_as(C.c_void_p), 0))
+
+    def import_device(self, part: int, name: str, ptr: int):
+        self.ctx._check(lib().pw_encdec_import(self._h, part, self._index[name], C.c_void_p(ptr), 1))
+
+    def load_params(self, params: dict):
+        for k in self.names:
+            self.import_(PW_PARAMS, k, params[k])
+
+    def export(self, part: int, name: str, shape=None) -> np.ndarray:
+        out = np.empty(self.numel[name], dtype=np.float32)
+        self.ctx._check(lib().pw_encdec_export(self._h, part, self._index[name], out.ctypes.data_as(C.c_void_p)))
+        return out.reshape(shape) if shape is not None else out
+
+    def export_all(self, part: int, like: dict) -> dict:
+        return {k: self.export(part, k, like[k].shape) for k in self.names}
+
+    def export_activation(self, name: str, numel: int) -> np.ndarray:
+        out = np.empty(numel, dtype=np.float32)
+        self.ctx._check(lib().pw_encdec_export_activation(self._h, name.encode(), out.ctypes.data_as(C.c_void_p), numel))
+        return out
+
+    def compile_train_step(self) -> int:
+        cfg = self.cfg
+        params = C.c_void_p(self._h.value)
+        return self.ctx.compile_fn(PW_FN_ENCDEC_TRAIN_STEP,
+                                   [make_spec(PW_I32, (cfg.batch, cfg.src_len)), make_spec(PW_I32, (cfg.batch, cfg.tgt_len + 1))],
+                                   [make_spec(PW_F32, (1,))], bytes(params))
 
 
 class Model:

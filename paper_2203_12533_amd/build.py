@@ -13,8 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpw.so")
-SOURCES = ["elementwise.hip", "norm.hip", "embed_xent.hip", "attention.hip", "attention_mfma.hip", "attention_dma.hip", "gemm.hip", "gemm_ring.hip",
-           "lm.hip", "runtime.hip"]
+SOURCES = ["model_common.hip", "elementwise.hip", "norm.hip", "embed_xent.hip", "attention.hip", "attention_mfma.hip", "attention_dma.hip", "gemm.hip", "gemm_ring.hip",
+           "lm.hip", "encdec.hip", "runtime.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-result", "-Wno-inline-asm"]
 

@@ -4,20 +4,22 @@
 
 namespace pw {
 
-// Token id of flat position p = b*T + t in the [B, T+1] token array, clamped into [0, V) so that a bad id
+// Token id of flat position p = b*T + t in a token array whose rows are `stride` ids apart (T+1 for the
+// [B, T+1] arrays that carry inputs and next-token targets together), clamped into [0, V) so that a bad id
 // can never index outside the tables (forward and backward clamp identically).
-__device__ __forceinline__ int token_at(const int32_t* __restrict__ tokens, int p, int T, int V, int shift = 0) {
+__device__ __forceinline__ int token_at(const int32_t* __restrict__ tokens, int p, int T, int stride, int V, int shift = 0) {
   const int b = p / T, t = p - b * T;
-  const int id = tokens[(size_t)b * (T + 1) + t + shift];
+  const int id = tokens[(size_t)b * stride + t + shift];
   return id < 0 ? 0 : (id >= V ? V - 1 : id);
 }
 
 // ---- embedding forward: x[b*T+t,:] = wte[tok[b,t],:] + wpe[t,:] (one fp32 add per element: exact) ----
 __global__ void embedding_fwd_kernel(const int32_t* __restrict__ tokens, const float* __restrict__ wte,
-                                     const float* __restrict__ wpe, float* __restrict__ x, int B, int T, int d, int V) {
+                                     const float* __restrict__ wpe, float* __restrict__ x, int B, int T, int d, int V,
+                                     int stride) {
   const int n = blockIdx.x;
   const int t = n % T;
-  const int id = token_at(tokens, n, T, V);
+  const int id = token_at(tokens, n, T, stride, V);
   const float4* we = reinterpret_cast<const float4*>(wte + (size_t)id * d);
   const float4* pe = reinterpret_cast<const float4*>(wpe + (size_t)t * d);
   float4* xo = reinterpret_cast<float4*>(x + (size_t)n * d);
@@ -28,11 +30,13 @@ __global__ void embedding_fwd_kernel(const int32_t* __restrict__ tokens, const f
 }
 
 hipError_t launch_embedding_fwd(hipStream_t s, const int32_t* tokens, const float* wte, const float* wpe, float* x,
-                                int B, int T, int d, int V) {
+                                int B, int T, int d, int V, int tok_stride) {
+  const int stride = tok_stride > 0 ? tok_stride : T + 1;
+  if (stride < T) return hipErrorInvalidValue;
   if (!tokens || !wte || !wpe || !x || B < 0 || T <= 0 || d <= 0 || d % 4 || V <= 0) return hipErrorInvalidValue;
   if (((uintptr_t)wte | (uintptr_t)wpe | (uintptr_t)x) & 15) return hipErrorInvalidValue;
   if (B == 0) return hipSuccess;
-  embedding_fwd_kernel<<<B * T, 256, 0, s>>>(tokens, wte, wpe, x, B, T, d, V);
+  embedding_fwd_kernel<<<B * T, 256, 0, s>>>(tokens, wte, wpe, x, B, T, d, V, stride);
   return hipGetLastError();
 }
 
@@ -46,18 +50,19 @@ constexpr int kEbList = 2048;
 
 __global__ __launch_bounds__(kEbThreads) void embedding_bwd_wte_kernel(const int32_t* __restrict__ tokens,
                                                                        const float* __restrict__ dx,
-                                                                       float* __restrict__ dwte, int B, int T, int d, int V) {
+                                                                       float* __restrict__ dwte, int B, int T, int d, int V,
+                                                                       int stride) {
   __shared__ int list[kEbList];
   __shared__ int wave_cnt[kEbThreads / 64];
   __shared__ int s_found_earlier;
   const int N = B * T;
   const int n = blockIdx.x;
-  const int my = token_at(tokens, n, T, V);
+  const int my = token_at(tokens, n, T, stride, V);
   if (threadIdx.x == 0) s_found_earlier = 0;
   __syncthreads();
   int found = 0;
   for (int p = threadIdx.x; p < n; p += kEbThreads)
-    if (token_at(tokens, p, T, V) == my) found = 1;
+    if (token_at(tokens, p, T, stride, V) == my) found = 1;
   if (found) s_found_earlier = 1;   // benign race: every writer stores 1
   __syncthreads();
   if (s_found_earlier) return;
@@ -75,7 +80,7 @@ __global__ __launch_bounds__(kEbThreads) void embedding_bwd_wte_kernel(const int
     int next_start = N;
     for (int base = start; base < N; base += kEbThreads) {
       const int p = base + threadIdx.x;
-      const bool hit = p < N && token_at(tokens, p, T, V) == my;
+      const bool hit = p < N && token_at(tokens, p, T, stride, V) == my;
       const uint64_t mask = __ballot(hit);
       const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
       if (lane == 0) wave_cnt[w] = __popcll(mask);
@@ -129,14 +134,16 @@ __global__ void embedding_bwd_wpe_kernel(const float* __restrict__ dx, float* __
 }
 
 hipError_t launch_embedding_bwd(hipStream_t s, const int32_t* tokens, const float* dx, float* dwte, float* dwpe,
-                                int B, int T, int d, int V) {
+                                int B, int T, int d, int V, int tok_stride) {
+  const int stride = tok_stride > 0 ? tok_stride : T + 1;
+  if (stride < T) return hipErrorInvalidValue;
   if (!tokens || !dx || !dwte || !dwpe || B < 0 || T <= 0 || d <= 0 || d % 4 || d > kEbThreads * 4 * 8 || V <= 0)
     return hipErrorInvalidValue;
   if (((uintptr_t)dx | (uintptr_t)dwte | (uintptr_t)dwpe) & 15) return hipErrorInvalidValue;
   hipError_t e = launch_fill_f32(s, dwte, (int64_t)V * d, 0.f);
   if (e != hipSuccess) return e;
   if (B == 0) return launch_fill_f32(s, dwpe, (int64_t)T * d, 0.f);
-  embedding_bwd_wte_kernel<<<B * T, kEbThreads, 0, s>>>(tokens, dx, dwte, B, T, d, V);
+  embedding_bwd_wte_kernel<<<B * T, kEbThreads, 0, s>>>(tokens, dx, dwte, B, T, d, V, stride);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   embedding_bwd_wpe_kernel<<<T, 256, 0, s>>>(dx, dwpe, B, T, d);
@@ -181,7 +188,7 @@ __global__ __launch_bounds__(kXeThreads) void softmax_xent_kernel(T* __restrict_
   __shared__ float red[kXeThreads / 64];
   constexpr int W = Vec8<T>::n;
   const int n = blockIdx.x;
-  const int tgt = token_at(tokens, n, T_, V, 1);
+  const int tgt = token_at(tokens, n, T_, T_ + 1, V, 1);
   T* zr = z + (size_t)n * V;
   float m = -INFINITY, l = 0.f;
   for (int c = threadIdx.x * W; c < V; c += kXeThreads * W) {

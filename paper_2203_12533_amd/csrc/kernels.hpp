@@ -51,10 +51,12 @@ hipError_t launch_colsum(hipStream_t s, int dtype, const void* in, float* out, f
                          int accumulate);
 
 // embed_xent.hip
+// tokens: rows tok_stride ids apart, the first T of each row are looked up; tok_stride = 0 means T + 1 (the
+// [B, T+1] arrays that carry inputs and next-token targets together).
 hipError_t launch_embedding_fwd(hipStream_t s, const int32_t* tokens, const float* wte, const float* wpe, float* x,
-                                int B, int T, int d, int V);
+                                int B, int T, int d, int V, int tok_stride = 0);
 hipError_t launch_embedding_bwd(hipStream_t s, const int32_t* tokens, const float* dx, float* dwte, float* dwpe,
-                                int B, int T, int d, int V);
+                                int B, int T, int d, int V, int tok_stride = 0);
 hipError_t launch_softmax_xent(hipStream_t s, int dtype, void* z, const int32_t* tokens, float* loss, float* row_loss,
                                int B, int T, int V);
 

@@ -19,16 +19,9 @@ namespace pw {
 
 namespace {
 
-constexpr int64_t kAlign = 64;   // elements; keeps every tensor 256-byte aligned in fp32 and 128 in bf16
-
-int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
-
 void build_param_table(const pw_lm_config& c, std::vector<ParamInfo>& t, int64_t& total) {
-  int64_t off = 0;
-  auto add = [&](const std::string& n, int64_t numel) {
-    t.push_back({n, off, numel});
-    off += round_up(numel, kAlign);
-  };
+  ParamTableBuilder tb{t};
+  auto add = [&](const std::string& n, int64_t numel) { tb.add(n, numel); };
   const int64_t d = c.d_model, F = c.d_ff, V = c.vocab, T = c.seq;
   if (c.has_embed) {
     add("wte", V * d);
@@ -47,18 +40,8 @@ void build_param_table(const pw_lm_config& c, std::vector<ParamInfo>& t, int64_t
     add("lnf_g", d); add("lnf_b", d);
     add("wh", d * V);
   }
-  total = off;
+  total = tb.off;
 }
-
-struct Carver {
-  size_t off = 0;
-  unsigned char* base = nullptr;
-  template <class T> T* take(size_t bytes) {
-    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
-    off += (bytes + 255) / 256 * 256;
-    return p;
-  }
-};
 
 // Assigns every activation / scratch pointer; with base == nullptr only measures.
 size_t plan(Model* m, unsigned char* base) {
@@ -110,59 +93,7 @@ size_t plan(Model* m, unsigned char* base) {
   return cv.off;
 }
 
-#define PW_TRY(expr, what)                                                        \
-  do {                                                                            \
-    hipError_t e_ = (expr);                                                       \
-    if (e_ != hipSuccess) {                                                       \
-      m->error = std::string(what) + ": " + hipGetErrorString(e_);                \
-      return e_;                                                                  \
-    }                                                                             \
-  } while (0)
-
 const ParamInfo& P(const Model* m, size_t idx) { return m->params[idx]; }
-
-// GEMM helpers in the model's three layouts.  W matrices are [in, out] row-major.
-hipError_t gemm_fwd(Model* m, const void* x, int64_t wi, const float* bias, int64_t N, int64_t in, int64_t out,
-                    int epi, int out_dtype, const void* aux, void* C, void* C2) {
-  GemmArgs a{};
-  a.dtype = m->act_dtype();
-  a.a_kmajor = 0;                      // x [N, in]
-  a.b_kmajor = 1;                      // W [in, out]: stored [k][n]
-  a.M = N; a.N = out; a.K = in; a.lda = in; a.ldb = out; a.ldc = out;
-  a.epilogue = epi; a.out_dtype = out_dtype; a.accumulate = 0;
-  a.A = x;
-  a.B = m->cfg.bf16 ? (const void*)((const uint16_t*)m->wlp + P(m, wi).offset) : (const void*)(m->w + P(m, wi).offset);
-  a.bias = bias; a.aux = aux; a.C = C; a.C2 = C2;
-  return launch_gemm(m->stream, a);
-}
-// dx[N, in] = dy[N, out] . W^T
-hipError_t gemm_dgrad(Model* m, const void* dy, int64_t wi, int64_t N, int64_t in, int64_t out, int epi,
-                      const void* aux, void* C) {
-  GemmArgs a{};
-  a.dtype = m->act_dtype();
-  a.a_kmajor = 0;                      // dy [N, out]
-  a.b_kmajor = 0;                      // W [in, out]: stored [n = in][k = out]
-  a.M = N; a.N = in; a.K = out; a.lda = out; a.ldb = out; a.ldc = in;
-  a.epilogue = epi; a.out_dtype = m->act_dtype(); a.accumulate = 0;
-  a.A = dy;
-  a.B = m->cfg.bf16 ? (const void*)((const uint16_t*)m->wlp + P(m, wi).offset) : (const void*)(m->w + P(m, wi).offset);
-  a.aux = aux; a.C = C;
-  return launch_gemm(m->stream, a);
-}
-// dW[in, out] (=|+=) x^T[in, N] . dy[N, out]
-GemmArgs wgrad_args(Model* m, const void* x, const void* dy, int64_t wi, int64_t N, int64_t in, int64_t out, int accumulate) {
-  GemmArgs a{};
-  a.dtype = m->act_dtype();
-  a.a_kmajor = 1;                      // x [N, in]: stored [k = N][m = in]
-  a.b_kmajor = 1;                      // dy [N, out]: stored [k = N][n = out]
-  a.M = in; a.N = out; a.K = N; a.lda = in; a.ldb = out; a.ldc = out;
-  a.epilogue = kEpiStore; a.out_dtype = kF32; a.accumulate = accumulate;
-  a.A = x; a.B = dy; a.C = m->g + P(m, wi).offset;
-  return a;
-}
-hipError_t gemm_wgrad(Model* m, const void* x, const void* dy, int64_t wi, int64_t N, int64_t in, int64_t out, int accumulate) {
-  return launch_gemm(m->stream, wgrad_args(m, x, dy, wi, N, in, out, accumulate));
-}
 
 size_t layer_base(const Model* m, int l) { return (m->cfg.has_embed ? 2 : 0) + (size_t)l * 12; }
 
@@ -200,24 +131,14 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
     const size_t e = layer_base(m, l);
     const void* dx_op = c.bf16 ? m->dx_lp : (const void*)m->dx_a;
     // FFN2: x_out = x_mid + h W2 + b2
-    PW_TRY(gemm_wgrad(m, A.h, dx_op, e + 10, N, F, d, accumulate), "ffn2 wgrad");
+    PW_TRY(launch_gemm(m->stream, wgrad_args(m, A.h, dx_op, e + 10, N, F, d, accumulate)), "ffn2 wgrad");
     if (l == c.n_layer - 1 && !top_b2_done)
       PW_TRY(launch_colsum(m->stream, kF32, m->dx_a, g + P(m, e + 11).offset, m->ws, N, d, accumulate), "b2 grad");
-    PW_TRY(gemm_dgrad(m, dx_op, e + 10, N, F, d, kEpiGeluBwd, A.u, m->d_big), "ffn2 dgrad + gelu'");
+    PW_TRY(gemm_dgrad(m, dx_op, e + 10, N, F, d, kEpiGeluBwd, A.u, m->d_big, dt, 0), "ffn2 dgrad + gelu'");
     // FFN1: u = m W1 + b1
-    {
-      // b1 gradient = column sums of d_big: delivered by the weight-gradient GEMM where that is free
-      GemmArgs wa = wgrad_args(m, A.mm, m->d_big, e + 8, N, d, F, accumulate);
-      wa.b_colsum = g + P(m, e + 9).offset;
-      if (gemm_colsum_fusable(wa, false)) {
-        PW_TRY(launch_gemm(m->stream, wa), "ffn1 wgrad + b1 grad");
-      } else {
-        wa.b_colsum = nullptr;
-        PW_TRY(launch_gemm(m->stream, wa), "ffn1 wgrad");
-        PW_TRY(launch_colsum(m->stream, dt, m->d_big, g + P(m, e + 9).offset, m->ws, N, F, accumulate), "b1 grad");
-      }
-    }
-    PW_TRY(gemm_dgrad(m, m->d_big, e + 8, N, d, F, kEpiStore, nullptr, m->d_small), "ffn1 dgrad");
+    // (b1 gradient = column sums of d_big: delivered by the weight-gradient GEMM where that is free)
+    PW_TRY(gemm_wgrad_bias(m, A.mm, m->d_big, e + 8, e + 9, N, d, F, accumulate, m->ws), "ffn1 wgrad + b1 grad");
+    PW_TRY(gemm_dgrad(m, m->d_big, e + 8, N, d, F, kEpiStore, nullptr, m->d_small, dt, 0), "ffn1 dgrad");
     // LN2 and the residual branch: dx_b = dx_a + LN2'(d_small)
     PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_mid, m->w + P(m, e + 6).offset, A.mean2, A.rstd2, m->dx_a,
                                 m->dx_b, c.bf16 ? m->dx_lp : nullptr, g + P(m, e + 6).offset, g + P(m, e + 7).offset,
@@ -226,24 +147,15 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
     // out-proj: x_mid = x_in + o Wo + bo
     // (its weight gradient is computed together with the QKV one below: neither fills the chip alone)
     const void* dy_out = dx_op;
-    PW_TRY(gemm_dgrad(m, dx_op, e + 4, N, d, d, kEpiStore, nullptr, m->d_small), "out-proj dgrad");
+    PW_TRY(gemm_dgrad(m, dx_op, e + 4, N, d, d, kEpiStore, nullptr, m->d_small, dt, 0), "out-proj dgrad");
     PW_TRY(launch_attention_bwd(m->stream, dt, A.qkv, A.o, m->d_small, A.lse, m->delta, m->d_qkv, c.batch, c.seq,
                                 c.n_head, m->hd()), "attention bwd");
     // QKV: qkv = a Wqkv + bqkv
     // (dy_out, the bf16 residual gradient, stays intact until the LN1 backward below rewrites it)
-    {
-      GemmArgs wq = wgrad_args(m, A.a, m->d_qkv, e + 2, N, d, 3 * d, accumulate);
-      const GemmArgs wo = wgrad_args(m, A.o, dy_out, e + 4, N, d, d, accumulate);
-      wq.b_colsum = g + P(m, e + 3).offset;   // bqkv gradient = column sums of d_qkv
-      if (gemm_colsum_fusable(wq, gemm_pair_shares_launch(wq, wo))) {
-        PW_TRY(launch_gemm_pair(m->stream, wq, wo), "qkv + out-proj wgrad + bqkv grad");
-      } else {
-        wq.b_colsum = nullptr;
-        PW_TRY(launch_gemm_pair(m->stream, wq, wo), "qkv + out-proj wgrad");
-        PW_TRY(launch_colsum(m->stream, dt, m->d_qkv, g + P(m, e + 3).offset, m->ws, N, 3 * d, accumulate), "bqkv grad");
-      }
-    }
-    PW_TRY(gemm_dgrad(m, m->d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small), "qkv dgrad");
+    PW_TRY(gemm_wgrad_pair_bias(m, wgrad_args(m, A.a, m->d_qkv, e + 2, N, d, 3 * d, accumulate), e + 3, m->d_qkv, N, 3 * d,
+                                wgrad_args(m, A.o, dy_out, e + 4, N, d, d, accumulate), accumulate, m->ws),
+           "qkv + out-proj wgrad + bqkv grad");
+    PW_TRY(gemm_dgrad(m, m->d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small, dt, 0), "qkv dgrad");
     // LN1 and the residual branch: dx_a = dx_b + LN1'(d_small)
     PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->w + P(m, e).offset, A.mean1, A.rstd1, m->dx_b,
                                 m->dx_a, c.bf16 ? m->dx_lp : nullptr, g + P(m, e).offset, g + P(m, e + 1).offset,
@@ -286,49 +198,32 @@ hipError_t model_create(const pw_lm_config& cfg, hipStream_t stream, Model** out
   Model* m = new Model();
   m->cfg = cfg;
   m->stream = stream;
+  m->bf16 = cfg.bf16 ? 1 : 0;
   build_param_table(cfg, m->params, m->total);
-  auto fail = [&](hipError_t e, const char* what) {
-    if (err) *err = std::string(what) + ": " + hipGetErrorString(e);
+  hipError_t e = model_state_alloc(m, cfg.optimizer, err);
+  if (e != hipSuccess) {
+    delete m;
+    return e;
+  }
+  m->act_bytes = plan(m, nullptr);
+  if ((e = hipMalloc(&m->act, m->act_bytes)) != hipSuccess) {
+    if (err) *err = std::string("alloc activations: ") + hipGetErrorString(e);
     model_destroy(m);
     return e;
-  };
-  hipError_t e;
-  const size_t bytes = (size_t)m->total * 4;
-  if ((e = hipMalloc(&m->w, bytes)) != hipSuccess) return fail(e, "alloc params");
-  if ((e = hipMalloc(&m->g, bytes)) != hipSuccess) return fail(e, "alloc grads");
-  if (cfg.optimizer == 2) {
-    if ((e = hipMalloc(&m->m, bytes)) != hipSuccess) return fail(e, "alloc adam m");
-    if ((e = hipMalloc(&m->v, bytes)) != hipSuccess) return fail(e, "alloc adam v");
   }
-  if (cfg.bf16 && (e = hipMalloc(&m->wlp, (size_t)m->total * 2)) != hipSuccess) return fail(e, "alloc bf16 weights");
-  if ((e = hipMalloc(&m->step_dev, 256)) != hipSuccess) return fail(e, "alloc step counter");
-  m->act_bytes = plan(m, nullptr);
-  if ((e = hipMalloc(&m->act, m->act_bytes)) != hipSuccess) return fail(e, "alloc activations");
   plan(m, m->act);
-  // zero everything that is read before it is written
-  if ((e = launch_fill_f32(stream, m->w, m->total, 0.f)) != hipSuccess) return fail(e, "zero params");
-  if ((e = launch_fill_f32(stream, m->g, m->total, 0.f)) != hipSuccess) return fail(e, "zero grads");
-  if (m->m && (e = launch_fill_f32(stream, m->m, m->total, 0.f)) != hipSuccess) return fail(e, "zero m");
-  if (m->v && (e = launch_fill_f32(stream, m->v, m->total, 0.f)) != hipSuccess) return fail(e, "zero v");
-  if (m->wlp && (e = launch_f32_to_bf16(stream, m->w, m->wlp, m->total)) != hipSuccess) return fail(e, "zero bf16 weights");
-  const int one = 1;
-  if ((e = hipMemcpyAsync(m->step_dev, &one, sizeof(int), hipMemcpyHostToDevice, stream)) != hipSuccess) return fail(e, "init step");
-  if ((e = hipStreamSynchronize(stream)) != hipSuccess) return fail(e, "sync");
   *out = m;
   return hipSuccess;
 }
 
 void model_destroy(Model* m) {
   if (!m) return;
-  (void)hipFree(m->w); (void)hipFree(m->g); (void)hipFree(m->m); (void)hipFree(m->v);
-  (void)hipFree(m->wlp); (void)hipFree(m->step_dev); (void)hipFree(m->act);
+  model_state_free(m);
+  (void)hipFree(m->act);
   delete m;
 }
 
-hipError_t model_refresh_lowp(Model* m, int64_t offset, int64_t numel) {
-  if (!m->wlp) return hipSuccess;
-  return launch_f32_to_bf16(m->stream, m->w + offset, (uint16_t*)m->wlp + offset, numel);
-}
+hipError_t model_refresh_lowp(Model* m, int64_t offset, int64_t numel) { return model_state_refresh_lowp(m, offset, numel); }
 
 hipError_t model_zero_grads(Model* m) {
   PW_TRY(launch_fill_f32(m->stream, m->g, m->total, 0.f), "zero grads");
@@ -337,14 +232,7 @@ hipError_t model_zero_grads(Model* m) {
 
 hipError_t model_apply_optimizer(Model* m) {
   const pw_lm_config& c = m->cfg;
-  if (c.optimizer == 1) {
-    PW_TRY(launch_sgd(m->stream, m->w, m->g, m->total, c.lr), "sgd");
-    if (m->wlp) PW_TRY(launch_f32_to_bf16(m->stream, m->w, m->wlp, m->total), "refresh bf16 weights");
-  } else {
-    PW_TRY(launch_adam(m->stream, m->w, m->m, m->v, m->g, m->wlp, m->total, c.lr, c.beta1, c.beta2, c.eps, 0, m->step_dev), "adam");
-    PW_TRY(launch_increment(m->stream, m->step_dev), "step counter");
-  }
-  return hipSuccess;
+  return model_state_apply_optimizer(m, OptimizerConfig{c.optimizer, c.lr, c.beta1, c.beta2, c.eps});
 }
 
 hipError_t model_train_step(Model* m, const int32_t* tokens, float* loss) {
@@ -364,8 +252,8 @@ hipError_t model_train_step(Model* m, const int32_t* tokens, float* loss) {
   PW_TRY(gemm_fwd(m, m->y, tail + 2, nullptr, N, d, V, kEpiStore, dt, nullptr, m->logits, nullptr), "head gemm");
   PW_TRY(launch_softmax_xent(m->stream, dt, m->logits, tokens, loss, m->row_loss, c.batch, c.seq, V), "softmax-xent");
   // head backward: logits now hold dlogits
-  PW_TRY(gemm_wgrad(m, m->y, m->logits, tail + 2, N, d, V, 0), "head wgrad");
-  PW_TRY(gemm_dgrad(m, m->logits, tail + 2, N, d, V, kEpiStore, nullptr, m->d_small), "head dgrad");
+  PW_TRY(launch_gemm(m->stream, wgrad_args(m, m->y, m->logits, tail + 2, N, d, V, 0)), "head wgrad");
+  PW_TRY(gemm_dgrad(m, m->logits, tail + 2, N, d, V, kEpiStore, nullptr, m->d_small, dt, 0), "head dgrad");
   PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, s.x_out, m->w + P(m, tail).offset, m->meanf, m->rstdf, nullptr, m->dx_a,
                               c.bf16 ? m->dx_lp : nullptr, m->g + P(m, tail).offset, m->g + P(m, tail + 1).offset,
                               c.n_layer > 0 ? m->g + P(m, layer_base(m, c.n_layer - 1) + 11).offset : nullptr, m->ws, N, d, 0), "lnf bwd");

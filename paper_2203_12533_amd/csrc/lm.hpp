@@ -7,28 +7,12 @@
 #include <vector>
 
 #include "../../include/pw.h"
+#include "model_common.hpp"
 
 namespace pw {
 
-struct ParamInfo {
-  std::string name;
-  int64_t offset, numel;
-};
-
-struct Model {
+struct Model : ModelBase {
   pw_lm_config cfg;
-  hipStream_t stream;
-  std::string error;
-
-  // parameters and optimiser state: flat fp32 arenas with one shared offset table
-  std::vector<ParamInfo> params;
-  int64_t total = 0;
-  float* w = nullptr;
-  float* g = nullptr;
-  float* m = nullptr;
-  float* v = nullptr;
-  void* wlp = nullptr;        // bf16 compute copy of w (bf16 mode only)
-  int* step_dev = nullptr;    // Adam step number, on the device so that captured graphs stay valid
 
   // activations: one allocation, carved by plan()
   unsigned char* act = nullptr;
@@ -52,7 +36,6 @@ struct Model {
 
   int N() const { return cfg.batch * cfg.seq; }
   int hd() const { return cfg.d_model / cfg.n_head; }
-  int act_dtype() const { return cfg.bf16 ? 1 : 0; }
 };
 
 // Each returns a hipError_t; on failure `model->error` says which launch was rejected.

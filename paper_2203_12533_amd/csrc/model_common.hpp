@@ -1,0 +1,104 @@
+// What the train-step models (lm.hip, encdec.hip) share: the flat parameter / gradient / optimiser-state arenas
+// with their offset table, the carving of one activation allocation, and the three GEMM layouts of a linear
+// layer (forward, input gradient, weight gradient).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "kernels.hpp"
+
+namespace pw {
+
+struct ParamInfo {
+  std::string name;
+  int64_t offset, numel;
+};
+
+struct OptimizerConfig {
+  int kind;   // 1 SGD, 2 Adam
+  float lr, beta1, beta2, eps;
+};
+
+struct ModelBase {
+  hipStream_t stream = nullptr;
+  std::string error;
+  int bf16 = 0;               // 1: bf16 GEMM/attention operands, fp32 accumulation and master weights
+
+  // parameters and optimiser state: flat fp32 arenas with one shared offset table
+  std::vector<ParamInfo> params;
+  int64_t total = 0;
+  float* w = nullptr;
+  float* g = nullptr;
+  float* m = nullptr;
+  float* v = nullptr;
+  void* wlp = nullptr;        // bf16 compute copy of w (bf16 mode only)
+  int* step_dev = nullptr;    // Adam step number, on the device so that captured graphs stay valid
+
+  int act_dtype() const { return bf16 ? kBF16 : kF32; }
+  const ParamInfo& P(size_t idx) const { return params[idx]; }
+  float* wp(size_t idx) const { return w + params[idx].offset; }
+  float* gp(size_t idx) const { return g + params[idx].offset; }
+};
+
+constexpr int64_t kParamAlign = 64;   // elements; keeps every tensor 256-byte aligned in fp32 and 128 in bf16
+
+// Appends to the offset table.
+struct ParamTableBuilder {
+  std::vector<ParamInfo>& t;
+  int64_t off = 0;
+  void add(const std::string& n, int64_t numel) {
+    t.push_back({n, off, numel});
+    off += (numel + kParamAlign - 1) / kParamAlign * kParamAlign;
+  }
+};
+
+// Hands out 256-byte aligned pieces of one allocation; with base == nullptr it only measures.
+struct Carver {
+  size_t off = 0;
+  unsigned char* base = nullptr;
+  template <class T> T* take(size_t bytes) {
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += (bytes + 255) / 256 * 256;
+    return p;
+  }
+};
+
+#define PW_TRY(expr, what)                                                        \
+  do {                                                                            \
+    hipError_t e_ = (expr);                                                       \
+    if (e_ != hipSuccess) {                                                       \
+      m->error = std::string(what) + ": " + hipGetErrorString(e_);                \
+      return e_;                                                                  \
+    }                                                                             \
+  } while (0)
+
+// Allocates and zeroes w, g, (m, v), (wlp) and the step counter for m->total elements; on failure frees what
+// it allocated and says what failed in *err.
+hipError_t model_state_alloc(ModelBase* m, int optimizer, std::string* err);
+void model_state_free(ModelBase* m);
+hipError_t model_state_refresh_lowp(ModelBase* m, int64_t offset, int64_t numel);
+hipError_t model_state_apply_optimizer(ModelBase* m, const OptimizerConfig& o);
+
+// GEMMs of a linear layer y = x W + b with W [in, out] row-major (parameter index wi).
+// y[N, out] = x[N, in] . W with a fused epilogue.
+hipError_t gemm_fwd(ModelBase* m, const void* x, int64_t wi, const float* bias, int64_t N, int64_t in, int64_t out,
+                    int epi, int out_dtype, const void* aux, void* C, void* C2);
+// dx[N, in] (=|+=) dy[N, out] . W^T; out_dtype kF32 is needed for accumulate = 1.
+hipError_t gemm_dgrad(ModelBase* m, const void* dy, int64_t wi, int64_t N, int64_t in, int64_t out, int epi,
+                      const void* aux, void* C, int out_dtype, int accumulate);
+// dW[in, out] (=|+=) x^T[in, N] . dy[N, out], into the gradient arena.
+GemmArgs wgrad_args(ModelBase* m, const void* x, const void* dy, int64_t wi, int64_t N, int64_t in, int64_t out,
+                    int accumulate);
+// Weight gradient plus the bias gradient db (= column sums of dy): fused into the GEMM where that is free,
+// a separate column-sum launch otherwise.  ws: workspace of colsum_ws_floats(N, out) floats.
+hipError_t gemm_wgrad_bias(ModelBase* m, const void* x, const void* dy, int64_t wi, int64_t bi, int64_t N, int64_t in,
+                           int64_t out, int accumulate, float* ws);
+// Two weight gradients in one launch where that fills the chip better; the first one also delivers its bias
+// gradient (parameter bi0) as above.
+hipError_t gemm_wgrad_pair_bias(ModelBase* m, const GemmArgs& w0, int64_t bi0, const void* dy0, int64_t N, int64_t out0,
+                                const GemmArgs& w1, int accumulate, float* ws);
+
+}  // namespace pw

@@ -35,6 +35,7 @@
 
 #include "../../include/pw.h"
 #include "kernels.hpp"
+#include "encdec.hpp"
 #include "lm.hpp"
 
 using namespace pw;
@@ -94,6 +95,7 @@ struct FnRec {
   float cst = 0.f, busy_us = 0.f;
   int reps = 1;
   Model* model = nullptr;
+  EncDec* encdec = nullptr;
   int microbatch = 0;
 };
 
@@ -148,6 +150,7 @@ struct pw_ctx {
   std::vector<uint32_t> free_futures;
   std::vector<FnRec> fns;
   std::vector<Model*> models;
+  std::vector<EncDec*> encdecs;
   int64_t live_futures = 0;
   uint64_t current_owner = 0;    // label given to futures created from now on
   int64_t memory_limit = 0;      // bytes the pool may have handed out at once; 0: no limit
@@ -181,6 +184,10 @@ struct pw_ctx {
 struct pw_model {
   pw_ctx* ctx;
   Model* impl;
+};
+struct pw_encdec {
+  pw_ctx* ctx;
+  EncDec* impl;
 };
 
 // ---- traced dataflow programs (Section 3) ---------------------------------------------------------------
@@ -406,6 +413,11 @@ pw_status fn_launch(pw_ctx* c, FnRec* fn, void* const* in, void* const* out) {
     if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "add2 launch: %s", hipGetErrorString(e));
     return PW_OK;
   }
+  if (k == PW_FN_ENCDEC_TRAIN_STEP) {
+    hipError_t e = encdec_train_step(fn->encdec, (const int32_t*)in[0], (const int32_t*)in[1], (float*)out[0]);
+    if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "%s", fn->encdec->error.c_str());
+    return PW_OK;
+  }
   hipError_t e = hipErrorInvalidValue;
   if (k == PW_FN_LM_TRAIN_STEP) e = model_train_step(fn->model, (const int32_t*)in[0], (float*)out[0]);
   if (k == PW_FN_STAGE_FWD) e = model_stage_fwd(fn->model, fn->microbatch, (const float*)in[0], (float*)out[0]);
@@ -437,6 +449,11 @@ pw_status wait_inputs(pw_ctx* c, FutureRec* const* in, int n_in, std::vector<std
 
 bool model_alive(pw_ctx* c, Model* m) {
   for (Model* x : c->models)
+    if (x == m) return true;
+  return false;
+}
+bool encdec_alive(pw_ctx* c, EncDec* m) {
+  for (EncDec* x : c->encdecs)
     if (x == m) return true;
   return false;
 }
@@ -556,6 +573,7 @@ pw_status pw_ctx_destroy(pw_ctx* c) {
     if (kv.second.graph) (void)hipGraphDestroy(kv.second.graph);
   }
   for (Model* m : c->models) model_destroy(m);
+  for (EncDec* m : c->encdecs) encdec_destroy(m);
   for (auto& f : c->futures) {
     if (!f.live) continue;
     if (f.owns && f.buf) (void)hipFree(f.buf);
@@ -704,6 +722,21 @@ pw_status pw_compile_fn(pw_ctx* c, const pw_fn_desc* d, pw_fn* out) {
       want_out = want_in;
     }
     pw_status st = spec_match(d->in[0], want_in);
+    if (st != PW_OK) return fail(c, st, "input signature does not fit the model");
+    st = spec_match(d->out[0], want_out);
+    if (st != PW_OK) return fail(c, st, "output signature does not fit the model");
+  } else if (k == PW_FN_ENCDEC_TRAIN_STEP) {
+    pw_encdec* pm = nullptr;
+    if (!d->params || d->params_bytes != sizeof(pw_encdec*)) return fail(c, PW_ERR_INVALID, "params must hold a pw_encdec*");
+    std::memcpy(&pm, d->params, sizeof pm);
+    if (!pm || pm->ctx != c || !encdec_alive(c, pm->impl)) return fail(c, PW_ERR_INVALID, "model does not belong to this context");
+    fn.encdec = pm->impl;
+    const pw_encdec_config& cfg = fn.encdec->cfg;
+    if (d->n_in != 2 || d->n_out != 1) return fail(c, PW_ERR_SHAPE, "two inputs (source, target tokens) and one output expected");
+    const pw_tensor_spec want_src{PW_I32, 2, {cfg.batch, cfg.src_len, 0, 0}}, want_tgt{PW_I32, 2, {cfg.batch, cfg.tgt_len + 1, 0, 0}};
+    const pw_tensor_spec want_out{PW_F32, 1, {1, 0, 0, 0}};
+    pw_status st = spec_match(d->in[0], want_src);
+    if (st == PW_OK) st = spec_match(d->in[1], want_tgt);
     if (st != PW_OK) return fail(c, st, "input signature does not fit the model");
     st = spec_match(d->out[0], want_out);
     if (st != PW_OK) return fail(c, st, "output signature does not fit the model");
@@ -1794,7 +1827,7 @@ pw_status pw_model_param_info(pw_model* pm, int64_t idx, char* name, int cap, in
   return PW_OK;
 }
 
-static float* part_base(Model* m, int part) {
+static float* part_base(ModelBase* m, int part) {
   switch (part) {
     case PW_PARAMS: return m->w;
     case PW_GRADS: return m->g;
@@ -1875,6 +1908,98 @@ pw_status pw_model_export_activation(pw_model* pm, const char* name, int mb, flo
 }
 
 double pw_model_step_flops(const pw_lm_config* cfg) { return cfg ? model_step_flops(*cfg) : 0.0; }
+
+// ---- encoder-decoder model -------------------------------------------------------------------------------
+
+pw_status pw_encdec_create(pw_ctx* c, const pw_encdec_config* cfg, pw_encdec** out) {
+  if (!c || !cfg || !out) return PW_ERR_INVALID;
+  std::string why;
+  if (!encdec_config_ok(*cfg, &why)) return fail(c, PW_ERR_UNSUPPORTED, "%s", why.c_str());
+  EncDec* m = nullptr;
+  hipError_t e = encdec_create(*cfg, c->exec, &m, &why);
+  if (e != hipSuccess) return fail(c, e == hipErrorOutOfMemory ? PW_ERR_OOM : PW_ERR_DEVICE, "%s", why.c_str());
+  c->encdecs.push_back(m);
+  *out = new pw_encdec{c, m};
+  return PW_OK;
+}
+
+pw_status pw_encdec_destroy(pw_encdec* pm) {
+  if (!pm) return PW_ERR_INVALID;
+  pw_ctx* c = pm->ctx;
+  (void)hipStreamSynchronize(c->exec);
+  for (size_t i = 0; i < c->encdecs.size(); ++i)
+    if (c->encdecs[i] == pm->impl) {
+      c->encdecs.erase(c->encdecs.begin() + i);
+      encdec_destroy(pm->impl);
+      break;
+    }
+  for (auto& f : c->fns)
+    if (f.live && f.encdec == pm->impl) f.live = false;   // functions of a dead model die with it
+  delete pm;
+  return PW_OK;
+}
+
+int64_t pw_encdec_param_count(pw_encdec* pm) { return pm ? (int64_t)pm->impl->params.size() : -1; }
+
+pw_status pw_encdec_param_info(pw_encdec* pm, int64_t idx, char* name, int cap, int64_t* numel) {
+  if (!pm || idx < 0 || idx >= (int64_t)pm->impl->params.size()) return PW_ERR_INVALID;
+  const ParamInfo& p = pm->impl->params[idx];
+  if (name && cap > 0) snprintf(name, cap, "%s", p.name.c_str());
+  if (numel) *numel = p.numel;
+  return PW_OK;
+}
+
+pw_status pw_encdec_import(pw_encdec* pm, int part, int64_t idx, const float* src, int src_on_device) {
+  if (!pm || !src || idx < 0 || idx >= (int64_t)pm->impl->params.size()) return PW_ERR_INVALID;
+  pw_ctx* c = pm->ctx;
+  EncDec* m = pm->impl;
+  float* base = part_base(m, part);
+  if (!base) return fail(c, PW_ERR_INVALID, "this model has no such part");
+  const ParamInfo& p = m->params[idx];
+  PW_HIP(c, hipMemcpyAsync(base + p.offset, src, (size_t)p.numel * 4, src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, c->exec));
+  if (part == PW_PARAMS) {
+    hipError_t e = model_state_refresh_lowp(m, p.offset, p.numel);
+    if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "bf16 refresh: %s", hipGetErrorString(e));
+  }
+  PW_HIP(c, hipStreamSynchronize(c->exec));
+  return PW_OK;
+}
+
+pw_status pw_encdec_export(pw_encdec* pm, int part, int64_t idx, float* dst) {
+  if (!pm || !dst || idx < 0 || idx >= (int64_t)pm->impl->params.size()) return PW_ERR_INVALID;
+  pw_ctx* c = pm->ctx;
+  EncDec* m = pm->impl;
+  float* base = part_base(m, part);
+  if (!base) return fail(c, PW_ERR_INVALID, "this model has no such part");
+  const ParamInfo& p = m->params[idx];
+  PW_HIP(c, hipStreamSynchronize(c->exec));
+  PW_HIP(c, hipMemcpy(dst, base + p.offset, (size_t)p.numel * 4, hipMemcpyDeviceToHost));
+  return PW_OK;
+}
+
+pw_status pw_encdec_export_activation(pw_encdec* pm, const char* name, float* dst, int64_t numel) {
+  if (!pm || !name || !dst) return PW_ERR_INVALID;
+  pw_ctx* c = pm->ctx;
+  EncDec* m = pm->impl;
+  if (std::string(name) != "dlogits") return fail(c, PW_ERR_INVALID, "unknown activation name");
+  const int64_t n = (int64_t)m->Nt() * m->cfg.vocab;
+  if (numel != n) return fail(c, PW_ERR_SHAPE, "activation has %lld elements", (long long)n);
+  PW_HIP(c, hipStreamSynchronize(c->exec));
+  if (!m->bf16) {
+    PW_HIP(c, hipMemcpy(dst, m->logits, (size_t)n * 4, hipMemcpyDeviceToHost));
+    return PW_OK;
+  }
+  float* tmp = nullptr;
+  PW_HIP(c, hipMalloc(&tmp, (size_t)n * 4));
+  hipError_t e = launch_bf16_to_f32(c->exec, m->logits, tmp, n);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->exec);
+  if (e == hipSuccess) e = hipMemcpy(dst, tmp, (size_t)n * 4, hipMemcpyDeviceToHost);
+  (void)hipFree(tmp);
+  if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "activation export: %s", hipGetErrorString(e));
+  return PW_OK;
+}
+
+double pw_encdec_step_flops(const pw_encdec_config* cfg) { return cfg ? encdec_step_flops(*cfg) : 0.0; }
 
 // ---- single kernels ------------------------------------------------------------------------------------
 

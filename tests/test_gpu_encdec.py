@@ -1,0 +1,156 @@
+"""Encoder-decoder train step on the GPU against the CPU oracle: the small fp32 configuration in full (loss,
+every gradient, the update), a reduced bf16 configuration, several Adam steps, determinism and argument
+checks."""
+import numpy as np
+import pytest
+
+from paper_2203_12533_amd import binding as pwb
+from paper_2203_12533_amd import inputs as I
+from gpu_util import TOL, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = pwb.Context(0)
+    yield c
+    c.close()
+
+
+def run_steps(ctx, cfg, params, src, tgt, n_steps=1):
+    """Runs n_steps train steps through the dispatch API; returns (losses, model) - caller closes the model."""
+    model = ctx.encdec(cfg)
+    model.load_params(params)
+    step = model.compile_train_step()
+    losses = []
+    for _ in range(n_steps):
+        fs, ft = ctx.future_from_host(src), ctx.future_from_host(tgt)
+        (fl,) = ctx.run_fn(step, [fs, ft], 1)
+        losses.append(float(ctx.await_(fl)[0]))
+        for f in (fs, ft, fl):
+            ctx.future_release(f)
+    return losses, model
+
+
+def check_against_oracle(params, ref, loss, model, tol, check_update=True):
+    assert abs(loss - ref["loss"]) / abs(ref["loss"]) < tol, (loss, ref["loss"])
+    grads = model.export_all(pwb.PW_GRADS, params)
+    worst = ("", 0.0)
+    for k, g in grads.items():
+        err = rel_l2(g, ref["grads"][k])
+        if err > worst[1]:
+            worst = (k, err)
+        assert err < tol, (k, err)
+    if check_update:
+        new = model.export_all(pwb.PW_PARAMS, params)
+        for k in new:
+            got_delta = new[k].astype(np.float64) - params[k].astype(np.float64)
+            ref_delta = ref["params"][k] - params[k].astype(np.float64)
+            # fp32 storage of w limits how well a tiny delta can be read back: allow w's rounding on top
+            slack = np.linalg.norm(params[k]) * 6e-8 / max(np.linalg.norm(ref_delta), 1e-30)
+            assert rel_l2(got_delta, ref_delta) < tol + slack, (k, rel_l2(got_delta, ref_delta))
+    return worst
+
+
+def test_parameter_table_matches_the_input_recipe(ctx):
+    cfg = I.EncDecConfig(1, 2, 128, 2, 256, 64, 10, 7, 2)
+    model = ctx.encdec(cfg)
+    shapes = I.encdec_param_shapes(cfg)
+    assert model.names == [n for n, _, _ in shapes]
+    for n, shape, _ in shapes:
+        assert model.numel[n] == int(np.prod(shape)), n
+    model.close()
+
+
+@pytest.mark.parametrize("perturb", [False, True])
+def test_ed1_fp32_step_matches_oracle(ctx, orc, perturb):
+    cfg = I.encdec_workload("ed1")           # ragged: 96 source and 80 target positions, batch 3
+    params = I.encdec_params(cfg, perturb=perturb)
+    src, tgt = I.encdec_tokens(cfg)
+    ref = orc.encdec_train_step(cfg, params, src, tgt)
+    (loss,), model = run_steps(ctx, cfg, params, src, tgt)
+    worst = check_against_oracle(params, ref, loss, model, TOL[False])
+    print("ed1 fp32 worst gradient error", worst)
+    model.close()
+
+
+def test_fp32_head_dim_128_source_longer_than_target_and_adam(ctx, orc):
+    """head_dim 128, lengths that are multiples of no tile, Adam, three steps."""
+    cfg = I.EncDecConfig(1, 2, 256, 2, 256, 264, 75, 41, 2, bf16=False, optimizer="adam", lr=1e-3)
+    params = I.encdec_params(cfg, perturb=True)
+    src, tgt = I.encdec_tokens(cfg)
+    losses, model = run_steps(ctx, cfg, params, src, tgt, n_steps=3)
+    p, st, ref_losses = params, None, []
+    for t in (1, 2, 3):
+        ref = orc.encdec_train_step(cfg, p, src, tgt, state=st, t=t)
+        ref_losses.append(ref["loss"])
+        p, st = ref["params"], {"m": ref["m"], "v": ref["v"]}
+    for a, b in zip(losses, ref_losses):
+        assert abs(a - b) / b < 1e-4
+    assert ref_losses[2] < ref_losses[0]          # it does train
+    model.close()
+
+
+# head_dim 128 so that the MFMA attention kernels run in all three of their roles; lengths straddle their tiles
+BF16_SMALL = I.EncDecConfig(2, 2, 256, 2, 1024, 2048, 200, 136, 2, bf16=True, optimizer="adam", lr=1e-4)
+
+
+def test_bf16_step_matches_oracle(ctx, orc):
+    cfg = BF16_SMALL
+    params = I.encdec_params(cfg, perturb=True)
+    src, tgt = I.encdec_tokens(cfg)
+    ref = orc.encdec_train_step(cfg, params, src, tgt)
+    (loss,), model = run_steps(ctx, cfg, params, src, tgt)
+    # Adam's first update is -lr*sign(g) wherever |g| >> eps: sign-sensitive for tiny g, so the update is held
+    # to the kernel-level test; here loss and every gradient are compared
+    worst = check_against_oracle(params, ref, loss, model, TOL[True], check_update=False)
+    print("enc-dec bf16 worst gradient error", worst)
+    model.close()
+
+
+def test_bf16_full_tile_shapes_match_oracle(ctx, orc):
+    """One layer each at widths and lengths for which every GEMM is made of full 256 x 256 tiles: the
+    ring-buffered GEMM kernel, the paired weight-gradient launches and the fused bias gradients all run."""
+    cfg = I.EncDecConfig(1, 1, 512, 4, 1024, 512, 512, 256, 2, bf16=True, optimizer="adam", lr=1e-4)
+    params = I.encdec_params(cfg, perturb=True)
+    src, tgt = I.encdec_tokens(cfg)
+    ref = orc.encdec_train_step(cfg, params, src, tgt)
+    (loss,), model = run_steps(ctx, cfg, params, src, tgt)
+    worst = check_against_oracle(params, ref, loss, model, TOL[True], check_update=False)
+    print("enc-dec bf16 full-tile worst gradient error", worst)
+    model.close()
+
+
+def test_bf16_steps_are_bit_reproducible(ctx):
+    cfg = BF16_SMALL
+    params = I.encdec_params(cfg, perturb=True)
+    src, tgt = I.encdec_tokens(cfg)
+    runs = []
+    for _ in range(2):
+        losses, model = run_steps(ctx, cfg, params, src, tgt, n_steps=2)
+        runs.append((losses, model.export(pwb.PW_PARAMS, "d1.wkv"), model.export(pwb.PW_GRADS, "enc.wte")))
+        model.close()
+    assert runs[0][0] == runs[1][0]
+    assert np.array_equal(runs[0][1], runs[1][1]) and np.array_equal(runs[0][2], runs[1][2])
+
+
+def test_bad_configurations_and_signatures_are_rejected(ctx):
+    with pytest.raises(pwb.PwError):
+        ctx.encdec(I.EncDecConfig(1, 1, 96, 2, 256, 64, 8, 8, 1))          # head_dim 48
+    with pytest.raises(pwb.PwError):
+        ctx.encdec(I.EncDecConfig(0, 1, 128, 2, 256, 64, 8, 8, 1))         # no encoder layer
+    cfg = I.EncDecConfig(1, 1, 128, 2, 256, 64, 8, 6, 2)
+    model = ctx.encdec(cfg)
+    step = model.compile_train_step()
+    src, tgt = I.encdec_tokens(cfg)
+    fs, ft = ctx.future_from_host(src), ctx.future_from_host(tgt)
+    with pytest.raises(pwb.PwError):
+        ctx.run_fn(step, [ft, fs], 1)                                       # swapped: shapes do not fit
+    with pytest.raises(pwb.PwError):
+        ctx.run_fn(step, [fs], 1)
+    (fl,) = ctx.run_fn(step, [fs, ft], 1)
+    assert np.isfinite(ctx.await_(fl)[0])
+    for f in (fs, ft, fl):
+        ctx.future_release(f)
+    model.close()
