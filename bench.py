@@ -7,7 +7,11 @@ inputs already resident in HBM.  Prints ONE JSON line: whole-step tokens/s, the 
 the GEMM kernel (HIP-event timing of every GEMM launch inside the timed steps), the chained-dispatch
 cost per function, and the CPU oracle timed on a bounded sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg5|cfg1] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg5|cfg4|cfg1|ed3|ed1] [--no-cpu-baseline]
+
+Workloads "ed*" are the encoder-decoder step (the second workload: one step = one source batch through the
+encoder plus one target batch through the decoder, tokens counted on both sides); the default stays the
+decoder-only step the headline metric is quoted on.
 """
 from __future__ import annotations
 
@@ -32,7 +36,8 @@ def fill_model_on_device(model, cfg, torch, seed: int):
     from paper_2203_12533_amd import inputs as I
     gen = torch.Generator(device="cuda")
     gen.manual_seed(seed)
-    for name, shape, kind in I.param_shapes(cfg):
+    shapes = I.encdec_param_shapes(cfg) if isinstance(cfg, I.EncDecConfig) else I.param_shapes(cfg)
+    for name, shape, kind in shapes:
         n = int(np.prod(shape))
         if kind == "matrix":
             t = torch.randn(n, device="cuda", generator=gen, dtype=torch.float32) * cfg.init_std
@@ -130,6 +135,25 @@ def dispatch_bench_c_abi():
     return out
 
 
+def cpu_baseline_encdec(cfg, pwb, I, budget_tokens: int = 64):
+    """The CPU oracle on a bounded sample of the encoder-decoder workload: one layer each, one sequence pair of
+    `budget_tokens` source and target tokens, the workload's widths.  Extrapolated by model-FLOP ratio."""
+    from oracle import oracle
+    sample = cfg.with_(n_enc_layer=1, n_dec_layer=1, batch=1, src_len=min(cfg.src_len, budget_tokens),
+                       tgt_len=min(cfg.tgt_len, budget_tokens))
+    params = I.encdec_params(sample)
+    src, tgt = I.encdec_tokens(sample)
+    secs = oracle.encdec_train_step(sample, params, src, tgt)["seconds"]
+    flops_sample = pwb.encdec_step_flops(sample)
+    flops_full_per_token = pwb.encdec_step_flops(cfg) / cfg.n_tokens
+    return {"value": (flops_sample / secs) / flops_full_per_token, "unit": "tokens/s", "cores": oracle.threads(),
+            "kind": "oracle",
+            "sample": f"one full oracle encoder-decoder train step (fp64, plain loops) on 1 + 1 layers, batch 1, "
+                      f"{sample.src_len} source and {sample.tgt_len} target tokens with the workload's d_model/d_ff/vocab "
+                      f"took {secs:.2f} s = {flops_sample / secs / 1e9:.2f} GFLOP/s; tokens/s extrapolated to the full "
+                      f"workload by model-FLOP ratio"}
+
+
 def cpu_baseline(cfg, pwb, budget_tokens: int = 128):
     if not cfg.has_head:
         return None
@@ -172,11 +196,22 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
-    cfg = I.workload(args.workload)
+    encdec = args.workload.startswith("ed")
+    cfg = I.encdec_workload(args.workload) if encdec else I.workload(args.workload)
     ctx = pwb.Context(0)
-    model = ctx.model(cfg)
+    model = ctx.encdec(cfg) if encdec else ctx.model(cfg)
     fill_model_on_device(model, cfg, torch, seed=1234)
-    if cfg.has_head:
+    if encdec:
+        src_np, tgt_np = I.encdec_tokens(cfg, seed=1234)
+        src, tgt = torch.from_numpy(src_np).cuda(), torch.from_numpy(tgt_np).cuda()
+        torch.cuda.synchronize()
+        f_src = ctx.future_wrap_device(src.data_ptr(), pwb.PW_I32, tuple(src.shape))
+        f_tgt = ctx.future_wrap_device(tgt.data_ptr(), pwb.PW_I32, tuple(tgt.shape))
+        step = model.compile_train_step()
+
+        def one_step():
+            return ctx.run_fn(step, [f_src, f_tgt], 1)[0]
+    elif cfg.has_head:
         tok = torch.from_numpy(I.lm_tokens(cfg, seed=1234)).cuda()
         torch.cuda.synchronize()
         f_tok = ctx.future_wrap_device(tok.data_ptr(), pwb.PW_I32, tuple(tok.shape))
@@ -259,25 +294,33 @@ def main():
         del src, dst
 
     ms_per_step = dt * 1e3 / args.steps
-    tokens_per_step = cfg.n_tokens * cfg.n_microbatch
+    tokens_per_step = cfg.n_tokens * (1 if encdec else cfg.n_microbatch)
     tokens_per_s = tokens_per_step * args.steps / dt
-    flops = pwb.step_flops(cfg)
+    flops = pwb.encdec_step_flops(cfg) if encdec else pwb.step_flops(cfg)
+    if encdec:
+        what = (f"{args.workload}: encoder-decoder train step, {cfg.n_enc_layer} encoder + {cfg.n_dec_layer} decoder layers, "
+                f"d_model {cfg.d_model}, {cfg.n_head} heads, FFN {cfg.d_ff}, vocab {cfg.vocab}, {cfg.src_len} source + "
+                f"{cfg.tgt_len} target positions, batch {cfg.batch}, "
+                f"{'bf16 compute / fp32 master' if cfg.bf16 else 'fp32'} + {cfg.optimizer}")
+        loss_key = "loss_first_last"
+    else:
+        what = (f"{args.workload}: {cfg.n_layer}-layer decoder-only LM "
+                f"{'train step' if cfg.has_head else f'pipeline stage, {cfg.n_microbatch} micro-batches fwd-all/bwd-all'}, "
+                f"d_model {cfg.d_model}, {cfg.n_head} heads, FFN {cfg.d_ff}, vocab {cfg.vocab}, seq {cfg.seq}, "
+                f"batch {cfg.batch}, {'bf16 compute / fp32 master' if cfg.bf16 else 'fp32'} + {cfg.optimizer}")
+        loss_key = "loss_first_last" if cfg.has_head else "dx0_first_last"
     achieved = flops / (dt / args.steps) / 1e12
     gemm_tflops = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     result = {
         "metric": "train tokens/sec/GPU", "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.bf16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {cfg.n_layer}-layer decoder-only LM "
-                               f"{'train step' if cfg.has_head else f'pipeline stage, {cfg.n_microbatch} micro-batches fwd-all/bwd-all'}, "
-                               f"d_model {cfg.d_model}, {cfg.n_head} heads, FFN {cfg.d_ff}, vocab {cfg.vocab}, seq {cfg.seq}, "
-                               f"batch {cfg.batch}, {'bf16 compute / fp32 master' if cfg.bf16 else 'fp32'} + {cfg.optimizer}",
-                   "tokens_per_step": tokens_per_step, "model_tflop_per_step": round(flops / 1e12, 3)},
+        "config": {"workload": what, "tokens_per_step": tokens_per_step, "model_tflop_per_step": round(flops / 1e12, 3)},
         "pct_peak_bf16_mfma": round(100.0 * achieved / PEAK_BF16_TFLOPS, 2),
         "step_tflops": round(achieved, 1),
         "ms_per_step_device": {"median": round(per_step[len(per_step) // 2], 3), "min": round(per_step[0], 3),
                                "max": round(per_step[-1], 3)},
-        ("loss_first_last" if cfg.has_head else "dx0_first_last"): [round(losses[0], 4), round(losses[-1], 4)],
+        loss_key: [round(losses[0], 4), round(losses[-1], 4)],
         "roofline": {"bound": "mfma", "kernel": "bf16 MFMA GEMM (gemm_ring_kernel + gemm_bf16_kernel, all layouts)", "achieved": round(gemm_tflops, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": recorded_gemm_traffic(args.workload), "launches_per_step": n_gemm // max(1, profiled_steps), "steps_with_events": profiled_steps,
@@ -294,7 +337,7 @@ def main():
         if cabi is not None:
             result["dispatch_c_abi"] = cabi
     if not args.no_cpu_baseline:
-        cb = cpu_baseline(cfg, pwb)
+        cb = cpu_baseline_encdec(cfg, pwb, I) if encdec else cpu_baseline(cfg, pwb)
         if cb is not None:
             result["cpu_baseline"] = cb
     print(json.dumps(result))

@@ -386,6 +386,9 @@ pw_status pw_op_gemm(pw_ctx* ctx, const pw_gemm_args* args);
  * compute units idle - the attention weight gradients of one layer, section 5.3's Transformer layers - their
  * tiles run side by side in one launch.  Nothing is enqueued if either argument set is invalid. */
 pw_status pw_op_gemm_pair(pw_ctx* ctx, const pw_gemm_args* args0, const pw_gemm_args* args1);
+/* The same for n = 1..3 GEMMs given as an array (the three weight gradients of a decoder's attention over the
+ * encoder output: query, key/value and output projections). */
+pw_status pw_op_gemm_group(pw_ctx* ctx, const pw_gemm_args* args, int n);
 /* x[b*T+t,:] = wte[tok[b*(T+1)+t],:] + wpe[t,:]  (fp32 in, fp32 out; exact). */
 pw_status pw_op_embedding_fwd(pw_ctx* ctx, const int32_t* tokens, const float* wte, const float* wpe,
                               float* x, int B, int T, int d, int V);

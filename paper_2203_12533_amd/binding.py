@@ -149,6 +149,7 @@ _SIGS = {
     "pw_profile_end": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "pw_op_gemm": (C.c_int, [C.c_void_p, C.POINTER(GemmArgs)]),
     "pw_op_gemm_pair": (C.c_int, [C.c_void_p, C.POINTER(GemmArgs), C.POINTER(GemmArgs)]),
+    "pw_op_gemm_group": (C.c_int, [C.c_void_p, C.POINTER(GemmArgs), C.c_int]),
     "pw_op_embedding_fwd": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4 + [C.c_int] * 4),
     "pw_op_embedding_bwd": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4 + [C.c_int] * 4),
     "pw_op_layernorm_fwd": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 6 + [C.c_int] * 2),
@@ -398,6 +399,13 @@ class Context:
     def mha_bwd(self, args: "MhaArgs", o: int, dout: int, lse: int, delta: int, dq: int, lddq: int, dk: int, dv: int,
                 lddkv: int):
         self._check(lib().pw_op_mha_bwd(self._h, C.byref(args), o, dout, lse, delta, dq, lddq, dk, dv, lddkv))
+
+    def gemm_group(self, kws: list):
+        arr = (GemmArgs * len(kws))()
+        for a, kw in zip(arr, kws):
+            for k, v in kw.items():
+                setattr(a, k, v)
+        self._check(lib().pw_op_gemm_group(self._h, arr, len(kws)))
 
     def gemm_pair(self, kw0: dict, kw1: dict):
         a0, a1 = GemmArgs(), GemmArgs()

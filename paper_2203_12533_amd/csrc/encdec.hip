@@ -176,8 +176,11 @@ hipError_t self_bwd(EncDec* m, size_t e, const EncDec::SelfActs& A, GradStream& 
   PW_TRY(launch_mha_bwd(m->stream, a, A.o, m->d_small, A.lse, m->delta, dqkv, 3 * (int64_t)d, dqkv + d * es, dqkv + 2 * d * es,
                         3 * (int64_t)d), "self-attention bwd");
   // (dy, the residual gradient in operand form, stays intact until the LayerNorm backward below rewrites it)
-  PW_TRY(gemm_wgrad_pair_bias(m, wgrad_args(m, A.a, m->d_qkv, e + 2, N, d, 3 * d, 0), e + 3, m->d_qkv, N, 3 * d,
-                              wgrad_args(m, A.o, dy, e + 4, N, d, d, 0), 0, m->ws), "qkv + out-proj wgrad + bqkv grad");
+  {
+    const WgradJob jobs[2] = {{wgrad_args(m, A.a, m->d_qkv, e + 2, N, d, 3 * d, 0), (int64_t)e + 3},
+                              {wgrad_args(m, A.o, dy, e + 4, N, d, d, 0), -1}};
+    PW_TRY(gemm_wgrad_group(m, jobs, 2, m->ws), "qkv + out-proj wgrad + bqkv grad");
+  }
   PW_TRY(gemm_dgrad(m, m->d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small, dt, 0), "qkv dgrad");
   PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->wp(e), A.mean, A.rstd, gs.cur, gs.other,
                               m->bf16 ? m->dx_lp : nullptr, m->gp(e), m->gp(e + 1), below_bias, m->ws, N, d, 0), "self-attention LN bwd");
@@ -213,9 +216,13 @@ hipError_t cross_bwd(EncDec* m, size_t e, const EncDec::CrossActs& A, GradStream
   const MhaArgs a{dt, A.q, kv, kv + d * es, (int64_t)d, 2 * (int64_t)d, c.batch, c.tgt_len, c.src_len, c.n_head, m->hd(), 0};
   PW_TRY(launch_mha_bwd(m->stream, a, A.o, m->d_small, A.lse, m->delta, m->d_q, (int64_t)d, dkv, dkv + d * es, 2 * (int64_t)d),
          "cross-attention bwd");
-  PW_TRY(gemm_wgrad_pair_bias(m, wgrad_args(m, A.a, m->d_q, e + 2, Nt, d, d, 0), e + 3, m->d_q, Nt, d,
-                              wgrad_args(m, A.o, dy, e + 6, Nt, d, d, 0), 0, m->ws), "cross q + out-proj wgrad + bq grad");
-  PW_TRY(gemm_wgrad_bias(m, m->mem, dkv, e + 4, e + 5, Ns, d, 2 * d, 0, m->ws), "cross kv wgrad + bkv grad");
+  {
+    // three weight gradients that each cover a quarter to a half of the chip: one launch
+    const WgradJob jobs[3] = {{wgrad_args(m, m->mem, dkv, e + 4, Ns, d, 2 * d, 0), (int64_t)e + 5},
+                              {wgrad_args(m, A.a, m->d_q, e + 2, Nt, d, d, 0), (int64_t)e + 3},
+                              {wgrad_args(m, A.o, dy, e + 6, Nt, d, d, 0), -1}};
+    PW_TRY(gemm_wgrad_group(m, jobs, 3, m->ws), "cross kv + q + out-proj wgrad + bias grads");
+  }
   PW_TRY(gemm_dgrad(m, dkv, e + 4, Ns, d, 2 * d, kEpiStore, nullptr, m->dmem, kF32, dmem_accumulate), "cross kv dgrad");
   PW_TRY(gemm_dgrad(m, m->d_q, e + 2, Nt, d, d, kEpiStore, nullptr, m->d_small, dt, 0), "cross q dgrad");
   PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->wp(e), A.mean, A.rstd, gs.cur, gs.other,

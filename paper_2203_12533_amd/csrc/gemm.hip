@@ -20,6 +20,8 @@
 //
 // fp32 path: a plain LDS-tiled ALU kernel; it serves the small fp32 configuration only.
 #include "common.hpp"
+#include <algorithm>
+
 #include "gemm_common.hpp"
 #include "kernels.hpp"
 
@@ -477,32 +479,58 @@ static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a) {
   return launch_bf16_tile<128, 128, 2, 2>(s, p, a.a_kmajor, a.b_kmajor, edge);
 }
 
-// Two independent GEMMs.  When both are ring-kernel problems of one operand layout and together fill at least
-// most of the chip, they share a single launch (their tiles run side by side); otherwise one launch each.
-// Whether launch_gemm_pair runs the two problems in one launch: both ring-kernel problems of one operand layout,
-// enough tiles together, and at least one of them would leave part of the chip idle (or miss the ring kernel) alone.
+// Up to three independent GEMMs.  When all are ring-kernel problems of one operand layout, together fill at least
+// most of the chip, and at least one of them would leave part of it idle (or miss the ring kernel) alone, they
+// share a single launch (their tiles run side by side); otherwise one launch each.
+bool gemm_group_shares_launch(const GemmArgs* a, int n) {
+  if (n < 2 || n > kRingGroupMax) return false;
+  int64_t total = 0;
+  bool all_full_rounds = true;
+  for (int i = 0; i < n; ++i) {
+    if (a[i].M <= 0 || a[i].N <= 0 || !ring_eligible(a[i])) return false;
+    if (a[i].a_kmajor != a[0].a_kmajor || a[i].b_kmajor != a[0].b_kmajor) return false;
+    const int64_t t = (a[i].M / 256) * (a[i].N / 256);
+    total += t;
+    all_full_rounds = all_full_rounds && t % 256 == 0;
+  }
+  return total >= 150 && total <= (1 << 20) && !all_full_rounds;
+}
 bool gemm_pair_shares_launch(const GemmArgs& a0, const GemmArgs& a1) {
-  if (a0.M <= 0 || a0.N <= 0 || a1.M <= 0 || a1.N <= 0) return false;
-  if (!ring_eligible(a0) || !ring_eligible(a1) || a0.a_kmajor != a1.a_kmajor || a0.b_kmajor != a1.b_kmajor) return false;
-  const int64_t t0 = (a0.M / 256) * (a0.N / 256), t1 = (a1.M / 256) * (a1.N / 256);
-  return t0 + t1 >= 150 && t0 + t1 <= (1 << 20) && !(t0 % 256 == 0 && t1 % 256 == 0);
+  const GemmArgs a[2] = {a0, a1};
+  return gemm_group_shares_launch(a, 2);
 }
 
-hipError_t launch_gemm_pair(hipStream_t s, const GemmArgs& a0, const GemmArgs& a1) {
-  bool e0, e1;
-  hipError_t err = check_gemm_args(a0, &e0);
-  if (err == hipSuccess) err = check_gemm_args(a1, &e1);
-  if (err != hipSuccess) return err;
-  const bool shared = !e0 && !e1 && gemm_pair_shares_launch(a0, a1);
-  const int64_t t0 = (a0.M / 256) * (a0.N / 256), t1 = (a1.M / 256) * (a1.N / 256);
-  if ((a0.b_colsum && !gemm_colsum_fusable(a0, shared)) || (a1.b_colsum && !gemm_colsum_fusable(a1, shared)))
-    return hipErrorInvalidValue;   // checked before anything is launched
-  if (!shared) {
-    err = launch_gemm(s, a0);
-    return err == hipSuccess ? launch_gemm(s, a1) : err;
+hipError_t launch_gemm_group(hipStream_t s, const GemmArgs* a, int n) {
+  if (n < 1 || n > kRingGroupMax || !a) return hipErrorInvalidValue;
+  bool empty[kRingGroupMax], any_empty = false;
+  for (int i = 0; i < n; ++i) {
+    const hipError_t err = check_gemm_args(a[i], &empty[i]);
+    if (err != hipSuccess) return err;
+    any_empty = any_empty || empty[i];
   }
+  const bool shared = !any_empty && gemm_group_shares_launch(a, n);
+  for (int i = 0; i < n; ++i)
+    if (a[i].b_colsum && !gemm_colsum_fusable(a[i], shared)) return hipErrorInvalidValue;   // checked before anything is launched
+  if (!shared) {
+    for (int i = 0; i < n; ++i) {
+      const hipError_t err = launch_gemm(s, a[i]);
+      if (err != hipSuccess) return err;
+    }
+    return hipSuccess;
+  }
+  // the larger problems' workgroups first
+  int order[kRingGroupMax];
+  double flops = 0.0;
+  for (int i = 0; i < n; ++i) {
+    order[i] = i;
+    flops += 2.0 * (double)a[i].M * (double)a[i].N * (double)a[i].K;
+  }
+  std::stable_sort(order, order + n, [&](int x, int y) { return a[x].M * a[x].N > a[y].M * a[y].N; });
+  GemmBf16Params p[kRingGroupMax];
+  for (int i = 0; i < n; ++i) p[i] = bf16_params_of(a[order[i]], 256);
   const bool timed = g_profile_on;
-  ProfiledLaunch pl{nullptr, nullptr, 2.0 * ((double)a0.M * (double)a0.N * (double)a0.K + (double)a1.M * (double)a1.N * (double)a1.K)};
+  ProfiledLaunch pl{nullptr, nullptr, flops};
+  hipError_t err = hipSuccess;
   if (timed) {
     pl.start = profile_event();
     pl.stop = profile_event();
@@ -510,14 +538,17 @@ hipError_t launch_gemm_pair(hipStream_t s, const GemmArgs& a0, const GemmArgs& a
     err = hipEventRecord(pl.start, s);
     if (err != hipSuccess) return err;
   }
-  // the larger problem's workgroups first
-  const bool swap = t1 > t0;
-  err = launch_gemm_ring_pair(s, bf16_params_of(swap ? a1 : a0, 256), bf16_params_of(swap ? a0 : a1, 256), a0.a_kmajor, a0.b_kmajor);
+  err = launch_gemm_ring_group(s, p, n, a[0].a_kmajor, a[0].b_kmajor);
   if (timed && err == hipSuccess) {
     err = hipEventRecord(pl.stop, s);
     if (err == hipSuccess) g_profile.push_back(pl);
   }
   return err;
+}
+
+hipError_t launch_gemm_pair(hipStream_t s, const GemmArgs& a0, const GemmArgs& a1) {
+  const GemmArgs a[2] = {a0, a1};
+  return launch_gemm_group(s, a, 2);
 }
 
 }  // namespace pw

@@ -289,8 +289,13 @@ __device__ __forceinline__ void gemm_epilogue_staged(bf16* smem, f32x16 (&acc)[F
 // Ring-buffered variant for full tiles (gemm_ring.hip).
 bool gemm_ring_supported(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemm_ring(hipStream_t s, const GemmBf16Params& p, bool a_kmajor, bool b_kmajor);
-hipError_t launch_gemm_ring_pair(hipStream_t s, const GemmBf16Params& p0, const GemmBf16Params& p1, bool a_kmajor,
-                                 bool b_kmajor);
+// n <= kRingGroupMax problems of one operand layout in a single launch, problem i's workgroups before problem i+1's.
+constexpr int kRingGroupMax = 3;
+struct GemmRingGroup {
+  GemmBf16Params p[kRingGroupMax];
+  int first[kRingGroupMax + 1];   // workgroup ranges; unused problems have empty ranges
+};
+hipError_t launch_gemm_ring_group(hipStream_t s, const GemmBf16Params* p, int n, bool a_kmajor, bool b_kmajor);
 hipError_t gemm_ring_init();
 
 }  // namespace pw

@@ -239,15 +239,15 @@ __global__ __launch_bounds__(2 * NW * 64) void gemm_ring_kernel(GemmBf16Params p
   ring_tile<A_KMAJOR, B_KMAJOR, NW>(p, blockIdx.x, smem);
 }
 
-// Two independent problems of the same operand layout in one launch: workgroups [0, tiles of p0) work on p0,
-// the rest on p1.  Lets two GEMMs that each fill only part of the chip share one round of workgroups.
+// Up to three independent problems of the same operand layout in one launch: workgroups [first[i], first[i+1])
+// work on problem i.  Lets GEMMs that each fill only part of the chip share one round of workgroups.
 template <bool A_KMAJOR, bool B_KMAJOR, int NW>
-__global__ __launch_bounds__(2 * NW * 64) void gemm_ring_pair_kernel(GemmBf16Params p0, GemmBf16Params p1) {
+__global__ __launch_bounds__(2 * NW * 64) void gemm_ring_group_kernel(GemmRingGroup g) {
   extern __shared__ __attribute__((aligned(16))) bf16 smem[];
-  const int t0 = p0.tiles_m * p0.tiles_n;
-  const bool first = (int)blockIdx.x < t0;
-  const GemmBf16Params p = first ? p0 : p1;
-  ring_tile<A_KMAJOR, B_KMAJOR, NW>(p, first ? (int)blockIdx.x : (int)blockIdx.x - t0, smem);
+  const int bid = (int)blockIdx.x;
+  const int which = bid < g.first[1] ? 0 : (bid < g.first[2] ? 1 : 2);
+  const GemmBf16Params p = which == 0 ? g.p[0] : (which == 1 ? g.p[1] : g.p[2]);
+  ring_tile<A_KMAJOR, B_KMAJOR, NW>(p, bid - g.first[which], smem);
 }
 
 constexpr size_t kRSmemBytes = (size_t)kRStages * kRStage * sizeof(bf16);   // 128 KiB
@@ -265,39 +265,50 @@ hipError_t prepare_ring_variant() {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_kernel<AK, BK_, NW>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRSmemBytes);
   if (e == hipSuccess)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_pair_kernel<AK, BK_, NW>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_group_kernel<AK, BK_, NW>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRSmemBytes);
   if (e == hipSuccess) attr_done = true;
   return e;
 }
 
 template <bool AK, bool BK_, int NW>
-hipError_t launch_ring_variant(hipStream_t s, const GemmBf16Params& p, const GemmBf16Params* p1) {
+hipError_t launch_ring_variant(hipStream_t s, const GemmBf16Params* p, int n) {
   hipError_t e = prepare_ring_variant<AK, BK_, NW>();
   if (e != hipSuccess) return e;
-  if (!p1) {
-    gemm_ring_kernel<AK, BK_, NW><<<p.tiles_m * p.tiles_n, 2 * NW * 64, kRSmemBytes, s>>>(p);
+  if (n == 1) {
+    gemm_ring_kernel<AK, BK_, NW><<<p[0].tiles_m * p[0].tiles_n, 2 * NW * 64, kRSmemBytes, s>>>(p[0]);
   } else {
-    gemm_ring_pair_kernel<AK, BK_, NW><<<p.tiles_m * p.tiles_n + p1->tiles_m * p1->tiles_n, 2 * NW * 64, kRSmemBytes, s>>>(p, *p1);
+    GemmRingGroup g{};
+    int total = 0;
+    for (int i = 0; i < kRingGroupMax; ++i) {
+      g.first[i] = total;
+      if (i < n) {
+        g.p[i] = p[i];
+        total += p[i].tiles_m * p[i].tiles_n;
+      }
+    }
+    g.first[kRingGroupMax] = total;
+    gemm_ring_group_kernel<AK, BK_, NW><<<total, 2 * NW * 64, kRSmemBytes, s>>>(g);
   }
   return hipGetLastError();
 }
 
 template <int NW>
-hipError_t launch_ring_nw(hipStream_t s, const GemmBf16Params& p, const GemmBf16Params* p1, bool ak, bool bk) {
-  if (!ak && !bk) return launch_ring_variant<false, false, NW>(s, p, p1);
-  if (!ak && bk) return launch_ring_variant<false, true, NW>(s, p, p1);
-  if (ak && bk) return launch_ring_variant<true, true, NW>(s, p, p1);
-  return launch_ring_variant<true, false, NW>(s, p, p1);
+hipError_t launch_ring_nw(hipStream_t s, const GemmBf16Params* p, int n, bool ak, bool bk) {
+  if (!ak && !bk) return launch_ring_variant<false, false, NW>(s, p, n);
+  if (!ak && bk) return launch_ring_variant<false, true, NW>(s, p, n);
+  if (ak && bk) return launch_ring_variant<true, true, NW>(s, p, n);
+  return launch_ring_variant<true, false, NW>(s, p, n);
 }
 
 }  // namespace
 
 hipError_t launch_gemm_ring(hipStream_t s, const GemmBf16Params& p, bool ak, bool bk) {
-  return launch_ring_nw<kRingNW>(s, p, nullptr, ak, bk);
+  return launch_ring_nw<kRingNW>(s, &p, 1, ak, bk);
 }
-hipError_t launch_gemm_ring_pair(hipStream_t s, const GemmBf16Params& p0, const GemmBf16Params& p1, bool ak, bool bk) {
-  return launch_ring_nw<kRingNW>(s, p0, &p1, ak, bk);
+hipError_t launch_gemm_ring_group(hipStream_t s, const GemmBf16Params* p, int n, bool ak, bool bk) {
+  if (n < 1 || n > kRingGroupMax) return hipErrorInvalidValue;
+  return launch_ring_nw<kRingNW>(s, p, n, ak, bk);
 }
 
 bool gemm_ring_supported(int64_t M, int64_t N, int64_t K) { return M % kRT == 0 && N % kRT == 0 && K % kRBK == 0 && K >= kRBK; }

@@ -93,8 +93,11 @@ hipError_t launch_gemm(hipStream_t s, const GemmArgs& a);
 // 256 x 256 tiles: the weight-gradient GEMMs); callers fall back to launch_colsum otherwise.
 bool gemm_colsum_fusable(const GemmArgs& a, bool paired);
 bool gemm_pair_shares_launch(const GemmArgs& a0, const GemmArgs& a1);
-// Two independent GEMMs; shares one launch between them when that fills the chip better (same results either way).
+bool gemm_group_shares_launch(const GemmArgs* a, int n);
+// Two (or up to three) independent GEMMs; one launch is shared between them when that fills the chip better
+// (same results either way).  Their outputs must not overlap each other or any operand.
 hipError_t launch_gemm_pair(hipStream_t s, const GemmArgs& a0, const GemmArgs& a1);
+hipError_t launch_gemm_group(hipStream_t s, const GemmArgs* a, int n);
 // Timing of MFMA GEMM launches with HIP events on the launch stream (measurement aid).
 void gemm_profile_begin();
 void gemm_profile_pause();   // stop bracketing launches; what was recorded so far stays for gemm_profile_end

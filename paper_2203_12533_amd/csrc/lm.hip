@@ -152,9 +152,11 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
                                 c.n_head, m->hd()), "attention bwd");
     // QKV: qkv = a Wqkv + bqkv
     // (dy_out, the bf16 residual gradient, stays intact until the LN1 backward below rewrites it)
-    PW_TRY(gemm_wgrad_pair_bias(m, wgrad_args(m, A.a, m->d_qkv, e + 2, N, d, 3 * d, accumulate), e + 3, m->d_qkv, N, 3 * d,
-                                wgrad_args(m, A.o, dy_out, e + 4, N, d, d, accumulate), accumulate, m->ws),
-           "qkv + out-proj wgrad + bqkv grad");
+    {
+      const WgradJob jobs[2] = {{wgrad_args(m, A.a, m->d_qkv, e + 2, N, d, 3 * d, accumulate), (int64_t)e + 3},
+                                {wgrad_args(m, A.o, dy_out, e + 4, N, d, d, accumulate), -1}};
+      PW_TRY(gemm_wgrad_group(m, jobs, 2, m->ws), "qkv + out-proj wgrad + bqkv grad");
+    }
     PW_TRY(gemm_dgrad(m, m->d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small, dt, 0), "qkv dgrad");
     // LN1 and the residual branch: dx_a = dx_b + LN1'(d_small)
     PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->w + P(m, e).offset, A.mean1, A.rstd1, m->dx_b,

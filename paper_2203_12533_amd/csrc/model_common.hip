@@ -110,15 +110,23 @@ hipError_t gemm_wgrad_bias(ModelBase* m, const void* x, const void* dy, int64_t 
   return launch_colsum(m->stream, m->act_dtype(), dy, m->gp(bi), ws, N, out, accumulate);
 }
 
-hipError_t gemm_wgrad_pair_bias(ModelBase* m, const GemmArgs& w0, int64_t bi0, const void* dy0, int64_t N, int64_t out0,
-                                const GemmArgs& w1, int accumulate, float* ws) {
-  GemmArgs a0 = w0;
-  a0.b_colsum = m->gp(bi0);
-  if (gemm_colsum_fusable(a0, gemm_pair_shares_launch(a0, w1))) return launch_gemm_pair(m->stream, a0, w1);
-  a0.b_colsum = nullptr;
-  hipError_t e = launch_gemm_pair(m->stream, a0, w1);
-  if (e != hipSuccess) return e;
-  return launch_colsum(m->stream, m->act_dtype(), dy0, m->gp(bi0), ws, N, out0, accumulate);
+hipError_t gemm_wgrad_group(ModelBase* m, const WgradJob* jobs, int n, float* ws) {
+  if (n < 1 || n > 3) return hipErrorInvalidValue;
+  GemmArgs a[3];
+  for (int i = 0; i < n; ++i) a[i] = jobs[i].args;
+  const bool shared = gemm_group_shares_launch(a, n);
+  bool fused[3] = {false, false, false};
+  for (int i = 0; i < n; ++i) {
+    if (jobs[i].bias < 0) continue;
+    a[i].b_colsum = m->gp(jobs[i].bias);
+    fused[i] = gemm_colsum_fusable(a[i], shared);
+    if (!fused[i]) a[i].b_colsum = nullptr;
+  }
+  hipError_t e = launch_gemm_group(m->stream, a, n);
+  for (int i = 0; i < n && e == hipSuccess; ++i)
+    if (jobs[i].bias >= 0 && !fused[i])   // dy of a weight gradient is its B operand: [K = N rows][N = out columns]
+      e = launch_colsum(m->stream, m->act_dtype(), a[i].B, m->gp(jobs[i].bias), ws, a[i].K, a[i].N, a[i].accumulate);
+  return e;
 }
 
 }  // namespace pw

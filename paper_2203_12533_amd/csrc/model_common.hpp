@@ -96,9 +96,13 @@ GemmArgs wgrad_args(ModelBase* m, const void* x, const void* dy, int64_t wi, int
 // a separate column-sum launch otherwise.  ws: workspace of colsum_ws_floats(N, out) floats.
 hipError_t gemm_wgrad_bias(ModelBase* m, const void* x, const void* dy, int64_t wi, int64_t bi, int64_t N, int64_t in,
                            int64_t out, int accumulate, float* ws);
-// Two weight gradients in one launch where that fills the chip better; the first one also delivers its bias
-// gradient (parameter bi0) as above.
-hipError_t gemm_wgrad_pair_bias(ModelBase* m, const GemmArgs& w0, int64_t bi0, const void* dy0, int64_t N, int64_t out0,
-                                const GemmArgs& w1, int accumulate, float* ws);
+// Several (up to three) weight gradients of one step, in one launch where that fills the chip better.  A job with
+// bias >= 0 also delivers the bias gradient db = column sums of its dy [N, out] into that parameter's slot: fused
+// where that is free, a separate column-sum launch otherwise.
+struct WgradJob {
+  GemmArgs args;       // from wgrad_args
+  int64_t bias;        // parameter index of the bias, or -1
+};
+hipError_t gemm_wgrad_group(ModelBase* m, const WgradJob* jobs, int n, float* ws);
 
 }  // namespace pw

@@ -2030,6 +2030,12 @@ pw_status pw_op_gemm_pair(pw_ctx* c, const pw_gemm_args* a0, const pw_gemm_args*
   if (!c || !a0 || !a1) return PW_ERR_INVALID;
   PW_OP(c, launch_gemm_pair(c->exec, gemm_args_of(a0), gemm_args_of(a1)));
 }
+pw_status pw_op_gemm_group(pw_ctx* c, const pw_gemm_args* a, int n) {
+  if (!c || !a || n < 1 || n > 3) return PW_ERR_INVALID;
+  GemmArgs g[3];
+  for (int i = 0; i < n; ++i) g[i] = gemm_args_of(&a[i]);
+  PW_OP(c, launch_gemm_group(c->exec, g, n));
+}
 pw_status pw_op_embedding_fwd(pw_ctx* c, const int32_t* tokens, const float* wte, const float* wpe, float* x, int B, int T, int d, int V) {
   PW_OP(c, launch_embedding_fwd(c->exec, tokens, wte, wpe, x, B, T, d, V));
 }

@@ -198,6 +198,38 @@ def test_full_cfg3_step_properties():
     assert (e1.reshape(V, D)[unused] == 0).all() and np.abs(e1.reshape(V, D)[used[:50]]).max() > 0
 
 
+def test_three_weight_gradients_share_one_launch(ctx, orc):
+    """The weight gradients of a decoder's attention over the encoder output at the encoder-decoder workload's
+    shape - dWkv = mem^T . dkv (128 tiles), dWq = a^T . dq and dWox = o^T . dy (64 tiles each) - in one launch
+    of 256 workgroups, with the two bias gradients riding along: against the oracle on sampled rows and against
+    single launches everywhere."""
+    mem, dkv = _bf16_randn((N, D), 21), _bf16_randn((N, 2 * D), 22)
+    a, dq = _bf16_randn((N // 2, D), 23), _bf16_randn((N // 2, D), 24)      # fewer target than source positions
+    o, dy = _bf16_randn((N // 2, D), 25), _bf16_randn((N // 2, D), 26)
+    def args(x, g, out, n_out):
+        return dict(dtype=pwb.PW_BF16, a_kmajor=1, b_kmajor=1, M=D, N=n_out, K=x.shape[0], lda=D, ldb=n_out, ldc=n_out,
+                    epilogue=pwb.PW_EPI_STORE, out_dtype=pwb.PW_F32, accumulate=0, A=ptr(x), B=ptr(g), C=ptr(out))
+    nan = float("nan")
+    dwkv, dwq, dwox = (torch.full(s, nan, device="cuda") for s in ((D, 2 * D), (D, D), (D, D)))
+    dbkv, dbq = torch.full((2 * D,), nan, device="cuda"), torch.full((D,), nan, device="cuda")
+    ctx.gemm_group([{**args(a, dq, dwq, D), "b_colsum": ptr(dbq)}, {**args(mem, dkv, dwkv, 2 * D), "b_colsum": ptr(dbkv)},
+                    args(o, dy, dwox, D)])
+    singles = [torch.empty_like(t) for t in (dwkv, dwq, dwox)]
+    for (x, g, n_out), out in zip(((mem, dkv, 2 * D), (a, dq, D), (o, dy, D)), singles):
+        ctx.gemm(**args(x, g, out, n_out))
+    ctx.synchronize()
+    cols = np.array([0, 9, 255, 256, 1031, D - 1])
+    for x, g, got in ((mem, dkv, dwkv), (a, dq, dwq), (o, dy, dwox)):
+        _, want, _ = orc.linear_bwd(host(x[:, cols]), np.zeros((len(cols), g.shape[1])), host(g))
+        assert rel_l2(host(got[cols]), want) < 1e-5
+    assert rel_l2(host(dbkv), host(dkv).astype(np.float64).sum(axis=0)) < 1e-5
+    assert rel_l2(host(dbq), host(dq).astype(np.float64).sum(axis=0)) < 1e-5
+    for got, one in zip((dwkv, dwq, dwox), singles):
+        assert torch.isfinite(got).all() and rel_l2(host(got), host(one)) < 1e-6
+    with pytest.raises(pwb.PwError):                               # a bad member: nothing is launched
+        ctx.gemm_group([args(a, dq, dwq, D), {**args(mem, dkv, dwkv, 2 * D), "ldb": 8}, args(o, dy, dwox, D)])
+
+
 def test_one_layer_step_at_cfg3_layer_shapes_matches_oracle(orc):
     """The production kernels end to end against the oracle: one layer with cfg3's d_model / heads / FFN width and
     full sequence length, 2048 tokens, so that the forward, data-gradient and weight-gradient GEMMs all run on the
