@@ -430,13 +430,16 @@ typedef struct {
   int32_t B, Tq, Tk, H, hd;
   int32_t causal;
 } pw_mha_args;
-/* o: dense [B*Tq, H*hd] in `dtype`; lse: fp32 [B, H, Tq]. */
-pw_status pw_op_mha_fwd(pw_ctx* ctx, const pw_mha_args* args, void* o, float* lse);
+/* o: dense [B*Tq, H*hd] in `dtype`; lse: fp32 [B, H, Tq].  o_lo: null, or an array like o that receives what
+ * the rounding of O to `dtype` left over (O ~ o + o_lo).  Passed on to pw_op_mha_bwd it removes the one rounding
+ * the gradients of queries and keys are sensitive to: delta = rowsum(dO * O) is a common offset on a whole row of
+ * the score gradient, and keys with a large common component amplify an error in it to several per cent. */
+pw_status pw_op_mha_fwd(pw_ctx* ctx, const pw_mha_args* args, void* o, void* o_lo, float* lse);
 /* Gradients from o, dout [B*Tq, H*hd] and lse: dq rows lddq elements apart, dk and dv rows lddkv (the H*hd
- * features of every row are overwritten; packed outputs are pointers into one array).  delta: fp32 workspace
- * [B, H, Tq]. */
-pw_status pw_op_mha_bwd(pw_ctx* ctx, const pw_mha_args* args, const void* o, const void* dout, const float* lse,
-                        float* delta, void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv);
+ * features of every row are overwritten; packed outputs are pointers into one array).  o_lo: what the forward
+ * call wrote there, or null.  delta: fp32 workspace [B, H, Tq]. */
+pw_status pw_op_mha_bwd(pw_ctx* ctx, const pw_mha_args* args, const void* o, const void* o_lo, const void* dout,
+                        const float* lse, float* delta, void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv);
 /* Mean softmax cross-entropy over N rows of logits z [N, V] in `dtype` against tokens[b*(T+1)+t+1];
  * z is overwritten by dz = (softmax(z) - onehot)/N; loss: one fp32; row_loss: fp32 workspace [N]. */
 pw_status pw_op_softmax_xent(pw_ctx* ctx, int dtype, void* z, const int32_t* tokens, float* loss, float* row_loss,

@@ -157,8 +157,8 @@ _SIGS = {
     "pw_layernorm_bwd_ws_floats": (C.c_int64, [C.c_int, C.c_int]),
     "pw_op_attention_fwd": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 3 + [C.c_int] * 4),
     "pw_op_attention_bwd": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 6 + [C.c_int] * 4),
-    "pw_op_mha_fwd": (C.c_int, [C.c_void_p] * 4),
-    "pw_op_mha_bwd": (C.c_int, [C.c_void_p] * 7 + [C.c_int64, C.c_void_p, C.c_void_p, C.c_int64]),
+    "pw_op_mha_fwd": (C.c_int, [C.c_void_p] * 5),
+    "pw_op_mha_bwd": (C.c_int, [C.c_void_p] * 8 + [C.c_int64, C.c_void_p, C.c_void_p, C.c_int64]),
     "pw_op_softmax_xent": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 4 + [C.c_int] * 3),
     "pw_op_colsum": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 3 + [C.c_int64] * 2 + [C.c_int]),
     "pw_colsum_ws_floats": (C.c_int64, [C.c_int64, C.c_int64]),
@@ -393,12 +393,12 @@ class Context:
             setattr(a, k, v)
         self._check(lib().pw_op_gemm(self._h, C.byref(a)))
 
-    def mha_fwd(self, args: "MhaArgs", o: int, lse: int):
-        self._check(lib().pw_op_mha_fwd(self._h, C.byref(args), o, lse))
+    def mha_fwd(self, args: "MhaArgs", o: int, lse: int, o_lo: int = 0):
+        self._check(lib().pw_op_mha_fwd(self._h, C.byref(args), o, o_lo or None, lse))
 
     def mha_bwd(self, args: "MhaArgs", o: int, dout: int, lse: int, delta: int, dq: int, lddq: int, dk: int, dv: int,
-                lddkv: int):
-        self._check(lib().pw_op_mha_bwd(self._h, C.byref(args), o, dout, lse, delta, dq, lddq, dk, dv, lddkv))
+                lddkv: int, o_lo: int = 0):
+        self._check(lib().pw_op_mha_bwd(self._h, C.byref(args), o, o_lo or None, dout, lse, delta, dq, lddq, dk, dv, lddkv))
 
     def gemm_group(self, kws: list):
         arr = (GemmArgs * len(kws))()

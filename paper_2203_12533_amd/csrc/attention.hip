@@ -24,9 +24,10 @@ hipError_t launch_attention_fwd_mfma(hipStream_t s, const void* qkv, void* o, fl
 hipError_t launch_attention_bwd_mfma(hipStream_t s, const void* qkv, const void* o, const void* dout, const float* lse,
                                      float* delta, void* dqkv, int B, int T, int H, int hd);
 bool attention_mfma_supported(int T, int hd);
-hipError_t launch_attention_delta128(hipStream_t s, const void* o, const void* dout, float* delta, int B, int T, int H);
+hipError_t launch_attention_delta128(hipStream_t s, const void* o, const void* o_lo, const void* dout, float* delta, int B,
+                                     int T, int H);
 bool mha_dma_supported(const MhaArgs& a);
-hipError_t launch_mha_fwd_dma(hipStream_t s, const MhaArgs& a, void* o, float* lse);
+hipError_t launch_mha_fwd_dma(hipStream_t s, const MhaArgs& a, void* o, void* o_lo, float* lse);
 hipError_t launch_mha_dq_dkv_dma(hipStream_t s, const MhaArgs& a, const void* dout, const float* lse, const float* delta,
                                  void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv);
 
@@ -56,7 +57,8 @@ __device__ __forceinline__ void stage_rows(const T* __restrict__ src, int64_t ld
 
 // ---- forward: thread = query row ---------------------------------------------------------------------
 template <class T, int HD>
-__global__ __launch_bounds__(128) void attention_fwd_row_kernel(RowArgs<T> a, T* __restrict__ o, float* __restrict__ lse) {
+__global__ __launch_bounds__(128) void attention_fwd_row_kernel(RowArgs<T> a, T* __restrict__ o, T* __restrict__ o_lo,
+                                                                float* __restrict__ lse) {
   __shared__ float Ks[kTileRows * HD];
   __shared__ float Vs[kTileRows * HD];
   const int Tn = a.Tq, Tk = a.Tk, H = a.H;
@@ -106,6 +108,11 @@ __global__ __launch_bounds__(128) void attention_fwd_row_kernel(RowArgs<T> a, T*
     T* orow = o + ((int64_t)b * Tn + i) * d + h * HD;
 #pragma unroll
     for (int c = 0; c < HD; ++c) orow[c] = from_f32<T>(acc[c] * inv);
+    if (o_lo) {   // what the rounding of O left over (zero in fp32)
+      T* lrow = o_lo + ((int64_t)b * Tn + i) * d + h * HD;
+#pragma unroll
+      for (int c = 0; c < HD; ++c) lrow[c] = from_f32<T>(acc[c] * inv - to_f32(from_f32<T>(acc[c] * inv)));
+    }
     lse[(int64_t)bh * Tn + i] = m + logf(l);
   }
 }
@@ -113,8 +120,8 @@ __global__ __launch_bounds__(128) void attention_fwd_row_kernel(RowArgs<T> a, T*
 // ---- backward ------------------------------------------------------------------------------------------
 // delta[b,h,i] = sum_c dO[i,c] O[i,c]
 template <class T>
-__global__ void attention_delta_kernel(const T* __restrict__ o, const T* __restrict__ dout, float* __restrict__ delta,
-                                       int Tn, int H, int hd, int64_t total) {
+__global__ void attention_delta_kernel(const T* __restrict__ o, const T* __restrict__ o_lo, const T* __restrict__ dout,
+                                       float* __restrict__ delta, int Tn, int H, int hd, int64_t total) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // over (b, t, h)
   if (idx >= total) return;
   const int h = idx % H;
@@ -123,7 +130,8 @@ __global__ void attention_delta_kernel(const T* __restrict__ o, const T* __restr
   const T* po = o + n * (int64_t)H * hd + (int64_t)h * hd;
   const T* pd = dout + n * (int64_t)H * hd + (int64_t)h * hd;
   float s = 0.f;
-  for (int c = 0; c < hd; ++c) s += to_f32(po[c]) * to_f32(pd[c]);
+  const T* pl = o_lo ? o_lo + n * (int64_t)H * hd + (int64_t)h * hd : nullptr;
+  for (int c = 0; c < hd; ++c) s += (to_f32(po[c]) + (pl ? to_f32(pl[c]) : 0.f)) * to_f32(pd[c]);
   delta[(b * H + h) * Tn + t] = s;
 }
 
@@ -252,16 +260,16 @@ template <class T> static RowArgs<T> row_args(const MhaArgs& a) {
 }
 
 template <class T, int HD>
-static hipError_t fwd_row(hipStream_t s, const MhaArgs& a, void* o, float* lse) {
+static hipError_t fwd_row(hipStream_t s, const MhaArgs& a, void* o, void* o_lo, float* lse) {
   dim3 grid((a.Tq + 127) / 128, a.B * a.H);
-  attention_fwd_row_kernel<T, HD><<<grid, 128, 0, s>>>(row_args<T>(a), (T*)o, lse);
+  attention_fwd_row_kernel<T, HD><<<grid, 128, 0, s>>>(row_args<T>(a), (T*)o, (T*)o_lo, lse);
   return hipGetLastError();
 }
 template <class T, int HD>
-static hipError_t bwd_row(hipStream_t s, const MhaArgs& a, const void* o, const void* dout, const float* lse,
+static hipError_t bwd_row(hipStream_t s, const MhaArgs& a, const void* o, const void* o_lo, const void* dout, const float* lse,
                           float* delta, void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv) {
   const int64_t total = (int64_t)a.B * a.Tq * a.H;
-  attention_delta_kernel<T><<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const T*)o, (const T*)dout, delta, a.Tq, a.H, HD, total);
+  attention_delta_kernel<T><<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const T*)o, (const T*)o_lo, (const T*)dout, delta, a.Tq, a.H, HD, total);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const RowArgs<T> r = row_args<T>(a);
@@ -300,34 +308,40 @@ static bool is_packed_causal(const MhaArgs& a) {
          (const char*)a.v == (const char*)a.q + 2 * d * es;
 }
 
-hipError_t launch_mha_fwd(hipStream_t s, const MhaArgs& a, void* o, float* lse) {
+hipError_t launch_mha_fwd(hipStream_t s, const MhaArgs& a, void* o, void* o_lo, float* lse) {
   if (!mha_args_ok(a) || !o || !lse) return hipErrorInvalidValue;
-  if (use_dma_kernels() && mha_dma_supported(a) && !((uintptr_t)o & 15)) return launch_mha_fwd_dma(s, a, o, lse);
-  if (a.dtype == kBF16 && is_packed_causal(a) && attention_mfma_supported(a.Tq, a.hd))
+  if (use_dma_kernels() && mha_dma_supported(a) && !(((uintptr_t)o | (uintptr_t)o_lo) & 15)) return launch_mha_fwd_dma(s, a, o, o_lo, lse);
+  if (a.dtype == kBF16 && is_packed_causal(a) && attention_mfma_supported(a.Tq, a.hd)) {
+    if (o_lo) {   // these kernels keep no remainder: an all-zero one says so to the backward pass
+      const int64_t n = (int64_t)a.B * a.Tq * a.H * a.hd;   // bf16 elements, an even number
+      const hipError_t e = launch_fill_f32(s, (float*)o_lo, n / 2, 0.f);
+      if (e != hipSuccess) return e;
+    }
     return launch_attention_fwd_mfma(s, a.q, o, lse, a.B, a.Tq, a.H, a.hd);
-  if (a.dtype == kF32) return a.hd == 64 ? fwd_row<float, 64>(s, a, o, lse) : fwd_row<float, 128>(s, a, o, lse);
-  return a.hd == 64 ? fwd_row<bf16, 64>(s, a, o, lse) : fwd_row<bf16, 128>(s, a, o, lse);
+  }
+  if (a.dtype == kF32) return a.hd == 64 ? fwd_row<float, 64>(s, a, o, o_lo, lse) : fwd_row<float, 128>(s, a, o, o_lo, lse);
+  return a.hd == 64 ? fwd_row<bf16, 64>(s, a, o, o_lo, lse) : fwd_row<bf16, 128>(s, a, o, o_lo, lse);
 }
 
-hipError_t launch_mha_bwd(hipStream_t s, const MhaArgs& a, const void* o, const void* dout, const float* lse,
-                          float* delta, void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv) {
+hipError_t launch_mha_bwd(hipStream_t s, const MhaArgs& a, const void* o, const void* o_lo, const void* dout,
+                          const float* lse, float* delta, void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv) {
   if (!mha_args_ok(a) || !o || !dout || !lse || !delta || !dq || !dk || !dv) return hipErrorInvalidValue;
   const int64_t d = (int64_t)a.H * a.hd;
   if (lddq < d || lddkv < d) return hipErrorInvalidValue;
-  if (use_dma_kernels() && mha_dma_supported(a) && !(((uintptr_t)o | (uintptr_t)dout) & 15)) {
-    hipError_t e = launch_attention_delta128(s, o, dout, delta, a.B, a.Tq, a.H);
+  if (use_dma_kernels() && mha_dma_supported(a) && !(((uintptr_t)o | (uintptr_t)o_lo | (uintptr_t)dout) & 15)) {
+    hipError_t e = launch_attention_delta128(s, o, o_lo, dout, delta, a.B, a.Tq, a.H);
     if (e != hipSuccess) return e;
     return launch_mha_dq_dkv_dma(s, a, dout, lse, delta, dq, lddq, dk, dv, lddkv);
   }
   const size_t es = a.dtype == kBF16 ? 2 : 4;
   const bool packed_out = lddq == 3 * d && lddkv == 3 * d && (char*)dk == (char*)dq + d * es && (char*)dv == (char*)dq + 2 * d * es;
   if (a.dtype == kBF16 && is_packed_causal(a) && packed_out && attention_mfma_supported(a.Tq, a.hd))
-    return launch_attention_bwd_mfma(s, a.q, o, dout, lse, delta, dq, a.B, a.Tq, a.H, a.hd);
+    return launch_attention_bwd_mfma(s, a.q, o, dout, lse, delta, dq, a.B, a.Tq, a.H, a.hd);   // (its forward left o_lo zero)
   if (a.dtype == kF32)
-    return a.hd == 64 ? bwd_row<float, 64>(s, a, o, dout, lse, delta, dq, lddq, dk, dv, lddkv)
-                      : bwd_row<float, 128>(s, a, o, dout, lse, delta, dq, lddq, dk, dv, lddkv);
-  return a.hd == 64 ? bwd_row<bf16, 64>(s, a, o, dout, lse, delta, dq, lddq, dk, dv, lddkv)
-                    : bwd_row<bf16, 128>(s, a, o, dout, lse, delta, dq, lddq, dk, dv, lddkv);
+    return a.hd == 64 ? bwd_row<float, 64>(s, a, o, o_lo, dout, lse, delta, dq, lddq, dk, dv, lddkv)
+                      : bwd_row<float, 128>(s, a, o, o_lo, dout, lse, delta, dq, lddq, dk, dv, lddkv);
+  return a.hd == 64 ? bwd_row<bf16, 64>(s, a, o, o_lo, dout, lse, delta, dq, lddq, dk, dv, lddkv)
+                    : bwd_row<bf16, 128>(s, a, o, o_lo, dout, lse, delta, dq, lddq, dk, dv, lddkv);
 }
 
 static MhaArgs packed_args(int dtype, const void* qkv, int B, int T, int H, int hd) {
@@ -340,7 +354,7 @@ static MhaArgs packed_args(int dtype, const void* qkv, int B, int T, int H, int 
 hipError_t launch_attention_fwd(hipStream_t s, int dtype, const void* qkv, void* o, float* lse, int B, int T, int H,
                                 int hd) {
   if (!qkv || (dtype != kF32 && dtype != kBF16)) return hipErrorInvalidValue;
-  return launch_mha_fwd(s, packed_args(dtype, qkv, B, T, H, hd), o, lse);
+  return launch_mha_fwd(s, packed_args(dtype, qkv, B, T, H, hd), o, nullptr, lse);
 }
 
 hipError_t launch_attention_bwd(hipStream_t s, int dtype, const void* qkv, const void* o, const void* dout,
@@ -349,7 +363,7 @@ hipError_t launch_attention_bwd(hipStream_t s, int dtype, const void* qkv, const
   const int64_t d = (int64_t)H * hd;
   const size_t es = dtype == kBF16 ? 2 : 4;
   char* g = (char*)dqkv;
-  return launch_mha_bwd(s, packed_args(dtype, qkv, B, T, H, hd), o, dout, lse, delta, g, 3 * d, g + d * es, g + 2 * d * es, 3 * d);
+  return launch_mha_bwd(s, packed_args(dtype, qkv, B, T, H, hd), o, nullptr, dout, lse, delta, g, 3 * d, g + d * es, g + 2 * d * es, 3 * d);
 }
 
 }  // namespace pw

@@ -81,4 +81,24 @@ __device__ __forceinline__ void store_row(bf16* __restrict__ dst, const f32x16* 
 }
 
 
+// The same, plus what the rounding left over to a second row (lo): value ~ bf16(dst) + bf16(lo).
+template <int HD>
+__device__ __forceinline__ void store_row_split(bf16* __restrict__ dst, bf16* __restrict__ lo, const f32x16* acc, float scale) {
+  const int half = (threadIdx.x & 63) >> 5;
+#pragma unroll
+  for (int cb = 0; cb < HD / 32; ++cb)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      bf16x4 o, r;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float v = acc[cb][q * 4 + e] * scale;
+        o[e] = (bf16)v;
+        r[e] = (bf16)(v - (float)o[e]);
+      }
+      *reinterpret_cast<bf16x4*>(dst + cb * 32 + q * 8 + half * 4) = o;
+      *reinterpret_cast<bf16x4*>(lo + cb * 32 + q * 8 + half * 4) = r;
+    }
+}
+
 }  // namespace pw

@@ -134,7 +134,8 @@ __device__ __forceinline__ void wait_and_sync() {
 // forward: block = 128 queries of one (batch, head); wave = 32 queries; key/value tiles of 64
 // ===================================================================================================
 template <bool CAUSAL>
-__global__ __launch_bounds__(kNT, 2) void attn_fwd_dma_kernel(MhaDev a, bf16* __restrict__ o, float* __restrict__ lse) {
+__global__ __launch_bounds__(kNT, 2) void attn_fwd_dma_kernel(MhaDev a, bf16* __restrict__ o, bf16* __restrict__ o_lo,
+                                                              float* __restrict__ lse) {
   constexpr int BKV = 64;
   constexpr int kTile = BKV * HD;                       // elements per K (or V) tile
   extern __shared__ __attribute__((aligned(1024))) bf16 smem[];         // [stage][K | V], 64 KiB
@@ -227,7 +228,11 @@ __global__ __launch_bounds__(kNT, 2) void attn_fwd_dma_kernel(MhaDev a, bf16* __
   }
   l += __shfl_xor(l, 32, 64);
   if (query < Tq) {
-    store_row<HD>(o + ((int64_t)b * Tq + query) * d + h * HD, acc, 1.f / l);
+    const int64_t row = ((int64_t)b * Tq + query) * d + h * HD;
+    if (o_lo)
+      store_row_split<HD>(o + row, o_lo + row, acc, 1.f / l);
+    else
+      store_row<HD>(o + row, acc, 1.f / l);
     if (half == 0) lse[(int64_t)bh * Tq + query] = (m + __builtin_amdgcn_logf(l)) * kLn2;
   }
 }
@@ -466,14 +471,14 @@ bool mha_dma_supported(const MhaArgs& a) {
   return a.ldq % 8 == 0 && a.ldkv % 8 == 0;
 }
 
-hipError_t launch_mha_fwd_dma(hipStream_t s, const MhaArgs& a, void* o, float* lse) {
+hipError_t launch_mha_fwd_dma(hipStream_t s, const MhaArgs& a, void* o, void* o_lo, float* lse) {
   hipError_t e = attention_dma_init();
   if (e != hipSuccess) return e;
   const int grid = ((a.Tq + 127) / 128) * a.B * a.H;          // (problem, block) pairs, see xcd_block_map
   if (a.causal)
-    attn_fwd_dma_kernel<true><<<grid, kNT, kSmemTiles, s>>>(dev_of(a), (bf16*)o, lse);
+    attn_fwd_dma_kernel<true><<<grid, kNT, kSmemTiles, s>>>(dev_of(a), (bf16*)o, (bf16*)o_lo, lse);
   else
-    attn_fwd_dma_kernel<false><<<grid, kNT, kSmemTiles, s>>>(dev_of(a), (bf16*)o, lse);
+    attn_fwd_dma_kernel<false><<<grid, kNT, kSmemTiles, s>>>(dev_of(a), (bf16*)o, (bf16*)o_lo, lse);
   return hipGetLastError();
 }
 

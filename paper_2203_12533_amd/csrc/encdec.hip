@@ -9,6 +9,10 @@
 // gradient delivers for free (its `dsum` output) - so each sub-block's backward takes the address of the bias
 // gradient of the sub-block below it.
 // Precision as in lm.hip: bf16 operands, fp32 residual stream, statistics, accumulators, gradients and state.
+// One thing more: every attention keeps, next to its bf16 output, what the rounding left over (o_lo), so that the
+// backward pass's delta = rowsum(dO * O) is exact to fp32.  Here the query projection of the cross-attention has a
+// weight tensor of its own, and at initialisation (near-uniform attention over keys that share a common
+// component) that one rounding alone put 3 to 4 per cent of error into its gradient.
 #include "encdec.hpp"
 
 #include <algorithm>
@@ -85,6 +89,7 @@ size_t plan(EncDec* m, unsigned char* base) {
     a.a = cv.take<void>(N * d * es);
     a.qkv = cv.take<void>(N * 3 * d * es);
     a.o = cv.take<void>(N * d * es);
+    a.o_lo = c.bf16 ? cv.take<void>(N * d * es) : nullptr;
   };
   auto ffn = [&](EncDec::FfnActs& a, size_t N) {
     a.x_in = cv.take<float>(N * d * 4);
@@ -114,6 +119,7 @@ size_t plan(EncDec* m, unsigned char* base) {
     L.ca.q = cv.take<void>(Nt * d * es);
     L.ca.kv = cv.take<void>(Ns * 2 * d * es);
     L.ca.o = cv.take<void>(Nt * d * es);
+    L.ca.o_lo = c.bf16 ? cv.take<void>(Nt * d * es) : nullptr;
     ffn(L.ff, Nt);
   }
   m->dec_x_out = cv.take<float>(Nt * d * 4);
@@ -157,7 +163,7 @@ hipError_t self_fwd(EncDec* m, size_t e, const EncDec::SelfActs& A, float* x_out
   const size_t es = m->bf16 ? 2 : 4;
   const char* qkv = (const char*)A.qkv;
   const MhaArgs a{dt, qkv, qkv + d * es, qkv + 2 * d * es, 3 * (int64_t)d, 3 * (int64_t)d, c.batch, T, T, c.n_head, m->hd(), causal};
-  PW_TRY(launch_mha_fwd(m->stream, a, A.o, A.lse), "self-attention fwd");
+  PW_TRY(launch_mha_fwd(m->stream, a, A.o, A.o_lo, A.lse), "self-attention fwd");
   PW_TRY(gemm_fwd(m, A.o, e + 4, m->wp(e + 5), N, d, d, kEpiBiasResidual, kF32, A.x_in, x_out, nullptr), "out-proj gemm");
   return hipSuccess;
 }
@@ -173,7 +179,7 @@ hipError_t self_bwd(EncDec* m, size_t e, const EncDec::SelfActs& A, GradStream& 
   const char* qkv = (const char*)A.qkv;
   char* dqkv = (char*)m->d_qkv;
   const MhaArgs a{dt, qkv, qkv + d * es, qkv + 2 * d * es, 3 * (int64_t)d, 3 * (int64_t)d, c.batch, T, T, c.n_head, m->hd(), causal};
-  PW_TRY(launch_mha_bwd(m->stream, a, A.o, m->d_small, A.lse, m->delta, dqkv, 3 * (int64_t)d, dqkv + d * es, dqkv + 2 * d * es,
+  PW_TRY(launch_mha_bwd(m->stream, a, A.o, A.o_lo, m->d_small, A.lse, m->delta, dqkv, 3 * (int64_t)d, dqkv + d * es, dqkv + 2 * d * es,
                         3 * (int64_t)d), "self-attention bwd");
   // (dy, the residual gradient in operand form, stays intact until the LayerNorm backward below rewrites it)
   {
@@ -199,7 +205,7 @@ hipError_t cross_fwd(EncDec* m, size_t e, const EncDec::CrossActs& A, float* y_o
   const size_t es = m->bf16 ? 2 : 4;
   const char* kv = (const char*)A.kv;
   const MhaArgs a{dt, A.q, kv, kv + d * es, (int64_t)d, 2 * (int64_t)d, c.batch, c.tgt_len, c.src_len, c.n_head, m->hd(), 0};
-  PW_TRY(launch_mha_fwd(m->stream, a, A.o, A.lse), "cross-attention fwd");
+  PW_TRY(launch_mha_fwd(m->stream, a, A.o, A.o_lo, A.lse), "cross-attention fwd");
   PW_TRY(gemm_fwd(m, A.o, e + 6, m->wp(e + 7), Nt, d, d, kEpiBiasResidual, kF32, A.x_in, y_out, nullptr), "cross out-proj gemm");
   return hipSuccess;
 }
@@ -214,7 +220,7 @@ hipError_t cross_bwd(EncDec* m, size_t e, const EncDec::CrossActs& A, GradStream
   const char* kv = (const char*)A.kv;
   char* dkv = (char*)m->d_qkv;
   const MhaArgs a{dt, A.q, kv, kv + d * es, (int64_t)d, 2 * (int64_t)d, c.batch, c.tgt_len, c.src_len, c.n_head, m->hd(), 0};
-  PW_TRY(launch_mha_bwd(m->stream, a, A.o, m->d_small, A.lse, m->delta, m->d_q, (int64_t)d, dkv, dkv + d * es, 2 * (int64_t)d),
+  PW_TRY(launch_mha_bwd(m->stream, a, A.o, A.o_lo, m->d_small, A.lse, m->delta, m->d_q, (int64_t)d, dkv, dkv + d * es, 2 * (int64_t)d),
          "cross-attention bwd");
   {
     // three weight gradients that each cover a quarter to a half of the chip: one launch

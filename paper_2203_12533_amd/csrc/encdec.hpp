@@ -10,8 +10,8 @@ struct EncDec : ModelBase {
   pw_encdec_config cfg;
 
   // activations kept for the backward pass, one set per residual sub-block
-  struct SelfActs { float *x_in, *lse, *mean, *rstd; void *a, *qkv, *o; };
-  struct CrossActs { float *x_in, *lse, *mean, *rstd; void *a, *q, *kv, *o; };
+  struct SelfActs { float *x_in, *lse, *mean, *rstd; void *a, *qkv, *o, *o_lo; };
+  struct CrossActs { float *x_in, *lse, *mean, *rstd; void *a, *q, *kv, *o, *o_lo; };
   struct FfnActs { float *x_in, *mean, *rstd; void *mm, *u, *h; };
   struct EncLayer { SelfActs sa; FfnActs ff; };
   struct DecLayer { SelfActs sa; CrossActs ca; FfnActs ff; };

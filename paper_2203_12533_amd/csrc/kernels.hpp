@@ -73,11 +73,15 @@ struct MhaArgs {
   int causal;
 };
 // o: dense [B*Tq, H*hd] in `dtype`; lse: [B, H, Tq] row log-sum-exp (kept for the backward pass).
-hipError_t launch_mha_fwd(hipStream_t s, const MhaArgs& a, void* o, float* lse);
+// o_lo (optional, same shape and type as o): receives what the rounding of O to `dtype` left over; handed to
+// launch_mha_bwd it makes the backward pass's delta = rowsum(dO * O) as exact as fp32 allows.  Without it the
+// bf16 rounding of O becomes a common offset on every dS of a row, which keys that share a large common
+// component turn into an error of several per cent in dq and dk.
+hipError_t launch_mha_fwd(hipStream_t s, const MhaArgs& a, void* o, void* o_lo, float* lse);
 // dq rows lddq elements apart, dk and dv rows lddkv; delta: [B, H, Tq] scratch.  Every feature of every row of
 // dq, dk, dv is overwritten.
-hipError_t launch_mha_bwd(hipStream_t s, const MhaArgs& a, const void* o, const void* dout, const float* lse,
-                          float* delta, void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv);
+hipError_t launch_mha_bwd(hipStream_t s, const MhaArgs& a, const void* o, const void* o_lo, const void* dout,
+                          const float* lse, float* delta, void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv);
 // Causal self-attention over packed qkv [B*T, 3d] (the two calls above with the packed layout).
 hipError_t launch_attention_fwd(hipStream_t s, int dtype, const void* qkv, void* o, float* lse, int B, int T, int H,
                                 int hd);

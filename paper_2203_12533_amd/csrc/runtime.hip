@@ -2060,14 +2060,14 @@ pw_status pw_op_attention_bwd(pw_ctx* c, int dtype, const void* qkv, const void*
 static MhaArgs mha_args_of(const pw_mha_args* a) {
   return MhaArgs{a->dtype, a->q, a->k, a->v, a->ldq, a->ldkv, a->B, a->Tq, a->Tk, a->H, a->hd, a->causal};
 }
-pw_status pw_op_mha_fwd(pw_ctx* c, const pw_mha_args* a, void* o, float* lse) {
+pw_status pw_op_mha_fwd(pw_ctx* c, const pw_mha_args* a, void* o, void* o_lo, float* lse) {
   if (!a) return PW_ERR_INVALID;
-  PW_OP(c, launch_mha_fwd(c->exec, mha_args_of(a), o, lse));
+  PW_OP(c, launch_mha_fwd(c->exec, mha_args_of(a), o, o_lo, lse));
 }
-pw_status pw_op_mha_bwd(pw_ctx* c, const pw_mha_args* a, const void* o, const void* dout, const float* lse, float* delta,
-                        void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv) {
+pw_status pw_op_mha_bwd(pw_ctx* c, const pw_mha_args* a, const void* o, const void* o_lo, const void* dout, const float* lse,
+                        float* delta, void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv) {
   if (!a) return PW_ERR_INVALID;
-  PW_OP(c, launch_mha_bwd(c->exec, mha_args_of(a), o, dout, lse, delta, dq, lddq, dk, dv, lddkv));
+  PW_OP(c, launch_mha_bwd(c->exec, mha_args_of(a), o, o_lo, dout, lse, delta, dq, lddq, dk, dv, lddkv));
 }
 pw_status pw_op_softmax_xent(pw_ctx* c, int dtype, void* z, const int32_t* tokens, float* loss, float* row_loss, int B, int T, int V) {
   PW_OP(c, launch_softmax_xent(c->exec, dtype, z, tokens, loss, row_loss, B, T, V));

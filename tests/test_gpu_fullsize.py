@@ -262,3 +262,38 @@ def test_one_layer_step_at_cfg3_layer_shapes_matches_oracle(orc):
             assert err < 2e-2, (k, err)
         print("worst gradient error", worst)
         model.close()
+
+
+def test_one_layer_encoder_decoder_step_at_full_layer_width_matches_oracle(orc):
+    """The encoder-decoder step end to end at the width of the measured workload: one encoder and one decoder layer
+    with d_model 2048 / 16 heads / FFN 8192, 2 x 1024 source and 2 x 512 target positions, so that the ring-buffered
+    GEMM kernel, the three-way weight-gradient launch of the cross-attention sub-block with its fused bias
+    gradients, the fp32-accumulating data-gradient GEMM into the encoder output's gradient and the head_dim-128
+    attention kernels in their three roles (unmasked 1024 x 1024, causal 512 x 512, 512 queries over 1024 keys) all
+    run on real shapes.  Loss and every gradient tensor are compared (vocabulary cut to 8192 for the oracle's sake)."""
+    cfg = I.EncDecConfig(1, 1, D, H, F, 8192, 1024, 512, 2, bf16=True, optimizer="adam", lr=1e-4)
+    src, tgt = I.encdec_tokens(cfg)
+    rng = np.random.default_rng(21)
+    params = {}
+    for name, shape, kind in I.encdec_param_shapes(cfg):
+        a = rng.standard_normal(int(np.prod(shape)), dtype=np.float32) * np.float32(cfg.init_std)
+        if kind == "gain":
+            a += np.float32(1.0)
+        params[name] = I.round_to_bf16(a).reshape(shape)       # biases and gains perturbed too
+    ref = orc.encdec_train_step(cfg, params, src, tgt)
+    with pwb.Context(0) as ctx:
+        model = ctx.encdec(cfg)
+        model.load_params(params)
+        step = model.compile_train_step()
+        fs, ft = ctx.future_from_host(src), ctx.future_from_host(tgt)
+        (fl,) = ctx.run_fn(step, [fs, ft], 1)
+        loss = float(ctx.await_(fl)[0])
+        assert abs(loss - ref["loss"]) / abs(ref["loss"]) < 2e-2, (loss, ref["loss"])
+        grads = model.export_all(pwb.PW_GRADS, params)
+        worst = ("", 0.0)
+        for k, g in grads.items():
+            err = rel_l2(g, ref["grads"][k])
+            worst = max(worst, (k, err), key=lambda t: t[1])
+            assert err < 2e-2, (k, err)
+        print("worst gradient error", worst)
+        model.close()
