@@ -12,17 +12,17 @@
 // textbook definition as scalar loops.
 //
 // Readings frozen here (the paper is silent on all of them):
-//   R11 source tokens are [B, Ts], all visible to every encoder position; target tokens are
+//   E1 source tokens are [B, Ts], all visible to every encoder position; target tokens are
 //       [B, Tt+1]: decoder inputs = columns 0..Tt-1, targets = columns 1..Tt; loss = mean over the
 //       B*Tt target positions.
-//   R12 encoder layer: x += SelfAttn_full(LN1 x) Wo + bo;  x += FFN(LN2 x).
+//   E2 encoder layer: x += SelfAttn_full(LN1 x) Wo + bo;  x += FFN(LN2 x).
 //       decoder layer: y += SelfAttn_causal(LN1 y) Wo + bo;  y += CrossAttn(LNx y, mem) Wox + box;
 //       y += FFN(LN2 y).  mem = LNf_enc(encoder stack output); logits = LNf_dec(y) Wh.
-//   R13 cross-attention: queries q = LNx(y) Wq + bq from the decoder, keys and values
+//   E3 cross-attention: queries q = LNx(y) Wq + bq from the decoder, keys and values
 //       [K | V] = mem Wkv + bkv from the encoder output, scale 1/sqrt(head_dim), no mask.
-//   R14 encoder and decoder have their own token and position tables; the head is untied.
+//   E4 encoder and decoder have their own token and position tables; the head is untied.
 //
-// Parity pins (tests/test_oracle_pins.py): attention closed forms without a mask (zero queries give
+// Parity pins (tests/test_oracle_pins_encdec.py): attention closed forms without a mask (zero queries give
 // the mean of all values; one key returns its value; key order does not matter); agreement with a
 // softmax written with library routines; central finite differences of the loss for every parameter
 // family; with Wox = box = 0 the decoder is the pinned decoder-only model, loss and gradients; a
@@ -33,7 +33,7 @@
 
 namespace oracle {
 
-// ---- multi-head attention of Tq queries over Tk keys (R6, R13) -----------------------------------
+// ---- multi-head attention of Tq queries over Tk keys (R6, E3) -----------------------------------
 
 // q, k, v point at (batch 0, row 0, feature 0); rows are ldq (q) / ldkv (k, v) elements apart, batch b
 // starts at row b*Tq (q) / b*Tk (k, v); head h owns features h*hd .. (h+1)*hd of a row.
@@ -292,7 +292,7 @@ void ffn_block_bwd(const S* P, S* G, const std::vector<ParamEntry>& tab, size_t 
   for (size_t i = 0; i < dx.size(); ++i) dx[i] += dxl[i];
 }
 
-// One full train step (R11, R12).  src [B, Ts], tgt [B, Tt+1].  P is updated in place when opt.kind != 0;
+// One full train step (E1, E2).  src [B, Ts], tgt [B, Tt+1].  P is updated in place when opt.kind != 0;
 // G receives the gradients (every parameter is used exactly once, so each entry is written once);
 // logits (optional) [B*Tt, V]; do_bwd = 0 stops after the loss.
 template <class S>
