@@ -537,27 +537,27 @@ def encdec_step_flops(cfg) -> float:
     return lib().pw_encdec_step_flops(C.byref(c))
 
 
-class EncDec:
-    """pw_encdec: parameters, optimiser state and the static activation plan of one encoder-decoder model."""
+class _ParamModel:
+    """What pw_model and pw_encdec have in common: named fp32 parameter tensors with gradients and optimiser state
+    that can be imported and exported one tensor at a time.  `_prefix` names the C entry points."""
+    _prefix = ""
 
-    def __init__(self, ctx: "Context", cfg):
-        self.ctx, self.cfg = ctx, cfg
-        self._h = C.c_void_p()
-        c = encdec_config_c(cfg)
-        ctx._check(lib().pw_encdec_create(ctx.handle, C.byref(c), C.byref(self._h)))
-        ctx._models.append(self)
+    def _fn(self, name: str):
+        return getattr(lib(), f"{self._prefix}_{name}")
+
+    def _read_param_table(self):
         self.names, self.numel = [], {}
         name = C.create_string_buffer(64)
         n = C.c_int64()
-        for i in range(lib().pw_encdec_param_count(self._h)):
-            lib().pw_encdec_param_info(self._h, i, name, 64, C.byref(n))
+        for i in range(self._fn("param_count")(self._h)):
+            self._fn("param_info")(self._h, i, name, 64, C.byref(n))
             self.names.append(name.value.decode())
             self.numel[self.names[-1]] = n.value
         self._index = {k: i for i, k in enumerate(self.names)}
 
     def close(self):
         if self._h is not None:
-            lib().pw_encdec_destroy(self._h)
+            self._fn("destroy")(self._h)
             self._h = None
             if self in self.ctx._models:
                 self.ctx._models.remove(self)
@@ -565,10 +565,10 @@ class EncDec:
     def import_(self, part: int, name: str, arr: np.ndarray):
         arr = np.ascontiguousarray(arr, dtype=np.float32)
         assert arr.size == self.numel[name], (name, arr.size, self.numel[name])
-        self.ctx._check(lib().pw_encdec_import(self._h, part, self._index[name], arr.ctypes.data_as(C.c_void_p), 0))
+        self.ctx._check(self._fn("import")(self._h, part, self._index[name], arr.ctypes.data_as(C.c_void_p), 0))
 
     def import_device(self, part: int, name: str, ptr: int):
-        self.ctx._check(lib().pw_encdec_import(self._h, part, self._index[name], C.c_void_p(ptr), 1))
+        self.ctx._check(self._fn("import")(self._h, part, self._index[name], C.c_void_p(ptr), 1))
 
     def load_params(self, params: dict):
         for k in self.names:
@@ -576,11 +576,24 @@ class EncDec:
 
     def export(self, part: int, name: str, shape=None) -> np.ndarray:
         out = np.empty(self.numel[name], dtype=np.float32)
-        self.ctx._check(lib().pw_encdec_export(self._h, part, self._index[name], out.ctypes.data_as(C.c_void_p)))
+        self.ctx._check(self._fn("export")(self._h, part, self._index[name], out.ctypes.data_as(C.c_void_p)))
         return out.reshape(shape) if shape is not None else out
 
     def export_all(self, part: int, like: dict) -> dict:
         return {k: self.export(part, k, like[k].shape) for k in self.names}
+
+
+class EncDec(_ParamModel):
+    """pw_encdec: parameters, optimiser state and the static activation plan of one encoder-decoder model."""
+    _prefix = "pw_encdec"
+
+    def __init__(self, ctx: "Context", cfg):
+        self.ctx, self.cfg = ctx, cfg
+        self._h = C.c_void_p()
+        c = encdec_config_c(cfg)
+        ctx._check(lib().pw_encdec_create(ctx.handle, C.byref(c), C.byref(self._h)))
+        ctx._models.append(self)
+        self._read_param_table()
 
     def export_activation(self, name: str, numel: int) -> np.ndarray:
         out = np.empty(numel, dtype=np.float32)
@@ -595,8 +608,9 @@ class EncDec:
                                    [make_spec(PW_F32, (1,))], bytes(params))
 
 
-class Model:
+class Model(_ParamModel):
     """pw_model: parameters, optimiser state and the static activation plan of one LM (or pipeline stage)."""
+    _prefix = "pw_model"
 
     def __init__(self, ctx: Context, cfg):
         self.ctx, self.cfg = ctx, cfg
@@ -604,41 +618,7 @@ class Model:
         c = lm_config_c(cfg)
         ctx._check(lib().pw_model_create(ctx.handle, C.byref(c), C.byref(self._h)))
         ctx._models.append(self)
-        self.names, self.numel = [], {}
-        name = C.create_string_buffer(64)
-        n = C.c_int64()
-        for i in range(lib().pw_model_param_count(self._h)):
-            lib().pw_model_param_info(self._h, i, name, 64, C.byref(n))
-            self.names.append(name.value.decode())
-            self.numel[self.names[-1]] = n.value
-        self._index = {k: i for i, k in enumerate(self.names)}
-
-    def close(self):
-        if self._h is not None:
-            lib().pw_model_destroy(self._h)
-            self._h = None
-            if self in self.ctx._models:
-                self.ctx._models.remove(self)
-
-    def import_(self, part: int, name: str, arr: np.ndarray):
-        arr = np.ascontiguousarray(arr, dtype=np.float32)
-        assert arr.size == self.numel[name], (name, arr.size, self.numel[name])
-        self.ctx._check(lib().pw_model_import(self._h, part, self._index[name], arr.ctypes.data_as(C.c_void_p), 0))
-
-    def import_device(self, part: int, name: str, ptr: int):
-        self.ctx._check(lib().pw_model_import(self._h, part, self._index[name], C.c_void_p(ptr), 1))
-
-    def load_params(self, params: dict):
-        for k in self.names:
-            self.import_(PW_PARAMS, k, params[k])
-
-    def export(self, part: int, name: str, shape=None) -> np.ndarray:
-        out = np.empty(self.numel[name], dtype=np.float32)
-        self.ctx._check(lib().pw_model_export(self._h, part, self._index[name], out.ctypes.data_as(C.c_void_p)))
-        return out.reshape(shape) if shape is not None else out
-
-    def export_all(self, part: int, like: dict) -> dict:
-        return {k: self.export(part, k, like[k].shape) for k in self.names}
+        self._read_param_table()
 
     def export_activation(self, name: str, numel: int, microbatch: int = 0) -> np.ndarray:
         out = np.empty(numel, dtype=np.float32)

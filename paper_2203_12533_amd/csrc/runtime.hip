@@ -1817,16 +1817,7 @@ pw_status pw_model_destroy(pw_model* pm) {
   return PW_OK;
 }
 
-int64_t pw_model_param_count(pw_model* pm) { return pm ? (int64_t)pm->impl->params.size() : -1; }
-
-pw_status pw_model_param_info(pw_model* pm, int64_t idx, char* name, int cap, int64_t* numel) {
-  if (!pm || idx < 0 || idx >= (int64_t)pm->impl->params.size()) return PW_ERR_INVALID;
-  const ParamInfo& p = pm->impl->params[idx];
-  if (name && cap > 0) snprintf(name, cap, "%s", p.name.c_str());
-  if (numel) *numel = p.numel;
-  return PW_OK;
-}
-
+// Parameter-table access shared by the two kinds of model (both keep their state in a ModelBase).
 static float* part_base(ModelBase* m, int part) {
   switch (part) {
     case PW_PARAMS: return m->w;
@@ -1836,33 +1827,61 @@ static float* part_base(ModelBase* m, int part) {
   }
   return nullptr;
 }
-
-pw_status pw_model_import(pw_model* pm, int part, int64_t idx, const float* src, int src_on_device) {
-  if (!pm || !src || idx < 0 || idx >= (int64_t)pm->impl->params.size()) return PW_ERR_INVALID;
-  pw_ctx* c = pm->ctx;
-  Model* m = pm->impl;
+static pw_status state_param_info(ModelBase* m, int64_t idx, char* name, int cap, int64_t* numel) {
+  if (idx < 0 || idx >= (int64_t)m->params.size()) return PW_ERR_INVALID;
+  const ParamInfo& p = m->params[idx];
+  if (name && cap > 0) snprintf(name, cap, "%s", p.name.c_str());
+  if (numel) *numel = p.numel;
+  return PW_OK;
+}
+static pw_status state_import(pw_ctx* c, ModelBase* m, int part, int64_t idx, const float* src, int src_on_device) {
+  if (!src || idx < 0 || idx >= (int64_t)m->params.size()) return PW_ERR_INVALID;
   float* base = part_base(m, part);
   if (!base) return fail(c, PW_ERR_INVALID, "this model has no such part");
   const ParamInfo& p = m->params[idx];
   PW_HIP(c, hipMemcpyAsync(base + p.offset, src, (size_t)p.numel * 4, src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, c->exec));
   if (part == PW_PARAMS) {
-    hipError_t e = model_refresh_lowp(m, p.offset, p.numel);
+    hipError_t e = model_state_refresh_lowp(m, p.offset, p.numel);
     if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "bf16 refresh: %s", hipGetErrorString(e));
   }
   PW_HIP(c, hipStreamSynchronize(c->exec));
   return PW_OK;
 }
-
-pw_status pw_model_export(pw_model* pm, int part, int64_t idx, float* dst) {
-  if (!pm || !dst || idx < 0 || idx >= (int64_t)pm->impl->params.size()) return PW_ERR_INVALID;
-  pw_ctx* c = pm->ctx;
-  Model* m = pm->impl;
+static pw_status state_export(pw_ctx* c, ModelBase* m, int part, int64_t idx, float* dst) {
+  if (!dst || idx < 0 || idx >= (int64_t)m->params.size()) return PW_ERR_INVALID;
   float* base = part_base(m, part);
   if (!base) return fail(c, PW_ERR_INVALID, "this model has no such part");
   const ParamInfo& p = m->params[idx];
   PW_HIP(c, hipStreamSynchronize(c->exec));
   PW_HIP(c, hipMemcpy(dst, base + p.offset, (size_t)p.numel * 4, hipMemcpyDeviceToHost));
   return PW_OK;
+}
+// Copies n elements of a device array in the activation type out as fp32, after draining the executor stream.
+static pw_status export_activation(pw_ctx* c, const void* src, int64_t n, bool is_bf16, float* dst) {
+  PW_HIP(c, hipStreamSynchronize(c->exec));
+  if (!is_bf16) {
+    PW_HIP(c, hipMemcpy(dst, src, (size_t)n * 4, hipMemcpyDeviceToHost));
+    return PW_OK;
+  }
+  float* tmp = nullptr;
+  PW_HIP(c, hipMalloc(&tmp, (size_t)n * 4));
+  hipError_t e = launch_bf16_to_f32(c->exec, src, tmp, n);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->exec);
+  if (e == hipSuccess) e = hipMemcpy(dst, tmp, (size_t)n * 4, hipMemcpyDeviceToHost);
+  (void)hipFree(tmp);
+  if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "activation export: %s", hipGetErrorString(e));
+  return PW_OK;
+}
+
+int64_t pw_model_param_count(pw_model* pm) { return pm ? (int64_t)pm->impl->params.size() : -1; }
+pw_status pw_model_param_info(pw_model* pm, int64_t idx, char* name, int cap, int64_t* numel) {
+  return pm ? state_param_info(pm->impl, idx, name, cap, numel) : PW_ERR_INVALID;
+}
+pw_status pw_model_import(pw_model* pm, int part, int64_t idx, const float* src, int src_on_device) {
+  return pm ? state_import(pm->ctx, pm->impl, part, idx, src, src_on_device) : PW_ERR_INVALID;
+}
+pw_status pw_model_export(pw_model* pm, int part, int64_t idx, float* dst) {
+  return pm ? state_export(pm->ctx, pm->impl, part, idx, dst) : PW_ERR_INVALID;
 }
 
 pw_status pw_model_zero_grads(pw_model* pm) {
@@ -1892,19 +1911,7 @@ pw_status pw_model_export_activation(pw_model* pm, const char* name, int mb, flo
   else if (s == "dx_in") { src = m->dx_a; n = N * d; }
   else return fail(c, PW_ERR_INVALID, "unknown activation name");
   if (numel != n) return fail(c, PW_ERR_SHAPE, "activation has %lld elements", (long long)n);
-  PW_HIP(c, hipStreamSynchronize(c->exec));
-  if (dt == PW_F32) {
-    PW_HIP(c, hipMemcpy(dst, src, (size_t)n * 4, hipMemcpyDeviceToHost));
-  } else {
-    float* tmp = nullptr;
-    PW_HIP(c, hipMalloc(&tmp, (size_t)n * 4));
-    hipError_t e = launch_bf16_to_f32(c->exec, src, tmp, n);
-    if (e == hipSuccess) e = hipStreamSynchronize(c->exec);
-    if (e == hipSuccess) e = hipMemcpy(dst, tmp, (size_t)n * 4, hipMemcpyDeviceToHost);
-    (void)hipFree(tmp);
-    if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "activation export: %s", hipGetErrorString(e));
-  }
-  return PW_OK;
+  return export_activation(c, src, n, dt != PW_F32, dst);
 }
 
 double pw_model_step_flops(const pw_lm_config* cfg) { return cfg ? model_step_flops(*cfg) : 0.0; }
@@ -1940,41 +1947,14 @@ pw_status pw_encdec_destroy(pw_encdec* pm) {
 }
 
 int64_t pw_encdec_param_count(pw_encdec* pm) { return pm ? (int64_t)pm->impl->params.size() : -1; }
-
 pw_status pw_encdec_param_info(pw_encdec* pm, int64_t idx, char* name, int cap, int64_t* numel) {
-  if (!pm || idx < 0 || idx >= (int64_t)pm->impl->params.size()) return PW_ERR_INVALID;
-  const ParamInfo& p = pm->impl->params[idx];
-  if (name && cap > 0) snprintf(name, cap, "%s", p.name.c_str());
-  if (numel) *numel = p.numel;
-  return PW_OK;
+  return pm ? state_param_info(pm->impl, idx, name, cap, numel) : PW_ERR_INVALID;
 }
-
 pw_status pw_encdec_import(pw_encdec* pm, int part, int64_t idx, const float* src, int src_on_device) {
-  if (!pm || !src || idx < 0 || idx >= (int64_t)pm->impl->params.size()) return PW_ERR_INVALID;
-  pw_ctx* c = pm->ctx;
-  EncDec* m = pm->impl;
-  float* base = part_base(m, part);
-  if (!base) return fail(c, PW_ERR_INVALID, "this model has no such part");
-  const ParamInfo& p = m->params[idx];
-  PW_HIP(c, hipMemcpyAsync(base + p.offset, src, (size_t)p.numel * 4, src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, c->exec));
-  if (part == PW_PARAMS) {
-    hipError_t e = model_state_refresh_lowp(m, p.offset, p.numel);
-    if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "bf16 refresh: %s", hipGetErrorString(e));
-  }
-  PW_HIP(c, hipStreamSynchronize(c->exec));
-  return PW_OK;
+  return pm ? state_import(pm->ctx, pm->impl, part, idx, src, src_on_device) : PW_ERR_INVALID;
 }
-
 pw_status pw_encdec_export(pw_encdec* pm, int part, int64_t idx, float* dst) {
-  if (!pm || !dst || idx < 0 || idx >= (int64_t)pm->impl->params.size()) return PW_ERR_INVALID;
-  pw_ctx* c = pm->ctx;
-  EncDec* m = pm->impl;
-  float* base = part_base(m, part);
-  if (!base) return fail(c, PW_ERR_INVALID, "this model has no such part");
-  const ParamInfo& p = m->params[idx];
-  PW_HIP(c, hipStreamSynchronize(c->exec));
-  PW_HIP(c, hipMemcpy(dst, base + p.offset, (size_t)p.numel * 4, hipMemcpyDeviceToHost));
-  return PW_OK;
+  return pm ? state_export(pm->ctx, pm->impl, part, idx, dst) : PW_ERR_INVALID;
 }
 
 pw_status pw_encdec_export_activation(pw_encdec* pm, const char* name, float* dst, int64_t numel) {
@@ -1984,19 +1964,7 @@ pw_status pw_encdec_export_activation(pw_encdec* pm, const char* name, float* ds
   if (std::string(name) != "dlogits") return fail(c, PW_ERR_INVALID, "unknown activation name");
   const int64_t n = (int64_t)m->Nt() * m->cfg.vocab;
   if (numel != n) return fail(c, PW_ERR_SHAPE, "activation has %lld elements", (long long)n);
-  PW_HIP(c, hipStreamSynchronize(c->exec));
-  if (!m->bf16) {
-    PW_HIP(c, hipMemcpy(dst, m->logits, (size_t)n * 4, hipMemcpyDeviceToHost));
-    return PW_OK;
-  }
-  float* tmp = nullptr;
-  PW_HIP(c, hipMalloc(&tmp, (size_t)n * 4));
-  hipError_t e = launch_bf16_to_f32(c->exec, m->logits, tmp, n);
-  if (e == hipSuccess) e = hipStreamSynchronize(c->exec);
-  if (e == hipSuccess) e = hipMemcpy(dst, tmp, (size_t)n * 4, hipMemcpyDeviceToHost);
-  (void)hipFree(tmp);
-  if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "activation export: %s", hipGetErrorString(e));
-  return PW_OK;
+  return export_activation(c, m->logits, n, m->bf16 != 0, dst);
 }
 
 double pw_encdec_step_flops(const pw_encdec_config* cfg) { return cfg ? encdec_step_flops(*cfg) : 0.0; }

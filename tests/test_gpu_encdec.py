@@ -135,6 +135,34 @@ def test_bf16_steps_are_bit_reproducible(ctx):
     assert np.array_equal(runs[0][1], runs[1][1]) and np.array_equal(runs[0][2], runs[1][2])
 
 
+@pytest.mark.parametrize("mode", [pwb.PW_STREAM, pwb.PW_GRAPH])
+def test_step_as_a_two_input_node_of_a_traced_program(ctx, mode):
+    """The step is a compiled function with two inputs: traced into a program it runs from one client call, as
+    stream launches or as the replay of one captured HIP graph (three replays, host work in between), and gives
+    the losses of the direct calls bit for bit."""
+    cfg = BF16_SMALL
+    params = I.encdec_params(cfg, perturb=True)
+    src, tgt = I.encdec_tokens(cfg)
+    want, model = run_steps(ctx, cfg, params, src, tgt, n_steps=3)
+    model.close()
+    model = ctx.encdec(cfg)
+    model.load_params(params)
+    step = model.compile_train_step()
+    prog = pwb.Program(ctx, [pwb.make_spec(pwb.PW_I32, src.shape), pwb.make_spec(pwb.PW_I32, tgt.shape)], [(step, [0, 1])], [2])
+    fs, ft = ctx.future_from_host(src), ctx.future_from_host(tgt)
+    got = []
+    for _ in range(3):
+        (fl,) = prog.run([fs, ft], mode)
+        got.append(float(ctx.await_(fl)[0]))
+        ctx.future_release(fl)
+        _ = model.export(pwb.PW_PARAMS, "dec.lnf_g")        # eager work and a synchronisation between replays
+    assert got == want
+    for f in (fs, ft):
+        ctx.future_release(f)
+    prog.close()
+    model.close()
+
+
 def test_bad_configurations_and_signatures_are_rejected(ctx):
     with pytest.raises(pwb.PwError):
         ctx.encdec(I.EncDecConfig(1, 1, 96, 2, 256, 64, 8, 8, 1))          # head_dim 48
