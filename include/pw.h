@@ -292,7 +292,8 @@ typedef struct {
 } pw_lm_config;
 
 /* Allocates parameters (zero), gradients, optimiser state and every activation buffer of the step
- * up front (static buffer plan).  d_model % n_head == 0, head_dim in {64, 128}. */
+ * up front (static buffer plan).  d_model % n_head == 0, head_dim in {64, 128}; with bf16 = 1 the number of
+ * tokens batch * seq must be a multiple of 8; PW_ERR_UNSUPPORTED otherwise. */
 pw_status pw_model_create(pw_ctx* ctx, const pw_lm_config* cfg, pw_model** out);
 pw_status pw_model_destroy(pw_model* m);
 /* Parameter tensors in the model's own order; weights are [in, out] row-major fp32. */
@@ -329,7 +330,8 @@ typedef struct {
 } pw_encdec_config;
 
 /* Allocates parameters (zero), gradients, optimiser state and every activation buffer of the step up front.
- * d_model % n_head == 0, head_dim in {64, 128}; PW_ERR_UNSUPPORTED otherwise, PW_ERR_OOM if HBM runs out. */
+ * d_model % n_head == 0, head_dim in {64, 128}, and with bf16 = 1 batch * src_len and batch * tgt_len multiples
+ * of 8; PW_ERR_UNSUPPORTED otherwise, PW_ERR_OOM if HBM runs out. */
 pw_status pw_encdec_create(pw_ctx* ctx, const pw_encdec_config* cfg, pw_encdec** out);
 pw_status pw_encdec_destroy(pw_encdec* m);
 /* Parameter tensors in the model's own order ("enc.wte", "e0.wqkv", ..., "d0.wkv", ..., "wh"); weights are

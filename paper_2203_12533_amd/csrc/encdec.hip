@@ -278,6 +278,9 @@ bool encdec_config_ok(const pw_encdec_config& c, std::string* why) {
   if (c.optimizer != 1 && c.optimizer != 2) return bad("optimizer must be 1 (SGD) or 2 (Adam)");
   if ((int64_t)c.batch * c.n_head > 65535) return bad("batch * n_head too large");
   if ((int64_t)c.batch * std::max(c.src_len, c.tgt_len) > (1 << 24)) return bad("too many tokens");
+  // the token count is the contraction length of every weight-gradient GEMM, and bf16 operands move in 16-byte pieces
+  if (c.bf16 && (((int64_t)c.batch * c.src_len) % 8 || ((int64_t)c.batch * c.tgt_len) % 8))
+    return bad("bf16 needs batch * src_len and batch * tgt_len to be multiples of 8");
   return true;
 }
 

@@ -188,6 +188,8 @@ bool model_config_ok(const pw_lm_config& c, std::string* why) {
   if (c.optimizer != 1 && c.optimizer != 2) return bad("optimizer must be 1 (SGD) or 2 (Adam)");
   if ((int64_t)c.batch * c.n_head > 65535) return bad("batch * n_head too large");
   if ((int64_t)c.batch * c.seq > (1 << 24)) return bad("too many tokens");
+  // the token count is the contraction length of every weight-gradient GEMM, and bf16 operands move in 16-byte pieces
+  if (c.bf16 && ((int64_t)c.batch * c.seq) % 8) return bad("bf16 needs batch * seq to be a multiple of 8");
   return true;
 }
 

@@ -122,6 +122,21 @@ def test_bf16_full_tile_shapes_match_oracle(ctx, orc):
     model.close()
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_head_dim_64_and_single_position_sequences(ctx, orc, bf16):
+    """head_dim 64 (in bf16: the causal self-attention runs on the head_dim-64 MFMA kernels, the other two
+    attention roles on the row kernels) and the degenerate lengths: one source position, then one target position."""
+    for src_len, tgt_len in ((1, 9), (70, 1)):
+        # (bf16 operands need token counts that are multiples of 8: batch 8 there, 3 in fp32)
+        cfg = I.EncDecConfig(1, 2, 128, 2, 256, 64, src_len, tgt_len, 8 if bf16 else 3, bf16=bf16, optimizer="sgd", lr=1e-2)
+        params = I.encdec_params(cfg, perturb=True)
+        src, tgt = I.encdec_tokens(cfg)
+        ref = orc.encdec_train_step(cfg, params, src, tgt)
+        (loss,), model = run_steps(ctx, cfg, params, src, tgt)
+        check_against_oracle(params, ref, loss, model, TOL[bf16], check_update=not bf16)
+        model.close()
+
+
 def test_bf16_steps_are_bit_reproducible(ctx):
     cfg = BF16_SMALL
     params = I.encdec_params(cfg, perturb=True)
@@ -168,6 +183,8 @@ def test_bad_configurations_and_signatures_are_rejected(ctx):
         ctx.encdec(I.EncDecConfig(1, 1, 96, 2, 256, 64, 8, 8, 1))          # head_dim 48
     with pytest.raises(pwb.PwError):
         ctx.encdec(I.EncDecConfig(0, 1, 128, 2, 256, 64, 8, 8, 1))         # no encoder layer
+    with pytest.raises(pwb.PwError):
+        ctx.encdec(I.EncDecConfig(1, 1, 128, 2, 256, 64, 9, 8, 3, bf16=True))   # 27 source tokens in bf16
     cfg = I.EncDecConfig(1, 1, 128, 2, 256, 64, 8, 6, 2)
     model = ctx.encdec(cfg)
     step = model.compile_train_step()
