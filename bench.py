@@ -135,7 +135,7 @@ def dispatch_bench_c_abi():
     return out
 
 
-def cpu_baseline_encdec(cfg, pwb, I, budget_tokens: int = 64):
+def cpu_baseline_encdec(cfg, pwb, I, budget_tokens: int = 384):
     """The CPU oracle on a bounded sample of the encoder-decoder workload: one layer each, one sequence pair of
     `budget_tokens` source and target tokens, the workload's widths.  Extrapolated by model-FLOP ratio."""
     from oracle import oracle
@@ -154,7 +154,7 @@ def cpu_baseline_encdec(cfg, pwb, I, budget_tokens: int = 64):
                       f"workload by model-FLOP ratio"}
 
 
-def cpu_baseline(cfg, pwb, budget_tokens: int = 128):
+def cpu_baseline(cfg, pwb, budget_tokens: int = 768):
     if not cfg.has_head:
         return None
     """The CPU oracle, as it stands, on a bounded sample: same layer / head shapes, one layer, one
