@@ -24,12 +24,10 @@ hipError_t launch_attention_fwd_mfma(hipStream_t s, const void* qkv, void* o, fl
 hipError_t launch_attention_bwd_mfma(hipStream_t s, const void* qkv, const void* o, const void* dout, const float* lse,
                                      float* delta, void* dqkv, int B, int T, int H, int hd);
 bool attention_mfma_supported(int T, int hd);
-hipError_t launch_attention_delta128(hipStream_t s, const void* o, const void* o_lo, const void* dout, float* delta, int B,
-                                     int T, int H);
 bool mha_dma_supported(const MhaArgs& a);
 hipError_t launch_mha_fwd_dma(hipStream_t s, const MhaArgs& a, void* o, void* o_lo, float* lse);
-hipError_t launch_mha_dq_dkv_dma(hipStream_t s, const MhaArgs& a, const void* dout, const float* lse, const float* delta,
-                                 void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv);
+hipError_t launch_mha_dq_dkv_dma(hipStream_t s, const MhaArgs& a, const void* o, const void* o_lo, const void* dout,
+                                 const float* lse, float* delta, void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv);
 
 // What the row kernels need of an MhaArgs, typed.
 template <class T> struct RowArgs {
@@ -329,9 +327,7 @@ hipError_t launch_mha_bwd(hipStream_t s, const MhaArgs& a, const void* o, const 
   const int64_t d = (int64_t)a.H * a.hd;
   if (lddq < d || lddkv < d) return hipErrorInvalidValue;
   if (use_dma_kernels() && mha_dma_supported(a) && !(((uintptr_t)o | (uintptr_t)o_lo | (uintptr_t)dout) & 15)) {
-    hipError_t e = launch_attention_delta128(s, o, o_lo, dout, delta, a.B, a.Tq, a.H);
-    if (e != hipSuccess) return e;
-    return launch_mha_dq_dkv_dma(s, a, dout, lse, delta, dq, lddq, dk, dv, lddkv);
+    return launch_mha_dq_dkv_dma(s, a, o, o_lo, dout, lse, delta, dq, lddq, dk, dv, lddkv);   // (delta comes from the dQ kernel)
   }
   const size_t es = a.dtype == kBF16 ? 2 : 4;
   const bool packed_out = lddq == 3 * d && lddkv == 3 * d && (char*)dk == (char*)dq + d * es && (char*)dv == (char*)dq + 2 * d * es;

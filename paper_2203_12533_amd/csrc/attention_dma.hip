@@ -240,10 +240,13 @@ __global__ __launch_bounds__(kNT, 2) void attn_fwd_dma_kernel(MhaDev a, bf16* __
 // ===================================================================================================
 // dQ: same tiling as the forward.  dQ_i = scale * sum_j dS_ij K_j, dS = P (dP - delta)
 // ===================================================================================================
+// It also produces delta_i = sum_c dO_ic O_ic for its queries (each wave has the dO fragments of its 32 rows in
+// registers anyway; O, plus the optional rounding remainder o_lo, is read the same way once) and leaves it in
+// `delta` for the dK/dV kernel, which is launched behind this one.
 template <bool CAUSAL>
-__global__ __launch_bounds__(kNT, 2) void attn_dq_dma_kernel(MhaDev a, const bf16* __restrict__ dout,
-                                                             const float* __restrict__ lse, const float* __restrict__ delta,
-                                                             bf16* __restrict__ dq, int64_t lddq) {
+__global__ __launch_bounds__(kNT, 2) void attn_dq_dma_kernel(MhaDev a, const bf16* __restrict__ o, const bf16* __restrict__ o_lo,
+                                                             const bf16* __restrict__ dout, const float* __restrict__ lse,
+                                                             float* __restrict__ delta, bf16* __restrict__ dq, int64_t lddq) {
   constexpr int BKV = 64;
   constexpr int kTile = BKV * HD;
   extern __shared__ __attribute__((aligned(1024))) bf16 smem[];
@@ -269,7 +272,27 @@ __global__ __launch_bounds__(kNT, 2) void attn_dq_dma_kernel(MhaDev a, const bf1
   load_row_frags<HD>(qbase, a.ldq, q0, Tq, qf);
   load_row_frags<HD>(dout + (int64_t)b * Tq * d + h * HD, d, q0, Tq, gf);
   const float lse2 = query < Tq ? lse[(int64_t)bh * Tq + query] * kLog2e : INFINITY;   // +inf: P = 0 for rows past the end
-  const float dl = query < Tq ? delta[(int64_t)bh * Tq + query] : 0.f;
+  float dl;
+  {
+    bf16x8 of[HD / 16];
+    load_row_frags<HD>(o + (int64_t)b * Tq * d + h * HD, d, q0, Tq, of);
+    float part = 0.f;
+    if (o_lo) {
+      bf16x8 lf[HD / 16];
+      load_row_frags<HD>(o_lo + (int64_t)b * Tq * d + h * HD, d, q0, Tq, lf);
+#pragma unroll
+      for (int kk = 0; kk < HD / 16; ++kk)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part += ((float)of[kk][e] + (float)lf[kk][e]) * (float)gf[kk][e];
+    } else {
+#pragma unroll
+      for (int kk = 0; kk < HD / 16; ++kk)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part += (float)of[kk][e] * (float)gf[kk][e];
+    }
+    dl = part + __shfl_xor(part, 32, 64);            // the two halves of the row's features
+    if (half == 0 && query < Tq) delta[(int64_t)bh * Tq + query] = dl;
+  }
   f32x16 acc[HD / 32];
 #pragma unroll
   for (int cb = 0; cb < HD / 32; ++cb)
@@ -482,18 +505,18 @@ hipError_t launch_mha_fwd_dma(hipStream_t s, const MhaArgs& a, void* o, void* o_
   return hipGetLastError();
 }
 
-hipError_t launch_mha_dq_dkv_dma(hipStream_t s, const MhaArgs& a, const void* dout, const float* lse, const float* delta,
-                                 void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv) {
+hipError_t launch_mha_dq_dkv_dma(hipStream_t s, const MhaArgs& a, const void* o, const void* o_lo, const void* dout,
+                                 const float* lse, float* delta, void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv) {
   hipError_t e = attention_dma_init();
   if (e != hipSuccess) return e;
   if ((((uintptr_t)dq | (uintptr_t)dk | (uintptr_t)dv) & 7) || lddq % 4 || lddkv % 4) return hipErrorInvalidValue;
   const int grid_q = ((a.Tq + 127) / 128) * a.B * a.H, grid_k = ((a.Tk + 127) / 128) * a.B * a.H;
   const MhaDev dv_ = dev_of(a);
   if (a.causal) {
-    attn_dq_dma_kernel<true><<<grid_q, kNT, kSmemTiles, s>>>(dv_, (const bf16*)dout, lse, delta, (bf16*)dq, lddq);
+    attn_dq_dma_kernel<true><<<grid_q, kNT, kSmemTiles, s>>>(dv_, (const bf16*)o, (const bf16*)o_lo, (const bf16*)dout, lse, delta, (bf16*)dq, lddq);
     attn_dkv_dma_kernel<true><<<grid_k, kNT, kSmemDkv, s>>>(dv_, (const bf16*)dout, lse, delta, (bf16*)dk, (bf16*)dv, lddkv);
   } else {
-    attn_dq_dma_kernel<false><<<grid_q, kNT, kSmemTiles, s>>>(dv_, (const bf16*)dout, lse, delta, (bf16*)dq, lddq);
+    attn_dq_dma_kernel<false><<<grid_q, kNT, kSmemTiles, s>>>(dv_, (const bf16*)o, (const bf16*)o_lo, (const bf16*)dout, lse, delta, (bf16*)dq, lddq);
     attn_dkv_dma_kernel<false><<<grid_k, kNT, kSmemDkv, s>>>(dv_, (const bf16*)dout, lse, delta, (bf16*)dk, (bf16*)dv, lddkv);
   }
   return hipGetLastError();

@@ -399,12 +399,9 @@ __global__ __launch_bounds__(kNT, HD == 64 ? 2 : 1) void attn_dkv_kernel(const b
 }
 
 // delta[b,h,i] = sum_c dO[i,c] O[i,c].  16 lanes share one (token, head) row of 128 (8 lanes for 64).
-// o_lo (optional): what the forward's rounding of O to bf16 left over, O_exact ~ o + o_lo.  delta is subtracted
-// from every dP of the row, so an error in it is a common offset on dS that the keys' common component turns into
-// a gradient error far above bf16's own; the remainder takes that error away.
 template <int HD>
-__global__ void attn_delta_kernel(const bf16* __restrict__ o, const bf16* __restrict__ o_lo, const bf16* __restrict__ dout,
-                                  float* __restrict__ delta, int T, int H, int64_t rows) {
+__global__ void attn_delta_kernel(const bf16* __restrict__ o, const bf16* __restrict__ dout, float* __restrict__ delta,
+                                  int T, int H, int64_t rows) {
   constexpr int LPR = HD / 8;                       // lanes per row
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t row = gid / LPR;                    // (token n, head h) flattened: n*H + h
@@ -413,14 +410,8 @@ __global__ void attn_delta_kernel(const bf16* __restrict__ o, const bf16* __rest
   if (row < rows) {
     const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + row * HD + part * 8);
     const bf16x8 g = *reinterpret_cast<const bf16x8*>(dout + row * HD + part * 8);
-    if (o_lo) {
-      const bf16x8 r = *reinterpret_cast<const bf16x8*>(o_lo + row * HD + part * 8);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) s += ((float)a[e] + (float)r[e]) * (float)g[e];
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) s += (float)a[e] * (float)g[e];
-    }
+    for (int e = 0; e < 8; ++e) s += (float)a[e] * (float)g[e];
   }
 #pragma unroll
   for (int off = LPR / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
@@ -459,23 +450,14 @@ hipError_t launch_attention_bwd_mfma(hipStream_t s, const void* qkv, const void*
   const int64_t threads = rows * (hd / 8);
   dim3 grid((T + 127) / 128, B * H);
   if (hd == 128) {
-    attn_delta_kernel<128><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>((const bf16*)o, nullptr, (const bf16*)dout, delta, T, H, rows);
+    attn_delta_kernel<128><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>((const bf16*)o, (const bf16*)dout, delta, T, H, rows);
     attn_dq_kernel<128><<<grid, kNT, 0, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
     attn_dkv_kernel<128><<<grid, kNT, 0, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
   } else {
-    attn_delta_kernel<64><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>((const bf16*)o, nullptr, (const bf16*)dout, delta, T, H, rows);
+    attn_delta_kernel<64><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>((const bf16*)o, (const bf16*)dout, delta, T, H, rows);
     attn_dq_kernel<64><<<grid, kNT, 0, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
     attn_dkv_kernel<64><<<grid, kNT, 0, s>>>((const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, T, H);
   }
-  return hipGetLastError();
-}
-
-// delta[b, h, t] = sum_c dO[b*T+t, h*128+c] O[b*T+t, h*128+c] for the head_dim-128 kernels of attention_dma.hip.
-hipError_t launch_attention_delta128(hipStream_t s, const void* o, const void* o_lo, const void* dout, float* delta, int B,
-                                     int T, int H) {
-  const int64_t rows = (int64_t)B * T * H;
-  const int64_t threads = rows * (128 / 8);
-  attn_delta_kernel<128><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>((const bf16*)o, (const bf16*)o_lo, (const bf16*)dout, delta, T, H, rows);
   return hipGetLastError();
 }
 
