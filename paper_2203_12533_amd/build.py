@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpw.so")
 SOURCES = ["model_common.hip", "elementwise.hip", "norm.hip", "embed_xent.hip", "attention.hip", "attention_mfma.hip", "attention_dma.hip", "gemm.hip", "gemm_ring.hip",
-           "lm.hip", "encdec.hip", "runtime.hip"]
+           "lm.hip", "encdec.hip", "runtime.hip", "runtime_sched.hip", "runtime_models.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-result", "-Wno-inline-asm"]
 

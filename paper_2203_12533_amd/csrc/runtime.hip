@@ -15,276 +15,10 @@
 //   device object store (4.6)              -> handle tables + size-class buffer pool + refcounts
 // An input that "is not ready" is made real by a gate kernel on a second stream that spins (bounded) on a
 // word in pinned host memory; consumers wait on the event recorded behind it.
-#include <hip/hip_runtime.h>
-
-#include <algorithm>
-#include <atomic>
-#include <chrono>
-#include <condition_variable>
-#include <cstdarg>
-#include <cstdio>
-#include <cstring>
-#include <deque>
-#include <map>
-#include <mutex>
-#include <thread>
-#include <memory>
-#include <string>
-#include <unordered_map>
-#include <vector>
-
-#include "../../include/pw.h"
-#include "kernels.hpp"
-#include "encdec.hpp"
-#include "lm.hpp"
-
-using namespace pw;
+#include "runtime_internal.hpp"
 
 namespace {
 
-size_t dtype_size(int dt) { return dt == PW_BF16 ? 2 : 4; }
-
-bool spec_ok(const pw_tensor_spec& s) {
-  if (s.dtype < PW_F32 || s.dtype > PW_I32 || s.rank < 0 || s.rank > 4) return false;
-  for (int i = 0; i < s.rank; ++i)
-    if (s.dims[i] < 0 || s.dims[i] > (1LL << 40)) return false;
-  return true;
-}
-int64_t spec_numel(const pw_tensor_spec& s) {
-  int64_t n = 1;
-  for (int i = 0; i < s.rank; ++i) n *= s.dims[i];
-  return n;
-}
-size_t spec_bytes(const pw_tensor_spec& s) { return (size_t)spec_numel(s) * dtype_size(s.dtype); }
-// 0 same, PW_ERR_DTYPE or PW_ERR_SHAPE otherwise
-pw_status spec_match(const pw_tensor_spec& a, const pw_tensor_spec& b) {
-  if (a.dtype != b.dtype) return PW_ERR_DTYPE;
-  if (a.rank != b.rank) return PW_ERR_SHAPE;
-  for (int i = 0; i < a.rank; ++i)
-    if (a.dims[i] != b.dims[i]) return PW_ERR_SHAPE;
-  return PW_OK;
-}
-
-// A pair of words in pinned host memory: [0] the gate flag the host sets, [1] the poison mark.
-struct GateWords {
-  uint32_t* words;   // host-visible, device-visible
-};
-
-struct FutureRec {
-  bool live = false;
-  uint32_t gen = 0;
-  void* buf = nullptr;
-  size_t bytes = 0, pool_bytes = 0;
-  pw_tensor_spec spec{};
-  bool owns = false;             // buffer goes back to the pool on release
-  bool on_gate_stream = false;   // produced by the gate stream: consumers must wait on `event`
-  bool pending = false;          // created by pw_future_pending and not resolved yet
-  hipEvent_t event = nullptr;    // null: ready w.r.t. the executor stream's order
-  int refcount = 0;
-  uint64_t owner = 0;            // ownership label (Section 4.6): who this object dies with
-  bool host_poison = false;
-  std::vector<std::shared_ptr<GateWords>> poison;   // gates this future depends on
-  std::shared_ptr<GateWords> gate;                  // own gate (pending futures)
-  void* staging = nullptr;                          // pinned host staging (pending futures)
-};
-
-struct FnRec {
-  bool live = false;
-  uint32_t gen = 0;
-  pw_fn_desc desc{};
-  float cst = 0.f, busy_us = 0.f;
-  int reps = 1;
-  Model* model = nullptr;
-  EncDec* encdec = nullptr;
-  int microbatch = 0;
-};
-
-struct GraphEntry {
-  hipGraph_t graph = nullptr;
-  hipGraphExec_t exec = nullptr;
-};
-
-// One node of a pipeline as handed to an executor's host thread.  Everything the thread needs is in here (the
-// controller planned every buffer beforehand: shapes are static), so the thread touches no context tables.
-struct NodeMsg {
-  int kind = 0;
-  float cst = 0.f, busy_us = 0.f;
-  int reps = 1;
-  int64_t numel = 0;
-  const float* in = nullptr;
-  float* out = nullptr;
-  void* xfer_dst = nullptr;          // consumer-side buffer on another executor (null: consumer shares this stream)
-  size_t xfer_bytes = 0;
-  hipEvent_t wait_event = nullptr;   // producer's event on another stream (null: none, or same stream)
-  std::atomic<int>* wait_flag = nullptr;   // set by the producer's thread once wait_event has been recorded (1) or it failed (2)
-  hipEvent_t done_event = nullptr;   // recorded behind this node (and its transfer)
-  std::atomic<int>* done_flag = nullptr;
-  std::atomic<int>* ack = nullptr;   // 1: enqueued, 2: failed
-  int prep_us = 0;                   // emulated host-side preparation (see pw_ctx_set_executor_prep_us)
-};
-
-struct Executor {
-  hipStream_t stream = nullptr;
-  bool own_stream = false;
-  std::thread thread;
-  std::mutex mu;
-  std::condition_variable cv;
-  std::deque<NodeMsg> queue;
-  bool stop = false;
-};
-
-}  // namespace
-
-struct pw_sched;
-
-struct pw_ctx {
-  int device = 0;
-  hipStream_t exec = nullptr;      // executor stream
-  bool own_exec = false;
-  hipStream_t gate = nullptr;      // gate kernels and their copies
-  hipStream_t io = nullptr;        // device-to-host copies of pw_await
-  std::string error;
-  int gate_timeout_ms = 20000;
-
-  std::vector<FutureRec> futures;
-  std::vector<uint32_t> free_futures;
-  std::vector<FnRec> fns;
-  std::vector<Model*> models;
-  std::vector<EncDec*> encdecs;
-  int64_t live_futures = 0;
-  uint64_t current_owner = 0;    // label given to futures created from now on
-  int64_t memory_limit = 0;      // bytes the pool may have handed out at once; 0: no limit
-
-  // buffer pool: power-of-two size classes
-  std::map<size_t, std::vector<void*>> pool;
-  int64_t pool_in_use = 0;
-  std::vector<hipEvent_t> event_pool;
-
-  // pinned host words for gates
-  std::vector<uint32_t*> word_slabs;
-  std::vector<uint32_t*> free_words;
-  std::map<size_t, std::vector<void*>> staging_pool;
-
-  std::unordered_map<std::string, GraphEntry> graphs;
-
-  std::vector<std::unique_ptr<Executor>> executors;   // pw_ctx_set_executors; [0] wraps the executor stream
-  int executor_prep_us = 0;
-
-  // Serialises the dispatch calls (functions, futures, chains, pipelines, await) so that client threads and the
-  // scheduler thread of pw_sched may share a context.  Recursive: some calls are built from others.
-  std::recursive_mutex api_mu;
-  std::vector<pw_sched*> scheds;
-  std::vector<pw_program*> programs;
-};
-
-#define PW_API_LOCK(c)                                  \
-  std::unique_lock<std::recursive_mutex> api_lk_;       \
-  if (c) api_lk_ = std::unique_lock<std::recursive_mutex>((c)->api_mu)
-
-struct pw_model {
-  pw_ctx* ctx;
-  Model* impl;
-};
-struct pw_encdec {
-  pw_ctx* ctx;
-  EncDec* impl;
-};
-
-// ---- traced dataflow programs (Section 3) ---------------------------------------------------------------
-namespace {
-struct ProgNode {
-  FnRec fn;            // snapshot: the handle may be released after tracing
-  pw_fn handle = 0;    // only part of the graph-cache key
-  int n_in = 0, in[8] = {0};
-  int first_out = 0;
-};
-}  // namespace
-struct pw_program {
-  pw_ctx* ctx = nullptr;
-  int n_inputs = 0;
-  std::vector<pw_tensor_spec> specs;   // per value
-  std::vector<ProgNode> nodes;
-  std::vector<int> outputs;
-  std::vector<int> last_use;           // per value: last node that reads it; n_nodes if it is a program output; -1 if unused
-  std::unordered_map<std::string, GraphEntry> graphs;
-};
-
-// ---- multi-tenant scheduler (Section 4.4 "centralized scheduler", Section 5.2) -----------------------------
-// Clients (any threads) put programs - chains of compiled functions - into per-client queues; ONE scheduler
-// thread decides the order in which programs reach the executor stream, so that order is consistent whatever
-// the clients do.  FIFO takes programs in arrival order; proportional share takes, among the clients that have
-// work queued, the one whose weighted device time consumed so far (estimated at enqueue) is smallest (stride
-// scheduling).  Only a bounded number of programs is kept in flight on the device, so a client that arrives
-// late is not stuck behind an arbitrarily long backlog of others.
-namespace {
-struct SchedProgram {
-  std::vector<pw_fn> fns;
-  pw_future in = 0;
-  uint64_t ticket = 0, arrival = 0;
-  double est_us = 0;
-  int n_computations = 0;
-};
-struct SchedClient {
-  double weight = 1, vtime = 0;
-  uint64_t owner = 0;
-  bool failed = false;
-  std::deque<SchedProgram> queue;
-  int64_t programs = 0, computations = 0;
-  double device_ms = 0;
-};
-struct SchedResult {
-  pw_status status = PW_OK;
-  pw_future out = 0;
-};
-struct SchedInFlight {
-  int client = 0;
-  int n_computations = 0;
-  hipEvent_t start = nullptr, stop = nullptr;
-};
-}  // namespace
-
-struct pw_sched {
-  pw_ctx* ctx = nullptr;
-  int policy = PW_SCHED_FIFO;
-  int window = 4;                       // programs in flight on the device at most
-  std::mutex mu;
-  std::condition_variable cv_work, cv_done;
-  std::vector<SchedClient> clients;
-  std::unordered_map<uint64_t, SchedResult> results;
-  std::unordered_map<uint64_t, bool> outstanding;   // tickets handed out and not yet collected (value: someone is waiting)
-  uint64_t next_ticket = 1, next_arrival = 1;
-  int64_t queued = 0;
-  std::deque<SchedInFlight> inflight;   // scheduler thread only
-  std::vector<hipEvent_t> timing_events;
-  hipEvent_t epoch = nullptr;           // recorded at creation: slices are reported relative to it
-  std::vector<pw_sched_slice> trace;
-  int collecting = 0;                   // results taken by pw_sched_wait whose futures are not released yet
-  int64_t stalls = 0;                   // programs that had to wait for memory
-  double stalled_ms = 0;
-  uint64_t id = 0;
-  bool stop = false, idle = true;
-  std::thread thread;
-};
-
-namespace {
-
-pw_status fail(pw_ctx* c, pw_status st, const char* fmt, ...) {
-  if (c) {
-    char buf[512];
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(buf, sizeof buf, fmt, ap);
-    va_end(ap);
-    c->error = buf;
-  }
-  return st;
-}
-#define PW_HIP(c, expr)                                                                          \
-  do {                                                                                           \
-    hipError_t e_ = (expr);                                                                      \
-    if (e_ != hipSuccess) return fail(c, e_ == hipErrorOutOfMemory ? PW_ERR_OOM : PW_ERR_DEVICE, \
-                                      "%s: %s", #expr, hipGetErrorString(e_));                   \
-  } while (0)
 
 size_t size_class(size_t bytes) {
   size_t c = 256;
@@ -364,12 +98,6 @@ pw_status future_new(pw_ctx* c, FutureRec** out, pw_future* handle) {
   return PW_OK;
 }
 
-FutureRec* future_get(pw_ctx* c, pw_future h) {
-  const uint32_t idx = (uint32_t)(h & 0xFFFFFFFFu), gen = (uint32_t)(h >> 32);
-  if (idx == 0 || idx > c->futures.size()) return nullptr;
-  FutureRec& f = c->futures[idx - 1];
-  return (f.live && f.gen == gen) ? &f : nullptr;
-}
 
 void future_drop(pw_ctx* c, pw_future h) {
   FutureRec* f = future_get(c, h);
@@ -391,12 +119,6 @@ void future_drop(pw_ctx* c, pw_future h) {
   c->free_futures.push_back((uint32_t)(h & 0xFFFFFFFFu) - 1);
 }
 
-FnRec* fn_get(pw_ctx* c, pw_fn h) {
-  const uint32_t idx = (uint32_t)(h & 0xFFFFFFFFu), gen = (uint32_t)(h >> 32);
-  if (idx == 0 || idx > c->fns.size()) return nullptr;
-  FnRec& f = c->fns[idx - 1];
-  return (f.live && f.gen == gen) ? &f : nullptr;
-}
 
 bool is_scalar_kind(int k) { return k >= PW_FN_ADD_CONST && k <= PW_FN_BUSY_CHAIN; }   // one fp32 input, one output
 
@@ -1283,333 +1005,6 @@ pw_status pw_program_run(pw_ctx* c, pw_program* p, const pw_future* in, int n_in
   return PW_OK;
 }
 
-// ---- scheduler ---------------------------------------------------------------------------------------------
-namespace {
-
-hipEvent_t sched_event(pw_sched* s) {
-  if (!s->timing_events.empty()) {
-    hipEvent_t e = s->timing_events.back();
-    s->timing_events.pop_back();
-    return e;
-  }
-  hipEvent_t e = nullptr;
-  if (hipEventCreate(&e) != hipSuccess) return nullptr;
-  return e;
-}
-
-// Retire the oldest program in flight: wait for it, charge its device time to its client.
-void sched_retire(pw_sched* s) {
-  SchedInFlight f = s->inflight.front();
-  s->inflight.pop_front();
-  float ms = 0.f, t0 = 0.f;
-  const bool ok = f.start && f.stop && hipEventSynchronize(f.stop) == hipSuccess &&
-                  hipEventElapsedTime(&ms, f.start, f.stop) == hipSuccess &&
-                  hipEventElapsedTime(&t0, s->epoch, f.start) == hipSuccess;
-  std::lock_guard<std::mutex> lk(s->mu);
-  if (ok) {
-    SchedClient& c = s->clients[f.client];
-    c.device_ms += ms;
-    if (s->trace.size() < 65536) s->trace.push_back(pw_sched_slice{f.client, f.n_computations, t0, t0 + ms});
-  }
-  if (f.start) s->timing_events.push_back(f.start);
-  if (f.stop) s->timing_events.push_back(f.stop);
-}
-
-void sched_loop(pw_sched* s) {
-  (void)hipSetDevice(s->ctx->device);
-  for (;;) {
-    SchedProgram prog;
-    int client = -1;
-    {
-      std::unique_lock<std::mutex> lk(s->mu);
-      while (!s->stop && s->queued == 0) {
-        if (!s->inflight.empty()) {          // nothing to hand out: use the time to retire finished programs
-          lk.unlock();
-          sched_retire(s);
-          lk.lock();
-          continue;
-        }
-        s->idle = true;
-        s->cv_done.notify_all();
-        s->cv_work.wait(lk);
-      }
-      if (s->stop && s->queued == 0) break;
-      s->idle = false;
-      // ---- the policy
-      double best = 0;
-      for (int i = 0; i < (int)s->clients.size(); ++i) {
-        SchedClient& c = s->clients[i];
-        if (c.queue.empty()) continue;
-        const double key = s->policy == PW_SCHED_FIFO ? (double)c.queue.front().arrival : c.vtime;
-        if (client < 0 || key < best) { client = i; best = key; }
-      }
-      SchedClient& c = s->clients[client];
-      prog = std::move(c.queue.front());
-      c.queue.pop_front();
-      s->queued--;
-      c.vtime += prog.est_us / c.weight;
-    }
-    while ((int)s->inflight.size() >= s->window) sched_retire(s);
-    // ---- enqueue on the executor stream, bracketed by timing events
-    SchedInFlight fl;
-    fl.client = client;
-    fl.n_computations = prog.n_computations;
-    SchedResult res;
-    const auto t_stall = std::chrono::steady_clock::now();
-    bool stalled = false;
-    for (;;) {
-      {
-        std::unique_lock<std::recursive_mutex> api(s->ctx->api_mu);
-        const uint64_t saved_owner = s->ctx->current_owner;
-        s->ctx->current_owner = s->clients[client].owner;   // what the program produces belongs to its client
-        if (!fl.start) fl.start = sched_event(s);
-        if (!fl.stop) fl.stop = sched_event(s);
-        if (fl.start) (void)hipEventRecord(fl.start, s->ctx->exec);
-        res.status = pw_chain(s->ctx, prog.fns.data(), (int)prog.fns.size(), &prog.in, 1, &res.out, 1, PW_STREAM);
-        if (fl.stop) (void)hipEventRecord(fl.stop, s->ctx->exec);
-        s->ctx->current_owner = saved_owner;
-      }
-      if (res.status != PW_ERR_OOM) break;
-      // Back-pressure (Section 4.6): other programs' buffers occupy the memory budget.  Stall this one: finish
-      // what is in flight, then wait for clients to collect results; give up when nothing can change any more.
-      stalled = true;
-      if (!s->inflight.empty()) { sched_retire(s); continue; }
-      bool hopeless;
-      {
-        std::lock_guard<std::mutex> lk(s->mu);
-        hopeless = (s->results.empty() && s->collecting == 0) || s->stop || s->clients[client].failed;   // nothing left to wait for
-      }
-      if (hopeless || std::chrono::steady_clock::now() - t_stall > std::chrono::seconds(20)) break;
-      std::this_thread::sleep_for(std::chrono::microseconds(50));
-    }
-    if (stalled) {
-      std::lock_guard<std::mutex> lk(s->mu);
-      s->stalls++;
-      s->stalled_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_stall).count();
-    }
-    s->inflight.push_back(fl);
-    {
-      std::lock_guard<std::mutex> lk(s->mu);
-      s->results[prog.ticket] = res;
-      SchedClient& c = s->clients[client];
-      c.programs++;
-      if (res.status == PW_OK) c.computations += prog.n_computations;
-    }
-    s->cv_done.notify_all();
-  }
-  while (!s->inflight.empty()) sched_retire(s);
-  std::lock_guard<std::mutex> lk(s->mu);
-  s->idle = true;
-  s->cv_done.notify_all();
-}
-
-void sched_shutdown(pw_sched* s) {
-  {
-    std::lock_guard<std::mutex> lk(s->mu);
-    s->stop = true;
-  }
-  s->cv_work.notify_all();
-  if (s->thread.joinable()) s->thread.join();
-  // results nobody collected: give their futures back
-  for (auto& kv : s->results)
-    if (kv.second.status == PW_OK && kv.second.out) (void)pw_future_release(s->ctx, kv.second.out);
-  s->results.clear();
-  for (hipEvent_t e : s->timing_events) (void)hipEventDestroy(e);
-  if (s->epoch) (void)hipEventDestroy(s->epoch);
-}
-
-}  // namespace
-
-pw_status pw_sched_create(pw_ctx* c, int policy, int max_in_flight, pw_sched** out) {
-  if (!c || !out) return PW_ERR_INVALID;
-  PW_API_LOCK(c);
-  if (policy != PW_SCHED_FIFO && policy != PW_SCHED_PROPORTIONAL) return fail(c, PW_ERR_INVALID, "unknown scheduling policy");
-  if (max_in_flight < 1 || max_in_flight > 1024) return fail(c, PW_ERR_INVALID, "programs in flight must be within [1, 1024]");
-  pw_sched* s = new pw_sched();
-  s->ctx = c;
-  s->policy = policy;
-  s->window = max_in_flight;
-  if (hipEventCreate(&s->epoch) != hipSuccess || hipEventRecord(s->epoch, c->exec) != hipSuccess) {
-    if (s->epoch) (void)hipEventDestroy(s->epoch);
-    delete s;
-    return fail(c, PW_ERR_DEVICE, "could not create the scheduler's timing events");
-  }
-  static std::atomic<uint64_t> next_id{1};
-  s->id = next_id.fetch_add(1) & 0x7FFFFFFFu;
-  s->thread = std::thread(sched_loop, s);
-  c->scheds.push_back(s);
-  *out = s;
-  return PW_OK;
-}
-
-pw_status pw_sched_destroy(pw_sched* s) {
-  if (!s) return PW_ERR_INVALID;
-  pw_ctx* c = s->ctx;
-  sched_shutdown(s);
-  {
-    PW_API_LOCK(c);
-    for (size_t i = 0; i < c->scheds.size(); ++i)
-      if (c->scheds[i] == s) { c->scheds.erase(c->scheds.begin() + i); break; }
-  }
-  delete s;
-  return PW_OK;
-}
-
-pw_status pw_sched_add_client(pw_sched* s, double weight, int* client) {
-  if (!s || !client || !(weight > 0.0) || weight > 1e6) return PW_ERR_INVALID;
-  std::lock_guard<std::mutex> lk(s->mu);
-  if (s->clients.size() >= 1024) return PW_ERR_INVALID;
-  SchedClient c;
-  c.weight = weight;
-  // a newcomer starts level with the least-served client, not with a credit for the past
-  bool any = false;
-  for (auto& o : s->clients)
-    if (!any || o.vtime < c.vtime) { c.vtime = o.vtime; any = true; }
-  c.owner = (1ull << 63) | (s->id << 32) | (uint64_t)s->clients.size();
-  s->clients.push_back(c);
-  *client = (int)s->clients.size() - 1;
-  return PW_OK;
-}
-
-pw_status pw_sched_client_fail(pw_sched* s, int client, int64_t* objects_released) {
-  if (!s) return PW_ERR_INVALID;
-  uint64_t owner;
-  {
-    std::lock_guard<std::mutex> lk(s->mu);
-    if (client < 0 || client >= (int)s->clients.size()) return PW_ERR_INVALID;
-    SchedClient& c = s->clients[client];
-    c.failed = true;
-    owner = c.owner;
-    // programs that never reached the device are dropped; whoever waits for them learns why
-    for (auto& p : c.queue) {
-      SchedResult r;
-      r.status = PW_ERR_POISONED;
-      s->results[p.ticket] = r;
-      s->queued--;
-    }
-    c.queue.clear();
-    // results of this client that nobody collected are collected with its other objects below
-    for (auto& kv : s->results)
-      if (kv.second.status == PW_OK && kv.second.out) {
-        FutureRec* f = nullptr;
-        {
-          std::unique_lock<std::recursive_mutex> api(s->ctx->api_mu);
-          f = future_get(s->ctx, kv.second.out);
-          if (f && f->owner == owner) { kv.second.status = PW_ERR_POISONED; kv.second.out = 0; }
-        }
-      }
-  }
-  s->cv_done.notify_all();
-  return pw_owner_collect(s->ctx, owner, objects_released);
-}
-
-pw_status pw_sched_stalls(pw_sched* s, int64_t* programs_stalled, double* stalled_ms) {
-  if (!s) return PW_ERR_INVALID;
-  std::lock_guard<std::mutex> lk(s->mu);
-  if (programs_stalled) *programs_stalled = s->stalls;
-  if (stalled_ms) *stalled_ms = s->stalled_ms;
-  return PW_OK;
-}
-
-pw_status pw_sched_submit(pw_sched* s, int client, const pw_fn* fns, int n_fns, pw_future in, uint64_t* ticket) {
-  if (!s || !fns || !ticket || n_fns < 1 || n_fns > 4096) return PW_ERR_INVALID;
-  SchedProgram p;
-  p.fns.assign(fns, fns + n_fns);
-  p.in = in;
-  {
-    // cost estimate from the compiled functions (busy time where known, a launch's worth otherwise)
-    PW_API_LOCK(s->ctx);
-    for (int i = 0; i < n_fns; ++i) {
-      FnRec* f = fn_get(s->ctx, fns[i]);
-      if (!f) return fail(s->ctx, PW_ERR_INVALID, "function %d of the program is not a live handle", i);
-      p.est_us += 3.0 + (double)f->busy_us * f->reps;
-      p.n_computations += f->reps;
-    }
-    if (!future_get(s->ctx, in)) return fail(s->ctx, PW_ERR_INVALID, "input is not a live future");
-  }
-  std::lock_guard<std::mutex> lk(s->mu);
-  if (client < 0 || client >= (int)s->clients.size()) return PW_ERR_INVALID;
-  if (s->stop) return PW_ERR_INVALID;
-  SchedClient& c = s->clients[client];
-  if (c.failed) return PW_ERR_INVALID;
-  if (c.queue.empty() && s->policy == PW_SCHED_PROPORTIONAL) {
-    // back from idle: no credit for time not used
-    bool any = false;
-    double floor_v = 0;
-    for (auto& o : s->clients)
-      if (!o.queue.empty() && (!any || o.vtime < floor_v)) { floor_v = o.vtime; any = true; }
-    if (any && c.vtime < floor_v) c.vtime = floor_v;
-  }
-  p.ticket = s->next_ticket++;
-  p.arrival = s->next_arrival++;
-  *ticket = p.ticket;
-  s->outstanding[p.ticket] = false;
-  c.queue.push_back(std::move(p));
-  s->queued++;
-  s->cv_work.notify_one();
-  return PW_OK;
-}
-
-pw_status pw_sched_wait(pw_sched* s, uint64_t ticket, void* host_dst, size_t bytes) {
-  if (!s) return PW_ERR_INVALID;
-  SchedResult r;
-  {
-    std::unique_lock<std::mutex> lk(s->mu);
-    auto o = s->outstanding.find(ticket);
-    if (o == s->outstanding.end() || o->second) return PW_ERR_INVALID;   // unknown, collected already, or being waited for
-    o->second = true;
-    s->cv_done.wait(lk, [&] { return s->results.count(ticket) != 0 || s->stop; });
-    s->outstanding.erase(ticket);
-    auto it = s->results.find(ticket);
-    if (it == s->results.end()) return PW_ERR_INVALID;   // the scheduler was shut down first
-    r = it->second;
-    s->results.erase(it);
-    if (r.status == PW_OK) s->collecting++;
-  }
-  if (r.status != PW_OK) return r.status;
-  pw_status st = pw_await(s->ctx, r.out, host_dst, bytes);
-  (void)pw_future_release(s->ctx, r.out);
-  {
-    std::lock_guard<std::mutex> lk(s->mu);
-    s->collecting--;
-  }
-  return st;
-}
-
-pw_status pw_sched_drain(pw_sched* s) {
-  if (!s) return PW_ERR_INVALID;
-  std::unique_lock<std::mutex> lk(s->mu);
-  s->cv_done.wait(lk, [&] { return (s->queued == 0 && s->idle) || s->stop; });
-  return PW_OK;
-}
-
-pw_status pw_sched_client_stats(pw_sched* s, int client, int64_t* programs, int64_t* computations, double* device_ms) {
-  if (!s) return PW_ERR_INVALID;
-  std::lock_guard<std::mutex> lk(s->mu);
-  if (client < 0 || client >= (int)s->clients.size()) return PW_ERR_INVALID;
-  if (programs) *programs = s->clients[client].programs;
-  if (computations) *computations = s->clients[client].computations;
-  if (device_ms) *device_ms = s->clients[client].device_ms;
-  return PW_OK;
-}
-
-pw_status pw_sched_trace(pw_sched* s, pw_sched_slice* out, int capacity, int* n) {
-  if (!s || !n || capacity < 0 || (capacity > 0 && !out)) return PW_ERR_INVALID;
-  std::lock_guard<std::mutex> lk(s->mu);
-  const int k = std::min<int>(capacity, (int)s->trace.size());
-  for (int i = 0; i < k; ++i) out[i] = s->trace[i];
-  *n = (int)s->trace.size();
-  return PW_OK;
-}
-
-pw_status pw_train_step(pw_ctx* c, pw_fn step_fn, pw_future tokens, pw_future* loss_out) {
-  PW_API_LOCK(c);
-  if (!c || !loss_out) return PW_ERR_INVALID;
-  FnRec* fn = fn_get(c, step_fn);
-  if (!fn || fn->desc.kind != PW_FN_LM_TRAIN_STEP) return fail(c, PW_ERR_INVALID, "not a train-step function");
-  return pw_run_fn(c, step_fn, &tokens, 1, loss_out, 1);
-}
-
 // ---- futures -----------------------------------------------------------------------------------------
 
 pw_status pw_await(pw_ctx* c, pw_future h, void* host_dst, size_t bytes) {
@@ -1784,286 +1179,6 @@ pw_status pw_future_release(pw_ctx* c, pw_future h) {
     (void)hipStreamWaitEvent(c->exec, f->event, 0);
   }
   future_drop(c, h);
-  return PW_OK;
-}
-
-// ---- model -------------------------------------------------------------------------------------------
-
-pw_status pw_model_create(pw_ctx* c, const pw_lm_config* cfg, pw_model** out) {
-  if (!c || !cfg || !out) return PW_ERR_INVALID;
-  std::string why;
-  if (!model_config_ok(*cfg, &why)) return fail(c, PW_ERR_UNSUPPORTED, "%s", why.c_str());
-  Model* m = nullptr;
-  hipError_t e = model_create(*cfg, c->exec, &m, &why);
-  if (e != hipSuccess) return fail(c, e == hipErrorOutOfMemory ? PW_ERR_OOM : PW_ERR_DEVICE, "%s", why.c_str());
-  c->models.push_back(m);
-  *out = new pw_model{c, m};
-  return PW_OK;
-}
-
-pw_status pw_model_destroy(pw_model* pm) {
-  if (!pm) return PW_ERR_INVALID;
-  pw_ctx* c = pm->ctx;
-  (void)hipStreamSynchronize(c->exec);
-  for (size_t i = 0; i < c->models.size(); ++i)
-    if (c->models[i] == pm->impl) {
-      c->models.erase(c->models.begin() + i);
-      model_destroy(pm->impl);
-      break;
-    }
-  for (auto& f : c->fns)
-    if (f.live && f.model == pm->impl) f.live = false;   // functions of a dead model die with it
-  delete pm;
-  return PW_OK;
-}
-
-// Parameter-table access shared by the two kinds of model (both keep their state in a ModelBase).
-static float* part_base(ModelBase* m, int part) {
-  switch (part) {
-    case PW_PARAMS: return m->w;
-    case PW_GRADS: return m->g;
-    case PW_ADAM_M: return m->m;
-    case PW_ADAM_V: return m->v;
-  }
-  return nullptr;
-}
-static pw_status state_param_info(ModelBase* m, int64_t idx, char* name, int cap, int64_t* numel) {
-  if (idx < 0 || idx >= (int64_t)m->params.size()) return PW_ERR_INVALID;
-  const ParamInfo& p = m->params[idx];
-  if (name && cap > 0) snprintf(name, cap, "%s", p.name.c_str());
-  if (numel) *numel = p.numel;
-  return PW_OK;
-}
-static pw_status state_import(pw_ctx* c, ModelBase* m, int part, int64_t idx, const float* src, int src_on_device) {
-  if (!src || idx < 0 || idx >= (int64_t)m->params.size()) return PW_ERR_INVALID;
-  float* base = part_base(m, part);
-  if (!base) return fail(c, PW_ERR_INVALID, "this model has no such part");
-  const ParamInfo& p = m->params[idx];
-  PW_HIP(c, hipMemcpyAsync(base + p.offset, src, (size_t)p.numel * 4, src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, c->exec));
-  if (part == PW_PARAMS) {
-    hipError_t e = model_state_refresh_lowp(m, p.offset, p.numel);
-    if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "bf16 refresh: %s", hipGetErrorString(e));
-  }
-  PW_HIP(c, hipStreamSynchronize(c->exec));
-  return PW_OK;
-}
-static pw_status state_export(pw_ctx* c, ModelBase* m, int part, int64_t idx, float* dst) {
-  if (!dst || idx < 0 || idx >= (int64_t)m->params.size()) return PW_ERR_INVALID;
-  float* base = part_base(m, part);
-  if (!base) return fail(c, PW_ERR_INVALID, "this model has no such part");
-  const ParamInfo& p = m->params[idx];
-  PW_HIP(c, hipStreamSynchronize(c->exec));
-  PW_HIP(c, hipMemcpy(dst, base + p.offset, (size_t)p.numel * 4, hipMemcpyDeviceToHost));
-  return PW_OK;
-}
-// Copies n elements of a device array in the activation type out as fp32, after draining the executor stream.
-static pw_status export_activation(pw_ctx* c, const void* src, int64_t n, bool is_bf16, float* dst) {
-  PW_HIP(c, hipStreamSynchronize(c->exec));
-  if (!is_bf16) {
-    PW_HIP(c, hipMemcpy(dst, src, (size_t)n * 4, hipMemcpyDeviceToHost));
-    return PW_OK;
-  }
-  float* tmp = nullptr;
-  PW_HIP(c, hipMalloc(&tmp, (size_t)n * 4));
-  hipError_t e = launch_bf16_to_f32(c->exec, src, tmp, n);
-  if (e == hipSuccess) e = hipStreamSynchronize(c->exec);
-  if (e == hipSuccess) e = hipMemcpy(dst, tmp, (size_t)n * 4, hipMemcpyDeviceToHost);
-  (void)hipFree(tmp);
-  if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "activation export: %s", hipGetErrorString(e));
-  return PW_OK;
-}
-
-int64_t pw_model_param_count(pw_model* pm) { return pm ? (int64_t)pm->impl->params.size() : -1; }
-pw_status pw_model_param_info(pw_model* pm, int64_t idx, char* name, int cap, int64_t* numel) {
-  return pm ? state_param_info(pm->impl, idx, name, cap, numel) : PW_ERR_INVALID;
-}
-pw_status pw_model_import(pw_model* pm, int part, int64_t idx, const float* src, int src_on_device) {
-  return pm ? state_import(pm->ctx, pm->impl, part, idx, src, src_on_device) : PW_ERR_INVALID;
-}
-pw_status pw_model_export(pw_model* pm, int part, int64_t idx, float* dst) {
-  return pm ? state_export(pm->ctx, pm->impl, part, idx, dst) : PW_ERR_INVALID;
-}
-
-pw_status pw_model_zero_grads(pw_model* pm) {
-  if (!pm) return PW_ERR_INVALID;
-  if (model_zero_grads(pm->impl) != hipSuccess) return fail(pm->ctx, PW_ERR_DEVICE, "%s", pm->impl->error.c_str());
-  return PW_OK;
-}
-
-pw_status pw_model_apply_optimizer(pw_model* pm) {
-  if (!pm) return PW_ERR_INVALID;
-  if (model_apply_optimizer(pm->impl) != hipSuccess) return fail(pm->ctx, PW_ERR_DEVICE, "%s", pm->impl->error.c_str());
-  return PW_OK;
-}
-
-pw_status pw_model_export_activation(pw_model* pm, const char* name, int mb, float* dst, int64_t numel) {
-  if (!pm || !name || !dst) return PW_ERR_INVALID;
-  pw_ctx* c = pm->ctx;
-  Model* m = pm->impl;
-  if (mb < 0 || mb >= m->cfg.n_microbatch) return fail(c, PW_ERR_INVALID, "micro-batch index out of range");
-  const int64_t N = m->N(), d = m->cfg.d_model;
-  const void* src = nullptr;
-  int64_t n = 0;
-  int dt = PW_F32;
-  const std::string s(name);
-  if (s == "x_out") { src = m->slots[mb].x_out; n = N * d; }
-  else if (s == "dlogits" && m->logits) { src = m->logits; n = N * m->cfg.vocab; dt = m->act_dtype(); }
-  else if (s == "dx_in") { src = m->dx_a; n = N * d; }
-  else return fail(c, PW_ERR_INVALID, "unknown activation name");
-  if (numel != n) return fail(c, PW_ERR_SHAPE, "activation has %lld elements", (long long)n);
-  return export_activation(c, src, n, dt != PW_F32, dst);
-}
-
-double pw_model_step_flops(const pw_lm_config* cfg) { return cfg ? model_step_flops(*cfg) : 0.0; }
-
-// ---- encoder-decoder model -------------------------------------------------------------------------------
-
-pw_status pw_encdec_create(pw_ctx* c, const pw_encdec_config* cfg, pw_encdec** out) {
-  if (!c || !cfg || !out) return PW_ERR_INVALID;
-  std::string why;
-  if (!encdec_config_ok(*cfg, &why)) return fail(c, PW_ERR_UNSUPPORTED, "%s", why.c_str());
-  EncDec* m = nullptr;
-  hipError_t e = encdec_create(*cfg, c->exec, &m, &why);
-  if (e != hipSuccess) return fail(c, e == hipErrorOutOfMemory ? PW_ERR_OOM : PW_ERR_DEVICE, "%s", why.c_str());
-  c->encdecs.push_back(m);
-  *out = new pw_encdec{c, m};
-  return PW_OK;
-}
-
-pw_status pw_encdec_destroy(pw_encdec* pm) {
-  if (!pm) return PW_ERR_INVALID;
-  pw_ctx* c = pm->ctx;
-  (void)hipStreamSynchronize(c->exec);
-  for (size_t i = 0; i < c->encdecs.size(); ++i)
-    if (c->encdecs[i] == pm->impl) {
-      c->encdecs.erase(c->encdecs.begin() + i);
-      encdec_destroy(pm->impl);
-      break;
-    }
-  for (auto& f : c->fns)
-    if (f.live && f.encdec == pm->impl) f.live = false;   // functions of a dead model die with it
-  delete pm;
-  return PW_OK;
-}
-
-int64_t pw_encdec_param_count(pw_encdec* pm) { return pm ? (int64_t)pm->impl->params.size() : -1; }
-pw_status pw_encdec_param_info(pw_encdec* pm, int64_t idx, char* name, int cap, int64_t* numel) {
-  return pm ? state_param_info(pm->impl, idx, name, cap, numel) : PW_ERR_INVALID;
-}
-pw_status pw_encdec_import(pw_encdec* pm, int part, int64_t idx, const float* src, int src_on_device) {
-  return pm ? state_import(pm->ctx, pm->impl, part, idx, src, src_on_device) : PW_ERR_INVALID;
-}
-pw_status pw_encdec_export(pw_encdec* pm, int part, int64_t idx, float* dst) {
-  return pm ? state_export(pm->ctx, pm->impl, part, idx, dst) : PW_ERR_INVALID;
-}
-
-pw_status pw_encdec_export_activation(pw_encdec* pm, const char* name, float* dst, int64_t numel) {
-  if (!pm || !name || !dst) return PW_ERR_INVALID;
-  pw_ctx* c = pm->ctx;
-  EncDec* m = pm->impl;
-  if (std::string(name) != "dlogits") return fail(c, PW_ERR_INVALID, "unknown activation name");
-  const int64_t n = (int64_t)m->Nt() * m->cfg.vocab;
-  if (numel != n) return fail(c, PW_ERR_SHAPE, "activation has %lld elements", (long long)n);
-  return export_activation(c, m->logits, n, m->bf16 != 0, dst);
-}
-
-double pw_encdec_step_flops(const pw_encdec_config* cfg) { return cfg ? encdec_step_flops(*cfg) : 0.0; }
-
-// ---- single kernels ------------------------------------------------------------------------------------
-
-#define PW_OP(c, expr)                                                                               \
-  do {                                                                                               \
-    if (!(c)) return PW_ERR_INVALID;                                                                 \
-    hipError_t e_ = (expr);                                                                          \
-    if (e_ == hipErrorInvalidValue) return fail(c, PW_ERR_INVALID, "arguments rejected by the launcher"); \
-    if (e_ == hipErrorNotSupported) return fail(c, PW_ERR_UNSUPPORTED, "not supported");            \
-    if (e_ != hipSuccess) return fail(c, PW_ERR_DEVICE, "%s", hipGetErrorString(e_));               \
-    return PW_OK;                                                                                    \
-  } while (0)
-
-static GemmArgs gemm_args_of(const pw_gemm_args* a) {
-  GemmArgs g{};
-  g.dtype = a->dtype; g.a_kmajor = a->a_kmajor; g.b_kmajor = a->b_kmajor;
-  g.M = a->M; g.N = a->N; g.K = a->K; g.lda = a->lda; g.ldb = a->ldb; g.ldc = a->ldc;
-  g.epilogue = a->epilogue; g.out_dtype = a->out_dtype; g.accumulate = a->accumulate;
-  g.A = a->A; g.B = a->B; g.bias = a->bias; g.aux = a->aux; g.C = a->C; g.C2 = a->C2;
-  g.b_colsum = a->b_colsum;
-  return g;
-}
-pw_status pw_op_gemm(pw_ctx* c, const pw_gemm_args* a) {
-  if (!c || !a) return PW_ERR_INVALID;
-  PW_OP(c, launch_gemm(c->exec, gemm_args_of(a)));
-}
-pw_status pw_op_gemm_pair(pw_ctx* c, const pw_gemm_args* a0, const pw_gemm_args* a1) {
-  if (!c || !a0 || !a1) return PW_ERR_INVALID;
-  PW_OP(c, launch_gemm_pair(c->exec, gemm_args_of(a0), gemm_args_of(a1)));
-}
-pw_status pw_op_gemm_group(pw_ctx* c, const pw_gemm_args* a, int n) {
-  if (!c || !a || n < 1 || n > 3) return PW_ERR_INVALID;
-  GemmArgs g[3];
-  for (int i = 0; i < n; ++i) g[i] = gemm_args_of(&a[i]);
-  PW_OP(c, launch_gemm_group(c->exec, g, n));
-}
-pw_status pw_op_embedding_fwd(pw_ctx* c, const int32_t* tokens, const float* wte, const float* wpe, float* x, int B, int T, int d, int V) {
-  PW_OP(c, launch_embedding_fwd(c->exec, tokens, wte, wpe, x, B, T, d, V));
-}
-pw_status pw_op_embedding_bwd(pw_ctx* c, const int32_t* tokens, const float* dx, float* dwte, float* dwpe, int B, int T, int d, int V) {
-  PW_OP(c, launch_embedding_bwd(c->exec, tokens, dx, dwte, dwpe, B, T, d, V));
-}
-pw_status pw_op_layernorm_fwd(pw_ctx* c, int dtype, const float* x, const float* g, const float* b, void* y, float* mean, float* rstd, int N, int d) {
-  PW_OP(c, launch_layernorm_fwd(c->exec, dtype, x, g, b, y, mean, rstd, N, d));
-}
-pw_status pw_op_layernorm_bwd(pw_ctx* c, int dtype, const void* dy, const float* x, const float* g, const float* mean, const float* rstd,
-                              const float* dres, float* dx, void* dx_lp, float* dg, float* db, float* dxsum, float* ws, int N, int d, int accumulate) {
-  PW_OP(c, launch_layernorm_bwd(c->exec, dtype, dy, x, g, mean, rstd, dres, dx, dx_lp, dg, db, dxsum, ws, N, d, accumulate));
-}
-int64_t pw_layernorm_bwd_ws_floats(int N, int d) { return layernorm_bwd_ws_floats(N, d); }
-pw_status pw_op_attention_fwd(pw_ctx* c, int dtype, const void* qkv, void* o, float* lse, int B, int T, int H, int hd) {
-  PW_OP(c, launch_attention_fwd(c->exec, dtype, qkv, o, lse, B, T, H, hd));
-}
-pw_status pw_op_attention_bwd(pw_ctx* c, int dtype, const void* qkv, const void* o, const void* dout, const float* lse, float* delta,
-                              void* dqkv, int B, int T, int H, int hd) {
-  PW_OP(c, launch_attention_bwd(c->exec, dtype, qkv, o, dout, lse, delta, dqkv, B, T, H, hd));
-}
-static MhaArgs mha_args_of(const pw_mha_args* a) {
-  return MhaArgs{a->dtype, a->q, a->k, a->v, a->ldq, a->ldkv, a->B, a->Tq, a->Tk, a->H, a->hd, a->causal};
-}
-pw_status pw_op_mha_fwd(pw_ctx* c, const pw_mha_args* a, void* o, void* o_lo, float* lse) {
-  if (!a) return PW_ERR_INVALID;
-  PW_OP(c, launch_mha_fwd(c->exec, mha_args_of(a), o, o_lo, lse));
-}
-pw_status pw_op_mha_bwd(pw_ctx* c, const pw_mha_args* a, const void* o, const void* o_lo, const void* dout, const float* lse,
-                        float* delta, void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv) {
-  if (!a) return PW_ERR_INVALID;
-  PW_OP(c, launch_mha_bwd(c->exec, mha_args_of(a), o, o_lo, dout, lse, delta, dq, lddq, dk, dv, lddkv));
-}
-pw_status pw_op_softmax_xent(pw_ctx* c, int dtype, void* z, const int32_t* tokens, float* loss, float* row_loss, int B, int T, int V) {
-  PW_OP(c, launch_softmax_xent(c->exec, dtype, z, tokens, loss, row_loss, B, T, V));
-}
-pw_status pw_op_colsum(pw_ctx* c, int dtype, const void* in, float* out, float* ws, int64_t rows, int64_t cols, int accumulate) {
-  PW_OP(c, launch_colsum(c->exec, dtype, in, out, ws, rows, cols, accumulate));
-}
-int64_t pw_colsum_ws_floats(int64_t rows, int64_t cols) { return colsum_ws_floats(rows, cols); }
-pw_status pw_op_sgd(pw_ctx* c, float* w, const float* g, int64_t n, float lr) { PW_OP(c, launch_sgd(c->exec, w, g, n, lr)); }
-pw_status pw_op_adam(pw_ctx* c, float* w, float* m, float* v, const float* g, void* w_bf16, int64_t n, float lr, float beta1, float beta2,
-                     float eps, int t) {
-  PW_OP(c, launch_adam(c->exec, w, m, v, g, w_bf16, n, lr, beta1, beta2, eps, t, nullptr));
-}
-
-pw_status pw_profile_begin(pw_ctx* c) {
-  if (!c) return PW_ERR_INVALID;
-  gemm_profile_begin();
-  return PW_OK;
-}
-pw_status pw_profile_pause(pw_ctx* c) {
-  if (!c) return PW_ERR_INVALID;
-  gemm_profile_pause();
-  return PW_OK;
-}
-pw_status pw_profile_end(pw_ctx* c, int64_t* launches, double* total_ms, double* total_flops) {
-  if (!c) return PW_ERR_INVALID;
-  hipError_t e = gemm_profile_end(launches, total_ms, total_flops);
-  if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "profile read: %s", hipGetErrorString(e));
   return PW_OK;
 }
 
