@@ -171,11 +171,29 @@ def cpu_baseline(cfg, pwb, budget_tokens: int = 768):
                       f"tokens/s extrapolated to the full workload by model-FLOP ratio"}
 
 
+def device_note(torch):
+    """What the numbers were taken on: device name, compute units, and the engine clock levels the driver lists
+    right after the timed region (sysfs; the active level carries a star; absent if not readable)."""
+    prop = torch.cuda.get_device_properties(0)
+    note = {"name": prop.name, "arch": getattr(prop, "gcnArchName", ""), "compute_units": prop.multi_processor_count,
+            "peak_used_tflops": PEAK_BF16_TFLOPS}
+    try:
+        import glob
+        for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
+            levels = [ln.strip() for ln in open(path) if ln.strip()]
+            if levels:
+                note["sclk_levels_after_run"] = levels
+                break
+    except OSError:
+        pass
+    return note
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dispatch", action="store_true")
@@ -321,13 +339,14 @@ def main():
         "ms_per_step_device": {"median": round(per_step[len(per_step) // 2], 3), "min": round(per_step[0], 3),
                                "max": round(per_step[-1], 3)},
         loss_key: [round(losses[0], 4), round(losses[-1], 4)],
-        "roofline": {"bound": "mfma", "kernel": "bf16 MFMA GEMM (gemm_ring_kernel + gemm_bf16_kernel, all layouts)", "achieved": round(gemm_tflops, 1),
+        "roofline": {"bound": "mfma", "kernel": "bf16 MFMA GEMM (gemm_ring_kernel, gemm_ring_group_kernel, gemm_bf16_kernel; all layouts)", "achieved": round(gemm_tflops, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": recorded_gemm_traffic(args.workload), "launches_per_step": n_gemm // max(1, profiled_steps), "steps_with_events": profiled_steps,
                      "avg_launch_ms": round(gemm_ms / max(1, n_gemm), 4),
                      "avg_launch_gflop": round(gemm_flops / max(1, n_gemm) / 1e9, 2),
                      "gemm_ms_per_step": round(gemm_ms / max(1, profiled_steps), 3)},
     }
+    result["device"] = device_note(torch)
     if not args.no_dispatch:
         result["dispatch_us_per_fn"] = dispatch_bench(ctx, pwb, I)
     model.close()
