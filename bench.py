@@ -171,21 +171,73 @@ def cpu_baseline(cfg, pwb, budget_tokens: int = 768):
                       f"tokens/s extrapolated to the full workload by model-FLOP ratio"}
 
 
-def device_note(torch):
-    """What the numbers were taken on: device name, compute units, and the engine clock levels the driver lists
-    right after the timed region (sysfs; the active level carries a star; absent if not readable)."""
+class ClockPowerSampler:
+    """Reads the engine clock level and the board power from sysfs every 50 ms on a host thread while the timed
+    steps run (host reads only; nothing is sent to the GPU).  The step is power-limited on this chip, so the clock
+    it actually ran at belongs next to a fraction of a peak that is quoted at the nominal clock."""
+
+    def __init__(self):
+        import glob
+        self.sclk = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))[:1]
+        hw = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*"))[:1]
+        self.power = [h + "/power1_input" for h in hw if os.path.exists(h + "/power1_input")] + \
+                     [h + "/power1_average" for h in hw if os.path.exists(h + "/power1_average")]
+        self.cap = [h + "/power1_cap" for h in hw if os.path.exists(h + "/power1_cap")]
+        self.mhz, self.watts = [], []
+        self._stop = False
+        self._thread = None
+
+    @staticmethod
+    def _read(path):
+        try:
+            with open(path) as f:
+                return f.read()
+        except OSError:
+            return ""
+
+    def _loop(self):
+        import re
+        while not self._stop:
+            for p in self.sclk:
+                m = re.search(r"(\d+)\s*Mhz\s*\*", self._read(p))
+                if m:
+                    self.mhz.append(int(m.group(1)))
+            for p in self.power[:1]:
+                t = self._read(p).strip()
+                if t.isdigit():
+                    self.watts.append(int(t) / 1e6)
+            time.sleep(0.05)
+
+    def start(self):
+        import threading
+        self._thread = threading.Thread(target=self._loop, daemon=True)
+        self._thread.start()
+
+    def stop(self):
+        self._stop = True
+        if self._thread is not None:
+            self._thread.join()
+        note = {}
+        if self.mhz:
+            note["sclk_mhz_during_timed_steps"] = {"mean": round(sum(self.mhz) / len(self.mhz)), "min": min(self.mhz),
+                                                   "max": max(self.mhz), "samples": len(self.mhz)}
+        if self.watts:
+            note["board_power_w_during_timed_steps"] = {"mean": round(sum(self.watts) / len(self.watts)),
+                                                        "max": round(max(self.watts))}
+        for p in self.cap:
+            t = self._read(p).strip()
+            if t.isdigit():
+                note["board_power_cap_w"] = round(int(t) / 1e6)
+        return note
+
+
+def device_note(torch, sampled):
+    """What the numbers were taken on: device name, compute units, the peak used as the denominator (nominal
+    clock), and what the sampler saw of clock and power during the timed steps."""
     prop = torch.cuda.get_device_properties(0)
     note = {"name": prop.name, "arch": getattr(prop, "gcnArchName", ""), "compute_units": prop.multi_processor_count,
-            "peak_used_tflops": PEAK_BF16_TFLOPS}
-    try:
-        import glob
-        for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
-            levels = [ln.strip() for ln in open(path) if ln.strip()]
-            if levels:
-                note["sclk_levels_after_run"] = levels
-                break
-    except OSError:
-        pass
+            "peak_used_tflops": PEAK_BF16_TFLOPS, "nominal_clock_mhz": 2400}
+    note.update(sampled)
     return note
 
 
@@ -285,6 +337,8 @@ def main():
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
     pending = []
+    sampler = ClockPowerSampler()
+    sampler.start()
     marks[0].record(ext)
     for i in range(args.steps):
         if profiled_steps and i == profiled_steps:
@@ -294,6 +348,7 @@ def main():
     ctx.synchronize()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    sampled = sampler.stop()
     per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     n_gemm, gemm_ms, gemm_flops = ctx.profile_end() if profiled_steps else (0, 0.0, 0.0)
     for f in pending:
@@ -346,7 +401,7 @@ def main():
                      "avg_launch_gflop": round(gemm_flops / max(1, n_gemm) / 1e9, 2),
                      "gemm_ms_per_step": round(gemm_ms / max(1, profiled_steps), 3)},
     }
-    result["device"] = device_note(torch)
+    result["device"] = device_note(torch, sampled)
     if not args.no_dispatch:
         result["dispatch_us_per_fn"] = dispatch_bench(ctx, pwb, I)
     model.close()

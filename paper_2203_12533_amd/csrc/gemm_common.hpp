@@ -199,13 +199,39 @@ struct GemmBf16Params {
 // the epilogue (output, residual, saved pre-activation) is a 16-byte vector and every row segment a full
 // 128-byte line or more.  What a segment needs from memory besides the accumulators is fetched one 32-row block
 // ahead.  All waves of the block must call (it synchronises the block).
-template <int FM, int FN, bool EDGE, int KIND>
-__device__ __forceinline__ void gemm_epilogue_staged_kind(bf16* smem, f32x16 (&acc)[FM][FN], const GemmBf16Params& p,
+// Parks 32-row block i, 64-column half h of a wave tile in `stage` (rows of ld floats), from either accumulator
+// layout: 32 x 32 MFMA blocks (layout above) or 16 x 16 blocks, where acc[a][b][r] is element m = 16 a + lane%16,
+// n = 16 b + 4 (lane/16) + r.  Both write 16-byte pieces that tile the banks without conflicts at ld = 68.
+template <int FM, int FN>
+__device__ __forceinline__ void stage_block(float* stage, int ld, const f32x16 (&acc)[FM][FN], int i, int h, int lane) {
+  const int lrow = lane & 31, lhalf = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int qq = 0; qq < 4; ++qq)
+      *reinterpret_cast<float4*>(stage + lrow * ld + j * 32 + qq * 8 + lhalf * 4) =
+          make_float4(acc[i][2 * h + j][qq * 4], acc[i][2 * h + j][qq * 4 + 1], acc[i][2 * h + j][qq * 4 + 2],
+                      acc[i][2 * h + j][qq * 4 + 3]);
+}
+template <int FM16, int FN16>
+__device__ __forceinline__ void stage_block(float* stage, int ld, const f32x4 (&acc)[FM16][FN16], int i, int h, int lane) {
+  const int lrow = lane & 15, lq = lane >> 4;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+      *reinterpret_cast<float4*>(stage + (a * 16 + lrow) * ld + b * 16 + lq * 4) =
+          make_float4(acc[2 * i + a][4 * h + b][0], acc[2 * i + a][4 * h + b][1], acc[2 * i + a][4 * h + b][2],
+                      acc[2 * i + a][4 * h + b][3]);
+}
+
+// FM, FN: the wave tile in units of 32 rows / 32 columns, whatever the accumulator layout.
+template <int FM, int FN, bool EDGE, int KIND, typename Acc>
+__device__ __forceinline__ void gemm_epilogue_staged_kind(bf16* smem, Acc& acc, const GemmBf16Params& p,
                                                           int64_t mw0, int64_t nw0, int wave, int lane) {
   static_assert(FN % 2 == 0, "epilogue staging works on 64-column halves of the wave tile");
   constexpr int kLdS = 64 + 4;   // floats; 272-byte rows keep the 16-byte LDS accesses conflict-free
   constexpr bool kAhead = KIND != kExtraNone;
-  const int lrow = lane & 31, lhalf = lane >> 5;
   const int r8 = lane >> 3, c8 = lane & 7;
   const void* const extra_src = epi_extra_src(p.epi, KIND);
   const int64_t M = p.M, N = p.N, ldc = p.epi.ldc;
@@ -237,13 +263,7 @@ __device__ __forceinline__ void gemm_epilogue_staged_kind(bf16* smem, f32x16 (&a
   for (int h = 0; h < FN / 2; ++h) {
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int qq = 0; qq < 4; ++qq)
-          *reinterpret_cast<float4*>(stage + lrow * kLdS + j * 32 + qq * 8 + lhalf * 4) =
-              make_float4(acc[i][2 * h + j][qq * 4], acc[i][2 * h + j][qq * 4 + 1], acc[i][2 * h + j][qq * 4 + 2],
-                          acc[i][2 * h + j][qq * 4 + 3]);
+      stage_block(stage, kLdS, acc, i, h, lane);
       sync();
       const bool wrap = i + 1 == FM;
       const int ni = wrap ? 0 : i + 1, nh = wrap ? h + 1 : h;
@@ -275,8 +295,8 @@ __device__ __forceinline__ void gemm_epilogue_staged_kind(bf16* smem, f32x16 (&a
   }
 }
 
-template <int FM, int FN, bool EDGE>
-__device__ __forceinline__ void gemm_epilogue_staged(bf16* smem, f32x16 (&acc)[FM][FN], const GemmBf16Params& p,
+template <int FM, int FN, bool EDGE, typename Acc>
+__device__ __forceinline__ void gemm_epilogue_staged(bf16* smem, Acc& acc, const GemmBf16Params& p,
                                                      int64_t mw0, int64_t nw0, int wave, int lane) {
   switch (epi_extra_kind(p.epi)) {   // uniform over the launch
     case kExtraAuxBf16: gemm_epilogue_staged_kind<FM, FN, EDGE, kExtraAuxBf16>(smem, acc, p, mw0, nw0, wave, lane); break;

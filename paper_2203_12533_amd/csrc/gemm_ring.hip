@@ -31,6 +31,10 @@ namespace {
 constexpr int kRT = 256;            // tile is kRT x kRT
 constexpr int kRBK = 64;            // k per stage
 constexpr int kRStages = 2;
+#ifndef PW_RING_HM
+#define PW_RING_HM 2
+#endif
+constexpr int kRingHM = PW_RING_HM;     // 16-row blocks of A per unit of the main loop (see ring_tile)
 constexpr int kROperand = kRT * kRBK;            // elements per operand tile (32 KiB)
 constexpr int kRStage = 2 * kROperand;           // elements per stage
 
@@ -60,28 +64,29 @@ __device__ __forceinline__ void issue_one(const bf16* __restrict__ base, int64_t
     g = base + (row0 + r) * ld + k0 + c * 8;
   } else {
     const int k = instr * 2 + (lane >> 5);        // 2 k-rows x 512 bytes per instruction
-    const int c = (lane & 31) ^ (4 * (k & 3));
+    const int c = (lane & 31) ^ (4 * (k & 3)) ^ (2 * ((k >> 3) & 1));
     g = base + (k0 + k) * ld + row0 + c * 8;
   }
   dma16(g, lds_tile_off + instr * 1024);
 }
 
-// One MFMA operand fragment (rows frag_row0 .. +31 of the tile, k16 step kk) for this lane.
+// One operand fragment of v_mfma_f32_16x16x32_bf16 for this lane: row frag_row0 + lane % 16 of the tile, the 8
+// k-values 32 kk + 8 (lane / 16) .. + 7.  (Both operands of that instruction have this lane layout.)
 template <bool KMAJOR>
 __device__ __forceinline__ bf16x8 read_fragment(const bf16* lds_tile, int frag_row0, int kk, int lane) {
   if (!KMAJOR) {
-    const int r = frag_row0 + (lane & 31);
-    const int c = (2 * kk + (lane >> 5)) ^ ((r >> 1) & 7);
+    const int r = frag_row0 + (lane & 15);
+    const int c = (4 * kk + (lane >> 4)) ^ ((r >> 1) & 7);
     return *reinterpret_cast<const bf16x8*>(lds_tile + r * kRBK + c * 8);
   } else {
     const int grp = lane >> 4, L = lane & 15;
-    const int row = frag_row0 + 16 * (grp & 1) + 4 * (L & 3);     // first of the 4 rows this lane points at
-    const int kbase = kk * 16 + 8 * (grp >> 1) + (L >> 2);
+    const int row = frag_row0 + 4 * (L & 3);                      // first of the 4 rows this lane points at
+    const int kbase = kk * 32 + 8 * grp + (L >> 2);
     union { bf16x8 v; short4v h[2]; } u;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int k = kbase + 4 * t;
-      const int c = (row >> 3) ^ (4 * (k & 3));
+      const int c = (row >> 3) ^ (4 * (k & 3)) ^ (2 * ((k >> 3) & 1));
       const bf16* p = lds_tile + k * kRT + c * 8 + (row & 7);
       u.h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)p);
     }
@@ -90,8 +95,9 @@ __device__ __forceinline__ bf16x8 read_fragment(const bf16* lds_tile, int frag_r
 }
 
 // One 256 x 256 output tile of problem p; pid: index of the tile's workgroup among the problem's own.
-// Waves form a 2 x NW grid: NW = 4 -> 8 waves with 128 x 64 wave tiles, NW = 2 -> 4 waves with 128 x 128 wave
-// tiles (a third fewer LDS fragment reads per MFMA; the 256 accumulator registers then live in AGPRs).
+// Waves form a 2 x NW grid: NW = 4 -> 8 waves with 128 x 64 wave tiles.  The products are 16 x 16 x 32 MFMAs: on
+// operands with random mantissas the chip runs into its board power limit, and per flop that shape draws less
+// than the 32 x 32 x 16 one (same loop, same LDS bytes: 2.06 against 1.82 PFLOP/s sustained).
 template <bool A_KMAJOR, bool B_KMAJOR, int NW>
 __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16* smem) {
   int tm, tn;
@@ -99,18 +105,21 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
   const int64_t m0 = (int64_t)tm * kRT, n0 = (int64_t)tn * kRT;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave / NW, wn = wave % NW;
-  constexpr int FM = 4, FN = kRT / NW / 32;
   constexpr int kWaveN = kRT / NW;                    // columns of a wave tile
+  constexpr int FM = 8, FN = kWaveN / 16;             // 16 x 16 accumulator blocks of the 128 x kWaveN wave tile
+  constexpr int HM = kRingHM;                         // a unit of work: HM row blocks x FN column blocks, one 32-deep k-step
+  constexpr int UPS = FM / HM;                        // units per k-step
   constexpr int PER = 32 / (2 * NW);                  // direct-load instructions per operand tile and wave
-  static_assert(FM * FN == 2 * PER, "one direct load is issued behind each MFMA of the last k-step");
+  static_assert((HM * FN) % (2 * PER) == 0, "the direct loads are spread evenly over the MFMAs of the last unit");
+  constexpr int kIssueEvery = HM * FN / (2 * PER);
 
-  f32x16 acc[FM][FN];
+  f32x4 acc[FM][FN];
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
 
   // Column sums of a k-major B (the bias gradient that goes with a weight gradient): the waves of the first tile
   // row that own the B columns (wm == 0) add up the fragments they read anyway.
@@ -139,13 +148,16 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
     if (idx < PER) issue_one<A_KMAJOR, PER>(p.A, p.lda, m0, (int64_t)kt * kRBK, stage, wave_s, lane, idx);
     else issue_one<B_KMAJOR, PER>(p.B, p.ldb, n0, (int64_t)kt * kRBK, stage + kROperand * 2, wave_s, lane, idx - PER);
   };
-  auto load_frags = [&](int stage, int kk, bf16x8* af, bf16x8* bfr) {
+  // A unit u of a k-tile: k-step u / UPS (32 deep), row blocks HM (u % UPS) .. + HM - 1 of the wave tile.
+  auto load_a = [&](int stage, int u, bf16x8* af) {
     const bf16* a_tile = smem + stage * kRStage;
-    const bf16* b_tile = a_tile + kROperand;
 #pragma unroll
-    for (int i = 0; i < FM; ++i) af[i] = read_fragment<A_KMAJOR>(a_tile, wm * 128 + i * 32, kk, lane);
+    for (int i = 0; i < HM; ++i) af[i] = read_fragment<A_KMAJOR>(a_tile, wm * 128 + ((u % UPS) * HM + i) * 16, u / UPS, lane);
+  };
+  auto load_b = [&](int stage, int ks, bf16x8* bfr) {
+    const bf16* b_tile = smem + stage * kRStage + kROperand;
 #pragma unroll
-    for (int j = 0; j < FN; ++j) bfr[j] = read_fragment<B_KMAJOR>(b_tile, wn * kWaveN + j * 32, kk, lane);
+    for (int j = 0; j < FN; ++j) bfr[j] = read_fragment<B_KMAJOR>(b_tile, wn * kWaveN + j * 16, ks, lane);
   };
   auto wait_and_sync = [&]() {
     // all of this wave's LDS reads and its share of the tile in flight are complete ...
@@ -156,11 +168,12 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
     asm volatile("" ::: "memory");
   };
 
-  // The MFMA stream runs across k-tiles without a gap.  Fragments are double-buffered in registers (the LDS
-  // reads of k-step kk+1 are issued before the MFMAs of k-step kk).  The one barrier per k-tile sits in front
-  // of the MFMAs of the LAST k-step: by then every wave has finished reading the current stage, so behind the
-  // barrier the first fragments of the next tile are fetched and the direct loads of the tile after next are
-  // issued between those last MFMAs.
+  // The MFMA stream runs across k-tiles without a gap.  A k-tile is four units of HM x FN MFMAs (two 32-deep
+  // k-steps, two halves of the wave tile's rows each).  Fragments are double-buffered in registers: the A fragments
+  // of unit u+1 (and the B fragments of the next k-step with them) are read before the MFMAs of unit u.  The one
+  // barrier per k-tile sits in front of the MFMAs of the LAST unit: by then every wave has finished reading the
+  // current stage, so behind the barrier the first fragments of the next tile are fetched and the direct loads of
+  // the tile after next are issued between those last MFMAs.
   // Prologue: both stages are free, so the first two k-tiles go out back to back; only the first is waited for.
 #pragma unroll
   for (int idx = 0; idx < 2 * PER; ++idx) issue_idx(0, idx);
@@ -173,45 +186,53 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
   } else {
     wait_and_sync();
   }
-  bf16x8 af[2][FM], bfr[2][FN];
-  load_frags(0, 0, af[0], bfr[0]);
-  constexpr int KS = kRBK / 16;   // 4 k-steps per tile
+  bf16x8 af[2][HM], bfr[2][FN];
+  load_a(0, 0, af[0]);
+  load_b(0, 0, bfr[0]);
+  constexpr int KU = UPS * (kRBK / 32);   // units per tile
+  static_assert(KU % 2 == 0 && (kRBK / 32) % 2 == 0, "fragment buffers alternate and must be in phase at every tile start");
+  auto mfma = [&](int u, int i, int j) {
+    const int row = (u % UPS) * HM + i;
+    acc[row][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[(u / UPS) & 1][j], af[u & 1][i], acc[row][j], 0, 0, 0);
+  };
   // One k-tile.  MORE: another tile follows (already in flight); MORE2: the one after that exists and is issued here.
   auto k_tile = [&](int kt, auto more, auto more2) {
     const int stage = kt & 1;
 #pragma unroll
-    for (int kk = 0; kk < KS - 1; ++kk) {
-      // k-step 0 starts with one MFMA on fragments fetched during the previous tile, so that the wait for
+    for (int u = 0; u < KU - 1; ++u) {
+      // unit 0 starts with one MFMA on fragments fetched during the previous tile, so that the wait for
       // those does not also cover the reads issued here.
-      if (kk == 0) {
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[0][0], af[0][0], acc[0][0], 0, 0, 0);
+      if (u == 0) {
+        mfma(0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
       }
-      load_frags(stage, kk + 1, af[(kk + 1) & 1], bfr[(kk + 1) & 1]);
+      load_a(stage, u + 1, af[(u + 1) & 1]);
+      if (u % UPS == 0 && u + UPS < KU) load_b(stage, u / UPS + 1, bfr[(u / UPS + 1) & 1]);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < FM; ++i)
+      for (int i = 0; i < HM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
-          if (kk != 0 || i != 0 || j != 0)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
-      add_colsum(bfr[kk & 1]);
+          if (u != 0 || i != 0 || j != 0) mfma(u, i, j);
+      if (u % UPS == 0) add_colsum(bfr[(u / UPS) & 1]);
       __builtin_amdgcn_sched_barrier(0);
     }
     if constexpr (decltype(more)::value) {
       wait_and_sync();
-      load_frags(stage ^ 1, 0, af[0], bfr[0]);
+      load_a(stage ^ 1, 0, af[0]);
+      load_b(stage ^ 1, 0, bfr[0]);
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < HM; ++i)
 #pragma unroll
       for (int j = 0; j < FN; ++j) {
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[(KS - 1) & 1][j], af[(KS - 1) & 1][i], acc[i][j], 0, 0, 0);
-        if constexpr (decltype(more2)::value) issue_idx(kt + 2, i * FN + j);
+        mfma(KU - 1, i, j);
+        if constexpr (decltype(more2)::value) {
+          if ((i * FN + j) % kIssueEvery == 0) issue_idx(kt + 2, (i * FN + j) / kIssueEvery);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
-    add_colsum(bfr[(KS - 1) & 1]);
     __builtin_amdgcn_sched_barrier(0);
   };
   using yes = std::integral_constant<bool, true>;
@@ -223,14 +244,15 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
   if (do_colsum) {
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
-      const float t = cs[j] + __shfl_xor(cs[j], 32, 64);   // the two k-halves of the fragment
-      if (lane < 32) {
-        float* o = p.b_colsum + n0 + wn * kWaveN + j * 32 + lane;
+      float t = cs[j] + __shfl_xor(cs[j], 16, 64);   // the four k-groups of the fragment
+      t += __shfl_xor(t, 32, 64);
+      if (lane < 16) {
+        float* o = p.b_colsum + n0 + wn * kWaveN + j * 16 + lane;
         *o = p.colsum_accumulate ? *o + t : t;
       }
     }
   }
-  gemm_epilogue_staged<FM, FN, false>(smem, acc, p, m0 + wm * 128, n0 + wn * kWaveN, wave, lane);
+  gemm_epilogue_staged<4, kWaveN / 32, false>(smem, acc, p, m0 + wm * 128, n0 + wn * kWaveN, wave, lane);
 }
 
 template <bool A_KMAJOR, bool B_KMAJOR, int NW>
