@@ -144,7 +144,7 @@ __global__ __launch_bounds__(kNT, 2) void attn_fwd_dma_kernel(MhaDev a, bf16* __
   const int64_t ld = a.ldkv;
   const int nq = (Tq + 127) / 128;
   int bh, qi;
-  xcd_block_map(blockIdx.x, gridDim.x, nq, bh, qi);
+  xcd_block_map(blockIdx.x, gridDim.x, nq, CAUSAL ? causal_group(nq, 64) : 1, bh, qi);
   const int b = bh / H, h = bh - b * H;
   const int qblk = CAUSAL ? nq - 1 - qi : qi;           // causal: longest blocks of a problem first
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5;
@@ -255,7 +255,7 @@ __global__ __launch_bounds__(kNT, 2) void attn_dq_dma_kernel(MhaDev a, const bf1
   const int64_t ld = a.ldkv;
   const int nq = (Tq + 127) / 128;
   int bh, qi;
-  xcd_block_map(blockIdx.x, gridDim.x, nq, bh, qi);
+  xcd_block_map(blockIdx.x, gridDim.x, nq, CAUSAL ? causal_group(nq, 64) : 1, bh, qi);
   const int b = bh / H, h = bh - b * H;
   const int qblk = CAUSAL ? nq - 1 - qi : qi;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5;
@@ -352,7 +352,7 @@ __global__ __launch_bounds__(kNT) void attn_dkv_dma_kernel(MhaDev a, const bf16*
   const int d = H * HD;
   const int64_t ld = a.ldq;
   int bh, kblk;                                         // causal: first key blocks see the most queries, they come first
-  xcd_block_map(blockIdx.x, gridDim.x, (Tk + 127) / 128, bh, kblk);
+  xcd_block_map(blockIdx.x, gridDim.x, (Tk + 127) / 128, CAUSAL ? causal_group((Tk + 127) / 128, 32) : 1, bh, kblk);
   const int b = bh / H, h = bh - b * H;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5;
   const int k0 = kblk * 128 + wave * 32;

@@ -1,75 +1,195 @@
-// Ceiling of the GEMM's inner loop on this chip, with no global memory involved: the instruction mix of
-// gemm_bf16_kernel's k-loop (8 waves, 4 + 2 LDS fragment reads per 8 MFMAs, optional barrier per 32 MFMAs),
-// on near-constant or on random bf16 operands.  The clock falls with operand activity, so the random-data
-// figure is the practical roofline of that loop.  Everything stays in bounds; loops are bounded.
+// Ceiling of the GEMM's inner loop on this chip, with no global memory involved, and what sets it: the board
+// power limit.  One workgroup of 8 waves per compute unit runs the instruction mix of the ring GEMM's k-loop
+// (128 x 64 wave tiles; per 64-deep k-tile 24 LDS fragment reads of 16 bytes and the MFMAs that consume them)
+// for a few seconds while a host thread samples the engine clock and the board power from sysfs.  Variants:
+// the two bf16 MFMA shapes (same flops, same LDS bytes), the order in which a wave walks its accumulator
+// blocks, constant against random operands, with and without one barrier per k-tile.
+// Everything stays in bounds; every loop is bounded.
 //   hipcc --offload-arch=gfx950 -O3 -std=c++17 -o /tmp/mfma_ceiling paper_2203_12533_amd/tools/mfma_ceiling.hip && /tmp/mfma_ceiling
 #include <hip/hip_runtime.h>
+#include <glob.h>
+
+#include <atomic>
+#include <chrono>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
+#include <string>
+#include <thread>
+#include <vector>
+
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 #define CK(x) do { hipError_t e = (x); if (e != hipSuccess) { printf("err %s line %d\n", hipGetErrorString(e), __LINE__); exit(1);} } while (0)
 
-// MODE 0: pure MFMA (8 independent accumulators).  MODE 1: + LDS fragment reads as in the GEMM (6 per 8 MFMAs).
-// MODE 2: MODE 1 + one barrier per 32 MFMAs.
-template <int MODE, int NT, int RANDOM>
-__global__ __launch_bounds__(NT) void k(float* out, int iters) {
+constexpr int kNT = 512;             // 8 waves: 2 (rows) x 4 (columns) wave tiles of 128 x 64
+constexpr int kLd = 72;              // LDS row of 64 k-values + padding
+constexpr int kLdsElems = 512 * kLd; // A tile (256 rows) then B tile (256 rows)
+
+// Operands: activation-like small values with random mantissas, or a constant pattern.
+__device__ inline void fill(__bf16* smem, int rnd) {
+  for (int i = threadIdx.x; i < kLdsElems; i += kNT) {
+    unsigned h = (unsigned)i * 2654435761u + blockIdx.x * 40503u; h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+    const float u = ((h & 255) + ((h >> 8) & 255) + ((h >> 16) & 255) + ((h >> 24) & 255) - 510.f) * (0.05f / 148.f);
+    smem[i] = rnd ? (__bf16)u : (__bf16)(0.001f * (i & 15));
+  }
+}
+
+// v_mfma_f32_32x32x16_bf16: 4 x 2 accumulator blocks per wave, four 16-deep k-steps per k-tile.
+template <int BARRIER>
+__global__ __launch_bounds__(kNT) void loop_32x32x16(float* out, int iters, int rnd) {
   extern __shared__ __attribute__((aligned(16))) __bf16 smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int i = threadIdx.x; i < 512 * 72; i += NT) {
-    unsigned h = (unsigned)i * 2654435761u + blockIdx.x * 40503u; h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
-    smem[i] = RANDOM ? (__bf16)(((int)(h & 0xFFFF) - 32768) * (1.0f / 32768.f)) : (__bf16)(0.001f * (i & 15));
-  }
+  fill(smem, rnd);
   __syncthreads();
-  f32x16 acc[8];
-  for (int a = 0; a < 8; ++a) for (int r = 0; r < 16; ++r) acc[a][r] = 0.f;
-  bf16x8 af[4], bf[2];
-  for (int i = 0; i < 4; ++i) for (int e = 0; e < 8; ++e) af[i][e] = (__bf16)(0.01f * (lane + i));
-  for (int i = 0; i < 2; ++i) for (int e = 0; e < 8; ++e) bf[i][e] = (__bf16)(0.02f * (lane + i));
-  const __bf16* a_tile = smem + ((wave / 4) * 128 + (lane & 31)) * 72 + (lane >> 5) * 8;
-  const __bf16* b_tile = smem + 256 * 72 + ((wave % 4) * 64 + (lane & 31)) * 72 + (lane >> 5) * 8;
+  constexpr int FM = 4, FN = 2;
+  f32x16 acc[FM * FN];
+  for (int a = 0; a < FM * FN; ++a) for (int r = 0; r < 16; ++r) acc[a][r] = 0.f;
+  bf16x8 af[FM], bf[FN];
+  const __bf16* a_tile = smem + ((wave & 1) * 128 + (lane & 31)) * kLd + (lane >> 5) * 8;
+  const __bf16* b_tile = smem + 256 * kLd + ((wave >> 1) * 64 + (lane & 31)) * kLd + (lane >> 5) * 8;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      if (MODE >= 1) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const bf16x8*>(a_tile + i * 32 * 72 + kk * 16);
+      for (int i = 0; i < FM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(a_tile + i * 32 * kLd + kk * 16);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) bf[j] = *reinterpret_cast<const bf16x8*>(b_tile + j * 32 * 72 + kk * 16);
-      }
+      for (int j = 0; j < FN; ++j) bf[j] = *reinterpret_cast<const bf16x8*>(b_tile + j * 32 * kLd + kk * 16);
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i * 2 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], af[i], acc[i * 2 + j], 0, 0, 0);
+        for (int j = 0; j < FN; ++j) acc[i * FN + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], af[i], acc[i * FN + j], 0, 0, 0);
     }
-    if (MODE == 2) __syncthreads();
+    if (BARRIER) __syncthreads();
   }
   float s = 0.f;
-  for (int a = 0; a < 8; ++a) for (int r = 0; r < 16; ++r) s += acc[a][r];
-  out[blockIdx.x * NT + threadIdx.x] = s;
+  for (int a = 0; a < FM * FN; ++a) for (int r = 0; r < 16; ++r) s += acc[a][r];
+  out[blockIdx.x * kNT + threadIdx.x] = s;
 }
 
-template <int MODE, int NT, int RANDOM>
-void run(const char* name, int blocks_per_cu, int iters) {
-  const int blocks = 256 * blocks_per_cu;
-  float* out; CK(hipMalloc(&out, (size_t)blocks * NT * 4));
-  const size_t smem = 512 * 72 * 2;
-  CK(hipFuncSetAttribute((const void*)k<MODE, NT, RANDOM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-  hipEvent_t a, b; CK(hipEventCreate(&a)); CK(hipEventCreate(&b));
-  k<MODE, NT, RANDOM><<<blocks, NT, smem>>>(out, 10); CK(hipDeviceSynchronize());
-  CK(hipEventRecord(a)); k<MODE, NT, RANDOM><<<blocks, NT, smem>>>(out, iters); CK(hipEventRecord(b)); CK(hipEventSynchronize(b));
-  float ms; CK(hipEventElapsedTime(&ms, a, b));
-  const double flops = (double)blocks * (NT / 64) * iters * 32.0 * 32768.0;
-  printf("%-30s rnd=%d NT=%d blocks/CU=%d iters=%d: %8.3f ms  %8.1f TFLOP/s\n", name, RANDOM, NT, blocks_per_cu, iters, ms, flops / ms / 1e9); fflush(stdout);
-  CK(hipFree(out));
+// v_mfma_f32_16x16x32_bf16: 8 x 4 accumulator blocks per wave, two 32-deep k-steps per k-tile.
+// ORDER 0: row block outer, column block inner, always ascending.  ORDER 1: columns back and forth, so that every
+// MFMA shares one operand with the one before it.
+template <int ORDER, int BARRIER>
+__global__ __launch_bounds__(kNT) void loop_16x16x32(float* out, int iters, int rnd) {
+  extern __shared__ __attribute__((aligned(16))) __bf16 smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  fill(smem, rnd);
+  __syncthreads();
+  constexpr int FM = 8, FN = 4;
+  f32x4 acc[FM * FN];
+  for (int a = 0; a < FM * FN; ++a) for (int r = 0; r < 4; ++r) acc[a][r] = 0.f;
+  bf16x8 af[FM], bf[FN];
+  const __bf16* a_tile = smem + ((wave & 1) * 128 + (lane & 15)) * kLd + (lane >> 4) * 8;
+  const __bf16* b_tile = smem + 256 * kLd + ((wave >> 1) * 64 + (lane & 15)) * kLd + (lane >> 4) * 8;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+#pragma unroll
+      for (int i = 0; i < FM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(a_tile + i * 16 * kLd + kk * 32);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) bf[j] = *reinterpret_cast<const bf16x8*>(b_tile + j * 16 * kLd + kk * 32);
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int jj = 0; jj < FN; ++jj) {
+          const int j = (ORDER == 1 && (i & 1)) ? FN - 1 - jj : jj;
+          acc[i * FN + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bf[j], af[i], acc[i * FN + j], 0, 0, 0);
+        }
+    }
+    if (BARRIER) __syncthreads();
+  }
+  float s = 0.f;
+  for (int a = 0; a < FM * FN; ++a) for (int r = 0; r < 4; ++r) s += acc[a][r];
+  out[blockIdx.x * kNT + threadIdx.x] = s;
 }
+
+// Host-side sampler of engine clock (the starred level of pp_dpm_sclk) and board power (hwmon power1_input).
+struct Sampler {
+  std::string sclk_path, power_path;
+  std::atomic<bool> stop{false};
+  std::vector<int> mhz;
+  std::vector<double> watts;
+  std::thread th;
+  static std::string first_match(const char* pattern) {
+    glob_t g;
+    std::string r;
+    if (glob(pattern, 0, nullptr, &g) == 0 && g.gl_pathc > 0) r = g.gl_pathv[0];
+    globfree(&g);
+    return r;
+  }
+  Sampler() {
+    sclk_path = first_match("/sys/class/drm/card*/device/pp_dpm_sclk");
+    power_path = first_match("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input");
+  }
+  void start() {
+    th = std::thread([this] {
+      while (!stop.load()) {
+        if (FILE* f = sclk_path.empty() ? nullptr : fopen(sclk_path.c_str(), "r")) {
+          char line[128];
+          while (fgets(line, sizeof line, f))
+            if (strchr(line, '*')) {
+              const char* c = strchr(line, ':');
+              if (c) mhz.push_back(atoi(c + 1));
+            }
+          fclose(f);
+        }
+        if (FILE* f = power_path.empty() ? nullptr : fopen(power_path.c_str(), "r")) {
+          long long uw = 0;
+          if (fscanf(f, "%lld", &uw) == 1) watts.push_back(uw / 1e6);
+          fclose(f);
+        }
+        std::this_thread::sleep_for(std::chrono::milliseconds(50));
+      }
+    });
+  }
+  void finish(double* mean_mhz, double* mean_w) {
+    stop.store(true);
+    th.join();
+    double a = 0, b = 0;
+    for (int v : mhz) a += v;
+    for (double v : watts) b += v;
+    *mean_mhz = mhz.empty() ? 0 : a / mhz.size();
+    *mean_w = watts.empty() ? 0 : b / watts.size();
+  }
+};
+
+// Launches of 4000 k-tiles each for `secs` seconds; the rate, the clock and the power are those of the second half.
+template <typename K>
+void run(const char* name, K kern, int rnd, double secs) {
+  const int blocks = 256, iters = 4000;
+  float* out; CK(hipMalloc(&out, (size_t)blocks * kNT * 4));
+  const size_t smem = (size_t)kLdsElems * 2;
+  CK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+  hipEvent_t a, b; CK(hipEventCreate(&a)); CK(hipEventCreate(&b));
+  kern<<<blocks, kNT, smem>>>(out, 10, rnd); CK(hipDeviceSynchronize());
+  CK(hipEventRecord(a)); kern<<<blocks, kNT, smem>>>(out, iters, rnd); CK(hipEventRecord(b)); CK(hipEventSynchronize(b));
+  float ms; CK(hipEventElapsedTime(&ms, a, b));
+  const int n = (int)(secs * 1e3 / ms) + 2, warm = n / 2;
+  for (int i = 0; i < warm; ++i) kern<<<blocks, kNT, smem>>>(out, iters, rnd);
+  CK(hipDeviceSynchronize());
+  Sampler s; s.start();
+  CK(hipEventRecord(a));
+  for (int i = 0; i < n - warm; ++i) kern<<<blocks, kNT, smem>>>(out, iters, rnd);
+  CK(hipEventRecord(b)); CK(hipEventSynchronize(b));
+  double mhz, w; s.finish(&mhz, &w);
+  CK(hipEventElapsedTime(&ms, a, b));
+  const double flops = 2.0 * 128 * 64 * 64 * 8 * (double)iters * blocks * (n - warm);   // per k-tile and wave: 128 x 64 x 64
+  printf("%-46s %-8s %8.1f TFLOP/s   %5.0f MHz  %5.0f W\n", name, rnd ? "random" : "constant", flops / (ms * 1e-3) / 1e12, mhz, w);
+  fflush(stdout);
+  CK(hipFree(out));
+  std::this_thread::sleep_for(std::chrono::milliseconds(1000));
+}
+
 int main() {
-  run<2, 512, 0>("MFMA + LDS reads + barrier", 1, 2000);
-  run<2, 512, 0>("MFMA + LDS reads + barrier", 1, 20000);
-  run<2, 512, 1>("MFMA + LDS reads + barrier", 1, 2000);
-  run<2, 512, 1>("MFMA + LDS reads + barrier", 1, 20000);
-  run<1, 512, 1>("MFMA + LDS reads", 1, 20000);
-  run<1, 256, 1>("MFMA + LDS reads", 1, 20000);
-  run<0, 512, 0>("pure MFMA", 1, 20000);
+  const double secs = 2.5;
+  printf("%-46s %-8s %17s %10s %8s\n", "loop (8 waves per CU, 256 CUs, LDS reads)", "operands", "sustained", "clock", "power");
+  run("32x32x16", loop_32x32x16<0>, 1, secs);
+  run("16x16x32, ascending columns", loop_16x16x32<0, 0>, 1, secs);
+  run("16x16x32, columns back and forth", loop_16x16x32<1, 0>, 1, secs);
+  run("16x16x32, back and forth, barrier per k-tile", loop_16x16x32<1, 1>, 1, secs);
+  run("32x32x16", loop_32x32x16<0>, 0, secs);
+  run("16x16x32, columns back and forth", loop_16x16x32<1, 0>, 0, secs);
   return 0;
 }
