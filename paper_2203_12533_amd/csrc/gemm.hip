@@ -467,6 +467,12 @@ static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a) {
   // Full 256x256 tiles with enough of them to fill the chip: the ring-buffered kernel.
   if (ring_eligible(a) && (a.M / 256) * (a.N / 256) >= 150)
     return launch_gemm_ring(s, bf16_params_of(a, 256), a.a_kmajor, a.b_kmajor);
+  // At most half the chip in full tiles, A row-major: the ring kernel on 128 x 256 tiles.
+  if (ring_eligible(a) && !a.a_kmajor && (a.M / 256) * (a.N / 256) <= 128 && (a.M / 128) * (a.N / 256) >= 64) {
+    GemmBf16Params p = bf16_params_of(a, 256);
+    p.tiles_m = (int)(a.M / 128);
+    return launch_gemm_ring_half(s, p, a.b_kmajor);
+  }
   // Tile choice: 256x256 when that still yields at least one workgroup per CU; otherwise 128x128.
   const int64_t big_tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
   if (big_tiles >= 150) {

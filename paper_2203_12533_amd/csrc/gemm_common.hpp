@@ -309,6 +309,9 @@ __device__ __forceinline__ void gemm_epilogue_staged(bf16* smem, Acc& acc, const
 // Ring-buffered variant for full tiles (gemm_ring.hip).
 bool gemm_ring_supported(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemm_ring(hipStream_t s, const GemmBf16Params& p, bool a_kmajor, bool b_kmajor);
+// The same kernel on 128 x 256 tiles (row-major A only; p.tiles_m counts 128-row tiles): for problems with at most
+// 128 full tiles, which would otherwise occupy half the chip.
+hipError_t launch_gemm_ring_half(hipStream_t s, const GemmBf16Params& p, bool b_kmajor);
 // n <= kRingGroupMax problems of one operand layout in a single launch, problem i's workgroups before problem i+1's.
 constexpr int kRingGroupMax = 3;
 struct GemmRingGroup {

@@ -35,8 +35,10 @@ constexpr int kRStages = 2;
 #define PW_RING_HM 2
 #endif
 constexpr int kRingHM = PW_RING_HM;     // 16-row blocks of A per unit of the main loop (see ring_tile)
-constexpr int kROperand = kRT * kRBK;            // elements per operand tile (32 KiB)
-constexpr int kRStage = 2 * kROperand;           // elements per stage
+constexpr int kROperand = kRT * kRBK;            // elements per full operand tile (32 KiB)
+// Elements per stage: an A tile of TM rows (256, or 128 for problems that would otherwise leave half the chip
+// idle) and a B tile of 256 rows.
+template <int TM> constexpr int ring_stage() { return (TM + kRT) * kRBK; }
 
 typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef const __attribute__((address_space(1))) void* gbl_ptr;
@@ -98,20 +100,26 @@ __device__ __forceinline__ bf16x8 read_fragment(const bf16* lds_tile, int frag_r
 // Waves form a 2 x NW grid: NW = 4 -> 8 waves with 128 x 64 wave tiles.  The products are 16 x 16 x 32 MFMAs: on
 // operands with random mantissas the chip runs into its board power limit, and per flop that shape draws less
 // than the 32 x 32 x 16 one (same loop, same LDS bytes: 2.06 against 1.82 PFLOP/s sustained).
-template <bool A_KMAJOR, bool B_KMAJOR, int NW>
+template <bool A_KMAJOR, bool B_KMAJOR, int NW, int TM>
 __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16* smem) {
+  static_assert(TM == kRT || (TM == 128 && !A_KMAJOR), "the half-height tile exists for row-major A only");
+  constexpr int kRStage = ring_stage<TM>();
+  constexpr int kAOperand = TM * kRBK;                // elements of the A tile
   int tm, tn;
   tile_of_block(pid, p.tiles_m * p.tiles_n, p.tiles_m, p.tiles_n, tm, tn);
-  const int64_t m0 = (int64_t)tm * kRT, n0 = (int64_t)tn * kRT;
+  const int64_t m0 = (int64_t)tm * TM, n0 = (int64_t)tn * kRT;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave / NW, wn = wave % NW;
   constexpr int kWaveN = kRT / NW;                    // columns of a wave tile
-  constexpr int FM = 8, FN = kWaveN / 16;             // 16 x 16 accumulator blocks of the 128 x kWaveN wave tile
+  constexpr int kWaveM = TM / 2;                      // rows of a wave tile
+  constexpr int FM = kWaveM / 16, FN = kWaveN / 16;   // 16 x 16 accumulator blocks of the wave tile
   constexpr int HM = kRingHM;                         // a unit of work: HM row blocks x FN column blocks, one 32-deep k-step
   constexpr int UPS = FM / HM;                        // units per k-step
-  constexpr int PER = 32 / (2 * NW);                  // direct-load instructions per operand tile and wave
-  static_assert((HM * FN) % (2 * PER) == 0, "the direct loads are spread evenly over the MFMAs of the last unit");
-  constexpr int kIssueEvery = HM * FN / (2 * PER);
+  constexpr int PER_A = TM / 8 / (2 * NW);            // direct-load instructions (1 KiB each) per A tile and wave
+  constexpr int PER_B = kRT / 8 / (2 * NW);           // ... per B tile and wave
+  constexpr int PER = PER_A + PER_B;
+  static_assert((HM * FN) % PER == 0 || HM * FN >= PER, "the direct loads fit between the MFMAs of the last unit");
+  constexpr int kIssueEvery = HM * FN / PER > 0 ? HM * FN / PER : 1;
 
   f32x4 acc[FM][FN];
 #pragma unroll
@@ -142,20 +150,20 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
   const int kt_total = (int)(p.K / kRBK);
   const uint32_t smem_off = (uint32_t)(uintptr_t)(lds_ptr)smem;   // byte offset of the ring inside LDS
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-  // idx 0..PER-1: A tile instructions, PER..2 PER-1: B tile instructions of k-tile kt
+  // idx 0..PER_A-1: A tile instructions, PER_A..PER-1: B tile instructions of k-tile kt
   auto issue_idx = [&](int kt, int idx) {
     const uint32_t stage = smem_off + (uint32_t)(kt % kRStages) * (kRStage * 2);
-    if (idx < PER) issue_one<A_KMAJOR, PER>(p.A, p.lda, m0, (int64_t)kt * kRBK, stage, wave_s, lane, idx);
-    else issue_one<B_KMAJOR, PER>(p.B, p.ldb, n0, (int64_t)kt * kRBK, stage + kROperand * 2, wave_s, lane, idx - PER);
+    if (idx < PER_A) issue_one<A_KMAJOR, PER_A>(p.A, p.lda, m0, (int64_t)kt * kRBK, stage, wave_s, lane, idx);
+    else issue_one<B_KMAJOR, PER_B>(p.B, p.ldb, n0, (int64_t)kt * kRBK, stage + kAOperand * 2, wave_s, lane, idx - PER_A);
   };
   // A unit u of a k-tile: k-step u / UPS (32 deep), row blocks HM (u % UPS) .. + HM - 1 of the wave tile.
   auto load_a = [&](int stage, int u, bf16x8* af) {
     const bf16* a_tile = smem + stage * kRStage;
 #pragma unroll
-    for (int i = 0; i < HM; ++i) af[i] = read_fragment<A_KMAJOR>(a_tile, wm * 128 + ((u % UPS) * HM + i) * 16, u / UPS, lane);
+    for (int i = 0; i < HM; ++i) af[i] = read_fragment<A_KMAJOR>(a_tile, wm * kWaveM + ((u % UPS) * HM + i) * 16, u / UPS, lane);
   };
   auto load_b = [&](int stage, int ks, bf16x8* bfr) {
-    const bf16* b_tile = smem + stage * kRStage + kROperand;
+    const bf16* b_tile = smem + stage * kRStage + kAOperand;
 #pragma unroll
     for (int j = 0; j < FN; ++j) bfr[j] = read_fragment<B_KMAJOR>(b_tile, wn * kWaveN + j * 16, ks, lane);
   };
@@ -176,11 +184,11 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
   // the tile after next are issued between those last MFMAs.
   // Prologue: both stages are free, so the first two k-tiles go out back to back; only the first is waited for.
 #pragma unroll
-  for (int idx = 0; idx < 2 * PER; ++idx) issue_idx(0, idx);
+  for (int idx = 0; idx < PER; ++idx) issue_idx(0, idx);
   if (kt_total > 1) {
 #pragma unroll
-    for (int idx = 0; idx < 2 * PER; ++idx) issue_idx(1, idx);
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * PER) : "memory");   // all but the second tile's loads have landed
+    for (int idx = 0; idx < PER; ++idx) issue_idx(1, idx);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER) : "memory");   // all but the second tile's loads have landed
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
   } else {
@@ -235,7 +243,7 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
       for (int jj = 0; jj < FN; ++jj) {
         mfma(KU - 1, i, snake(i, jj));
         if constexpr (decltype(more2)::value) {
-          if ((i * FN + jj) % kIssueEvery == 0) issue_idx(kt + 2, (i * FN + jj) / kIssueEvery);
+          if ((i * FN + jj) % kIssueEvery == 0 && (i * FN + jj) / kIssueEvery < PER) issue_idx(kt + 2, (i * FN + jj) / kIssueEvery);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -258,13 +266,13 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
       }
     }
   }
-  gemm_epilogue_staged<4, kWaveN / 32, false>(smem, acc, p, m0 + wm * 128, n0 + wn * kWaveN, wave, lane);
+  gemm_epilogue_staged<kWaveM / 32, kWaveN / 32, false>(smem, acc, p, m0 + wm * kWaveM, n0 + wn * kWaveN, wave, lane);
 }
 
-template <bool A_KMAJOR, bool B_KMAJOR, int NW>
+template <bool A_KMAJOR, bool B_KMAJOR, int NW, int TM>
 __global__ __launch_bounds__(2 * NW * 64) void gemm_ring_kernel(GemmBf16Params p) {
   extern __shared__ __attribute__((aligned(16))) bf16 smem[];
-  ring_tile<A_KMAJOR, B_KMAJOR, NW>(p, blockIdx.x, smem);
+  ring_tile<A_KMAJOR, B_KMAJOR, NW, TM>(p, blockIdx.x, smem);
 }
 
 // Up to three independent problems of the same operand layout in one launch: workgroups [first[i], first[i+1])
@@ -275,26 +283,32 @@ __global__ __launch_bounds__(2 * NW * 64) void gemm_ring_group_kernel(GemmRingGr
   const int bid = (int)blockIdx.x;
   const int which = bid < g.first[1] ? 0 : (bid < g.first[2] ? 1 : 2);
   const GemmBf16Params p = which == 0 ? g.p[0] : (which == 1 ? g.p[1] : g.p[2]);
-  ring_tile<A_KMAJOR, B_KMAJOR, NW>(p, bid - g.first[which], smem);
+  ring_tile<A_KMAJOR, B_KMAJOR, NW, kRT>(p, bid - g.first[which], smem);
 }
 
-constexpr size_t kRSmemBytes = (size_t)kRStages * kRStage * sizeof(bf16);   // 128 KiB
-static_assert(kRSmemBytes >= 8 * 32 * 68 * 4, "epilogue staging must fit");
+template <int TM> constexpr size_t ring_smem_bytes() { return (size_t)kRStages * ring_stage<TM>() * sizeof(bf16); }
+constexpr size_t kRSmemBytes = ring_smem_bytes<kRT>();   // 128 KiB (96 KiB with the half-height A tile)
+static_assert(ring_smem_bytes<128>() >= 8 * 32 * 68 * 4, "epilogue staging must fit");
 
 // Waves along n.  4 (8 waves, 128 x 64 wave tiles) is what runs; 2 (4 waves, 128 x 128 wave tiles, accumulators in
-// AGPRs, a third fewer LDS fragment reads per MFMA) compiles to a clean loop as well and measured the same
-// within noise on every shape of the step, so it is not instantiated.
+// AGPRs, a third fewer LDS fragment reads per MFMA) measured the same within noise with 32 x 32 MFMA blocks on every
+// shape of the step, so it is not instantiated.
 constexpr int kRingNW = 4;
 
 template <bool AK, bool BK_, int NW>
 hipError_t prepare_ring_variant() {
   static bool attr_done = false;
   if (attr_done) return hipSuccess;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_kernel<AK, BK_, NW>),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_kernel<AK, BK_, NW, kRT>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRSmemBytes);
   if (e == hipSuccess)
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_group_kernel<AK, BK_, NW>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRSmemBytes);
+  if constexpr (!AK) {
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_kernel<AK, BK_, NW, 128>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)ring_smem_bytes<128>());
+  }
   if (e == hipSuccess) attr_done = true;
   return e;
 }
@@ -304,7 +318,7 @@ hipError_t launch_ring_variant(hipStream_t s, const GemmBf16Params* p, int n) {
   hipError_t e = prepare_ring_variant<AK, BK_, NW>();
   if (e != hipSuccess) return e;
   if (n == 1) {
-    gemm_ring_kernel<AK, BK_, NW><<<p[0].tiles_m * p[0].tiles_n, 2 * NW * 64, kRSmemBytes, s>>>(p[0]);
+    gemm_ring_kernel<AK, BK_, NW, kRT><<<p[0].tiles_m * p[0].tiles_n, 2 * NW * 64, kRSmemBytes, s>>>(p[0]);
   } else {
     GemmRingGroup g{};
     int total = 0;
@@ -318,6 +332,14 @@ hipError_t launch_ring_variant(hipStream_t s, const GemmBf16Params* p, int n) {
     g.first[kRingGroupMax] = total;
     gemm_ring_group_kernel<AK, BK_, NW><<<total, 2 * NW * 64, kRSmemBytes, s>>>(g);
   }
+  return hipGetLastError();
+}
+
+template <bool BK_, int NW>
+hipError_t launch_ring_half(hipStream_t s, const GemmBf16Params& p) {
+  hipError_t e = prepare_ring_variant<false, BK_, NW>();
+  if (e != hipSuccess) return e;
+  gemm_ring_kernel<false, BK_, NW, 128><<<p.tiles_m * p.tiles_n, 2 * NW * 64, ring_smem_bytes<128>(), s>>>(p);
   return hipGetLastError();
 }
 
@@ -337,6 +359,11 @@ hipError_t launch_gemm_ring(hipStream_t s, const GemmBf16Params& p, bool ak, boo
 hipError_t launch_gemm_ring_group(hipStream_t s, const GemmBf16Params* p, int n, bool ak, bool bk) {
   if (n < 1 || n > kRingGroupMax) return hipErrorInvalidValue;
   return launch_ring_nw<kRingNW>(s, p, n, ak, bk);
+}
+
+// 128 x 256 tiles (p.tiles_m counts 128-row tiles), A row-major.
+hipError_t launch_gemm_ring_half(hipStream_t s, const GemmBf16Params& p, bool bk) {
+  return bk ? launch_ring_half<true, kRingNW>(s, p) : launch_ring_half<false, kRingNW>(s, p);
 }
 
 bool gemm_ring_supported(int64_t M, int64_t N, int64_t K) { return M % kRT == 0 && N % kRT == 0 && K % kRBK == 0 && K >= kRBK; }
