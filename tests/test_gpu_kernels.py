@@ -262,6 +262,13 @@ def test_unmasked_attention_with_separate_lengths(ctx, orc, B, Tq, Tk, H, hd, bf
     _mha_case(ctx, orc, bf16, B, Tq, Tk, H, hd, causal=False, packed_kv=True)
 
 
+def test_causal_attention_block_order_with_partial_problem_groups(ctx, orc):
+    """Under the causal mask the workgroups of several problems are interleaved, longest blocks first, in groups
+    sized from the number of 128-row blocks per problem: 9 problems of 5 blocks give one group of 9 in the forward
+    and dQ kernels and groups of 7 and 2 in the dK/dV kernel, with a ragged last block."""
+    _mha_case(ctx, orc, True, 3, 520, 520, 3, 128, causal=True, packed_kv=False)
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 def test_general_attention_entry_point_other_layouts(ctx, orc, bf16):
     _mha_case(ctx, orc, bf16, 2, 150, 150, 2, 128, causal=True, packed_kv=False)    # causal, k and v separate
