@@ -17,8 +17,8 @@
 //    position c ^ ((r >> 1) & 7): the 16-byte fragment reads of 16 consecutive rows hit 16 distinct
 //    bank groups.
 //  * operand stored [k][row] in memory: LDS [64 k][32 chunks of 8 rows]; chunk c of k-row k sits at
-//    position c ^ (4 * (k & 3)): the four k-rows touched by one transposing read fall into four
-//    different 64-byte bank windows.
+//    position c ^ (4 * (k & 3)) ^ (2 * ((k >> 3) & 1)): the eight k-rows (k0..k0+3 and k0+8..k0+11, 16 rows
+//    each) that the first 32 lanes of one transposing read touch fall into eight different 32-byte bank windows.
 #include "common.hpp"
 #include "gemm_common.hpp"
 #include "kernels.hpp"
@@ -31,10 +31,7 @@ namespace {
 constexpr int kRT = 256;            // tile is kRT x kRT
 constexpr int kRBK = 64;            // k per stage
 constexpr int kRStages = 2;
-#ifndef PW_RING_HM
-#define PW_RING_HM 2
-#endif
-constexpr int kRingHM = PW_RING_HM;     // 16-row blocks of A per unit of the main loop (see ring_tile)
+constexpr int kRingHM = 2;          // 16-row blocks of A per unit of the main loop (see ring_tile); 4 spills registers
 constexpr int kROperand = kRT * kRBK;            // elements per full operand tile (32 KiB)
 // Elements per stage: an A tile of TM rows (256, or 128 for problems that would otherwise leave half the chip
 // idle) and a B tile of 256 rows.

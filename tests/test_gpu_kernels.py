@@ -77,9 +77,13 @@ def test_gemm_dgrad_and_wgrad_layouts(ctx, orc, shape, bf16):
     assert rel_l2(host(dx), rdx) < (4e-3 if bf16 else 2e-6)
 
 
+# ragged (register-staged kernel), 64 full tiles (ring kernel on 128 x 256 tiles), 256 full tiles (ring kernel)
 @pytest.mark.parametrize("bf16", [False, True])
-def test_gemm_fused_epilogues(ctx, orc, bf16):
-    M, N, K = 264, 328, 192
+@pytest.mark.parametrize("shape", [(264, 328, 192), (1024, 4096, 128), (4096, 4096, 128)])
+def test_gemm_fused_epilogues(ctx, orc, bf16, shape):
+    M, N, K = shape
+    if not bf16 and M * N * K > 1e8:
+        pytest.skip("fp32 ALU path is for the small configuration")
     x, xv = dev_act(_rand(8, (M, K)), bf16)
     w, wv = dev_act(_rand(9, (K, N), 0.08), bf16)
     b = _rand(10, (N,), 0.5)
