@@ -90,7 +90,10 @@ __device__ __forceinline__ void issue_tile(const bf16* __restrict__ src, int64_t
 }
 
 // 32x32 block of a first product: A rows (permuted) from a swizzled natural LDS tile, B from register fragments.
+// The A fragments are fetched kDepth MFMAs ahead of their use (left alone the compiler fetches each one right
+// before the MFMA that needs it, and every MFMA of the chain then waits out a full LDS round trip).
 __device__ __forceinline__ f32x16 first_product(const bf16* __restrict__ tile, int row_base, const bf16x8* bfrag) {
+  constexpr int kDepth = 3, KK = HD / 16;   // 2 and 4 measured the same
   const int lane = threadIdx.x & 63;
   const int row = row_base + perm_row(lane & 31);
   const int t = (lane >> 5) ^ swz(row);                 // chunk (2 kk + half) ^ swz = (2 kk) ^ t
@@ -98,9 +101,16 @@ __device__ __forceinline__ f32x16 first_product(const bf16* __restrict__ tile, i
   f32x16 acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  bf16x8 af[kDepth];
 #pragma unroll
-  for (int kk = 0; kk < HD / 16; ++kk)
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(a + ((2 * kk) ^ t) * 8), bfrag[kk], acc, 0, 0, 0);
+  for (int kk = 0; kk < kDepth; ++kk) af[kk] = *reinterpret_cast<const bf16x8*>(a + ((2 * kk) ^ t) * 8);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk % kDepth], bfrag[kk], acc, 0, 0, 0);
+    if (kk + kDepth < KK) af[kk % kDepth] = *reinterpret_cast<const bf16x8*>(a + ((2 * (kk + kDepth)) ^ t) * 8);
+    __builtin_amdgcn_sched_barrier(0);
+  }
   return acc;
 }
 
