@@ -98,3 +98,32 @@ def test_generator_is_counter_based_and_reproducible():
     x = np.array([1.0, 1.00390625, 1.01171875, -3.0e-41], dtype=np.float32)
     r = I.round_to_bf16(x)
     assert r[0] == 1.0 and r[1] == 1.0 and r[2] == np.float32(1.015625)   # ties to even, both directions
+
+
+def test_bench_refuses_more_than_one_gpu_and_its_sampler_survives_missing_sysfs(tmp_path):
+    """bench.py --gpus 2 exits with a message (one GPU only); the clock / power sampler of the timed region is a
+    host thread reading sysfs and must return a plain dict whether or not the files exist."""
+    import importlib.util
+    import subprocess
+    import sys
+    root = os.path.join(os.path.dirname(os.path.abspath(__file__)), "..")
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr
+    spec = importlib.util.spec_from_file_location("pw_bench", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    s = bench.ClockPowerSampler()
+    s.sclk, s.power, s.cap = [str(tmp_path / "absent")], [str(tmp_path / "absent")], [str(tmp_path / "absent")]
+    s.start()
+    assert s.stop() == {}
+    (tmp_path / "sclk").write_text("0: 500Mhz\n1: 2100Mhz *\n2: 2400Mhz\n")
+    (tmp_path / "power").write_text("1350000000\n")
+    (tmp_path / "cap").write_text("1400000000\n")
+    s = bench.ClockPowerSampler()
+    s.sclk, s.power, s.cap = [str(tmp_path / "sclk")], [str(tmp_path / "power")], [str(tmp_path / "cap")]
+    s.start()
+    import time
+    time.sleep(0.12)
+    note = s.stop()
+    assert note["sclk_mhz_during_timed_steps"]["mean"] == 2100 and note["board_power_w_during_timed_steps"]["max"] == 1350
+    assert note["board_power_cap_w"] == 1400
