@@ -45,6 +45,34 @@ def test_forward_gemms_at_cfg3_shape(ctx, orc, name, n_out, k_in):
     assert rel_l2(host(out[ROWS]), ref) < 4e-3
 
 
+def test_gemms_of_a_pipeline_stage_micro_batch_at_cfg4_shape(ctx, orc):
+    """cfg4's micro-batches of 2048 tokens give the GEMMs that write d_model = 4096 columns only 128 full tiles;
+    they run on 128 x 256 tiles.  FFN2 forward (K = 16384) with the residual epilogue and the FFN1 data gradient
+    (both operands k-contiguous) at full shape, sampled rows against the oracle."""
+    c4 = I.workload("cfg4")
+    n, d, f = c4.n_tokens, c4.d_model, c4.d_ff
+    assert (n // 256) * (d // 256) == 128
+    rows = np.array([0, 127, 128, 255, 256, 1029, n - 1])
+    h, w2 = _bf16_randn((n, f), 11), _bf16_randn((f, d), 12, 0.02)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(13)
+    res = torch.randn((n, d), device="cuda", generator=g)
+    bias = torch.randn((d,), device="cuda", generator=g)
+    out = torch.empty((n, d), dtype=torch.float32, device="cuda")
+    ctx.gemm(dtype=pwb.PW_BF16, a_kmajor=0, b_kmajor=1, M=n, N=d, K=f, lda=f, ldb=d, ldc=d,
+             epilogue=pwb.PW_EPI_BIAS_RESIDUAL, out_dtype=pwb.PW_F32, accumulate=0, A=ptr(h), B=ptr(w2), bias=ptr(bias),
+             aux=ptr(res), C=ptr(out))
+    du, w1 = _bf16_randn((n, f), 14), _bf16_randn((d, f), 15, 0.02)
+    dx = torch.empty((n, d), dtype=torch.bfloat16, device="cuda")
+    ctx.gemm(dtype=pwb.PW_BF16, a_kmajor=0, b_kmajor=0, M=n, N=d, K=f, lda=f, ldb=f, ldc=d,
+             epilogue=pwb.PW_EPI_STORE, out_dtype=pwb.PW_BF16, accumulate=0, A=ptr(du), B=ptr(w1), C=ptr(dx))
+    ctx.synchronize()
+    ref = orc.linear_fwd(host(h[rows]), host(w2), host(bias).astype(np.float64)) + host(res[rows])
+    assert rel_l2(host(out[rows]), ref) < 1e-5
+    rdx, _, _ = orc.linear_bwd(np.zeros((len(rows), d)), host(w1), host(du[rows]))
+    assert rel_l2(host(dx[rows]), rdx) < 4e-3
+
+
 @pytest.mark.parametrize("name,n_in,k_out", [("ffn2", F, D), ("ffn1", D, F), ("head", D, V)])
 def test_dgrad_and_wgrad_gemms_at_cfg3_shape(ctx, orc, name, n_in, k_out):
     dy, w, x = _bf16_randn((N, k_out), 3), _bf16_randn((n_in, k_out), 4, 0.02), _bf16_randn((N, n_in), 5)
