@@ -135,7 +135,7 @@ def dispatch_bench_c_abi():
     return out
 
 
-def cpu_baseline_encdec(cfg, pwb, I, budget_tokens: int = 384):
+def cpu_baseline_encdec(cfg, pwb, I, budget_tokens: int = 512):
     """The CPU oracle on a bounded sample of the encoder-decoder workload: one layer each, one sequence pair of
     `budget_tokens` source and target tokens, the workload's widths.  Extrapolated by model-FLOP ratio."""
     from oracle import oracle
@@ -154,13 +154,17 @@ def cpu_baseline_encdec(cfg, pwb, I, budget_tokens: int = 384):
                       f"workload by model-FLOP ratio"}
 
 
-def cpu_baseline(cfg, pwb, budget_tokens: int = 768):
+def cpu_baseline(cfg, pwb, budget_flops: float = 0.8e12):
+    """The CPU oracle, as it stands, on a bounded sample: same layer / head shapes, one layer, one sequence cut to
+    as many tokens (a multiple of 8, at most the workload's) as keep the step near `budget_flops` - about 10 s on
+    the host cores.  Extrapolated to the full workload by model-FLOP ratio."""
     if not cfg.has_head:
         return None
-    """The CPU oracle, as it stands, on a bounded sample: same layer / head shapes, one layer, one
-    sequence of `budget_tokens` tokens.  Extrapolated to the full workload by model-FLOP ratio."""
     from oracle import oracle
-    sample = cfg.with_(n_layer=1, batch=1, seq=min(cfg.seq, budget_tokens))
+    seq = cfg.seq
+    while seq > 8 and pwb.step_flops(cfg.with_(n_layer=1, batch=1, seq=seq)) > budget_flops:
+        seq = max(8, (seq * 3 // 4) // 8 * 8)
+    sample = cfg.with_(n_layer=1, batch=1, seq=seq)
     secs = oracle.time_train_step(sample)
     flops_sample = pwb.step_flops(sample)
     flops_full_per_token = pwb.step_flops(cfg) / cfg.n_tokens
