@@ -93,8 +93,8 @@ __device__ __forceinline__ bf16x8 read_fragment(const bf16* lds_tile, int frag_r
   }
 }
 
-// One 256 x 256 output tile of problem p; pid: index of the tile's workgroup among the problem's own.
-// Waves form a 2 x NW grid: NW = 4 -> 8 waves with 128 x 64 wave tiles.  The products are 16 x 16 x 32 MFMAs: on
+// One TM x 256 output tile of problem p (TM = 256, or 128 for problems of few tiles); pid: index of the tile's
+// workgroup among the problem's own.  Waves form a 2 x NW grid: NW = 4 -> 8 waves with (TM / 2) x 64 wave tiles.  The products are 16 x 16 x 32 MFMAs: on
 // operands with random mantissas the chip runs into its board power limit, and per flop that shape draws less
 // than the 32 x 32 x 16 one (same loop, same LDS bytes: 2.06 against 1.82 PFLOP/s sustained).
 template <bool A_KMAJOR, bool B_KMAJOR, int NW, int TM>
@@ -115,8 +115,8 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
   constexpr int PER_A = TM / 8 / (2 * NW);            // direct-load instructions (1 KiB each) per A tile and wave
   constexpr int PER_B = kRT / 8 / (2 * NW);           // ... per B tile and wave
   constexpr int PER = PER_A + PER_B;
-  static_assert((HM * FN) % PER == 0 || HM * FN >= PER, "the direct loads fit between the MFMAs of the last unit");
-  constexpr int kIssueEvery = HM * FN / PER > 0 ? HM * FN / PER : 1;
+  static_assert(HM * FN >= PER, "one direct load at most goes out behind each MFMA of the last unit");
+  constexpr int kIssueEvery = HM * FN / PER;          // ... behind every kIssueEvery-th MFMA, until all PER are out
 
   f32x4 acc[FM][FN];
 #pragma unroll
