@@ -464,6 +464,26 @@ static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a) {
     gemm_f32_kernel<<<grid, 256, 0, s>>>(p);
     return hipGetLastError();
   }
+  // Full tiles whose last round would occupy at most half the chip (384 tiles: a round of 256, then 128), A
+  // row-major: the columns of that last round become a problem of their own, which takes the 128 x 256 tiles below.
+  if (ring_eligible(a) && !a.a_kmajor && !a.b_colsum) {
+    const int64_t tm = a.M / 256, tiles = tm * (a.N / 256), rest = tiles % 256;
+    if (tiles > 256 && rest > 0 && rest <= 128 && rest % tm == 0) {
+      const int64_t n2 = rest / tm * 256, n1 = a.N - n2;
+      const int64_t out_size = a.out_dtype == kBF16 ? 2 : 4;
+      const int64_t aux_size = a.epilogue == kEpiBiasResidual ? 4 : 2;
+      GemmArgs head = a, tail = a;
+      head.N = n1;
+      tail.N = n2;
+      tail.B = (const char*)a.B + (a.b_kmajor ? n1 : n1 * a.ldb) * 2;
+      if (a.bias) tail.bias = a.bias + n1;
+      if (a.aux) tail.aux = (const char*)a.aux + n1 * aux_size;
+      tail.C = (char*)a.C + n1 * out_size;
+      if (a.C2) tail.C2 = (char*)a.C2 + n1 * out_size;
+      err = launch_gemm_impl(s, head);
+      return err != hipSuccess ? err : launch_gemm_impl(s, tail);
+    }
+  }
   // Full 256x256 tiles with enough of them to fill the chip: the ring-buffered kernel.
   if (ring_eligible(a) && (a.M / 256) * (a.N / 256) >= 150)
     return launch_gemm_ring(s, bf16_params_of(a, 256), a.a_kmajor, a.b_kmajor);

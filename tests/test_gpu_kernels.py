@@ -26,9 +26,11 @@ def _rand(seed, shape, std=1.0):
 # ---- GEMM ---------------------------------------------------------------------------------------------
 
 # (4096, 4096, K): 256 full 256x256 tiles, the ring-buffered kernel, with 1, 2 and 3 k-tiles of 64;
-# (1024, 4096, K): 64 full tiles, which the ring-buffered kernel takes as 128 tiles of 128 x 256
+# (1024, 4096, K): 64 full tiles, which the ring-buffered kernel takes as 128 tiles of 128 x 256;
+# (2048, 12288, K): 384 full tiles = one round of 256 and a last round of 128, whose columns are computed on
+# 128 x 256 tiles by a second launch
 GEMM_SHAPES = [(300, 200, 136), (512, 384, 256), (130, 72, 8), (4096, 4096, 128), (4072, 4088, 200), (4096, 4096, 64),
-               (4096, 4096, 192), (1024, 4096, 192), (1024, 4096, 64)]
+               (4096, 4096, 192), (1024, 4096, 192), (1024, 4096, 64), (2048, 12288, 128)]
 
 
 @pytest.mark.parametrize("bf16", [False, True])
@@ -51,7 +53,8 @@ def test_gemm_forward_layout_bias(ctx, orc, shape, bf16):
 
 
 @pytest.mark.parametrize("bf16", [False, True])
-@pytest.mark.parametrize("shape", GEMM_SHAPES[:3] + [(4096, 4096, 128), (4096, 4096, 64), (4096, 4096, 192), (1024, 4096, 192)])
+@pytest.mark.parametrize("shape", GEMM_SHAPES[:3] + [(4096, 4096, 128), (4096, 4096, 64), (4096, 4096, 192), (1024, 4096, 192),
+                                                    (2048, 12288, 64)])
 def test_gemm_dgrad_and_wgrad_layouts(ctx, orc, shape, bf16):
     """dx = dy . W^T (B stored [n][k]) and dW = x^T . dy (both operands k-major), fp32 accumulate-into."""
     M, N, K = shape          # M tokens, N = in features, K = out features
@@ -79,7 +82,7 @@ def test_gemm_dgrad_and_wgrad_layouts(ctx, orc, shape, bf16):
 
 # ragged (register-staged kernel), 64 full tiles (ring kernel on 128 x 256 tiles), 256 full tiles (ring kernel)
 @pytest.mark.parametrize("bf16", [False, True])
-@pytest.mark.parametrize("shape", [(264, 328, 192), (1024, 4096, 128), (4096, 4096, 128)])
+@pytest.mark.parametrize("shape", [(264, 328, 192), (1024, 4096, 128), (4096, 4096, 128), (2048, 12288, 64)])
 def test_gemm_fused_epilogues(ctx, orc, bf16, shape):
     M, N, K = shape
     if not bf16 and M * N * K > 1e8:
