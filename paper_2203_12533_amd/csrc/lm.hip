@@ -51,7 +51,10 @@ size_t plan(Model* m, unsigned char* base) {
   const size_t BHT = (size_t)c.batch * c.n_head * c.seq;
   Carver cv;
   cv.base = base;
-  m->slots.resize(c.n_microbatch);
+  const size_t n_mb = (size_t)c.n_microbatch;
+  m->defer_wgrad = !c.has_embed && !c.has_head && c.bf16 && n_mb > 1;
+  m->slots.resize(n_mb);
+  m->pending.assign(n_mb, 0);
   for (auto& s : m->slots) {
     s.layer.resize(L);
     for (size_t l = 0; l < L; ++l) {
@@ -63,14 +66,34 @@ size_t plan(Model* m, unsigned char* base) {
       a.rstd1 = cv.take<float>(N * 4);
       a.mean2 = cv.take<float>(N * 4);
       a.rstd2 = cv.take<float>(N * 4);
-      a.a = cv.take<void>(N * d * es);
       a.qkv = cv.take<void>(N * 3 * d * es);
-      a.o = cv.take<void>(N * d * es);
-      a.mm = cv.take<void>(N * d * es);
       a.u = cv.take<void>(N * F * es);
-      a.h = cv.take<void>(N * F * es);
+      if (!m->defer_wgrad) {
+        a.a = cv.take<void>(N * d * es);
+        a.o = cv.take<void>(N * d * es);
+        a.mm = cv.take<void>(N * d * es);
+        a.h = cv.take<void>(N * F * es);
+      }
     }
     s.x_out = cv.take<float>(N * d * 4);
+  }
+  if (m->defer_wgrad) {
+    // operands of the weight-gradient GEMMs: per layer and tensor one block [micro-batch][token][feature], so that
+    // any run of consecutive micro-batches is one k-major operand
+    auto block = [&](size_t l, void* Model::LayerActs::*field, size_t width) {
+      unsigned char* b0 = cv.take<unsigned char>(n_mb * N * width * es);
+      for (size_t mb = 0; mb < n_mb; ++mb) m->slots[mb].layer[l].*field = b0 ? b0 + mb * N * width * es : nullptr;
+    };
+    for (size_t l = 0; l < L; ++l) {
+      block(l, &Model::LayerActs::a, d);
+      block(l, &Model::LayerActs::o, d);
+      block(l, &Model::LayerActs::mm, d);
+      block(l, &Model::LayerActs::h, F);
+      block(l, &Model::LayerActs::g_y2, d);
+      block(l, &Model::LayerActs::g_u, F);
+      block(l, &Model::LayerActs::g_yo, d);
+      block(l, &Model::LayerActs::g_qkv, 3 * d);
+    }
   }
   if (c.has_head) {
     m->y = cv.take<void>(N * d * es);
@@ -88,7 +111,7 @@ size_t plan(Model* m, unsigned char* base) {
   m->d_small = cv.take<void>(N * d * es);
   int64_t wsf = layernorm_bwd_ws_floats((int)N, (int)d);
   const int64_t widest = (int64_t)std::max(std::max(3 * d, F), d);
-  wsf = std::max(wsf, colsum_ws_floats((int64_t)N, widest));
+  wsf = std::max(wsf, colsum_ws_floats((int64_t)(m->defer_wgrad ? n_mb * N : N), widest));
   m->ws = cv.take<float>((size_t)wsf * 4);
   return cv.off;
 }
@@ -121,7 +144,9 @@ hipError_t layers_forward(Model* m, Model::Slot& s) {
 // The bias gradients of the two projections that write the residual stream (b2, bo) are column sums of the
 // stream's gradient; the LayerNorm backward that produces that gradient delivers them.  top_b2_done says
 // whether the caller's producer of dx_a already did so for the last layer's b2.
-hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2_done) {
+// defer: with deferred weight gradients (see lm.hpp) the four gradients that feed them go to this micro-batch's own
+// storage instead of the shared scratch, and the weight-gradient GEMMs are left to flush_wgrads.
+hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2_done, bool defer) {
   const pw_lm_config& c = m->cfg;
   const int N = m->N(), d = c.d_model, F = c.d_ff;
   const int dt = m->act_dtype();
@@ -129,40 +154,74 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
   for (int l = c.n_layer - 1; l >= 0; --l) {
     auto& A = s.layer[l];
     const size_t e = layer_base(m, l);
-    const void* dx_op = c.bf16 ? m->dx_lp : (const void*)m->dx_a;
+    void* const d_big = defer ? A.g_u : m->d_big;
+    void* const d_qkv = defer ? A.g_qkv : m->d_qkv;
+    void* const lp_mid = defer ? A.g_yo : m->dx_lp;                                    // bf16 copy of dx_b
+    void* const lp_below = defer && l > 0 ? s.layer[l - 1].g_y2 : m->dx_lp;            // bf16 copy of the new dx_a
+    const void* dx_op = c.bf16 ? (defer ? (const void*)A.g_y2 : (const void*)m->dx_lp) : (const void*)m->dx_a;
     // FFN2: x_out = x_mid + h W2 + b2
-    PW_TRY(launch_gemm(m->stream, wgrad_args(m, A.h, dx_op, e + 10, N, F, d, accumulate)), "ffn2 wgrad");
+    if (!defer) PW_TRY(launch_gemm(m->stream, wgrad_args(m, A.h, dx_op, e + 10, N, F, d, accumulate)), "ffn2 wgrad");
     if (l == c.n_layer - 1 && !top_b2_done)
       PW_TRY(launch_colsum(m->stream, kF32, m->dx_a, g + P(m, e + 11).offset, m->ws, N, d, accumulate), "b2 grad");
-    PW_TRY(gemm_dgrad(m, dx_op, e + 10, N, F, d, kEpiGeluBwd, A.u, m->d_big, dt, 0), "ffn2 dgrad + gelu'");
+    PW_TRY(gemm_dgrad(m, dx_op, e + 10, N, F, d, kEpiGeluBwd, A.u, d_big, dt, 0), "ffn2 dgrad + gelu'");
     // FFN1: u = m W1 + b1
     // (b1 gradient = column sums of d_big: delivered by the weight-gradient GEMM where that is free)
-    PW_TRY(gemm_wgrad_bias(m, A.mm, m->d_big, e + 8, e + 9, N, d, F, accumulate, m->ws), "ffn1 wgrad + b1 grad");
-    PW_TRY(gemm_dgrad(m, m->d_big, e + 8, N, d, F, kEpiStore, nullptr, m->d_small, dt, 0), "ffn1 dgrad");
+    if (!defer) PW_TRY(gemm_wgrad_bias(m, A.mm, d_big, e + 8, e + 9, N, d, F, accumulate, m->ws), "ffn1 wgrad + b1 grad");
+    PW_TRY(gemm_dgrad(m, d_big, e + 8, N, d, F, kEpiStore, nullptr, m->d_small, dt, 0), "ffn1 dgrad");
     // LN2 and the residual branch: dx_b = dx_a + LN2'(d_small)
     PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_mid, m->w + P(m, e + 6).offset, A.mean2, A.rstd2, m->dx_a,
-                                m->dx_b, c.bf16 ? m->dx_lp : nullptr, g + P(m, e + 6).offset, g + P(m, e + 7).offset,
+                                m->dx_b, c.bf16 ? lp_mid : nullptr, g + P(m, e + 6).offset, g + P(m, e + 7).offset,
                                 g + P(m, e + 5).offset /* bo */, m->ws, N, d, accumulate), "ln2 bwd");
-    dx_op = c.bf16 ? m->dx_lp : (const void*)m->dx_b;
+    dx_op = c.bf16 ? (const void*)lp_mid : (const void*)m->dx_b;
     // out-proj: x_mid = x_in + o Wo + bo
     // (its weight gradient is computed together with the QKV one below: neither fills the chip alone)
     const void* dy_out = dx_op;
     PW_TRY(gemm_dgrad(m, dx_op, e + 4, N, d, d, kEpiStore, nullptr, m->d_small, dt, 0), "out-proj dgrad");
-    PW_TRY(launch_attention_bwd(m->stream, dt, A.qkv, A.o, m->d_small, A.lse, m->delta, m->d_qkv, c.batch, c.seq,
+    PW_TRY(launch_attention_bwd(m->stream, dt, A.qkv, A.o, m->d_small, A.lse, m->delta, d_qkv, c.batch, c.seq,
                                 c.n_head, m->hd()), "attention bwd");
     // QKV: qkv = a Wqkv + bqkv
     // (dy_out, the bf16 residual gradient, stays intact until the LN1 backward below rewrites it)
-    {
-      const WgradJob jobs[2] = {{wgrad_args(m, A.a, m->d_qkv, e + 2, N, d, 3 * d, accumulate), (int64_t)e + 3},
+    if (!defer) {
+      const WgradJob jobs[2] = {{wgrad_args(m, A.a, d_qkv, e + 2, N, d, 3 * d, accumulate), (int64_t)e + 3},
                                 {wgrad_args(m, A.o, dy_out, e + 4, N, d, d, accumulate), -1}};
       PW_TRY(gemm_wgrad_group(m, jobs, 2, m->ws), "qkv + out-proj wgrad + bqkv grad");
     }
-    PW_TRY(gemm_dgrad(m, m->d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small, dt, 0), "qkv dgrad");
+    PW_TRY(gemm_dgrad(m, d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small, dt, 0), "qkv dgrad");
     // LN1 and the residual branch: dx_a = dx_b + LN1'(d_small)
     PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->w + P(m, e).offset, A.mean1, A.rstd1, m->dx_b,
-                                m->dx_a, c.bf16 ? m->dx_lp : nullptr, g + P(m, e).offset, g + P(m, e + 1).offset,
+                                m->dx_a, c.bf16 ? lp_below : nullptr, g + P(m, e).offset, g + P(m, e + 1).offset,
                                 l > 0 ? g + P(m, layer_base(m, l - 1) + 11).offset /* b2 of the layer below */ : nullptr,
                                 m->ws, N, d, accumulate), "ln1 bwd");
+  }
+  return hipSuccess;
+}
+
+// The weight gradients that the backward passes of the pending micro-batches left undone: per layer four GEMMs
+// (three launches) over each run of consecutive pending micro-batches - one run, all of them, after a full
+// schedule - accumulated into g.
+hipError_t flush_wgrads(Model* m) {
+  if (!m->defer_wgrad) return hipSuccess;
+  const pw_lm_config& c = m->cfg;
+  const int N = m->N(), d = c.d_model, F = c.d_ff, n_mb = c.n_microbatch;
+  for (int first = 0; first < n_mb;) {
+    if (!m->pending[first]) {
+      ++first;
+      continue;
+    }
+    int last = first;
+    while (last + 1 < n_mb && m->pending[last + 1]) ++last;
+    const int64_t K = (int64_t)(last - first + 1) * N;
+    for (int l = c.n_layer - 1; l >= 0; --l) {
+      const auto& A = m->slots[first].layer[l];
+      const size_t e = layer_base(m, l);
+      PW_TRY(launch_gemm(m->stream, wgrad_args(m, A.h, A.g_y2, e + 10, K, F, d, 1)), "ffn2 wgrad");
+      PW_TRY(gemm_wgrad_bias(m, A.mm, A.g_u, e + 8, e + 9, K, d, F, 1, m->ws), "ffn1 wgrad + b1 grad");
+      const WgradJob jobs[2] = {{wgrad_args(m, A.a, A.g_qkv, e + 2, K, d, 3 * d, 1), (int64_t)e + 3},
+                                {wgrad_args(m, A.o, A.g_yo, e + 4, K, d, d, 1), -1}};
+      PW_TRY(gemm_wgrad_group(m, jobs, 2, m->ws), "qkv + out-proj wgrad + bqkv grad");
+    }
+    for (int mb = first; mb <= last; ++mb) m->pending[mb] = 0;
+    first = last + 1;
   }
   return hipSuccess;
 }
@@ -216,6 +275,7 @@ hipError_t model_create(const pw_lm_config& cfg, hipStream_t stream, Model** out
     return e;
   }
   plan(m, m->act);
+  m->flush_pending = [](ModelBase* base) { return flush_wgrads(static_cast<Model*>(base)); };
   *out = m;
   return hipSuccess;
 }
@@ -230,12 +290,15 @@ void model_destroy(Model* m) {
 hipError_t model_refresh_lowp(Model* m, int64_t offset, int64_t numel) { return model_state_refresh_lowp(m, offset, numel); }
 
 hipError_t model_zero_grads(Model* m) {
+  std::fill(m->pending.begin(), m->pending.end(), 0);   // contributions held back go the way of the ones in g
   PW_TRY(launch_fill_f32(m->stream, m->g, m->total, 0.f), "zero grads");
   return hipSuccess;
 }
 
 hipError_t model_apply_optimizer(Model* m) {
   const pw_lm_config& c = m->cfg;
+  hipError_t e = flush_wgrads(m);
+  if (e != hipSuccess) return e;
   return model_state_apply_optimizer(m, OptimizerConfig{c.optimizer, c.lr, c.beta1, c.beta2, c.eps});
 }
 
@@ -261,7 +324,7 @@ hipError_t model_train_step(Model* m, const int32_t* tokens, float* loss) {
   PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, s.x_out, m->w + P(m, tail).offset, m->meanf, m->rstdf, nullptr, m->dx_a,
                               c.bf16 ? m->dx_lp : nullptr, m->g + P(m, tail).offset, m->g + P(m, tail + 1).offset,
                               c.n_layer > 0 ? m->g + P(m, layer_base(m, c.n_layer - 1) + 11).offset : nullptr, m->ws, N, d, 0), "lnf bwd");
-  e = layers_backward(m, s, 0, true);
+  e = layers_backward(m, s, 0, true, false);
   if (e != hipSuccess) return e;
   PW_TRY(launch_embedding_bwd(m->stream, tokens, m->dx_a, m->g + P(m, 0).offset, m->g + P(m, 1).offset, c.batch, c.seq, d, V), "embedding bwd");
   return model_apply_optimizer(m);
@@ -274,6 +337,16 @@ hipError_t model_stage_fwd(Model* m, int mb, const float* x, float* y) {
     return hipErrorInvalidValue;
   }
   Model::Slot& s = m->slots[mb];
+  if (m->pending[mb]) {   // the activations about to be overwritten are operands of weight gradients held back
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    PW_TRY(hipStreamIsCapturing(m->stream, &cap), "capture status");
+    if (cap != hipStreamCaptureStatusNone) {
+      m->error = "stage_fwd under graph capture while weight gradients of this micro-batch are held back: apply the optimizer or zero the gradients first";
+      return hipErrorInvalidValue;
+    }
+    hipError_t e = flush_wgrads(m);
+    if (e != hipSuccess) return e;
+  }
   const int64_t bytes = (int64_t)m->N() * c.d_model * 4;
   PW_TRY(launch_copy_bytes(m->stream, x, s.layer[0].x_in, bytes), "stage input copy");
   hipError_t e = layers_forward(m, s);
@@ -289,11 +362,27 @@ hipError_t model_stage_bwd(Model* m, int mb, const float* dy, float* dx) {
     return hipErrorInvalidValue;
   }
   Model::Slot& s = m->slots[mb];
+  // Work held back lives in host-side bookkeeping, which the replay of a captured graph would not repeat: a call
+  // that is being captured does all of its work at once.
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  PW_TRY(hipStreamIsCapturing(m->stream, &cap), "capture status");
+  const bool capturing = cap != hipStreamCaptureStatusNone;
+  if (m->pending[mb]) {   // a second backward pass of this micro-batch: the first one's contribution goes in first
+    if (capturing) {
+      m->error = "stage_bwd under graph capture while weight gradients of this micro-batch are held back: apply the optimizer or zero the gradients first";
+      return hipErrorInvalidValue;
+    }
+    hipError_t e = flush_wgrads(m);
+    if (e != hipSuccess) return e;
+  }
+  const bool defer = m->defer_wgrad && !capturing;
   const int64_t n = (int64_t)m->N() * c.d_model;
   PW_TRY(launch_copy_bytes(m->stream, dy, m->dx_a, n * 4), "stage grad-output copy");
-  if (c.bf16) PW_TRY(launch_f32_to_bf16(m->stream, dy, m->dx_lp, n), "stage grad-output to bf16");
-  hipError_t e = layers_backward(m, s, 1, false);
+  if (c.bf16)
+    PW_TRY(launch_f32_to_bf16(m->stream, dy, defer ? s.layer[c.n_layer - 1].g_y2 : m->dx_lp, n), "stage grad-output to bf16");
+  hipError_t e = layers_backward(m, s, 1, false, defer);
   if (e != hipSuccess) return e;
+  if (defer) m->pending[mb] = 1;
   PW_TRY(launch_copy_bytes(m->stream, m->dx_a, dx, n * 4), "stage grad-input copy");
   return hipSuccess;
 }

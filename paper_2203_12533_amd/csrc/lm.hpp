@@ -20,12 +20,23 @@ struct Model : ModelBase {
   struct LayerActs {
     float *x_in, *x_mid, *lse, *mean1, *rstd1, *mean2, *rstd2;
     void *a, *qkv, *o, *mm, *u, *h;
+    // deferred weight gradients only: the four gradients that are the second operands of this layer's weight
+    // gradients (w.r.t. the layer output, the FFN pre-activation, the attention sub-block output, qkv)
+    void *g_y2 = nullptr, *g_u = nullptr, *g_yo = nullptr, *g_qkv = nullptr;
   };
   struct Slot {
     std::vector<LayerActs> layer;
     float* x_out;
   };
   std::vector<Slot> slots;    // one per micro-batch
+  // A pipeline stage in bf16 with several micro-batches holds its weight gradients back: the backward pass of a
+  // micro-batch leaves the operands of its four weight-gradient GEMMs per layer in per-micro-batch storage, which
+  // is laid out micro-batch after micro-batch, and one GEMM per weight over ALL pending micro-batches (contraction
+  // length n_microbatch x tokens) follows when the gradients are needed.  With HBM to spare this replaces
+  // n_microbatch read-modify-write passes over every gradient tensor by one, and 32 k-tiles per output tile by
+  // 32 x n_microbatch.  pending[mb]: the backward pass of micro-batch mb has run and its contribution is not in g yet.
+  bool defer_wgrad = false;
+  std::vector<char> pending;
   // head
   void* y = nullptr;
   void* logits = nullptr;

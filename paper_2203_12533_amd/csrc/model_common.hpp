@@ -36,6 +36,9 @@ struct ModelBase {
   float* v = nullptr;
   void* wlp = nullptr;        // bf16 compute copy of w (bf16 mode only)
   int* step_dev = nullptr;    // Adam step number, on the device so that captured graphs stay valid
+  // Set by a model that holds back gradient work (see lm.hpp): enqueues it.  Whoever is about to read or
+  // overwrite `g` from outside the model calls it first.
+  hipError_t (*flush_pending)(ModelBase*) = nullptr;
 
   int act_dtype() const { return bf16 ? kBF16 : kF32; }
   const ParamInfo& P(size_t idx) const { return params[idx]; }

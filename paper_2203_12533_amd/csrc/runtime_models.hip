@@ -57,6 +57,7 @@ static pw_status state_import(pw_ctx* c, ModelBase* m, int part, int64_t idx, co
   float* base = part_base(m, part);
   if (!base) return fail(c, PW_ERR_INVALID, "this model has no such part");
   const ParamInfo& p = m->params[idx];
+  if (m->flush_pending && m->flush_pending(m) != hipSuccess) return fail(c, PW_ERR_DEVICE, "%s", m->error.c_str());
   PW_HIP(c, hipMemcpyAsync(base + p.offset, src, (size_t)p.numel * 4, src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, c->exec));
   if (part == PW_PARAMS) {
     hipError_t e = model_state_refresh_lowp(m, p.offset, p.numel);
@@ -70,6 +71,7 @@ static pw_status state_export(pw_ctx* c, ModelBase* m, int part, int64_t idx, fl
   float* base = part_base(m, part);
   if (!base) return fail(c, PW_ERR_INVALID, "this model has no such part");
   const ParamInfo& p = m->params[idx];
+  if (m->flush_pending && m->flush_pending(m) != hipSuccess) return fail(c, PW_ERR_DEVICE, "%s", m->error.c_str());
   PW_HIP(c, hipStreamSynchronize(c->exec));
   PW_HIP(c, hipMemcpy(dst, base + p.offset, (size_t)p.numel * 4, hipMemcpyDeviceToHost));
   return PW_OK;

@@ -164,6 +164,72 @@ def test_pipeline_stage_schedule_matches_oracle(ctx, orc, bf16):
     model.close()
 
 
+def test_pipeline_stage_weight_gradients_held_back_are_flushed_whenever_needed(ctx, orc):
+    """A bf16 stage with several micro-batches computes each weight gradient once, over all micro-batches whose
+    backward pass has run, when the gradients are read, applied or about to lose their operands.  Partial and
+    non-adjacent sets of micro-batches, a second backward pass of one micro-batch and a forward pass that overwrites
+    pending activations must all leave what the sum rule says."""
+    cfg = I.LMConfig(2, 256, 2, 512, 0, 72, 1, bf16=True, optimizer="adam", has_embed=False, has_head=False,
+                     n_microbatch=4)
+    params = I.lm_params(cfg, perturb=True)
+    xs, dys = I.stage_io(cfg)
+    model = ctx.model(cfg)
+    model.load_params(params)
+    model.zero_grads()
+    fwd = [model.compile_stage(pwb.PW_FN_STAGE_FWD, mb) for mb in range(4)]
+    bwd = [model.compile_stage(pwb.PW_FN_STAGE_BWD, mb) for mb in range(4)]
+
+    def run(fn, arr):
+        f = ctx.future_from_host(arr)
+        (o,) = ctx.run_fn(fn, [f])
+        out = ctx.await_(o)
+        ctx.future_release(f)
+        ctx.future_release(o)
+        return out
+
+    def oracle_grads(mbs, x_of=None):
+        x_of = x_of or {}
+        _, _, g = orc.stage_fwd_bwd(cfg, params, [x_of.get(mb, xs[mb]) for mb in mbs], [dys[mb] for mb in mbs])
+        return g
+
+    def check(expected):
+        got = model.export_all(pwb.PW_GRADS, params)
+        for k in got:
+            assert rel_l2(got[k], expected[k]) < TOL[True], k
+
+    def plus(a, b, w=1.0):
+        return {k: a[k] + w * b[k] for k in a}
+
+    for mb in range(4):
+        run(fwd[mb], xs[mb])
+    for mb in (3, 1):                              # two runs of one micro-batch each
+        run(bwd[mb], dys[mb])
+    want = oracle_grads([1, 3])
+    check(want)
+    for mb in (2, 0):                              # the rest, on top of what is already in g
+        run(bwd[mb], dys[mb])
+    want = plus(want, oracle_grads([0, 2]))
+    check(want)
+    run(bwd[2], dys[2])                            # twice the same micro-batch without a read in between
+    run(bwd[2], dys[2])
+    g2 = oracle_grads([2])
+    want = plus(want, g2, 2.0)
+    check(want)
+    run(bwd[1], dys[1])                            # pending, then its activations are overwritten by a new forward
+    other = xs[0][::-1].copy()
+    run(fwd[1], other)
+    want = plus(want, oracle_grads([1]))
+    run(bwd[1], dys[1])                            # now with the new activations
+    want = plus(want, oracle_grads([1], {1: other}))
+    check(want)
+    model.zero_grads()                             # a pending contribution is dropped together with the gradients
+    run(bwd[3], dys[3])
+    model.zero_grads()
+    run(bwd[0], dys[0])
+    check(oracle_grads([0]))
+    model.close()
+
+
 def test_wrong_token_shape_is_rejected(ctx):
     cfg = I.LMConfig(1, 128, 2, 256, 64, 16, 2)
     model = ctx.model(cfg)
