@@ -211,15 +211,17 @@ hipError_t flush_wgrads(Model* m) {
     int last = first;
     while (last + 1 < n_mb && m->pending[last + 1]) ++last;
     const int64_t K = (int64_t)(last - first + 1) * N;
+    const int acc = m->wgrads_zero ? 0 : 1;   // into freshly zeroed gradients: no need to read the zeros back
     for (int l = c.n_layer - 1; l >= 0; --l) {
       const auto& A = m->slots[first].layer[l];
       const size_t e = layer_base(m, l);
-      PW_TRY(launch_gemm(m->stream, wgrad_args(m, A.h, A.g_y2, e + 10, K, F, d, 1)), "ffn2 wgrad");
-      PW_TRY(gemm_wgrad_bias(m, A.mm, A.g_u, e + 8, e + 9, K, d, F, 1, m->ws), "ffn1 wgrad + b1 grad");
-      const WgradJob jobs[2] = {{wgrad_args(m, A.a, A.g_qkv, e + 2, K, d, 3 * d, 1), (int64_t)e + 3},
-                                {wgrad_args(m, A.o, A.g_yo, e + 4, K, d, d, 1), -1}};
+      PW_TRY(launch_gemm(m->stream, wgrad_args(m, A.h, A.g_y2, e + 10, K, F, d, acc)), "ffn2 wgrad");
+      PW_TRY(gemm_wgrad_bias(m, A.mm, A.g_u, e + 8, e + 9, K, d, F, acc, m->ws), "ffn1 wgrad + b1 grad");
+      const WgradJob jobs[2] = {{wgrad_args(m, A.a, A.g_qkv, e + 2, K, d, 3 * d, acc), (int64_t)e + 3},
+                                {wgrad_args(m, A.o, A.g_yo, e + 4, K, d, d, acc), -1}};
       PW_TRY(gemm_wgrad_group(m, jobs, 2, m->ws), "qkv + out-proj wgrad + bqkv grad");
     }
+    m->wgrads_zero = false;
     for (int mb = first; mb <= last; ++mb) m->pending[mb] = 0;
     first = last + 1;
   }
@@ -275,7 +277,12 @@ hipError_t model_create(const pw_lm_config& cfg, hipStream_t stream, Model** out
     return e;
   }
   plan(m, m->act);
-  m->flush_pending = [](ModelBase* base) { return flush_wgrads(static_cast<Model*>(base)); };
+  m->flush_pending = [](ModelBase* base) {   // someone outside is about to read or write the gradients
+    Model* self = static_cast<Model*>(base);
+    const hipError_t e = flush_wgrads(self);
+    self->wgrads_zero = false;
+    return e;
+  };
   *out = m;
   return hipSuccess;
 }
@@ -292,6 +299,7 @@ hipError_t model_refresh_lowp(Model* m, int64_t offset, int64_t numel) { return 
 hipError_t model_zero_grads(Model* m) {
   std::fill(m->pending.begin(), m->pending.end(), 0);   // contributions held back go the way of the ones in g
   PW_TRY(launch_fill_f32(m->stream, m->g, m->total, 0.f), "zero grads");
+  m->wgrads_zero = true;
   return hipSuccess;
 }
 
@@ -383,6 +391,7 @@ hipError_t model_stage_bwd(Model* m, int mb, const float* dy, float* dx) {
   hipError_t e = layers_backward(m, s, 1, false, defer);
   if (e != hipSuccess) return e;
   if (defer) m->pending[mb] = 1;
+  else m->wgrads_zero = false;
   PW_TRY(launch_copy_bytes(m->stream, m->dx_a, dx, n * 4), "stage grad-input copy");
   return hipSuccess;
 }

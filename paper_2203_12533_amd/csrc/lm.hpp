@@ -37,6 +37,8 @@ struct Model : ModelBase {
   // 32 x n_microbatch.  pending[mb]: the backward pass of micro-batch mb has run and its contribution is not in g yet.
   bool defer_wgrad = false;
   std::vector<char> pending;
+  bool wgrads_zero = false;   // nothing has gone into the weight (and fused bias) gradients since they were zeroed:
+                              // the next GEMMs over pending micro-batches may overwrite instead of accumulate
   // head
   void* y = nullptr;
   void* logits = nullptr;
