@@ -126,8 +126,15 @@ def test_paired_attention_weight_gradients_at_cfg3_shape(ctx, orc):
     assert rel_l2(host(dwqkv), host(one_qkv)) < 1e-6 and rel_l2(host(dwo), host(one_o)) < 1e-6
 
 
-def test_attention_at_cfg3_shape(ctx, orc):
-    B, hd = CFG3.batch, CFG3.head_dim
+@pytest.mark.parametrize("workload,problems", [("cfg3", [(0, 0), (3, 7), (7, 15)]), ("cfg4", [(0, 0), (0, 31)]),
+                                               ("cfg5", [(0, 5), (1, 63)])])
+def test_attention_at_full_shapes(ctx, orc, workload, problems):
+    """Causal attention at the batch / sequence / head counts of the measured workloads (8 x 1024 x 16,
+    1 x 2048 x 32, 2 x 2048 x 64; the number of 128-row blocks per problem decides how the blocks of several
+    problems are interleaved), a few (batch, head) problems recomputed whole by the oracle."""
+    cfg = I.workload(workload)
+    B, hd, T, H = cfg.batch, cfg.head_dim, cfg.seq, cfg.n_head
+    N, D = B * T, H * hd
     qkv = _bf16_randn((N, 3 * D), 6)
     o = torch.empty((N, D), dtype=torch.bfloat16, device="cuda")
     lse = torch.empty((B, H, T), device="cuda")
@@ -137,7 +144,7 @@ def test_attention_at_cfg3_shape(ctx, orc):
     delta = torch.empty((B, H, T), device="cuda")
     ctx.op("attention_bwd", pwb.PW_BF16, ptr(qkv), ptr(o), ptr(dout), ptr(lse), ptr(delta), ptr(dqkv), B, T, H, hd)
     ctx.synchronize()
-    for (b, h) in [(0, 0), (3, 7), (7, 15)]:                      # sampled (batch, head) problems, recomputed whole
+    for (b, h) in problems:                                       # sampled (batch, head) problems, recomputed whole
         rows = slice(b * T, (b + 1) * T)
         cols = [slice(p * D + h * hd, p * D + (h + 1) * hd) for p in range(3)]
         sub = np.concatenate([host(qkv[rows, c]) for c in cols], axis=1)       # a 1-batch, 1-head problem
