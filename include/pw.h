@@ -75,7 +75,12 @@ typedef enum {
   PW_FN_ADD2 = 6,        /* two inputs of one shape: y = a + b (no params): the fan-in node of dataflow programs */
   PW_FN_LM_TRAIN_STEP = 16, /* in: tokens i32 [B, T+1]; out: loss f32 [1].  params: pw_model*. */
   PW_FN_STAGE_FWD = 17,  /* in: X [N, d]; out: Y [N, d].  params: pw_stage_params */
-  PW_FN_STAGE_BWD = 18,  /* in: dY [N, d]; out: dX [N, d]; adds into the stage's weight gradients */
+  PW_FN_STAGE_BWD = 18,  /* in: dY [N, d]; out: dX [N, d]; adds into the stage's weight gradients.  A bf16 stage with
+                            several micro-batches may hold the weight-gradient GEMMs back and run them once over all
+                            micro-batches whose backward pass has run; pw_model_export, pw_model_import,
+                            pw_model_apply_optimizer, pw_model_zero_grads and any call that would overwrite an operand
+                            account for what is held back, so the gradients read through this API are always the
+                            full sums.  Under HIP-graph capture nothing is held back. */
   PW_FN_ENCDEC_TRAIN_STEP = 19 /* in: source tokens i32 [B, Ts], target tokens i32 [B, Tt+1]; out: loss f32 [1].
                             params: pw_encdec*. */
 } pw_fn_kind;
