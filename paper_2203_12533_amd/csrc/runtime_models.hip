@@ -97,21 +97,29 @@ int64_t pw_model_param_count(pw_model* pm) { return pm ? (int64_t)pm->impl->para
 pw_status pw_model_param_info(pw_model* pm, int64_t idx, char* name, int cap, int64_t* numel) {
   return pm ? state_param_info(pm->impl, idx, name, cap, numel) : PW_ERR_INVALID;
 }
+// The calls below enqueue on the executor stream and touch the model's host-side bookkeeping, as the dispatch calls
+// do that run one of its functions: they take the same lock.
 pw_status pw_model_import(pw_model* pm, int part, int64_t idx, const float* src, int src_on_device) {
-  return pm ? state_import(pm->ctx, pm->impl, part, idx, src, src_on_device) : PW_ERR_INVALID;
+  if (!pm) return PW_ERR_INVALID;
+  PW_API_LOCK(pm->ctx);
+  return state_import(pm->ctx, pm->impl, part, idx, src, src_on_device);
 }
 pw_status pw_model_export(pw_model* pm, int part, int64_t idx, float* dst) {
-  return pm ? state_export(pm->ctx, pm->impl, part, idx, dst) : PW_ERR_INVALID;
+  if (!pm) return PW_ERR_INVALID;
+  PW_API_LOCK(pm->ctx);
+  return state_export(pm->ctx, pm->impl, part, idx, dst);
 }
 
 pw_status pw_model_zero_grads(pw_model* pm) {
   if (!pm) return PW_ERR_INVALID;
+  PW_API_LOCK(pm->ctx);
   if (model_zero_grads(pm->impl) != hipSuccess) return fail(pm->ctx, PW_ERR_DEVICE, "%s", pm->impl->error.c_str());
   return PW_OK;
 }
 
 pw_status pw_model_apply_optimizer(pw_model* pm) {
   if (!pm) return PW_ERR_INVALID;
+  PW_API_LOCK(pm->ctx);
   if (model_apply_optimizer(pm->impl) != hipSuccess) return fail(pm->ctx, PW_ERR_DEVICE, "%s", pm->impl->error.c_str());
   return PW_OK;
 }
@@ -171,10 +179,14 @@ pw_status pw_encdec_param_info(pw_encdec* pm, int64_t idx, char* name, int cap, 
   return pm ? state_param_info(pm->impl, idx, name, cap, numel) : PW_ERR_INVALID;
 }
 pw_status pw_encdec_import(pw_encdec* pm, int part, int64_t idx, const float* src, int src_on_device) {
-  return pm ? state_import(pm->ctx, pm->impl, part, idx, src, src_on_device) : PW_ERR_INVALID;
+  if (!pm) return PW_ERR_INVALID;
+  PW_API_LOCK(pm->ctx);
+  return state_import(pm->ctx, pm->impl, part, idx, src, src_on_device);
 }
 pw_status pw_encdec_export(pw_encdec* pm, int part, int64_t idx, float* dst) {
-  return pm ? state_export(pm->ctx, pm->impl, part, idx, dst) : PW_ERR_INVALID;
+  if (!pm) return PW_ERR_INVALID;
+  PW_API_LOCK(pm->ctx);
+  return state_export(pm->ctx, pm->impl, part, idx, dst);
 }
 
 pw_status pw_encdec_export_activation(pw_encdec* pm, const char* name, float* dst, int64_t numel) {
