@@ -406,6 +406,13 @@ def main():
                      "gemm_ms_per_step": round(gemm_ms / max(1, profiled_steps), 3)},
     }
     result["device"] = device_note(torch, sampled)
+    clk = sampled.get("sclk_mhz_during_timed_steps", {}).get("mean")
+    if clk:
+        # context, not the headline: the same achieved rate against the matrix peak at the clock the power limit
+        # left the chip during the timed steps (published peak x sampled clock / nominal 2400 MHz)
+        peak_at_clk = PEAK_BF16_TFLOPS * clk / 2400.0
+        result["roofline"]["peak_at_sampled_clock"] = round(peak_at_clk, 1)
+        result["roofline"]["frac_at_sampled_clock"] = round(gemm_tflops / peak_at_clk, 4)
     if not args.no_dispatch:
         result["dispatch_us_per_fn"] = dispatch_bench(ctx, pwb, I)
     model.close()
