@@ -17,3 +17,8 @@ def orc():
     from oracle import oracle
     oracle.lib()
     return oracle
+
+
+def pytest_sessionfinish(session, exitstatus):
+    import parity
+    parity.dump_margins()

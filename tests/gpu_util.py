@@ -4,6 +4,7 @@ import torch
 
 from paper_2203_12533_amd import binding as pwb
 from paper_2203_12533_amd import inputs as I
+from parity import assert_close, rel_l2  # noqa: F401  (the criterion lives in parity.py, numpy only)
 
 
 def dev_f32(a):
@@ -31,12 +32,6 @@ def host(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def rel_l2(got, ref):
-    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
-    den = np.linalg.norm(ref)
-    return float(np.linalg.norm(got - ref) / den) if den > 0 else float(np.linalg.norm(got))
-
-
 def ptr(t):
     """Device address of a torch tensor.  torch fills tensors on its own stream and the library runs on the
     context's executor stream, so wait for torch first."""
@@ -45,5 +40,6 @@ def ptr(t):
 
 
 DT = {False: pwb.PW_F32, True: pwb.PW_BF16}
-# parity bars of this build: fp32 path 1e-4, bf16 path 2e-2 (relative L2 per tensor, |d|/|ref| for the loss)
+# parity bars of this build: fp32 path 1e-4, bf16 path 2e-2 (relative L2 per tensor and, at the same bar, every
+# element - parity.assert_close; |d|/|ref| for the loss)
 TOL = {False: 1e-4, True: 2e-2}

@@ -7,7 +7,7 @@ import torch
 
 from paper_2203_12533_amd import binding as pwb
 from paper_2203_12533_amd import inputs as I
-from gpu_util import DT, TOL, dev_act, dev_f32, dev_i32, empty_act, host, ptr, rel_l2
+from gpu_util import DT, TOL, assert_close, dev_act, dev_f32, dev_i32, empty_act, host, ptr, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -49,7 +49,7 @@ def test_gemm_forward_layout_bias(ctx, orc, shape, bf16):
              out_dtype=DT[bf16], accumulate=0, A=ptr(x), B=ptr(w), bias=ptr(bd), C=ptr(out))
     ctx.synchronize()
     ref = orc.linear_fwd(xv, wv, b.astype(np.float64))
-    assert rel_l2(host(out), ref) < (4e-3 if bf16 else 2e-6)
+    assert_close(host(out), ref, 4e-3 if bf16 else 2e-6)
 
 
 @pytest.mark.parametrize("bf16", [False, True])
@@ -76,8 +76,8 @@ def test_gemm_dgrad_and_wgrad_layouts(ctx, orc, shape, bf16):
         ctx.synchronize()
         rdx, rdw, _ = orc.linear_bwd(xv, wv, dyv)
         want = rdw + base if acc else rdw
-        assert rel_l2(host(dw), want) < 2e-6, acc
-    assert rel_l2(host(dx), rdx) < (4e-3 if bf16 else 2e-6)
+        assert_close(host(dw), want, 2e-6, acc)
+    assert_close(host(dx), rdx, 4e-3 if bf16 else 2e-6)
 
 
 # ragged (register-staged kernel), 64 full tiles (ring kernel on 128 x 256 tiles), 256 full tiles (ring kernel)
@@ -107,11 +107,11 @@ def test_gemm_fused_epilogues(ctx, orc, bf16, shape):
     ctx.gemm(epilogue=pwb.PW_EPI_GELU_BWD, out_dtype=DT[bf16], aux=ptr(pre), C=ptr(du), **common)
     ctx.synchronize()
     tol = 4e-3 if bf16 else 2e-6
-    assert rel_l2(host(u), lin) < tol
-    assert rel_l2(host(h), orc.gelu_fwd(lin)) < tol * 1.5
-    assert rel_l2(host(xo), lin + res) < (2e-6 if not bf16 else 1e-5)
+    assert_close(host(u), lin, tol)
+    assert_close(host(h), orc.gelu_fwd(lin), tol * 1.5)
+    assert_close(host(xo), lin + res, 2e-6 if not bf16 else 1e-5)
     nobias = orc.linear_fwd(xv, wv)
-    assert rel_l2(host(du), orc.gelu_bwd(prev, nobias)) < tol
+    assert_close(host(du), orc.gelu_bwd(prev, nobias), tol)
 
 
 @pytest.mark.parametrize("bf16", [False, True])
@@ -134,8 +134,8 @@ def test_gemm_pair_small_problems_and_rejection(ctx, orc, bf16):
     assert (host(c0) == 7.0).all() and (host(c1) == 7.0).all()
     ctx.gemm_pair(args(x0, w0, c0, M0, N0, K0), args(x1, w1, c1, M1, N1, K1))
     ctx.synchronize()
-    assert rel_l2(host(c0), orc.linear_fwd(x0v, w0v)) < 2e-6
-    assert rel_l2(host(c1), orc.linear_fwd(x1v, w1v)) < 2e-6
+    assert_close(host(c0), orc.linear_fwd(x0v, w0v), 2e-6)
+    assert_close(host(c1), orc.linear_fwd(x1v, w1v), 2e-6)
 
 
 def test_gemm_rejects_what_the_kernel_cannot_take(ctx):
@@ -181,15 +181,19 @@ def test_layernorm_forward_backward(ctx, orc, N, d, bf16):
     ctx.op("layernorm_bwd", DT[bf16], ptr(dy), ptr(xd), ptr(gd), ptr(mean), ptr(rstd), None, ptr(dx0), None,
            ptr(dg0), ptr(db0), None, ptr(ws), N, d, 0)
     ctx.synchronize()
-    assert rel_l2(host(y), ry) < (4e-3 if bf16 else 2e-6)
-    assert rel_l2(host(mean), rmean) < 1e-5 and rel_l2(host(rstd), rrstd) < 1e-5
+    assert_close(host(y), ry, 4e-3 if bf16 else 2e-6)
+    assert_close(host(mean), rmean, 1e-5)
+    assert_close(host(rstd), rrstd, 1e-5)
     rdx, rdg, rdb = orc.layernorm_bwd(dyv, x, g)
-    assert rel_l2(host(dx), rdx + dres) < 1e-5
-    assert rel_l2(host(dg), rdg + 1.0) < 1e-5 and rel_l2(host(db), rdb + 1.0) < 1e-5   # accumulate = 1 adds
-    assert rel_l2(host(dsum), (rdx + dres).sum(axis=0) + 1.0) < 1e-5                   # column sums of dx
-    assert rel_l2(host(dx0), rdx) < 1e-5 and rel_l2(host(dg0), rdg) < 1e-5 and rel_l2(host(db0), rdb) < 1e-5
+    assert_close(host(dx), rdx + dres, 1e-5)
+    assert_close(host(dg), rdg + 1.0, 1e-5)                                            # accumulate = 1 adds
+    assert_close(host(db), rdb + 1.0, 1e-5)
+    assert_close(host(dsum), (rdx + dres).sum(axis=0) + 1.0, 1e-5)                     # column sums of dx
+    assert_close(host(dx0), rdx, 1e-5)
+    assert_close(host(dg0), rdg, 1e-5)
+    assert_close(host(db0), rdb, 1e-5)
     if bf16:
-        assert rel_l2(host(dxlp), rdx + dres) < 4e-3
+        assert_close(host(dxlp), rdx + dres, 4e-3)
 
 
 # ---- attention ----------------------------------------------------------------------------------------
@@ -204,7 +208,7 @@ def test_attention_forward_backward(ctx, orc, B, T, H, hd, bf16):
     ctx.op("attention_fwd", DT[bf16], ptr(qkv), ptr(o), ptr(lse), B, T, H, hd)
     ctx.synchronize()
     ro = orc.attention_fwd(qkvv, B, T, H, hd)
-    assert rel_l2(host(o), ro) < (6e-3 if bf16 else 1e-5)
+    assert_close(host(o), ro, 6e-3 if bf16 else 1e-5)
     # log-sum-exp of the scaled causal scores, brute force for a few rows
     r = qkvv.reshape(B, T, 3, H, hd)
     for (b, h, i) in [(0, 0, 0), (B - 1, H - 1, T - 1), (0, H - 1, T // 2)]:
@@ -219,7 +223,7 @@ def test_attention_forward_backward(ctx, orc, B, T, H, hd, bf16):
     rd = orc.attention_bwd(qkvv, doutv, B, T, H, hd)
     got = host(dqkv)
     for name, sl in (("dq", slice(0, d)), ("dk", slice(d, 2 * d)), ("dv", slice(2 * d, 3 * d))):
-        assert rel_l2(got[:, sl], rd[:, sl]) < (1.5e-2 if bf16 else 1e-5), name
+        assert_close(got[:, sl], rd[:, sl], 1.5e-2 if bf16 else 1e-5, name)
 
 
 def _mha_case(ctx, orc, bf16, B, Tq, Tk, H, hd, causal, packed_kv):
@@ -242,9 +246,9 @@ def _mha_case(ctx, orc, bf16, B, Tq, Tk, H, hd, causal, packed_kv):
     ro = orc.mha_fwd(qv, kh, vh, B, Tq, Tk, H, hd, causal=causal)
     # o_lo holds what rounding O left over (nothing in fp32); the sum is the kernel's fp32 result, itself exact only
     # as far as the bf16 probabilities of the second product allow
-    assert rel_l2(host(o) + host(o_lo), ro) < (4e-3 if bf16 else 1e-5)
+    assert_close(host(o) + host(o_lo), ro, 4e-3 if bf16 else 1e-5)
     assert np.abs(host(o_lo)).max() <= (np.abs(host(o)).max() * 2.0 ** -8 if bf16 else 0.0)
-    assert rel_l2(host(o), ro) < (6e-3 if bf16 else 1e-5)
+    assert_close(host(o), ro, 6e-3 if bf16 else 1e-5)
     qr, kr = qv.reshape(B, Tq, H, hd), np.ascontiguousarray(kh).reshape(B, Tk, H, hd)
     for (b, h, i) in [(0, 0, 0), (B - 1, H - 1, Tq - 1), (0, H - 1, Tq // 2)]:
         s = kr[b, : (i + 1 if causal else Tk), h] @ qr[b, i, h] / np.sqrt(hd)
@@ -258,8 +262,9 @@ def _mha_case(ctx, orc, bf16, B, Tq, Tk, H, hd, causal, packed_kv):
     ctx.synchronize()
     rdq, rdk, rdv = orc.mha_bwd(qv, kh, vh, doutv, B, Tq, Tk, H, hd, causal=causal)
     tol = 1.5e-2 if bf16 else 1e-5
-    assert rel_l2(host(dq), rdq) < tol
-    assert rel_l2(host(dkv)[:, :d], rdk) < tol and rel_l2(host(dkv)[:, d:], rdv) < tol
+    assert_close(host(dq), rdq, tol)
+    assert_close(host(dkv)[:, :d], rdk, tol)
+    assert_close(host(dkv)[:, d:], rdv, tol)
 
 
 @pytest.mark.parametrize("bf16", [False, True])
@@ -309,6 +314,8 @@ def test_attention_output_remainder_keeps_query_gradient_accurate(ctx, orc):
             assert rel_l2(host(o) + host(o_lo), ro) < 0.2 * rel_l2(host(o), ro)
     print("dq, dk, dv errors without / with the remainder:", errs[False], errs[True])
     assert max(errs[True]) < 1.5e-2
+    for got, want, name in ((host(dq), rdq, "dq"), (host(dkv)[:, :d], rdk, "dk"), (host(dkv)[:, d:], rdv, "dv")):
+        assert_close(got, want, 1.5e-2, name)          # the last pass of the loop kept the remainder
     assert errs[False][0] > 3 * errs[True][0]          # what the remainder is for
 
 
@@ -338,7 +345,7 @@ def test_softmax_xent(ctx, orc, B, T, V, bf16):
     ctx.synchronize()
     rl, rdz = orc.softmax_xent(zv, tok[:, 1:].reshape(-1))
     assert abs(host(loss)[0] - rl) / rl < 1e-5
-    assert rel_l2(host(z), rdz) < (6e-3 if bf16 else 1e-5)
+    assert_close(host(z), rdz, 6e-3 if bf16 else 1e-5)
     if not bf16:
         assert np.abs(host(z).sum(axis=1)).max() < 1e-6     # rows of dlogits sum to 0
 
@@ -371,7 +378,8 @@ def test_embedding_forward_is_bit_exact_and_backward_is_deterministic(ctx, orc):
         outs.append((dwte.cpu().numpy(), dwpe.cpu().numpy()))
     assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
     rwte, rwpe = orc.embedding_bwd(inp, dx, V)
-    assert rel_l2(outs[0][0], rwte) < 1e-6 and rel_l2(outs[0][1], rwpe) < 1e-6
+    assert_close(outs[0][0], rwte, 1e-6)
+    assert_close(outs[0][1], rwpe, 1e-6)
     unused = sorted(set(range(V)) - set(inp.reshape(-1).tolist()))
     for u in unused:
         assert (outs[0][0][u] == 0).all()
@@ -387,7 +395,7 @@ def test_embedding_backward_handles_one_id_everywhere(ctx, orc):
     ctx.op("embedding_bwd", ptr(tokd), ptr(dxd), ptr(dwte), ptr(dwpe), B, T, d, V)
     ctx.synchronize()
     rwte, _ = orc.embedding_bwd(tok[:, :T], dx, V)
-    assert rel_l2(host(dwte), rwte) < 1e-5
+    assert_close(host(dwte), rwte, 1e-5)
 
 
 # ---- column sums and optimisers -----------------------------------------------------------------------
@@ -400,10 +408,10 @@ def test_colsum(ctx, rows, cols, bf16):
     ws = torch.empty(pwb.lib().pw_colsum_ws_floats(rows, cols), device="cuda")
     ctx.op("colsum", DT[bf16], ptr(a), ptr(out), ptr(ws), rows, cols, 1)
     ctx.synchronize()
-    assert rel_l2(host(out), av.sum(axis=0) + 3.0) < 1e-5
+    assert_close(host(out), av.sum(axis=0) + 3.0, 1e-5)
     ctx.op("colsum", DT[bf16], ptr(a), ptr(out), ptr(ws), rows, cols, 0)
     ctx.synchronize()
-    assert rel_l2(host(out), av.sum(axis=0)) < 1e-5
+    assert_close(host(out), av.sum(axis=0), 1e-5)
 
 
 @pytest.mark.parametrize("n", [1, 1023, 1 << 20])
@@ -413,7 +421,7 @@ def test_sgd_and_adam_kernels(ctx, orc, n):
     wd, gd = dev_f32(w), dev_f32(g)
     ctx.op("sgd", ptr(wd), ptr(gd), n, 0.01)
     ctx.synchronize()
-    assert rel_l2(host(wd), orc.sgd(w.astype(np.float64), g.astype(np.float64), np.float32(0.01))) < 1e-7
+    assert_close(host(wd), orc.sgd(w.astype(np.float64), g.astype(np.float64), np.float32(0.01)), 1e-7)
     wd, md, vd = dev_f32(w), dev_f32(np.zeros(n)), dev_f32(np.zeros(n))
     wlp = torch.empty(n, dtype=torch.bfloat16, device="cuda")
     rw, rm, rv = w.astype(np.float64), np.zeros(n), np.zeros(n)
@@ -424,5 +432,6 @@ def test_sgd_and_adam_kernels(ctx, orc, n):
                               np.float32(eps), t)
     ctx.synchronize()
     assert np.abs(host(wd) - rw).max() < 1e-6            # identical gradient: the kernel itself is held to 1e-6
-    assert rel_l2(host(md), rm) < 1e-6 and rel_l2(host(vd), rv) < 1e-6
+    assert_close(host(md), rm, 1e-6)
+    assert_close(host(vd), rv, 1e-6)
     assert np.array_equal(wlp.float().cpu().numpy(), I.round_to_bf16(wd.cpu().numpy()))   # bf16 copy is RNE of w
