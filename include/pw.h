@@ -20,7 +20,9 @@
  *  - returns a pw_status; never throws; outputs go through pointer arguments;
  *  - "host" pointers are ordinary process memory, "device" pointers are HIP
  *    device memory on the context's GPU; the caller owns what it passes in;
- *  - calls on one pw_ctx must come from one thread at a time;
+ *  - the context, function, future, chain, pipeline, program, await, scheduler and model-state calls (pw_model_*,
+ *    pw_encdec_*) of one pw_ctx are serialised inside the library, so threads may share a context; the
+ *    single-kernel calls (pw_op_*) and pw_profile_* take no lock and must come from one thread at a time;
  *  - on error nothing is enqueued unless the text says otherwise, and
  *    pw_last_error() gives a message.
  * There is no CPU fallback: without a usable GPU pw_ctx_create fails.
@@ -102,7 +104,8 @@ typedef enum {
   PW_STREAM = 0,      /* enqueue every function of the chain at once on the executor stream */
   PW_GRAPH = 1,       /* the same launches, captured once into a HIP graph and replayed */
   PW_SEQUENTIAL = 2   /* wait for each function to complete before enqueuing the next: the
-                         sequential-dispatch baseline of Section 5.1, for comparison only */
+                         sequential-dispatch baseline of Section 5.1, for comparison only.  Its inputs must not
+                         depend on an unresolved pending future: PW_ERR_NOT_READY, nothing enqueued */
 } pw_chain_mode;
 
 typedef enum {
@@ -190,7 +193,7 @@ pw_status pw_ctx_set_executor_prep_us(pw_ctx* ctx, int us);
  * producer's stream copies its output into it (Section 4.5: shapes are static, so every buffer is planned
  * before anything runs); the dependency is a HIP event.  Everything is validated first: on any error nothing
  * is enqueued.  Returns when every node has been enqueued (not run); `out` receives the last node's output
- * (refcount 1).  dispatch: a pw_dispatch_mode.  Not thread-safe, like every call on a context. */
+ * (refcount 1).  dispatch: a pw_dispatch_mode. */
 pw_status pw_pipeline(pw_ctx* ctx, const pw_fn* fns, const int32_t* executor_of, int n_fns, pw_future in,
                       pw_future* out, int dispatch);
 
@@ -210,7 +213,7 @@ pw_status pw_program_destroy(pw_program* program);
 /* ---- several clients, one executor: the centralized scheduler (Section 4.4 "gang-scheduled dynamic dispatch",
  * measured in Section 5.2).  pw_sched_submit / _wait / _client_stats / _drain / _trace may be called from any
  * thread at any time; so may the function / future / chain / await calls of the context while a scheduler exists
- * (they are serialised inside).  Model and pw_op_* calls stay single-threaded. */
+ * (they are serialised inside, like the model-state calls).  pw_op_* calls stay single-threaded. */
 /* max_in_flight: programs the scheduler keeps enqueued on the device at once (1..1024); the rest wait in the
  * clients' queues, where the policy still has a say. */
 pw_status pw_sched_create(pw_ctx* ctx, int policy, int max_in_flight, pw_sched** out);

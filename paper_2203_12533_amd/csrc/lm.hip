@@ -303,6 +303,13 @@ hipError_t model_zero_grads(Model* m) {
   return hipSuccess;
 }
 
+hipError_t model_before_graph(Model* m, bool backward) {
+  const hipError_t e = flush_wgrads(m);   // with acc = 0 only into gradients that nothing has touched since zeroing
+  if (e != hipSuccess) return e;
+  if (backward) m->wgrads_zero = false;
+  return hipSuccess;
+}
+
 hipError_t model_apply_optimizer(Model* m) {
   const pw_lm_config& c = m->cfg;
   hipError_t e = flush_wgrads(m);

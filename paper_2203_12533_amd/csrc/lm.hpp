@@ -59,6 +59,11 @@ hipError_t model_train_step(Model* m, const int32_t* tokens_dev, float* loss_dev
 hipError_t model_stage_fwd(Model* m, int mb, const float* x_dev, float* y_dev);
 hipError_t model_stage_bwd(Model* m, int mb, const float* dy_dev, float* dx_dev);
 hipError_t model_zero_grads(Model* m);
+// What the host must do for a stage function that is about to run as part of a HIP graph, captured now or replayed
+// from the cache (a replay repeats the launches, not the host-side bookkeeping of held-back weight gradients):
+// contributions still held back are enqueued first - the graph's forward pass overwrites their operands, its
+// backward pass adds to the gradients at once - and a backward pass marks the gradients as written.
+hipError_t model_before_graph(Model* m, bool backward);
 hipError_t model_apply_optimizer(Model* m);
 double model_step_flops(const pw_lm_config& cfg);
 bool model_config_ok(const pw_lm_config& cfg, std::string* why);

@@ -174,6 +174,15 @@ bool model_alive(pw_ctx* c, Model* m) {
     if (x == m) return true;
   return false;
 }
+// Host-side part of a stage function that runs inside a HIP graph (fresh capture or cached replay alike).
+pw_status graph_host_effects(pw_ctx* c, const FnRec* fn) {
+  const int k = fn->desc.kind;
+  if ((k == PW_FN_STAGE_FWD || k == PW_FN_STAGE_BWD) && fn->model &&
+      model_before_graph(fn->model, k == PW_FN_STAGE_BWD) != hipSuccess)
+    return fail(c, PW_ERR_DEVICE, "%s", fn->model->error.c_str());
+  return PW_OK;
+}
+
 bool encdec_alive(pw_ctx* c, EncDec* m) {
   for (EncDec* x : c->encdecs)
     if (x == m) return true;
@@ -563,6 +572,14 @@ pw_status pw_chain(pw_ctx* c, const pw_fn* fns, int n_fns, const pw_future* in, 
     if (!fin[i]) return fail(c, PW_ERR_INVALID, "input %d is not a live future", i);
     specs[i] = fin[i]->spec;
   }
+  if (mode == PW_SEQUENTIAL) {
+    // This baseline waits on the host for every link.  An input that hangs on an unresolved pending future would
+    // make it wait - holding the context's lock, so that pw_future_resolve could not get in - until the gate gives up.
+    for (int i = 0; i < n_in; ++i)
+      for (auto& gw : fin[i]->poison)
+        if (__atomic_load_n(&gw->words[0], __ATOMIC_ACQUIRE) == 0u)
+          return fail(c, PW_ERR_NOT_READY, "PW_SEQUENTIAL waits for every link: input %d depends on a pending future that has not been resolved", i);
+  }
   int cur_n = n_in;
   for (int i = 0; i < n_fns; ++i) {
     const int want_out = i + 1 < n_fns ? recs[i]->desc.n_out : n_out;
@@ -623,6 +640,8 @@ pw_status pw_chain(pw_ctx* c, const pw_fn* fns, int n_fns, const pw_future* in, 
   };
 
   if (mode == PW_GRAPH) {
+    for (int i = 0; i < n_fns; ++i)
+      if ((st = graph_host_effects(c, recs[i])) != PW_OK) { release_all(); return st; }
     std::string key;
     key.append((const char*)fns, sizeof(pw_fn) * n_fns);
     for (int j = 0; j < n_in; ++j) key.append((const char*)&fin[j]->buf, sizeof(void*));
@@ -631,6 +650,7 @@ pw_status pw_chain(pw_ctx* c, const pw_fn* fns, int n_fns, const pw_future* in, 
     auto it = c->graphs.find(key);
     if (it == c->graphs.end()) {
       if (c->graphs.size() >= 256) {   // bounded cache: drop everything rather than grow without limit
+        (void)hipStreamSynchronize(c->exec);   // a replay enqueued by an earlier call may not have run yet
         for (auto& kv : c->graphs) {
           (void)hipGraphExecDestroy(kv.second.exec);
           (void)hipGraphDestroy(kv.second.graph);
@@ -907,6 +927,11 @@ pw_status pw_program_run(pw_ctx* c, pw_program* p, const pw_future* in, int n_in
     pw_status st = spec_match(fin[i]->spec, p->specs[i]);
     if (st != PW_OK) return fail(c, st, "input %d does not match the traced signature", i);
   }
+  for (size_t i = 0; i < p->nodes.size(); ++i) {   // the nodes hold snapshots of their functions: a model may be gone since
+    const FnRec& fn = p->nodes[i].fn;
+    if ((fn.model && !model_alive(c, fn.model)) || (fn.encdec && !encdec_alive(c, fn.encdec)))
+      return fail(c, PW_ERR_INVALID, "node %zu runs a function of a model that has been destroyed", i);
+  }
   // ---- buffer plan: allocate each value when its producer is reached, give it back when its last consumer has
   // been passed (stream order keeps the reuse safe; the pool then repeats the same addresses call after call)
   const int n_nodes = (int)p->nodes.size();
@@ -957,6 +982,8 @@ pw_status pw_program_run(pw_ctx* c, pw_program* p, const pw_future* in, int n_in
     return PW_OK;
   };
   if (mode == PW_GRAPH) {
+    for (int i = 0; i < n_nodes; ++i)
+      if ((st = graph_host_effects(c, &p->nodes[i].fn)) != PW_OK) { release_outputs(); return st; }
     std::string key;
     for (auto& b : val) key.append((const char*)&b.p, sizeof(void*));
     auto it = p->graphs.find(key);

@@ -9,6 +9,7 @@ extern "C" {
 
 pw_status pw_model_create(pw_ctx* c, const pw_lm_config* cfg, pw_model** out) {
   if (!c || !cfg || !out) return PW_ERR_INVALID;
+  PW_API_LOCK(c);
   std::string why;
   if (!model_config_ok(*cfg, &why)) return fail(c, PW_ERR_UNSUPPORTED, "%s", why.c_str());
   Model* m = nullptr;
@@ -22,6 +23,7 @@ pw_status pw_model_create(pw_ctx* c, const pw_lm_config* cfg, pw_model** out) {
 pw_status pw_model_destroy(pw_model* pm) {
   if (!pm) return PW_ERR_INVALID;
   pw_ctx* c = pm->ctx;
+  PW_API_LOCK(c);   // the tables edited below are read by the dispatch calls, the scheduler and the executors
   (void)hipStreamSynchronize(c->exec);
   for (size_t i = 0; i < c->models.size(); ++i)
     if (c->models[i] == pm->impl) {
@@ -148,6 +150,7 @@ double pw_model_step_flops(const pw_lm_config* cfg) { return cfg ? model_step_fl
 
 pw_status pw_encdec_create(pw_ctx* c, const pw_encdec_config* cfg, pw_encdec** out) {
   if (!c || !cfg || !out) return PW_ERR_INVALID;
+  PW_API_LOCK(c);
   std::string why;
   if (!encdec_config_ok(*cfg, &why)) return fail(c, PW_ERR_UNSUPPORTED, "%s", why.c_str());
   EncDec* m = nullptr;
@@ -161,6 +164,7 @@ pw_status pw_encdec_create(pw_ctx* c, const pw_encdec_config* cfg, pw_encdec** o
 pw_status pw_encdec_destroy(pw_encdec* pm) {
   if (!pm) return PW_ERR_INVALID;
   pw_ctx* c = pm->ctx;
+  PW_API_LOCK(c);
   (void)hipStreamSynchronize(c->exec);
   for (size_t i = 0; i < c->encdecs.size(); ++i)
     if (c->encdecs[i] == pm->impl) {

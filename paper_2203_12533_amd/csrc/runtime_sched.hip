@@ -39,6 +39,7 @@ void sched_loop(pw_sched* s) {
   for (;;) {
     SchedProgram prog;
     int client = -1;
+    uint64_t client_owner = 0;
     {
       std::unique_lock<std::mutex> lk(s->mu);
       while (!s->stop && s->queued == 0) {
@@ -67,6 +68,7 @@ void sched_loop(pw_sched* s) {
       c.queue.pop_front();
       s->queued--;
       c.vtime += prog.est_us / c.weight;
+      client_owner = c.owner;   // copied under the lock: pw_sched_add_client may move the vector
     }
     while ((int)s->inflight.size() >= s->window) sched_retire(s);
     // ---- enqueue on the executor stream, bracketed by timing events
@@ -80,7 +82,7 @@ void sched_loop(pw_sched* s) {
       {
         std::unique_lock<std::recursive_mutex> api(s->ctx->api_mu);
         const uint64_t saved_owner = s->ctx->current_owner;
-        s->ctx->current_owner = s->clients[client].owner;   // what the program produces belongs to its client
+        s->ctx->current_owner = client_owner;   // what the program produces belongs to its client
         if (!fl.start) fl.start = sched_event(s);
         if (!fl.stop) fl.stop = sched_event(s);
         if (fl.start) (void)hipEventRecord(fl.start, s->ctx->exec);

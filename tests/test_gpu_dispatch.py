@@ -60,6 +60,27 @@ def test_sequential_mode_is_not_given_a_pending_input(ctx):
     ctx.future_release(f_in)
 
 
+def test_sequential_mode_refuses_an_unresolved_input(ctx, orc):
+    """The baseline blocks on the host after every link; on an input nobody has resolved yet it would block with the
+    context locked until the gate times out.  It is refused up front, nothing is enqueued, and works once resolved."""
+    x = I.dispatch_input()
+    add1 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    f_in = ctx.future_pending(pwb.PW_F32, (128,))
+    (f_mid,) = ctx.chain([add1], [f_in], 1, pwb.PW_STREAM)          # derived from the pending one
+    live0, bytes0 = ctx.stats()
+    for f in (f_in, f_mid):
+        with pytest.raises(pwb.PwError) as e:
+            ctx.chain([add1] * 4, [f], 1, pwb.PW_SEQUENTIAL)
+        assert e.value.status == pwb.PW_ERR_NOT_READY
+    assert ctx.stats() == (live0, bytes0)
+    ctx.future_resolve(f_in, x)
+    (f_out,) = ctx.chain([add1] * 4, [f_mid], 1, pwb.PW_SEQUENTIAL)
+    assert np.array_equal(ctx.await_(f_out), orc.chain_add(x, 5))      # five sequential fp32 additions
+    for f in (f_in, f_mid, f_out):
+        ctx.future_release(f)
+    ctx.fn_release(add1)
+
+
 def test_op_by_op_equals_chained(ctx, orc):
     x = I.dispatch_input()
     add1 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)

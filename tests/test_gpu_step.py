@@ -241,6 +241,91 @@ def test_pipeline_stage_weight_gradients_held_back_are_flushed_whenever_needed(c
     model.close()
 
 
+def test_pipeline_stage_graph_replays_and_stream_calls_mix_in_one_step(ctx, orc):
+    """Micro-batches of one step dispatched in different modes: a backward pass replayed from the HIP-graph cache adds
+    to the gradients at once, one enqueued on the stream is held back - the replay must leave the host-side record of
+    "nothing written since zeroing" as a stream call would, or the held-back GEMMs overwrite what the replay added.
+    Likewise a forward pass run as a graph while a contribution of its micro-batch is held back must let that
+    contribution in first, because it overwrites its operands."""
+    cfg = I.LMConfig(2, 256, 2, 512, 0, 72, 1, bf16=True, optimizer="adam", has_embed=False, has_head=False,
+                     n_microbatch=2)
+    params = I.lm_params(cfg, perturb=True)
+    xs, dys = I.stage_io(cfg)
+    model = ctx.model(cfg)
+    model.load_params(params)
+    fwd = [model.compile_stage(pwb.PW_FN_STAGE_FWD, mb) for mb in range(2)]
+    bwd = [model.compile_stage(pwb.PW_FN_STAGE_BWD, mb) for mb in range(2)]
+
+    def grads_of(mbs, x_of=None):
+        x_of = x_of or {}
+        _, _, g = orc.stage_fwd_bwd(cfg, params, [x_of.get(mb, xs[mb]) for mb in mbs], [dys[mb] for mb in mbs])
+        return g
+
+    def check(expected):
+        got = model.export_all(pwb.PW_GRADS, params)
+        for k in got:
+            assert_close(got[k], expected[k], TOL[True], k)
+
+    def run(fn, fut, mode):
+        if mode is None:
+            (o,) = ctx.run_fn(fn, [fut])
+        else:
+            (o,) = ctx.chain([fn], [fut], 1, mode)
+        ctx.await_(o)
+        ctx.future_release(o)
+
+    fx = [ctx.future_from_host(xs[mb]) for mb in range(2)]
+    fd = [ctx.future_from_host(dys[mb]) for mb in range(2)]
+    for mb in range(2):
+        run(fwd[mb], fx[mb], None)
+    g0, g1 = grads_of([0]), grads_of([1])
+    model.zero_grads()
+    run(bwd[0], fd[0], pwb.PW_GRAPH)               # captured now
+    check(g0)
+    for first in (pwb.PW_GRAPH, None):             # the cached graph replayed / the stream call, then the other mode
+        model.zero_grads()
+        run(bwd[0], fd[0], first)
+        run(bwd[1], fd[1], None if first is not None else pwb.PW_GRAPH)
+        check({k: g0[k] + g1[k] for k in g0})
+    # held back, then the same micro-batch's forward pass as a graph (capture, then replay) on other activations
+    other = xs[0][::-1].copy()
+    fo = ctx.future_from_host(other)
+    g1o = grads_of([1], {1: other})
+    for rep in range(2):
+        model.zero_grads()
+        run(fwd[1], fx[1], None)
+        run(bwd[1], fd[1], None)                   # pending, operands = activations of xs[1]
+        run(fwd[1], fo, pwb.PW_GRAPH)              # overwrites them
+        run(bwd[1], fd[1], None)
+        check({k: g1[k] + g1o[k] for k in g1})
+    for f in fx + fd + [fo]:
+        ctx.future_release(f)
+    model.close()
+
+
+def test_program_of_a_destroyed_model_is_refused(ctx):
+    """A traced program keeps snapshots of its functions; once their model is gone a run must be refused, not
+    launched on freed memory."""
+    cfg = I.LMConfig(1, 128, 2, 256, 0, 16, 1, has_embed=False, has_head=False)
+    model = ctx.model(cfg)
+    fwd = model.compile_stage(pwb.PW_FN_STAGE_FWD, 0)
+    spec = pwb.make_spec(pwb.PW_F32, (16, 128))
+    prog = pwb.Program(ctx, [spec], [(fwd, [0])], [1])
+    fx = ctx.future_from_host(np.zeros((16, 128), np.float32))
+    (fy,) = prog.run([fx])
+    ctx.await_(fy)
+    ctx.future_release(fy)
+    model.close()
+    live0, bytes0 = ctx.stats()
+    for mode in (pwb.PW_STREAM, pwb.PW_GRAPH):
+        with pytest.raises(pwb.PwError) as e:
+            prog.run([fx], mode)
+        assert e.value.status == pwb.PW_ERR_INVALID
+    assert ctx.stats() == (live0, bytes0)
+    ctx.future_release(fx)
+    prog.close()
+
+
 def test_wrong_token_shape_is_rejected(ctx):
     cfg = I.LMConfig(1, 128, 2, 256, 64, 16, 2)
     model = ctx.model(cfg)

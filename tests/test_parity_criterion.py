@@ -65,3 +65,18 @@ def test_heavy_tailed_rows_and_exact_zeros():
     with pytest.raises(AssertionError, match="non-finite"):
         assert_close(np.array([1.0, np.nan]), np.array([1.0, 1.0]), 1e-5)
     assert ELEM_C == 8.0
+
+
+def test_rows_of_zeros_do_not_shrink_the_allowance_of_the_rows_that_carry_values():
+    """An embedding gradient: most rows exactly zero.  The same honest error on the used rows must use the same share
+    of the allowance whether the zero rows are there or not."""
+    rng = np.random.default_rng(5)
+    dense = rng.standard_normal((64, 256))
+    err = 2e-3 * rng.standard_normal((64, 256))
+    sparse, sparse_err = np.zeros((1024, 256)), np.zeros((1024, 256))
+    rows = rng.choice(1024, 64, replace=False)
+    sparse[rows], sparse_err[rows] = dense, err
+    a, _ = elem_ratio(dense + err, dense, 2e-2)
+    b, _ = elem_ratio(sparse + sparse_err, sparse, 2e-2)
+    assert a == pytest.approx(b, rel=1e-12)
+    assert_close(sparse + sparse_err, sparse, 2e-2)
