@@ -418,6 +418,17 @@ pw_status pw_op_layernorm_bwd(pw_ctx* ctx, int dtype, const void* dy, const floa
                               const float* mean, const float* rstd, const float* dres, float* dx, void* dx_lp,
                               float* dg, float* db, float* dxsum, float* ws, int N, int d, int accumulate);
 int64_t pw_layernorm_bwd_ws_floats(int N, int d);
+/* pw_op_layernorm_bwd for callers that cannot allocate device memory - code under HIP-graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: same arguments without `ws`, same kernels, same bits.  The block sums go
+ * to a fixed 12 MiB array inside the library's code object (every GPU the library runs on holds its copy until the
+ * process ends; its address is looked up once per device by pw_ctx_create), and the call itself allocates nothing,
+ * frees nothing and calls no routine that does.  Limit: pw_layernorm_bwd_ws_floats(N, d) <= 3 * 512 * 2048
+ * (any N for d <= 2048; wider rows only with N < 512 * 2048 / d); beyond it PW_ERR_UNSUPPORTED, nothing enqueued.
+ * All calls on one GPU share the array and nothing in it has to survive or be cleared between calls, but two calls
+ * in flight at once on one GPU (different streams or contexts) race on it: keep them in one stream's order. */
+pw_status pw_op_layernorm_bwd_noalloc(pw_ctx* ctx, int dtype, const void* dy, const float* x, const float* g,
+                                      const float* mean, const float* rstd, const float* dres, float* dx, void* dx_lp,
+                                      float* dg, float* db, float* dxsum, int N, int d, int accumulate);
 /* Causal multi-head attention over qkv [B*T, 3d] in `dtype` (columns [Q|K|V], head h at h*hd):
  * o [B*T, d] in `dtype`, lse fp32 [B, H, T] (log-sum-exp of the scaled scores of each row). */
 pw_status pw_op_attention_fwd(pw_ctx* ctx, int dtype, const void* qkv, void* o, float* lse, int B, int T, int H, int hd);

@@ -155,6 +155,7 @@ _SIGS = {
     "pw_op_layernorm_fwd": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 6 + [C.c_int] * 2),
     "pw_op_layernorm_bwd": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 12 + [C.c_int] * 3),
     "pw_layernorm_bwd_ws_floats": (C.c_int64, [C.c_int, C.c_int]),
+    "pw_op_layernorm_bwd_noalloc": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 11 + [C.c_int] * 3),
     "pw_op_attention_fwd": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 3 + [C.c_int] * 4),
     "pw_op_attention_bwd": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 6 + [C.c_int] * 4),
     "pw_op_mha_fwd": (C.c_int, [C.c_void_p] * 5),

@@ -43,6 +43,14 @@ hipError_t launch_increment(hipStream_t s, int* counter);
 hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, const float* x, const float* g, const float* b, void* y,
                                 float* mean, float* rstd, int N, int d);
 int64_t layernorm_bwd_ws_floats(int N, int d);
+// The same with the workspace in a fixed device array of the library (no allocation anywhere on the path):
+// _init looks the array's address up for `device`, which must be current; the launcher needs that to have happened
+// (hipErrorNotInitialized) and takes problems whose workspace fits the array (hipErrorNotSupported otherwise).
+hipError_t layernorm_bwd_static_init(int device);
+int64_t layernorm_bwd_static_max_ws_floats();
+hipError_t launch_layernorm_bwd_static(hipStream_t s, int device, int dtype, const void* dy, const float* x, const float* g,
+                                       const float* mean, const float* rstd, const float* dres, float* dx, void* dx_lp,
+                                       float* dg, float* db, float* dsum, int N, int d, int accumulate);
 hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const float* x, const float* g,
                                 const float* mean, const float* rstd, const float* dres, float* dx, void* dx_lp,
                                 float* dg, float* db, float* dsum, float* ws, int N, int d, int accumulate);

@@ -405,6 +405,46 @@ hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const 
   return hipGetLastError();
 }
 
+// ---- LayerNorm backward for callers that cannot allocate ----------------------------------------------
+// The same kernels with the block sums in a fixed array of the code object instead of a caller workspace.  Each GPU
+// that loads the library holds its own copy of the array, at its own address, until the process ends.  In host code
+// the array's name is only a handle for hipGetSymbolAddress: the address the kernels get is the one looked up below,
+// once per device with that device current.
+constexpr int64_t kLnScratchFloats = 3LL * kLnBwdMaxBlocks * kLnWaveMaxD;   // 3 x 512 x 2048 floats = 12 MiB
+static __device__ __align__(256) float scratch[kLnScratchFloats];
+
+constexpr int kMaxDevices = 64;
+static float* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+int64_t layernorm_bwd_static_max_ws_floats() { return kLnScratchFloats; }
+
+hipError_t layernorm_bwd_static_init(int device) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  if (g_scratch_ptr[device]) return hipSuccess;
+  int cur = -1;
+  hipError_t e = hipGetDevice(&cur);
+  if (e != hipSuccess) return e;
+  if (cur != device) return hipErrorInvalidDevice;   // the lookup below answers for the current device
+  float* p = nullptr;
+  e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+  if (e != hipSuccess) return e;
+  if (!p) return hipErrorInvalidSymbol;
+  g_scratch_ptr[device] = p;
+  return hipSuccess;
+}
+
+hipError_t launch_layernorm_bwd_static(hipStream_t s, int device, int dtype, const void* dy, const float* x, const float* g,
+                                       const float* mean, const float* rstd, const float* dres, float* dx, void* dx_lp,
+                                       float* dg, float* db, float* dsum, int N, int d, int accumulate) {
+  if (device < 0 || device >= kMaxDevices || !g_scratch_ptr[device]) return hipErrorNotInitialized;
+  if (N < 0 || d <= 0) return hipErrorInvalidValue;
+  if (layernorm_bwd_ws_floats(N, d) > kLnScratchFloats) return hipErrorNotSupported;
+  // Every block of the first kernel overwrites its slots of the array and the second kernel reads exactly those
+  // slots, so nothing has to be cleared between calls; two calls in flight at once on one GPU would share the slots.
+  return launch_layernorm_bwd(s, dtype, dy, x, g, mean, rstd, dres, dx, dx_lp, dg, db, dsum, g_scratch_ptr[device], N, d,
+                              accumulate);
+}
+
 // ---- column sums --------------------------------------------------------------------------------
 // Grid (column blocks, row slabs).  Each thread owns kVec adjacent columns and walks its slab's rows;
 // partial sums land in ws[slab][cols]; reduce_parts_kernel adds the slabs in order.

@@ -276,7 +276,7 @@ pw_status pw_ctx_create(int device, void* hip_stream, pw_ctx** out) {
     delete c;
     return PW_ERR_DEVICE;
   }
-  if (gemm_init() != hipSuccess || attention_dma_init() != hipSuccess) {
+  if (gemm_init() != hipSuccess || attention_dma_init() != hipSuccess || layernorm_bwd_static_init(device) != hipSuccess) {
     (void)hipStreamDestroy(c->gate);
     (void)hipStreamDestroy(c->io);
     if (c->own_exec) (void)hipStreamDestroy(c->exec);

@@ -254,6 +254,15 @@ pw_status pw_op_layernorm_bwd(pw_ctx* c, int dtype, const void* dy, const float*
   PW_OP(c, launch_layernorm_bwd(c->exec, dtype, dy, x, g, mean, rstd, dres, dx, dx_lp, dg, db, dxsum, ws, N, d, accumulate));
 }
 int64_t pw_layernorm_bwd_ws_floats(int N, int d) { return layernorm_bwd_ws_floats(N, d); }
+pw_status pw_op_layernorm_bwd_noalloc(pw_ctx* c, int dtype, const void* dy, const float* x, const float* g, const float* mean,
+                                      const float* rstd, const float* dres, float* dx, void* dx_lp, float* dg, float* db,
+                                      float* dxsum, int N, int d, int accumulate) {
+  if (!c) return PW_ERR_INVALID;
+  if (N >= 0 && d > 0 && layernorm_bwd_ws_floats(N, d) > layernorm_bwd_static_max_ws_floats())
+    return fail(c, PW_ERR_UNSUPPORTED, "N = %d rows of d = %d columns need %lld floats of block sums, the library's fixed array holds %lld",
+                N, d, (long long)layernorm_bwd_ws_floats(N, d), (long long)layernorm_bwd_static_max_ws_floats());
+  PW_OP(c, launch_layernorm_bwd_static(c->exec, c->device, dtype, dy, x, g, mean, rstd, dres, dx, dx_lp, dg, db, dxsum, N, d, accumulate));
+}
 pw_status pw_op_attention_fwd(pw_ctx* c, int dtype, const void* qkv, void* o, float* lse, int B, int T, int H, int hd) {
   PW_OP(c, launch_attention_fwd(c->exec, dtype, qkv, o, lse, B, T, H, hd));
 }
