@@ -297,6 +297,14 @@ typedef struct {
   int32_t has_embed;     /* 0 for a pipeline stage fed with activations */
   int32_t has_head;      /* 0 for a pipeline stage returning activations */
   int32_t n_microbatch;  /* activation slots kept for a GPipe-like fwd-all / bwd-all schedule */
+  int32_t fused_update;  /* 1 (full LM, bf16, Adam): every weight whose gradient is one full-tile GEMM is updated by
+                            Adam inside that GEMM's epilogue - 26 instead of 30 bytes of optimizer traffic per
+                            parameter.  Those gradients are never stored: pw_model_export of PW_GRADS returns
+                            PW_ERR_UNSUPPORTED for them (their Adam moments are there).  0: one optimizer launch */
+  int32_t fused_head_loss; /* 1 (full LM, bf16, head on full tiles): the LM-head GEMM is fused with the softmax
+                            cross-entropy - logits are never stored; a first pass over the product keeps softmax
+                            statistics only, a second writes the gradient of the logits in bf16 once.  0: logits are
+                            stored and the loss kernel turns them into their gradient in place */
 } pw_lm_config;
 
 /* Allocates parameters (zero), gradients, optimiser state and every activation buffer of the step
@@ -364,8 +372,38 @@ typedef enum {
   PW_EPI_BIAS = 1,           /* C = acc + bias[n] */
   PW_EPI_BIAS_RESIDUAL = 2,  /* C(f32) = aux(f32)[m,n] + acc + bias[n] */
   PW_EPI_BIAS_GELU = 3,      /* C = u = acc + bias[n];  C2 = gelu(u) */
-  PW_EPI_GELU_BWD = 4        /* C = acc * gelu'(aux[m,n]),  aux in the activation dtype */
+  PW_EPI_GELU_BWD = 4,       /* C = acc * gelu'(aux[m,n]),  aux in the activation dtype */
+  PW_EPI_ADAM = 5,           /* acc is the gradient of a weight: Adam updates args->adam's w, m, v in the epilogue; the
+                                gradient goes to C only if C is non-null (fp32).  bf16, both operands k-major, full
+                                256 x 256 tiles (at least 150 of them, or any number in a shared group launch) */
+  PW_EPI_XENT_STATS = 6,     /* acc is a tile of logits (rows: token positions, columns: vocabulary): only softmax
+                                statistics leave the kernel (args->xent); C unused.  bf16, A row-major, B k-major,
+                                at least 150 full tiles */
+  PW_EPI_XENT_GRAD = 7       /* the same product: C (bf16) = (exp(acc - lse[row]) - [column == target]) * inv_n */
 } pw_epilogue;
+
+/* Adam in a weight-gradient epilogue: w, m, v (fp32 device arrays) and w_bf16 (optional bf16 copy of w) are laid out
+ * like the product, [M, N] with leading dimension ldc; t >= 1 is the step number of the bias correction. */
+typedef struct {
+  float* w;
+  float* m;
+  float* v;
+  void* w_bf16;
+  float lr, beta1, beta2, eps;
+  int32_t t;
+} pw_adam_epilogue;
+/* Loss epilogues of the LM head (Section 5.3: "a softmax layer at the end"): row r = b*T + t of the product has the
+ * target tokens[b*(T+1) + t + 1] (device, int32 [B, T+1]).  PW_EPI_XENT_STATS writes part[r][N/64][2] = (max, sum of
+ * exp(z - max)) of every 64-column group of row r and zt[r] = the target's logit; pw_op_xent_from_stats turns them
+ * into lse[r] and the loss.  PW_EPI_XENT_GRAD reads lse[r]; inv_n = 1 / (number of rows). */
+typedef struct {
+  const int32_t* tokens;
+  int32_t T;
+  float* part;
+  float* zt;
+  const float* lse;
+  float inv_n;
+} pw_xent_epilogue;
 
 typedef struct {
   int32_t dtype;             /* operand element type (A and B) */
@@ -386,6 +424,8 @@ typedef struct {
                                 Served only where it is free: bf16, both operands k-major, M, N multiples of 256, K of
                                 64, fp32 PW_EPI_STORE output and at least 150 tiles of 256 x 256 (alone or as a pair);
                                 PW_ERR_DEVICE otherwise.  Null: not wanted. */
+  const pw_adam_epilogue* adam;  /* host pointer, read during the call; PW_EPI_ADAM only, else null */
+  const pw_xent_epilogue* xent;  /* host pointer, read during the call; PW_EPI_XENT_* only, else null */
 } pw_gemm_args;
 
 /* C[M,N] = op(A)[M,K] . op(B)[K,N] with fp32 accumulation and a fused epilogue.  bf16 operands run on
@@ -465,6 +505,10 @@ pw_status pw_op_mha_bwd(pw_ctx* ctx, const pw_mha_args* args, const void* o, con
  * z is overwritten by dz = (softmax(z) - onehot)/N; loss: one fp32; row_loss: fp32 workspace [N]. */
 pw_status pw_op_softmax_xent(pw_ctx* ctx, int dtype, void* z, const int32_t* tokens, float* loss, float* row_loss,
                              int B, int T, int V);
+/* From what a PW_EPI_XENT_STATS GEMM left: lse[r] = log sum exp of row r over its `groups` 64-column groups,
+ * row_loss[r] = lse[r] - zt[r] (both fp32 [N], overwritten), loss = their mean. */
+pw_status pw_op_xent_from_stats(pw_ctx* ctx, const float* part, const float* zt, float* lse, float* row_loss,
+                                float* loss, int N, int groups);
 /* out[c] (=|+=) sum_r in[r, c]; `in` is [rows, cols] in `dtype`; ws: fp32 workspace of
  * pw_colsum_ws_floats(rows, cols) floats. */
 pw_status pw_op_colsum(pw_ctx* ctx, int dtype, const void* in, float* out, float* ws, int64_t rows, int64_t cols,

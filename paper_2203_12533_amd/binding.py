@@ -26,7 +26,8 @@ PW_SCHED_FIFO, PW_SCHED_PROPORTIONAL = 0, 1
 PW_FN_LM_TRAIN_STEP, PW_FN_STAGE_FWD, PW_FN_STAGE_BWD, PW_FN_ENCDEC_TRAIN_STEP = 16, 17, 18, 19
 PW_STREAM, PW_GRAPH, PW_SEQUENTIAL = 0, 1, 2
 PW_PARAMS, PW_GRADS, PW_ADAM_M, PW_ADAM_V = 0, 1, 2, 3
-PW_EPI_STORE, PW_EPI_BIAS, PW_EPI_BIAS_RESIDUAL, PW_EPI_BIAS_GELU, PW_EPI_GELU_BWD = range(5)
+PW_EPI_STORE, PW_EPI_BIAS, PW_EPI_BIAS_RESIDUAL, PW_EPI_BIAS_GELU, PW_EPI_GELU_BWD, PW_EPI_ADAM, PW_EPI_XENT_STATS, \
+    PW_EPI_XENT_GRAD = range(8)
 
 
 class TensorSpec(C.Structure):
@@ -47,7 +48,17 @@ class LMConfigC(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layer", "d_model", "n_head", "d_ff", "vocab", "seq", "batch", "bf16",
                                          "optimizer")] + \
                [(n, C.c_float) for n in ("lr", "beta1", "beta2", "eps")] + \
-               [(n, C.c_int32) for n in ("has_embed", "has_head", "n_microbatch")]
+               [(n, C.c_int32) for n in ("has_embed", "has_head", "n_microbatch", "fused_update", "fused_head_loss")]
+
+
+class AdamEpilogue(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p), ("w_bf16", C.c_void_p),
+                ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("t", C.c_int32)]
+
+
+class XentEpilogue(C.Structure):
+    _fields_ = [("tokens", C.c_void_p), ("T", C.c_int32), ("part", C.c_void_p), ("zt", C.c_void_p),
+                ("lse", C.c_void_p), ("inv_n", C.c_float)]
 
 
 class GemmArgs(C.Structure):
@@ -56,7 +67,8 @@ class GemmArgs(C.Structure):
                 ("lda", C.c_int64), ("ldb", C.c_int64), ("ldc", C.c_int64),
                 ("epilogue", C.c_int32), ("out_dtype", C.c_int32), ("accumulate", C.c_int32),
                 ("A", C.c_void_p), ("B", C.c_void_p), ("bias", C.c_void_p), ("aux", C.c_void_p),
-                ("C", C.c_void_p), ("C2", C.c_void_p), ("b_colsum", C.c_void_p)]
+                ("C", C.c_void_p), ("C2", C.c_void_p), ("b_colsum", C.c_void_p),
+                ("adam", C.POINTER(AdamEpilogue)), ("xent", C.POINTER(XentEpilogue))]
 
 
 class EncDecConfigC(C.Structure):
@@ -161,6 +173,7 @@ _SIGS = {
     "pw_op_mha_fwd": (C.c_int, [C.c_void_p] * 5),
     "pw_op_mha_bwd": (C.c_int, [C.c_void_p] * 8 + [C.c_int64, C.c_void_p, C.c_void_p, C.c_int64]),
     "pw_op_softmax_xent": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 4 + [C.c_int] * 3),
+    "pw_op_xent_from_stats": (C.c_int, [C.c_void_p] * 6 + [C.c_int] * 2),
     "pw_op_colsum": (C.c_int, [C.c_void_p, C.c_int] + [C.c_void_p] * 3 + [C.c_int64] * 2 + [C.c_int]),
     "pw_colsum_ws_floats": (C.c_int64, [C.c_int64, C.c_int64]),
     "pw_op_sgd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float]),
@@ -378,8 +391,8 @@ class Context:
         return n.value, ms.value, fl.value
 
     # -- model
-    def model(self, cfg) -> "Model":
-        return Model(self, cfg)
+    def model(self, cfg, fused_update: bool = False, fused_head_loss: bool = False) -> "Model":
+        return Model(self, cfg, fused_update, fused_head_loss)
 
     def encdec(self, cfg) -> "EncDec":
         return EncDec(self, cfg)
@@ -389,9 +402,7 @@ class Context:
         self._check(getattr(lib(), "pw_op_" + name)(self._h, *args))
 
     def gemm(self, **kw):
-        a = GemmArgs()
-        for k, v in kw.items():
-            setattr(a, k, v)
+        a = _gemm_args(kw)
         self._check(lib().pw_op_gemm(self._h, C.byref(a)))
 
     def mha_fwd(self, args: "MhaArgs", o: int, lse: int, o_lo: int = 0):
@@ -403,17 +414,26 @@ class Context:
 
     def gemm_group(self, kws: list):
         arr = (GemmArgs * len(kws))()
+        keep = []
         for a, kw in zip(arr, kws):
-            for k, v in kw.items():
-                setattr(a, k, v)
+            keep.append(_gemm_args(kw, a))
         self._check(lib().pw_op_gemm_group(self._h, arr, len(kws)))
 
     def gemm_pair(self, kw0: dict, kw1: dict):
-        a0, a1 = GemmArgs(), GemmArgs()
-        for a, kw in ((a0, kw0), (a1, kw1)):
-            for k, v in kw.items():
-                setattr(a, k, v)
+        a0, a1 = _gemm_args(kw0), _gemm_args(kw1)
         self._check(lib().pw_op_gemm_pair(self._h, C.byref(a0), C.byref(a1)))
+
+
+def _gemm_args(kw: dict, a: "GemmArgs | None" = None) -> "GemmArgs":
+    """Fills a pw_gemm_args from keywords; adam= / xent= take an AdamEpilogue / XentEpilogue, which the returned
+    structure keeps alive (ctypes holds the pointee of a pointer field set from a structure)."""
+    a = GemmArgs() if a is None else a
+    for k, v in kw.items():
+        if k in ("adam", "xent"):
+            setattr(a, k, C.pointer(v))
+        else:
+            setattr(a, k, v)
+    return a
 
 
 class Node(C.Structure):
@@ -514,11 +534,12 @@ class Scheduler:
             self._h = None
 
 
-def lm_config_c(cfg) -> LMConfigC:
-    """From the generator module's LMConfig (or any object with the same fields)."""
+def lm_config_c(cfg, fused_update: bool = False, fused_head_loss: bool = False) -> LMConfigC:
+    """From the generator module's LMConfig (or any object with the same fields); the two fusion switches are
+    choices of the GPU path, not part of the workload."""
     return LMConfigC(cfg.n_layer, cfg.d_model, cfg.n_head, cfg.d_ff, cfg.vocab, cfg.seq, cfg.batch, int(cfg.bf16),
                      {"sgd": 1, "adam": 2}[cfg.optimizer], cfg.lr, cfg.beta1, cfg.beta2, cfg.eps,
-                     int(cfg.has_embed), int(cfg.has_head), cfg.n_microbatch)
+                     int(cfg.has_embed), int(cfg.has_head), cfg.n_microbatch, int(fused_update), int(fused_head_loss))
 
 
 def step_flops(cfg) -> float:
@@ -613,10 +634,10 @@ class Model(_ParamModel):
     """pw_model: parameters, optimiser state and the static activation plan of one LM (or pipeline stage)."""
     _prefix = "pw_model"
 
-    def __init__(self, ctx: Context, cfg):
+    def __init__(self, ctx: Context, cfg, fused_update: bool = False, fused_head_loss: bool = False):
         self.ctx, self.cfg = ctx, cfg
         self._h = C.c_void_p()
-        c = lm_config_c(cfg)
+        c = lm_config_c(cfg, fused_update, fused_head_loss)
         ctx._check(lib().pw_model_create(ctx.handle, C.byref(c), C.byref(self._h)))
         ctx._models.append(self)
         self._read_param_table()

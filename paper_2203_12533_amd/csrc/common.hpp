@@ -74,4 +74,12 @@ __device__ __forceinline__ float gelu_grad_f(float u) {
   return __builtin_fmaf(__builtin_fmaf(-h, g.s, h), g.dz2, g.s);
 }
 
+// One Adam update with bias corrections inv_c1 = 1 / (1 - beta1^t), inv_c2 = 1 / (1 - beta2^t).
+__device__ __forceinline__ void adam_one(float& w, float& m, float& v, float g, float lr, float b1, float b2,
+                                         float eps, float inv_c1, float inv_c2) {
+  m = b1 * m + (1.f - b1) * g;
+  v = b2 * v + (1.f - b2) * g * g;
+  w -= lr * (m * inv_c1) / (sqrtf(v * inv_c2) + eps);
+}
+
 }  // namespace pw

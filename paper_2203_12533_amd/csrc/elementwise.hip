@@ -166,12 +166,6 @@ hipError_t launch_sgd(hipStream_t s, float* w, const float* g, int64_t n, float 
 // Adam over a flat fp32 arena: 16 B read of g, w, m, v and 16 B write of w, m, v per 4 elements, plus the
 // bf16 compute copy (8 B): 30 B per parameter, all fully coalesced.  The step number comes from t_dev
 // when non-null (so that a captured graph can be replayed across steps), else from t.
-__device__ __forceinline__ void adam_one(float& w, float& m, float& v, float g, float lr, float b1, float b2,
-                                         float eps, float inv_c1, float inv_c2) {
-  m = b1 * m + (1.f - b1) * g;
-  v = b2 * v + (1.f - b2) * g * g;
-  w -= lr * (m * inv_c1) / (sqrtf(v * inv_c2) + eps);
-}
 __global__ void adam_kernel(float* __restrict__ w, float* __restrict__ m, float* __restrict__ v,
                             const float* __restrict__ g, bf16* __restrict__ wlp, int64_t n, float lr, float b1,
                             float b2, float eps, int t, const int* __restrict__ t_dev) {
@@ -221,6 +215,20 @@ __global__ void increment_kernel(int* c) {
 hipError_t launch_increment(hipStream_t s, int* counter) {
   if (!counter) return hipErrorInvalidValue;
   increment_kernel<<<1, 64, 0, s>>>(counter);
+  return hipGetLastError();
+}
+
+__global__ void adam_step_kernel(int* state, int set_to, float b1, float b2) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const int t = set_to > 0 ? set_to : state[0] + 1;
+  state[0] = t;
+  float* c = reinterpret_cast<float*>(state);
+  c[4] = 1.f / (1.f - powf(b1, (float)t));     // the expressions of adam_kernel: same bits
+  c[5] = 1.f / (1.f - powf(b2, (float)t));
+}
+hipError_t launch_adam_step(hipStream_t s, int* state, int set_to, float b1, float b2) {
+  if (!state || set_to < 0) return hipErrorInvalidValue;
+  adam_step_kernel<<<1, 64, 0, s>>>(state, set_to, b1, b2);
   return hipGetLastError();
 }
 

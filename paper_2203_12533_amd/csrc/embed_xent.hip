@@ -232,6 +232,41 @@ __global__ void mean_rows_kernel(const float* __restrict__ row_loss, float* __re
   }
 }
 
+// Loss from the per-group statistics that the LM-head GEMM's kEpiXentStats epilogue leaves (the logits themselves
+// were never stored): one wave per row merges the (max, sum exp(z - max)) pairs of the row's 64-column groups.
+__global__ __launch_bounds__(256) void xent_from_stats_kernel(const float* __restrict__ part, const float* __restrict__ zt,
+                                                               float* __restrict__ lse, float* __restrict__ row_loss,
+                                                               int N, int groups) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= N) return;   // whole waves leave together
+  const float2* pr = reinterpret_cast<const float2*>(part) + (size_t)r * groups;
+  float m = -INFINITY, l = 0.f;
+  for (int g = lane; g < groups; g += 64) {
+    const float2 p = pr[g];
+    const float nm = fmaxf(m, p.x);
+    l = l * __expf(m - nm) + p.y * __expf(p.x - nm);
+    m = nm;
+  }
+  const float gm = wave_max(m);
+  const float gl = wave_sum(l * __expf(m - gm));   // lanes without a group: l = 0, exp(-inf) = 0
+  if (lane == 0) {
+    const float v = gm + logf(gl);
+    lse[r] = v;
+    row_loss[r] = v - zt[r];
+  }
+}
+
+hipError_t launch_xent_from_stats(hipStream_t s, const float* part, const float* zt, float* lse, float* row_loss,
+                                  float* loss, int N, int groups) {
+  if (!part || !zt || !lse || !row_loss || !loss || N <= 0 || groups <= 0 || ((uintptr_t)part & 7)) return hipErrorInvalidValue;
+  xent_from_stats_kernel<<<(N + 3) / 4, 256, 0, s>>>(part, zt, lse, row_loss, N, groups);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  mean_rows_kernel<<<1, 256, 0, s>>>(row_loss, loss, N);
+  return hipGetLastError();
+}
+
 hipError_t launch_softmax_xent(hipStream_t s, int dtype, void* z, const int32_t* tokens, float* loss, float* row_loss,
                                int B, int T, int V) {
   if (!z || !tokens || !loss || !row_loss || B <= 0 || T <= 0 || V <= 0) return hipErrorInvalidValue;

@@ -295,7 +295,7 @@ hipError_t encdec_create(const pw_encdec_config& cfg, hipStream_t stream, EncDec
   m->stream = stream;
   m->bf16 = cfg.bf16 ? 1 : 0;
   build_param_table(cfg, m->params, m->total);
-  hipError_t e = model_state_alloc(m, cfg.optimizer, err);
+  hipError_t e = model_state_alloc(m, OptimizerConfig{cfg.optimizer, cfg.lr, cfg.beta1, cfg.beta2, cfg.eps}, err);
   if (e != hipSuccess) {
     delete m;
     return e;

@@ -21,6 +21,7 @@
 // fp32 path: a plain LDS-tiled ALU kernel; it serves the small fp32 configuration only.
 #include "common.hpp"
 #include <algorithm>
+#include <cmath>
 
 #include "gemm_common.hpp"
 #include "kernels.hpp"
@@ -383,8 +384,20 @@ hipError_t launch_gemm(hipStream_t s, const GemmArgs& a) {
 // Argument checks shared by every path; *empty is set when there is nothing to compute.
 static hipError_t check_gemm_args(const GemmArgs& a, bool* empty) {
   *empty = false;
-  if (!a.A || !a.B || !a.C || a.M < 0 || a.N < 0 || a.K < 0) return hipErrorInvalidValue;
-  if (a.epilogue < kEpiStore || a.epilogue > kEpiGeluBwd) return hipErrorInvalidValue;
+  const bool no_c = a.epilogue == kEpiAdam || a.epilogue == kEpiXentStats;   // C optional / unused there
+  if (!a.A || !a.B || (!a.C && !no_c) || a.M < 0 || a.N < 0 || a.K < 0) return hipErrorInvalidValue;
+  if (a.epilogue < kEpiStore || a.epilogue > kEpiXentGrad) return hipErrorInvalidValue;
+  if (a.epilogue == kEpiAdam) {
+    const AdamEpi& d = a.adam;
+    if (!d.w || !d.m || !d.v || (!d.c_dev && d.t < 1) || a.out_dtype != kF32 || a.accumulate) return hipErrorInvalidValue;
+    if (((uintptr_t)d.w | (uintptr_t)d.m | (uintptr_t)d.v | (uintptr_t)d.w_bf16 | (uintptr_t)d.c_dev) & 15) return hipErrorInvalidValue;
+  }
+  if (a.epilogue == kEpiXentStats || a.epilogue == kEpiXentGrad) {
+    const XentEpi& x = a.xent;
+    if (!x.tokens || x.T < 1 || a.M % x.T || a.accumulate) return hipErrorInvalidValue;
+    if (a.epilogue == kEpiXentStats && (!x.part || !x.zt || ((uintptr_t)x.part & 7))) return hipErrorInvalidValue;
+    if (a.epilogue == kEpiXentGrad && (!x.lse || a.out_dtype != kBF16)) return hipErrorInvalidValue;
+  }
   if (a.lda < (a.a_kmajor ? a.M : a.K) || a.ldb < (a.b_kmajor ? a.N : a.K) || a.ldc < a.N) return hipErrorInvalidValue;
   if ((a.epilogue == kEpiBiasResidual || a.epilogue == kEpiGeluBwd) && !a.aux) return hipErrorInvalidValue;
   if (a.epilogue == kEpiBiasGelu && !a.C2) return hipErrorInvalidValue;
@@ -419,6 +432,15 @@ static EpiParams epi_of(const GemmArgs& a) {
   e.C = a.C;
   e.C2 = a.C2;
   e.ldc = a.ldc;
+  e.ad_w = a.adam.w; e.ad_m = a.adam.m; e.ad_v = a.adam.v; e.ad_wlp = (bf16*)a.adam.w_bf16; e.ad_c = a.adam.c_dev;
+  e.ad_lr = a.adam.lr; e.ad_b1 = a.adam.b1; e.ad_b2 = a.adam.b2; e.ad_eps = a.adam.eps;
+  e.ad_ic1 = e.ad_ic2 = 0.f;
+  if (a.epilogue == kEpiAdam && !a.adam.c_dev) {   // the expressions of the Adam kernel
+    e.ad_ic1 = 1.f / (1.f - powf(a.adam.b1, (float)a.adam.t));
+    e.ad_ic2 = 1.f / (1.f - powf(a.adam.b2, (float)a.adam.t));
+  }
+  e.xe_tokens = a.xent.tokens; e.xe_part = a.xent.part; e.xe_zt = a.xent.zt; e.xe_lse = a.xent.lse;
+  e.xe_inv_n = a.xent.inv_n; e.xe_T = a.xent.T; e.xe_V = (int)a.N; e.xe_groups = (int)(a.N / 64);
   return e;
 }
 
@@ -440,9 +462,20 @@ static bool ring_eligible(const GemmArgs& a) {
   return g_use_ring && a.dtype == kBF16 && gemm_ring_supported(a.M, a.N, a.K);
 }
 
+// The Adam epilogue lives in the ring kernel's weight-gradient instantiation (full 256 x 256 tiles, both operands
+// k-major, fp32 product), alone when the problem fills most of the chip or as a member of a shared launch.
+bool gemm_adam_fusable(const GemmArgs& a, bool grouped) {
+  return ring_eligible(a) && a.a_kmajor && a.b_kmajor && a.out_dtype == kF32 && !a.accumulate &&
+         (grouped || (a.M / 256) * (a.N / 256) >= 150);
+}
+// The loss epilogues live in the ring kernel's forward-layout instantiation.
+bool gemm_xent_fusable(const GemmArgs& a) {
+  return ring_eligible(a) && !a.a_kmajor && a.b_kmajor && (a.M / 256) * (a.N / 256) >= 150 && a.N <= (1 << 24);
+}
+
 bool gemm_colsum_fusable(const GemmArgs& a, bool paired) {
-  return ring_eligible(a) && a.a_kmajor && a.b_kmajor && a.out_dtype == kF32 && a.epilogue == kEpiStore &&
-         (paired || (a.M / 256) * (a.N / 256) >= 150);
+  return ring_eligible(a) && a.a_kmajor && a.b_kmajor && a.out_dtype == kF32 &&
+         (a.epilogue == kEpiStore || a.epilogue == kEpiAdam) && (paired || (a.M / 256) * (a.N / 256) >= 150);
 }
 
 static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a) {
@@ -450,6 +483,10 @@ static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a) {
   hipError_t err = check_gemm_args(a, &empty);
   if (err != hipSuccess || empty) return err;
   if (a.b_colsum && (!gemm_colsum_fusable(a, false) || ((uintptr_t)a.b_colsum & 3))) return hipErrorInvalidValue;
+  if (a.epilogue == kEpiAdam)
+    return gemm_adam_fusable(a, false) ? launch_gemm_ring(s, bf16_params_of(a, 256), true, true) : hipErrorInvalidValue;
+  if (a.epilogue == kEpiXentStats || a.epilogue == kEpiXentGrad)
+    return gemm_xent_fusable(a) ? launch_gemm_ring(s, bf16_params_of(a, 256), false, true) : hipErrorInvalidValue;
 
   if (a.dtype == kF32) {
     GemmF32Params p;
@@ -535,8 +572,12 @@ hipError_t launch_gemm_group(hipStream_t s, const GemmArgs* a, int n) {
     any_empty = any_empty || empty[i];
   }
   const bool shared = !any_empty && gemm_group_shares_launch(a, n);
-  for (int i = 0; i < n; ++i)
-    if (a[i].b_colsum && !gemm_colsum_fusable(a[i], shared)) return hipErrorInvalidValue;   // checked before anything is launched
+  for (int i = 0; i < n; ++i) {   // checked before anything is launched
+    if (a[i].b_colsum && !gemm_colsum_fusable(a[i], shared)) return hipErrorInvalidValue;
+    if (a[i].epilogue == kEpiAdam && !gemm_adam_fusable(a[i], shared)) return hipErrorInvalidValue;
+    if (shared && (a[i].epilogue == kEpiAdam) != (a[0].epilogue == kEpiAdam)) return hipErrorInvalidValue;
+    if (a[i].epilogue == kEpiXentStats || a[i].epilogue == kEpiXentGrad) return hipErrorInvalidValue;
+  }
   if (!shared) {
     for (int i = 0; i < n; ++i) {
       const hipError_t err = launch_gemm(s, a[i]);

@@ -12,6 +12,19 @@ struct EpiParams {
   void* C;
   void* C2;
   int64_t ldc;
+  // kEpiAdam (see AdamEpi): arrays laid out like C; ad_c: device pointer to the two bias corrections, or null
+  // (then ad_ic1, ad_ic2 hold them)
+  float *ad_w, *ad_m, *ad_v;
+  bf16* ad_wlp;
+  const float* ad_c;
+  float ad_lr, ad_b1, ad_b2, ad_eps, ad_ic1, ad_ic2;
+  // kEpiXentStats / kEpiXentGrad (see XentEpi); xe_groups = N / 64
+  const int32_t* xe_tokens;
+  float* xe_part;
+  float* xe_zt;
+  const float* xe_lse;
+  float xe_inv_n;
+  int xe_T, xe_V, xe_groups;
 };
 
 __device__ __forceinline__ bool epi_has_bias(int mode) {
@@ -92,8 +105,11 @@ __device__ __forceinline__ void epilogue1(const EpiParams& e, int64_t m, int64_t
 // 32 bytes of fp32 output it accumulates into.  The staged epilogue fetches these a few row segments ahead of their
 // use, so that a wave has several such loads in flight instead of one round trip per row segment.
 struct EpiExtra { uint4 lo, hi; };
-enum { kExtraNone = 0, kExtraAuxBf16, kExtraAuxF32, kExtraOldC };
+enum { kExtraNone = 0, kExtraAuxBf16, kExtraAuxF32, kExtraOldC, kExtraAdam, kExtraXentStats, kExtraXentGrad };
 __device__ __forceinline__ int epi_extra_kind(const EpiParams& e) {
+  if (e.mode == kEpiAdam) return kExtraAdam;
+  if (e.mode == kEpiXentStats) return kExtraXentStats;
+  if (e.mode == kEpiXentGrad) return kExtraXentGrad;
   if (e.mode == kEpiBiasResidual) return kExtraAuxF32;
   if (e.mode == kEpiGeluBwd) return kExtraAuxBf16;
   return (!e.out_bf16 && e.accumulate) ? kExtraOldC : kExtraNone;
@@ -166,6 +182,76 @@ __device__ __forceinline__ void epilogue8(const EpiParams& e, int64_t m, int64_t
   }
 }
 
+// ---- epilogues of the dedicated kernel instantiations ---------------------------------------------------------
+// Adam on 8 consecutive elements at offset off of w, m, v (and the bf16 copy): g[8] is the gradient the GEMM just
+// produced, xw / xm / xv what was fetched from w, m, v (32 bytes each).  26 bytes of traffic per parameter - the
+// gradient itself never reaches memory unless e.C asks for it.
+__device__ __forceinline__ void unpack8(const EpiExtra& x, float* o) {
+  o[0] = __uint_as_float(x.lo.x); o[1] = __uint_as_float(x.lo.y); o[2] = __uint_as_float(x.lo.z); o[3] = __uint_as_float(x.lo.w);
+  o[4] = __uint_as_float(x.hi.x); o[5] = __uint_as_float(x.hi.y); o[6] = __uint_as_float(x.hi.z); o[7] = __uint_as_float(x.hi.w);
+}
+__device__ __forceinline__ void store8(float* p, const float* o) {
+  *reinterpret_cast<float4*>(p) = make_float4(o[0], o[1], o[2], o[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(o[4], o[5], o[6], o[7]);
+}
+__device__ __forceinline__ void epilogue8_adam(const EpiParams& e, int64_t off, const float* g, const EpiExtra& xw,
+                                               const EpiExtra& xm, const EpiExtra& xv, float ic1, float ic2) {
+  float w[8], m[8], v[8];
+  unpack8(xw, w);
+  unpack8(xm, m);
+  unpack8(xv, v);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) adam_one(w[i], m[i], v[i], g[i], e.ad_lr, e.ad_b1, e.ad_b2, e.ad_eps, ic1, ic2);
+  store8(e.ad_w + off, w);
+  store8(e.ad_m + off, m);
+  store8(e.ad_v + off, v);
+  if (e.ad_wlp) {
+    bf16x8 o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (bf16)w[i];
+    *reinterpret_cast<bf16x8*>(e.ad_wlp + off) = o;
+  }
+  if (e.C) store8(reinterpret_cast<float*>(e.C) + off, g);
+}
+
+// Target token of row r = b*T + t of the logits: tokens[b*(T+1) + t + 1], clamped into [0, V) as everywhere.
+__device__ __forceinline__ int xent_target(const EpiParams& e, int64_t r) {
+  const int b = (int)(r / e.xe_T), t = (int)(r - (int64_t)b * e.xe_T);
+  const int id = e.xe_tokens[(size_t)b * (e.xe_T + 1) + t + 1];
+  return id < 0 ? 0 : (id >= e.xe_V ? e.xe_V - 1 : id);
+}
+// Softmax statistics of 8 consecutive logits z[8] of row m, columns n..n+7; the 8 lanes that hold the 64 columns of
+// one row segment (lane & 7 = 0..7) combine theirs, lane 0 of them writes (max, sum exp(z - max)) of the group.
+__device__ __forceinline__ void epilogue8_xent_stats(const EpiParams& e, int64_t m, int64_t n, const float* z, int c8) {
+  float mx = z[0];
+#pragma unroll
+  for (int i = 1; i < 8; ++i) mx = fmaxf(mx, z[i]);
+#pragma unroll
+  for (int o = 1; o < 8; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) sum += __expf(z[i] - mx);
+#pragma unroll
+  for (int o = 1; o < 8; o <<= 1) sum += __shfl_xor(sum, o, 64);
+  if (c8 == 0) *reinterpret_cast<float2*>(e.xe_part + 2 * (m * e.xe_groups + (n >> 6))) = make_float2(mx, sum);
+  const int tgt = xent_target(e, m);
+  if (tgt >= n && tgt < n + 8) {
+    float zt = z[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) zt = (tgt - (int)n == i) ? z[i] : zt;
+    e.xe_zt[m] = zt;
+  }
+}
+// (softmax - onehot) / N of 8 consecutive logits; x.lo.x holds lse[m], x.lo.y the target id (fetched ahead).
+__device__ __forceinline__ void epilogue8_xent_grad(const EpiParams& e, int64_t m, int64_t n, const float* z, const EpiExtra& x) {
+  const float lse = __uint_as_float(x.lo.x);
+  const int tgt = (int)x.lo.y;
+  bf16x8 o;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = (bf16)((__expf(z[i] - lse) - ((int)n + i == tgt ? 1.f : 0.f)) * e.xe_inv_n);
+  *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(e.C) + m * e.ldc + n) = o;
+}
+
 // Workgroup id -> output tile, XCD-aware (see file header).
 __device__ __forceinline__ void tile_of_block(int pid, int nblk, int tiles_m, int tiles_n, int& tm, int& tn) {
   constexpr int kXcd = 8, kGroup = 8;
@@ -231,14 +317,30 @@ __device__ __forceinline__ void gemm_epilogue_staged_kind(bf16* smem, Acc& acc, 
                                                           int64_t mw0, int64_t nw0, int wave, int lane) {
   static_assert(FN % 2 == 0, "epilogue staging works on 64-column halves of the wave tile");
   constexpr int kLdS = 64 + 4;   // floats; 272-byte rows keep the 16-byte LDS accesses conflict-free
-  constexpr bool kAhead = KIND != kExtraNone;
+  static_assert(!EDGE || KIND <= kExtraOldC, "the dedicated epilogues exist for full tiles only");
+  constexpr bool kAhead = KIND != kExtraNone && KIND != kExtraXentStats;
   const int r8 = lane >> 3, c8 = lane & 7;
   const void* const extra_src = epi_extra_src(p.epi, KIND);
   const int64_t M = p.M, N = p.N, ldc = p.epi.ldc;
-  // Row segment `it` of 32-row block i, column half h: the fetch of what this lane needs there.
-  auto fetch = [=](int h, int i, int it, EpiExtra& x) {
+  float ic1 = 0.f, ic2 = 0.f;   // Adam's bias corrections
+  if (KIND == kExtraAdam) {
+    ic1 = p.epi.ad_c ? p.epi.ad_c[0] : p.epi.ad_ic1;
+    ic2 = p.epi.ad_c ? p.epi.ad_c[1] : p.epi.ad_ic2;
+  }
+  // Row segment `it` of 32-row block i, column half h: the fetch of what this lane needs there (x2, x3: the second
+  // and third array of the Adam epilogue).
+  auto fetch = [&](int h, int i, int it, EpiExtra& x, EpiExtra& x2, EpiExtra& x3) {
     const int64_t m = mw0 + i * 32 + it * 8 + r8, n = nw0 + h * 64 + c8 * 8;
-    if (!EDGE || (m < M && n + 7 < N)) epi_extra_load(KIND, extra_src, m * ldc + n, x);
+    if (KIND == kExtraAdam) {
+      epi_extra_load(kExtraAuxF32, p.epi.ad_w, m * ldc + n, x);
+      epi_extra_load(kExtraAuxF32, p.epi.ad_m, m * ldc + n, x2);
+      epi_extra_load(kExtraAuxF32, p.epi.ad_v, m * ldc + n, x3);
+    } else if (KIND == kExtraXentGrad) {
+      x.lo.x = __float_as_uint(p.epi.xe_lse[m]);
+      x.lo.y = (uint32_t)xent_target(p.epi, m);
+    } else if (!EDGE || (m < M && n + 7 < N)) {
+      epi_extra_load(KIND, extra_src, m * ldc + n, x);
+    }
   };
   // Between the staging writes and the row-wise reads of a wave's private slice.  With extras in flight a block
   // barrier would wait for them (and for the stores); a wave's LDS accesses execute in issue order, so keeping
@@ -254,10 +356,15 @@ __device__ __forceinline__ void gemm_epilogue_staged_kind(bf16* smem, Acc& acc, 
   };
   __syncthreads();   // every wave is done with the operand tiles
   float* stage = reinterpret_cast<float*>(smem) + wave * (32 * kLdS);
-  EpiExtra q[4] = {};   // extras of the four row segments of a 32-row block, fetched one block ahead
+  // Extras are fetched kSlots row segments ahead of their use: a whole 32-row block (four segments) where a segment
+  // needs 16 or 32 bytes per lane, two segments for Adam's 96 bytes (a block's worth would not fit the registers
+  // next to the accumulators still waiting to be parked).
+  constexpr int kSlots = KIND == kExtraAdam ? 2 : 4;
+  EpiExtra q[kSlots] = {};
+  EpiExtra q2[kSlots] = {}, q3[kSlots] = {};   // Adam only (dead otherwise)
   if (kAhead) {
 #pragma unroll
-    for (int it = 0; it < 4; ++it) fetch(0, 0, it, q[it]);
+    for (int it = 0; it < kSlots; ++it) fetch(0, 0, it, q[it], q2[it], q3[it]);
   }
 #pragma unroll
   for (int h = 0; h < FN / 2; ++h) {
@@ -267,16 +374,25 @@ __device__ __forceinline__ void gemm_epilogue_staged_kind(bf16* smem, Acc& acc, 
       sync();
       const bool wrap = i + 1 == FM;
       const int ni = wrap ? 0 : i + 1, nh = wrap ? h + 1 : h;
-      auto segment = [&](int it, EpiExtra& slot) {
+      auto segment = [&](int it, EpiExtra& slot, EpiExtra& slot2, EpiExtra& slot3) {
         const int row = it * 8 + r8;
         const float4 v0 = *reinterpret_cast<const float4*>(stage + row * kLdS + c8 * 8);
         const float4 v1 = *reinterpret_cast<const float4*>(stage + row * kLdS + c8 * 8 + 4);
         float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-        const EpiExtra x = slot;
-        if (kAhead && nh < FN / 2) fetch(nh, ni, it, slot);
+        const EpiExtra x = slot, x2 = slot2, x3 = slot3;
+        if (kAhead) {   // the segment kSlots further on takes over the slot
+          if (it + kSlots < 4) fetch(h, i, it + kSlots, slot, slot2, slot3);
+          else if (nh < FN / 2) fetch(nh, ni, it + kSlots - 4, slot, slot2, slot3);
+        }
         const int64_t m = mw0 + i * 32 + row;
         const int64_t n = nw0 + h * 64 + c8 * 8;
-        if (!EDGE || (m < M && n + 7 < N)) {
+        if (KIND == kExtraAdam) {
+          epilogue8_adam(p.epi, m * ldc + n, v, x, x2, x3, ic1, ic2);
+        } else if (KIND == kExtraXentStats) {
+          epilogue8_xent_stats(p.epi, m, n, v, c8);
+        } else if (KIND == kExtraXentGrad) {
+          epilogue8_xent_grad(p.epi, m, n, v, x);
+        } else if (!EDGE || (m < M && n + 7 < N)) {
           epilogue8(p.epi, m, n, v, KIND, x);
         } else if (m < M) {
           for (int e = 0; e < 8; ++e)
@@ -285,19 +401,31 @@ __device__ __forceinline__ void gemm_epilogue_staged_kind(bf16* smem, Acc& acc, 
       };
       if (kAhead) {   // unrolled: each segment has its own registers for what was fetched ahead
 #pragma unroll
-        for (int it = 0; it < 4; ++it) segment(it, q[it]);
+        for (int it = 0; it < 4; ++it) segment(it, q[it % kSlots], q2[it % kSlots], q3[it % kSlots]);
       } else {
 #pragma unroll 1
-        for (int it = 0; it < 4; ++it) segment(it, q[0]);
+        for (int it = 0; it < 4; ++it) segment(it, q[0], q2[0], q3[0]);
       }
       sync();
     }
   }
 }
 
-template <int FM, int FN, bool EDGE, typename Acc>
+// EPISET: which epilogues the instantiation carries: 0 the general ones (store, bias, residual, GELU, GELU', add-to);
+// 1 the two of the LM head fused with the loss (statistics; gradient of the logits); 2 Adam on the product.  The
+// dedicated sets have kernel instantiations of their own so that the general kernels do not grow.
+constexpr int kEpiSetGeneral = 0, kEpiSetXent = 1, kEpiSetAdam = 2;
+template <int FM, int FN, bool EDGE, int EPISET = kEpiSetGeneral, typename Acc>
 __device__ __forceinline__ void gemm_epilogue_staged(bf16* smem, Acc& acc, const GemmBf16Params& p,
                                                      int64_t mw0, int64_t nw0, int wave, int lane) {
+  if constexpr (EPISET == kEpiSetAdam) {
+    gemm_epilogue_staged_kind<FM, FN, EDGE, kExtraAdam>(smem, acc, p, mw0, nw0, wave, lane);
+    return;
+  } else if constexpr (EPISET == kEpiSetXent) {
+    if (p.epi.mode == kEpiXentStats) gemm_epilogue_staged_kind<FM, FN, EDGE, kExtraXentStats>(smem, acc, p, mw0, nw0, wave, lane);
+    else gemm_epilogue_staged_kind<FM, FN, EDGE, kExtraXentGrad>(smem, acc, p, mw0, nw0, wave, lane);
+    return;
+  }
   switch (epi_extra_kind(p.epi)) {   // uniform over the launch
     case kExtraAuxBf16: gemm_epilogue_staged_kind<FM, FN, EDGE, kExtraAuxBf16>(smem, acc, p, mw0, nw0, wave, lane); break;
     case kExtraAuxF32: gemm_epilogue_staged_kind<FM, FN, EDGE, kExtraAuxF32>(smem, acc, p, mw0, nw0, wave, lane); break;

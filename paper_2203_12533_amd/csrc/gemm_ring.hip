@@ -97,7 +97,7 @@ __device__ __forceinline__ bf16x8 read_fragment(const bf16* lds_tile, int frag_r
 // workgroup among the problem's own.  Waves form a 2 x NW grid: NW = 4 -> 8 waves with (TM / 2) x 64 wave tiles.  The products are 16 x 16 x 32 MFMAs: on
 // operands with random mantissas the chip runs into its board power limit, and per flop that shape draws less
 // than the 32 x 32 x 16 one (same loop, same LDS bytes: 2.06 against 1.82 PFLOP/s sustained).
-template <bool A_KMAJOR, bool B_KMAJOR, int NW, int TM>
+template <bool A_KMAJOR, bool B_KMAJOR, int NW, int TM, int EPISET = kEpiSetGeneral>
 __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16* smem) {
   static_assert(TM == kRT || (TM == 128 && !A_KMAJOR), "the half-height tile exists for row-major A only");
   constexpr int kRStage = ring_stage<TM>();
@@ -263,24 +263,24 @@ __device__ __forceinline__ void ring_tile(const GemmBf16Params& p, int pid, bf16
       }
     }
   }
-  gemm_epilogue_staged<kWaveM / 32, kWaveN / 32, false>(smem, acc, p, m0 + wm * kWaveM, n0 + wn * kWaveN, wave, lane);
+  gemm_epilogue_staged<kWaveM / 32, kWaveN / 32, false, EPISET>(smem, acc, p, m0 + wm * kWaveM, n0 + wn * kWaveN, wave, lane);
 }
 
-template <bool A_KMAJOR, bool B_KMAJOR, int NW, int TM>
+template <bool A_KMAJOR, bool B_KMAJOR, int NW, int TM, int EPISET = kEpiSetGeneral>
 __global__ __launch_bounds__(2 * NW * 64) void gemm_ring_kernel(GemmBf16Params p) {
   extern __shared__ __attribute__((aligned(16))) bf16 smem[];
-  ring_tile<A_KMAJOR, B_KMAJOR, NW, TM>(p, blockIdx.x, smem);
+  ring_tile<A_KMAJOR, B_KMAJOR, NW, TM, EPISET>(p, blockIdx.x, smem);
 }
 
 // Up to three independent problems of the same operand layout in one launch: workgroups [first[i], first[i+1])
 // work on problem i.  Lets GEMMs that each fill only part of the chip share one round of workgroups.
-template <bool A_KMAJOR, bool B_KMAJOR, int NW>
+template <bool A_KMAJOR, bool B_KMAJOR, int NW, int EPISET = kEpiSetGeneral>
 __global__ __launch_bounds__(2 * NW * 64) void gemm_ring_group_kernel(GemmRingGroup g) {
   extern __shared__ __attribute__((aligned(16))) bf16 smem[];
   const int bid = (int)blockIdx.x;
   const int which = bid < g.first[1] ? 0 : (bid < g.first[2] ? 1 : 2);
   const GemmBf16Params p = which == 0 ? g.p[0] : (which == 1 ? g.p[1] : g.p[2]);
-  ring_tile<A_KMAJOR, B_KMAJOR, NW, kRT>(p, bid - g.first[which], smem);
+  ring_tile<A_KMAJOR, B_KMAJOR, NW, kRT, EPISET>(p, bid - g.first[which], smem);
 }
 
 template <int TM> constexpr size_t ring_smem_bytes() { return (size_t)kRStages * ring_stage<TM>() * sizeof(bf16); }
@@ -306,15 +306,57 @@ hipError_t prepare_ring_variant() {
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_kernel<AK, BK_, NW, 128>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)ring_smem_bytes<128>());
   }
+  if constexpr (!AK && BK_) {   // the forward layout also carries the LM head's loss epilogues
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_kernel<AK, BK_, NW, kRT, kEpiSetXent>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRSmemBytes);
+  }
+  if constexpr (AK && BK_) {    // the weight-gradient layout also carries the Adam epilogue
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_kernel<AK, BK_, NW, kRT, kEpiSetAdam>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRSmemBytes);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_group_kernel<AK, BK_, NW, kEpiSetAdam>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRSmemBytes);
+  }
   if (e == hipSuccess) attr_done = true;
   return e;
+}
+
+// Which set of epilogues the problems of one launch need (all of one set), or -1.
+static int epi_set_of(const GemmBf16Params* p, int n) {
+  auto set_of = [](int mode) { return mode == kEpiAdam ? kEpiSetAdam : (mode == kEpiXentStats || mode == kEpiXentGrad) ? kEpiSetXent : kEpiSetGeneral; };
+  const int set = set_of(p[0].epi.mode);
+  for (int i = 1; i < n; ++i)
+    if (set_of(p[i].epi.mode) != set) return -1;
+  return set;
 }
 
 template <bool AK, bool BK_, int NW>
 hipError_t launch_ring_variant(hipStream_t s, const GemmBf16Params* p, int n) {
   hipError_t e = prepare_ring_variant<AK, BK_, NW>();
   if (e != hipSuccess) return e;
+  const int set = epi_set_of(p, n);
+  if (set < 0) return hipErrorInvalidValue;
+  if (set == kEpiSetXent) {
+    if constexpr (!AK && BK_) {
+      if (n != 1) return hipErrorInvalidValue;
+      gemm_ring_kernel<AK, BK_, NW, kRT, kEpiSetXent><<<p[0].tiles_m * p[0].tiles_n, 2 * NW * 64, kRSmemBytes, s>>>(p[0]);
+      return hipGetLastError();
+    } else {
+      return hipErrorInvalidValue;
+    }
+  }
+  if (set == kEpiSetAdam) {
+    if constexpr (!(AK && BK_)) return hipErrorInvalidValue;
+  }
   if (n == 1) {
+    if constexpr (AK && BK_) {
+      if (set == kEpiSetAdam) {
+        gemm_ring_kernel<AK, BK_, NW, kRT, kEpiSetAdam><<<p[0].tiles_m * p[0].tiles_n, 2 * NW * 64, kRSmemBytes, s>>>(p[0]);
+        return hipGetLastError();
+      }
+    }
     gemm_ring_kernel<AK, BK_, NW, kRT><<<p[0].tiles_m * p[0].tiles_n, 2 * NW * 64, kRSmemBytes, s>>>(p[0]);
   } else {
     GemmRingGroup g{};
@@ -327,6 +369,12 @@ hipError_t launch_ring_variant(hipStream_t s, const GemmBf16Params* p, int n) {
       }
     }
     g.first[kRingGroupMax] = total;
+    if constexpr (AK && BK_) {
+      if (set == kEpiSetAdam) {
+        gemm_ring_group_kernel<AK, BK_, NW, kEpiSetAdam><<<total, 2 * NW * 64, kRSmemBytes, s>>>(g);
+        return hipGetLastError();
+      }
+    }
     gemm_ring_group_kernel<AK, BK_, NW><<<total, 2 * NW * 64, kRSmemBytes, s>>>(g);
   }
   return hipGetLastError();

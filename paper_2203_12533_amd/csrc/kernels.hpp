@@ -8,7 +8,35 @@
 namespace pw {
 
 enum DType { kF32 = 0, kBF16 = 1, kI32 = 2 };
-enum Epilogue { kEpiStore = 0, kEpiBias = 1, kEpiBiasResidual = 2, kEpiBiasGelu = 3, kEpiGeluBwd = 4 };
+enum Epilogue {
+  kEpiStore = 0, kEpiBias = 1, kEpiBiasResidual = 2, kEpiBiasGelu = 3, kEpiGeluBwd = 4,
+  kEpiAdam = 5,        // the product is the gradient of a weight: the Adam update of that weight runs in the epilogue
+  kEpiXentStats = 6,   // the product is a tile of logits: only softmax statistics leave the kernel
+  kEpiXentGrad = 7     // the product is a tile of logits: what is stored is (softmax - onehot) / N in bf16
+};
+
+// kEpiAdam: w, m, v (fp32) and w_bf16 (optional) are laid out like the product [M, N] with leading dimension
+// ldc; the gradient itself is stored to C only if C is non-null.  Bias corrections 1 / (1 - beta^t): read from
+// c_dev[0..1] (device) when non-null - a captured graph then stays valid across steps - else computed from t.
+struct AdamEpi {
+  float *w, *m, *v;
+  void* w_bf16;
+  float lr, b1, b2, eps;
+  int t;
+  const float* c_dev;
+};
+// kEpiXentStats / kEpiXentGrad: rows of the product are token positions (row r = b*T + t, target
+// tokens[b*(T+1) + t + 1]), columns the vocabulary.  Stats: part[r][N/64] receives (max, sum exp(z - max)) of each
+// 64-column group, zt[r] the target's logit; C is not written.  Grad: lse[r] is the row's log-sum-exp;
+// C (bf16) receives (exp(z - lse) - [column == target]) * inv_n.
+struct XentEpi {
+  const int32_t* tokens;
+  int T;
+  float* part;
+  float* zt;
+  const float* lse;
+  float inv_n;
+};
 
 struct GemmArgs {
   int dtype;
@@ -22,6 +50,8 @@ struct GemmArgs {
   void* C;
   void* C2;
   float* b_colsum;   // optional: column sums of op(B) over k (= or +=, following `accumulate`); see gemm_colsum_fusable
+  AdamEpi adam;      // kEpiAdam
+  XentEpi xent;      // kEpiXentStats, kEpiXentGrad
 };
 
 // elementwise.hip
@@ -38,6 +68,17 @@ hipError_t launch_sgd(hipStream_t s, float* w, const float* g, int64_t n, float 
 hipError_t launch_adam(hipStream_t s, float* w, float* m, float* v, const float* g, void* w_bf16, int64_t n,
                        float lr, float b1, float b2, float eps, int t, const int* t_dev);
 hipError_t launch_increment(hipStream_t s, int* counter);
+// Adam's step state on the device (at least 32 bytes): state[0] (int) the step number t, state[4], state[5] (float,
+// 16-byte aligned) the bias corrections 1 / (1 - beta1^t), 1 / (1 - beta2^t).  set_to > 0: t = set_to; set_to = 0: t += 1.
+hipError_t launch_adam_step(hipStream_t s, int* state, int set_to, float b1, float b2);
+// Mean cross-entropy from the statistics a kEpiXentStats GEMM left: lse[r] = log sum exp over the row's `groups`
+// 64-column groups, row_loss[r] = lse[r] - zt[r], loss = mean.
+hipError_t launch_xent_from_stats(hipStream_t s, const float* part, const float* zt, float* lse, float* row_loss,
+                                  float* loss, int N, int groups);
+// Whether launch_gemm can run this problem with epilogue kEpiAdam (alone, or as a member of a shared launch) /
+// with kEpiXentStats and kEpiXentGrad.
+bool gemm_adam_fusable(const GemmArgs& a, bool grouped);
+bool gemm_xent_fusable(const GemmArgs& a);
 
 // norm.hip
 hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, const float* x, const float* g, const float* b, void* y,

@@ -19,9 +19,43 @@ namespace pw {
 
 namespace {
 
-void build_param_table(const pw_lm_config& c, std::vector<ParamInfo>& t, int64_t& total) {
+OptimizerConfig opt_of(const pw_lm_config& c) { return OptimizerConfig{c.optimizer, c.lr, c.beta1, c.beta2, c.eps}; }
+
+// The weight-gradient GEMM of a [in, out] weight over N tokens, as far as the launcher's choice of kernel goes.
+GemmArgs wgrad_shape(int64_t N, int64_t in, int64_t out) {
+  GemmArgs a{};
+  a.dtype = kBF16; a.a_kmajor = 1; a.b_kmajor = 1;
+  a.M = in; a.N = out; a.K = N; a.lda = in; a.ldb = out; a.ldc = out;
+  a.epilogue = kEpiStore; a.out_dtype = kF32;
+  return a;
+}
+
+// Which weights of a layer (and the head) get their Adam update inside the weight-gradient GEMM: those whose GEMM
+// runs on the ring kernel's full tiles, alone or - QKV and out-projection - in their shared launch.
+struct FusedPlan { bool qkv = false, wo = false, w1 = false, w2 = false, wh = false; };
+FusedPlan fused_plan(const pw_lm_config& c) {
+  FusedPlan f;
+  if (!c.fused_update || !c.bf16 || c.optimizer != 2 || !c.has_head) return f;
+  const int64_t N = (int64_t)c.batch * c.seq, d = c.d_model, F = c.d_ff, V = c.vocab;
+  const GemmArgs pair[2] = {wgrad_shape(N, d, 3 * d), wgrad_shape(N, d, d)};
+  const bool shared = gemm_group_shares_launch(pair, 2);
+  f.qkv = gemm_adam_fusable(pair[0], shared);
+  f.wo = gemm_adam_fusable(pair[1], shared);
+  if (shared && f.qkv != f.wo) f.qkv = f.wo = false;   // one launch, one kind of epilogue
+  f.w1 = gemm_adam_fusable(wgrad_shape(N, d, F), false);
+  f.w2 = gemm_adam_fusable(wgrad_shape(N, F, d), false);
+  f.wh = gemm_adam_fusable(wgrad_shape(N, d, V), false);
+  return f;
+}
+
+void build_param_table(const pw_lm_config& c, std::vector<ParamInfo>& t, int64_t& total, int64_t& fused_from) {
   ParamTableBuilder tb{t};
-  auto add = [&](const std::string& n, int64_t numel) { tb.add(n, numel); };
+  const FusedPlan fp = fused_plan(c);
+  std::vector<char> late;   // per parameter: updated in its weight-gradient GEMM -> placed behind all the others
+  auto add = [&](const std::string& n, int64_t numel, bool fused = false) {
+    tb.add(n, numel);
+    late.push_back(fused ? 1 : 0);
+  };
   const int64_t d = c.d_model, F = c.d_ff, V = c.vocab, T = c.seq;
   if (c.has_embed) {
     add("wte", V * d);
@@ -30,17 +64,29 @@ void build_param_table(const pw_lm_config& c, std::vector<ParamInfo>& t, int64_t
   for (int l = 0; l < c.n_layer; ++l) {
     const std::string p = "l" + std::to_string(l) + ".";
     add(p + "ln1_g", d); add(p + "ln1_b", d);
-    add(p + "wqkv", d * 3 * d); add(p + "bqkv", 3 * d);
-    add(p + "wo", d * d); add(p + "bo", d);
+    add(p + "wqkv", d * 3 * d, fp.qkv); add(p + "bqkv", 3 * d);
+    add(p + "wo", d * d, fp.wo); add(p + "bo", d);
     add(p + "ln2_g", d); add(p + "ln2_b", d);
-    add(p + "w1", d * F); add(p + "b1", F);
-    add(p + "w2", F * d); add(p + "b2", d);
+    add(p + "w1", d * F, fp.w1); add(p + "b1", F);
+    add(p + "w2", F * d, fp.w2); add(p + "b2", d);
   }
   if (c.has_head) {
     add("lnf_g", d); add("lnf_b", d);
-    add("wh", d * V);
+    add("wh", d * V, fp.wh);
   }
   total = tb.off;
+  // Offsets again, in two runs: everything the optimizer launch updates first, then the weights updated by their
+  // GEMMs, so that the launch covers one contiguous range.  (Index order, which is what the API shows, is unchanged.)
+  fused_from = -1;
+  int64_t off = 0;
+  for (int pass = 0; pass < 2; ++pass) {
+    for (size_t i = 0; i < t.size(); ++i) {
+      if (late[i] != pass) continue;
+      if (pass == 1 && fused_from < 0) fused_from = off;
+      t[i].offset = off;
+      off += (t[i].numel + kParamAlign - 1) / kParamAlign * kParamAlign;
+    }
+  }
 }
 
 // Assigns every activation / scratch pointer; with base == nullptr only measures.
@@ -101,6 +147,11 @@ size_t plan(Model* m, unsigned char* base) {
     m->meanf = cv.take<float>(N * 4);
     m->rstdf = cv.take<float>(N * 4);
     m->row_loss = cv.take<float>(N * 4);
+    if (m->fused_head) {   // statistics instead of a second use of the logits buffer
+      m->xe_part = cv.take<float>(N * (V / 64) * 2 * 4);
+      m->xe_zt = cv.take<float>(N * 4);
+      m->xe_lse = cv.take<float>(N * 4);
+    }
   }
   m->dx_a = cv.take<float>(N * d * 4);
   m->dx_b = cv.take<float>(N * d * 4);
@@ -151,6 +202,8 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
   const int N = m->N(), d = c.d_model, F = c.d_ff;
   const int dt = m->act_dtype();
   float* g = m->g;
+  const FusedPlan fz = (m->fused_from >= 0 && !accumulate && !defer) ? fused_plan(c) : FusedPlan{};
+  const OptimizerConfig opt = opt_of(c);
   for (int l = c.n_layer - 1; l >= 0; --l) {
     auto& A = s.layer[l];
     const size_t e = layer_base(m, l);
@@ -159,15 +212,19 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
     void* const lp_mid = defer ? A.g_yo : m->dx_lp;                                    // bf16 copy of dx_b
     void* const lp_below = defer && l > 0 ? s.layer[l - 1].g_y2 : m->dx_lp;            // bf16 copy of the new dx_a
     const void* dx_op = c.bf16 ? (defer ? (const void*)A.g_y2 : (const void*)m->dx_lp) : (const void*)m->dx_a;
+    // Every data gradient comes BEFORE the weight gradient of the same layer: a weight gradient whose epilogue
+    // applies the optimizer (fused update) rewrites the weight its data gradient still has to read.
     // FFN2: x_out = x_mid + h W2 + b2
-    if (!defer) PW_TRY(launch_gemm(m->stream, wgrad_args(m, A.h, dx_op, e + 10, N, F, d, accumulate)), "ffn2 wgrad");
     if (l == c.n_layer - 1 && !top_b2_done)
       PW_TRY(launch_colsum(m->stream, kF32, m->dx_a, g + P(m, e + 11).offset, m->ws, N, d, accumulate), "b2 grad");
     PW_TRY(gemm_dgrad(m, dx_op, e + 10, N, F, d, kEpiGeluBwd, A.u, d_big, dt, 0), "ffn2 dgrad + gelu'");
+    if (!defer)
+      PW_TRY(launch_gemm(m->stream, fz.w2 ? wgrad_adam_args(m, opt, A.h, dx_op, e + 10, N, F, d)
+                                          : wgrad_args(m, A.h, dx_op, e + 10, N, F, d, accumulate)), "ffn2 wgrad");
     // FFN1: u = m W1 + b1
     // (b1 gradient = column sums of d_big: delivered by the weight-gradient GEMM where that is free)
-    if (!defer) PW_TRY(gemm_wgrad_bias(m, A.mm, d_big, e + 8, e + 9, N, d, F, accumulate, m->ws), "ffn1 wgrad + b1 grad");
     PW_TRY(gemm_dgrad(m, d_big, e + 8, N, d, F, kEpiStore, nullptr, m->d_small, dt, 0), "ffn1 dgrad");
+    if (!defer) PW_TRY(gemm_wgrad_bias(m, A.mm, d_big, e + 8, e + 9, N, d, F, accumulate, m->ws, fz.w1 ? &opt : nullptr), "ffn1 wgrad + b1 grad");
     // LN2 and the residual branch: dx_b = dx_a + LN2'(d_small)
     PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_mid, m->w + P(m, e + 6).offset, A.mean2, A.rstd2, m->dx_a,
                                 m->dx_b, c.bf16 ? lp_mid : nullptr, g + P(m, e + 6).offset, g + P(m, e + 7).offset,
@@ -181,12 +238,14 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
                                 c.n_head, m->hd()), "attention bwd");
     // QKV: qkv = a Wqkv + bqkv
     // (dy_out, the bf16 residual gradient, stays intact until the LN1 backward below rewrites it)
+    PW_TRY(gemm_dgrad(m, d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small, dt, 0), "qkv dgrad");
     if (!defer) {
-      const WgradJob jobs[2] = {{wgrad_args(m, A.a, d_qkv, e + 2, N, d, 3 * d, accumulate), (int64_t)e + 3},
-                                {wgrad_args(m, A.o, dy_out, e + 4, N, d, d, accumulate), -1}};
+      const WgradJob jobs[2] = {{fz.qkv ? wgrad_adam_args(m, opt, A.a, d_qkv, e + 2, N, d, 3 * d)
+                                        : wgrad_args(m, A.a, d_qkv, e + 2, N, d, 3 * d, accumulate), (int64_t)e + 3},
+                                {fz.wo ? wgrad_adam_args(m, opt, A.o, dy_out, e + 4, N, d, d)
+                                       : wgrad_args(m, A.o, dy_out, e + 4, N, d, d, accumulate), -1}};
       PW_TRY(gemm_wgrad_group(m, jobs, 2, m->ws), "qkv + out-proj wgrad + bqkv grad");
     }
-    PW_TRY(gemm_dgrad(m, d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small, dt, 0), "qkv dgrad");
     // LN1 and the residual branch: dx_a = dx_b + LN1'(d_small)
     PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->w + P(m, e).offset, A.mean1, A.rstd1, m->dx_b,
                                 m->dx_a, c.bf16 ? lp_below : nullptr, g + P(m, e).offset, g + P(m, e + 1).offset,
@@ -254,6 +313,15 @@ bool model_config_ok(const pw_lm_config& c, std::string* why) {
   return true;
 }
 
+// The LM-head GEMM [N, d] . [d, V], as far as the launcher's choice of kernel goes.
+static GemmArgs head_fwd_shape(const pw_lm_config& c) {
+  GemmArgs a{};
+  a.dtype = kBF16; a.a_kmajor = 0; a.b_kmajor = 1;
+  a.M = (int64_t)c.batch * c.seq; a.N = c.vocab; a.K = c.d_model; a.lda = a.K; a.ldb = a.N; a.ldc = a.N;
+  a.epilogue = kEpiStore; a.out_dtype = kBF16;
+  return a;
+}
+
 hipError_t model_create(const pw_lm_config& cfg, hipStream_t stream, Model** out, std::string* err) {
   std::string why;
   if (!model_config_ok(cfg, &why)) {
@@ -264,8 +332,9 @@ hipError_t model_create(const pw_lm_config& cfg, hipStream_t stream, Model** out
   m->cfg = cfg;
   m->stream = stream;
   m->bf16 = cfg.bf16 ? 1 : 0;
-  build_param_table(cfg, m->params, m->total);
-  hipError_t e = model_state_alloc(m, cfg.optimizer, err);
+  build_param_table(cfg, m->params, m->total, m->fused_from);
+  m->fused_head = cfg.fused_head_loss && cfg.bf16 && cfg.has_head && gemm_xent_fusable(head_fwd_shape(cfg));
+  hipError_t e = model_state_alloc(m, opt_of(cfg), err);
   if (e != hipSuccess) {
     delete m;
     return e;
@@ -314,7 +383,7 @@ hipError_t model_apply_optimizer(Model* m) {
   const pw_lm_config& c = m->cfg;
   hipError_t e = flush_wgrads(m);
   if (e != hipSuccess) return e;
-  return model_state_apply_optimizer(m, OptimizerConfig{c.optimizer, c.lr, c.beta1, c.beta2, c.eps});
+  return model_state_apply_optimizer(m, opt_of(c));
 }
 
 hipError_t model_train_step(Model* m, const int32_t* tokens, float* loss) {
@@ -331,11 +400,29 @@ hipError_t model_train_step(Model* m, const int32_t* tokens, float* loss) {
   hipError_t e = layers_forward(m, s);
   if (e != hipSuccess) return e;
   PW_TRY(launch_layernorm_fwd(m->stream, dt, s.x_out, m->w + P(m, tail).offset, m->w + P(m, tail + 1).offset, m->y, m->meanf, m->rstdf, N, d), "lnf fwd");
-  PW_TRY(gemm_fwd(m, m->y, tail + 2, nullptr, N, d, V, kEpiStore, dt, nullptr, m->logits, nullptr), "head gemm");
-  PW_TRY(launch_softmax_xent(m->stream, dt, m->logits, tokens, loss, m->row_loss, c.batch, c.seq, V), "softmax-xent");
-  // head backward: logits now hold dlogits
-  PW_TRY(launch_gemm(m->stream, wgrad_args(m, m->y, m->logits, tail + 2, N, d, V, 0)), "head wgrad");
+  if (m->fused_head) {
+    // The head GEMM fused with the loss: the logits never reach memory.  A first pass over the product leaves only
+    // softmax statistics per 64-column group (and the target's logit); a second pass over the same product writes
+    // the gradient of the logits straight from the accumulators.
+    GemmArgs hz = head_fwd_shape(c);
+    hz.A = m->y;
+    hz.B = (const uint16_t*)m->wlp + P(m, tail + 2).offset;
+    hz.epilogue = kEpiXentStats;
+    hz.C = nullptr;
+    hz.xent = XentEpi{tokens, c.seq, m->xe_part, m->xe_zt, m->xe_lse, 1.f / (float)N};
+    PW_TRY(launch_gemm(m->stream, hz), "head gemm + softmax statistics");
+    PW_TRY(launch_xent_from_stats(m->stream, m->xe_part, m->xe_zt, m->xe_lse, m->row_loss, loss, N, V / 64), "loss from statistics");
+    hz.epilogue = kEpiXentGrad;
+    hz.C = m->logits;
+    PW_TRY(launch_gemm(m->stream, hz), "head gemm + gradient of the logits");
+  } else {
+    PW_TRY(gemm_fwd(m, m->y, tail + 2, nullptr, N, d, V, kEpiStore, dt, nullptr, m->logits, nullptr), "head gemm");
+    PW_TRY(launch_softmax_xent(m->stream, dt, m->logits, tokens, loss, m->row_loss, c.batch, c.seq, V), "softmax-xent");
+  }
+  // head backward: logits now hold dlogits (the data gradient first: see layers_backward)
   PW_TRY(gemm_dgrad(m, m->logits, tail + 2, N, d, V, kEpiStore, nullptr, m->d_small, dt, 0), "head dgrad");
+  PW_TRY(launch_gemm(m->stream, fused_plan(c).wh && m->fused_from >= 0 ? wgrad_adam_args(m, opt_of(c), m->y, m->logits, tail + 2, N, d, V)
+                                                                         : wgrad_args(m, m->y, m->logits, tail + 2, N, d, V, 0)), "head wgrad");
   PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, s.x_out, m->w + P(m, tail).offset, m->meanf, m->rstdf, nullptr, m->dx_a,
                               c.bf16 ? m->dx_lp : nullptr, m->g + P(m, tail).offset, m->g + P(m, tail + 1).offset,
                               c.n_layer > 0 ? m->g + P(m, layer_base(m, c.n_layer - 1) + 11).offset : nullptr, m->ws, N, d, 0), "lnf bwd");

@@ -43,6 +43,10 @@ struct Model : ModelBase {
   void* y = nullptr;
   void* logits = nullptr;
   float *meanf = nullptr, *rstdf = nullptr, *row_loss = nullptr;
+  // head fused with the loss (cfg.fused_head_loss on a shape the ring kernel takes): softmax statistics per
+  // 64-column group, the targets' logits, the rows' log-sum-exp
+  bool fused_head = false;
+  float *xe_part = nullptr, *xe_zt = nullptr, *xe_lse = nullptr;
   // backward scratch
   float *dx_a = nullptr, *dx_b = nullptr, *delta = nullptr, *ws = nullptr;
   void *dx_lp = nullptr, *d_big = nullptr, *d_qkv = nullptr, *d_small = nullptr;

@@ -3,7 +3,8 @@
 
 namespace pw {
 
-hipError_t model_state_alloc(ModelBase* m, int optimizer, std::string* err) {
+hipError_t model_state_alloc(ModelBase* m, const OptimizerConfig& o, std::string* err) {
+  const int optimizer = o.kind;
   auto fail = [&](hipError_t e, const char* what) {
     if (err) *err = std::string(what) + ": " + hipGetErrorString(e);
     model_state_free(m);
@@ -25,8 +26,7 @@ hipError_t model_state_alloc(ModelBase* m, int optimizer, std::string* err) {
   if (m->m && (e = launch_fill_f32(m->stream, m->m, m->total, 0.f)) != hipSuccess) return fail(e, "zero m");
   if (m->v && (e = launch_fill_f32(m->stream, m->v, m->total, 0.f)) != hipSuccess) return fail(e, "zero v");
   if (m->wlp && (e = launch_f32_to_bf16(m->stream, m->w, m->wlp, m->total)) != hipSuccess) return fail(e, "zero bf16 weights");
-  const int one = 1;
-  if ((e = hipMemcpyAsync(m->step_dev, &one, sizeof(int), hipMemcpyHostToDevice, m->stream)) != hipSuccess) return fail(e, "init step");
+  if ((e = launch_adam_step(m->stream, m->step_dev, 1, o.beta1, o.beta2)) != hipSuccess) return fail(e, "init step");
   if ((e = hipStreamSynchronize(m->stream)) != hipSuccess) return fail(e, "sync");
   return hipSuccess;
 }
@@ -49,8 +49,9 @@ hipError_t model_state_apply_optimizer(ModelBase* m, const OptimizerConfig& o) {
     PW_TRY(launch_sgd(m->stream, m->w, m->g, m->total, o.lr), "sgd");
     if (m->wlp) PW_TRY(launch_f32_to_bf16(m->stream, m->w, m->wlp, m->total), "refresh bf16 weights");
   } else {
-    PW_TRY(launch_adam(m->stream, m->w, m->m, m->v, m->g, m->wlp, m->total, o.lr, o.beta1, o.beta2, o.eps, 0, m->step_dev), "adam");
-    PW_TRY(launch_increment(m->stream, m->step_dev), "step counter");
+    const int64_t n = m->fused_from >= 0 ? m->fused_from : m->total;   // the rest was updated by its weight-gradient GEMMs
+    PW_TRY(launch_adam(m->stream, m->w, m->m, m->v, m->g, m->wlp, n, o.lr, o.beta1, o.beta2, o.eps, 0, m->step_dev), "adam");
+    PW_TRY(launch_adam_step(m->stream, m->step_dev, 0, o.beta1, o.beta2), "step counter");
   }
   return hipSuccess;
 }
@@ -99,9 +100,20 @@ GemmArgs wgrad_args(ModelBase* m, const void* x, const void* dy, int64_t wi, int
   return a;
 }
 
+GemmArgs wgrad_adam_args(ModelBase* m, const OptimizerConfig& o, const void* x, const void* dy, int64_t wi, int64_t N,
+                         int64_t in, int64_t out) {
+  GemmArgs a = wgrad_args(m, x, dy, wi, N, in, out, 0);
+  const int64_t off = m->P(wi).offset;
+  a.epilogue = kEpiAdam;
+  a.C = nullptr;
+  a.adam = AdamEpi{m->w + off, m->m + off, m->v + off, m->wlp ? (void*)((uint16_t*)m->wlp + off) : nullptr,
+                   o.lr, o.beta1, o.beta2, o.eps, 0, m->adam_c()};
+  return a;
+}
+
 hipError_t gemm_wgrad_bias(ModelBase* m, const void* x, const void* dy, int64_t wi, int64_t bi, int64_t N, int64_t in,
-                           int64_t out, int accumulate, float* ws) {
-  GemmArgs wa = wgrad_args(m, x, dy, wi, N, in, out, accumulate);
+                           int64_t out, int accumulate, float* ws, const OptimizerConfig* fused) {
+  GemmArgs wa = fused ? wgrad_adam_args(m, *fused, x, dy, wi, N, in, out) : wgrad_args(m, x, dy, wi, N, in, out, accumulate);
   wa.b_colsum = m->gp(bi);
   if (gemm_colsum_fusable(wa, false)) return launch_gemm(m->stream, wa);
   wa.b_colsum = nullptr;

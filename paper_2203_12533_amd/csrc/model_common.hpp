@@ -35,7 +35,11 @@ struct ModelBase {
   float* m = nullptr;
   float* v = nullptr;
   void* wlp = nullptr;        // bf16 compute copy of w (bf16 mode only)
-  int* step_dev = nullptr;    // Adam step number, on the device so that captured graphs stay valid
+  int* step_dev = nullptr;    // Adam step state on the device (launch_adam_step), so that captured graphs stay valid
+  // Parameters at offsets >= fused_from (-1: none) are updated inside the epilogue of their weight-gradient GEMM:
+  // their gradients are never stored, and the optimizer launch covers [0, fused_from) only.
+  int64_t fused_from = -1;
+  const float* adam_c() const { return reinterpret_cast<const float*>(step_dev) + 4; }   // the two bias corrections
   // Set by a model that holds back gradient work (see lm.hpp): enqueues it.  Whoever is about to read or
   // overwrite `g` from outside the model calls it first.
   hipError_t (*flush_pending)(ModelBase*) = nullptr;
@@ -80,7 +84,7 @@ struct Carver {
 
 // Allocates and zeroes w, g, (m, v), (wlp) and the step counter for m->total elements; on failure frees what
 // it allocated and says what failed in *err.
-hipError_t model_state_alloc(ModelBase* m, int optimizer, std::string* err);
+hipError_t model_state_alloc(ModelBase* m, const OptimizerConfig& o, std::string* err);
 void model_state_free(ModelBase* m);
 hipError_t model_state_refresh_lowp(ModelBase* m, int64_t offset, int64_t numel);
 hipError_t model_state_apply_optimizer(ModelBase* m, const OptimizerConfig& o);
@@ -95,10 +99,14 @@ hipError_t gemm_dgrad(ModelBase* m, const void* dy, int64_t wi, int64_t N, int64
 // dW[in, out] (=|+=) x^T[in, N] . dy[N, out], into the gradient arena.
 GemmArgs wgrad_args(ModelBase* m, const void* x, const void* dy, int64_t wi, int64_t N, int64_t in, int64_t out,
                     int accumulate);
+// The same GEMM with the Adam update of parameter wi in its epilogue (gradient not stored).
+GemmArgs wgrad_adam_args(ModelBase* m, const OptimizerConfig& o, const void* x, const void* dy, int64_t wi, int64_t N,
+                         int64_t in, int64_t out);
 // Weight gradient plus the bias gradient db (= column sums of dy): fused into the GEMM where that is free,
 // a separate column-sum launch otherwise.  ws: workspace of colsum_ws_floats(N, out) floats.
+// fused (optional): the weight (not the bias) is updated by Adam in the GEMM's epilogue instead of its gradient being stored.
 hipError_t gemm_wgrad_bias(ModelBase* m, const void* x, const void* dy, int64_t wi, int64_t bi, int64_t N, int64_t in,
-                           int64_t out, int accumulate, float* ws);
+                           int64_t out, int accumulate, float* ws, const OptimizerConfig* fused = nullptr);
 // Several (up to three) weight gradients of one step, in one launch where that fills the chip better.  A job with
 // bias >= 0 also delivers the bias gradient db = column sums of its dy [N, out] into that parameter's slot: fused
 // where that is free, a separate column-sum launch otherwise.

@@ -73,6 +73,8 @@ static pw_status state_export(pw_ctx* c, ModelBase* m, int part, int64_t idx, fl
   float* base = part_base(m, part);
   if (!base) return fail(c, PW_ERR_INVALID, "this model has no such part");
   const ParamInfo& p = m->params[idx];
+  if (part == PW_GRADS && m->fused_from >= 0 && p.offset >= m->fused_from)
+    return fail(c, PW_ERR_UNSUPPORTED, "%s is updated inside its weight-gradient GEMM (fused_update): its gradient is never stored", p.name.c_str());
   if (m->flush_pending && m->flush_pending(m) != hipSuccess) return fail(c, PW_ERR_DEVICE, "%s", m->error.c_str());
   PW_HIP(c, hipStreamSynchronize(c->exec));
   PW_HIP(c, hipMemcpy(dst, base + p.offset, (size_t)p.numel * 4, hipMemcpyDeviceToHost));
@@ -224,6 +226,9 @@ static GemmArgs gemm_args_of(const pw_gemm_args* a) {
   g.epilogue = a->epilogue; g.out_dtype = a->out_dtype; g.accumulate = a->accumulate;
   g.A = a->A; g.B = a->B; g.bias = a->bias; g.aux = a->aux; g.C = a->C; g.C2 = a->C2;
   g.b_colsum = a->b_colsum;
+  if (a->adam) g.adam = AdamEpi{a->adam->w, a->adam->m, a->adam->v, a->adam->w_bf16, a->adam->lr, a->adam->beta1,
+                                a->adam->beta2, a->adam->eps, a->adam->t, nullptr};
+  if (a->xent) g.xent = XentEpi{a->xent->tokens, a->xent->T, a->xent->part, a->xent->zt, a->xent->lse, a->xent->inv_n};
   return g;
 }
 pw_status pw_op_gemm(pw_ctx* c, const pw_gemm_args* a) {
@@ -284,6 +289,9 @@ pw_status pw_op_mha_bwd(pw_ctx* c, const pw_mha_args* a, const void* o, const vo
 }
 pw_status pw_op_softmax_xent(pw_ctx* c, int dtype, void* z, const int32_t* tokens, float* loss, float* row_loss, int B, int T, int V) {
   PW_OP(c, launch_softmax_xent(c->exec, dtype, z, tokens, loss, row_loss, B, T, V));
+}
+pw_status pw_op_xent_from_stats(pw_ctx* c, const float* part, const float* zt, float* lse, float* row_loss, float* loss, int N, int groups) {
+  PW_OP(c, launch_xent_from_stats(c->exec, part, zt, lse, row_loss, loss, N, groups));
 }
 pw_status pw_op_colsum(pw_ctx* c, int dtype, const void* in, float* out, float* ws, int64_t rows, int64_t cols, int accumulate) {
   PW_OP(c, launch_colsum(c->exec, dtype, in, out, ws, rows, cols, accumulate));

@@ -269,12 +269,10 @@ def test_three_weight_gradients_share_one_launch(ctx, orc):
         ctx.gemm_group([args(a, dq, dwq, D), {**args(mem, dkv, dwkv, 2 * D), "ldb": 8}, args(o, dy, dwox, D)])
 
 
-def test_one_layer_step_at_cfg3_layer_shapes_matches_oracle(orc):
-    """The production kernels end to end against the oracle: one layer with cfg3's d_model / heads / FFN width and
-    full sequence length, 2048 tokens, so that the forward, data-gradient and weight-gradient GEMMs all run on the
-    ring-buffered kernel (192-1024 tiles), the weight-gradient pair and the fused bias-gradient sums included, the
-    head_dim-128 attention kernels see 1024-token sequences and LayerNorm its one-wave-per-row path.  Loss and
-    every gradient tensor are compared (the vocabulary is cut to 8192 to keep the oracle's run near 20 s)."""
+@pytest.fixture(scope="module")
+def one_layer(orc):
+    """One layer with cfg3's d_model / heads / FFN width and full sequence length, 2048 tokens, vocabulary cut to 8192
+    (the oracle's step then takes about 20 s): parameters, tokens and the oracle's first TWO steps."""
     cfg = CFG3.with_(n_layer=1, batch=2, vocab=8192)
     tok = I.lm_tokens(cfg)
     rng = np.random.default_rng(20)            # 84 M parameters: numpy's generator draws them in a second
@@ -284,7 +282,17 @@ def test_one_layer_step_at_cfg3_layer_shapes_matches_oracle(orc):
         if kind == "gain":
             a += np.float32(1.0)
         params[name] = I.round_to_bf16(a).reshape(shape)       # biases and gains perturbed too
-    ref = orc.lm_train_step(cfg, params, tok)
+    ref1 = orc.lm_train_step(cfg, params, tok)
+    ref2 = orc.lm_train_step(cfg, ref1["params"], tok, state={"m": ref1["m"], "v": ref1["v"]}, t=2, backward=False, update=False)
+    return cfg, params, tok, ref1, ref2["loss"]
+
+
+def test_one_layer_step_at_cfg3_layer_shapes_matches_oracle(one_layer):
+    """The production kernels end to end against the oracle: the forward, data-gradient and weight-gradient GEMMs all
+    run on the ring-buffered kernel (192-1024 tiles), the weight-gradient pair and the fused bias-gradient sums
+    included, the head_dim-128 attention kernels see 1024-token sequences and LayerNorm its one-wave-per-row path.
+    Loss and every gradient tensor are compared."""
+    cfg, params, tok, ref, _ = one_layer
     with pwb.Context(0) as ctx:
         model = ctx.model(cfg)
         model.load_params(params)
@@ -301,6 +309,59 @@ def test_one_layer_step_at_cfg3_layer_shapes_matches_oracle(orc):
             assert_close(g, ref["grads"][k], 2e-2, k)
         print("worst gradient error", worst)
         model.close()
+
+
+@pytest.mark.parametrize("fused_update,fused_head_loss", [(True, False), (False, True), (True, True)])
+def test_one_layer_step_with_fused_update_and_fused_head_loss(one_layer, fused_update, fused_head_loss):
+    """The same step with Adam inside the weight-gradient epilogues and / or the LM head fused with the loss.  The
+    gradients of the fused weights are never stored; after the first step Adam's first moment is (1 - beta1) g, so
+    m / (1 - beta1) is compared with the oracle's gradient element by element, v with (1 - beta2) g^2, the bf16 copy
+    with the master weights; the other gradients are read as usual; the loss of the SECOND step (which sees the
+    updated weights) must follow the oracle's.  Twice, stream and HIP-graph dispatch: same bits."""
+    cfg, params, tok, ref, ref_loss2 = one_layer
+    big = [k for k in params if k.split(".")[-1] in ("wqkv", "wo", "w1", "w2", "wh")]
+    results = []
+    for mode in (pwb.PW_STREAM, pwb.PW_GRAPH):
+        with pwb.Context(0) as ctx:
+            model = ctx.model(cfg, fused_update=fused_update, fused_head_loss=fused_head_loss)
+            model.load_params(params)
+            step = model.compile_train_step()
+            ft = ctx.future_from_host(tok)
+            losses = []
+            for it in range(2):
+                (fl,) = ctx.chain([step], [ft], 1, mode)
+                losses.append(float(ctx.await_(fl)[0]))
+                ctx.future_release(fl)
+                if it == 0 and mode == pwb.PW_STREAM:
+                    assert abs(losses[0] - ref["loss"]) / abs(ref["loss"]) < 2e-2, (losses, ref["loss"])
+                    new1 = model.export_all(pwb.PW_PARAMS, params)
+                    m1 = model.export_all(pwb.PW_ADAM_M, params)
+                    v1 = model.export_all(pwb.PW_ADAM_V, params)
+                    for k in params:
+                        g_ref = ref["grads"][k]
+                        assert_close(m1[k].astype(np.float64) / (1 - cfg.beta1), g_ref, 2e-2, k + " (from m)")
+                        assert_close(v1[k].astype(np.float64) / (1 - cfg.beta2), g_ref ** 2, 4e-2, k + " (from v)")
+                        if fused_update and k in big:
+                            with pytest.raises(pwb.PwError) as e:
+                                model.export(pwb.PW_GRADS, k)
+                            assert e.value.status == pwb.PW_ERR_UNSUPPORTED
+                        else:
+                            assert_close(model.export(pwb.PW_GRADS, k).reshape(g_ref.shape), g_ref, 2e-2, k)
+            # the second step saw the weights the first one wrote (master copy and bf16 copy alike)
+            assert abs(losses[1] - ref_loss2) / abs(ref_loss2) < 2e-2, (losses, ref_loss2)
+            assert losses[1] < losses[0]
+            results.append((losses, model.export_all(pwb.PW_PARAMS, params), model.export_all(pwb.PW_ADAM_V, params)))
+            model.close()
+    assert results[0][0] == results[1][0]
+    for k in params:
+        assert np.array_equal(results[0][1][k], results[1][1][k]), k
+        assert np.array_equal(results[0][2][k], results[1][2][k]), k
+    # Adam's first update is -lr sign(g) wherever |g| >> eps: the updated weights are compared through that
+    for k in big:
+        g_ref = ref["grads"][k].reshape(-1)
+        sure = np.abs(g_ref) > 0.05 * np.sqrt(np.mean(g_ref ** 2))        # the sign of g is beyond the bf16 error there
+        moved = (new1[k].astype(np.float64) - params[k].astype(np.float64)).reshape(-1)[sure]
+        assert (np.sign(moved) == -np.sign(g_ref[sure])).mean() > 0.999, k
 
 
 def test_one_layer_encoder_decoder_step_at_full_layer_width_matches_oracle(orc):

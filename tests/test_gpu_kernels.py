@@ -138,6 +138,119 @@ def test_gemm_pair_small_problems_and_rejection(ctx, orc, bf16):
     assert_close(host(c1), orc.linear_fwd(x1v, w1v), 2e-6)
 
 
+# ---- fused epilogues of the step's two largest non-GEMM passes -------------------------------------------
+
+def _adam_case(seed, n_in, n_out, ntok):
+    x, xv = dev_act(_rand(seed, (ntok, n_in)), True)
+    dy, dyv = dev_act(_rand(seed + 1, (ntok, n_out), 0.3), True)
+    w = _rand(seed + 2, (n_in, n_out), 0.02).astype(np.float32)
+    m = _rand(seed + 3, (n_in, n_out), 0.05).astype(np.float32)
+    # second moments bounded away from zero: where v and g are both tiny the update is a quotient of two roundings
+    v = ((0.05 + np.abs(_rand(seed + 4, (n_in, n_out), 0.05))) ** 2).astype(np.float32)
+    return dict(x=x, xv=xv, dy=dy, dyv=dyv, w=w, m=m, v=v, wd=dev_f32(w), md=dev_f32(m), vd=dev_f32(v),
+                wlp=torch.zeros((n_in, n_out), dtype=torch.bfloat16, device="cuda"),
+                g=torch.full((n_in, n_out), float("nan"), device="cuda"), n_in=n_in, n_out=n_out, ntok=ntok)
+
+
+def _adam_gemm_kw(c, hp, t, store_g):
+    ep = pwb.AdamEpilogue(ptr(c["wd"]), ptr(c["md"]), ptr(c["vd"]), ptr(c["wlp"]), *hp, t)
+    return dict(dtype=pwb.PW_BF16, a_kmajor=1, b_kmajor=1, M=c["n_in"], N=c["n_out"], K=c["ntok"], lda=c["n_in"],
+                ldb=c["n_out"], ldc=c["n_out"], epilogue=pwb.PW_EPI_ADAM, out_dtype=pwb.PW_F32, accumulate=0,
+                A=ptr(c["x"]), B=ptr(c["dy"]), C=ptr(c["g"]) if store_g else None, adam=ep)
+
+
+def _check_adam_case(orc, c, hp, t, store_g):
+    _, g, _ = orc.linear_bwd(c["xv"], np.zeros((c["n_in"], c["n_out"])), c["dyv"])
+    rw, rm, rv = orc.adam(c["w"], c["m"], c["v"], g, *[np.float32(h) for h in hp], t)
+    if store_g:
+        assert_close(host(c["g"]), g, 2e-6, "g")
+    assert_close(host(c["md"]), rm, 1e-5, "m")
+    assert_close(host(c["vd"]), rv, 1e-5, "v")
+    w64 = c["w"].astype(np.float64)
+    # the update is small against w: compare it, and allow the fp32 storage of w on top
+    assert_close(host(c["wd"]) - w64, rw - w64, 1e-4, "dw", norm_slack=1e-3, extra=np.abs(w64) * 1.2e-7)
+    assert np.array_equal(c["wlp"].float().cpu().numpy(), I.round_to_bf16(c["wd"].cpu().numpy()))   # bf16 copy = RNE(w)
+
+
+@pytest.mark.parametrize("t", [1, 3])
+def test_gemm_with_adam_epilogue(ctx, orc, t):
+    """dW = x^T . dy with the Adam update of W in the GEMM's epilogue (26 bytes of optimizer traffic per parameter,
+    the gradient stored only on request): against the oracle's linear backward followed by the oracle's Adam."""
+    hp = (1e-3, 0.9, 0.95, 1e-8)
+    c = _adam_case(80, 2048, 5120, 192)                   # 160 tiles of 256 x 256: one launch of the ring kernel
+    if t == 1:
+        c["md"].zero_(), c["vd"].zero_()
+        c["m"][:], c["v"][:] = 0, 0
+    ctx.gemm(**_adam_gemm_kw(c, hp, t, store_g=True))
+    ctx.synchronize()
+    _check_adam_case(orc, c, hp, t, store_g=True)
+    # without the gradient output, from the same state: same update
+    c2 = _adam_case(80, 2048, 5120, 192)
+    if t == 1:
+        c2["md"].zero_(), c2["vd"].zero_()
+        c2["m"][:], c2["v"][:] = 0, 0
+    ctx.gemm(**_adam_gemm_kw(c2, hp, t, store_g=False))
+    ctx.synchronize()
+    for k in ("wd", "md", "vd", "wlp"):
+        assert torch.equal(c[k], c2[k]), k
+    assert torch.isnan(c2["g"]).all()
+
+
+def test_gemm_group_with_adam_epilogues_and_bias_gradient(ctx, orc):
+    """Two weight gradients sharing one launch (128 + 32 tiles), both with the Adam epilogue, one with the bias
+    gradient riding along - the QKV / out-projection pair of a layer."""
+    hp = (1e-3, 0.9, 0.95, 1e-8)
+    a, b = _adam_case(90, 2048, 4096, 128), _adam_case(95, 2048, 1024, 128)
+    dbias = torch.full((4096,), float("nan"), device="cuda")
+    ctx.gemm_group([{**_adam_gemm_kw(a, hp, 2, True), "b_colsum": ptr(dbias)}, _adam_gemm_kw(b, hp, 2, False)])
+    ctx.synchronize()
+    _check_adam_case(orc, a, hp, 2, True)
+    _check_adam_case(orc, b, hp, 2, False)
+    assert_close(host(dbias), a["dyv"].sum(axis=0), 1e-5)
+    # what the kernel cannot take is refused before anything runs: ragged shape, row-major operand, accumulate
+    w0 = a["wd"].clone()
+    for bad in (dict(M=2040, lda=2040), dict(a_kmajor=0), dict(accumulate=1)):
+        with pytest.raises(pwb.PwError):
+            ctx.gemm(**{**_adam_gemm_kw(a, hp, 2, True), **bad})
+    ctx.synchronize()
+    assert torch.equal(w0, a["wd"])
+
+
+def test_lm_head_fused_with_the_loss(ctx, orc):
+    """The LM-head GEMM with the loss in its epilogue: a first pass over y . Wh leaves only softmax statistics per
+    64-column group and the targets' logits, a second pass writes (softmax - onehot) / N in bf16 - the logits
+    themselves are never stored.  Against the oracle's linear forward + softmax cross-entropy."""
+    B, T, d, V = 4, 512, 256, 8192                        # 8 x 32 tiles
+    N = B * T
+    y, yv = dev_act(_rand(100, (N, d)), True)
+    wh, whv = dev_act(_rand(101, (d, V), 0.08), True)
+    tok = I.tokens(102, 1, (B, T + 1), V)
+    tok[1, 5], tok[2, 7] = -3, V + 11                      # out-of-range ids are clamped, as everywhere
+    tokd = dev_i32(tok)
+    part = torch.full((N, V // 64, 2), float("nan"), device="cuda")
+    zt, lse, rows, loss = (torch.full((n,), float("nan"), device="cuda") for n in (N, N, N, 1))
+    dz = torch.full((N, V), float("nan"), dtype=torch.bfloat16, device="cuda")
+    common = dict(dtype=pwb.PW_BF16, a_kmajor=0, b_kmajor=1, M=N, N=V, K=d, lda=d, ldb=V, ldc=V, accumulate=0,
+                  A=ptr(y), B=ptr(wh))
+    xe = pwb.XentEpilogue(ptr(tokd), T, ptr(part), ptr(zt), ptr(lse), 1.0 / N)
+    ctx.gemm(epilogue=pwb.PW_EPI_XENT_STATS, out_dtype=pwb.PW_BF16, C=None, xent=xe, **common)
+    ctx.op("xent_from_stats", ptr(part), ptr(zt), ptr(lse), ptr(rows), ptr(loss), N, V // 64)
+    ctx.gemm(epilogue=pwb.PW_EPI_XENT_GRAD, out_dtype=pwb.PW_BF16, C=ptr(dz), xent=xe, **common)
+    ctx.synchronize()
+    z = orc.linear_fwd(yv, whv)
+    tgt = np.clip(tok[:, 1:].reshape(-1), 0, V - 1)
+    rl, rdz = orc.softmax_xent(z, tgt)
+    zmax = z.max(axis=1)
+    rlse = np.log(np.exp(z - zmax[:, None]).sum(axis=1)) + zmax
+    assert abs(host(loss)[0] - rl) / rl < 1e-5
+    assert_close(host(lse), rlse, 1e-5, "lse")
+    assert_close(host(zt), z[np.arange(N), tgt], 1e-5, "target logits")
+    assert_close(host(rows), rlse - z[np.arange(N), tgt], 1e-5, "row losses")
+    assert_close(host(dz), rdz, 6e-3, "dz")
+    with pytest.raises(pwb.PwError):                       # ragged vocabulary: refused, nothing runs
+        ctx.gemm(epilogue=pwb.PW_EPI_XENT_STATS, out_dtype=pwb.PW_BF16, C=None, xent=xe, **{**common, "N": V - 8})
+
+
 def test_gemm_rejects_what_the_kernel_cannot_take(ctx):
     a = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
     c = torch.zeros(64 * 64, dtype=torch.float32, device="cuda")
