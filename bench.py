@@ -35,22 +35,13 @@ DEFAULT_FUSED_HEAD_LOSS = False  # cfg3: + 0.78 ms per step (the head GEMM runs 
 
 
 def fill_model_on_device(model, cfg, torch, seed: int):
-    """Random-init weights drawn on the GPU (N(0, init_std), bf16-representable), biases 0, gains 1."""
+    """The workload's initial weights - the seeded counter-based generator of inputs.py (N(0, init_std),
+    bf16-representable; biases 0, gains 1), evaluated on the GPU - imported tensor by tensor."""
     from paper_2203_12533_amd import binding as pwb
     from paper_2203_12533_amd import inputs as I
-    gen = torch.Generator(device="cuda")
-    gen.manual_seed(seed)
     shapes = I.encdec_param_shapes(cfg) if isinstance(cfg, I.EncDecConfig) else I.param_shapes(cfg)
     for name, shape, kind in shapes:
-        n = int(np.prod(shape))
-        if kind == "matrix":
-            t = torch.randn(n, device="cuda", generator=gen, dtype=torch.float32) * cfg.init_std
-            if cfg.bf16:
-                t = t.to(torch.bfloat16).float()
-        elif kind == "gain":
-            t = torch.ones(n, device="cuda", dtype=torch.float32)
-        else:
-            t = torch.zeros(n, device="cuda", dtype=torch.float32)
+        t = I.param_torch(cfg, name, shape, kind, "cuda", seed)
         torch.cuda.synchronize()      # torch filled t on its own stream; the import runs on the executor stream
         model.import_device(pwb.PW_PARAMS, name, t.data_ptr())
         del t
@@ -257,6 +248,8 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dispatch", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="with the default workload: skip the short runs of cfg4, cfg5 and ed3 appended under other_workloads")
     ap.add_argument("--graph", action="store_true",
                     help="run the step as one HIP-graph replay (PW_GRAPH); the per-GEMM event timing is then off")
     ap.add_argument("--fused-update", type=int, default=None,
@@ -278,8 +271,39 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
-    encdec = args.workload.startswith("ed")
-    cfg = I.encdec_workload(args.workload) if encdec else I.workload(args.workload)
+    result = measure(args, args.workload, args.steps, args.warmup, torch, pwb, I)
+    if args.workload == "cfg3" and not args.no_other_workloads:
+        # The other workloads of this build, briefly (5 timed steps each), so that one default run shows them all;
+        # the headline above stays the cfg3 step.
+        result["other_workloads"] = {}
+        for w in ("cfg4", "cfg5", "ed3"):
+            r = measure(args, w, 5, 2, torch, pwb, I)
+            result["other_workloads"][w] = {
+                "workload": r["config"]["workload"], "tokens_per_s": r["value"], "ms_per_step": r["ms_per_step"],
+                "steps": 5, "warmup": 2, "model_tflop_per_step": r["config"]["model_tflop_per_step"],
+                "pct_peak_bf16_mfma": r["pct_peak_bf16_mfma"], "gemm_frac_of_peak": r["roofline"]["frac"],
+                "gemm_ms_per_step": r["roofline"]["gemm_ms_per_step"],
+                "fused_update_gemm_ms_per_step": r["roofline"].get("fused_update_gemms", {}).get("ms_per_step", 0.0)}
+    if not args.no_dispatch:
+        with pwb.Context(0) as ctx:
+            result["dispatch_us_per_fn"] = dispatch_bench(ctx, pwb, I)
+        cabi = dispatch_bench_c_abi()
+        if cabi is not None:
+            result["dispatch_c_abi"] = cabi
+    if not args.no_cpu_baseline:
+        encdec = args.workload.startswith("ed")
+        cfg = I.encdec_workload(args.workload) if encdec else I.workload(args.workload)
+        cb = cpu_baseline_encdec(cfg, pwb, I) if encdec else cpu_baseline(cfg, pwb)
+        if cb is not None:
+            result["cpu_baseline"] = cb
+    print(json.dumps(result))
+
+
+def measure(args, workload, steps, warmup, torch, pwb, I):
+    """Times `steps` steps of one workload (after `warmup` untimed ones) on a context and model of its own; returns
+    the result object of the JSON line (without the dispatch and CPU-baseline parts)."""
+    encdec = workload.startswith("ed")
+    cfg = I.encdec_workload(workload) if encdec else I.workload(workload)
     ctx = pwb.Context(0)
     fused_update = DEFAULT_FUSED_UPDATE if args.fused_update is None else bool(args.fused_update)
     fused_head_loss = DEFAULT_FUSED_HEAD_LOSS if args.fused_head_loss is None else bool(args.fused_head_loss)
@@ -335,7 +359,7 @@ def main():
             return last
 
     losses = []
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         f = one_step()
         losses.append(float(ctx.await_(f).reshape(-1)[0]))
         ctx.future_release(f)
@@ -343,18 +367,18 @@ def main():
     torch.cuda.synchronize()
     # The GEMM launches of the first `profiled_steps` timed steps are bracketed by HIP events (the roofline
     # figure); each pair costs a few microseconds of stream time, ~2 % of a step if left on throughout.
-    profiled_steps = 0 if args.graph else min(2, args.steps)
+    profiled_steps = 0 if args.graph else min(2, steps)
     if profiled_steps:
         ctx.profile_begin()
     # per-step durations as well: HIP events on the executor stream between the steps (no synchronisation)
     ext = torch.cuda.ExternalStream(ctx.stream_ptr())
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
     pending = []
     sampler = ClockPowerSampler()
     sampler.start()
     marks[0].record(ext)
-    for i in range(args.steps):
+    for i in range(steps):
         if profiled_steps and i == profiled_steps:
             ctx.profile_pause()
         pending.append(one_step())
@@ -363,8 +387,9 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     sampled = sampler.stop()
-    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
     n_gemm, gemm_ms, gemm_flops = ctx.profile_end() if profiled_steps else (0, 0.0, 0.0)
+    n_fu, fu_ms, fu_flops = ctx.profile_fused_update() if profiled_steps else (0, 0.0, 0.0)
     for f in pending:
         losses.append(float(ctx.await_(f).reshape(-1)[0]))
         ctx.future_release(f)
@@ -380,27 +405,27 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    ms_per_step = dt * 1e3 / args.steps
+    ms_per_step = dt * 1e3 / steps
     tokens_per_step = cfg.n_tokens * (1 if encdec else cfg.n_microbatch)
-    tokens_per_s = tokens_per_step * args.steps / dt
+    tokens_per_s = tokens_per_step * steps / dt
     flops = pwb.encdec_step_flops(cfg) if encdec else pwb.step_flops(cfg)
     if encdec:
-        what = (f"{args.workload}: encoder-decoder train step, {cfg.n_enc_layer} encoder + {cfg.n_dec_layer} decoder layers, "
+        what = (f"{workload}: encoder-decoder train step, {cfg.n_enc_layer} encoder + {cfg.n_dec_layer} decoder layers, "
                 f"d_model {cfg.d_model}, {cfg.n_head} heads, FFN {cfg.d_ff}, vocab {cfg.vocab}, {cfg.src_len} source + "
                 f"{cfg.tgt_len} target positions, batch {cfg.batch}, "
                 f"{'bf16 compute / fp32 master' if cfg.bf16 else 'fp32'} + {cfg.optimizer}")
         loss_key = "loss_first_last"
     else:
-        what = (f"{args.workload}: {cfg.n_layer}-layer decoder-only LM "
+        what = (f"{workload}: {cfg.n_layer}-layer decoder-only LM "
                 f"{'train step' if cfg.has_head else f'pipeline stage, {cfg.n_microbatch} micro-batches fwd-all/bwd-all'}, "
                 f"d_model {cfg.d_model}, {cfg.n_head} heads, FFN {cfg.d_ff}, vocab {cfg.vocab}, seq {cfg.seq}, "
                 f"batch {cfg.batch}, {'bf16 compute / fp32 master' if cfg.bf16 else 'fp32'} + {cfg.optimizer}")
         loss_key = "loss_first_last" if cfg.has_head else "dx0_first_last"
-    achieved = flops / (dt / args.steps) / 1e12
+    achieved = flops / (dt / steps) / 1e12
     gemm_tflops = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     result = {
         "metric": "train tokens/sec/GPU", "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
+        "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.bf16 else "f32", "data": "synthetic",
         "config": {"workload": what, "tokens_per_step": tokens_per_step, "model_tflop_per_step": round(flops / 1e12, 3),
                    "fused_update": bool(fused_update and not encdec), "fused_head_loss": bool(fused_head_loss and not encdec)},
@@ -409,13 +434,26 @@ def main():
         "ms_per_step_device": {"median": round(per_step[len(per_step) // 2], 3), "min": round(per_step[0], 3),
                                "max": round(per_step[-1], 3)},
         loss_key: [round(losses[0], 4), round(losses[-1], 4)],
-        "roofline": {"bound": "mfma", "kernel": "bf16 MFMA GEMM (gemm_ring_kernel, gemm_ring_group_kernel, gemm_bf16_kernel; all layouts)", "achieved": round(gemm_tflops, 1),
+        "roofline": {"bound": "mfma", "kernel": "bf16 MFMA GEMM (gemm_ring_kernel, gemm_ring_group_kernel, gemm_bf16_kernel; all layouts, general epilogues)", "achieved": round(gemm_tflops, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": recorded_gemm_traffic(args.workload), "launches_per_step": n_gemm // max(1, profiled_steps), "steps_with_events": profiled_steps,
+                     "traffic": recorded_gemm_traffic(workload), "launches_per_step": n_gemm // max(1, profiled_steps), "steps_with_events": profiled_steps,
                      "avg_launch_ms": round(gemm_ms / max(1, n_gemm), 4),
                      "avg_launch_gflop": round(gemm_flops / max(1, n_gemm) / 1e9, 2),
                      "gemm_ms_per_step": round(gemm_ms / max(1, profiled_steps), 3)},
     }
+    if n_fu:
+        # The weight-gradient GEMMs that apply Adam in their epilogue are a kernel instantiation of their own: MFMA work
+        # plus 26 bytes of optimizer traffic per parameter.  They are priced on both rooflines, next to the GEMM figure.
+        fused_params = sum(int(np.prod(sh)) for nm, sh, kind in I.param_shapes(cfg)
+                           if nm.split(".")[-1] in ("wqkv", "wo", "w1", "w2", "wh"))
+        result["roofline"]["fused_update_gemms"] = {
+            "kernel": "gemm_ring_kernel / gemm_ring_group_kernel with the Adam epilogue (weight-gradient layout)",
+            "launches_per_step": n_fu // profiled_steps, "ms_per_step": round(fu_ms / profiled_steps, 3),
+            "tflops": round(fu_flops / (fu_ms * 1e-3) / 1e12, 1),
+            "optimizer_gb_per_step": round(26.0 * fused_params / 1e9, 2),
+            "note": "the same launches without the epilogue's optimizer traffic take about the GEMM family's rate; "
+                    "the separate Adam launch they replace moved 30 B/param at 5.5 TB/s"}
+        result["roofline"]["gemm_ms_per_step_incl_fused_update"] = round((gemm_ms + fu_ms) / profiled_steps, 3)
     result["device"] = device_note(torch, sampled)
     clk = sampled.get("sclk_mhz_during_timed_steps", {}).get("mean")
     if clk:
@@ -424,19 +462,9 @@ def main():
         peak_at_clk = PEAK_BF16_TFLOPS * clk / 2400.0
         result["roofline"]["peak_at_sampled_clock"] = round(peak_at_clk, 1)
         result["roofline"]["frac_at_sampled_clock"] = round(gemm_tflops / peak_at_clk, 4)
-    if not args.no_dispatch:
-        result["dispatch_us_per_fn"] = dispatch_bench(ctx, pwb, I)
     model.close()
     ctx.close()
-    if not args.no_dispatch:
-        cabi = dispatch_bench_c_abi()
-        if cabi is not None:
-            result["dispatch_c_abi"] = cabi
-    if not args.no_cpu_baseline:
-        cb = cpu_baseline_encdec(cfg, pwb, I) if encdec else cpu_baseline(cfg, pwb)
-        if cb is not None:
-            result["cpu_baseline"] = cb
-    print(json.dumps(result))
+    return result
 
 
 if __name__ == "__main__":

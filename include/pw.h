@@ -102,7 +102,8 @@ typedef struct {
 
 typedef enum {
   PW_STREAM = 0,      /* enqueue every function of the chain at once on the executor stream */
-  PW_GRAPH = 1,       /* the same launches, captured once into a HIP graph and replayed */
+  PW_GRAPH = 1,       /* the same launches, captured once into a HIP graph and replayed (chains of fewer than 8
+                         single-kernel functions are enqueued as stream launches: a graph launch costs more) */
   PW_SEQUENTIAL = 2   /* wait for each function to complete before enqueuing the next: the
                          sequential-dispatch baseline of Section 5.1, for comparison only.  Its inputs must not
                          depend on an unresolved pending future: PW_ERR_NOT_READY, nothing enqueued */
@@ -531,6 +532,10 @@ pw_status pw_profile_begin(pw_ctx* ctx);
  * still returned by pw_profile_end. */
 pw_status pw_profile_pause(pw_ctx* ctx);
 pw_status pw_profile_end(pw_ctx* ctx, int64_t* launches, double* total_ms, double* total_flops);
+/* GEMM launches that carried the Adam epilogue (PW_EPI_ADAM) also do the optimizer's memory traffic - 26 bytes per
+ * output element - so pw_profile_end leaves them out of its three figures; this call returns theirs, as of the last
+ * pw_profile_end. */
+pw_status pw_profile_fused_update(pw_ctx* ctx, int64_t* launches, double* total_ms, double* total_flops);
 
 #ifdef __cplusplus
 }

@@ -159,6 +159,7 @@ _SIGS = {
     "pw_profile_begin": (C.c_int, [C.c_void_p]),
     "pw_profile_pause": (C.c_int, [C.c_void_p]),
     "pw_profile_end": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "pw_profile_fused_update": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "pw_op_gemm": (C.c_int, [C.c_void_p, C.POINTER(GemmArgs)]),
     "pw_op_gemm_pair": (C.c_int, [C.c_void_p, C.POINTER(GemmArgs), C.POINTER(GemmArgs)]),
     "pw_op_gemm_group": (C.c_int, [C.c_void_p, C.POINTER(GemmArgs), C.c_int]),
@@ -388,6 +389,12 @@ class Context:
     def profile_end(self):
         n, ms, fl = C.c_int64(), C.c_double(), C.c_double()
         self._check(lib().pw_profile_end(self._h, C.byref(n), C.byref(ms), C.byref(fl)))
+        return n.value, ms.value, fl.value
+
+    def profile_fused_update(self):
+        """(launches, ms, flops) of the GEMM launches with the Adam epilogue, as of the last profile_end()."""
+        n, ms, fl = C.c_int64(), C.c_double(), C.c_double()
+        self._check(lib().pw_profile_fused_update(self._h, C.byref(n), C.byref(ms), C.byref(fl)))
         return n.value, ms.value, fl.value
 
     # -- model

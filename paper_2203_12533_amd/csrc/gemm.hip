@@ -318,7 +318,10 @@ namespace {
 struct ProfiledLaunch {
   hipEvent_t start, stop;
   double flops;
+  bool optimizer = false;   // the launch carried the Adam epilogue: MFMA work plus 26 bytes per output element
 };
+int64_t g_fused_launches = 0;   // what the last gemm_profile_end saw of such launches
+double g_fused_ms = 0.0, g_fused_flops = 0.0;
 bool g_profile_on = false;
 std::vector<ProfiledLaunch> g_profile;
 std::vector<hipEvent_t> g_profile_free;
@@ -349,22 +352,38 @@ void gemm_profile_pause() { g_profile_on = false; }
 hipError_t gemm_profile_end(int64_t* launches, double* total_ms, double* total_flops) {
   g_profile_on = false;
   double ms = 0.0, fl = 0.0;
+  int64_t n = 0;
+  g_fused_launches = 0;
+  g_fused_ms = g_fused_flops = 0.0;
   hipError_t err = hipSuccess;
   for (auto& p : g_profile) {
     hipError_t e = hipEventSynchronize(p.stop);
     float t = 0.f;
     if (e == hipSuccess) e = hipEventElapsedTime(&t, p.start, p.stop);
     if (e != hipSuccess) err = e;
-    ms += t;
-    fl += p.flops;
+    if (p.optimizer) {
+      g_fused_launches++;
+      g_fused_ms += t;
+      g_fused_flops += p.flops;
+    } else {
+      n++;
+      ms += t;
+      fl += p.flops;
+    }
     g_profile_free.push_back(p.start);
     g_profile_free.push_back(p.stop);
   }
-  if (launches) *launches = (int64_t)g_profile.size();
+  if (launches) *launches = n;
   if (total_ms) *total_ms = ms;
   if (total_flops) *total_flops = fl;
   g_profile.clear();
   return err;
+}
+
+void gemm_profile_fused(int64_t* launches, double* total_ms, double* total_flops) {
+  if (launches) *launches = g_fused_launches;
+  if (total_ms) *total_ms = g_fused_ms;
+  if (total_flops) *total_flops = g_fused_flops;
 }
 
 static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a);
@@ -372,7 +391,7 @@ static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a);
 hipError_t launch_gemm(hipStream_t s, const GemmArgs& a) {
   const bool timed = g_profile_on && a.dtype == kBF16 && a.M > 0 && a.N > 0;
   if (!timed) return launch_gemm_impl(s, a);
-  ProfiledLaunch p{profile_event(), profile_event(), 2.0 * (double)a.M * (double)a.N * (double)a.K};
+  ProfiledLaunch p{profile_event(), profile_event(), 2.0 * (double)a.M * (double)a.N * (double)a.K, a.epilogue == kEpiAdam};
   if (!p.start || !p.stop) return hipErrorOutOfMemory;
   hipError_t e = hipEventRecord(p.start, s);
   if (e == hipSuccess) e = launch_gemm_impl(s, a);
@@ -596,7 +615,7 @@ hipError_t launch_gemm_group(hipStream_t s, const GemmArgs* a, int n) {
   GemmBf16Params p[kRingGroupMax];
   for (int i = 0; i < n; ++i) p[i] = bf16_params_of(a[order[i]], 256);
   const bool timed = g_profile_on;
-  ProfiledLaunch pl{nullptr, nullptr, flops};
+  ProfiledLaunch pl{nullptr, nullptr, flops, a[0].epilogue == kEpiAdam};
   hipError_t err = hipSuccess;
   if (timed) {
     pl.start = profile_event();

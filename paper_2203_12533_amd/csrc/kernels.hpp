@@ -155,6 +155,9 @@ hipError_t launch_gemm_group(hipStream_t s, const GemmArgs* a, int n);
 void gemm_profile_begin();
 void gemm_profile_pause();   // stop bracketing launches; what was recorded so far stays for gemm_profile_end
 hipError_t gemm_profile_end(int64_t* launches, double* total_ms, double* total_flops);
+// Launches that carried the Adam epilogue are kept out of those figures (they do the optimizer's memory traffic as
+// well); this returns theirs, as of the last gemm_profile_end.
+void gemm_profile_fused(int64_t* launches, double* total_ms, double* total_flops);
 // One-time per-process set-up of kernel attributes (large dynamic LDS); call once before any capture.
 hipError_t gemm_init();
 

@@ -572,6 +572,13 @@ pw_status pw_chain(pw_ctx* c, const pw_fn* fns, int n_fns, const pw_future* in, 
     if (!fin[i]) return fail(c, PW_ERR_INVALID, "input %d is not a live future", i);
     specs[i] = fin[i]->spec;
   }
+  // A HIP-graph launch has a fixed cost worth about eight stream launches of a trivial kernel: shorter chains of
+  // single-kernel functions are enqueued as stream launches (same launches, same results).
+  if (mode == PW_GRAPH && n_fns < 8) {
+    bool single_kernels = true;
+    for (int i = 0; i < n_fns; ++i) single_kernels = single_kernels && (is_scalar_kind(recs[i]->desc.kind) || recs[i]->desc.kind == PW_FN_ADD2);
+    if (single_kernels) mode = PW_STREAM;
+  }
   if (mode == PW_SEQUENTIAL) {
     // This baseline waits on the host for every link.  An input that hangs on an unresolved pending future would
     // make it wait - holding the context's lock, so that pw_future_resolve could not get in - until the gate gives up.

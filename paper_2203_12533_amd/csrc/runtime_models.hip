@@ -320,4 +320,10 @@ pw_status pw_profile_end(pw_ctx* c, int64_t* launches, double* total_ms, double*
   return PW_OK;
 }
 
+pw_status pw_profile_fused_update(pw_ctx* c, int64_t* launches, double* total_ms, double* total_flops) {
+  if (!c) return PW_ERR_INVALID;
+  gemm_profile_fused(launches, total_ms, total_flops);
+  return PW_OK;
+}
+
 }  // extern "C"

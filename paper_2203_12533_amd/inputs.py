@@ -72,6 +72,50 @@ def normal(seed: int, tid: int, n: int, std: float = 1.0) -> np.ndarray:
     return out
 
 
+def normal_torch(seed: int, tid: int, n: int, std: float, device):
+    """The generator of normal() evaluated by torch on `device` (a GPU for the 0.7 G parameters of the measured
+    workload, which numpy would take minutes over): the same counters, the same splitmix64 bits (int64 arithmetic
+    wraps like uint64; right shifts are made logical by masking), the same Box-Muller formula in float64.  The 64
+    random bits are identical to numpy's; log / cos may differ from numpy's in the last place of float64, which the
+    rounding to float32 hides for all but a few values in a million."""
+    import torch
+
+    def lsr(z, k):                                   # logical shift right of the uint64 held in an int64
+        return (z >> k) & ((1 << (64 - k)) - 1)
+
+    def mix(z):
+        z = (z ^ lsr(z, 30)) * _i64(_M1)
+        z = (z ^ lsr(z, 27)) * _i64(_M2)
+        return z ^ lsr(z, 31)
+
+    key, gold = _i64(_key(seed, tid)), _i64(_GOLD)
+    out = torch.empty(n, dtype=torch.float32, device=device)
+    for s in range(0, n, _CHUNK):
+        m = min(_CHUNK, n - s)
+        idx = torch.arange(2 * s + 1, 2 * (s + m) + 1, dtype=torch.int64, device=device)
+        r = lsr(mix(key + idx * gold), 11)
+        u1 = (r[0::2].to(torch.float64) + 1.0) * (1.0 / (1 << 53))
+        u2 = r[1::2].to(torch.float64) * (1.0 / (1 << 53))
+        out[s:s + m] = (std * torch.sqrt(-2.0 * torch.log(u1)) * torch.cos(2.0 * math.pi * u2)).to(torch.float32)
+    return out
+
+
+def _i64(u) -> int:
+    """The int64 with the bit pattern of a uint64."""
+    u = int(u)
+    return u - (1 << 64) if u >= (1 << 63) else u
+
+
+def param_torch(cfg, name: str, shape, kind: str, device, seed: int = 1234):
+    """One parameter tensor of lm_params / encdec_params (perturb=False), flat float32, drawn on `device`."""
+    import torch
+    n = int(np.prod(shape))
+    if kind == "matrix":
+        t = normal_torch(seed, _tid(name), n, cfg.init_std, device)
+        return t.to(torch.bfloat16).to(torch.float32) if cfg.bf16 else t      # round-to-nearest-even, as round_to_bf16
+    return (torch.ones if kind == "gain" else torch.zeros)(n, dtype=torch.float32, device=device)
+
+
 def tokens(seed: int, tid: int, shape, vocab: int) -> np.ndarray:
     """int32 token ids uniform over [0, vocab)."""
     n = int(np.prod(shape))

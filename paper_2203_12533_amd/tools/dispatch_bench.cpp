@@ -92,11 +92,51 @@ double throughput(int count, double budget_s, F program) {
 }  // namespace
 
 int main(int argc, char** argv) {
-  bool quick = false;
-  for (int i = 1; i < argc; ++i) quick = quick || std::strcmp(argv[i], "--quick") == 0;
+  bool quick = false, gaps = false;
+  for (int i = 1; i < argc; ++i) {
+    quick = quick || std::strcmp(argv[i], "--quick") == 0;
+    gaps = gaps || std::strcmp(argv[i], "--gaps") == 0;
+  }
   if (pw_ctx_create(0, nullptr, &ctx) != PW_OK) {
     std::fprintf(stderr, "no usable gfx950 GPU\n");
     return 2;
+  }
+  if (gaps) {
+    // For a kernel trace (rocprofv3 --kernel-trace -- dispatch_bench --gaps): the same chain of 128 trivial
+    // computations dispatched four ways, 20 times each, the phases 100 ms apart so that the trace can be cut at the
+    // pauses.  The device-side launch gap of a mode is next.start - previous.end between consecutive kernels of a chain.
+    constexpr int L = 128, reps = 20;
+    pw_future x = input();
+    pw_fn one = compile(PW_FN_ADD_CONST, 1.f, 0.f, 1);
+    std::vector<pw_fn> chain(L, one);
+    const char* names[4] = {"chained_stream", "chained_graph", "sequential", "op_by_op"};
+    for (int phase = 0; phase < 4; ++phase) {
+      std::this_thread::sleep_for(std::chrono::milliseconds(100));
+      const double t0 = now_s();
+      for (int r = 0; r < reps + 2; ++r) {      // two warm-up chains (graph capture) count as part of the phase
+        if (phase < 3) {
+          pw_future out;
+          CHECK(pw_chain(ctx, chain.data(), L, &x, 1, &out, 1, phase == 0 ? PW_STREAM : phase == 1 ? PW_GRAPH : PW_SEQUENTIAL));
+          CHECK(pw_await(ctx, out, nullptr, 0));
+          CHECK(pw_future_release(ctx, out));
+        } else {
+          pw_future cur = x;
+          for (int i = 0; i < L; ++i) {
+            pw_future out;
+            CHECK(pw_run_fn(ctx, one, &cur, 1, &out, 1));
+            CHECK(pw_await(ctx, out, nullptr, 0));
+            if (i) CHECK(pw_future_release(ctx, cur));
+            cur = out;
+          }
+          CHECK(pw_future_release(ctx, cur));
+        }
+      }
+      std::printf("{\"bench\": \"launch_gaps\", \"phase\": %d, \"mode\": \"%s\", \"chains\": %d, \"chain_length\": %d, "
+                  "\"wall_us_per_computation\": %.3f}\n", phase, names[phase], reps + 2, L, (now_s() - t0) * 1e6 / ((reps + 2) * L));
+    }
+    CHECK(pw_future_release(ctx, x));
+    pw_ctx_destroy(ctx);
+    return 0;
   }
   CHECK(pw_ctx_set_executors(ctx, 64));
   const double budget = quick ? 0.05 : 0.25;

@@ -128,3 +128,23 @@ def test_bench_refuses_more_than_one_gpu_and_its_sampler_survives_missing_sysfs(
     note = s.stop()
     assert note["sclk_mhz_during_timed_steps"]["mean"] == 2100 and note["board_power_w_during_timed_steps"]["max"] == 1350
     assert note["board_power_cap_w"] == 1400
+
+
+def test_device_version_of_the_input_generator_draws_the_same_numbers():
+    """bench.py and the full-size GPU tests draw the 0.7 G weights of the measured workload with inputs.normal_torch;
+    on the CPU it must reproduce inputs.normal: identical random bits, values equal after the rounding to float32 up
+    to rare last-place differences of the float64 logarithm / cosine, and equal distribution parameters."""
+    import numpy as np
+    import torch
+    n = 200_000
+    for seed, tid, std in ((1234, 77, 0.02), (5, I._tid("l3.w1"), 1.0)):
+        a = I.normal(seed, tid, n, std)
+        b = I.normal_torch(seed, tid, n, std, "cpu").numpy()
+        assert (a != b).mean() < 1e-4
+        assert np.abs(a - b).max() <= np.abs(a).max() * 2.0 ** -22
+    cfg = I.workload("cfg3").with_(n_layer=1, vocab=512, seq=16)
+    ref = I.lm_params(cfg)
+    for name, shape, kind in I.param_shapes(cfg):
+        got = I.param_torch(cfg, name, shape, kind, "cpu").numpy().reshape(shape)
+        assert (got != ref[name]).mean() < 1e-4, name
+        assert np.array_equal(I.round_to_bf16(got), got)          # bf16-representable

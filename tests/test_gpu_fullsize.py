@@ -204,14 +204,8 @@ def test_full_cfg3_step_properties():
     def run():
         with pwb.Context(0) as ctx:
             model = ctx.model(CFG3)
-            gen = torch.Generator(device="cuda")
-            gen.manual_seed(99)
-            for name, shape, kind in I.param_shapes(CFG3):
-                n = int(np.prod(shape))
-                if kind == "matrix":
-                    t = (torch.randn(n, device="cuda", generator=gen) * CFG3.init_std).to(torch.bfloat16).float()
-                else:
-                    t = torch.ones(n, device="cuda") if kind == "gain" else torch.zeros(n, device="cuda")
+            for name, shape, kind in I.param_shapes(CFG3):      # the workload's seeded weights, drawn on the GPU
+                t = I.param_torch(CFG3, name, shape, kind, "cuda")
                 torch.cuda.synchronize()
                 model.import_device(pwb.PW_PARAMS, name, t.data_ptr())
             step = model.compile_train_step()
@@ -362,6 +356,70 @@ def test_one_layer_step_with_fused_update_and_fused_head_loss(one_layer, fused_u
         sure = np.abs(g_ref) > 0.05 * np.sqrt(np.mean(g_ref ** 2))        # the sign of g is beyond the bf16 error there
         moved = (new1[k].astype(np.float64) - params[k].astype(np.float64)).reshape(-1)[sure]
         assert (np.sign(moved) == -np.sign(g_ref[sure])).mean() > 0.999, k
+
+
+def test_one_layer_step_at_cfg5_width_matches_oracle(orc):
+    """The wide-layer workload's width end to end against the oracle: one layer with d_model 8192 and 64 heads of 128
+    (LayerNorm's block-per-row path, contraction length 8192 in the ring-buffered GEMM, 3072-tile weight gradients,
+    the 128 x 256-tile kernel for the out-projection), 2 x 256 tokens; FFN width and vocabulary are cut (4096, 2048)
+    so that the fp64 oracle's 0.37 G parameters fit the host and its step takes tens of seconds.  Loss and every
+    gradient tensor are compared, weights drawn with the workload's own standard deviation."""
+    c5 = I.workload("cfg5")
+    cfg = c5.with_(n_layer=1, batch=2, seq=256, d_ff=4096, vocab=2048)
+    assert cfg.d_model == 8192 and cfg.n_head == 64 and cfg.head_dim == 128
+    tok = I.lm_tokens(cfg)
+    rng = np.random.default_rng(22)
+    params = {}
+    for name, shape, kind in I.param_shapes(cfg):
+        a = rng.standard_normal(int(np.prod(shape)), dtype=np.float32) * np.float32(cfg.init_std)
+        if kind == "gain":
+            a += np.float32(1.0)
+        params[name] = I.round_to_bf16(a).reshape(shape)       # biases and gains perturbed too
+    ref = orc.lm_train_step(cfg, params, tok, update=False)
+    with pwb.Context(0) as ctx:
+        model = ctx.model(cfg)
+        model.load_params(params)
+        step = model.compile_train_step()
+        ft = ctx.future_from_host(tok)
+        fl = ctx.train_step(step, ft)
+        loss = float(ctx.await_(fl)[0])
+        assert abs(loss - ref["loss"]) / abs(ref["loss"]) < 2e-2, (loss, ref["loss"])
+        worst = ("", 0.0)
+        for k in params:
+            g = model.export(pwb.PW_GRADS, k).reshape(ref["grads"][k].shape)
+            worst = max(worst, (k, rel_l2(g, ref["grads"][k])), key=lambda t: t[1])
+            assert_close(g, ref["grads"][k], 2e-2, k)
+        print("worst gradient error", worst)
+        model.close()
+
+
+@pytest.mark.parametrize("name,n_out,k_in", [("qkv", 3 * 8192, 8192), ("ffn1", 32768, 8192), ("ffn2", 8192, 32768)])
+def test_gemms_at_cfg5_shape(ctx, orc, name, n_out, k_in):
+    """Forward, data-gradient and weight-gradient GEMMs at the wide-layer workload's shapes (4096 tokens; contraction
+    and leading dimensions of 8192 and 32768), sampled rows of each product recomputed by the oracle from the very
+    operands the kernel read."""
+    n = I.workload("cfg5").n_tokens
+    x, w = _bf16_randn((n, k_in), 31), _bf16_randn((k_in, n_out), 32, 0.01)
+    out = torch.empty((n, n_out), dtype=torch.bfloat16, device="cuda")
+    ctx.gemm(dtype=pwb.PW_BF16, a_kmajor=0, b_kmajor=1, M=n, N=n_out, K=k_in, lda=k_in, ldb=n_out, ldc=n_out,
+             epilogue=pwb.PW_EPI_STORE, out_dtype=pwb.PW_BF16, accumulate=0, A=ptr(x), B=ptr(w), C=ptr(out))
+    dy = _bf16_randn((n, n_out), 33)
+    dx = torch.empty((n, k_in), dtype=torch.bfloat16, device="cuda")
+    ctx.gemm(dtype=pwb.PW_BF16, a_kmajor=0, b_kmajor=0, M=n, N=k_in, K=n_out, lda=n_out, ldb=n_out, ldc=k_in,
+             epilogue=pwb.PW_EPI_STORE, out_dtype=pwb.PW_BF16, accumulate=0, A=ptr(dy), B=ptr(w), C=ptr(dx))
+    dw = torch.empty((k_in, n_out), dtype=torch.float32, device="cuda")
+    ctx.gemm(dtype=pwb.PW_BF16, a_kmajor=1, b_kmajor=1, M=k_in, N=n_out, K=n, lda=k_in, ldb=n_out, ldc=n_out,
+             epilogue=pwb.PW_EPI_STORE, out_dtype=pwb.PW_F32, accumulate=0, A=ptr(x), B=ptr(dy), C=ptr(dw))
+    ctx.synchronize()
+    rows = np.array([0, 255, 256, 2049, n - 1])
+    wh = host(w)
+    assert_close(host(out[rows]), orc.linear_fwd(host(x[rows]), wh), 4e-3, "forward")
+    rdx, _, _ = orc.linear_bwd(np.zeros((len(rows), k_in)), wh, host(dy[rows]))
+    assert_close(host(dx[rows]), rdx, 4e-3, "data gradient")
+    del wh
+    cols = np.array([0, 7, 256, k_in - 1])                       # sampled input features = rows of dW
+    _, rdw, _ = orc.linear_bwd(host(x[:, cols]), np.zeros((len(cols), n_out)), host(dy))
+    assert_close(host(dw[cols]), rdw, 1e-5, "weight gradient")
 
 
 def test_one_layer_encoder_decoder_step_at_full_layer_width_matches_oracle(orc):
