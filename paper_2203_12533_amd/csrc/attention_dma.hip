@@ -19,6 +19,8 @@
 // Queries, keys and values come with their own pointers, row strides and lengths (MhaDev), so one set of kernels
 // serves the packed causal self-attention of a decoder, the unmasked self-attention of an encoder and attention
 // of decoder queries over encoder keys; CAUSAL is a template parameter (it decides which tiles are visited).
+#include <type_traits>
+
 #include "attention_common.hpp"
 #include "common.hpp"
 #include "kernels.hpp"
@@ -44,6 +46,11 @@ __device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 
 
 __device__ __forceinline__ void dma16(const bf16* g, uint32_t lds_off) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_off) : "memory", "m0");
+}
+
+// 4 bytes per lane straight into LDS at lds_off + 4*lane (per-row statistics of a tile).
+__device__ __forceinline__ void dma4(const float* g, uint32_t lds_off) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" : : "v"(g), "s"(lds_off) : "memory", "m0");
 }
 
 // Same with a wave-uniform base pointer in scalar registers and a 32-bit per-lane byte offset.
@@ -347,18 +354,138 @@ __global__ __launch_bounds__(kNT, 2) void attn_dq_dma_kernel(MhaDev a, const bf1
 }
 
 // ===================================================================================================
-// dK, dV: block = 128 keys of one (batch, head); wave = 32 keys; query tiles of 64 (two 32-row halves)
+// dK, dV: block = 128 keys of one (batch, head); wave = 32 keys; query tiles of 64 as two 32-query blocks.
+// Software-pipelined: the four phases of a block - first products S and dP, softmax / dS arithmetic on the
+// vector ALU, second products into dV and dK - no longer run one after the other.  A wave has one SIMD to itself
+// here (its two output accumulators, the K / V fragments and the scores leave no room for a second wave), so
+// nothing else hides the latencies: the first products of block n+1 are issued between the vector instructions
+// of block n (one score element per MFMA: about as many vector cycles as the MFMA occupies the matrix pipe), and
+// the transposed LDS reads of the second products run two MFMAs ahead.  Three tiles are resident (ring of
+// three stages): the first products of the next tile start while the second products of the current one still
+// read theirs.
 // ===================================================================================================
+struct DkvStats { float lq[16], dq[16]; };
+
+// This lane's log-sum-exp (scaled for exp2) and delta of the 16 queries its score registers stand for (block hb of
+// the tile).
+// (Raw values: the scaling of the log-sum-exp is left to the user, so that the reads can be issued a phase early.)
+__device__ __forceinline__ void load_stats(const float* Ls, const float* Ds, int hb, int half, DkvStats& st) {
+#pragma unroll
+  for (int g = 0; g < 2; ++g)
+#pragma unroll
+    for (int v4 = 0; v4 < 2; ++v4) {
+      const int base = hb * 32 + 16 * g + 8 * half + 4 * v4;
+      const float4 l = *reinterpret_cast<const float4*>(Ls + base);
+      const float4 d = *reinterpret_cast<const float4*>(Ds + base);
+      const int r = 8 * g + 4 * v4;
+      st.lq[r] = l.x; st.lq[r + 1] = l.y; st.lq[r + 2] = l.z; st.lq[r + 3] = l.w;
+      st.dq[r] = d.x; st.dq[r + 1] = d.y; st.dq[r + 2] = d.z; st.dq[r + 3] = d.w;
+    }
+}
+
+// First products of block `next` (sn = S, dpn = dP against the tile rows rbn .. rbn+31 of Qn / Gn), with - when
+// HAVE_CUR - the arithmetic of block `cur` between the MFMAs: s becomes P = exp2(S c2 - lse), ds = P (dP - delta).
+// (Masked scores are handled through the statistics: a log-sum-exp of +inf makes P an exact zero.)
+template <bool HAVE_NEXT, bool HAVE_CUR>
+__device__ __forceinline__ void dkv_front(const bf16* __restrict__ Qn, const bf16* __restrict__ Gn, int rbn,
+                                          const bf16x8* kf, const bf16x8* vf, f32x16& sn, f32x16& dpn, f32x16& s,
+                                          const f32x16& dp, const DkvStats& st, float c2, bf16x8* pf, bf16x8* dsf) {
+  constexpr int kDepth = 3, KK = HD / 16;
+  const int lane = threadIdx.x & 63;
+  const int row = rbn + perm_row(lane & 31);
+  const int t = (lane >> 5) ^ swz(row);
+  const bf16* aq = Qn + row * HD;
+  const bf16* ag = Gn + row * HD;
+  bf16x8 fq[kDepth], fg[kDepth];
+  if (HAVE_NEXT) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sn[r] = dpn[r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < kDepth; ++kk) {
+      fq[kk] = *reinterpret_cast<const bf16x8*>(aq + ((2 * kk) ^ t) * 8);
+      fg[kk] = *reinterpret_cast<const bf16x8*>(ag + ((2 * kk) ^ t) * 8);
+    }
+  }
+  f32x16 ds;
+  auto element = [&](int r) {
+    if (HAVE_CUR) {
+      const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -st.lq[r]));
+      s[r] = p;
+      ds[r] = p * (dp[r] - st.dq[r]);
+    }
+  };
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    if (HAVE_NEXT) {
+      sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[kk % kDepth], kf[kk], sn, 0, 0, 0);
+      if (kk + kDepth < KK) fq[kk % kDepth] = *reinterpret_cast<const bf16x8*>(aq + ((2 * (kk + kDepth)) ^ t) * 8);
+    }
+    element(2 * kk);
+    __builtin_amdgcn_sched_barrier(0);
+    if (HAVE_NEXT) {
+      dpn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fg[kk % kDepth], vf[kk], dpn, 0, 0, 0);
+      if (kk + kDepth < KK) fg[kk % kDepth] = *reinterpret_cast<const bf16x8*>(ag + ((2 * (kk + kDepth)) ^ t) * 8);
+    }
+    element(2 * kk + 1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  if (HAVE_CUR) {
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2) {
+      pf[b2] = pack8(s, b2 * 8);
+      dsf[b2] = pack8(ds, b2 * 8);
+    }
+  }
+}
+
+// Second products of a block: dv += Gs^T . P and dk += Qs^T . dS over the 32 queries at tile rows rb .. rb+31,
+// 16 MFMAs whose transposed operand reads run kAhead steps ahead.
+__device__ __forceinline__ void dkv_back(const bf16* __restrict__ Qs, const bf16* __restrict__ Gs, int rb, const bf16x8* pf,
+                                         const bf16x8* dsf, f32x16* dk, f32x16* dv) {
+  constexpr int kAhead = 2, kSteps = 16;
+  const int lane = threadIdx.x & 63;
+  const int grp = lane >> 4, L = lane & 15;
+  const int f0 = 16 * (grp & 1) + 4 * (L & 3);
+  // step j: b2 = j / 8 (16-query half of the block), mat = (j / 4) % 2 (0: dO -> dV, 1: Q -> dK), cb = j % 4
+  auto read = [&](int j) {
+    const int b2 = j >> 3, mat = (j >> 2) & 1, cb = j & 3;
+    const bf16* tile = mat ? Qs : Gs;
+    const int row0 = rb + b2 * 16 + 8 * (grp >> 1) + (L >> 2);
+    union { bf16x8 v; short4v h[2]; } u;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int row = row0 + 4 * t;
+      const int chunk = (cb * 32 + f0) >> 3;
+      const bf16* p = tile + row * HD + ((chunk ^ swz(row)) << 3) + (f0 & 7);
+      u.h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)p);
+    }
+    return u.v;
+  };
+  bf16x8 fr[kAhead + 1];
+#pragma unroll
+  for (int j = 0; j < kAhead; ++j) fr[j] = read(j);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int j = 0; j < kSteps; ++j) {
+    if (j + kAhead < kSteps) fr[(j + kAhead) % (kAhead + 1)] = read(j + kAhead);
+    const int b2 = j >> 3, mat = (j >> 2) & 1, cb = j & 3;
+    if (mat) dk[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % (kAhead + 1)], dsf[b2], dk[cb], 0, 0, 0);
+    else dv[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % (kAhead + 1)], pf[b2], dv[cb], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 template <bool CAUSAL>
 __global__ __launch_bounds__(kNT) void attn_dkv_dma_kernel(MhaDev a, const bf16* __restrict__ dout,
-                                                           const float* __restrict__ lse, const float* __restrict__ delta,
-                                                           bf16* __restrict__ dk_out, bf16* __restrict__ dv_out, int64_t lddkv) {
-  constexpr int BQ = 64;
+                                                            const float* __restrict__ lse, const float* __restrict__ delta,
+                                                            bf16* __restrict__ dk_out, bf16* __restrict__ dv_out, int64_t lddkv) {
+  constexpr int BQ = 64, kStages = 3;
   constexpr int kTile = BQ * HD;
   extern __shared__ __attribute__((aligned(1024))) bf16 smem[];          // [stage][Q | dO], then the statistics
-  float (*Ls)[BQ] = reinterpret_cast<float (*)[BQ]>(smem + 2 * 2 * kTile);
-  float (*Ds)[BQ] = Ls + 2;
-  const int T = a.Tq, Tk = a.Tk, H = a.H;               // T: number of queries (the streamed side)
+  float (*Ls)[BQ] = reinterpret_cast<float (*)[BQ]>(smem + kStages * 2 * kTile);
+  float (*Ds)[BQ] = Ls + kStages;
+  const int T = a.Tq, Tk = a.Tk, H = a.H;
   const int d = H * HD;
   const int64_t ld = a.ldq;
   int bh, kblk;                                         // causal: first key blocks see the most queries, they come first
@@ -373,6 +500,9 @@ __global__ __launch_bounds__(kNT) void attn_dkv_dma_kernel(MhaDev a, const bf16*
   const float c2 = kLog2e * scale;
   const uint32_t smem_off = (uint32_t)(uintptr_t)(lds_ptr)smem;
 
+  TileOffsets<BQ> to_q, to_g;
+  to_q.init(ld, wave, lane);
+  to_g.init(d, wave, lane);
   bf16x8 kf[HD / 16], vf[HD / 16];
   load_row_frags<HD>(a.k + (int64_t)b * Tk * a.ldkv + h * HD, a.ldkv, k0, Tk, kf);
   load_row_frags<HD>(a.v + (int64_t)b * Tk * a.ldkv + h * HD, a.ldkv, k0, Tk, vf);
@@ -387,80 +517,114 @@ __global__ __launch_bounds__(kNT) void attn_dkv_dma_kernel(MhaDev a, const bf16*
 
   const int first_tile = CAUSAL ? (kblk * 128) / BQ : 0;
   const int n_tiles = (T + BQ - 1) / BQ;
-  TileOffsets<BQ> to_q, to_g;
-  to_q.init(ld, wave, lane);
-  to_g.init(d, wave, lane);
+  // A tile = 64 rows of Q and of dO plus the 64 queries' log-sum-exp and delta; all of it travels global -> LDS
+  // directly (no destination registers: the compiler then has no pending load to wait for in the middle of the
+  // pipeline, and the loads stay in flight until the explicit wait in front of the tile's barrier).  Statistics of
+  // rows past the end are fetched from the last row and masked where they are used.
+  const float* lse_bh = lse + (int64_t)bh * T;
+  const float* delta_bh = delta + (int64_t)bh * T;
+  const uint32_t stats_off = smem_off + kStages * 2 * kTile * 2;
   auto issue = [&](int t) {
-    const uint32_t st = smem_off + (uint32_t)(t & 1) * (2 * kTile * 2);
+    const uint32_t st = smem_off + (uint32_t)(t % kStages) * (2 * kTile * 2);
     issue_tile<BQ>(qbase, ld, t * BQ, T - 1, to_q, st, wave, lane);
     issue_tile<BQ>(gbase, d, t * BQ, T - 1, to_g, st + kTile * 2, wave, lane);
-  };
-  // per-query statistics of a tile: fetched one tile ahead into registers by the first 64 threads
-  float l_next = 0.f, d_next = 0.f;
-  auto fetch_stats = [&](int t) {
-    if (threadIdx.x < BQ) {
-      const int i = t * BQ + threadIdx.x;
-      l_next = i < T ? lse[(int64_t)bh * T + i] * kLog2e : INFINITY;   // +inf: P = 0 for queries past the end
-      d_next = i < T ? delta[(int64_t)bh * T + i] : 0.f;
+    if (wave == 0) {
+      const int i = min(t * BQ + lane, T - 1);
+      dma4(lse_bh + i, stats_off + (uint32_t)(t % kStages) * (BQ * 4));
+      dma4(delta_bh + i, stats_off + (uint32_t)(kStages + t % kStages) * (BQ * 4));
     }
   };
-  fetch_stats(first_tile);
+  // Block n = 2 t + hb covers queries 32 n .. 32 n + 31.  Under the causal mask this wave's keys see the blocks from
+  // k0 / 32 on; it starts with the tile that holds that block (waves 2 and 3 of a workgroup one tile after waves 0
+  // and 1) and from there on runs every block - an odd first block's even neighbour is computed fully masked, which
+  // keeps the pipeline below free of per-wave branches.
+  auto tile_q = [&](int n) { return smem + ((n >> 1) % kStages) * (2 * kTile); };
+  // What happens between the two blocks of tile t: tile t + 1 has to have landed, for every wave; behind the barrier
+  // nobody reads tile t - 1 any more, so its stage takes tile t + 2.
+  auto advance = [&](int t) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (t + 2 < n_tiles) issue(t + 2);
+  };
+
   issue(first_tile);
-  for (int t = first_tile; t < n_tiles; ++t) {
-    const int i0 = t * BQ;
-    if (threadIdx.x < BQ) {          // stage t&1 of the statistics was last read two tiles ago
-      Ls[t & 1][threadIdx.x] = l_next;
-      Ds[t & 1][threadIdx.x] = d_next;
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the two LDS stores above are done before the barrier
-    wait_and_sync();
-    if (t + 1 < n_tiles) {
-      issue(t + 1);
-      fetch_stats(t + 1);
-    }
-    const bf16* Qs = smem + (t & 1) * (2 * kTile);
-    const bf16* Gs = Qs + kTile;
+  if (first_tile + 1 < n_tiles) {
+    issue(first_tile + 1);
+    // all but the second tile: 2 x 4 direct loads per wave, two more (the statistics) in wave 0
+    if (wave == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (BQ / 16) + 2) : "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (BQ / 16)) : "memory");
+  } else {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+
+  // Two sets of score registers: the even block of a tile lives in (s0, dp0), the odd one in (s1, dp1), so nothing is
+  // ever copied from "next" to "current".
+  f32x16 s0, dp0, s1, dp1;
+  bf16x8 pf[2], dsf[2];
+  DkvStats st;
+  // One step of the pipeline: the arithmetic of block n (scores in s, dp) between the first products of block n + 1
+  // (into sn, dpn; NEXT: there is one), then the second products of block n.
+  auto step = [&](int n, auto next, f32x16& s, f32x16& dp, f32x16& sn, f32x16& dpn) {
+    constexpr bool NEXT = decltype(next)::value;
+    const int hb = n & 1, t = n >> 1;
+    const bf16* Qs = tile_q(n);
+    const bf16* Qn = tile_q(n + 1);
+    // st holds the block's raw statistics, read from LDS during the previous step
 #pragma unroll
-    for (int hb = 0; hb < 2; ++hb) {                     // the two 32-query halves of the tile
-      const int ib = i0 + hb * 32;
-      if (CAUSAL && ib + 31 < k0) continue;              // every query of this half precedes this wave's keys
-      f32x16 s = first_product(Qs, hb * 32, kf);         // S[query][key]
-      f32x16 dp = first_product(Gs, hb * 32, vf);        // dP = dO . V^T
-      if (CAUSAL && ib < k0 + 31) {                      // diagonal: a key may not see an earlier query
+    for (int r = 0; r < 16; ++r) st.lq[r] *= kLog2e;
+    const int ib = 32 * n;
+    // (The empty volatile statements tie the values to the rare branches below: without them the compiler turns the
+    // two fix-ups into selects that every block pays for - some 130 vector instructions with their wait states.)
+    if (CAUSAL && ib < k0 + 31) {        // a block on (or before) the diagonal: register r stands for query ib + reg_row(r, half)
+      const int thr = key - ib - 8 * half;
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (key > ib + reg_row(r, half)) s[r] = -INFINITY;
+      for (int r = 0; r < 16; ++r) {
+        if (16 * (r >> 3) + (r & 7) < thr) st.lq[r] = INFINITY;     // the key may not see this earlier query: P = 0
+        asm volatile("" : "+v"(st.lq[r]));
       }
-      f32x16 ds;
-#pragma unroll
-      for (int g = 0; g < 2; ++g)
-#pragma unroll
-        for (int v4 = 0; v4 < 2; ++v4) {
-          const int base = hb * 32 + 16 * g + 8 * half + 4 * v4;
-          const float4 lq = *reinterpret_cast<const float4*>(&Ls[t & 1][base]);
-          const float4 dq = *reinterpret_cast<const float4*>(&Ds[t & 1][base]);
-          const float lqa[4] = {lq.x, lq.y, lq.z, lq.w}, dqa[4] = {dq.x, dq.y, dq.z, dq.w};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int r = 8 * g + 4 * v4 + e;
-            const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lqa[e]));
-            s[r] = p;
-            ds[r] = p * (dp[r] - dqa[e]);
-          }
-        }
-#pragma unroll
-      for (int b2 = 0; b2 < 2; ++b2) {
-        second_product(Gs, hb * 32 + b2 * 16, pack8(s, b2 * 8), dv);    // dV^T += dO^T . P
-        second_product(Qs, hb * 32 + b2 * 16, pack8(ds, b2 * 8), dk);   // dK^T += Q^T . dS
-      }
-      // Register classes: the two output accumulators are only ever touched by MFMAs, so they belong in the
-      // accumulation registers; the K/V fragments feed MFMAs as ordinary operands.  Without the hint the
-      // allocator parks the fragments and the score accumulators there and copies them back and forth.
-#pragma unroll
-      for (int cb = 0; cb < HD / 32; ++cb) asm volatile("" : "+a"(dk[cb]), "+a"(dv[cb]));
-#pragma unroll
-      for (int kk = 0; kk < HD / 16; ++kk) asm volatile("" : "+v"(kf[kk]), "+v"(vf[kk]));
     }
+    if (ib + 31 >= T) {                  // the block straddles the end of the queries
+      const int thr = T - ib - 8 * half;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        if (16 * (r >> 3) + (r & 7) >= thr) st.lq[r] = INFINITY;    // no such query: P = 0
+        asm volatile("" : "+v"(st.lq[r]));
+      }
+    }
+    dkv_front<NEXT, true>(Qn, Qn + kTile, (hb ^ 1) * 32, kf, vf, sn, dpn, s, dp, st, c2, pf, dsf);
+    // the next block's statistics travel to registers under the second products (its tile is resident: see advance)
+    if (NEXT) load_stats(Ls[((n + 1) >> 1) % kStages], Ds[((n + 1) >> 1) % kStages], hb ^ 1, half, st);
+    dkv_back(Qs, Qs + kTile, hb * 32, pf, dsf, dk, dv);
+    // Register classes: the output accumulators and the K / V fragments are only ever touched by MFMAs and live in
+    // the accumulation registers; the scores are worked on by the vector ALU and stay in ordinary registers, so no
+    // MFMA result has to be copied across (with the wait states that costs).
+#pragma unroll
+    for (int cb = 0; cb < HD / 32; ++cb) asm volatile("" : "+a"(dk[cb]), "+a"(dv[cb]));
+#pragma unroll
+    for (int kk = 0; kk < HD / 16; ++kk) asm volatile("" : "+v"(kf[kk]), "+v"(vf[kk]));
+  };
+  using yes = std::integral_constant<bool, true>;
+  using no = std::integral_constant<bool, false>;
+  int t0 = first_tile;
+  bool any = true;
+  if (CAUSAL && wave >= 2) {             // this wave's first tile is the next one
+    any = first_tile + 1 < n_tiles;
+    if (any) advance(first_tile);
+    t0 = first_tile + 1;
+  }
+  if (any) {
+    load_stats(Ls[t0 % kStages], Ds[t0 % kStages], 0, half, st);
+    dkv_front<true, false>(tile_q(2 * t0), tile_q(2 * t0) + kTile, 0, kf, vf, s0, dp0, s0, dp0, st, c2, pf, dsf);
+    for (int t = t0; t + 1 < n_tiles; ++t) {
+      step(2 * t, yes{}, s0, dp0, s1, dp1);
+      advance(t);
+      step(2 * t + 1, yes{}, s1, dp1, s0, dp0);
+    }
+    step(2 * (n_tiles - 1), yes{}, s0, dp0, s1, dp1);
+    step(2 * (n_tiles - 1) + 1, no{}, s1, dp1, s0, dp0);
   }
   if (key < Tk) {
     const int64_t row = ((int64_t)b * Tk + key) * lddkv + h * HD;
@@ -472,7 +636,7 @@ __global__ __launch_bounds__(kNT) void attn_dkv_dma_kernel(MhaDev a, const bf16*
 }  // namespace
 
 constexpr int kSmemTiles = 2 * 2 * 64 * HD * 2;          // two stages of two 64 x 128 bf16 tiles: 64 KiB
-constexpr int kSmemDkv = kSmemTiles + 4 * 64 * 4;        // + log-sum-exp and delta of two query tiles
+constexpr int kSmemDkv = 3 * 2 * 64 * HD * 2 + 6 * 64 * 4;   // dK/dV: three stages and their statistics: 97.5 KiB
 
 // Raises the dynamic-LDS limit of the kernels (once; called at context creation, never inside a capture).
 hipError_t attention_dma_init() {
