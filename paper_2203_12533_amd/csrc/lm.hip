@@ -157,6 +157,7 @@ size_t plan(Model* m, unsigned char* base) {
   m->dx_b = cv.take<float>(N * d * 4);
   m->delta = cv.take<float>(BHT * 4);
   m->dx_lp = cv.take<void>(N * d * es);
+  m->dx_lp2 = cv.take<void>(N * d * es);
   m->d_big = cv.take<void>(N * F * es);
   m->d_qkv = cv.take<void>(N * 3 * d * es);
   m->d_small = cv.take<void>(N * d * es);
@@ -209,7 +210,7 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
     const size_t e = layer_base(m, l);
     void* const d_big = defer ? A.g_u : m->d_big;
     void* const d_qkv = defer ? A.g_qkv : m->d_qkv;
-    void* const lp_mid = defer ? A.g_yo : m->dx_lp;                                    // bf16 copy of dx_b
+    void* const lp_mid = defer ? A.g_yo : m->dx_lp2;                                   // bf16 copy of dx_b
     void* const lp_below = defer && l > 0 ? s.layer[l - 1].g_y2 : m->dx_lp;            // bf16 copy of the new dx_a
     const void* dx_op = c.bf16 ? (defer ? (const void*)A.g_y2 : (const void*)m->dx_lp) : (const void*)m->dx_a;
     // Every data gradient comes BEFORE the weight gradient of the same layer: a weight gradient whose epilogue
@@ -224,11 +225,13 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
     // FFN1: u = m W1 + b1
     // (b1 gradient = column sums of d_big: delivered by the weight-gradient GEMM where that is free)
     PW_TRY(gemm_dgrad(m, d_big, e + 8, N, d, F, kEpiStore, nullptr, m->d_small, dt, 0), "ffn1 dgrad");
-    if (!defer) PW_TRY(gemm_wgrad_bias(m, A.mm, d_big, e + 8, e + 9, N, d, F, accumulate, m->ws, fz.w1 ? &opt : nullptr), "ffn1 wgrad + b1 grad");
-    // LN2 and the residual branch: dx_b = dx_a + LN2'(d_small)
+    // LN2 and the residual branch: dx_b = dx_a + LN2'(d_small).  It runs right behind the GEMM that wrote d_small and
+    // before the FFN1 weight gradient, which needs nothing of it: that GEMM (and, fused, the optimizer traffic of its
+    // epilogue) would otherwise push d_small and the residual gradient out of the memory-side cache first.
     PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_mid, m->w + P(m, e + 6).offset, A.mean2, A.rstd2, m->dx_a,
                                 m->dx_b, c.bf16 ? lp_mid : nullptr, g + P(m, e + 6).offset, g + P(m, e + 7).offset,
                                 g + P(m, e + 5).offset /* bo */, m->ws, N, d, accumulate), "ln2 bwd");
+    if (!defer) PW_TRY(gemm_wgrad_bias(m, A.mm, d_big, e + 8, e + 9, N, d, F, accumulate, m->ws, fz.w1 ? &opt : nullptr), "ffn1 wgrad + b1 grad");
     dx_op = c.bf16 ? (const void*)lp_mid : (const void*)m->dx_b;
     // out-proj: x_mid = x_in + o Wo + bo
     // (its weight gradient is computed together with the QKV one below: neither fills the chip alone)
@@ -237,8 +240,13 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
     PW_TRY(launch_attention_bwd(m->stream, dt, A.qkv, A.o, m->d_small, A.lse, m->delta, d_qkv, c.batch, c.seq,
                                 c.n_head, m->hd()), "attention bwd");
     // QKV: qkv = a Wqkv + bqkv
-    // (dy_out, the bf16 residual gradient, stays intact until the LN1 backward below rewrites it)
     PW_TRY(gemm_dgrad(m, d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small, dt, 0), "qkv dgrad");
+    // LN1 and the residual branch: dx_a = dx_b + LN1'(d_small); again right behind the producer of d_small.  Its bf16
+    // output goes to the other of the two low-precision buffers, so dy_out stays intact for the weight gradients below.
+    PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->w + P(m, e).offset, A.mean1, A.rstd1, m->dx_b,
+                                m->dx_a, c.bf16 ? lp_below : nullptr, g + P(m, e).offset, g + P(m, e + 1).offset,
+                                l > 0 ? g + P(m, layer_base(m, l - 1) + 11).offset /* b2 of the layer below */ : nullptr,
+                                m->ws, N, d, accumulate), "ln1 bwd");
     if (!defer) {
       const WgradJob jobs[2] = {{fz.qkv ? wgrad_adam_args(m, opt, A.a, d_qkv, e + 2, N, d, 3 * d)
                                         : wgrad_args(m, A.a, d_qkv, e + 2, N, d, 3 * d, accumulate), (int64_t)e + 3},
@@ -246,11 +254,6 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
                                        : wgrad_args(m, A.o, dy_out, e + 4, N, d, d, accumulate), -1}};
       PW_TRY(gemm_wgrad_group(m, jobs, 2, m->ws), "qkv + out-proj wgrad + bqkv grad");
     }
-    // LN1 and the residual branch: dx_a = dx_b + LN1'(d_small)
-    PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->w + P(m, e).offset, A.mean1, A.rstd1, m->dx_b,
-                                m->dx_a, c.bf16 ? lp_below : nullptr, g + P(m, e).offset, g + P(m, e + 1).offset,
-                                l > 0 ? g + P(m, layer_base(m, l - 1) + 11).offset /* b2 of the layer below */ : nullptr,
-                                m->ws, N, d, accumulate), "ln1 bwd");
   }
   return hipSuccess;
 }
