@@ -390,6 +390,7 @@ def measure(args, workload, steps, warmup, torch, pwb, I):
     per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
     n_gemm, gemm_ms, gemm_flops = ctx.profile_end() if profiled_steps else (0, 0.0, 0.0)
     n_fu, fu_ms, fu_flops = ctx.profile_fused_update() if profiled_steps else (0, 0.0, 0.0)
+    shape_rows = ctx.profile_gemm_shapes() if profiled_steps else []
     for f in pending:
         losses.append(float(ctx.await_(f).reshape(-1)[0]))
         ctx.future_release(f)
@@ -454,6 +455,15 @@ def measure(args, workload, steps, warmup, torch, pwb, I):
             "note": "the same launches without the epilogue's optimizer traffic take about the GEMM family's rate; "
                     "the separate Adam launch they replace moved 30 B/param at 5.5 TB/s"}
         result["roofline"]["gemm_ms_per_step_incl_fused_update"] = round((gemm_ms + fu_ms) / profiled_steps, 3)
+    if shape_rows:
+        # every GEMM launch of the bracketed steps by (shape, operand layouts, epilogue): which instantiation runs
+        # at what rate.  layout "tn" = A k-major, B row-major, and so on; members > 1 = one launch shared by several GEMMs.
+        epi_names = ["store", "bias", "bias_residual", "bias_gelu", "gelu_bwd", "adam", "xent_stats", "xent_grad"]
+        result["roofline"]["by_shape"] = [
+            {"M": r["M"], "N": r["N"], "K": r["K"], "layout": ("t" if r["a_kmajor"] else "n") + ("n" if r["b_kmajor"] else "t"),
+             "epilogue": epi_names[r["epilogue"]], "members": r["members"], "launches_per_step": r["launches"] // profiled_steps,
+             "avg_us": round(1e3 * r["total_ms"] / r["launches"], 1),
+             "tflops": round(r["total_flops"] / (r["total_ms"] * 1e-3) / 1e12, 1)} for r in shape_rows]
     result["device"] = device_note(torch, sampled)
     clk = sampled.get("sclk_mhz_during_timed_steps", {}).get("mean")
     if clk:

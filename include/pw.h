@@ -536,6 +536,17 @@ pw_status pw_profile_end(pw_ctx* ctx, int64_t* launches, double* total_ms, doubl
  * output element - so pw_profile_end leaves them out of its three figures; this call returns theirs, as of the last
  * pw_profile_end. */
 pw_status pw_profile_fused_update(pw_ctx* ctx, int64_t* launches, double* total_ms, double* total_flops);
+/* The launches of the last pw_profile_end (with and without the Adam epilogue) by problem shape, largest total time
+ * first.  One launch shared by several GEMMs (pw_op_gemm_group, the weight-gradient pairs of a train step) is one
+ * row entry under its largest member's shape, with members > 1 and total_flops covering all members.  rows (host,
+ * caller-owned, may be NULL when cap is 0) receives at most cap rows; *n_rows the number there are. */
+typedef struct pw_gemm_shape_row {
+  int64_t M, N, K;
+  int32_t a_kmajor, b_kmajor, epilogue, members;
+  int64_t launches;
+  double total_ms, total_flops;
+} pw_gemm_shape_row;
+pw_status pw_profile_gemm_shapes(pw_ctx* ctx, pw_gemm_shape_row* rows, int32_t cap, int32_t* n_rows);
 
 #ifdef __cplusplus
 }

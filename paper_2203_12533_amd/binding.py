@@ -61,6 +61,12 @@ class XentEpilogue(C.Structure):
                 ("lse", C.c_void_p), ("inv_n", C.c_float)]
 
 
+class GemmShapeRow(C.Structure):
+    _fields_ = [("M", C.c_int64), ("N", C.c_int64), ("K", C.c_int64), ("a_kmajor", C.c_int32), ("b_kmajor", C.c_int32),
+                ("epilogue", C.c_int32), ("members", C.c_int32), ("launches", C.c_int64), ("total_ms", C.c_double),
+                ("total_flops", C.c_double)]
+
+
 class GemmArgs(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("a_kmajor", C.c_int32), ("b_kmajor", C.c_int32),
                 ("M", C.c_int64), ("N", C.c_int64), ("K", C.c_int64),
@@ -160,6 +166,7 @@ _SIGS = {
     "pw_profile_pause": (C.c_int, [C.c_void_p]),
     "pw_profile_end": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "pw_profile_fused_update": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "pw_profile_gemm_shapes": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]),
     "pw_op_gemm": (C.c_int, [C.c_void_p, C.POINTER(GemmArgs)]),
     "pw_op_gemm_pair": (C.c_int, [C.c_void_p, C.POINTER(GemmArgs), C.POINTER(GemmArgs)]),
     "pw_op_gemm_group": (C.c_int, [C.c_void_p, C.POINTER(GemmArgs), C.c_int]),
@@ -396,6 +403,14 @@ class Context:
         n, ms, fl = C.c_int64(), C.c_double(), C.c_double()
         self._check(lib().pw_profile_fused_update(self._h, C.byref(n), C.byref(ms), C.byref(fl)))
         return n.value, ms.value, fl.value
+
+    def profile_gemm_shapes(self):
+        """The launches of the last profile_end() by shape: a list of dicts, largest total time first."""
+        n = C.c_int32()
+        self._check(lib().pw_profile_gemm_shapes(self._h, None, 0, C.byref(n)))
+        rows = (GemmShapeRow * max(n.value, 1))()
+        self._check(lib().pw_profile_gemm_shapes(self._h, C.cast(rows, C.c_void_p), n.value, C.byref(n)))
+        return [{f: getattr(r, f) for f, _ in GemmShapeRow._fields_} for r in rows[:n.value]]
 
     # -- model
     def model(self, cfg, fused_update: bool = False, fused_head_loss: bool = False) -> "Model":

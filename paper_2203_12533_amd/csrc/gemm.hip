@@ -27,6 +27,8 @@
 #include "kernels.hpp"
 
 #include <cstdlib>
+#include <map>
+#include <tuple>
 #include <vector>
 
 #ifndef PW_WM
@@ -319,7 +321,18 @@ struct ProfiledLaunch {
   hipEvent_t start, stop;
   double flops;
   bool optimizer = false;   // the launch carried the Adam epilogue: MFMA work plus 26 bytes per output element
+  GemmShapeKey key{};       // shape, layouts and epilogue (of the first member of a shared launch)
 };
+struct ShapeLess {
+  bool operator()(const GemmShapeKey& x, const GemmShapeKey& y) const {
+    return std::tie(x.M, x.N, x.K, x.a_kmajor, x.b_kmajor, x.epilogue, x.members) <
+           std::tie(y.M, y.N, y.K, y.a_kmajor, y.b_kmajor, y.epilogue, y.members);
+  }
+};
+std::vector<GemmShapeRow> g_shape_rows;   // per-shape totals as of the last gemm_profile_end
+GemmShapeKey shape_key(const GemmArgs& a, int members) {
+  return GemmShapeKey{a.M, a.N, a.K, a.a_kmajor, a.b_kmajor, a.epilogue, members};
+}
 int64_t g_fused_launches = 0;   // what the last gemm_profile_end saw of such launches
 double g_fused_ms = 0.0, g_fused_flops = 0.0;
 bool g_profile_on = false;
@@ -356,11 +369,17 @@ hipError_t gemm_profile_end(int64_t* launches, double* total_ms, double* total_f
   g_fused_launches = 0;
   g_fused_ms = g_fused_flops = 0.0;
   hipError_t err = hipSuccess;
+  std::map<GemmShapeKey, GemmShapeRow, ShapeLess> by_shape;
   for (auto& p : g_profile) {
     hipError_t e = hipEventSynchronize(p.stop);
     float t = 0.f;
     if (e == hipSuccess) e = hipEventElapsedTime(&t, p.start, p.stop);
     if (e != hipSuccess) err = e;
+    GemmShapeRow& row = by_shape[p.key];
+    row.key = p.key;
+    row.launches++;
+    row.total_ms += t;
+    row.total_flops += p.flops;
     if (p.optimizer) {
       g_fused_launches++;
       g_fused_ms += t;
@@ -377,7 +396,17 @@ hipError_t gemm_profile_end(int64_t* launches, double* total_ms, double* total_f
   if (total_ms) *total_ms = ms;
   if (total_flops) *total_flops = fl;
   g_profile.clear();
+  g_shape_rows.clear();
+  for (auto& kv : by_shape) g_shape_rows.push_back(kv.second);
+  std::stable_sort(g_shape_rows.begin(), g_shape_rows.end(),
+                   [](const GemmShapeRow& x, const GemmShapeRow& y) { return x.total_ms > y.total_ms; });
   return err;
+}
+
+int gemm_profile_shapes(GemmShapeRow* rows, int cap) {
+  const int n = (int)g_shape_rows.size();
+  for (int i = 0; rows && i < n && i < cap; ++i) rows[i] = g_shape_rows[i];
+  return n;
 }
 
 void gemm_profile_fused(int64_t* launches, double* total_ms, double* total_flops) {
@@ -391,7 +420,8 @@ static hipError_t launch_gemm_impl(hipStream_t s, const GemmArgs& a);
 hipError_t launch_gemm(hipStream_t s, const GemmArgs& a) {
   const bool timed = g_profile_on && a.dtype == kBF16 && a.M > 0 && a.N > 0;
   if (!timed) return launch_gemm_impl(s, a);
-  ProfiledLaunch p{profile_event(), profile_event(), 2.0 * (double)a.M * (double)a.N * (double)a.K, a.epilogue == kEpiAdam};
+  ProfiledLaunch p{profile_event(), profile_event(), 2.0 * (double)a.M * (double)a.N * (double)a.K, a.epilogue == kEpiAdam,
+                   shape_key(a, 1)};
   if (!p.start || !p.stop) return hipErrorOutOfMemory;
   hipError_t e = hipEventRecord(p.start, s);
   if (e == hipSuccess) e = launch_gemm_impl(s, a);
@@ -615,7 +645,7 @@ hipError_t launch_gemm_group(hipStream_t s, const GemmArgs* a, int n) {
   GemmBf16Params p[kRingGroupMax];
   for (int i = 0; i < n; ++i) p[i] = bf16_params_of(a[order[i]], 256);
   const bool timed = g_profile_on;
-  ProfiledLaunch pl{nullptr, nullptr, flops, a[0].epilogue == kEpiAdam};
+  ProfiledLaunch pl{nullptr, nullptr, flops, a[0].epilogue == kEpiAdam, shape_key(a[order[0]], n)};
   hipError_t err = hipSuccess;
   if (timed) {
     pl.start = profile_event();

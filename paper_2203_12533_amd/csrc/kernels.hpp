@@ -158,6 +158,11 @@ hipError_t gemm_profile_end(int64_t* launches, double* total_ms, double* total_f
 // Launches that carried the Adam epilogue are kept out of those figures (they do the optimizer's memory traffic as
 // well); this returns theirs, as of the last gemm_profile_end.
 void gemm_profile_fused(int64_t* launches, double* total_ms, double* total_flops);
+// The same launches (all of them) by shape, as of the last gemm_profile_end, largest total time first.  A launch
+// shared by several GEMMs counts under its largest member's shape with members > 1 and the FLOPs of all of them.
+struct GemmShapeKey { int64_t M, N, K; int a_kmajor, b_kmajor, epilogue, members; };
+struct GemmShapeRow { GemmShapeKey key; int64_t launches; double total_ms, total_flops; };
+int gemm_profile_shapes(GemmShapeRow* rows, int cap);   // returns how many rows there are
 // One-time per-process set-up of kernel attributes (large dynamic LDS); call once before any capture.
 hipError_t gemm_init();
 

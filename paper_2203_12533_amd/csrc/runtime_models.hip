@@ -326,4 +326,16 @@ pw_status pw_profile_fused_update(pw_ctx* c, int64_t* launches, double* total_ms
   return PW_OK;
 }
 
+pw_status pw_profile_gemm_shapes(pw_ctx* c, pw_gemm_shape_row* rows, int32_t cap, int32_t* n_rows) {
+  if (!c || !n_rows || cap < 0 || (cap > 0 && !rows)) return PW_ERR_INVALID;
+  std::vector<GemmShapeRow> r((size_t)cap);
+  const int n = gemm_profile_shapes(r.data(), cap);
+  for (int i = 0; i < n && i < cap; ++i) {
+    const GemmShapeKey& k = r[i].key;
+    rows[i] = pw_gemm_shape_row{k.M, k.N, k.K, k.a_kmajor, k.b_kmajor, k.epilogue, k.members, r[i].launches, r[i].total_ms, r[i].total_flops};
+  }
+  *n_rows = n;
+  return PW_OK;
+}
+
 }  // extern "C"

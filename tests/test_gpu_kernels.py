@@ -216,6 +216,27 @@ def test_gemm_group_with_adam_epilogues_and_bias_gradient(ctx, orc):
     assert torch.equal(w0, a["wd"])
 
 
+def test_profile_reports_the_launches_by_shape(ctx):
+    """The measurement aid's per-shape table: three launches of one shape and one of another, bracketed by events."""
+    x = torch.zeros(512 * 512, dtype=torch.bfloat16, device="cuda")
+    c = torch.empty(512 * 512, dtype=torch.bfloat16, device="cuda")
+
+    def run(K):
+        ctx.gemm(dtype=pwb.PW_BF16, a_kmajor=0, b_kmajor=1, M=512, N=512, K=K, lda=K, ldb=512, ldc=512, accumulate=0,
+                 epilogue=pwb.PW_EPI_STORE, out_dtype=pwb.PW_BF16, A=ptr(x), B=ptr(x), C=ptr(c))
+    ctx.profile_begin()
+    for K in (256, 512, 512, 512):
+        run(K)
+    n, ms, fl = ctx.profile_end()
+    rows = ctx.profile_gemm_shapes()
+    assert n == 4 and ms > 0 and fl == 2.0 * 512 * 512 * (256 + 3 * 512)
+    assert sorted((r["K"], r["launches"]) for r in rows) == [(256, 1), (512, 3)]
+    assert all(r["M"] == 512 and r["N"] == 512 and r["members"] == 1 and r["a_kmajor"] == 0 and r["b_kmajor"] == 1
+               and r["epilogue"] == pwb.PW_EPI_STORE for r in rows)
+    assert abs(sum(r["total_ms"] for r in rows) - ms) < 1e-6 * max(ms, 1.0) + 1e-9
+    assert sum(r["total_flops"] for r in rows) == fl
+
+
 def test_lm_head_fused_with_the_loss(ctx, orc):
     """The LM-head GEMM with the loss in its epilogue: a first pass over y . Wh leaves only softmax statistics per
     64-column group and the targets' logits, a second pass writes (softmax - onehot) / N in bf16 - the logits
