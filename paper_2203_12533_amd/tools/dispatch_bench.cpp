@@ -103,7 +103,7 @@ int main(int argc, char** argv) {
   }
   if (gaps) {
     // For a kernel trace (rocprofv3 --kernel-trace -- dispatch_bench --gaps): the same chain of 128 trivial
-    // computations dispatched four ways, 20 times each, the phases 100 ms apart so that the trace can be cut at the
+    // computations dispatched four ways, 20 times each (then two pipelines, below), the phases 100 ms apart so that the trace can be cut at the
     // pauses.  The device-side launch gap of a mode is next.start - previous.end between consecutive kernels of a chain.
     constexpr int L = 128, reps = 20;
     pw_future x = input();
@@ -133,6 +133,29 @@ int main(int argc, char** argv) {
       }
       std::printf("{\"bench\": \"launch_gaps\", \"phase\": %d, \"mode\": \"%s\", \"chains\": %d, \"chain_length\": %d, "
                   "\"wall_us_per_computation\": %.3f}\n", phase, names[phase], reps + 2, L, (now_s() - t0) * 1e6 / ((reps + 2) * L));
+    }
+    // Two more phases for the cost of a dependency that crosses executors: a pipeline of 64 stages, every stage on an
+    // executor (stream + host thread) of its own, parallel dispatch - and the same pipeline with all stages on
+    // executor 0, where the dependency is stream order.
+    CHECK(pw_ctx_set_executors(ctx, 64));
+    {
+      constexpr int stages = 64;
+      std::vector<pw_fn> fns(stages, one);
+      const char* pnames[2] = {"pipeline_64_executors", "pipeline_1_executor"};
+      for (int phase = 0; phase < 2; ++phase) {
+        std::vector<int32_t> where(stages);
+        for (int i = 0; i < stages; ++i) where[i] = phase == 0 ? i : 0;
+        std::this_thread::sleep_for(std::chrono::milliseconds(100));
+        const double t0 = now_s();
+        for (int r = 0; r < reps + 2; ++r) {
+          pw_future out;
+          CHECK(pw_pipeline(ctx, fns.data(), where.data(), stages, x, &out, PW_DISPATCH_PARALLEL));
+          CHECK(pw_await(ctx, out, nullptr, 0));
+          CHECK(pw_future_release(ctx, out));
+        }
+        std::printf("{\"bench\": \"launch_gaps\", \"phase\": %d, \"mode\": \"%s\", \"chains\": %d, \"chain_length\": %d, "
+                    "\"wall_us_per_computation\": %.3f}\n", 4 + phase, pnames[phase], reps + 2, stages, (now_s() - t0) * 1e6 / ((reps + 2) * stages));
+      }
     }
     CHECK(pw_future_release(ctx, x));
     pw_ctx_destroy(ctx);

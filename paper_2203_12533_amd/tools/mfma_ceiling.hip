@@ -105,6 +105,52 @@ __global__ __launch_bounds__(kNT) void loop_16x16x32(float* out, int iters, int 
   out[blockIdx.x * kNT + threadIdx.x] = s;
 }
 
+// The same loop laid out as the ring GEMM does it: fragments double-buffered in registers - the reads of a k-step
+// are issued under the MFMAs of the step before - and, with BARRIER, one bare s_barrier per k-tile placed in front
+// of the last eight MFMAs of the tile, the next tile's first fragment reads right behind it.  (The plain variant
+// above waits for its fragments at the top of every k-step and, with its barrier, drains the matrix pipe once per
+// k-tile: its cost is that of the drain, not of the barrier instruction.)
+template <int BARRIER>
+__global__ __launch_bounds__(kNT) void loop_16x16x32_pipelined(float* out, int iters, int rnd) {
+  extern __shared__ __attribute__((aligned(16))) __bf16 smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  fill(smem, rnd);
+  __syncthreads();
+  constexpr int FM = 8, FN = 4;
+  f32x4 acc[FM * FN];
+  for (int a = 0; a < FM * FN; ++a) for (int r = 0; r < 4; ++r) acc[a][r] = 0.f;
+  bf16x8 af[2][FM], bf[2][FN];
+  const __bf16* a_tile = smem + ((wave & 1) * 128 + (lane & 15)) * kLd + (lane >> 4) * 8;
+  const __bf16* b_tile = smem + 256 * kLd + ((wave >> 1) * 64 + (lane & 15)) * kLd + (lane >> 4) * 8;
+  auto read = [&](int kk) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i) af[kk][i] = *reinterpret_cast<const bf16x8*>(a_tile + i * 16 * kLd + kk * 32);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) bf[kk][j] = *reinterpret_cast<const bf16x8*>(b_tile + j * 16 * kLd + kk * 32);
+  };
+  auto rows = [&](int kk, int i0, int i1) {
+#pragma unroll
+    for (int i = i0; i < i1; ++i)
+#pragma unroll
+      for (int jj = 0; jj < FN; ++jj) {
+        const int j = (i & 1) ? FN - 1 - jj : jj;
+        acc[i * FN + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bf[kk][j], af[kk][i], acc[i * FN + j], 0, 0, 0);
+      }
+  };
+  read(0);
+  for (int it = 0; it < iters; ++it) {
+    read(1);
+    rows(0, 0, FM);
+    rows(1, 0, FM - 2);
+    if (BARRIER) __builtin_amdgcn_s_barrier();
+    read(0);
+    rows(1, FM - 2, FM);
+  }
+  float s = 0.f;
+  for (int a = 0; a < FM * FN; ++a) for (int r = 0; r < 4; ++r) s += acc[a][r];
+  out[blockIdx.x * kNT + threadIdx.x] = s;
+}
+
 // Host-side sampler of engine clock (the starred level of pp_dpm_sclk) and board power (hwmon power1_input).
 struct Sampler {
   std::string sclk_path, power_path;
@@ -189,6 +235,8 @@ int main() {
   run("16x16x32, ascending columns", loop_16x16x32<0, 0>, 1, secs);
   run("16x16x32, columns back and forth", loop_16x16x32<1, 0>, 1, secs);
   run("16x16x32, back and forth, barrier per k-tile", loop_16x16x32<1, 1>, 1, secs);
+  run("16x16x32, b&f, fragments double-buffered", loop_16x16x32_pipelined<0>, 1, secs);
+  run("16x16x32, b&f, double-buffered, bare barrier", loop_16x16x32_pipelined<1>, 1, secs);
   run("32x32x16", loop_32x32x16<0>, 0, secs);
   run("16x16x32, columns back and forth", loop_16x16x32<1, 0>, 0, secs);
   return 0;
