@@ -83,18 +83,22 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_fwd_wave_kernel(const fl
                                                                         int N, int d) {
   const int d4 = d >> 2, lane = threadIdx.x & 63;
   const int wave = blockIdx.x * (kLnThreads / 64) + (threadIdx.x >> 6), nwaves = gridDim.x * (kLnThreads / 64);
-  for (int n = wave; n < N; n += nwaves) {
+  // The next row of this wave is requested before the current one is reduced and stored, so a wave always has
+  // loads in flight.
+  auto fetch = [&](int n, float4* r) {
     const float4* xr = reinterpret_cast<const float4*>(x + (size_t)n * d);
-    float4 v[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i)
+      if (lane + i * 64 < d4) r[i] = xr[lane + i * 64];
+  };
+  float4 v[VEC], nx[VEC];
+  if (wave < N) fetch(wave, v);
+  for (int n = wave; n < N; n += nwaves) {
+    if (n + nwaves < N) fetch(n + nwaves, nx);
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) {
-      const int c4 = lane + i * 64;
-      if (c4 < d4) {
-        v[i] = xr[c4];
-        s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
-      }
-    }
+    for (int i = 0; i < VEC; ++i)
+      if (lane + i * 64 < d4) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
     const float mu = wave_sum(s) / (float)d;
     float q = 0.f;
 #pragma unroll
@@ -120,6 +124,8 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_fwd_wave_kernel(const fl
       mean[n] = mu;
       rstd[n] = rs;
     }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) v[i] = nx[i];
   }
 }
 
@@ -128,7 +134,7 @@ static void launch_ln_fwd_wave(hipStream_t s, const float* x, const float* g, co
                                float* rstd, int N, int d) {
   const int rows_per_block = kLnThreads / 64;
   int grid = (N + rows_per_block - 1) / rows_per_block;
-  if (grid > 4096) grid = 4096;
+  if (grid > 1024) grid = 1024;   // 16 waves per compute unit, each with its next row already requested
   if (d <= 256) layernorm_fwd_wave_kernel<T, 1><<<grid, kLnThreads, 0, s>>>(x, g, b, y, mean, rstd, N, d);
   else if (d <= 512) layernorm_fwd_wave_kernel<T, 2><<<grid, kLnThreads, 0, s>>>(x, g, b, y, mean, rstd, N, d);
   else if (d <= 1024) layernorm_fwd_wave_kernel<T, 4><<<grid, kLnThreads, 0, s>>>(x, g, b, y, mean, rstd, N, d);
