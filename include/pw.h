@@ -250,7 +250,10 @@ pw_status pw_train_step(pw_ctx* ctx, pw_fn step_fn, pw_future tokens, pw_future*
 /* ---- futures (Sections 4.4, 4.6) -------------------------------------------------------------- */
 
 /* Blocks until the future is ready; then copies `bytes` (<= its size) to host_dst if non-null.
- * PW_ERR_POISONED if it or a dependency failed. */
+ * PW_ERR_POISONED if it or a dependency failed.  With nothing to copy out (host_dst NULL or bytes 0) the call only
+ * establishes readiness; for the output of a one-workgroup elementwise function enqueued as a stream launch
+ * (pw_run_fn, pw_chain outside a HIP graph) that is learnt from a completion word the kernel itself writes to pinned
+ * host memory, a few microseconds before the stream's event reaches the host (pw_future_query consults it too). */
 pw_status pw_await(pw_ctx* ctx, pw_future f, void* host_dst, size_t bytes);
 /* New future whose library-owned device buffer is filled from host memory (asynchronous copy). */
 pw_status pw_future_from_host(pw_ctx* ctx, const void* host_src, const pw_tensor_spec* spec, pw_future* out);

@@ -16,8 +16,10 @@ static inline int grid_for(int64_t work_items, int block, int max_blocks = 1 << 
 // ---- trivial compiled functions of the dispatch micro-benchmark -------------------------------------
 // kind 1: x + c, 2: x * c, 3: x / c, 4: x + c after a bounded spin of busy_ticks (100 MHz wall clock),
 // 5: kind 4 applied `reps` times in a row inside one launch (a chain of computations fused into one node).
+// done (optional, one-block launches only): a word in pinned host memory that receives `token` once every element has
+// been written - a completion signal the host can poll without going through the stream's end-of-kernel event.
 __global__ void scalar_fn_kernel(int kind, const float* __restrict__ x, float* __restrict__ y, int64_t n, float c,
-                                 uint64_t busy_ticks, int reps) {
+                                 uint64_t busy_ticks, int reps, uint32_t* done, uint32_t token) {
   if (kind < 5) {
     if (kind == 4 && busy_ticks) {
       const uint64_t t0 = wall_clock64();
@@ -27,29 +29,39 @@ __global__ void scalar_fn_kernel(int kind, const float* __restrict__ x, float* _
       const float v = x[i];
       y[i] = kind == 2 ? v * c : kind == 3 ? v / c : v + c;
     }
-    return;
+  } else {
+    // Every thread owns its elements through all repetitions, so no synchronisation is needed between them; each
+    // repetition is one fp32 addition rounded to nearest, exactly as in a chain of separate functions.
+    for (int r = 0; r < reps; ++r) {
+      if (busy_ticks) {
+        const uint64_t t0 = wall_clock64();
+        while (wall_clock64() - t0 < busy_ticks) __builtin_amdgcn_s_sleep(8);
+      }
+      for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const float v = r == 0 ? x[i] : y[i];
+        y[i] = __fadd_rn(v, c);
+      }
+    }
   }
-  // Every thread owns its elements through all repetitions, so no synchronisation is needed between them; each
-  // repetition is one fp32 addition rounded to nearest, exactly as in a chain of separate functions.
-  for (int r = 0; r < reps; ++r) {
-    if (busy_ticks) {
-      const uint64_t t0 = wall_clock64();
-      while (wall_clock64() - t0 < busy_ticks) __builtin_amdgcn_s_sleep(8);
-    }
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-      const float v = r == 0 ? x[i] : y[i];
-      y[i] = __fadd_rn(v, c);
-    }
+  if (done) {   // uniform over the (single) block
+    __threadfence_system();
+    __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_store(done, token, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
   }
 }
 
-hipError_t launch_scalar_fn(hipStream_t s, int kind, const float* x, float* y, int64_t n, float c, float busy_us, int reps) {
+static inline int scalar_fn_block(int64_t n) { return n <= 128 ? 128 : 256; }
+bool scalar_fn_one_block(int64_t n) { return n > 0 && grid_for(n, scalar_fn_block(n)) == 1; }
+
+hipError_t launch_scalar_fn(hipStream_t s, int kind, const float* x, float* y, int64_t n, float c, float busy_us, int reps,
+                            uint32_t* done, uint32_t token) {
   if (kind < 1 || kind > 5 || !x || !y || n < 0 || reps < 1 || reps > 65536) return hipErrorInvalidValue;
   if (busy_us < 0.f || busy_us > 1e6f) return hipErrorInvalidValue;   // at most one second of spin per repetition
   if ((double)busy_us * reps > 1e7) return hipErrorInvalidValue;       // and ten seconds per launch
+  if (done && !scalar_fn_one_block(n)) return hipErrorInvalidValue;   // one block signals; several would need a count
   if (n == 0) return hipSuccess;
-  const int block = n <= 128 ? 128 : 256;
-  scalar_fn_kernel<<<grid_for(n, block), block, 0, s>>>(kind, x, y, n, c, (uint64_t)(busy_us * 100.f), reps);
+  const int block = scalar_fn_block(n);
+  scalar_fn_kernel<<<grid_for(n, block), block, 0, s>>>(kind, x, y, n, c, (uint64_t)(busy_us * 100.f), reps, done, token);
   return hipGetLastError();
 }
 

@@ -55,7 +55,11 @@ struct GemmArgs {
 };
 
 // elementwise.hip
-hipError_t launch_scalar_fn(hipStream_t s, int kind, const float* x, float* y, int64_t n, float c, float busy_us, int reps);
+// done / token (optional): the launch writes token to *done (pinned host memory) when its output is complete; only
+// launches of one block can (scalar_fn_one_block).
+hipError_t launch_scalar_fn(hipStream_t s, int kind, const float* x, float* y, int64_t n, float c, float busy_us, int reps,
+                            uint32_t* done = nullptr, uint32_t token = 0);
+bool scalar_fn_one_block(int64_t n);
 hipError_t launch_add2(hipStream_t s, const float* a, const float* b, float* y, int64_t n);
 hipError_t launch_fill_f32(hipStream_t s, float* p, int64_t n, float v);
 hipError_t launch_f32_to_bf16(hipStream_t s, const float* src, void* dst, int64_t n);

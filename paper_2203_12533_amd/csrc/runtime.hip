@@ -76,6 +76,26 @@ std::shared_ptr<GateWords> words_get(pw_ctx* c) {
   });
 }
 
+// A completion word and a token no earlier user of the word can have written (tokens are unique per context; a late
+// write of an old token to a recycled word is overwritten, in stream order, by the new owner's).
+std::shared_ptr<GateWords> done_word_get(pw_ctx* c, uint32_t* token) {
+  if (c->free_done_words.empty()) {
+    uint32_t* slab = nullptr;
+    if (hipHostMalloc((void**)&slab, 4096, hipHostMallocDefault) != hipSuccess) return nullptr;
+    c->word_slabs.push_back(slab);   // freed with the gate slabs at context destruction
+    for (int i = 0; i < 4096 / 64; ++i) c->free_done_words.push_back(slab + i * 16);
+  }
+  uint32_t* w = c->free_done_words.back();
+  c->free_done_words.pop_back();
+  if (++c->done_seq == 0) ++c->done_seq;
+  *token = c->done_seq;
+  pw_ctx* ctx = c;
+  return std::shared_ptr<GateWords>(new GateWords{w}, [ctx](GateWords* g) {
+    ctx->free_done_words.push_back(g->words);
+    delete g;
+  });
+}
+
 pw_status future_new(pw_ctx* c, FutureRec** out, pw_future* handle) {
   uint32_t idx;
   if (!c->free_futures.empty()) {
@@ -114,6 +134,7 @@ void future_drop(pw_ctx* c, pw_future h) {
   if (f->staging) c->staging_pool[size_class(f->bytes)].push_back(f->staging);
   f->poison.clear();
   f->gate.reset();
+  f->done.reset();
   f->live = false;
   c->live_futures--;
   c->free_futures.push_back((uint32_t)(h & 0xFFFFFFFFu) - 1);
@@ -123,10 +144,14 @@ void future_drop(pw_ctx* c, pw_future h) {
 bool is_scalar_kind(int k) { return k >= PW_FN_ADD_CONST && k <= PW_FN_BUSY_CHAIN; }   // one fp32 input, one output
 
 // Launch the body of one function on the executor stream.  in/out are device pointers.
-pw_status fn_launch(pw_ctx* c, FnRec* fn, void* const* in, void* const* out) {
+// Whether a launch of fn can carry a completion word (see FutureRec::done).
+bool fn_signals_completion(const FnRec* fn) { return is_scalar_kind(fn->desc.kind) && scalar_fn_one_block(spec_numel(fn->desc.in[0])); }
+
+pw_status fn_launch(pw_ctx* c, FnRec* fn, void* const* in, void* const* out, uint32_t* done = nullptr, uint32_t token = 0) {
   const int k = fn->desc.kind;
   if (is_scalar_kind(k)) {
-    hipError_t e = launch_scalar_fn(c->exec, k, (const float*)in[0], (float*)out[0], spec_numel(fn->desc.in[0]), fn->cst, fn->busy_us, fn->reps);
+    hipError_t e = launch_scalar_fn(c->exec, k, (const float*)in[0], (float*)out[0], spec_numel(fn->desc.in[0]), fn->cst, fn->busy_us, fn->reps,
+                                    done, token);
     if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "scalar fn launch: %s", hipGetErrorString(e));
     return PW_OK;
   }
@@ -524,7 +549,10 @@ pw_status pw_run_fn(pw_ctx* c, pw_fn h, const pw_future* in, int n_in, pw_future
   st = wait_inputs(c, fin, n_in, poison, host_poison);
   void* ibuf[8];
   for (int i = 0; i < n_in; ++i) ibuf[i] = fin[i]->buf;
-  if (st == PW_OK) st = fn_launch(c, fn, ibuf, obuf);
+  std::shared_ptr<GateWords> done;
+  uint32_t done_token = 0;
+  if (st == PW_OK && fn_signals_completion(fn)) done = done_word_get(c, &done_token);   // none to be had: the event alone
+  if (st == PW_OK) st = fn_launch(c, fn, ibuf, obuf, done ? done->words : nullptr, done_token);
   hipEvent_t ev = nullptr;
   if (st == PW_OK) st = event_get(c, &ev);
   if (st == PW_OK && hipEventRecord(ev, c->exec) != hipSuccess) st = fail(c, PW_ERR_DEVICE, "hipEventRecord failed");
@@ -546,6 +574,8 @@ pw_status pw_run_fn(pw_ctx* c, pw_fn h, const pw_future* in, int n_in, pw_future
     f->host_poison = host_poison;
     if (i == 0) {
       f->event = ev;
+      f->done = done;
+      f->done_token = done_token;
     } else {   // one event per future keeps release simple
       hipEvent_t e2;
       if (event_get(c, &e2) == PW_OK && hipEventRecord(e2, c->exec) == hipSuccess) f->event = e2;
@@ -632,13 +662,18 @@ pw_status pw_chain(pw_ctx* c, const pw_fn* fns, int n_fns, const pw_future* in, 
   pw_status st = wait_inputs(c, fin, n_in, poison, host_poison);
   if (st != PW_OK) { release_all(); return st; }
 
+  // Stream launches whose last link is a one-block elementwise function: that launch also signals completion to the host.
+  std::shared_ptr<GateWords> done;
+  uint32_t done_token = 0;
+  if (mode != PW_GRAPH && n_out == 1 && fn_signals_completion(recs[n_fns - 1])) done = done_word_get(c, &done_token);
   auto enqueue_all = [&](bool sync_each) -> pw_status {
     void* ibuf[8];
     void* obuf[8];
     for (int j = 0; j < n_in; ++j) ibuf[j] = fin[j]->buf;
     for (int i = 0; i < n_fns; ++i) {
       for (size_t j = 0; j < plan_bufs[i].size(); ++j) obuf[j] = plan_bufs[i][j].p;
-      pw_status s2 = fn_launch(c, recs[i], ibuf, obuf);
+      const bool last = i + 1 == n_fns && done;
+      pw_status s2 = fn_launch(c, recs[i], ibuf, obuf, last ? done->words : nullptr, last ? done_token : 0);
       if (s2 != PW_OK) return s2;
       if (sync_each && hipStreamSynchronize(c->exec) != hipSuccess) return fail(c, PW_ERR_DEVICE, "stream synchronize failed");
       for (size_t j = 0; j < plan_bufs[i].size(); ++j) ibuf[j] = obuf[j];
@@ -704,6 +739,8 @@ pw_status pw_chain(pw_ctx* c, const pw_fn* fns, int n_fns, const pw_future* in, 
     f->host_poison = host_poison;
     if (i == 0) {
       f->event = ev;
+      f->done = done;
+      f->done_token = done_token;
     } else {
       hipEvent_t e2;
       if (event_get(c, &e2) == PW_OK && hipEventRecord(e2, c->exec) == hipSuccess) f->event = e2;
@@ -1052,8 +1089,20 @@ pw_status pw_await(pw_ctx* c, pw_future h, void* host_dst, size_t bytes) {
   f->refcount++;
   hipEvent_t ev = f->event;
   hipStream_t exec = c->exec;
+  // Readiness alone (nothing to copy out) of a future with a completion word: poll the word for a while - it arrives
+  // microseconds before the stream's event does - and fall back to the event if it does not show up.
+  const std::shared_ptr<GateWords> done = (host_dst && bytes) ? nullptr : f->done;
+  const uint32_t done_token = f->done_token;
   api_lk_.unlock();
-  hipError_t e = ev ? hipEventSynchronize(ev) : hipStreamSynchronize(exec);
+  bool signalled = false;
+  if (done) {
+    const auto t0 = std::chrono::steady_clock::now();
+    for (int spin = 0; !signalled; ++spin) {
+      signalled = __atomic_load_n(&done->words[0], __ATOMIC_ACQUIRE) == done_token;
+      if (!signalled && (spin & 255) == 255 && std::chrono::steady_clock::now() - t0 > std::chrono::microseconds(200)) break;
+    }
+  }
+  hipError_t e = signalled ? hipSuccess : ev ? hipEventSynchronize(ev) : hipStreamSynchronize(exec);
   api_lk_.lock();
   f = future_get(c, h);   // the table may have been reallocated
   if (!f) return fail(c, PW_ERR_POISONED, "the future was garbage-collected with its owner while being waited for");
@@ -1167,7 +1216,8 @@ pw_status pw_future_query(pw_ctx* c, pw_future h) {
   FutureRec* f = future_get(c, h);
   if (!f) return fail(c, PW_ERR_INVALID, "bad future handle");
   if (f->host_poison) return PW_ERR_POISONED;
-  hipError_t e = f->event ? hipEventQuery(f->event) : hipStreamQuery(c->exec);
+  const bool signalled = f->done && __atomic_load_n(&f->done->words[0], __ATOMIC_ACQUIRE) == f->done_token;
+  hipError_t e = signalled ? hipSuccess : f->event ? hipEventQuery(f->event) : hipStreamQuery(c->exec);
   if (e == hipErrorNotReady) return PW_ERR_NOT_READY;
   if (e != hipSuccess) return fail(c, PW_ERR_DEVICE, "query: %s", hipGetErrorString(e));
   for (auto& p : f->poison)

@@ -74,6 +74,11 @@ struct FutureRec {
   std::vector<std::shared_ptr<GateWords>> poison;   // gates this future depends on
   std::shared_ptr<GateWords> gate;                  // own gate (pending futures)
   void* staging = nullptr;                          // pinned host staging (pending futures)
+  // Completion word (futures produced by a one-block elementwise launch on the executor stream): the kernel writes
+  // done_token to done->words[0] when its output is complete, so pw_await can poll pinned memory instead of waiting
+  // for the stream's end-of-kernel event to reach the host.
+  std::shared_ptr<GateWords> done;
+  uint32_t done_token = 0;
 };
 
 struct FnRec {
@@ -156,6 +161,10 @@ struct pw_ctx {
   // pinned host words for gates
   std::vector<uint32_t*> word_slabs;
   std::vector<uint32_t*> free_words;
+  // completion words: a pool of their own - a kernel may write its word after the future was released, which a
+  // word recycled as a gate flag would read as "resolved"
+  std::vector<uint32_t*> free_done_words;
+  uint32_t done_seq = 0;
   std::map<size_t, std::vector<void*>> staging_pool;
 
   std::unordered_map<std::string, GraphEntry> graphs;

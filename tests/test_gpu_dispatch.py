@@ -46,6 +46,52 @@ def test_chain_on_pending_input_is_exact(ctx, orc, L, mode):
     ctx.fn_release(add1)
 
 
+@pytest.mark.parametrize("L", [1, 8])
+def test_readiness_through_the_completion_word_is_not_early_and_not_lost(ctx, orc, L):
+    """A one-block elementwise launch tells the host it is done through a word in pinned memory, which pw_await polls
+    when nothing has to be copied out.  Readiness must not be reported before a pending input was resolved, the value
+    behind it must be complete, and words recycled over many futures must keep their futures apart."""
+    import threading, time
+    x = I.dispatch_input()
+    add1 = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 128, 1.0)
+    # (a) not early: the input is resolved 50 ms after the wait has begun
+    f_in = ctx.future_pending(pwb.PW_F32, (128,))
+    (f_out,) = ctx.chain([add1] * L, [f_in], 1, pwb.PW_STREAM)
+    t0 = time.perf_counter()
+    th = threading.Thread(target=lambda: (time.sleep(0.05), ctx.future_resolve(f_in, x)))
+    th.start()
+    ctx.await_(f_out, fetch=False)
+    waited = time.perf_counter() - t0
+    th.join()
+    assert waited >= 0.045, waited
+    assert np.array_equal(ctx.await_(f_out), orc.chain_add(x, L))
+    ctx.future_release(f_in)
+    ctx.future_release(f_out)
+    # (b) many short-lived futures, op by op and as chains, some released without ever being awaited
+    f = ctx.future_from_host(x)
+    for i in range(300):
+        (g,) = ctx.run_fn(add1, [f]) if i % 2 else ctx.chain([add1], [f], 1, pwb.PW_GRAPH)
+        if i % 3:
+            ctx.await_(g, fetch=False)
+            assert ctx.future_query(g) == pwb.PW_OK
+        ctx.future_release(f)
+        f = g
+    ctx.await_(f, fetch=False)
+    assert np.array_equal(ctx.await_(f), orc.chain_add(x, 300))
+    ctx.future_release(f)
+    # (c) a function of several blocks has no completion word and goes through the event as before
+    big = ctx.compile_scalar_fn(pwb.PW_FN_ADD_CONST, 4096, 1.0)
+    xb = np.arange(4096, dtype=np.float32)
+    fb = ctx.future_from_host(xb)
+    (gb,) = ctx.run_fn(big, [fb])
+    ctx.await_(gb, fetch=False)
+    assert np.array_equal(ctx.await_(gb), xb + np.float32(1.0))
+    for h in (fb, gb):
+        ctx.future_release(h)
+    ctx.fn_release(add1)
+    ctx.fn_release(big)
+
+
 def test_sequential_mode_is_not_given_a_pending_input(ctx):
     """PW_SEQUENTIAL synchronises after every link; with a ready input it must give the same bits."""
     x = I.dispatch_input()
