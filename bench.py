@@ -307,7 +307,7 @@ def measure(args, workload, steps, warmup, torch, pwb, I):
     ctx = pwb.Context(0)
     fused_update = DEFAULT_FUSED_UPDATE if args.fused_update is None else bool(args.fused_update)
     fused_head_loss = DEFAULT_FUSED_HEAD_LOSS if args.fused_head_loss is None else bool(args.fused_head_loss)
-    model = ctx.encdec(cfg) if encdec else ctx.model(cfg, fused_update=fused_update, fused_head_loss=fused_head_loss)
+    model = ctx.encdec(cfg, fused_update=fused_update) if encdec else ctx.model(cfg, fused_update=fused_update, fused_head_loss=fused_head_loss)
     fill_model_on_device(model, cfg, torch, seed=1234)
     if encdec:
         src_np, tgt_np = I.encdec_tokens(cfg, seed=1234)
@@ -429,7 +429,7 @@ def measure(args, workload, steps, warmup, torch, pwb, I):
         "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.bf16 else "f32", "data": "synthetic",
         "config": {"workload": what, "tokens_per_step": tokens_per_step, "model_tflop_per_step": round(flops / 1e12, 3),
-                   "fused_update": bool(fused_update and not encdec), "fused_head_loss": bool(fused_head_loss and not encdec)},
+                   "fused_update": bool(fused_update), "fused_head_loss": bool(fused_head_loss and not encdec)},
         "pct_peak_bf16_mfma": round(100.0 * achieved / PEAK_BF16_TFLOPS, 2),
         "step_tflops": round(achieved, 1),
         "ms_per_step_device": {"median": round(per_step[len(per_step) // 2], 3), "min": round(per_step[0], 3),
@@ -445,8 +445,9 @@ def measure(args, workload, steps, warmup, torch, pwb, I):
     if n_fu:
         # The weight-gradient GEMMs that apply Adam in their epilogue are a kernel instantiation of their own: MFMA work
         # plus 26 bytes of optimizer traffic per parameter.  They are priced on both rooflines, next to the GEMM figure.
-        fused_params = sum(int(np.prod(sh)) for nm, sh, kind in I.param_shapes(cfg)
-                           if nm.split(".")[-1] in ("wqkv", "wo", "w1", "w2", "wh"))
+        shapes = I.encdec_param_shapes(cfg) if encdec else I.param_shapes(cfg)
+        fused_params = sum(int(np.prod(sh)) for nm, sh, kind in shapes
+                           if nm.split(".")[-1] in ("wqkv", "wo", "wq", "wkv", "wox", "w1", "w2", "wh"))
         result["roofline"]["fused_update_gemms"] = {
             "kernel": "gemm_ring_kernel / gemm_ring_group_kernel with the Adam epilogue (weight-gradient layout)",
             "launches_per_step": n_fu // profiled_steps, "ms_per_step": round(fu_ms / profiled_steps, 3),

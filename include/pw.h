@@ -347,6 +347,8 @@ typedef struct {
   int32_t bf16;          /* as in pw_lm_config */
   int32_t optimizer;     /* 1 SGD, 2 Adam */
   float lr, beta1, beta2, eps;
+  int32_t fused_update;  /* as in pw_lm_config: with bf16 and Adam, and every weight-gradient GEMM of the step on full
+                            tiles, all GEMM weights are updated inside those GEMMs; ignored (0) otherwise */
 } pw_encdec_config;
 
 /* Allocates parameters (zero), gradients, optimiser state and every activation buffer of the step up front.

@@ -80,7 +80,7 @@ class GemmArgs(C.Structure):
 class EncDecConfigC(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_enc_layer", "n_dec_layer", "d_model", "n_head", "d_ff", "vocab", "src_len",
                                          "tgt_len", "batch", "bf16", "optimizer")] + \
-               [(n, C.c_float) for n in ("lr", "beta1", "beta2", "eps")]
+               [(n, C.c_float) for n in ("lr", "beta1", "beta2", "eps")] + [("fused_update", C.c_int32)]
 
 
 class MhaArgs(C.Structure):
@@ -416,8 +416,8 @@ class Context:
     def model(self, cfg, fused_update: bool = False, fused_head_loss: bool = False) -> "Model":
         return Model(self, cfg, fused_update, fused_head_loss)
 
-    def encdec(self, cfg) -> "EncDec":
-        return EncDec(self, cfg)
+    def encdec(self, cfg, fused_update: bool = False) -> "EncDec":
+        return EncDec(self, cfg, fused_update)
 
     # -- single kernels (device pointers as ints)
     def op(self, name: str, *args):
@@ -569,11 +569,11 @@ def step_flops(cfg) -> float:
     return lib().pw_model_step_flops(C.byref(c))
 
 
-def encdec_config_c(cfg) -> EncDecConfigC:
+def encdec_config_c(cfg, fused_update: bool = False) -> EncDecConfigC:
     """From the generator module's EncDecConfig (or any object with the same fields)."""
     return EncDecConfigC(cfg.n_enc_layer, cfg.n_dec_layer, cfg.d_model, cfg.n_head, cfg.d_ff, cfg.vocab, cfg.src_len,
                          cfg.tgt_len, cfg.batch, int(cfg.bf16), {"sgd": 1, "adam": 2}[cfg.optimizer], cfg.lr, cfg.beta1,
-                         cfg.beta2, cfg.eps)
+                         cfg.beta2, cfg.eps, int(fused_update))
 
 
 def encdec_step_flops(cfg) -> float:
@@ -631,10 +631,10 @@ class EncDec(_ParamModel):
     """pw_encdec: parameters, optimiser state and the static activation plan of one encoder-decoder model."""
     _prefix = "pw_encdec"
 
-    def __init__(self, ctx: "Context", cfg):
+    def __init__(self, ctx: "Context", cfg, fused_update: bool = False):
         self.ctx, self.cfg = ctx, cfg
         self._h = C.c_void_p()
-        c = encdec_config_c(cfg)
+        c = encdec_config_c(cfg, fused_update)
         ctx._check(lib().pw_encdec_create(ctx.handle, C.byref(c), C.byref(self._h)))
         ctx._models.append(self)
         self._read_param_table()

@@ -27,19 +27,49 @@ namespace {
 constexpr int kSelfParams = 6, kCrossParams = 8, kFfnParams = 6;
 constexpr int kEncLayerParams = kSelfParams + kFfnParams, kDecLayerParams = kSelfParams + kCrossParams + kFfnParams;
 
-void build_param_table(const pw_encdec_config& c, std::vector<ParamInfo>& t, int64_t& total) {
+OptimizerConfig opt_of(const pw_encdec_config& c) { return OptimizerConfig{c.optimizer, c.lr, c.beta1, c.beta2, c.eps}; }
+
+// Whether every GEMM weight of the step gets its Adam update inside its weight-gradient GEMM: all of them or none, and
+// all only if each of those GEMMs - alone or as a member of the launch it shares - runs on the ring kernel's full tiles.
+bool fused_update_possible(const pw_encdec_config& c) {
+  if (!c.fused_update || !c.bf16 || c.optimizer != 2) return false;
+  const int64_t Ns = (int64_t)c.batch * c.src_len, Nt = (int64_t)c.batch * c.tgt_len, d = c.d_model, F = c.d_ff, V = c.vocab;
+  auto shape = [](int64_t N, int64_t in, int64_t out) {
+    GemmArgs a{};
+    a.dtype = kBF16; a.a_kmajor = 1; a.b_kmajor = 1;
+    a.M = in; a.N = out; a.K = N; a.lda = in; a.ldb = out; a.ldc = out;
+    a.epilogue = kEpiStore; a.out_dtype = kF32;
+    return a;
+  };
+  auto group_ok = [](const GemmArgs* g, int n) {
+    const bool shared = gemm_group_shares_launch(g, n);
+    for (int i = 0; i < n; ++i)
+      if (!gemm_adam_fusable(g[i], shared)) return false;
+    return true;
+  };
+  bool ok = true;
+  for (int64_t N : {Ns, Nt}) {
+    const GemmArgs pair[2] = {shape(N, d, 3 * d), shape(N, d, d)};
+    ok = ok && group_ok(pair, 2) && gemm_adam_fusable(shape(N, d, F), false) && gemm_adam_fusable(shape(N, F, d), false);
+  }
+  const GemmArgs cross[3] = {shape(Ns, d, 2 * d), shape(Nt, d, d), shape(Nt, d, d)};
+  return ok && group_ok(cross, 3) && gemm_adam_fusable(shape(Nt, d, V), false);
+}
+
+void build_param_table(const pw_encdec_config& c, std::vector<ParamInfo>& t, int64_t& total, int64_t& fused_from) {
   ParamTableBuilder tb{t};
-  auto add = [&](const std::string& n, int64_t numel) { tb.add(n, numel); };
+  const bool fz = fused_update_possible(c);
+  auto add = [&](const std::string& n, int64_t numel, bool gemm_weight = false) { tb.add(n, numel, gemm_weight && fz); };
   const int64_t d = c.d_model, F = c.d_ff, V = c.vocab;
   auto self = [&](const std::string& p) {
     add(p + "ln1_g", d); add(p + "ln1_b", d);
-    add(p + "wqkv", d * 3 * d); add(p + "bqkv", 3 * d);
-    add(p + "wo", d * d); add(p + "bo", d);
+    add(p + "wqkv", d * 3 * d, true); add(p + "bqkv", 3 * d);
+    add(p + "wo", d * d, true); add(p + "bo", d);
   };
   auto ffn = [&](const std::string& p) {
     add(p + "ln2_g", d); add(p + "ln2_b", d);
-    add(p + "w1", d * F); add(p + "b1", F);
-    add(p + "w2", F * d); add(p + "b2", d);
+    add(p + "w1", d * F, true); add(p + "b1", F);
+    add(p + "w2", F * d, true); add(p + "b2", d);
   };
   add("enc.wte", V * d);
   add("enc.wpe", (int64_t)c.src_len * d);
@@ -55,14 +85,14 @@ void build_param_table(const pw_encdec_config& c, std::vector<ParamInfo>& t, int
     const std::string p = "d" + std::to_string(l) + ".";
     self(p);
     add(p + "lnx_g", d); add(p + "lnx_b", d);
-    add(p + "wq", d * d); add(p + "bq", d);
-    add(p + "wkv", d * 2 * d); add(p + "bkv", 2 * d);
-    add(p + "wox", d * d); add(p + "box", d);
+    add(p + "wq", d * d, true); add(p + "bq", d);
+    add(p + "wkv", d * 2 * d, true); add(p + "bkv", 2 * d);
+    add(p + "wox", d * d, true); add(p + "box", d);
     ffn(p);
   }
   add("dec.lnf_g", d); add("dec.lnf_b", d);
-  add("wh", d * V);
-  total = tb.off;
+  add("wh", d * V, true);
+  tb.finish(total, fused_from);
 }
 
 // parameter indices
@@ -154,6 +184,13 @@ struct GradStream {
 
 const void* grad_operand(const EncDec* m, const GradStream& gs) { return m->bf16 ? (const void*)m->dx_lp : (const void*)gs.cur; }
 
+// The weight-gradient GEMM of weight wi = x^T dy over N rows - with the weight's Adam update in its epilogue when the
+// model updates its GEMM weights that way.  Such a GEMM rewrites the weight's bf16 copy, so every backward routine
+// below runs a weight's data-gradient GEMM (which reads that copy) before its weight-gradient GEMM.
+GemmArgs wgrad_of(EncDec* m, const void* x, const void* dy, int64_t wi, int64_t N, int64_t in, int64_t out) {
+  return m->fused_from >= 0 ? wgrad_adam_args(m, opt_of(m->cfg), x, dy, wi, N, in, out) : wgrad_args(m, x, dy, wi, N, in, out, 0);
+}
+
 // x_out = x_in + Attn(LN(x_in) Wqkv + bqkv) Wo + bo over T positions per batch; parameters e .. e+5.
 hipError_t self_fwd(EncDec* m, size_t e, const EncDec::SelfActs& A, float* x_out, int N, int T, int causal) {
   const pw_encdec_config& c = m->cfg;
@@ -181,13 +218,14 @@ hipError_t self_bwd(EncDec* m, size_t e, const EncDec::SelfActs& A, GradStream& 
   const MhaArgs a{dt, qkv, qkv + d * es, qkv + 2 * d * es, 3 * (int64_t)d, 3 * (int64_t)d, c.batch, T, T, c.n_head, m->hd(), causal};
   PW_TRY(launch_mha_bwd(m->stream, a, A.o, A.o_lo, m->d_small, A.lse, m->delta, dqkv, 3 * (int64_t)d, dqkv + d * es, dqkv + 2 * d * es,
                         3 * (int64_t)d), "self-attention bwd");
-  // (dy, the residual gradient in operand form, stays intact until the LayerNorm backward below rewrites it)
+  // (dy, the residual gradient in operand form, stays intact until the LayerNorm backward below rewrites it; d_small,
+  //  the attention backward's input, is free again and takes the QKV data gradient)
+  PW_TRY(gemm_dgrad(m, m->d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small, dt, 0), "qkv dgrad");
   {
-    const WgradJob jobs[2] = {{wgrad_args(m, A.a, m->d_qkv, e + 2, N, d, 3 * d, 0), (int64_t)e + 3},
-                              {wgrad_args(m, A.o, dy, e + 4, N, d, d, 0), -1}};
+    const WgradJob jobs[2] = {{wgrad_of(m, A.a, m->d_qkv, e + 2, N, d, 3 * d), (int64_t)e + 3},
+                              {wgrad_of(m, A.o, dy, e + 4, N, d, d), -1}};
     PW_TRY(gemm_wgrad_group(m, jobs, 2, m->ws), "qkv + out-proj wgrad + bqkv grad");
   }
-  PW_TRY(gemm_dgrad(m, m->d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small, dt, 0), "qkv dgrad");
   PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->wp(e), A.mean, A.rstd, gs.cur, gs.other,
                               m->bf16 ? m->dx_lp : nullptr, m->gp(e), m->gp(e + 1), below_bias, m->ws, N, d, 0), "self-attention LN bwd");
   gs.swap();
@@ -222,15 +260,15 @@ hipError_t cross_bwd(EncDec* m, size_t e, const EncDec::CrossActs& A, GradStream
   const MhaArgs a{dt, A.q, kv, kv + d * es, (int64_t)d, 2 * (int64_t)d, c.batch, c.tgt_len, c.src_len, c.n_head, m->hd(), 0};
   PW_TRY(launch_mha_bwd(m->stream, a, A.o, A.o_lo, m->d_small, A.lse, m->delta, m->d_q, (int64_t)d, dkv, dkv + d * es, 2 * (int64_t)d),
          "cross-attention bwd");
-  {
-    // three weight gradients that each cover a quarter to a half of the chip: one launch
-    const WgradJob jobs[3] = {{wgrad_args(m, m->mem, dkv, e + 4, Ns, d, 2 * d, 0), (int64_t)e + 5},
-                              {wgrad_args(m, A.a, m->d_q, e + 2, Nt, d, d, 0), (int64_t)e + 3},
-                              {wgrad_args(m, A.o, dy, e + 6, Nt, d, d, 0), -1}};
-    PW_TRY(gemm_wgrad_group(m, jobs, 3, m->ws), "cross kv + q + out-proj wgrad + bias grads");
-  }
   PW_TRY(gemm_dgrad(m, dkv, e + 4, Ns, d, 2 * d, kEpiStore, nullptr, m->dmem, kF32, dmem_accumulate), "cross kv dgrad");
   PW_TRY(gemm_dgrad(m, m->d_q, e + 2, Nt, d, d, kEpiStore, nullptr, m->d_small, dt, 0), "cross q dgrad");
+  {
+    // three weight gradients that each cover a quarter to a half of the chip: one launch
+    const WgradJob jobs[3] = {{wgrad_of(m, m->mem, dkv, e + 4, Ns, d, 2 * d), (int64_t)e + 5},
+                              {wgrad_of(m, A.a, m->d_q, e + 2, Nt, d, d), (int64_t)e + 3},
+                              {wgrad_of(m, A.o, dy, e + 6, Nt, d, d), -1}};
+    PW_TRY(gemm_wgrad_group(m, jobs, 3, m->ws), "cross kv + q + out-proj wgrad + bias grads");
+  }
   PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->wp(e), A.mean, A.rstd, gs.cur, gs.other,
                               m->bf16 ? m->dx_lp : nullptr, m->gp(e), m->gp(e + 1), below_bias, m->ws, Nt, d, 0), "cross-attention LN bwd");
   gs.swap();
@@ -249,10 +287,11 @@ hipError_t ffn_fwd(EncDec* m, size_t e, const EncDec::FfnActs& A, float* x_out, 
 hipError_t ffn_bwd(EncDec* m, size_t e, const EncDec::FfnActs& A, GradStream& gs, float* below_bias, int N) {
   const int d = m->cfg.d_model, F = m->cfg.d_ff, dt = m->act_dtype();
   const void* dy = grad_operand(m, gs);
-  PW_TRY(launch_gemm(m->stream, wgrad_args(m, A.h, dy, e + 4, N, F, d, 0)), "ffn2 wgrad");
+  const OptimizerConfig opt = opt_of(m->cfg);
   PW_TRY(gemm_dgrad(m, dy, e + 4, N, F, d, kEpiGeluBwd, A.u, m->d_big, dt, 0), "ffn2 dgrad + gelu'");
-  PW_TRY(gemm_wgrad_bias(m, A.mm, m->d_big, e + 2, e + 3, N, d, F, 0, m->ws), "ffn1 wgrad + b1 grad");
+  PW_TRY(launch_gemm(m->stream, wgrad_of(m, A.h, dy, e + 4, N, F, d)), "ffn2 wgrad");
   PW_TRY(gemm_dgrad(m, m->d_big, e + 2, N, d, F, kEpiStore, nullptr, m->d_small, dt, 0), "ffn1 dgrad");
+  PW_TRY(gemm_wgrad_bias(m, A.mm, m->d_big, e + 2, e + 3, N, d, F, 0, m->ws, m->fused_from >= 0 ? &opt : nullptr), "ffn1 wgrad + b1 grad");
   PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->wp(e), A.mean, A.rstd, gs.cur, gs.other,
                               m->bf16 ? m->dx_lp : nullptr, m->gp(e), m->gp(e + 1), below_bias, m->ws, N, d, 0), "ffn LN bwd");
   gs.swap();
@@ -294,7 +333,7 @@ hipError_t encdec_create(const pw_encdec_config& cfg, hipStream_t stream, EncDec
   m->cfg = cfg;
   m->stream = stream;
   m->bf16 = cfg.bf16 ? 1 : 0;
-  build_param_table(cfg, m->params, m->total);
+  build_param_table(cfg, m->params, m->total, m->fused_from);
   hipError_t e = model_state_alloc(m, OptimizerConfig{cfg.optimizer, cfg.lr, cfg.beta1, cfg.beta2, cfg.eps}, err);
   if (e != hipSuccess) {
     delete m;
@@ -353,8 +392,8 @@ hipError_t encdec_train_step(EncDec* m, const int32_t* src, const int32_t* tgt, 
   PW_TRY(launch_softmax_xent(m->stream, dt, m->logits, tgt, loss, m->row_loss, c.batch, c.tgt_len, V), "softmax-xent");
 
   // ---- backward: head (logits now hold dlogits) and decoder
-  PW_TRY(launch_gemm(m->stream, wgrad_args(m, m->y, m->logits, dtl + 2, Nt, d, V, 0)), "head wgrad");
   PW_TRY(gemm_dgrad(m, m->logits, dtl + 2, Nt, d, V, kEpiStore, nullptr, m->d_small, dt, 0), "head dgrad");
+  PW_TRY(launch_gemm(m->stream, wgrad_of(m, m->y, m->logits, dtl + 2, Nt, d, V)), "head wgrad");
   GradStream gs{m->dx_a, m->dx_b};
   const size_t top_dec = dec_layer_base(c, Ld - 1);
   PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, m->dec_x_out, m->wp(dtl), m->meanf, m->rstdf, nullptr, gs.cur,
@@ -394,7 +433,7 @@ hipError_t encdec_train_step(EncDec* m, const int32_t* src, const int32_t* tgt, 
   }
   PW_TRY(launch_embedding_bwd(m->stream, src, gs.cur, m->gp(0), m->gp(1), c.batch, c.src_len, d, V, c.src_len), "encoder embedding bwd");
 
-  return model_state_apply_optimizer(m, OptimizerConfig{c.optimizer, c.lr, c.beta1, c.beta2, c.eps});
+  return model_state_apply_optimizer(m, opt_of(c));
 }
 
 double encdec_step_flops(const pw_encdec_config& c) {

@@ -51,11 +51,7 @@ FusedPlan fused_plan(const pw_lm_config& c) {
 void build_param_table(const pw_lm_config& c, std::vector<ParamInfo>& t, int64_t& total, int64_t& fused_from) {
   ParamTableBuilder tb{t};
   const FusedPlan fp = fused_plan(c);
-  std::vector<char> late;   // per parameter: updated in its weight-gradient GEMM -> placed behind all the others
-  auto add = [&](const std::string& n, int64_t numel, bool fused = false) {
-    tb.add(n, numel);
-    late.push_back(fused ? 1 : 0);
-  };
+  auto add = [&](const std::string& n, int64_t numel, bool fused = false) { tb.add(n, numel, fused); };
   const int64_t d = c.d_model, F = c.d_ff, V = c.vocab, T = c.seq;
   if (c.has_embed) {
     add("wte", V * d);
@@ -74,19 +70,7 @@ void build_param_table(const pw_lm_config& c, std::vector<ParamInfo>& t, int64_t
     add("lnf_g", d); add("lnf_b", d);
     add("wh", d * V, fp.wh);
   }
-  total = tb.off;
-  // Offsets again, in two runs: everything the optimizer launch updates first, then the weights updated by their
-  // GEMMs, so that the launch covers one contiguous range.  (Index order, which is what the API shows, is unchanged.)
-  fused_from = -1;
-  int64_t off = 0;
-  for (int pass = 0; pass < 2; ++pass) {
-    for (size_t i = 0; i < t.size(); ++i) {
-      if (late[i] != pass) continue;
-      if (pass == 1 && fused_from < 0) fused_from = off;
-      t[i].offset = off;
-      off += (t[i].numel + kParamAlign - 1) / kParamAlign * kParamAlign;
-    }
-  }
+  tb.finish(total, fused_from);
 }
 
 // Assigns every activation / scratch pointer; with base == nullptr only measures.

@@ -56,9 +56,26 @@ constexpr int64_t kParamAlign = 64;   // elements; keeps every tensor 256-byte a
 struct ParamTableBuilder {
   std::vector<ParamInfo>& t;
   int64_t off = 0;
-  void add(const std::string& n, int64_t numel) {
+  std::vector<char> late;   // per parameter: updated inside its weight-gradient GEMM
+  void add(const std::string& n, int64_t numel, bool updated_in_gemm = false) {
     t.push_back({n, off, numel});
+    late.push_back(updated_in_gemm ? 1 : 0);
     off += (numel + kParamAlign - 1) / kParamAlign * kParamAlign;
+  }
+  // Offsets again, in two runs: everything the optimizer launch updates first, then the weights updated by their
+  // GEMMs, so that the launch covers one contiguous range [0, fused_from) (-1: no such weights).  Index order, which
+  // is what the API shows, is unchanged.
+  void finish(int64_t& total, int64_t& fused_from) {
+    total = off;
+    fused_from = -1;
+    int64_t o = 0;
+    for (int pass = 0; pass < 2; ++pass)
+      for (size_t i = 0; i < t.size(); ++i) {
+        if (late[i] != pass) continue;
+        if (pass == 1 && fused_from < 0) fused_from = o;
+        t[i].offset = o;
+        o += (t[i].numel + kParamAlign - 1) / kParamAlign * kParamAlign;
+      }
   }
 };
 

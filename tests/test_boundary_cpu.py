@@ -37,7 +37,7 @@ def test_struct_layouts_match_the_header(tmp_path):
     structs = [("pw_tensor_spec", pwb.TensorSpec, "dims"), ("pw_fn_desc", pwb.FnDesc, "params_bytes"),
                ("pw_lm_config", pwb.LMConfigC, "fused_head_loss"), ("pw_stage_params", pwb.StageParams, "microbatch"),
                ("pw_gemm_args", pwb.GemmArgs, "xent"), ("pw_adam_epilogue", pwb.AdamEpilogue, "t"),
-               ("pw_xent_epilogue", pwb.XentEpilogue, "inv_n"), ("pw_mha_args", pwb.MhaArgs, "causal"), ("pw_encdec_config", pwb.EncDecConfigC, "eps"), ("pw_node", pwb.Node, "in"),
+               ("pw_xent_epilogue", pwb.XentEpilogue, "inv_n"), ("pw_mha_args", pwb.MhaArgs, "causal"), ("pw_encdec_config", pwb.EncDecConfigC, "fused_update"), ("pw_node", pwb.Node, "in"),
                ("pw_sched_slice", pwb.SchedSlice, "end_ms"), ("pw_gemm_shape_row", pwb.GemmShapeRow, "total_flops")]
     src = tmp_path / "sizes.c"
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "pw.h"', 'int main(void) {']

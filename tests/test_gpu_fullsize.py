@@ -454,4 +454,40 @@ def test_one_layer_encoder_decoder_step_at_full_layer_width_matches_oracle(orc):
             worst = max(worst, (k, err), key=lambda t: t[1])
             assert_close(g, ref["grads"][k], 2e-2, k)
         print("worst gradient error", worst)
+        plain = model.export_all(pwb.PW_PARAMS, params)            # after the step's Adam launch
+        model.close()
+    # The same step with every GEMM weight updated inside its weight-gradient GEMM (the pair, the three-way launch and
+    # the single launches alike).  Those gradients are not stored: after the first step m / (1 - beta1) is the
+    # gradient and v / (1 - beta2) its square; the update itself must be the one the optimizer launch made above from
+    # the same accumulator values.
+    big = [k for k in params if k.split(".")[-1] in ("wqkv", "wo", "wq", "wkv", "wox", "w1", "w2", "wh")]
+    assert len(big) == 12
+    with pwb.Context(0) as ctx:
+        model = ctx.encdec(cfg, fused_update=True)
+        model.load_params(params)
+        step = model.compile_train_step()
+        fs, ft = ctx.future_from_host(src), ctx.future_from_host(tgt)
+        (fl,) = ctx.run_fn(step, [fs, ft], 1)
+        loss = float(ctx.await_(fl)[0])
+        assert abs(loss - ref["loss"]) / abs(ref["loss"]) < 2e-2, (loss, ref["loss"])
+        m1 = model.export_all(pwb.PW_ADAM_M, params)
+        v1 = model.export_all(pwb.PW_ADAM_V, params)
+        new = model.export_all(pwb.PW_PARAMS, params)
+        for k in params:
+            g_ref = ref["grads"][k]
+            assert_close(m1[k].astype(np.float64).reshape(g_ref.shape) / (1 - cfg.beta1), g_ref, 2e-2, k + " (from m)")
+            assert_close(v1[k].astype(np.float64).reshape(g_ref.shape) / (1 - cfg.beta2), g_ref ** 2, 4e-2, k + " (from v)")
+            if k in big:
+                with pytest.raises(pwb.PwError) as e:
+                    model.export(pwb.PW_GRADS, k)
+                assert e.value.status == pwb.PW_ERR_UNSUPPORTED
+            else:
+                assert_close(model.export(pwb.PW_GRADS, k).reshape(g_ref.shape), g_ref, 2e-2, k)
+            w0 = params[k].astype(np.float64).reshape(-1)
+            assert_close(new[k].astype(np.float64).reshape(-1) - w0, plain[k].astype(np.float64).reshape(-1) - w0, 1e-4,
+                         k + " (update)", extra=np.abs(w0) * 1.2e-7)
+        # a second step runs on the weights and bf16 copies the epilogues wrote
+        (fl2,) = ctx.run_fn(step, [fs, ft], 1)
+        loss2 = float(ctx.await_(fl2)[0])
+        assert loss2 < loss
         model.close()
