@@ -163,6 +163,7 @@ size_t plan(EncDec* m, unsigned char* base) {
   m->dmem = cv.take<float>(Ns * d * 4);
   m->delta = cv.take<float>(BH * std::max(c.src_len, c.tgt_len) * 4);
   m->dx_lp = cv.take<void>(Nmax * d * es);
+  m->dx_lp2 = c.bf16 ? cv.take<void>(Nmax * d * es) : nullptr;
   m->d_big = cv.take<void>(Nmax * F * es);
   m->d_qkv = cv.take<void>(Nmax * 3 * d * es);
   m->d_small = cv.take<void>(Nmax * d * es);
@@ -175,14 +176,18 @@ size_t plan(EncDec* m, unsigned char* base) {
 
 // The gradient w.r.t. the residual stream travels in two fp32 buffers that alternate (a LayerNorm backward reads
 // one as the residual branch and writes the sum to the other) plus, in bf16 mode, a bf16 copy of the current
-// one in dx_lp, the GEMM operand.
+// one, the GEMM operand, which alternates between two buffers likewise: a sub-block's LayerNorm backward runs right
+// behind the data-gradient GEMM that produced its input (while that is still in the caches) and writes the copy for
+// the sub-block below, and the weight-gradient GEMMs that follow still read the copy of this sub-block.
 struct GradStream {
   float* cur;
   float* other;
-  void swap() { std::swap(cur, other); }
+  void* lp_cur;     // bf16 copy of cur (bf16 mode)
+  void* lp_other;
+  void swap() { std::swap(cur, other); std::swap(lp_cur, lp_other); }
 };
 
-const void* grad_operand(const EncDec* m, const GradStream& gs) { return m->bf16 ? (const void*)m->dx_lp : (const void*)gs.cur; }
+const void* grad_operand(const EncDec* m, const GradStream& gs) { return m->bf16 ? (const void*)gs.lp_cur : (const void*)gs.cur; }
 
 // The weight-gradient GEMM of weight wi = x^T dy over N rows - with the weight's Adam update in its epilogue when the
 // model updates its GEMM weights that way.  Such a GEMM rewrites the weight's bf16 copy, so every backward routine
@@ -218,16 +223,15 @@ hipError_t self_bwd(EncDec* m, size_t e, const EncDec::SelfActs& A, GradStream& 
   const MhaArgs a{dt, qkv, qkv + d * es, qkv + 2 * d * es, 3 * (int64_t)d, 3 * (int64_t)d, c.batch, T, T, c.n_head, m->hd(), causal};
   PW_TRY(launch_mha_bwd(m->stream, a, A.o, A.o_lo, m->d_small, A.lse, m->delta, dqkv, 3 * (int64_t)d, dqkv + d * es, dqkv + 2 * d * es,
                         3 * (int64_t)d), "self-attention bwd");
-  // (dy, the residual gradient in operand form, stays intact until the LayerNorm backward below rewrites it; d_small,
-  //  the attention backward's input, is free again and takes the QKV data gradient)
+  // (d_small, the attention backward's input, is free again and takes the QKV data gradient)
   PW_TRY(gemm_dgrad(m, m->d_qkv, e + 2, N, d, 3 * d, kEpiStore, nullptr, m->d_small, dt, 0), "qkv dgrad");
+  PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->wp(e), A.mean, A.rstd, gs.cur, gs.other,
+                              m->bf16 ? gs.lp_other : nullptr, m->gp(e), m->gp(e + 1), below_bias, m->ws, N, d, 0), "self-attention LN bwd");
   {
     const WgradJob jobs[2] = {{wgrad_of(m, A.a, m->d_qkv, e + 2, N, d, 3 * d), (int64_t)e + 3},
                               {wgrad_of(m, A.o, dy, e + 4, N, d, d), -1}};
     PW_TRY(gemm_wgrad_group(m, jobs, 2, m->ws), "qkv + out-proj wgrad + bqkv grad");
   }
-  PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->wp(e), A.mean, A.rstd, gs.cur, gs.other,
-                              m->bf16 ? m->dx_lp : nullptr, m->gp(e), m->gp(e + 1), below_bias, m->ws, N, d, 0), "self-attention LN bwd");
   gs.swap();
   return hipSuccess;
 }
@@ -262,6 +266,8 @@ hipError_t cross_bwd(EncDec* m, size_t e, const EncDec::CrossActs& A, GradStream
          "cross-attention bwd");
   PW_TRY(gemm_dgrad(m, dkv, e + 4, Ns, d, 2 * d, kEpiStore, nullptr, m->dmem, kF32, dmem_accumulate), "cross kv dgrad");
   PW_TRY(gemm_dgrad(m, m->d_q, e + 2, Nt, d, d, kEpiStore, nullptr, m->d_small, dt, 0), "cross q dgrad");
+  PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->wp(e), A.mean, A.rstd, gs.cur, gs.other,
+                              m->bf16 ? gs.lp_other : nullptr, m->gp(e), m->gp(e + 1), below_bias, m->ws, Nt, d, 0), "cross-attention LN bwd");
   {
     // three weight gradients that each cover a quarter to a half of the chip: one launch
     const WgradJob jobs[3] = {{wgrad_of(m, m->mem, dkv, e + 4, Ns, d, 2 * d), (int64_t)e + 5},
@@ -269,8 +275,6 @@ hipError_t cross_bwd(EncDec* m, size_t e, const EncDec::CrossActs& A, GradStream
                               {wgrad_of(m, A.o, dy, e + 6, Nt, d, d), -1}};
     PW_TRY(gemm_wgrad_group(m, jobs, 3, m->ws), "cross kv + q + out-proj wgrad + bias grads");
   }
-  PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->wp(e), A.mean, A.rstd, gs.cur, gs.other,
-                              m->bf16 ? m->dx_lp : nullptr, m->gp(e), m->gp(e + 1), below_bias, m->ws, Nt, d, 0), "cross-attention LN bwd");
   gs.swap();
   return hipSuccess;
 }
@@ -289,11 +293,11 @@ hipError_t ffn_bwd(EncDec* m, size_t e, const EncDec::FfnActs& A, GradStream& gs
   const void* dy = grad_operand(m, gs);
   const OptimizerConfig opt = opt_of(m->cfg);
   PW_TRY(gemm_dgrad(m, dy, e + 4, N, F, d, kEpiGeluBwd, A.u, m->d_big, dt, 0), "ffn2 dgrad + gelu'");
-  PW_TRY(launch_gemm(m->stream, wgrad_of(m, A.h, dy, e + 4, N, F, d)), "ffn2 wgrad");
   PW_TRY(gemm_dgrad(m, m->d_big, e + 2, N, d, F, kEpiStore, nullptr, m->d_small, dt, 0), "ffn1 dgrad");
-  PW_TRY(gemm_wgrad_bias(m, A.mm, m->d_big, e + 2, e + 3, N, d, F, 0, m->ws, m->fused_from >= 0 ? &opt : nullptr), "ffn1 wgrad + b1 grad");
   PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_in, m->wp(e), A.mean, A.rstd, gs.cur, gs.other,
-                              m->bf16 ? m->dx_lp : nullptr, m->gp(e), m->gp(e + 1), below_bias, m->ws, N, d, 0), "ffn LN bwd");
+                              m->bf16 ? gs.lp_other : nullptr, m->gp(e), m->gp(e + 1), below_bias, m->ws, N, d, 0), "ffn LN bwd");
+  PW_TRY(launch_gemm(m->stream, wgrad_of(m, A.h, dy, e + 4, N, F, d)), "ffn2 wgrad");
+  PW_TRY(gemm_wgrad_bias(m, A.mm, m->d_big, e + 2, e + 3, N, d, F, 0, m->ws, m->fused_from >= 0 ? &opt : nullptr), "ffn1 wgrad + b1 grad");
   gs.swap();
   return hipSuccess;
 }
@@ -394,10 +398,10 @@ hipError_t encdec_train_step(EncDec* m, const int32_t* src, const int32_t* tgt, 
   // ---- backward: head (logits now hold dlogits) and decoder
   PW_TRY(gemm_dgrad(m, m->logits, dtl + 2, Nt, d, V, kEpiStore, nullptr, m->d_small, dt, 0), "head dgrad");
   PW_TRY(launch_gemm(m->stream, wgrad_of(m, m->y, m->logits, dtl + 2, Nt, d, V)), "head wgrad");
-  GradStream gs{m->dx_a, m->dx_b};
+  GradStream gs{m->dx_a, m->dx_b, m->dx_lp, m->dx_lp2};
   const size_t top_dec = dec_layer_base(c, Ld - 1);
   PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, m->dec_x_out, m->wp(dtl), m->meanf, m->rstdf, nullptr, gs.cur,
-                              m->bf16 ? m->dx_lp : nullptr, m->gp(dtl), m->gp(dtl + 1), m->gp(top_dec + kDecLayerParams - 1), m->ws,
+                              m->bf16 ? gs.lp_cur : nullptr, m->gp(dtl), m->gp(dtl + 1), m->gp(top_dec + kDecLayerParams - 1), m->ws,
                               Nt, d, 0), "decoder final LN bwd");
   for (int l = Ld - 1; l >= 0; --l) {
     const size_t e = dec_layer_base(c, l);
@@ -418,10 +422,10 @@ hipError_t encdec_train_step(EncDec* m, const int32_t* src, const int32_t* tgt, 
     PW_TRY(launch_f32_to_bf16(m->stream, m->dmem, m->d_small, (int64_t)Ns * d), "dmem to bf16");
     dmem_op = m->d_small;
   }
-  gs = GradStream{m->dx_a, m->dx_b};
+  gs = GradStream{m->dx_a, m->dx_b, m->dx_lp, m->dx_lp2};
   const size_t top_enc = enc_layer_base(Le - 1);
   PW_TRY(launch_layernorm_bwd(m->stream, dt, dmem_op, m->enc_x_out, m->wp(et), m->enc_meanf, m->enc_rstdf, nullptr, gs.cur,
-                              m->bf16 ? m->dx_lp : nullptr, m->gp(et), m->gp(et + 1), m->gp(top_enc + kEncLayerParams - 1), m->ws, Ns,
+                              m->bf16 ? gs.lp_cur : nullptr, m->gp(et), m->gp(et + 1), m->gp(top_enc + kEncLayerParams - 1), m->ws, Ns,
                               d, 0), "encoder final LN bwd");
   for (int l = Le - 1; l >= 0; --l) {
     const size_t e = enc_layer_base(l);

@@ -25,7 +25,7 @@ struct EncDec : ModelBase {
   void *y = nullptr, *logits = nullptr;
   // backward scratch, sized for the longer of the two sides
   float *dx_a = nullptr, *dx_b = nullptr, *delta = nullptr, *ws = nullptr, *dmem = nullptr;
-  void *dx_lp = nullptr, *d_big = nullptr, *d_qkv = nullptr, *d_small = nullptr, *d_q = nullptr;
+  void *dx_lp = nullptr, *dx_lp2 = nullptr, *d_big = nullptr, *d_qkv = nullptr, *d_small = nullptr, *d_q = nullptr;
 
   int Ns() const { return cfg.batch * cfg.src_len; }
   int Nt() const { return cfg.batch * cfg.tgt_len; }

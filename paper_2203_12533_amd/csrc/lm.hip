@@ -203,19 +203,21 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
     if (l == c.n_layer - 1 && !top_b2_done)
       PW_TRY(launch_colsum(m->stream, kF32, m->dx_a, g + P(m, e + 11).offset, m->ws, N, d, accumulate), "b2 grad");
     PW_TRY(gemm_dgrad(m, dx_op, e + 10, N, F, d, kEpiGeluBwd, A.u, d_big, dt, 0), "ffn2 dgrad + gelu'");
-    if (!defer)
-      PW_TRY(launch_gemm(m->stream, fz.w2 ? wgrad_adam_args(m, opt, A.h, dx_op, e + 10, N, F, d)
-                                          : wgrad_args(m, A.h, dx_op, e + 10, N, F, d, accumulate)), "ffn2 wgrad");
     // FFN1: u = m W1 + b1
     // (b1 gradient = column sums of d_big: delivered by the weight-gradient GEMM where that is free)
     PW_TRY(gemm_dgrad(m, d_big, e + 8, N, d, F, kEpiStore, nullptr, m->d_small, dt, 0), "ffn1 dgrad");
-    // LN2 and the residual branch: dx_b = dx_a + LN2'(d_small).  It runs right behind the GEMM that wrote d_small and
-    // before the FFN1 weight gradient, which needs nothing of it: that GEMM (and, fused, the optimizer traffic of its
-    // epilogue) would otherwise push d_small and the residual gradient out of the memory-side cache first.
+    // LN2 and the residual branch: dx_b = dx_a + LN2'(d_small).  The chain FFN2 data gradient -> FFN1 data gradient ->
+    // LN2 backward runs without the two weight-gradient GEMMs in between, which need nothing of it: those GEMMs (and,
+    // fused, the optimizer traffic of their epilogues) would otherwise push d_big, d_small and the residual gradient
+    // out of the caches before their one reader gets to them.
     PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_mid, m->w + P(m, e + 6).offset, A.mean2, A.rstd2, m->dx_a,
                                 m->dx_b, c.bf16 ? lp_mid : nullptr, g + P(m, e + 6).offset, g + P(m, e + 7).offset,
                                 g + P(m, e + 5).offset /* bo */, m->ws, N, d, accumulate), "ln2 bwd");
-    if (!defer) PW_TRY(gemm_wgrad_bias(m, A.mm, d_big, e + 8, e + 9, N, d, F, accumulate, m->ws, fz.w1 ? &opt : nullptr), "ffn1 wgrad + b1 grad");
+    if (!defer) {
+      PW_TRY(launch_gemm(m->stream, fz.w2 ? wgrad_adam_args(m, opt, A.h, dx_op, e + 10, N, F, d)
+                                          : wgrad_args(m, A.h, dx_op, e + 10, N, F, d, accumulate)), "ffn2 wgrad");
+      PW_TRY(gemm_wgrad_bias(m, A.mm, d_big, e + 8, e + 9, N, d, F, accumulate, m->ws, fz.w1 ? &opt : nullptr), "ffn1 wgrad + b1 grad");
+    }
     dx_op = c.bf16 ? (const void*)lp_mid : (const void*)m->dx_b;
     // out-proj: x_mid = x_in + o Wo + bo
     // (its weight gradient is computed together with the QKV one below: neither fills the chip alone)
