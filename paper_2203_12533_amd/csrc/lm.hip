@@ -142,6 +142,7 @@ size_t plan(Model* m, unsigned char* base) {
   m->delta = cv.take<float>(BHT * 4);
   m->dx_lp = cv.take<void>(N * d * es);
   m->dx_lp2 = cv.take<void>(N * d * es);
+  m->dx_lp3 = cv.take<void>(N * d * es);
   m->d_big = cv.take<void>(N * F * es);
   m->d_qkv = cv.take<void>(N * 3 * d * es);
   m->d_small = cv.take<void>(N * d * es);
@@ -195,8 +196,15 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
     void* const d_big = defer ? A.g_u : m->d_big;
     void* const d_qkv = defer ? A.g_qkv : m->d_qkv;
     void* const lp_mid = defer ? A.g_yo : m->dx_lp2;                                   // bf16 copy of dx_b
-    void* const lp_below = defer && l > 0 ? s.layer[l - 1].g_y2 : m->dx_lp;            // bf16 copy of the new dx_a
-    const void* dx_op = c.bf16 ? (defer ? (const void*)A.g_y2 : (const void*)m->dx_lp) : (const void*)m->dx_a;
+    // All weight gradients of the layer at its end (bf16, not deferred): the bf16 copy of the layer's incoming gradient,
+    // which the FFN2 weight gradient reads, must then survive LN1's backward - the copies of consecutive layers
+    // alternate between two buffers.
+    const bool late = c.bf16 && !defer;
+    const bool odd = ((c.n_layer - 1 - l) & 1) != 0;
+    void* const lp_in = late && odd ? m->dx_lp3 : m->dx_lp;
+    void* const lp_below = defer && l > 0 ? s.layer[l - 1].g_y2 : (late && !odd ? m->dx_lp3 : m->dx_lp);   // bf16 copy of the new dx_a
+    const void* dx_op = c.bf16 ? (defer ? (const void*)A.g_y2 : (const void*)lp_in) : (const void*)m->dx_a;
+    const void* const dx_in = dx_op;
     // Every data gradient comes BEFORE the weight gradient of the same layer: a weight gradient whose epilogue
     // applies the optimizer (fused update) rewrites the weight its data gradient still has to read.
     // FFN2: x_out = x_mid + h W2 + b2
@@ -213,10 +221,15 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
     PW_TRY(launch_layernorm_bwd(m->stream, dt, m->d_small, A.x_mid, m->w + P(m, e + 6).offset, A.mean2, A.rstd2, m->dx_a,
                                 m->dx_b, c.bf16 ? lp_mid : nullptr, g + P(m, e + 6).offset, g + P(m, e + 7).offset,
                                 g + P(m, e + 5).offset /* bo */, m->ws, N, d, accumulate), "ln2 bwd");
-    if (!defer) {
-      PW_TRY(launch_gemm(m->stream, fz.w2 ? wgrad_adam_args(m, opt, A.h, dx_op, e + 10, N, F, d)
-                                          : wgrad_args(m, A.h, dx_op, e + 10, N, F, d, accumulate)), "ffn2 wgrad");
+    auto ffn_wgrads = [&]() -> hipError_t {
+      PW_TRY(launch_gemm(m->stream, fz.w2 ? wgrad_adam_args(m, opt, A.h, dx_in, e + 10, N, F, d)
+                                          : wgrad_args(m, A.h, dx_in, e + 10, N, F, d, accumulate)), "ffn2 wgrad");
       PW_TRY(gemm_wgrad_bias(m, A.mm, d_big, e + 8, e + 9, N, d, F, accumulate, m->ws, fz.w1 ? &opt : nullptr), "ffn1 wgrad + b1 grad");
+      return hipSuccess;
+    };
+    if (!defer && !late) {
+      const hipError_t er = ffn_wgrads();
+      if (er != hipSuccess) return er;
     }
     dx_op = c.bf16 ? (const void*)lp_mid : (const void*)m->dx_b;
     // out-proj: x_mid = x_in + o Wo + bo
@@ -233,6 +246,10 @@ hipError_t layers_backward(Model* m, Model::Slot& s, int accumulate, bool top_b2
                                 m->dx_a, c.bf16 ? lp_below : nullptr, g + P(m, e).offset, g + P(m, e + 1).offset,
                                 l > 0 ? g + P(m, layer_base(m, l - 1) + 11).offset /* b2 of the layer below */ : nullptr,
                                 m->ws, N, d, accumulate), "ln1 bwd");
+    if (late) {
+      const hipError_t er = ffn_wgrads();
+      if (er != hipSuccess) return er;
+    }
     if (!defer) {
       const WgradJob jobs[2] = {{fz.qkv ? wgrad_adam_args(m, opt, A.a, d_qkv, e + 2, N, d, 3 * d)
                                         : wgrad_args(m, A.a, d_qkv, e + 2, N, d, 3 * d, accumulate), (int64_t)e + 3},

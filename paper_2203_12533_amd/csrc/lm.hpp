@@ -50,6 +50,7 @@ struct Model : ModelBase {
   // backward scratch
   float *dx_a = nullptr, *dx_b = nullptr, *delta = nullptr, *ws = nullptr;
   void *dx_lp = nullptr, *d_big = nullptr, *d_qkv = nullptr, *d_small = nullptr;
+  void* dx_lp3 = nullptr;   // second home of the copy at a layer's input / output (the two alternate from layer to layer)
   void* dx_lp2 = nullptr;   // bf16 copy of the residual gradient at a layer's mid-point (dx_lp: at its input / output)
 
   int N() const { return cfg.batch * cfg.seq; }
