@@ -18,9 +18,9 @@ def ctx():
     c.close()
 
 
-def run_steps(ctx, cfg, params, src, tgt, n_steps=1):
+def run_steps(ctx, cfg, params, src, tgt, n_steps=1, fused_update=False):
     """Runs n_steps train steps through the dispatch API; returns (losses, model) - caller closes the model."""
-    model = ctx.encdec(cfg)
+    model = ctx.encdec(cfg, fused_update=fused_update)
     model.load_params(params)
     step = model.compile_train_step()
     losses = []
@@ -120,6 +120,30 @@ def test_bf16_full_tile_shapes_match_oracle(ctx, orc):
     worst = check_against_oracle(params, ref, loss, model, TOL[True], check_update=False)
     print("enc-dec bf16 full-tile worst gradient error", worst)
     model.close()
+
+
+def test_fused_update_switch_where_it_cannot_apply(ctx):
+    """The switch takes effect only if every weight-gradient GEMM of the step can carry the epilogue (bf16, Adam, full
+    256 x 256 tiles, enough of them per launch); it is all or nothing.  On ragged shapes, in fp32, with SGD, and on
+    full-tile shapes too small for the kernel the epilogue lives in, a model created with it behaves bit for bit like
+    one created without, gradients exportable as ever.  (Where it applies: the full-width layer pair of
+    test_gpu_fullsize.py.)"""
+    for cfg in (BF16_SMALL,
+                I.EncDecConfig(1, 1, 256, 2, 512, 512, 72, 40, 2, bf16=False, optimizer="adam", lr=1e-4),
+                I.EncDecConfig(1, 1, 512, 4, 1024, 512, 512, 256, 2, bf16=True, optimizer="sgd", lr=1e-2),
+                I.EncDecConfig(1, 1, 512, 4, 1024, 512, 512, 256, 2, bf16=True, optimizer="adam", lr=1e-4)):
+        params = I.encdec_params(cfg, perturb=True)
+        src, tgt = I.encdec_tokens(cfg)
+        l0, m0 = run_steps(ctx, cfg, params, src, tgt, n_steps=2)
+        l1, m1 = run_steps(ctx, cfg, params, src, tgt, n_steps=2, fused_update=True)
+        assert l0 == l1
+        w0, w1 = m0.export_all(pwb.PW_PARAMS, params), m1.export_all(pwb.PW_PARAMS, params)
+        g0, g1 = m0.export_all(pwb.PW_GRADS, params), m1.export_all(pwb.PW_GRADS, params)
+        for k in params:
+            assert np.array_equal(w0[k], w1[k]), k
+            assert np.array_equal(g0[k], g1[k]), k
+        m0.close()
+        m1.close()
 
 
 @pytest.mark.parametrize("bf16", [False, True])
